@@ -1,0 +1,313 @@
+"""CPU oracle for the secure-layer hot path (two parties, ring Z_2^64).
+
+TEST INFRASTRUCTURE ONLY.  Imported by ``tests/``, by ``__graft_entry__.smoke``
+and by the ``cpu_baseline`` leg of ``bench.py``; never by the GPU library or its
+Python binding.  The arithmetic lives in ``mpc_oracle.c`` (plain C, uint64
+wrap-around, straight loops); this module is a ctypes shim plus a handful of
+plain-definition checkers on reconstructed values and a second, independent
+adder form (the divide-and-conquer prefix tree of the paper's Sec. 4.2 listing)
+used only to cross-check the Kogge-Stone form.
+
+Parity status: values of individual shares are not fixed by the paper (it prints
+no worked example), so share bit patterns are "parity unpinned" by the paper
+itself; every function here is pinned by identities, closed forms, exhaustive
+enumeration and library special cases in ``tests/test_oracle_*.py``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mpc_oracle.c")
+_LIB = os.path.join(_HERE, "libmpc_oracle.so")
+
+U64 = np.uint64
+_P64 = ctypes.POINTER(ctypes.c_uint64)
+_P8 = ctypes.POINTER(ctypes.c_uint8)
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (portable x86-64-v3 code, OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".{os.getpid()}.tmp"
+        subprocess.check_call(
+            ["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-shared", "-fPIC",
+             "-Wall", "-Wextra", "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+    return _lib
+
+
+def _w(a):
+    a = np.ascontiguousarray(a, dtype=U64)
+    return a, a.ctypes.data_as(_P64)
+
+
+def _b(a):
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    return a, a.ctypes.data_as(_P8)
+
+
+def n_threads() -> int:
+    """Threads the OpenMP loops will use (OMP_NUM_THREADS or all cores)."""
+    v = os.environ.get("OMP_NUM_THREADS")
+    return int(v) if v else (os.cpu_count() or 1)
+
+
+# --------------------------------------------------------------------- ring ops
+def ring_matmul(L, R):
+    """Z = L @ R mod 2^64 (plain definition)."""
+    L, pl = _w(L); R, pr = _w(R)
+    M, K = L.shape; K2, N = R.shape
+    assert K == K2
+    Z = np.empty((M, N), dtype=U64)
+    lib().orc_ring_matmul(pl, pr, Z.ctypes.data_as(_P64), M, K, N)
+    return Z
+
+
+def conv_out_hw(H, W, KH, KW, pad, stride):
+    return (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+
+
+def ring_conv2d(x, w, pad, stride):
+    """Direct NHWC x [KH,KW,Cin,Cout] cross-correlation mod 2^64, zero padding."""
+    x, px = _w(x); w, pw = _w(w)
+    B, H, W, Cin = x.shape; KH, KW, Cin2, Cout = w.shape
+    assert Cin == Cin2
+    Ho, Wo = conv_out_hw(H, W, KH, KW, pad, stride)
+    z = np.empty((B, Ho, Wo, Cout), dtype=U64)
+    lib().orc_ring_conv2d(px, pw, z.ctypes.data_as(_P64), B, H, W, Cin, Cout, KH, KW, pad, stride)
+    return z
+
+
+def im2col(x, KH, KW, pad, stride):
+    x, px = _w(x)
+    B, H, W, Cin = x.shape
+    Ho, Wo = conv_out_hw(H, W, KH, KW, pad, stride)
+    col = np.empty((B * Ho * Wo, KH * KW * Cin), dtype=U64)
+    lib().orc_im2col(px, col.ctypes.data_as(_P64), B, H, W, Cin, KH, KW, pad, stride)
+    return col
+
+
+# --------------------------------------------------------------- Alg. 1 / Eq. 3
+def open_shares(s0, s1):
+    """Reconstruct a two-party additive sharing (Sec. 3.1)."""
+    s0, p0 = _w(s0); s1, p1 = _w(s1)
+    out = np.empty_like(s0)
+    lib().orc_open(p0, p1, out.ctypes.data_as(_P64), s0.size)
+    return out
+
+
+def beaver_matmul(x, y, a, b, c, want_open=False):
+    """Alg. 1 on matrices.  x, y, a, b, c are pairs (party 0, party 1)."""
+    (x0, px0), (x1, px1) = _w(x[0]), _w(x[1])
+    (y0, py0), (y1, py1) = _w(y[0]), _w(y[1])
+    (a0, pa0), (a1, pa1) = _w(a[0]), _w(a[1])
+    (b0, pb0), (b1, pb1) = _w(b[0]), _w(b[1])
+    (c0, pc0), (c1, pc1) = _w(c[0]), _w(c[1])
+    M, K = x0.shape; _, N = y0.shape
+    z0 = np.empty((M, N), dtype=U64); z1 = np.empty((M, N), dtype=U64)
+    e = np.empty((M, K), dtype=U64) if want_open else None
+    f = np.empty((K, N), dtype=U64) if want_open else None
+    lib().orc_beaver_matmul(px0, px1, py0, py1, pa0, pa1, pb0, pb1, pc0, pc1,
+                            z0.ctypes.data_as(_P64), z1.ctypes.data_as(_P64), M, K, N,
+                            e.ctypes.data_as(_P64) if want_open else None,
+                            f.ctypes.data_as(_P64) if want_open else None)
+    return ((z0, z1), e, f) if want_open else (z0, z1)
+
+
+def beaver_conv2d(x, w, a, b, c, pad, stride):
+    """Eq. 3: Alg. 1 with Conv as the product.  NHWC / [KH,KW,Cin,Cout]."""
+    (x0, px0), (x1, px1) = _w(x[0]), _w(x[1])
+    (w0, pw0), (w1, pw1) = _w(w[0]), _w(w[1])
+    (a0, pa0), (a1, pa1) = _w(a[0]), _w(a[1])
+    (b0, pb0), (b1, pb1) = _w(b[0]), _w(b[1])
+    (c0, pc0), (c1, pc1) = _w(c[0]), _w(c[1])
+    B, H, W, Cin = x0.shape; KH, KW, _, Cout = w0.shape
+    Ho, Wo = conv_out_hw(H, W, KH, KW, pad, stride)
+    z0 = np.empty((B, Ho, Wo, Cout), dtype=U64); z1 = np.empty_like(z0)
+    lib().orc_beaver_conv2d(px0, px1, pw0, pw1, pa0, pa1, pb0, pb1, pc0, pc1,
+                            z0.ctypes.data_as(_P64), z1.ctypes.data_as(_P64),
+                            B, H, W, Cin, Cout, KH, KW, pad, stride)
+    return z0, z1
+
+
+def truncate(z, bits=16):
+    """Local two-party truncation; returns new arrays."""
+    z0 = np.array(z[0], dtype=U64, copy=True); z1 = np.array(z[1], dtype=U64, copy=True)
+    lib().orc_truncate(z0.ctypes.data_as(_P64), z1.ctypes.data_as(_P64), z0.size, bits)
+    return z0, z1
+
+
+# ------------------------------------------------------------------ binary side
+def beaver_and(X, Y, a, b, c):
+    """Beaver AND on one word pair: all arguments are 2-sequences of ints."""
+    arrs = [np.array(v, dtype=U64) for v in (X, Y, a, b, c)]
+    out = np.zeros(2, dtype=U64)
+    lib().orc_beaver_and(*[v.ctypes.data_as(_P64) for v in arrs], out.ctypes.data_as(_P64))
+    return int(out[0]), int(out[1])
+
+
+def ks_add(U, V, w, ta, tb, tc):
+    """XOR shares of (U+V) mod 2^w via the Kogge-Stone network.
+    U, V: 2-sequences; ta/tb/tc: pairs of arrays with 2*log2(w) words each."""
+    Ua = np.array(U, dtype=U64); Va = np.array(V, dtype=U64)
+    t = [np.ascontiguousarray(v, dtype=U64) for v in (ta[0], ta[1], tb[0], tb[1], tc[0], tc[1])]
+    S = np.zeros(2, dtype=U64)
+    lib().orc_ks_add(Ua.ctypes.data_as(_P64), Va.ctypes.data_as(_P64), w,
+                     *[v.ctypes.data_as(_P64) for v in t], S.ctypes.data_as(_P64))
+    return int(S[0]), int(S[1])
+
+
+def b2a(s, rb, ra):
+    sa = np.array(s, dtype=np.uint8); rba = np.array(rb, dtype=np.uint8)
+    raa = np.array(ra, dtype=U64); out = np.zeros(2, dtype=U64)
+    lib().orc_b2a(sa.ctypes.data_as(_P8), rba.ctypes.data_as(_P8),
+                  raa.ctypes.data_as(_P64), out.ctypes.data_as(_P64))
+    return int(out[0]), int(out[1])
+
+
+class _ReluMaterialC(ctypes.Structure):
+    _fields_ = [("r", _P64 * 2), ("ta", _P64 * 2), ("tb", _P64 * 2), ("tc", _P64 * 2),
+                ("rb", _P8 * 2), ("ra", _P64 * 2),
+                ("ma", _P64 * 2), ("mb", _P64 * 2), ("mc", _P64 * 2)]
+
+
+@dataclass
+class ReluResult:
+    y: tuple          # output shares (y_0, y_1)
+    s_bit: tuple      # XOR shares of the sign bit, uint8
+    s_arith: tuple    # additive shares of the sign bit
+
+
+def relu(x, mat) -> ReluResult:
+    """Secure ReLU on additive shares x = (x_0, x_1).
+
+    ``mat`` is a mapping with keys r, and_a, and_b, and_c ([12, n] each),
+    rb (uint8), ra, ma, mb, mc; every value a pair (party 0, party 1)."""
+    x0, px0 = _w(np.ravel(x[0])); x1, px1 = _w(np.ravel(x[1]))
+    n = x0.size
+    keep = []
+    m = _ReluMaterialC()
+
+    def put(field, key, conv, size):
+        for p in range(2):
+            arr, ptr = conv(np.ravel(mat[key][p]))
+            assert arr.size == size, (key, arr.size, size)
+            keep.append(arr)
+            getattr(m, field)[p] = ptr
+
+    put("r", "r", _w, n)
+    put("ta", "and_a", _w, 12 * n); put("tb", "and_b", _w, 12 * n); put("tc", "and_c", _w, 12 * n)
+    put("rb", "rb", _b, n); put("ra", "ra", _w, n)
+    put("ma", "ma", _w, n); put("mb", "mb", _w, n); put("mc", "mc", _w, n)
+    y0 = np.empty(n, dtype=U64); y1 = np.empty(n, dtype=U64)
+    sb0 = np.empty(n, dtype=np.uint8); sb1 = np.empty(n, dtype=np.uint8)
+    sa0 = np.empty(n, dtype=U64); sa1 = np.empty(n, dtype=U64)
+    lib().orc_relu(px0, px1, ctypes.byref(m), y0.ctypes.data_as(_P64), y1.ctypes.data_as(_P64),
+                   ctypes.c_size_t(n), sb0.ctypes.data_as(_P8), sb1.ctypes.data_as(_P8),
+                   sa0.ctypes.data_as(_P64), sa1.ctypes.data_as(_P64))
+    shp = np.shape(x[0])
+    return ReluResult((y0.reshape(shp), y1.reshape(shp)), (sb0.reshape(shp), sb1.reshape(shp)),
+                      (sa0.reshape(shp), sa1.reshape(shp)))
+
+
+# ------------------------------------------------------------------ max-pooling
+def pool_level1(x):
+    """One party's local gather for the first tournament level (NHWC, 2x2/2)."""
+    x, px = _w(x); B, H, W, C = x.shape
+    d = np.empty(2 * B * (H // 2) * (W // 2) * C, dtype=U64)
+    lib().orc_pool_level1(px, d.ctypes.data_as(_P64), B, H, W, C)
+    return d
+
+
+def pool_level2(x, r1):
+    x, px = _w(x); r1, pr = _w(r1); B, H, W, C = x.shape
+    n = B * (H // 2) * (W // 2) * C
+    v = np.empty(n, dtype=U64); d2 = np.empty(n, dtype=U64)
+    lib().orc_pool_level2(px, pr, v.ctypes.data_as(_P64), d2.ctypes.data_as(_P64), B, H, W, C)
+    return v, d2
+
+
+def maxpool2x2(x, mat1, mat2):
+    """max over 2x2 windows by max(p,q) = q + ReLU(p-q), two tournament levels.
+    mat1 covers 2*n_out elements, mat2 n_out elements.  Returns output shares."""
+    B, H, W, C = np.shape(x[0])
+    d1 = (pool_level1(x[0]), pool_level1(x[1]))
+    r1 = relu(d1, mat1).y
+    v0, d20 = pool_level2(x[0], r1[0]); v1, d21 = pool_level2(x[1], r1[1])
+    r2 = relu((d20, d21), mat2).y
+    shp = (B, H // 2, W // 2, C)
+    return ((v0 + r2[0]).reshape(shp), (v1 + r2[1]).reshape(shp))
+
+
+# --------------------------------------------- checkers on reconstructed values
+def to_signed(u):
+    return np.asarray(u, dtype=U64).view(np.int64)
+
+
+def decode(u, frac_bits=16):
+    """Fixed-point decode of reconstructed ring values to float64."""
+    return to_signed(u).astype(np.float64) / float(1 << frac_bits)
+
+
+def truncation_wraps(z_rec, t_rec, bits=16):
+    """Boolean mask of elements where local truncation left the +-1 band
+    around floor(z / 2^bits) (the share-wrap event)."""
+    want = to_signed(z_rec) >> bits
+    got = to_signed(t_rec)
+    return np.abs(got - want) > 1
+
+
+# ----------------------------- the divide-and-conquer adder of Sec. 4.2's listing
+def spk_constants():
+    """Public per-level constants for a 64-bit prefix tree in which level i
+    joins blocks of 2^i bits into blocks of 2^(i+1): the top bit of each lower
+    half is selected (in_mask), spread over the upper half by an integer
+    multiply (mult), and combined under P restricted to the upper half
+    (out_mask).  The paper does not print the values; these follow from that
+    description."""
+    in_masks, out_masks, mults = [], [], []
+    for i in range(6):
+        half, blk = 1 << i, 1 << (i + 1)
+        im = om = 0
+        for base in range(0, 64, blk):
+            im |= 1 << (base + half - 1)
+            om |= ((1 << half) - 1) << (base + half)
+        in_masks.append(im); out_masks.append(om)
+        mults.append(sum(1 << k for k in range(1, half + 1)))
+    return in_masks, out_masks, mults
+
+
+def spk_tree_carries(U, V, and_fn):
+    """Carry word (bit j = carry out of [0..j]) for python ints U, V < 2^64 in
+    the clear, looping as the listing does: per level one AND of the stacked
+    (S, P) selection against P on the upper halves.  ``and_fn(x, y)`` is the
+    AND gate (tests pass either plain & or a Beaver AND on shares)."""
+    M64 = (1 << 64) - 1
+    in_masks, out_masks, mults = spk_constants()
+    S, P = and_fn(U, V), U ^ V
+    for i in range(6):
+        im, om, mu = in_masks[i], out_masks[i], mults[i]
+        P0 = P & om
+        S1 = ((S & im) * mu) & M64
+        P1 = ((P & im) * mu) & M64
+        upd_S = and_fn(P0, S1)
+        upd_P = and_fn(P0, P1)
+        P = (P & (om ^ M64)) ^ upd_P
+        S = S ^ upd_S
+    return S

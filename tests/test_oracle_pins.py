@@ -1,0 +1,371 @@
+"""Pins for the CPU oracle: everything here runs without a GPU and compares the
+oracle with something other than itself - Python big-int arithmetic, numpy /
+torch library routines, closed forms, exhaustive enumeration.
+
+Citations are to the paper's sections / algorithms / equations."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2209_13643_amd import synth
+
+U64 = np.uint64
+MOD = 1 << 64
+
+
+def rec(pair):
+    return np.asarray(pair[0], dtype=U64) + np.asarray(pair[1], dtype=U64)
+
+
+def big_matmul(L, R):
+    """Python big-int matrix product reduced mod 2^64 at the end."""
+    L = [[int(v) for v in row] for row in L]
+    R = [[int(v) for v in row] for row in R]
+    return np.array([[sum(L[m][k] * R[k][n] for k in range(len(R))) % MOD
+                      for n in range(len(R[0]))] for m in range(len(L))], dtype=U64)
+
+
+def deal_matmul(rng, M, K, N, x=None, y=None):
+    X = synth.rand_words(rng, (M, K)) if x is None else x
+    Y = synth.rand_words(rng, (K, N)) if y is None else y
+    xs, ys = synth.share_additive(rng, X), synth.share_additive(rng, Y)
+    a, b, c = synth.deal_product_triple(rng, (M, K), (K, N), lambda A, B: A @ B)
+    return X, Y, xs, ys, a, b, c
+
+
+# ------------------------------------------------------------ Alg. 1 on matrices
+@pytest.mark.parametrize("shape", [(1, 1, 1), (2, 3, 2), (3, 1, 4), (5, 7, 3)])
+def test_ring_matmul_vs_bigint(shape):
+    M, K, N = shape
+    rng = np.random.default_rng(1)
+    L, R = synth.rand_words(rng, (M, K)), synth.rand_words(rng, (K, N))
+    assert np.array_equal(oracle.ring_matmul(L, R), big_matmul(L, R))
+
+
+def test_ring_matmul_not_transposed():
+    # a non-square, non-symmetric case with a known answer: [1 2 3] * [[1],[10],[100]]
+    L = np.array([[1, 2, 3]], dtype=U64); R = np.array([[1], [10], [100]], dtype=U64)
+    assert oracle.ring_matmul(L, R).tolist() == [[321]]
+    # wrap-around: (2^63) * 2 = 0, (2^64 - 1)^2 = 1
+    L = np.array([[1 << 63, MOD - 1]], dtype=U64); R = np.array([[2], [MOD - 1]], dtype=U64)
+    assert oracle.ring_matmul(L, R).tolist() == [[1]]
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (2, 3, 2), (3, 1, 4), (17, 33, 9), (64, 256, 128)])
+def test_beaver_matmul_reconstructs_product(shape):
+    """Sec. 3.2: the sum of the [z_i] is X*Y."""
+    M, K, N = shape
+    rng = np.random.default_rng(10 + M)
+    X, Y, xs, ys, a, b, c = deal_matmul(rng, M, K, N)
+    z, e, f = oracle.beaver_matmul(xs, ys, a, b, c, want_open=True)
+    want = big_matmul(X, Y) if M * K * N <= 5000 else X @ Y
+    assert np.array_equal(rec(z), want)
+    assert np.array_equal(e, X - rec(a))      # Delta = X - A
+    assert np.array_equal(f, Y - rec(b))      # epsilon = Y - B
+    # the shares themselves are masked: neither equals the product on its own
+    assert not np.array_equal(z[0], want) and not np.array_equal(z[1], want)
+
+
+def test_beaver_matmul_independent_of_triple_and_masks():
+    rng = np.random.default_rng(3)
+    X, Y = synth.rand_words(rng, (6, 5)), synth.rand_words(rng, (5, 4))
+    outs = []
+    for _ in range(3):
+        _, _, xs, ys, a, b, c = deal_matmul(rng, 6, 5, 4, X, Y)
+        outs.append(rec(oracle.beaver_matmul(xs, ys, a, b, c)))
+    assert all(np.array_equal(o, outs[0]) for o in outs)
+
+
+def test_beaver_matmul_zero_triple_degenerates_to_plain_product():
+    """A = B = C = 0: e = X, f = Y, party 0 ends with X*Y, party 1 with 0."""
+    rng = np.random.default_rng(4)
+    X, Y = synth.rand_words(rng, (4, 6)), synth.rand_words(rng, (6, 3))
+    xs, ys = synth.share_additive(rng, X), synth.share_additive(rng, Y)
+    zA, zB, zC = np.zeros((4, 6), U64), np.zeros((6, 3), U64), np.zeros((4, 3), U64)
+    z = oracle.beaver_matmul(xs, ys, (zA, zA), (zB, zB), (zC, zC))
+    assert np.array_equal(z[0], big_matmul(X, Y))
+    assert not z[1].any()
+
+
+def test_beaver_matmul_each_term_matters():
+    """Dropping or mis-assigning any term of Alg. 1's last two lines breaks
+    reconstruction: rebuild z from the opened values term by term."""
+    rng = np.random.default_rng(5)
+    X, Y, xs, ys, a, b, c = deal_matmul(rng, 3, 4, 2)
+    z, e, f = oracle.beaver_matmul(xs, ys, a, b, c, want_open=True)
+    t = {k: big_matmul(*v) for k, v in
+         dict(eb0=(e, b[0]), a0f=(a[0], f), ef=(e, f), eb1=(e, b[1]), a1f=(a[1], f)).items()}
+    assert np.array_equal(z[0], c[0] + t["eb0"] + t["a0f"] + t["ef"])
+    assert np.array_equal(z[1], c[1] + t["eb1"] + t["a1f"])
+
+
+# ------------------------------------------------------------------ Eq. 3 (conv)
+CONV_CASES = [  # B,H,W,Cin,Cout,KH,KW,pad,stride
+    (1, 3, 3, 1, 1, 3, 3, 1, 1), (2, 5, 4, 3, 2, 3, 3, 1, 1), (1, 6, 6, 2, 3, 3, 3, 0, 2),
+    (2, 4, 4, 5, 4, 1, 1, 0, 1), (1, 7, 5, 2, 2, 3, 3, 1, 2)]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_equals_im2col_matmul(case):
+    B, H, W, Cin, Cout, KH, KW, pad, stride = case
+    rng = np.random.default_rng(6)
+    x = synth.rand_words(rng, (B, H, W, Cin)); w = synth.rand_words(rng, (KH, KW, Cin, Cout))
+    direct = oracle.ring_conv2d(x, w, pad, stride)
+    col = oracle.im2col(x, KH, KW, pad, stride)
+    viaim = big_matmul(col, w.reshape(-1, Cout)).reshape(direct.shape)
+    assert np.array_equal(direct, viaim)
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_matches_torch_float64(case):
+    """Small integers keep float64 exact, so torch's conv2d is an independent
+    definition of the same cross-correlation (layout NCHW / OIHW there)."""
+    B, H, W, Cin, Cout, KH, KW, pad, stride = case
+    rng = np.random.default_rng(7)
+    xi = rng.integers(-1000, 1000, size=(B, H, W, Cin)); wi = rng.integers(-1000, 1000, size=(KH, KW, Cin, Cout))
+    got = oracle.ring_conv2d(xi.astype(np.int64).view(U64), wi.astype(np.int64).view(U64), pad, stride)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(xi).double().permute(0, 3, 1, 2),
+                                     torch.from_numpy(wi).double().permute(3, 2, 0, 1),
+                                     padding=pad, stride=stride).permute(0, 2, 3, 1).numpy()
+    assert np.array_equal(oracle.to_signed(got), ref.astype(np.int64))
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_beaver_conv_reconstructs_conv(case):
+    B, H, W, Cin, Cout, KH, KW, pad, stride = case
+    rng = np.random.default_rng(8)
+    X = synth.rand_words(rng, (B, H, W, Cin)); Wt = synth.rand_words(rng, (KH, KW, Cin, Cout))
+    xs, ws = synth.share_additive(rng, X), synth.share_additive(rng, Wt)
+
+    def conv_via_bigint(A, Bf):  # independent of ring_conv2d: im2col + big ints
+        col = oracle.im2col(A, KH, KW, pad, stride)
+        Ho, Wo = oracle.conv_out_hw(H, W, KH, KW, pad, stride)
+        return big_matmul(col, Bf.reshape(-1, Cout)).reshape(B, Ho, Wo, Cout)
+
+    a, b, c = synth.deal_product_triple(rng, X.shape, Wt.shape, conv_via_bigint)
+    z = oracle.beaver_conv2d(xs, ws, a, b, c, pad, stride)
+    assert np.array_equal(rec(z), conv_via_bigint(X, Wt))
+
+
+# -------------------------------------------------------------------- truncation
+def test_truncation_within_one_lsb_and_wrap_flag():
+    rng = np.random.default_rng(9)
+    vals = rng.integers(-(1 << 40), 1 << 40, size=20000).astype(np.int64)
+    Z = vals.view(U64)
+    z = synth.share_additive(rng, Z)
+    t = oracle.truncate(z, 16)
+    got = oracle.to_signed(rec(t))
+    diff = got - (vals >> 16)
+    assert not oracle.truncation_wraps(Z, rec(t)).any()   # |z| / 2^64 ~ 2^-24 per element
+    assert set(np.unique(diff)) <= {0, 1}
+    # closed form for party 0 = z0 >> 16 and party 1 = -((-z1) >> 16)
+    assert np.array_equal(t[0], z[0] >> U64(16))
+    assert np.array_equal(t[1], (-(((-z[1].astype(object)) % MOD) >> 16)) % MOD)
+    # forced wrap: z0 = 0 and a small positive value sitting wholly in party 1
+    z0 = np.zeros(4, U64); z1 = np.array([5 << 16, 1 << 20, 3, 1 << 40], dtype=U64)
+    t = oracle.truncate((z0, z1), 16)
+    assert oracle.truncation_wraps(z0 + z1, rec(t)).all()
+
+
+def test_truncation_negative_values_floor():
+    Z = np.array([-65536, -65537, -1, 65535, 65536], dtype=np.int64).view(U64)
+    rng = np.random.default_rng(11)
+    for _ in range(20):
+        t = oracle.truncate(synth.share_additive(rng, Z), 16)
+        d = oracle.to_signed(rec(t)) - np.array([-1, -2, -1, 0, 1])
+        assert ((d == 0) | (d == 1)).all()
+
+
+# -------------------------------------------------------------------- Beaver AND
+def test_beaver_and_exhaustive_one_bit():
+    """Sec. 3.2 / Alg. 4: all 2^9 one-bit assignments reconstruct X & Y."""
+    for x0, x1, y0, y1, a0, a1, b0, b1, c0 in itertools.product((0, 1), repeat=9):
+        c1 = ((a0 ^ a1) & (b0 ^ b1)) ^ c0
+        t = oracle.beaver_and((x0, x1), (y0, y1), (a0, a1), (b0, b1), (c0, c1))
+        assert (t[0] ^ t[1]) == ((x0 ^ x1) & (y0 ^ y1))
+
+
+def test_beaver_and_words_bitwise():
+    rng = np.random.default_rng(12)
+    for _ in range(200):
+        v = [int(q) for q in synth.rand_words(rng, 9)]
+        c1 = ((v[4] ^ v[5]) & (v[6] ^ v[7])) ^ v[8]
+        t = oracle.beaver_and(v[0:2], v[2:4], v[4:6], v[6:8], (v[8], c1))
+        assert (t[0] ^ t[1]) == ((v[0] ^ v[1]) & (v[2] ^ v[3]))
+
+
+# ------------------------------------------------------------- prefix adder (A2B)
+def _adder_triples(rng, w):
+    levels = w.bit_length() - 1
+    wm = (1 << w) - 1
+    a = [rng.integers(0, 1 << 64, size=2 * levels, dtype=U64) & U64(wm) for _ in range(2)]
+    b = [rng.integers(0, 1 << 64, size=2 * levels, dtype=U64) & U64(wm) for _ in range(2)]
+    c0 = rng.integers(0, 1 << 64, size=2 * levels, dtype=U64) & U64(wm)
+    c1 = ((a[0] ^ a[1]) & (b[0] ^ b[1])) ^ c0
+    return a, b, (c0, c1)
+
+
+def test_adder_exhaustive_width_8():
+    """Alg. 2's last step at w = 8: every (U, V) pair, random sharings/triples."""
+    rng = np.random.default_rng(13)
+    for U in range(256):
+        a, b, c = _adder_triples(rng, 8)
+        for V in range(256):
+            u0 = int(rng.integers(0, 256)); v0 = int(rng.integers(0, 256))
+            S = oracle.ks_add((u0, U ^ u0), (v0, V ^ v0), 8, a, b, c)
+            assert (S[0] ^ S[1]) == (U + V) % 256, (U, V)
+
+
+@pytest.mark.parametrize("w", [16, 32, 64])
+def test_adder_random_and_carry_corners(w):
+    rng = np.random.default_rng(14 + w)
+    wm = (1 << w) - 1
+    corners = [(wm, 1), (wm >> 1, 1), (0xAAAAAAAAAAAAAAAA & wm, 0x5555555555555555 & wm),
+               (0xAAAAAAAAAAAAAAAA & wm, 0xAAAAAAAAAAAAAAAA & wm), (wm, wm), (0, 0),
+               (1 << (w - 1), 1 << (w - 1)), ((1 << (w // 2)) - 1, 1)]
+    rand = [(int(rng.integers(0, 1 << 64, dtype=U64)) & wm, int(rng.integers(0, 1 << 64, dtype=U64)) & wm)
+            for _ in range(300)]
+    for U, V in corners + rand:
+        a, b, c = _adder_triples(rng, w)
+        u0 = int(rng.integers(0, 1 << 64, dtype=U64)) & wm; v0 = int(rng.integers(0, 1 << 64, dtype=U64)) & wm
+        S = oracle.ks_add((u0, U ^ u0), (v0, V ^ v0), w, a, b, c)
+        assert (S[0] ^ S[1]) == (U + V) & wm, (hex(U), hex(V))
+
+
+def test_kogge_stone_agrees_with_listing_tree():
+    """The divide-and-conquer tree of the Sec. 4.2 listing (six levels, one
+    stacked AND each) yields the same carries, hence the same sum."""
+    rng = np.random.default_rng(15)
+    M64 = MOD - 1
+    cases = [(M64, 1), (M64 >> 1, 1), (0, 0), (M64, M64)] + \
+            [(int(q), int(p)) for q, p in zip(synth.rand_words(rng, 200), synth.rand_words(rng, 200))]
+    for U, V in cases:
+        carries = oracle.spk_tree_carries(U, V, lambda p, q: p & q)
+        assert (U ^ V ^ ((carries << 1) & M64)) == (U + V) & M64
+        a, b, c = _adder_triples(rng, 64)
+        u0, v0 = int(rng.integers(0, 1 << 64, dtype=U64)), int(rng.integers(0, 1 << 64, dtype=U64))
+        S = oracle.ks_add((u0, U ^ u0), (v0, V ^ v0), 64, a, b, c)
+        assert (S[0] ^ S[1]) == (U ^ V ^ ((carries << 1) & M64))
+
+
+def test_listing_tree_on_shares_with_beaver_and():
+    """Same tree evaluated on XOR shares, every gate a Beaver AND from the oracle."""
+    rng = np.random.default_rng(16)
+    for _ in range(20):
+        U, V = int(rng.integers(0, 1 << 64, dtype=U64)), int(rng.integers(0, 1 << 64, dtype=U64))
+        # run the tree twice, once per party view, by carrying share pairs through and_fn
+        def and_fn(p, q):
+            t = [int(v) for v in synth.rand_words(rng, 5)]
+            c1 = ((t[0] ^ t[1]) & (t[2] ^ t[3])) ^ t[4]
+            p0, q0 = int(rng.integers(0, 1 << 64, dtype=U64)), int(rng.integers(0, 1 << 64, dtype=U64))
+            o = oracle.beaver_and((p0, p ^ p0), (q0, q ^ q0), t[0:2], t[2:4], (t[4], c1))
+            return o[0] ^ o[1]
+        carries = oracle.spk_tree_carries(U, V, and_fn)
+        assert (U ^ V ^ ((carries << 1) & (MOD - 1))) == (U + V) % MOD
+
+
+# --------------------------------------------------------------------------- B2A
+def test_b2a_exhaustive():
+    rng = np.random.default_rng(17)
+    for s0, s1, rb0, rb1 in itertools.product((0, 1), repeat=4):
+        for _ in range(8):
+            ra0 = int(rng.integers(0, 1 << 64, dtype=U64)); ra1 = ((rb0 ^ rb1) - ra0) % MOD
+            o = oracle.b2a((s0, s1), (rb0, rb1), (ra0, ra1))
+            assert (o[0] + o[1]) % MOD == (s0 ^ s1)
+
+
+# -------------------------------------------------------------------------- ReLU
+def _relu_check(xvals, x0=None, seed=18):
+    rng = np.random.default_rng(seed)
+    X = np.asarray(xvals, dtype=np.int64).view(U64)
+    if x0 is None:
+        xs = synth.share_additive(rng, X)
+    else:
+        x0 = np.full(X.shape, x0, dtype=U64); xs = (x0, X - x0)
+    res = oracle.relu(xs, synth.deal_relu_material(rng, X.size))
+    want = np.maximum(X.view(np.int64), 0).view(U64)
+    assert np.array_equal(rec(res.y), want)
+    sign = (X.view(np.int64) < 0)
+    assert np.array_equal((res.s_bit[0] ^ res.s_bit[1]).astype(bool), sign)
+    assert np.array_equal(rec(res.s_arith), sign.astype(U64))
+    return res
+
+
+def test_relu_exhaustive_small_magnitude():
+    _relu_check(np.arange(-4096, 4097))
+
+
+@pytest.mark.parametrize("x0", [0, 1 << 63, MOD - 1, 1, (1 << 63) - 1])
+def test_relu_adversarial_share_patterns(x0):
+    _relu_check(np.arange(-4096, 4097), x0=x0)
+
+
+def test_relu_powers_of_two_edges():
+    vals = []
+    for k in range(63):
+        for s in (1, -1):
+            for d in (-1, 0, 1):
+                vals.append(s * (1 << k) + d)
+    vals += [-(1 << 63), (1 << 63) - 1, 0]
+    _relu_check(np.array(vals, dtype=np.int64))
+    for x0 in (0, 1 << 63, MOD - 1):
+        _relu_check(np.array(vals, dtype=np.int64), x0=x0)
+
+
+def test_relu_trivial_a2b_masks():
+    """r = 0 is a legal (if insecure) A2B sharing: (x_0, 0) and (0, x_1)."""
+    rng = np.random.default_rng(19)
+    X = rng.integers(-(1 << 62), 1 << 62, size=1000).astype(np.int64).view(U64)
+    xs = synth.share_additive(rng, X)
+    mat = synth.deal_relu_material(rng, X.size)
+    mat["r"] = (np.zeros(X.size, U64), np.zeros(X.size, U64))
+    assert np.array_equal(rec(oracle.relu(xs, mat).y), np.maximum(X.view(np.int64), 0).view(U64))
+
+
+def test_relu_material_index_sensitivity():
+    """Each of the 12 AND triples is consumed: corrupting c of any one of them
+    (at a bit that can reach bit 63) changes some sign."""
+    rng = np.random.default_rng(20)
+    X = rng.integers(-(1 << 62), 1 << 62, size=4000).astype(np.int64).view(U64)
+    xs = synth.share_additive(rng, X)
+    mat = synth.deal_relu_material(rng, X.size)
+    base = oracle.relu(xs, mat)
+    for t in range(12):
+        bad = dict(mat)
+        c0 = mat["and_c"][0].copy(); c0[t] ^= U64(MOD - 1)
+        bad["and_c"] = (c0, mat["and_c"][1])
+        out = oracle.relu(xs, bad)
+        assert not np.array_equal(out.s_bit[0] ^ out.s_bit[1], base.s_bit[0] ^ base.s_bit[1]), t
+
+
+# ---------------------------------------------------------------------- max-pool
+def test_maxpool_by_composition():
+    rng = np.random.default_rng(21)
+    B, H, W, C = 2, 6, 4, 3
+    X = rng.integers(-(1 << 30), 1 << 30, size=(B, H, W, C)).astype(np.int64)
+    xs = synth.share_additive(rng, X.view(U64))
+    n_out = B * (H // 2) * (W // 2) * C
+    out = oracle.maxpool2x2(xs, synth.deal_relu_material(rng, 2 * n_out), synth.deal_relu_material(rng, n_out))
+    want = X.reshape(B, H // 2, 2, W // 2, 2, C).max(axis=(2, 4))
+    assert np.array_equal(oracle.to_signed(rec(out)), want)
+
+
+# ------------------------------------------------------- fixed point vs float64
+def test_tiny_layer_float64_agreement():
+    """Config 0 end to end on the oracle: decoded output within 2^-12 of the
+    float64 product of the decoded (quantised) inputs; ReLU exact."""
+    wl = synth.config_tiny(); g = wl.layers[0]
+    rng = synth.rng_for(wl.index)
+    X = synth.normal_fixed(rng, (g.M, g.K), g.x_std); Wt = synth.normal_fixed(rng, (g.K, g.N), g.w_std)
+    xs, ws = synth.share_additive(rng, X), synth.share_additive(rng, Wt)
+    a, b, c = synth.deal_product_triple(rng, X.shape, Wt.shape, lambda A, B: A @ B)
+    z = oracle.beaver_matmul(xs, ws, a, b, c)
+    t = oracle.truncate(z, 16)
+    assert not oracle.truncation_wraps(rec(z), rec(t)).any()
+    ref = oracle.decode(X) @ oracle.decode(Wt)
+    assert np.abs(oracle.decode(rec(t)) - ref).max() <= 2.0 ** -12
+    res = oracle.relu(t, synth.deal_relu_material(rng, g.M * g.N))
+    assert np.array_equal(oracle.to_signed(rec(res.y)), np.maximum(oracle.to_signed(rec(t)), 0))
