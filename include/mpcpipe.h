@@ -1,0 +1,195 @@
+/*
+ * mpcpipe - two-party semi-honest online phase of MPC-Pipe's secure layer on
+ * one AMD MI355X (gfx950): Beaver-triple matmul / conv over the ring Z_2^64
+ * with fixed-point truncation, and secure ReLU through A2B conversion.
+ *
+ * Both parties are simulated on one device.  Party i's work is enqueued on
+ * party i's stream and touches only party i's buffers plus opened ("public")
+ * values; the exchange of masked shares - the protocol's communication - is
+ * a device-to-device copy on a third, "wire" stream ordered by events.
+ *
+ * General rules for every entry point
+ *   - all tensor pointers are DEVICE pointers to dense row-major arrays of
+ *     uint64_t ring elements unless a parameter says otherwise;
+ *   - the caller owns every buffer it passes in, including the workspace; the
+ *     library never allocates or frees device memory in these calls (the
+ *     context owns only streams and events);
+ *   - calls enqueue work and return; party i's outputs are ordered on party
+ *     i's stream (mpc_ctx_sync waits for all three streams);
+ *   - return value 0 = success, negative = error (see mpc_strerror); on an
+ *     argument error nothing has been enqueued and no output is written;
+ *   - build party 0 is the paper's "Party #1": the one whose share receives
+ *     the Delta*epsilon term (Alg. 1; Alg. 4);
+ *   - a context is one execution lane: two calls on the same context are
+ *     serialised by its streams and share its workspace; use one context per
+ *     micro-batch to overlap them (inter-batch pipeline, Sec. 4.3).
+ */
+#ifndef MPCPIPE_H
+#define MPCPIPE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mpc_ctx mpc_ctx;
+
+/* One pointer per simulated party. */
+typedef struct { const uint64_t* p[2]; } mpc_cshare;
+typedef struct { uint64_t* p[2]; } mpc_share;
+
+enum {
+    MPC_OK = 0,
+    MPC_EINVAL = -1,   /* null pointer, non-positive size, unsupported shape   */
+    MPC_ENOMEM = -2,   /* workspace missing or smaller than mpc_*_workspace()  */
+    MPC_EHIP = -3,     /* a HIP call failed; mpc_last_hip_error() has the code */
+    MPC_ERANGE = -4    /* contraction too long for exact int32 digit sums      */
+};
+
+/* flags for mpc_beaver_matmul / mpc_conv2d */
+enum {
+    MPC_TRUNCATE = 1,     /* rescale the product by 2^-frac_bits (local truncation)       */
+    MPC_TWO_PHASE = 2     /* Alg. 3 ordering: [a_i]*f first, while e is still "in flight" */
+};
+
+#define MPC_N_AND_TRIPLES 12
+/* Longest contraction (K, or KH*KW*Cin padded to 16 per filter tap) accepted:
+ * with 2K terms per digit-sum group the int32 sums stay exact below this. */
+#define MPC_MAX_K 16368
+
+/* ------------------------------------------------------------------ context */
+
+/* Creates a lane on `device` with its own three non-blocking streams (default
+ * priority).  frac_bits in [0, 62] is the fixed-point scale used by
+ * MPC_TRUNCATE.  Host-side allocation only. */
+int mpc_ctx_create(mpc_ctx** out, int device, int frac_bits);
+int mpc_ctx_destroy(mpc_ctx* ctx);
+
+/* Replace the lane's streams by caller-owned hipStream_t handles (e.g. from
+ * torch.cuda.Stream); NULL keeps the current one. */
+int mpc_ctx_set_streams(mpc_ctx* ctx, void* s_party0, void* s_party1, void* s_wire);
+/* stream handle: which = 0, 1 (party) or 2 (wire) */
+void* mpc_ctx_stream(mpc_ctx* ctx, int which);
+
+/* Caller-allocated device scratch, 256-byte aligned.  Contents are undefined
+ * between calls.  The lane must be idle when the workspace is replaced. */
+int mpc_ctx_set_workspace(mpc_ctx* ctx, void* dev_ptr, size_t bytes);
+
+/* Blocks the host until all three streams of the lane are idle. */
+int mpc_ctx_sync(mpc_ctx* ctx);
+
+/* Make party streams of `ctx` wait (device side) for everything enqueued so
+ * far on the party streams of `after`; used to chain layers across lanes. */
+int mpc_ctx_wait(mpc_ctx* ctx, mpc_ctx* after);
+
+int mpc_last_hip_error(const mpc_ctx* ctx);
+const char* mpc_strerror(int code);
+
+/* Bytes of workspace the calls below need for the given problem. */
+size_t mpc_matmul_workspace_bytes(int M, int K, int N, int batch);
+size_t mpc_conv2d_workspace_bytes(int B, int H, int W, int Cin, int Cout,
+                                  int KH, int KW, int pad, int stride);
+size_t mpc_relu_workspace_bytes(size_t n);
+size_t mpc_maxpool_workspace_bytes(int B, int H, int W, int C);
+
+/* ------------------------------------------------------------------ opening */
+
+/* Reconstruct an additive sharing (Sec. 3.1; Alg. 1's Delta = sum of the
+ * broadcast differences): out[k] = s.p[0][k] + s.p[1][k] mod 2^64.  Each
+ * party's share crosses the wire stream once; the sum is written by party
+ * 0's stream.  Needs 16*n bytes of workspace. */
+int mpc_open(mpc_ctx* ctx, mpc_cshare s, uint64_t* out_public, size_t n);
+
+/* --------------------------------------------------- Beaver matmul (Alg. 1) */
+
+/* z = x * y on additive shares with the triple (a, b, c), C = A*B:
+ *   e = open(x - a), f = open(y - b)
+ *   z_0 = c_0 + e*b_0 + a_0*f + e*f,   z_1 = c_1 + e*b_1 + a_1*f
+ * x, a: [batch][M][K];  y, b: [batch][K][N];  c, z: [batch][M][N].
+ * f_public: NULL, or a device array [batch][K][N] holding y - b already
+ *   opened ahead of time (Alg. 3: the weight mask is input independent); y
+ *   may then be {NULL, NULL}.
+ * n_chunks >= 1 splits the opening of e by rows into that many pieces whose
+ *   mask kernels and wire copies are issued back to back (Alg. 4's tiling
+ *   applied to the linear layer's exchange); results do not depend on it.
+ * flags: MPC_TRUNCATE, MPC_TWO_PHASE.
+ * Errors: MPC_EINVAL (null / non-positive), MPC_ERANGE (K > MPC_MAX_K),
+ *   MPC_ENOMEM (workspace < mpc_matmul_workspace_bytes). */
+int mpc_beaver_matmul(mpc_ctx* ctx, mpc_cshare x, mpc_cshare y,
+                      mpc_cshare a, mpc_cshare b, mpc_cshare c, mpc_share z,
+                      int M, int K, int N, int batch,
+                      const uint64_t* f_public, int n_chunks, int flags);
+
+/* The same with Conv as the product (Eq. 3).  x, a: [B][H][W][Cin] (NHWC);
+ * w, b: [KH][KW][Cin][Cout];  c, z: [B][Ho][Wo][Cout] with
+ * Ho = (H + 2*pad - KH)/stride + 1.  Padding pads shares with zero words.
+ * The im2col matrix is never materialised as ring words: the GEMM's tile
+ * loader gathers filter taps from the NHWC digit planes. */
+int mpc_conv2d(mpc_ctx* ctx, mpc_cshare x, mpc_cshare w,
+               mpc_cshare a, mpc_cshare b, mpc_cshare c, mpc_share z,
+               int B, int H, int W, int Cin, int Cout, int KH, int KW,
+               int pad, int stride,
+               const uint64_t* f_public, int n_chunks, int flags);
+
+/* Local fixed-point rescale of a two-party sharing, in place (the paper only
+ * requires fixed-point operands, Sec. 1.1; this is the usual local protocol):
+ *   z_0 <- z_0 >> bits (logical),   z_1 <- -((-z_1) >> bits). */
+int mpc_truncate(mpc_ctx* ctx, mpc_share z, size_t n, int bits);
+
+/* --------------------------------------------- secure ReLU (Alg. 2, Sec. 4.2) */
+
+/* Offline material for n elements, one pointer per party (device memory):
+ *   r            n words      A2B masks: party i keeps x_i ^ r_i, sends r_i
+ *   and_a/b/c    [12][n]      XOR-shared AND triples, triple-major; triple 0
+ *                             for G = U & V, 1+2l / 2+2l for prefix level l
+ *   rb, ra       n bytes / n words: XOR-shared random bit and additive shares
+ *                             of the same bit (B2A of the sign)
+ *   ma, mb, mc   n words      element-wise multiplication triple (select) */
+typedef struct {
+    mpc_cshare r;
+    mpc_cshare and_a, and_b, and_c;
+    const uint8_t* rb[2];
+    mpc_cshare ra;
+    mpc_cshare ma, mb, mc;
+} mpc_relu_material;
+
+/* y = ReLU(x) = x * (1 - MSB(x)) on additive shares:
+ *   A2B distribution (Alg. 2) -> 64-bit Kogge-Stone carry network whose AND
+ *   gates are Beaver ANDs (Eq. 4 / Alg. 4; 7 opening rounds, 12 word ANDs)
+ *   -> sign share = bit 63 of the sum -> B2A with a shared random bit
+ *   -> y = x * (1 - s) by element-wise Alg. 1 (no rescale).
+ * n_chunks >= 1 tiles every round's exchange as in Alg. 4: all chunks' mask
+ *   kernels and wire copies are issued back to back, then each chunk's gate
+ *   evaluation waits only for its own copy.  Results do not depend on it.
+ * s_bit[i] (n bytes) / s_arith[i] (n words): optional per-party outputs of
+ *   the sign's XOR share and additive share; NULL to skip. */
+int mpc_relu(mpc_ctx* ctx, mpc_cshare x, const mpc_relu_material* mat, mpc_share y,
+             size_t n, int n_chunks,
+             uint8_t* const s_bit[2], uint64_t* const s_arith[2]);
+
+/* 2x2 / stride-2 max-pool on NHWC shares by max(p, q) = q + ReLU(p - q): two
+ * tournament levels, i.e. two conversions per window (Sec. 4.2).  mat1 holds
+ * material for 2*n_out elements (level 1: pairs (p00,p01), (p10,p11) per
+ * output, interleaved), mat2 for n_out = B*(H/2)*(W/2)*C elements.  H, W even. */
+int mpc_maxpool2x2(mpc_ctx* ctx, mpc_cshare x, const mpc_relu_material* mat1,
+                   const mpc_relu_material* mat2, mpc_share y,
+                   int B, int H, int W, int C, int n_chunks);
+
+/* -------------------------------------------------- dealer helper (offline) */
+
+/* Plain ring product Z = L*R mod 2^64 on public device arrays, computed with
+ * the same digit-plane MFMA kernel: lets a synthetic dealer form C = A*B for
+ * a triple without leaving the device.  Not part of the online phase.
+ * Runs on party 0's stream; workspace as for mpc_beaver_matmul. */
+int mpc_ring_matmul(mpc_ctx* ctx, const uint64_t* L, const uint64_t* R, uint64_t* Z,
+                    int M, int K, int N, int batch);
+int mpc_ring_conv2d(mpc_ctx* ctx, const uint64_t* x, const uint64_t* w, uint64_t* z,
+                    int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                    int pad, int stride);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPCPIPE_H */

@@ -1,0 +1,152 @@
+// Internal declarations shared by the translation units of libmpcpipe.
+// Nothing here is part of the C ABI (that is include/mpcpipe.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/mpcpipe.h"
+
+typedef uint64_t u64;
+typedef uint8_t u8;
+
+constexpr int kEventPool = 256;
+constexpr size_t kAlign = 256;
+
+struct mpc_ctx {
+    int device;
+    int frac_bits;
+    hipStream_t s[3];        // 0, 1: party streams; 2: wire
+    bool own_stream[3];
+    hipEvent_t ev[kEventPool];
+    int ev_next;
+    u8* ws;                  // caller-owned workspace
+    size_t ws_bytes;
+    int last_hip;
+};
+
+static inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
+
+// Event pool: an event may be re-recorded once every wait on its previous
+// record has been enqueued, which host program order guarantees here because
+// each record is followed at once by the waits that consume it.
+static inline hipEvent_t next_event(mpc_ctx* c)
+{
+    hipEvent_t e = c->ev[c->ev_next];
+    c->ev_next = (c->ev_next + 1) % kEventPool;
+    return e;
+}
+
+#define MPC_HIP(ctx, call)                                   \
+    do {                                                     \
+        hipError_t _e = (call);                              \
+        if (_e != hipSuccess) {                              \
+            (ctx)->last_hip = (int)_e;                       \
+            return MPC_EHIP;                                 \
+        }                                                    \
+    } while (0)
+
+#define MPC_TRY(expr)                                        \
+    do {                                                     \
+        int _rc = (expr);                                    \
+        if (_rc != MPC_OK) return _rc;                       \
+    } while (0)
+
+// record on `from`, make `to` wait for it
+static inline int chain(mpc_ctx* c, hipStream_t from, hipStream_t to)
+{
+    if (from == to) return MPC_OK;
+    hipEvent_t e = next_event(c);
+    MPC_HIP(c, hipEventRecord(e, from));
+    MPC_HIP(c, hipStreamWaitEvent(to, e, 0));
+    return MPC_OK;
+}
+
+// Start of an entry point: every stream of the lane waits for the work already
+// enqueued on the other two, so a call may reuse the workspace and may read the
+// previous call's outputs of either party.
+static inline int lane_join(mpc_ctx* c)
+{
+    hipEvent_t e[3];
+    for (int i = 0; i < 3; ++i) {
+        e[i] = next_event(c);
+        MPC_HIP(c, hipEventRecord(e[i], c->s[i]));
+    }
+    for (int i = 0; i < 3; ++i)
+        for (int j = 0; j < 3; ++j)
+            if (i != j) MPC_HIP(c, hipStreamWaitEvent(c->s[i], e[j], 0));
+    return MPC_OK;
+}
+
+// Bump allocator over the workspace.
+struct WsAlloc {
+    u8* base; size_t cap; size_t off; bool ok;
+    WsAlloc(u8* b, size_t c) : base(b), cap(c), off(0), ok(true) {}
+    template <typename T> T* take(size_t count)
+    {
+        size_t bytes = align_up(count * sizeof(T));
+        if (!base || off + bytes > cap) { ok = false; off += bytes; return nullptr; }
+        T* p = reinterpret_cast<T*>(base + off);
+        off += bytes;
+        return p;
+    }
+};
+
+// ---- element-wise launchers (elementwise.hip) --------------------------------
+int launch_sub(mpc_ctx* c, hipStream_t st, const u64* x, const u64* a, u64* out, size_t n);
+int launch_add(mpc_ctx* c, hipStream_t st, const u64* x, const u64* y, u64* out, size_t n);
+int launch_copy(mpc_ctx* c, hipStream_t st, const void* src, void* dst, size_t bytes);
+int launch_fill_zero(mpc_ctx* c, hipStream_t st, void* dst, size_t bytes);
+int launch_truncate(mpc_ctx* c, hipStream_t st, u64* z, size_t n, int bits, int party);
+
+// ---- digit planes -------------------------------------------------------------
+// A digit-plane tensor stores a [rows][K] ring matrix as eight int8 planes,
+// one per balanced base-256 digit, each laid out [kb][row][16]: 16 consecutive
+// k of one row are one 16-byte unit, units of consecutive rows are adjacent.
+// KB is padded to an even number of blocks; digits beyond K are zero.
+static inline int kblocks(int K) { int kb = (K + 15) / 16; return (kb + 1) & ~1; }
+static inline size_t plane_bytes(int rows, int KB) { return (size_t)KB * rows * 16; }
+
+struct RecodeArgs {
+    const u64* src;       // element (row r, k) at src[r*row_stride + k*k_stride (+ tap*tap_stride)]
+    const u64* src2;      // optional addends with the same indexing (nullptr: none)
+    const u64* src3;
+    u8* dst;              // plane base
+    long long row_stride, k_stride, tap_stride;
+    int rows, K;          // valid extent per tap
+    int KB_tap;           // k-blocks per tap (ceil(K/16))
+    int ntaps;            // filter taps (1 for a plain matrix)
+    int KB_total;         // padded k-blocks of the plane tensor (>= ntaps*KB_tap)
+    long long digit_stride;   // bytes between digit planes
+    long long src_batch_stride, dst_batch_stride;  // elements / bytes
+    int batch;
+};
+int launch_recode(mpc_ctx* c, hipStream_t st, const RecodeArgs& a);
+
+// ---- limb GEMM (limb_gemm.hip) --------------------------------------------------
+struct GemmSeg {
+    const u8* L; const u8* R;         // digit planes (left: rows = M or pixels; right: rows = N)
+    long long L_dstride, R_dstride;   // bytes between digit planes
+    long long L_bstride, R_bstride;   // bytes between batch items
+    int KB;                           // 16-wide k blocks to contract (even)
+};
+struct ConvGeom {
+    int enabled;
+    int H, W, Ho, Wo, CB, KH, KW, pad, stride;
+    long long npix;                   // B*H*W: rows of the activation planes
+};
+struct GemmArgs {
+    GemmSeg seg[2][2];                // [party][segment]
+    int nseg, nparty;
+    const u64* addend[2];             // c_i, may be nullptr
+    const u64* addend2[2];            // partial sums of an earlier phase, may be nullptr
+    u64* out[2];
+    int M, N, batch;
+    long long out_bstride;            // elements between batch items of addend/out
+    int trunc_bits;                   // 0: none
+    int rows_L;                       // rows of the left planes (plain: M)
+    ConvGeom conv;
+    const u8* zero16;                 // 16 readable zero bytes (conv padding)
+};
+int launch_limb_gemm(mpc_ctx* c, hipStream_t st, const GemmArgs& g);

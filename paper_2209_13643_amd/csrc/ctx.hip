@@ -1,0 +1,138 @@
+// Context (execution lane), opening and truncation entry points.
+#include "common.h"
+
+#include <new>
+
+extern "C" {
+
+int mpc_ctx_create(mpc_ctx** out, int device, int frac_bits)
+{
+    if (!out || frac_bits < 0 || frac_bits > 62) return MPC_EINVAL;
+    mpc_ctx* c = new (std::nothrow) mpc_ctx();
+    if (!c) return MPC_ENOMEM;
+    c->device = device; c->frac_bits = frac_bits; c->ev_next = 0;
+    c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0;
+    for (int i = 0; i < 3; ++i) { c->s[i] = nullptr; c->own_stream[i] = false; }
+    for (int i = 0; i < kEventPool; ++i) c->ev[i] = nullptr;
+    hipError_t e = hipSetDevice(device);
+    for (int i = 0; i < 3 && e == hipSuccess; ++i) {
+        e = hipStreamCreateWithFlags(&c->s[i], hipStreamNonBlocking);
+        c->own_stream[i] = (e == hipSuccess);
+    }
+    for (int i = 0; i < kEventPool && e == hipSuccess; ++i)
+        e = hipEventCreateWithFlags(&c->ev[i], hipEventDisableTiming);
+    if (e != hipSuccess) {
+        int code = (int)e;
+        mpc_ctx_destroy(c);
+        (void)code;
+        return MPC_EHIP;
+    }
+    *out = c;
+    return MPC_OK;
+}
+
+int mpc_ctx_destroy(mpc_ctx* c)
+{
+    if (!c) return MPC_EINVAL;
+    for (int i = 0; i < 3; ++i)
+        if (c->s[i]) (void)hipStreamSynchronize(c->s[i]);
+    for (int i = 0; i < kEventPool; ++i)
+        if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+    for (int i = 0; i < 3; ++i)
+        if (c->own_stream[i] && c->s[i]) (void)hipStreamDestroy(c->s[i]);
+    delete c;
+    return MPC_OK;
+}
+
+int mpc_ctx_set_streams(mpc_ctx* c, void* s0, void* s1, void* sw)
+{
+    if (!c) return MPC_EINVAL;
+    void* in[3] = { s0, s1, sw };
+    for (int i = 0; i < 3; ++i) {
+        if (!in[i]) continue;
+        if (c->own_stream[i]) {
+            MPC_HIP(c, hipStreamSynchronize(c->s[i]));
+            MPC_HIP(c, hipStreamDestroy(c->s[i]));
+            c->own_stream[i] = false;
+        }
+        c->s[i] = (hipStream_t)in[i];
+    }
+    return MPC_OK;
+}
+
+void* mpc_ctx_stream(mpc_ctx* c, int which)
+{
+    if (!c || which < 0 || which > 2) return nullptr;
+    return (void*)c->s[which];
+}
+
+int mpc_ctx_set_workspace(mpc_ctx* c, void* p, size_t bytes)
+{
+    if (!c) return MPC_EINVAL;
+    if (p && ((uintptr_t)p % kAlign) != 0) return MPC_EINVAL;
+    c->ws = (u8*)p;
+    c->ws_bytes = p ? bytes : 0;
+    return MPC_OK;
+}
+
+int mpc_ctx_sync(mpc_ctx* c)
+{
+    if (!c) return MPC_EINVAL;
+    for (int i = 0; i < 3; ++i) MPC_HIP(c, hipStreamSynchronize(c->s[i]));
+    return MPC_OK;
+}
+
+int mpc_ctx_wait(mpc_ctx* c, mpc_ctx* after)
+{
+    if (!c || !after) return MPC_EINVAL;
+    for (int i = 0; i < 2; ++i) {
+        hipEvent_t e = next_event(after);
+        MPC_HIP(after, hipEventRecord(e, after->s[i]));
+        for (int j = 0; j < 2; ++j) MPC_HIP(c, hipStreamWaitEvent(c->s[j], e, 0));
+    }
+    return MPC_OK;
+}
+
+int mpc_last_hip_error(const mpc_ctx* c) { return c ? c->last_hip : 0; }
+
+const char* mpc_strerror(int code)
+{
+    switch (code) {
+    case MPC_OK: return "success";
+    case MPC_EINVAL: return "invalid argument (null pointer, non-positive size or unsupported shape)";
+    case MPC_ENOMEM: return "workspace missing or too small for this call";
+    case MPC_EHIP: return "a HIP runtime call failed (see mpc_last_hip_error)";
+    case MPC_ERANGE: return "contraction length exceeds the exact int32 digit-sum bound";
+    default: return "unknown mpcpipe error code";
+    }
+}
+
+// out = s0 + s1.  Each share is copied once over the wire stream into the
+// workspace ("received"), then party 0's stream adds the two.
+int mpc_open(mpc_ctx* c, mpc_cshare s, uint64_t* out, size_t n)
+{
+    if (!c || !s.p[0] || !s.p[1] || !out || n == 0) return MPC_EINVAL;
+    WsAlloc ws(c->ws, c->ws_bytes);
+    u64* r0 = ws.take<u64>(n);
+    u64* r1 = ws.take<u64>(n);
+    if (!ws.ok) return MPC_ENOMEM;
+    MPC_TRY(lane_join(c));
+    MPC_TRY(launch_copy(c, c->s[2], s.p[0], r0, n * sizeof(u64)));
+    MPC_TRY(launch_copy(c, c->s[2], s.p[1], r1, n * sizeof(u64)));
+    MPC_TRY(chain(c, c->s[2], c->s[0]));
+    MPC_TRY(launch_add(c, c->s[0], r0, r1, out, n));
+    // the workspace may be reused by party 1's next call only after the add
+    MPC_TRY(chain(c, c->s[0], c->s[1]));
+    return MPC_OK;
+}
+
+int mpc_truncate(mpc_ctx* c, mpc_share z, size_t n, int bits)
+{
+    if (!c || !z.p[0] || !z.p[1] || n == 0 || bits < 0 || bits > 63) return MPC_EINVAL;
+    MPC_TRY(lane_join(c));
+    MPC_TRY(launch_truncate(c, c->s[0], z.p[0], n, bits, 0));
+    MPC_TRY(launch_truncate(c, c->s[1], z.p[1], n, bits, 1));
+    return MPC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,205 @@
+// Streaming element-wise kernels: masking, opening, truncation, wire copy,
+// and the recoding of ring words into balanced base-256 digit planes.
+// All of them are HBM-bound; they use 16-byte accesses and grid-stride loops.
+#include "common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+inline int grid_for(size_t items, int per_thread = 1)
+{
+    size_t blocks = (items + (size_t)kThreads * per_thread - 1) / ((size_t)kThreads * per_thread);
+    const size_t cap = 256 * 16;          // 16 workgroups per CU keep HBM busy
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    return (int)blocks;
+}
+
+struct alignas(16) u64x2 { u64 a, b; };
+
+template <int OP>  // 0: x - y, 1: x + y
+__global__ __launch_bounds__(kThreads) void k_binary(const u64* __restrict__ x, const u64* __restrict__ y,
+                                                     u64* __restrict__ out, size_t n)
+{
+    const size_t n2 = n / 2;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const u64x2* x2 = reinterpret_cast<const u64x2*>(x);
+    const u64x2* y2 = reinterpret_cast<const u64x2*>(y);
+    u64x2* o2 = reinterpret_cast<u64x2*>(out);
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n2; i += stride) {
+        u64x2 p = x2[i], q = y2[i], r;
+        if (OP == 0) { r.a = p.a - q.a; r.b = p.b - q.b; }
+        else         { r.a = p.a + q.a; r.b = p.b + q.b; }
+        o2[i] = r;
+    }
+    if ((n & 1) && blockIdx.x == 0 && threadIdx.x == 0) {
+        const size_t i = n - 1;
+        out[i] = OP == 0 ? x[i] - y[i] : x[i] + y[i];
+    }
+}
+
+// scalar fallback when a pointer is only 8-byte aligned
+template <int OP>
+__global__ __launch_bounds__(kThreads) void k_binary_scalar(const u64* __restrict__ x, const u64* __restrict__ y,
+                                                            u64* __restrict__ out, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+        out[i] = OP == 0 ? x[i] - y[i] : x[i] + y[i];
+}
+
+__global__ __launch_bounds__(kThreads) void k_copy16(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(kThreads) void k_copy1(const u8* __restrict__ src, u8* __restrict__ dst, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(kThreads) void k_zero16(uint4* __restrict__ dst, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+        dst[i] = make_uint4(0, 0, 0, 0);
+}
+
+// Local two-party truncation: party 0 shifts, party 1 negates, shifts, negates.
+__global__ __launch_bounds__(kThreads) void k_truncate(u64* __restrict__ z, size_t n, int bits, int party)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const u64 v = z[i];
+        z[i] = party == 0 ? (v >> bits) : (u64)0 - (((u64)0 - v) >> bits);
+    }
+}
+
+// Balanced base-256 digits of x: x = sum_j d_j 2^(8j) (mod 2^64), d_j in
+// [-128, 127].  Adding 0x80 to every byte position (with carries) and flipping
+// the top bit of every byte yields the eight digits as two's-complement bytes.
+__device__ __forceinline__ u64 balanced_digits(u64 x)
+{
+    const u64 h = 0x8080808080808080ull;
+    return (x + h) ^ h;
+}
+
+// One thread recodes one (row, k-block): 16 ring words in, one 16-byte unit
+// out per digit plane.  Consecutive lanes take consecutive rows so that the
+// plane stores are contiguous.
+__global__ __launch_bounds__(kThreads) void k_recode(RecodeArgs a)
+{
+    const int tap = blockIdx.y;                       // == ntaps: zero padding block(s)
+    const int b = blockIdx.z;
+    const u64* src = a.src + (size_t)b * a.src_batch_stride;
+    const u64* src2 = a.src2 ? a.src2 + (size_t)b * a.src_batch_stride : nullptr;
+    const u64* src3 = a.src3 ? a.src3 + (size_t)b * a.src_batch_stride : nullptr;
+    u8* dst = a.dst + (size_t)b * a.dst_batch_stride;
+    const bool padtap = tap >= a.ntaps;
+    const int kb_count = padtap ? a.KB_total - a.ntaps * a.KB_tap : a.KB_tap;
+    const size_t items = (size_t)kb_count * a.rows;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t it = (size_t)blockIdx.x * blockDim.x + threadIdx.x; it < items; it += stride) {
+        const int kbl = (int)(it / a.rows);
+        const int row = (int)(it - (size_t)kbl * a.rows);
+        const int kb_out = (padtap ? a.ntaps * a.KB_tap : tap * a.KB_tap) + kbl;
+        u64 dg[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const int k = kbl * 16 + t;
+            u64 v = 0;
+            if (!padtap && k < a.K) {
+                const size_t idx = (size_t)row * a.row_stride + (size_t)k * a.k_stride + (size_t)tap * a.tap_stride;
+                v = src[idx];
+                if (src2) v += src2[idx];
+                if (src3) v += src3[idx];
+            }
+            dg[t] = balanced_digits(v);
+        }
+        u8* out = dst + ((size_t)kb_out * a.rows + row) * 16;
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            uint32_t w[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint32_t v = 0;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    v |= (uint32_t)((dg[q * 4 + t] >> (8 * d)) & 0xff) << (8 * t);
+                w[q] = v;
+            }
+            *reinterpret_cast<uint4*>(out + (size_t)d * a.digit_stride) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+}
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+template <int OP>
+int launch_binary(mpc_ctx* c, hipStream_t st, const u64* x, const u64* y, u64* out, size_t n)
+{
+    if (aligned16(x) && aligned16(y) && aligned16(out))
+        hipLaunchKernelGGL(k_binary<OP>, dim3(grid_for(n / 2 + 1)), dim3(kThreads), 0, st, x, y, out, n);
+    else
+        hipLaunchKernelGGL(k_binary_scalar<OP>, dim3(grid_for(n)), dim3(kThreads), 0, st, x, y, out, n);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+}  // namespace
+
+int launch_sub(mpc_ctx* c, hipStream_t st, const u64* x, const u64* a, u64* out, size_t n)
+{
+    return launch_binary<0>(c, st, x, a, out, n);
+}
+
+int launch_add(mpc_ctx* c, hipStream_t st, const u64* x, const u64* y, u64* out, size_t n)
+{
+    return launch_binary<1>(c, st, x, y, out, n);
+}
+
+// The "wire": a plain device copy kernel (kept as a kernel rather than
+// hipMemcpyAsync so that the same path can be captured into a HIP graph).
+int launch_copy(mpc_ctx* c, hipStream_t st, const void* src, void* dst, size_t bytes)
+{
+    if (bytes == 0) return MPC_OK;
+    if (aligned16(src) && aligned16(dst) && bytes % 16 == 0) {
+        const size_t n16 = bytes / 16;
+        hipLaunchKernelGGL(k_copy16, dim3(grid_for(n16)), dim3(kThreads), 0, st,
+                           (const uint4*)src, (uint4*)dst, n16);
+    } else {
+        hipLaunchKernelGGL(k_copy1, dim3(grid_for(bytes)), dim3(kThreads), 0, st,
+                           (const u8*)src, (u8*)dst, bytes);
+    }
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+int launch_fill_zero(mpc_ctx* c, hipStream_t st, void* dst, size_t bytes)
+{
+    if (bytes == 0) return MPC_OK;
+    if (!aligned16(dst) || bytes % 16) return MPC_EINVAL;
+    hipLaunchKernelGGL(k_zero16, dim3(grid_for(bytes / 16)), dim3(kThreads), 0, st, (uint4*)dst, bytes / 16);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+int launch_truncate(mpc_ctx* c, hipStream_t st, u64* z, size_t n, int bits, int party)
+{
+    hipLaunchKernelGGL(k_truncate, dim3(grid_for(n)), dim3(kThreads), 0, st, z, n, bits, party);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+int launch_recode(mpc_ctx* c, hipStream_t st, const RecodeArgs& a)
+{
+    const bool has_pad = a.KB_total > a.ntaps * a.KB_tap;
+    const size_t items = (size_t)a.KB_tap * a.rows;
+    dim3 grid(grid_for(items), a.ntaps + (has_pad ? 1 : 0), a.batch);
+    hipLaunchKernelGGL(k_recode, grid, dim3(kThreads), 0, st, a);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}

@@ -1,0 +1,311 @@
+// Beaver-triple matmul / conv (Alg. 1, Eq. 3) and the inter-linear ordering
+// of Alg. 3: host-side orchestration of mask kernels, wire copies, digit
+// recoding and the limb GEMM on the lane's three streams.
+#include "common.h"
+
+namespace {
+
+// Geometry of one secure linear layer seen as a GEMM.
+struct LinearShape {
+    bool conv;
+    int M, K, N, batch;          // GEMM view (conv: M = B*Ho*Wo, K = KH*KW*Cin, batch = 1)
+    // conv only
+    int B, H, W, Cin, Cout, KH, KW, pad, stride, Ho, Wo, CB;
+    // derived
+    size_t nx, nw, nz;           // words in x / w / z per party (all batch items)
+    int rowsL;                   // rows of a left plane (M, or B*H*W pixels)
+    int KB_L;                    // k blocks stored per left plane row
+    int KB;                      // k blocks contracted per segment (even)
+    size_t L_plane, R_plane;     // bytes of one digit plane (one batch item)
+};
+
+LinearShape shape_matmul(int M, int K, int N, int batch)
+{
+    LinearShape s{};
+    s.conv = false; s.M = M; s.K = K; s.N = N; s.batch = batch;
+    s.nx = (size_t)batch * M * K; s.nw = (size_t)batch * K * N; s.nz = (size_t)batch * M * N;
+    s.rowsL = M; s.KB = kblocks(K); s.KB_L = s.KB;
+    s.L_plane = plane_bytes(M, s.KB); s.R_plane = plane_bytes(N, s.KB);
+    return s;
+}
+
+LinearShape shape_conv(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    LinearShape s{};
+    s.conv = true; s.B = B; s.H = H; s.W = W; s.Cin = Cin; s.Cout = Cout;
+    s.KH = KH; s.KW = KW; s.pad = pad; s.stride = stride;
+    s.Ho = (H + 2 * pad - KH) / stride + 1; s.Wo = (W + 2 * pad - KW) / stride + 1;
+    s.CB = (Cin + 15) / 16;
+    s.M = B * s.Ho * s.Wo; s.K = KH * KW * Cin; s.N = Cout; s.batch = 1;
+    s.nx = (size_t)B * H * W * Cin; s.nw = (size_t)KH * KW * Cin * Cout; s.nz = (size_t)s.M * Cout;
+    s.rowsL = B * H * W; s.KB_L = s.CB;
+    s.KB = (KH * KW * s.CB + 1) & ~1;
+    s.L_plane = plane_bytes(s.rowsL, s.KB_L); s.R_plane = plane_bytes(Cout, s.KB);
+    return s;
+}
+
+struct LinearWs {
+    u8* zero;                  // 256 zero bytes
+    u64 *se[2], *re[2];        // masked x shares: sent / received
+    u64 *sf[2], *rf[2];        // masked y shares
+    u8 *pl_e, *pl_a[2];        // left digit planes
+    u8 *pr_f, *pr_b[2];        // right digit planes
+    size_t bytes; bool ok;
+};
+
+LinearWs carve(u8* base, size_t cap, const LinearShape& s)
+{
+    WsAlloc w(base, cap);
+    LinearWs r{};
+    r.zero = w.take<u8>(256);
+    for (int i = 0; i < 2; ++i) { r.se[i] = w.take<u64>(s.nx); r.re[i] = w.take<u64>(s.nx); }
+    for (int i = 0; i < 2; ++i) { r.sf[i] = w.take<u64>(s.nw); r.rf[i] = w.take<u64>(s.nw); }
+    const size_t lp = 8 * s.L_plane * s.batch, rp = 8 * s.R_plane * s.batch;
+    r.pl_e = w.take<u8>(lp); r.pl_a[0] = w.take<u8>(lp); r.pl_a[1] = w.take<u8>(lp);
+    r.pr_f = w.take<u8>(rp); r.pr_b[0] = w.take<u8>(rp); r.pr_b[1] = w.take<u8>(rp);
+    r.bytes = w.off; r.ok = w.ok;
+    return r;
+}
+
+RecodeArgs recode_left(const LinearShape& s, const u64* src, const u64* src2, u8* dst)
+{
+    RecodeArgs a{};
+    a.src = src; a.src2 = src2; a.src3 = nullptr; a.dst = dst;
+    a.k_stride = 1; a.tap_stride = 0; a.ntaps = 1; a.batch = s.batch;
+    if (s.conv) { a.rows = s.rowsL; a.K = s.Cin; a.row_stride = s.Cin; a.KB_tap = s.CB; a.KB_total = s.CB; }
+    else        { a.rows = s.M; a.K = s.K; a.row_stride = s.K; a.KB_tap = (s.K + 15) / 16; a.KB_total = s.KB; }
+    a.digit_stride = (long long)s.L_plane;
+    a.src_batch_stride = (long long)s.M * s.K;          // unused for conv (batch == 1)
+    a.dst_batch_stride = (long long)(8 * s.L_plane);
+    return a;
+}
+
+RecodeArgs recode_right(const LinearShape& s, const u64* src, const u64* src2, const u64* src3, u8* dst)
+{
+    RecodeArgs a{};
+    a.src = src; a.src2 = src2; a.src3 = src3; a.dst = dst;
+    a.rows = s.N; a.row_stride = 1; a.k_stride = s.N; a.batch = s.batch;
+    if (s.conv) { a.K = s.Cin; a.KB_tap = s.CB; a.ntaps = s.KH * s.KW; a.tap_stride = (long long)s.Cin * s.Cout; }
+    else        { a.K = s.K; a.KB_tap = (s.K + 15) / 16; a.ntaps = 1; a.tap_stride = 0; }
+    a.KB_total = s.KB;
+    a.digit_stride = (long long)s.R_plane;
+    a.src_batch_stride = (long long)s.K * s.N;
+    a.dst_batch_stride = (long long)(8 * s.R_plane);
+    return a;
+}
+
+void fill_geom(const LinearShape& s, const LinearWs& w, GemmArgs& g)
+{
+    g.M = s.M; g.N = s.N; g.batch = s.batch;
+    g.out_bstride = (long long)s.M * s.N;
+    g.rows_L = s.rowsL;
+    g.zero16 = w.zero;
+    g.conv = ConvGeom{};
+    if (s.conv) {
+        g.conv.enabled = 1; g.conv.H = s.H; g.conv.W = s.W; g.conv.Ho = s.Ho; g.conv.Wo = s.Wo;
+        g.conv.CB = s.CB; g.conv.KH = s.KH; g.conv.KW = s.KW; g.conv.pad = s.pad; g.conv.stride = s.stride;
+        g.conv.npix = (long long)s.rowsL;
+    }
+}
+
+GemmSeg make_seg(const LinearShape& s, const u8* L, const u8* R)
+{
+    GemmSeg q{};
+    q.L = L; q.R = R;
+    q.L_dstride = (long long)s.L_plane; q.R_dstride = (long long)s.R_plane;
+    q.L_bstride = (long long)(8 * s.L_plane); q.R_bstride = (long long)(8 * s.R_plane);
+    q.KB = s.KB;
+    return q;
+}
+
+int check_shape(const LinearShape& s)
+{
+    if (s.M <= 0 || s.K <= 0 || s.N <= 0 || s.batch <= 0) return MPC_EINVAL;
+    if (s.conv) {
+        if (s.B <= 0 || s.H <= 0 || s.W <= 0 || s.Cin <= 0 || s.Cout <= 0 || s.KH <= 0 || s.KW <= 0 ||
+            s.pad < 0 || s.stride <= 0 || s.Ho <= 0 || s.Wo <= 0 || s.KH * s.KW > 64)
+            return MPC_EINVAL;
+        if ((long long)s.KH * s.KW * s.CB * 16 > MPC_MAX_K) return MPC_ERANGE;
+    } else if (s.K > MPC_MAX_K) return MPC_ERANGE;
+    if ((long long)s.batch * 2 > 65535) return MPC_EINVAL;
+    return MPC_OK;
+}
+
+// The whole secure linear layer.  See mpc_beaver_matmul in the public header.
+int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
+                  mpc_cshare a, mpc_cshare b, mpc_cshare cc, mpc_share z,
+                  const u64* f_public, int n_chunks, int flags)
+{
+    if (!c) return MPC_EINVAL;
+    MPC_TRY(check_shape(s));
+    if (n_chunks < 1) return MPC_EINVAL;
+    for (int i = 0; i < 2; ++i) {
+        if (!x.p[i] || !a.p[i] || !b.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
+        if (!f_public && !y.p[i]) return MPC_EINVAL;
+    }
+    LinearWs w = carve(c->ws, c->ws_bytes, s);
+    if (!w.ok) return MPC_ENOMEM;
+
+    hipStream_t P0 = c->s[0], P1 = c->s[1], Wr = c->s[2];
+    hipStream_t P[2] = { P0, P1 };
+    const bool two_phase = (flags & MPC_TWO_PHASE) != 0;
+    const int trunc = (flags & MPC_TRUNCATE) ? c->frac_bits : 0;
+
+    MPC_TRY(lane_join(c));
+    MPC_TRY(launch_fill_zero(c, P0, w.zero, 256));
+
+    // -- Alg. 1 line 1-2 / Alg. 3 line 2-3: mask and start the exchange, chunk by chunk
+    if (!f_public) {
+        for (int i = 0; i < 2; ++i) {
+            MPC_TRY(launch_sub(c, P[i], y.p[i], b.p[i], w.sf[i], s.nw));
+            MPC_TRY(chain(c, P[i], Wr));
+        }
+        for (int i = 0; i < 2; ++i)
+            MPC_TRY(launch_copy(c, Wr, w.sf[i], w.rf[1 - i], s.nw * sizeof(u64)));
+    }
+    if ((size_t)n_chunks > s.nx) n_chunks = (int)s.nx;
+    for (int ch = 0; ch < n_chunks; ++ch) {
+        // contiguous word ranges, 2-word aligned so the 16-byte paths stay usable
+        size_t lo = (s.nx * ch / n_chunks) & ~(size_t)1, hi = (s.nx * (ch + 1) / n_chunks) & ~(size_t)1;
+        if (ch == n_chunks - 1) hi = s.nx;
+        if (hi <= lo) continue;
+        for (int i = 0; i < 2; ++i) {
+            MPC_TRY(launch_sub(c, P[i], x.p[i] + lo, a.p[i] + lo, w.se[i] + lo, hi - lo));
+            MPC_TRY(chain(c, P[i], Wr));
+        }
+        for (int i = 0; i < 2; ++i)
+            MPC_TRY(launch_copy(c, Wr, w.se[i] + lo, w.re[1 - i] + lo, (hi - lo) * sizeof(u64)));
+    }
+
+    // -- digit planes that do not depend on the exchange: [a_i] (and b_1)
+    for (int i = 0; i < 2; ++i)
+        MPC_TRY(launch_recode(c, P[i], recode_left(s, a.p[i], nullptr, w.pl_a[i])));
+    MPC_TRY(launch_recode(c, P1, recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1])));
+
+    GemmArgs g{};
+    fill_geom(s, w, g);
+    g.nparty = 2;
+
+    if (two_phase && f_public) {
+        // Alg. 3 lines 4-6: epsilon is already here; z_i = Conv([a_i], epsilon)
+        // runs while the masked inputs are still crossing the wire.
+        MPC_TRY(launch_recode(c, P0, recode_right(s, f_public, nullptr, nullptr, w.pr_f)));
+        MPC_TRY(launch_recode(c, P0, recode_right(s, b.p[0], f_public, nullptr, w.pr_b[0])));
+        MPC_TRY(chain(c, P1, P0));
+        g.nseg = 1;
+        for (int i = 0; i < 2; ++i) {
+            g.seg[i][0] = make_seg(s, w.pl_a[i], w.pr_f);
+            g.addend[i] = nullptr; g.addend2[i] = nullptr; g.out[i] = z.p[i];
+        }
+        g.trunc_bits = 0;
+        MPC_TRY(launch_limb_gemm(c, P0, g));
+        // Alg. 3 lines 7-10: wait for Delta, add [c_i] + Conv(Delta, [b_i]) (+ Conv(Delta, epsilon))
+        MPC_TRY(chain(c, Wr, P0));
+        MPC_TRY(launch_recode(c, P0, recode_left(s, w.se[0], w.re[0], w.pl_e)));
+        for (int i = 0; i < 2; ++i) {
+            g.seg[i][0] = make_seg(s, w.pl_e, w.pr_b[i]);
+            g.addend[i] = cc.p[i]; g.addend2[i] = z.p[i];
+        }
+        g.trunc_bits = trunc;
+        MPC_TRY(launch_limb_gemm(c, P0, g));
+    } else {
+        // Alg. 1 lines 3-7: wait for the exchange, open, one fused contraction
+        // [e | a_i] x [b_i (+ f for party 0) ; f] per party.
+        MPC_TRY(chain(c, Wr, P0));
+        MPC_TRY(launch_recode(c, P0, recode_left(s, w.se[0], w.re[0], w.pl_e)));
+        if (f_public) {
+            MPC_TRY(launch_recode(c, P0, recode_right(s, f_public, nullptr, nullptr, w.pr_f)));
+            MPC_TRY(launch_recode(c, P0, recode_right(s, b.p[0], f_public, nullptr, w.pr_b[0])));
+        } else {
+            MPC_TRY(launch_recode(c, P0, recode_right(s, w.sf[0], w.rf[0], nullptr, w.pr_f)));
+            MPC_TRY(launch_recode(c, P0, recode_right(s, b.p[0], w.sf[0], w.rf[0], w.pr_b[0])));
+        }
+        MPC_TRY(chain(c, P1, P0));
+        g.nseg = 2;
+        for (int i = 0; i < 2; ++i) {
+            g.seg[i][0] = make_seg(s, w.pl_e, w.pr_b[i]);
+            g.seg[i][1] = make_seg(s, w.pl_a[i], w.pr_f);
+            g.addend[i] = cc.p[i]; g.addend2[i] = nullptr; g.out[i] = z.p[i];
+        }
+        g.trunc_bits = trunc;
+        MPC_TRY(launch_limb_gemm(c, P0, g));
+    }
+    // party 1's output was produced by the joint launch on party 0's stream
+    MPC_TRY(chain(c, P0, P1));
+    return MPC_OK;
+}
+
+int ring_product(mpc_ctx* c, const LinearShape& s, const u64* L, const u64* R, u64* Z)
+{
+    if (!c || !L || !R || !Z) return MPC_EINVAL;
+    MPC_TRY(check_shape(s));
+    LinearWs w = carve(c->ws, c->ws_bytes, s);
+    if (!w.ok) return MPC_ENOMEM;
+    hipStream_t P0 = c->s[0];
+    MPC_TRY(lane_join(c));
+    MPC_TRY(launch_fill_zero(c, P0, w.zero, 256));
+    MPC_TRY(launch_recode(c, P0, recode_left(s, L, nullptr, w.pl_e)));
+    MPC_TRY(launch_recode(c, P0, recode_right(s, R, nullptr, nullptr, w.pr_f)));
+    GemmArgs g{};
+    fill_geom(s, w, g);
+    g.nparty = 1; g.nseg = 1;
+    g.seg[0][0] = make_seg(s, w.pl_e, w.pr_f);
+    g.addend[0] = nullptr; g.addend2[0] = nullptr; g.out[0] = Z; g.trunc_bits = 0;
+    MPC_TRY(launch_limb_gemm(c, P0, g));
+    MPC_TRY(chain(c, P0, c->s[1]));
+    return MPC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t mpc_matmul_workspace_bytes(int M, int K, int N, int batch)
+{
+    LinearShape s = shape_matmul(M, K, N, batch);
+    if (check_shape(s) != MPC_OK) return 0;
+    return carve(nullptr, 0, s).bytes;
+}
+
+size_t mpc_conv2d_workspace_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (stride <= 0) return 0;
+    LinearShape s = shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride);
+    if (check_shape(s) != MPC_OK) return 0;
+    return carve(nullptr, 0, s).bytes;
+}
+
+int mpc_beaver_matmul(mpc_ctx* ctx, mpc_cshare x, mpc_cshare y, mpc_cshare a, mpc_cshare b, mpc_cshare c,
+                      mpc_share z, int M, int K, int N, int batch,
+                      const uint64_t* f_public, int n_chunks, int flags)
+{
+    if (M <= 0 || K <= 0 || N <= 0 || batch <= 0) return MPC_EINVAL;
+    return beaver_linear(ctx, shape_matmul(M, K, N, batch), x, y, a, b, c, z, f_public, n_chunks, flags);
+}
+
+int mpc_conv2d(mpc_ctx* ctx, mpc_cshare x, mpc_cshare w, mpc_cshare a, mpc_cshare b, mpc_cshare c,
+               mpc_share z, int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride,
+               const uint64_t* f_public, int n_chunks, int flags)
+{
+    if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
+        return MPC_EINVAL;
+    return beaver_linear(ctx, shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride), x, w, a, b, c, z,
+                         f_public, n_chunks, flags);
+}
+
+int mpc_ring_matmul(mpc_ctx* ctx, const uint64_t* L, const uint64_t* R, uint64_t* Z,
+                    int M, int K, int N, int batch)
+{
+    if (M <= 0 || K <= 0 || N <= 0 || batch <= 0) return MPC_EINVAL;
+    return ring_product(ctx, shape_matmul(M, K, N, batch), L, R, Z);
+}
+
+int mpc_ring_conv2d(mpc_ctx* ctx, const uint64_t* x, const uint64_t* w, uint64_t* z,
+                    int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
+        return MPC_EINVAL;
+    return ring_product(ctx, shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride), x, w, z);
+}
+
+}  // extern "C"

@@ -1,0 +1,518 @@
+// Secure ReLU (Alg. 2 + Sec. 4.2) and 2x2 max-pool by composition.
+//
+// Per party the protocol is a chain of streaming kernels separated by the
+// exchange of masked words over the wire stream:
+//
+//   wire: A2B masks r_i                                   (1 word / element)
+//   K_first   U, V from x_i, r_i, received r; mask for G = U & V        -> wire (2)
+//   K_level l (l = 0..5): finish the AND(s) of the previous round, then mask
+//             the operands of prefix level l: (P, G << 2^l), (P, P << 2^l) -> wire (4; 2 at l = 5)
+//   K_sign    finish level 5, sign share = bit63(U^V) ^ bit62(G),
+//             mask it with the shared random bit                          -> wire (1 byte)
+//   K_b2a     additive share of the sign, m = 1 - s, mask x and m          -> wire (2)
+//   K_select  y = x * m (element-wise Alg. 1)
+//
+// Every kernel is HBM-bound: it reads the triple words of its round once,
+// carries (G, P) as state, and writes what it sends.  Chunks (Alg. 4's tiles)
+// are disjoint element ranges; all chunks of a round are launched back to
+// back and chunk m of the next round waits only for chunk m's copy.
+#include "common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxChunks = 32;
+
+struct alignas(16) u64x2 { u64 a, b; };
+
+// Everything one party's kernels may touch.
+struct ReluParty {
+    const u64* x; const u64* r;
+    const u64* ta; const u64* tb; const u64* tc;       // [12][n]
+    const u8* rb; const u64* ra;
+    const u64* ma; const u64* mb; const u64* mc;
+    u64* send;      // [4][n] words this party sends in the current round
+    const u64* recv;   // [4][n] words received from the other party
+    u8* sendb; const u8* recvb;    // byte exchange (B2A)
+    u64* G; u64* P; u8* p63;       // carried state
+    u64* y; u8* s_bit; u64* s_arith;
+    size_t n;       // total elements (stride of the [12][n] / [4][n] arrays)
+};
+
+template <int V> struct Pack;
+template <> struct Pack<1> {
+    u64 v[1];
+    __device__ static Pack ld(const u64* p, size_t i) { Pack r; r.v[0] = p[i]; return r; }
+    __device__ void st(u64* p, size_t i) const { p[i] = v[0]; }
+};
+template <> struct Pack<2> {
+    u64 v[2];
+    __device__ static Pack ld(const u64* p, size_t i)
+    {
+        const u64x2 t = *reinterpret_cast<const u64x2*>(p + i);
+        Pack r; r.v[0] = t.a; r.v[1] = t.b; return r;
+    }
+    __device__ void st(u64* p, size_t i) const
+    {
+        u64x2 t; t.a = v[0]; t.b = v[1];
+        *reinterpret_cast<u64x2*>(p + i) = t;
+    }
+};
+
+// Beaver AND, one party's side (Eq. 4; Alg. 4 for the party that adds d & g):
+// d, g are the opened masked operands, (a, b, c) this party's triple words.
+template <int PARTY>
+__device__ __forceinline__ u64 and_finish(u64 d, u64 g, u64 a, u64 b, u64 c)
+{
+    u64 t = c ^ (d & b) ^ (g & a);
+    if (PARTY == 0) t ^= d & g;
+    return t;
+}
+
+#define FOR_ELEMS(V)                                                                         \
+    const size_t stride_ = (size_t)gridDim.x * blockDim.x * V;                               \
+    for (size_t i = lo + ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * V; i < hi; i += stride_)
+
+// ---- K_first ------------------------------------------------------------------
+template <int PARTY, int V>
+__global__ __launch_bounds__(kThreads) void k_first(ReluParty p, size_t lo, size_t hi)
+{
+    const size_t n = p.n;
+    FOR_ELEMS(V) {
+        const Pack<V> x = Pack<V>::ld(p.x, i), r = Pack<V>::ld(p.r, i), rr = Pack<V>::ld(p.recv, i);
+        const Pack<V> a0 = Pack<V>::ld(p.ta, i), b0 = Pack<V>::ld(p.tb, i);
+        Pack<V> d, g, P;
+        u8 top[V];
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            // Alg. 2: U is the sharing of the word x_0, V of the word x_1
+            const u64 U = PARTY == 0 ? (x.v[k] ^ r.v[k]) : rr.v[k];
+            const u64 Vv = PARTY == 0 ? rr.v[k] : (x.v[k] ^ r.v[k]);
+            d.v[k] = U ^ a0.v[k];
+            g.v[k] = Vv ^ b0.v[k];
+            P.v[k] = U ^ Vv;
+            top[k] = (u8)(P.v[k] >> 63);
+        }
+        d.st(p.send, i); g.st(p.send + n, i); P.st(p.P, i);
+#pragma unroll
+        for (int k = 0; k < V; ++k) p.p63[i + k] = top[k];
+    }
+}
+
+// ---- K_level ------------------------------------------------------------------
+// LEVEL 0 finishes G = U & V (triple 0, own masked words re-read from the send
+// buffer); LEVEL l > 0 finishes the two ANDs of level l-1 from the carried
+// (G, P).  Then masks the operands of level LEVEL.
+template <int PARTY, int LEVEL, int V>
+__global__ __launch_bounds__(kThreads) void k_level(ReluParty p, size_t lo, size_t hi)
+{
+    const size_t n = p.n;
+    constexpr int sh = 1 << LEVEL;
+    FOR_ELEMS(V) {
+        Pack<V> G, P;
+        if constexpr (LEVEL == 0) {
+            const Pack<V> sd = Pack<V>::ld(p.send, i), sg = Pack<V>::ld(p.send + n, i);
+            const Pack<V> rd = Pack<V>::ld(p.recv, i), rg = Pack<V>::ld(p.recv + n, i);
+            const Pack<V> a = Pack<V>::ld(p.ta, i), b = Pack<V>::ld(p.tb, i), c = Pack<V>::ld(p.tc, i);
+            P = Pack<V>::ld(p.P, i);
+#pragma unroll
+            for (int k = 0; k < V; ++k)
+                G.v[k] = and_finish<PARTY>(sd.v[k] ^ rd.v[k], sg.v[k] ^ rg.v[k], a.v[k], b.v[k], c.v[k]);
+        } else {
+            constexpr int psh = 1 << (LEVEL - 1);
+            constexpr int t1 = 1 + 2 * (LEVEL - 1), t2 = 2 + 2 * (LEVEL - 1);
+            const Pack<V> Go = Pack<V>::ld(p.G, i), Po = Pack<V>::ld(p.P, i);
+            const Pack<V> rd1 = Pack<V>::ld(p.recv, i), rg1 = Pack<V>::ld(p.recv + n, i);
+            const Pack<V> rd2 = Pack<V>::ld(p.recv + 2 * n, i), rg2 = Pack<V>::ld(p.recv + 3 * n, i);
+            const Pack<V> a1 = Pack<V>::ld(p.ta + t1 * n, i), b1 = Pack<V>::ld(p.tb + t1 * n, i),
+                          c1 = Pack<V>::ld(p.tc + t1 * n, i);
+            const Pack<V> a2 = Pack<V>::ld(p.ta + t2 * n, i), b2 = Pack<V>::ld(p.tb + t2 * n, i),
+                          c2 = Pack<V>::ld(p.tc + t2 * n, i);
+#pragma unroll
+            for (int k = 0; k < V; ++k) {
+                // own masked words are recomputed from the carried state
+                const u64 d1 = (Po.v[k] ^ a1.v[k]) ^ rd1.v[k];
+                const u64 g1 = ((Go.v[k] << psh) ^ b1.v[k]) ^ rg1.v[k];
+                const u64 d2 = (Po.v[k] ^ a2.v[k]) ^ rd2.v[k];
+                const u64 g2 = ((Po.v[k] << psh) ^ b2.v[k]) ^ rg2.v[k];
+                G.v[k] = Go.v[k] ^ and_finish<PARTY>(d1, g1, a1.v[k], b1.v[k], c1.v[k]);
+                P.v[k] = and_finish<PARTY>(d2, g2, a2.v[k], b2.v[k], c2.v[k]);
+            }
+        }
+        constexpr int u1 = 1 + 2 * LEVEL, u2 = 2 + 2 * LEVEL;
+        const Pack<V> na1 = Pack<V>::ld(p.ta + u1 * n, i), nb1 = Pack<V>::ld(p.tb + u1 * n, i);
+        Pack<V> d1, g1;
+#pragma unroll
+        for (int k = 0; k < V; ++k) { d1.v[k] = P.v[k] ^ na1.v[k]; g1.v[k] = (G.v[k] << sh) ^ nb1.v[k]; }
+        d1.st(p.send, i); g1.st(p.send + n, i);
+        if constexpr (LEVEL < 5) {
+            const Pack<V> na2 = Pack<V>::ld(p.ta + u2 * n, i), nb2 = Pack<V>::ld(p.tb + u2 * n, i);
+            Pack<V> d2, g2;
+#pragma unroll
+            for (int k = 0; k < V; ++k) { d2.v[k] = P.v[k] ^ na2.v[k]; g2.v[k] = (P.v[k] << sh) ^ nb2.v[k]; }
+            d2.st(p.send + 2 * n, i); g2.st(p.send + 3 * n, i);
+        }
+        G.st(p.G, i); P.st(p.P, i);
+    }
+}
+
+// ---- K_sign -------------------------------------------------------------------
+template <int PARTY, int V>
+__global__ __launch_bounds__(kThreads) void k_sign(ReluParty p, size_t lo, size_t hi)
+{
+    const size_t n = p.n;
+    constexpr int t1 = 11, psh = 32;
+    FOR_ELEMS(V) {
+        const Pack<V> Go = Pack<V>::ld(p.G, i), Po = Pack<V>::ld(p.P, i);
+        const Pack<V> rd1 = Pack<V>::ld(p.recv, i), rg1 = Pack<V>::ld(p.recv + n, i);
+        const Pack<V> a1 = Pack<V>::ld(p.ta + t1 * n, i), b1 = Pack<V>::ld(p.tb + t1 * n, i),
+                      c1 = Pack<V>::ld(p.tc + t1 * n, i);
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            const u64 d1 = (Po.v[k] ^ a1.v[k]) ^ rd1.v[k];
+            const u64 g1 = ((Go.v[k] << psh) ^ b1.v[k]) ^ rg1.v[k];
+            const u64 G = Go.v[k] ^ and_finish<PARTY>(d1, g1, a1.v[k], b1.v[k], c1.v[k]);
+            // bit 63 of the sum = bit 63 of U^V xor the carry out of bits [0..62]
+            const u8 s = (u8)(p.p63[i + k] ^ (u8)((G >> 62) & 1));
+            if (p.s_bit) p.s_bit[i + k] = s;
+            p.sendb[i + k] = (u8)(s ^ p.rb[i + k]);
+        }
+    }
+}
+
+// ---- K_b2a --------------------------------------------------------------------
+template <int PARTY, int V>
+__global__ __launch_bounds__(kThreads) void k_b2a(ReluParty p, size_t lo, size_t hi)
+{
+    const size_t n = p.n;
+    FOR_ELEMS(V) {
+        const Pack<V> x = Pack<V>::ld(p.x, i), ra = Pack<V>::ld(p.ra, i);
+        const Pack<V> ma = Pack<V>::ld(p.ma, i), mb = Pack<V>::ld(p.mb, i);
+        Pack<V> e, f, sa;
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            const u64 v = (u64)(p.sendb[i + k] ^ p.recvb[i + k]);     // opened s ^ rb
+            // s = v xor rb = v + rb - 2 v rb on additive shares of rb
+            sa.v[k] = ra.v[k] - 2 * v * ra.v[k] + (PARTY == 0 ? v : 0);
+            const u64 m = (PARTY == 0 ? (u64)1 : (u64)0) - sa.v[k];    // shares of 1 - s
+            e.v[k] = x.v[k] - ma.v[k];
+            f.v[k] = m - mb.v[k];
+        }
+        e.st(p.send, i); f.st(p.send + n, i);
+        if (p.s_arith) sa.st(p.s_arith, i);
+    }
+}
+
+// ---- K_select -----------------------------------------------------------------
+template <int PARTY, int V>
+__global__ __launch_bounds__(kThreads) void k_select(ReluParty p, size_t lo, size_t hi)
+{
+    const size_t n = p.n;
+    FOR_ELEMS(V) {
+        const Pack<V> se = Pack<V>::ld(p.send, i), sf = Pack<V>::ld(p.send + n, i);
+        const Pack<V> re = Pack<V>::ld(p.recv, i), rf = Pack<V>::ld(p.recv + n, i);
+        const Pack<V> ma = Pack<V>::ld(p.ma, i), mb = Pack<V>::ld(p.mb, i), mc = Pack<V>::ld(p.mc, i);
+        Pack<V> y;
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            const u64 e = se.v[k] + re.v[k], f = sf.v[k] + rf.v[k];
+            u64 t = mc.v[k] + e * mb.v[k] + ma.v[k] * f;
+            if (PARTY == 0) t += e * f;
+            y.v[k] = t;
+        }
+        y.st(p.y, i);
+    }
+}
+
+// rows x len words, both sides with pitch `pitch` words: the per-round wire copy
+__global__ __launch_bounds__(kThreads) void k_wire_words(const u64* __restrict__ src, u64* __restrict__ dst,
+                                                         size_t pitch, size_t lo, size_t hi, int rows)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x * 2;
+    for (int r = 0; r < rows; ++r) {
+        const u64* s = src + (size_t)r * pitch; u64* d = dst + (size_t)r * pitch;
+        for (size_t i = lo + ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 2; i < hi; i += stride)
+            *reinterpret_cast<u64x2*>(d + i) = *reinterpret_cast<const u64x2*>(s + i);
+    }
+}
+__global__ __launch_bounds__(kThreads) void k_wire_words1(const u64* __restrict__ src, u64* __restrict__ dst,
+                                                          size_t pitch, size_t lo, size_t hi, int rows)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (int r = 0; r < rows; ++r)
+        for (size_t i = lo + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < hi; i += stride)
+            dst[(size_t)r * pitch + i] = src[(size_t)r * pitch + i];
+}
+__global__ __launch_bounds__(kThreads) void k_wire_bytes(const u8* __restrict__ src, u8* __restrict__ dst,
+                                                         size_t lo, size_t hi)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = lo + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < hi; i += stride) dst[i] = src[i];
+}
+
+inline int grid_for(size_t items)
+{
+    size_t blocks = (items + kThreads - 1) / kThreads;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks < 1) blocks = 1;
+    return (int)blocks;
+}
+
+struct ReluWs {
+    u64 *send[2], *recv[2];     // [4][n]
+    u8 *sendb[2], *recvb[2];
+    u64 *G[2], *P[2]; u8* p63[2];
+    size_t bytes; bool ok;
+};
+
+ReluWs carve_relu(u8* base, size_t cap, size_t n)
+{
+    WsAlloc w(base, cap);
+    ReluWs r{};
+    for (int i = 0; i < 2; ++i) {
+        r.send[i] = w.take<u64>(4 * n); r.recv[i] = w.take<u64>(4 * n);
+        r.sendb[i] = w.take<u8>(n); r.recvb[i] = w.take<u8>(n);
+        r.G[i] = w.take<u64>(n); r.P[i] = w.take<u64>(n); r.p63[i] = w.take<u8>(n);
+    }
+    r.bytes = w.off; r.ok = w.ok;
+    return r;
+}
+
+enum Stage { ST_FIRST = 0, ST_LEVEL0 = 1, ST_SIGN = 7, ST_B2A = 8, ST_SELECT = 9, ST_COUNT = 10 };
+
+template <int PARTY, int V>
+void launch_stage(int stage, hipStream_t st, const ReluParty& p, size_t lo, size_t hi)
+{
+    const dim3 grid(grid_for((hi - lo + V - 1) / V)), block(kThreads);
+    switch (stage) {
+    case 0: hipLaunchKernelGGL((k_first<PARTY, V>), grid, block, 0, st, p, lo, hi); break;
+    case 1: hipLaunchKernelGGL((k_level<PARTY, 0, V>), grid, block, 0, st, p, lo, hi); break;
+    case 2: hipLaunchKernelGGL((k_level<PARTY, 1, V>), grid, block, 0, st, p, lo, hi); break;
+    case 3: hipLaunchKernelGGL((k_level<PARTY, 2, V>), grid, block, 0, st, p, lo, hi); break;
+    case 4: hipLaunchKernelGGL((k_level<PARTY, 3, V>), grid, block, 0, st, p, lo, hi); break;
+    case 5: hipLaunchKernelGGL((k_level<PARTY, 4, V>), grid, block, 0, st, p, lo, hi); break;
+    case 6: hipLaunchKernelGGL((k_level<PARTY, 5, V>), grid, block, 0, st, p, lo, hi); break;
+    case 7: hipLaunchKernelGGL((k_sign<PARTY, V>), grid, block, 0, st, p, lo, hi); break;
+    case 8: hipLaunchKernelGGL((k_b2a<PARTY, V>), grid, block, 0, st, p, lo, hi); break;
+    case 9: hipLaunchKernelGGL((k_select<PARTY, V>), grid, block, 0, st, p, lo, hi); break;
+    default: break;
+    }
+}
+
+// words (rows of the [4][n] buffer) exchanged after each stage; 0 = byte exchange
+inline int words_after(int stage)
+{
+    if (stage == ST_FIRST) return 2;
+    if (stage >= ST_LEVEL0 && stage < ST_LEVEL0 + 5) return 4;
+    if (stage == ST_LEVEL0 + 5) return 2;
+    if (stage == ST_SIGN) return 0;
+    if (stage == ST_B2A) return 2;
+    return -1;  // select: nothing to send
+}
+
+int wire_words(mpc_ctx* c, const u64* src, u64* dst, size_t pitch, size_t lo, size_t hi, int rows, bool vec)
+{
+    const size_t len = hi - lo;
+    if (vec)
+        hipLaunchKernelGGL(k_wire_words, dim3(grid_for(len / 2)), dim3(kThreads), 0, c->s[2], src, dst, pitch, lo, hi, rows);
+    else
+        hipLaunchKernelGGL(k_wire_words1, dim3(grid_for(len)), dim3(kThreads), 0, c->s[2], src, dst, pitch, lo, hi, rows);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+// The protocol on n elements whose buffers are described by parties[2].
+int relu_run(mpc_ctx* c, ReluParty (&pp)[2], size_t n, int n_chunks)
+{
+    if (n_chunks > kMaxChunks) n_chunks = kMaxChunks;
+    if ((size_t)n_chunks > (n + 1) / 2) n_chunks = (int)((n + 1) / 2);
+    if (n_chunks < 1) n_chunks = 1;
+    // 16-byte accesses need even n (so that every [k][n] row stays aligned) and aligned bases
+    bool vec = (n % 2 == 0);
+    for (int i = 0; i < 2 && vec; ++i) {
+        const void* ptrs[] = { pp[i].x, pp[i].r, pp[i].ta, pp[i].tb, pp[i].tc, pp[i].ra, pp[i].ma,
+                               pp[i].mb, pp[i].mc, pp[i].y, pp[i].s_arith };
+        for (const void* q : ptrs) if (q && ((uintptr_t)q & 15)) vec = false;
+    }
+    size_t lo[kMaxChunks], hi[kMaxChunks];
+    for (int m = 0; m < n_chunks; ++m) {
+        lo[m] = (n * m / n_chunks) & ~(size_t)1;
+        hi[m] = (m == n_chunks - 1) ? n : ((n * (m + 1) / n_chunks) & ~(size_t)1);
+    }
+    hipStream_t P[2] = { c->s[0], c->s[1] }, Wr = c->s[2];
+    hipEvent_t got[kMaxChunks];
+
+    // Alg. 2: each party sends the mask half of the XOR sharing of its own share
+    for (int m = 0; m < n_chunks; ++m) {
+        if (hi[m] <= lo[m]) continue;
+        for (int i = 0; i < 2; ++i)
+            MPC_TRY(wire_words(c, pp[i].r, const_cast<u64*>(pp[1 - i].recv), n, lo[m], hi[m], 1, vec));
+        got[m] = next_event(c);
+        MPC_HIP(c, hipEventRecord(got[m], Wr));
+    }
+    for (int stage = 0; stage < ST_COUNT; ++stage) {
+        const int rows = words_after(stage);
+        for (int m = 0; m < n_chunks; ++m) {
+            if (hi[m] <= lo[m]) continue;
+            for (int i = 0; i < 2; ++i) {
+                MPC_HIP(c, hipStreamWaitEvent(P[i], got[m], 0));
+                if (i == 0) { if (vec) launch_stage<0, 2>(stage, P[0], pp[0], lo[m], hi[m]);
+                              else     launch_stage<0, 1>(stage, P[0], pp[0], lo[m], hi[m]); }
+                else        { if (vec) launch_stage<1, 2>(stage, P[1], pp[1], lo[m], hi[m]);
+                              else     launch_stage<1, 1>(stage, P[1], pp[1], lo[m], hi[m]); }
+                MPC_HIP(c, hipGetLastError());
+                if (rows >= 0) MPC_TRY(chain(c, P[i], Wr));
+            }
+            if (rows < 0) continue;
+            for (int i = 0; i < 2; ++i) {
+                if (rows == 0) {
+                    hipLaunchKernelGGL(k_wire_bytes, dim3(grid_for(hi[m] - lo[m])), dim3(kThreads), 0, Wr,
+                                       pp[i].sendb, const_cast<u8*>(pp[1 - i].recvb), lo[m], hi[m]);
+                    MPC_HIP(c, hipGetLastError());
+                } else {
+                    MPC_TRY(wire_words(c, pp[i].send, const_cast<u64*>(pp[1 - i].recv), n, lo[m], hi[m], rows, vec));
+                }
+            }
+            got[m] = next_event(c);
+            MPC_HIP(c, hipEventRecord(got[m], Wr));
+        }
+    }
+    return MPC_OK;
+}
+
+int check_material(const mpc_relu_material* m)
+{
+    if (!m) return MPC_EINVAL;
+    for (int i = 0; i < 2; ++i)
+        if (!m->r.p[i] || !m->and_a.p[i] || !m->and_b.p[i] || !m->and_c.p[i] || !m->rb[i] || !m->ra.p[i] ||
+            !m->ma.p[i] || !m->mb.p[i] || !m->mc.p[i])
+            return MPC_EINVAL;
+    return MPC_OK;
+}
+
+void fill_party(ReluParty& p, int i, const u64* x, const mpc_relu_material* m, const ReluWs& w, u64* y,
+                u8* s_bit, u64* s_arith, size_t n)
+{
+    p.x = x; p.r = m->r.p[i];
+    p.ta = m->and_a.p[i]; p.tb = m->and_b.p[i]; p.tc = m->and_c.p[i];
+    p.rb = m->rb[i]; p.ra = m->ra.p[i];
+    p.ma = m->ma.p[i]; p.mb = m->mb.p[i]; p.mc = m->mc.p[i];
+    p.send = w.send[i]; p.recv = w.recv[i]; p.sendb = w.sendb[i]; p.recvb = w.recvb[i];
+    p.G = w.G[i]; p.P = w.P[i]; p.p63 = w.p63[i];
+    p.y = y; p.s_bit = s_bit; p.s_arith = s_arith; p.n = n;
+}
+
+// ---- max-pool gathers (local, linear) ----------------------------------------------
+// level 1: d[2o] = p00 - p01, d[2o+1] = p10 - p11 for output index o (NHWC)
+__global__ __launch_bounds__(kThreads) void k_pool_l1(const u64* __restrict__ x, u64* __restrict__ d,
+                                                      int B, int H, int W, int C)
+{
+    const int Ho = H / 2, Wo = W / 2;
+    const size_t n_out = (size_t)B * Ho * Wo * C;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < n_out; o += stride) {
+        const int ch = (int)(o % C); size_t t = o / C;
+        const int wo = (int)(t % Wo); t /= Wo;
+        const int ho = (int)(t % Ho); const int b = (int)(t / Ho);
+        const size_t base = (((size_t)b * H + 2 * ho) * W + 2 * wo) * C + ch;
+        const size_t dw = C, dh = (size_t)W * C;
+        d[2 * o + 0] = x[base] - x[base + dw];
+        d[2 * o + 1] = x[base + dh] - x[base + dh + dw];
+    }
+}
+// level 2: u = p01 + r1[2o], v = p11 + r1[2o+1]; keep v, d2 = u - v
+__global__ __launch_bounds__(kThreads) void k_pool_l2(const u64* __restrict__ x, const u64* __restrict__ r1,
+                                                      u64* __restrict__ v_out, u64* __restrict__ d2,
+                                                      int B, int H, int W, int C)
+{
+    const int Ho = H / 2, Wo = W / 2;
+    const size_t n_out = (size_t)B * Ho * Wo * C;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < n_out; o += stride) {
+        const int ch = (int)(o % C); size_t t = o / C;
+        const int wo = (int)(t % Wo); t /= Wo;
+        const int ho = (int)(t % Ho); const int b = (int)(t / Ho);
+        const size_t base = (((size_t)b * H + 2 * ho) * W + 2 * wo) * C + ch;
+        const size_t dw = C, dh = (size_t)W * C;
+        const u64 u = x[base + dw] + r1[2 * o];
+        const u64 v = x[base + dh + dw] + r1[2 * o + 1];
+        v_out[o] = v;
+        d2[o] = u - v;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t mpc_relu_workspace_bytes(size_t n)
+{
+    if (n == 0) return 0;
+    return carve_relu(nullptr, 0, n).bytes;
+}
+
+size_t mpc_maxpool_workspace_bytes(int B, int H, int W, int C)
+{
+    if (B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1)) return 0;
+    const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
+    // per party: d1 (2 n_out), r1 (2 n_out), v (n_out), d2 (n_out); then the ReLU's own scratch
+    return 2 * (align_up(2 * n_out * 8) * 2 + align_up(n_out * 8) * 2) + carve_relu(nullptr, 0, 2 * n_out).bytes;
+}
+
+int mpc_relu(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat, mpc_share y, size_t n, int n_chunks,
+             uint8_t* const s_bit[2], uint64_t* const s_arith[2])
+{
+    if (!c || n == 0 || n_chunks < 1 || !x.p[0] || !x.p[1] || !y.p[0] || !y.p[1]) return MPC_EINVAL;
+    MPC_TRY(check_material(mat));
+    ReluWs w = carve_relu(c->ws, c->ws_bytes, n);
+    if (!w.ok) return MPC_ENOMEM;
+    MPC_TRY(lane_join(c));
+    ReluParty pp[2];
+    for (int i = 0; i < 2; ++i)
+        fill_party(pp[i], i, x.p[i], mat, w, y.p[i], s_bit ? s_bit[i] : nullptr, s_arith ? s_arith[i] : nullptr, n);
+    return relu_run(c, pp, n, n_chunks);
+}
+
+int mpc_maxpool2x2(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat1, const mpc_relu_material* mat2,
+                   mpc_share y, int B, int H, int W, int C, int n_chunks)
+{
+    if (!c || B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1) || n_chunks < 1 ||
+        !x.p[0] || !x.p[1] || !y.p[0] || !y.p[1])
+        return MPC_EINVAL;
+    MPC_TRY(check_material(mat1));
+    MPC_TRY(check_material(mat2));
+    const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
+    WsAlloc wa(c->ws, c->ws_bytes);
+    u64 *d1[2], *r1[2], *v[2], *d2[2];
+    for (int i = 0; i < 2; ++i) {
+        d1[i] = wa.take<u64>(2 * n_out); r1[i] = wa.take<u64>(2 * n_out);
+        v[i] = wa.take<u64>(n_out); d2[i] = wa.take<u64>(n_out);
+    }
+    if (!wa.ok) return MPC_ENOMEM;
+    ReluWs w = carve_relu(c->ws + wa.off, c->ws_bytes - wa.off, 2 * n_out);
+    if (!w.ok) return MPC_ENOMEM;
+    MPC_TRY(lane_join(c));
+    const dim3 grid(grid_for(n_out)), block(kThreads);
+    ReluParty pp[2];
+    // first tournament level: max(p00, p01) and max(p10, p11)
+    for (int i = 0; i < 2; ++i) {
+        hipLaunchKernelGGL(k_pool_l1, grid, block, 0, c->s[i], x.p[i], d1[i], B, H, W, C);
+        MPC_HIP(c, hipGetLastError());
+        fill_party(pp[i], i, d1[i], mat1, w, r1[i], nullptr, nullptr, 2 * n_out);
+    }
+    MPC_TRY(lane_join(c));
+    MPC_TRY(relu_run(c, pp, 2 * n_out, n_chunks));
+    // second level: max of the two winners; out = v + ReLU(u - v)
+    for (int i = 0; i < 2; ++i) {
+        hipLaunchKernelGGL(k_pool_l2, grid, block, 0, c->s[i], x.p[i], r1[i], v[i], d2[i], B, H, W, C);
+        MPC_HIP(c, hipGetLastError());
+        fill_party(pp[i], i, d2[i], mat2, w, y.p[i], nullptr, nullptr, n_out);
+    }
+    MPC_TRY(lane_join(c));
+    MPC_TRY(relu_run(c, pp, n_out, n_chunks));
+    for (int i = 0; i < 2; ++i)
+        MPC_TRY(launch_add(c, c->s[i], y.p[i], v[i], y.p[i], n_out));
+    return MPC_OK;
+}
+
+}  // extern "C"

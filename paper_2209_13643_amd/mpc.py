@@ -1,0 +1,265 @@
+"""ctypes binding over libmpcpipe (the C ABI in include/mpcpipe.h).
+
+Argument marshalling only: every protocol step runs in the library's HIP
+kernels.  torch is used for device memory (int64 tensors carry the uint64 ring
+elements bit for bit) and nothing else.  There is no CPU fallback: if the
+library is missing or the device is absent, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, byref, c_int, c_size_t, c_uint8, c_uint64, c_void_p
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmpcpipe.so")
+
+MPC_TRUNCATE = 1
+MPC_TWO_PHASE = 2
+N_AND_TRIPLES = 12
+
+_P64 = POINTER(c_uint64)
+_P8 = POINTER(c_uint8)
+
+
+class CShare(ctypes.Structure):
+    _fields_ = [("p", _P64 * 2)]
+
+
+class ReluMaterial(ctypes.Structure):
+    _fields_ = [("r", CShare), ("and_a", CShare), ("and_b", CShare), ("and_c", CShare),
+                ("rb", _P8 * 2), ("ra", CShare), ("ma", CShare), ("mb", CShare), ("mc", CShare)]
+
+
+EXPORTS = [
+    "mpc_ctx_create", "mpc_ctx_destroy", "mpc_ctx_set_streams", "mpc_ctx_stream", "mpc_ctx_set_workspace",
+    "mpc_ctx_sync", "mpc_ctx_wait", "mpc_last_hip_error", "mpc_strerror",
+    "mpc_matmul_workspace_bytes", "mpc_conv2d_workspace_bytes", "mpc_relu_workspace_bytes",
+    "mpc_maxpool_workspace_bytes", "mpc_open", "mpc_beaver_matmul", "mpc_conv2d", "mpc_truncate",
+    "mpc_relu", "mpc_maxpool2x2", "mpc_ring_matmul", "mpc_ring_conv2d",
+]
+
+_lib = None
+
+
+def lib():
+    """Load the shared library (built by __graft_entry__.build())."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+    L = ctypes.CDLL(LIB_PATH)
+    L.mpc_ctx_create.argtypes = [POINTER(c_void_p), c_int, c_int]
+    L.mpc_ctx_destroy.argtypes = [c_void_p]
+    L.mpc_ctx_set_streams.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
+    L.mpc_ctx_stream.argtypes = [c_void_p, c_int]; L.mpc_ctx_stream.restype = c_void_p
+    L.mpc_ctx_set_workspace.argtypes = [c_void_p, c_void_p, c_size_t]
+    L.mpc_ctx_sync.argtypes = [c_void_p]
+    L.mpc_ctx_wait.argtypes = [c_void_p, c_void_p]
+    L.mpc_last_hip_error.argtypes = [c_void_p]
+    L.mpc_strerror.argtypes = [c_int]; L.mpc_strerror.restype = ctypes.c_char_p
+    L.mpc_matmul_workspace_bytes.argtypes = [c_int] * 4; L.mpc_matmul_workspace_bytes.restype = c_size_t
+    L.mpc_conv2d_workspace_bytes.argtypes = [c_int] * 9; L.mpc_conv2d_workspace_bytes.restype = c_size_t
+    L.mpc_relu_workspace_bytes.argtypes = [c_size_t]; L.mpc_relu_workspace_bytes.restype = c_size_t
+    L.mpc_maxpool_workspace_bytes.argtypes = [c_int] * 4; L.mpc_maxpool_workspace_bytes.restype = c_size_t
+    L.mpc_open.argtypes = [c_void_p, CShare, _P64, c_size_t]
+    L.mpc_beaver_matmul.argtypes = [c_void_p] + [CShare] * 6 + [c_int] * 4 + [_P64, c_int, c_int]
+    L.mpc_conv2d.argtypes = [c_void_p] + [CShare] * 6 + [c_int] * 9 + [_P64, c_int, c_int]
+    L.mpc_truncate.argtypes = [c_void_p, CShare, c_size_t, c_int]
+    L.mpc_relu.argtypes = [c_void_p, CShare, POINTER(ReluMaterial), CShare, c_size_t, c_int,
+                           POINTER(_P8 * 2), POINTER(_P64 * 2)]
+    L.mpc_maxpool2x2.argtypes = [c_void_p, CShare, POINTER(ReluMaterial), POINTER(ReluMaterial), CShare,
+                                 c_int, c_int, c_int, c_int, c_int]
+    L.mpc_ring_matmul.argtypes = [c_void_p, _P64, _P64, _P64] + [c_int] * 4
+    L.mpc_ring_conv2d.argtypes = [c_void_p, _P64, _P64, _P64] + [c_int] * 9
+    _lib = L
+    return L
+
+
+class MpcError(RuntimeError):
+    pass
+
+
+def _p64(t):
+    if t is None:
+        return ctypes.cast(None, _P64)
+    assert t.is_cuda and t.is_contiguous() and t.dtype == torch.int64, "int64 contiguous device tensor expected"
+    return ctypes.cast(t.data_ptr(), _P64)
+
+
+def _p8(t):
+    if t is None:
+        return ctypes.cast(None, _P8)
+    assert t.is_cuda and t.is_contiguous() and t.dtype == torch.uint8
+    return ctypes.cast(t.data_ptr(), _P8)
+
+
+def _share(pair):
+    s = CShare()
+    if pair is None:
+        pair = (None, None)
+    s.p[0], s.p[1] = _p64(pair[0]), _p64(pair[1])
+    return s
+
+
+def to_device(arr, device="cuda:0"):
+    """numpy uint64 / uint8 array -> device tensor with the same bits."""
+    import numpy as np
+    a = np.ascontiguousarray(arr)
+    if a.dtype == np.uint64:
+        a = a.view(np.int64)
+    return torch.from_numpy(a).to(device)
+
+
+def to_host(t):
+    """device int64 tensor -> numpy uint64 (uint8 stays uint8)."""
+    import numpy as np
+    a = t.cpu().numpy()
+    return a.view(np.uint64) if a.dtype == np.int64 else a
+
+
+def material_to_device(mat: dict, device="cuda:0") -> dict:
+    return {k: (to_device(v[0], device), to_device(v[1], device)) for k, v in mat.items()}
+
+
+def _material(mat: dict, n: int) -> ReluMaterial:
+    m = ReluMaterial()
+    for key in ("r", "ra", "ma", "mb", "mc"):
+        assert mat[key][0].numel() == n and mat[key][1].numel() == n, key
+        setattr(m, key, _share(mat[key]))
+    for key in ("and_a", "and_b", "and_c"):
+        assert mat[key][0].numel() == N_AND_TRIPLES * n and mat[key][1].numel() == N_AND_TRIPLES * n, key
+        setattr(m, key, _share(mat[key]))
+    assert mat["rb"][0].numel() == n and mat["rb"][1].numel() == n
+    m.rb[0], m.rb[1] = _p8(mat["rb"][0]), _p8(mat["rb"][1])
+    return m
+
+
+class Lane:
+    """One execution lane: a library context plus a grow-only workspace."""
+
+    def __init__(self, device: int = 0, frac_bits: int = 16):
+        if not torch.cuda.is_available():
+            raise RuntimeError("mpcpipe needs a GPU: no HIP device is visible")
+        self.device = torch.device("cuda", device)
+        self._h = c_void_p()
+        self._check(lib().mpc_ctx_create(byref(self._h), device, frac_bits))
+        self._ws = None
+
+    # -- plumbing
+    def _check(self, rc: int):
+        if rc != 0:
+            msg = lib().mpc_strerror(rc).decode()
+            hip = lib().mpc_last_hip_error(self._h) if self._h else 0
+            raise MpcError(f"mpcpipe error {rc}: {msg}" + (f" (hipError {hip})" if rc == -3 else ""))
+
+    def close(self):
+        if self._h:
+            lib().mpc_ctx_destroy(self._h)
+            self._h = c_void_p()
+            self._ws = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def sync(self):
+        self._check(lib().mpc_ctx_sync(self._h))
+
+    def wait_for(self, other: "Lane"):
+        self._check(lib().mpc_ctx_wait(self._h, other._h))
+
+    def stream(self, which: int) -> int:
+        return lib().mpc_ctx_stream(self._h, which) or 0
+
+    def reserve(self, nbytes: int):
+        """Make the workspace at least nbytes large (syncs the lane if it has to grow)."""
+        if nbytes <= 0:
+            raise MpcError("workspace query rejected the shape")
+        if self._ws is None or self._ws.numel() < nbytes:
+            if self._ws is not None:
+                self.sync()
+            self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+            base = self._ws.data_ptr()
+            off = (-base) % 256
+            self._check(lib().mpc_ctx_set_workspace(self._h, c_void_p(base + off), nbytes))
+
+    # -- protocol calls
+    def open(self, s):
+        n = s[0].numel()
+        self.reserve(2 * (n * 8 + 256))
+        out = torch.empty_like(s[0])
+        self._check(lib().mpc_open(self._h, _share(s), _p64(out), n))
+        return out
+
+    def beaver_matmul(self, x, y, a, b, c, f_public=None, n_chunks=1, flags=MPC_TRUNCATE, out=None):
+        shp = a[0].shape
+        batch = 1 if len(shp) == 2 else shp[0]
+        M, K = shp[-2], shp[-1]
+        N = b[0].shape[-1]
+        assert b[0].shape[-2] == K and c[0].shape[-2:] == (M, N)
+        self.reserve(lib().mpc_matmul_workspace_bytes(M, K, N, batch))
+        z = out if out is not None else (torch.empty_like(c[0]), torch.empty_like(c[1]))
+        self._check(lib().mpc_beaver_matmul(self._h, _share(x), _share(y), _share(a), _share(b), _share(c),
+                                            _share(z), M, K, N, batch, _p64(f_public), n_chunks, flags))
+        return z
+
+    def conv2d(self, x, w, a, b, c, pad, stride, f_public=None, n_chunks=1, flags=MPC_TRUNCATE, out=None):
+        B, H, W, Cin = a[0].shape
+        KH, KW, Cin2, Cout = b[0].shape
+        assert Cin == Cin2
+        self.reserve(lib().mpc_conv2d_workspace_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride))
+        z = out if out is not None else (torch.empty_like(c[0]), torch.empty_like(c[1]))
+        self._check(lib().mpc_conv2d(self._h, _share(x), _share(w), _share(a), _share(b), _share(c), _share(z),
+                                     B, H, W, Cin, Cout, KH, KW, pad, stride, _p64(f_public), n_chunks, flags))
+        return z
+
+    def truncate(self, z, bits=16):
+        self._check(lib().mpc_truncate(self._h, _share(z), z[0].numel(), bits))
+        return z
+
+    def relu(self, x, mat, n_chunks=1, want_sign=False, out=None):
+        n = x[0].numel()
+        self.reserve(lib().mpc_relu_workspace_bytes(n))
+        y = out if out is not None else (torch.empty_like(x[0]), torch.empty_like(x[1]))
+        m = _material(mat, n)
+        if want_sign:
+            sb = tuple(torch.empty(n, dtype=torch.uint8, device=self.device) for _ in range(2))
+            sa = tuple(torch.empty(n, dtype=torch.int64, device=self.device) for _ in range(2))
+            sbp = (_P8 * 2)(_p8(sb[0]), _p8(sb[1])); sap = (_P64 * 2)(_p64(sa[0]), _p64(sa[1]))
+            self._check(lib().mpc_relu(self._h, _share(x), byref(m), _share(y), n, n_chunks, byref(sbp), byref(sap)))
+            return y, sb, sa
+        self._check(lib().mpc_relu(self._h, _share(x), byref(m), _share(y), n, n_chunks, None, None))
+        return y
+
+    def maxpool2x2(self, x, mat1, mat2, n_chunks=1):
+        B, H, W, C = x[0].shape
+        n_out = B * (H // 2) * (W // 2) * C
+        self.reserve(lib().mpc_maxpool_workspace_bytes(B, H, W, C))
+        y = tuple(torch.empty((B, H // 2, W // 2, C), dtype=torch.int64, device=self.device) for _ in range(2))
+        m1, m2 = _material(mat1, 2 * n_out), _material(mat2, n_out)
+        self._check(lib().mpc_maxpool2x2(self._h, _share(x), byref(m1), byref(m2), _share(y), B, H, W, C, n_chunks))
+        return y
+
+    # -- dealer helpers (offline phase stand-in)
+    def ring_matmul(self, L, R):
+        shp = L.shape
+        batch = 1 if len(shp) == 2 else shp[0]
+        M, K = shp[-2], shp[-1]; N = R.shape[-1]
+        self.reserve(lib().mpc_matmul_workspace_bytes(M, K, N, batch))
+        Z = torch.empty(shp[:-1] + (N,), dtype=torch.int64, device=self.device)
+        self._check(lib().mpc_ring_matmul(self._h, _p64(L), _p64(R), _p64(Z), M, K, N, batch))
+        return Z
+
+    def ring_conv2d(self, x, w, pad, stride):
+        B, H, W, Cin = x.shape; KH, KW, _, Cout = w.shape
+        Ho = (H + 2 * pad - KH) // stride + 1; Wo = (W + 2 * pad - KW) // stride + 1
+        self.reserve(lib().mpc_conv2d_workspace_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride))
+        z = torch.empty((B, Ho, Wo, Cout), dtype=torch.int64, device=self.device)
+        self._check(lib().mpc_ring_conv2d(self._h, _p64(x), _p64(w), _p64(z), B, H, W, Cin, Cout, KH, KW, pad, stride))
+        return z

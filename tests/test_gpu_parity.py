@@ -1,0 +1,251 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on the same seeded inputs.  Shares must agree bit for bit; decoded fixed-point
+results must be within 2^-12 of float64 on the decoded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import deal_conv, deal_matmul, oracle_conv, oracle_matmul, rec
+from paper_2209_13643_amd import synth
+
+pytestmark = pytest.mark.gpu
+U64 = np.uint64
+TOL = 2.0 ** -12
+
+
+@pytest.fixture(scope="module")
+def mpc():
+    from paper_2209_13643_amd import mpc as m
+    return m
+
+
+@pytest.fixture()
+def lane(mpc):
+    ln = mpc.Lane(0)
+    yield ln
+    ln.sync()
+    ln.close()
+
+
+def dev(mpc, pair):
+    return (mpc.to_device(pair[0]), mpc.to_device(pair[1]))
+
+
+def host(mpc, lane, pair):
+    lane.sync()
+    return (mpc.to_host(pair[0]), mpc.to_host(pair[1]))
+
+
+def assert_shares_equal(got, want, what=""):
+    for i in range(2):
+        g = np.asarray(got[i]).reshape(np.shape(want[i]))
+        if not np.array_equal(g, want[i]):
+            bad = np.argwhere(g != want[i])
+            raise AssertionError(f"{what}: party {i} differs at {len(bad)} of {g.size} elements, first {bad[0]}: "
+                                 f"got {int(g[tuple(bad[0])]):#x} want {int(want[i][tuple(bad[0])]):#x}")
+
+
+# ------------------------------------------------------------------- element-wise
+@pytest.mark.parametrize("n", [1, 2, 255, 4097, 1 << 20])
+def test_open_and_truncate(mpc, lane, n):
+    print(f"open/truncate n={n}", flush=True)
+    rng = np.random.default_rng(n)
+    s = (synth.rand_words(rng, n), synth.rand_words(rng, n))
+    out = lane.open(dev(mpc, s))
+    lane.sync()
+    assert np.array_equal(mpc.to_host(out), oracle.open_shares(*s))
+    z = dev(mpc, s)
+    lane.truncate(z, 16)
+    assert_shares_equal(host(mpc, lane, z), oracle.truncate(s, 16), "truncate")
+
+
+# ------------------------------------------------------------------ plain ring GEMM
+RING_SHAPES = [(1, 1, 1), (5, 3, 2), (32, 32, 32), (33, 17, 65), (70, 100, 150), (300, 257, 90), (128, 2304, 64)]
+
+
+@pytest.mark.parametrize("shape", RING_SHAPES)
+def test_ring_matmul(mpc, lane, shape):
+    M, K, N = shape
+    print(f"ring_matmul {shape}", flush=True)
+    rng = np.random.default_rng(M * 7 + K)
+    L, R = synth.rand_words(rng, (M, K)), synth.rand_words(rng, (K, N))
+    Z = lane.ring_matmul(mpc.to_device(L), mpc.to_device(R))
+    lane.sync()
+    assert np.array_equal(mpc.to_host(Z), oracle.ring_matmul(L, R))
+
+
+def test_ring_matmul_extreme_digits(mpc, lane):
+    """Operands whose balanced digits are all -128 / 127 / carries: the int32
+    digit sums are at their largest magnitude."""
+    print("ring_matmul extreme digits", flush=True)
+    M, K, N = 64, 4608, 64
+    pats = np.array([0x8080808080808080, 0x7F7F7F7F7F7F7F7F, 0xFFFFFFFFFFFFFFFF, 0x80, 0x8000000000000000],
+                    dtype=U64)
+    rng = np.random.default_rng(5)
+    L = pats[rng.integers(0, 2, size=(M, K))]            # only the two extreme patterns
+    R = pats[rng.integers(0, 2, size=(K, N))]
+    L[::3] = pats[0]; R[:, ::2] = pats[0]                # rows/columns of all -128 digits
+    Z = lane.ring_matmul(mpc.to_device(L), mpc.to_device(R))
+    lane.sync()
+    assert np.array_equal(mpc.to_host(Z), oracle.ring_matmul(L, R))
+
+
+def test_ring_matmul_batched(mpc, lane):
+    print("ring_matmul batched", flush=True)
+    rng = np.random.default_rng(6)
+    L, R = synth.rand_words(rng, (5, 40, 64)), synth.rand_words(rng, (5, 64, 48))
+    Z = lane.ring_matmul(mpc.to_device(L), mpc.to_device(R))
+    lane.sync()
+    want = np.stack([oracle.ring_matmul(L[i], R[i]) for i in range(5)])
+    assert np.array_equal(mpc.to_host(Z), want)
+
+
+# ------------------------------------------------------------- Beaver matmul (Alg. 1)
+BEAVER_SHAPES = [(1, 1, 1), (7, 5, 3), (64, 256, 128), (130, 70, 67), (257, 48, 200)]
+
+
+@pytest.mark.parametrize("shape", BEAVER_SHAPES)
+@pytest.mark.parametrize("trunc", [True, False])
+def test_beaver_matmul(mpc, lane, shape, trunc):
+    M, K, N = shape
+    print(f"beaver_matmul {shape} trunc={trunc}", flush=True)
+    d = deal_matmul(np.random.default_rng(M + K + N), M, K, N)
+    z = lane.beaver_matmul(dev(mpc, d["x"]), dev(mpc, d["y"]), dev(mpc, d["a"]), dev(mpc, d["b"]),
+                           dev(mpc, d["c"]), flags=mpc.MPC_TRUNCATE if trunc else 0)
+    assert_shares_equal(host(mpc, lane, z), oracle_matmul(d, 16 if trunc else 0), "beaver_matmul")
+
+
+def test_beaver_matmul_batched(mpc, lane):
+    print("beaver_matmul batched", flush=True)
+    d = deal_matmul(np.random.default_rng(77), 48, 64, 40, batch=6)
+    z = lane.beaver_matmul(dev(mpc, d["x"]), dev(mpc, d["y"]), dev(mpc, d["a"]), dev(mpc, d["b"]), dev(mpc, d["c"]))
+    assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "batched")
+
+
+@pytest.mark.parametrize("n_chunks", [1, 2, 4, 8])
+@pytest.mark.parametrize("mode", ["in-call", "pre-opened", "two-phase"])
+def test_beaver_matmul_schedule_invariance(mpc, lane, n_chunks, mode):
+    """Chunked openings, a pre-opened weight mask and the Alg. 3 ordering all
+    give the shares of the plain Alg. 1 run (Sec. 5.10)."""
+    print(f"schedule invariance chunks={n_chunks} mode={mode}", flush=True)
+    d = deal_matmul(np.random.default_rng(88), 150, 96, 70)
+    f_pub = None
+    y = dev(mpc, d["y"])
+    flags = mpc.MPC_TRUNCATE
+    if mode != "in-call":
+        f_pub = mpc.to_device((d["y"][0] - d["b"][0]) + (d["y"][1] - d["b"][1]))
+        y = None
+    if mode == "two-phase":
+        flags |= mpc.MPC_TWO_PHASE
+    z = lane.beaver_matmul(dev(mpc, d["x"]), y, dev(mpc, d["a"]), dev(mpc, d["b"]), dev(mpc, d["c"]),
+                           f_public=f_pub, n_chunks=n_chunks, flags=flags)
+    assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "schedule")
+
+
+# ---------------------------------------------------------------------- conv (Eq. 3)
+CONV_CASES = [  # B,H,W,Cin,Cout,KH,KW,pad,stride
+    (1, 3, 3, 1, 1, 3, 3, 1, 1), (2, 8, 8, 3, 16, 3, 3, 1, 1), (2, 9, 7, 20, 24, 3, 3, 1, 1),
+    (1, 12, 12, 16, 8, 3, 3, 0, 2), (3, 10, 10, 32, 40, 1, 1, 0, 1), (2, 11, 9, 5, 7, 3, 3, 1, 2),
+    (4, 16, 16, 64, 64, 3, 3, 1, 1)]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv2d(mpc, lane, case):
+    print(f"conv2d {case}", flush=True)
+    d = deal_conv(np.random.default_rng(sum(case)), *case)
+    z = lane.conv2d(dev(mpc, d["x"]), dev(mpc, d["y"]), dev(mpc, d["a"]), dev(mpc, d["b"]), dev(mpc, d["c"]),
+                    d["pad"], d["stride"])
+    assert_shares_equal(host(mpc, lane, z), oracle_conv(d), "conv2d")
+
+
+def test_ring_conv2d(mpc, lane):
+    print("ring_conv2d", flush=True)
+    rng = np.random.default_rng(9)
+    x, w = synth.rand_words(rng, (2, 9, 8, 19)), synth.rand_words(rng, (3, 3, 19, 33))
+    z = lane.ring_conv2d(mpc.to_device(x), mpc.to_device(w), 1, 1)
+    lane.sync()
+    assert np.array_equal(mpc.to_host(z), oracle.ring_conv2d(x, w, 1, 1))
+
+
+# ---------------------------------------------------------------------------- ReLU
+@pytest.mark.parametrize("n", [1, 2, 63, 1000, 4097, 70000])
+@pytest.mark.parametrize("n_chunks", [1, 3])
+def test_relu(mpc, lane, n, n_chunks):
+    print(f"relu n={n} chunks={n_chunks}", flush=True)
+    rng = np.random.default_rng(n + n_chunks)
+    X = rng.integers(-(1 << 40), 1 << 40, size=n).astype(np.int64).view(U64)
+    X[: min(n, 9)] = np.array([0, 1, -1, 1 << 62, -(1 << 63), (1 << 63) - 1, -65536, 65536, 5],
+                              dtype=np.int64).view(U64)[: min(n, 9)]
+    xs = synth.share_additive(rng, X)
+    mat = synth.deal_relu_material(rng, n)
+    want = oracle.relu(xs, mat)
+    y, sb, sa = lane.relu(dev(mpc, xs), mpc.material_to_device(mat), n_chunks=n_chunks, want_sign=True)
+    lane.sync()
+    assert_shares_equal((mpc.to_host(sb[0]), mpc.to_host(sb[1])), want.s_bit, "sign bit share")
+    assert_shares_equal((mpc.to_host(sa[0]), mpc.to_host(sa[1])), want.s_arith, "sign arithmetic share")
+    got = (mpc.to_host(y[0]), mpc.to_host(y[1]))
+    assert_shares_equal(got, want.y, "relu output")
+    assert np.array_equal(rec(got).view(np.int64), np.maximum(X.view(np.int64), 0))
+
+
+def test_relu_exhaustive_small_magnitude(mpc, lane):
+    print("relu exhaustive", flush=True)
+    rng = np.random.default_rng(123)
+    vals = np.arange(-4096, 4097, dtype=np.int64)
+    for x0 in (None, 0, 1 << 63, (1 << 64) - 1):
+        X = vals.view(U64)
+        xs = synth.share_additive(rng, X) if x0 is None else (np.full(X.shape, x0, U64), X - np.full(X.shape, x0, U64))
+        mat = synth.deal_relu_material(rng, X.size)
+        y = lane.relu(dev(mpc, xs), mpc.material_to_device(mat))
+        got = host(mpc, lane, y)
+        assert_shares_equal(got, oracle.relu(xs, mat).y, "relu")
+        assert np.array_equal(rec(got).view(np.int64), np.maximum(vals, 0))
+
+
+@pytest.mark.parametrize("n_chunks", [1, 2, 4, 8, 16])
+def test_relu_chunk_invariance(mpc, lane, n_chunks):
+    print(f"relu chunk invariance {n_chunks}", flush=True)
+    rng = np.random.default_rng(321)
+    n = 50000
+    xs = (synth.rand_words(rng, n), synth.rand_words(rng, n))
+    mat = synth.deal_relu_material(rng, n)
+    y = lane.relu(dev(mpc, xs), mpc.material_to_device(mat), n_chunks=n_chunks)
+    assert_shares_equal(host(mpc, lane, y), oracle.relu(xs, mat).y, "relu chunks")
+
+
+@pytest.mark.parametrize("shape", [(1, 2, 2, 1), (2, 6, 4, 3), (3, 8, 8, 16)])
+def test_maxpool(mpc, lane, shape):
+    print(f"maxpool {shape}", flush=True)
+    B, H, W, C = shape
+    rng = np.random.default_rng(sum(shape))
+    X = rng.integers(-(1 << 30), 1 << 30, size=shape).astype(np.int64)
+    xs = synth.share_additive(rng, X.view(U64))
+    n_out = B * (H // 2) * (W // 2) * C
+    m1, m2 = synth.deal_relu_material(rng, 2 * n_out), synth.deal_relu_material(rng, n_out)
+    y = lane.maxpool2x2(dev(mpc, xs), mpc.material_to_device(m1), mpc.material_to_device(m2))
+    got = host(mpc, lane, y)
+    assert_shares_equal(got, oracle.maxpool2x2(xs, m1, m2), "maxpool")
+    assert np.array_equal(rec(got).view(np.int64), X.reshape(B, H // 2, 2, W // 2, 2, C).max(axis=(2, 4)))
+
+
+# ------------------------------------------------------------------ error handling
+def test_argument_errors(mpc, lane):
+    print("argument errors", flush=True)
+    import torch
+    t = torch.zeros(16, dtype=torch.int64, device="cuda:0")
+    pair = (t, t)
+    L = mpc.lib()
+    sh = mpc._share(pair)
+    null = mpc._share(None)
+    h = lane._h
+    lane.reserve(1 << 20)
+    assert L.mpc_open(h, null, mpc._p64(t), 16) == -1
+    assert L.mpc_open(h, sh, mpc._p64(t), 0) == -1
+    assert L.mpc_beaver_matmul(h, sh, sh, sh, sh, sh, sh, 0, 4, 4, 1, None, 1, 0) == -1
+    assert L.mpc_beaver_matmul(h, sh, sh, sh, sh, sh, sh, 4, 4, 4, 1, None, 0, 0) == -1
+    assert L.mpc_beaver_matmul(h, sh, null, sh, sh, sh, sh, 4, 2, 2, 1, None, 1, 0) == -1   # no y and no f_public
+    assert L.mpc_beaver_matmul(h, sh, sh, sh, sh, sh, sh, 4, 20000, 4, 1, None, 1, 0) == -4  # K too long
+    assert L.mpc_beaver_matmul(h, sh, sh, sh, sh, sh, sh, 4096, 4096, 4096, 1, None, 1, 0) == -2  # workspace
+    assert L.mpc_truncate(h, sh, 16, 64) == -1
+    assert L.mpc_relu(h, sh, None, sh, 16, 1, None, None) == -1
+    lane.sync()
