@@ -114,6 +114,7 @@ struct RecodeArgs {
     const u64* src3;
     u8* dst;              // plane base
     long long row_stride, k_stride, tap_stride;
+    int plane_rows;       // rows of the plane tensor (>= rows); rows beyond `rows` are zero-filled
     int rows, K;          // valid extent per tap
     int KB_tap;           // k-blocks per tap (ceil(K/16))
     int ntaps;            // filter taps (1 for a plain matrix)

@@ -100,18 +100,18 @@ __global__ __launch_bounds__(kThreads) void k_recode(RecodeArgs a)
     u8* dst = a.dst + (size_t)b * a.dst_batch_stride;
     const bool padtap = tap >= a.ntaps;
     const int kb_count = padtap ? a.KB_total - a.ntaps * a.KB_tap : a.KB_tap;
-    const size_t items = (size_t)kb_count * a.rows;
+    const size_t items = (size_t)kb_count * a.plane_rows;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t it = (size_t)blockIdx.x * blockDim.x + threadIdx.x; it < items; it += stride) {
-        const int kbl = (int)(it / a.rows);
-        const int row = (int)(it - (size_t)kbl * a.rows);
+        const int kbl = (int)(it / a.plane_rows);
+        const int row = (int)(it - (size_t)kbl * a.plane_rows);
         const int kb_out = (padtap ? a.ntaps * a.KB_tap : tap * a.KB_tap) + kbl;
         u64 dg[16];
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
             const int k = kbl * 16 + t;
             u64 v = 0;
-            if (!padtap && k < a.K) {
+            if (!padtap && k < a.K && row < a.rows) {
                 const size_t idx = (size_t)row * a.row_stride + (size_t)k * a.k_stride + (size_t)tap * a.tap_stride;
                 v = src[idx];
                 if (src2) v += src2[idx];
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void k_recode(RecodeArgs a)
             }
             dg[t] = balanced_digits(v);
         }
-        u8* out = dst + ((size_t)kb_out * a.rows + row) * 16;
+        u8* out = dst + ((size_t)kb_out * a.plane_rows + row) * 16;
 #pragma unroll
         for (int d = 0; d < 8; ++d) {
             uint32_t w[4];
@@ -197,7 +197,7 @@ int launch_truncate(mpc_ctx* c, hipStream_t st, u64* z, size_t n, int bits, int 
 int launch_recode(mpc_ctx* c, hipStream_t st, const RecodeArgs& a)
 {
     const bool has_pad = a.KB_total > a.ntaps * a.KB_tap;
-    const size_t items = (size_t)a.KB_tap * a.rows;
+    const size_t items = (size_t)a.KB_tap * a.plane_rows;
     dim3 grid(grid_for(items), a.ntaps + (has_pad ? 1 : 0), a.batch);
     hipLaunchKernelGGL(k_recode, grid, dim3(kThreads), 0, st, a);
     MPC_HIP(c, hipGetLastError());

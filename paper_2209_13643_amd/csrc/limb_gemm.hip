@@ -8,17 +8,29 @@
 // recombines sum_s acc_s * 2^(8s) mod 2^64, adds the party's addend (c_i or a
 // partial sum), optionally truncates, and stores.
 //
-// Each wave owns a 32x32 output tile = 8 digit-sum groups x 16 accumulator
-// registers, and issues 36 v_mfma_i32_32x32x32_i8 per 32-deep K step.  A
-// workgroup of WGM x WGN waves stages the eight digit planes of its
-// (32*WGM) x 32 left tile and 32 x (32*WGN) right tile through LDS, double
-// buffered; the planes' [kb][row][16] layout makes both the global reads and
-// the ds_read_b128 operand fetches contiguous in lane order.
+// One wave per SIMD, the whole register file per wave: a wave owns a 32x64
+// output tile = 2 x 8 digit-sum groups x 16 accumulator registers (256 AGPRs)
+// and issues 72 v_mfma_i32_32x32x32_i8 per 32-deep K step.  A workgroup of
+// WGM x WGN waves streams the eight digit planes of its (32*WGM)-row left tile
+// and (64*WGN)-row right tile through a three-slot LDS ring filled by direct
+// global->LDS loads (no staging registers).  Every load is "scalar base +
+// per-lane constant offset": the lane offsets are fixed for the whole kernel
+// and the bases advance with scalar arithmetic, so the loader costs almost no
+// vector ALU work.  Inside a K step an operand register is refilled from the
+// next ring slot right after its last use, and the global loads for step t+3
+// are issued in the same MFMA shadow.  The planes' [kb][row][16] layout makes
+// the global reads and the ds_read_b128 operand fetches contiguous in lane
+// order.
 //
 // The contraction may run over two operand segments (party i contracts
 // [e | a_i] against [b_i' ; f]) and, for convolutions, the left tile loader
-// gathers filter taps from NHWC activation planes (implicit im2col).
+// gathers filter taps from NHWC activation planes (implicit im2col); taps
+// that fall into the zero padding read the all-zero row that ends every
+// activation plane.
 #include "common.h"
+
+#include <type_traits>
+#include <utility>
 
 namespace {
 
@@ -26,50 +38,87 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int KS = 2;   // 16-wide k blocks per pipeline stage = one MFMA K step
+constexpr int NS = 3;   // LDS ring depth
 
 template <int WGM, int WGN>
 struct Cfg {
-    static constexpr int TM = 32 * WGM, TN = 32 * WGN, NW = WGM * WGN, NT = 64 * NW;
+    static constexpr int TM = 32 * WGM, TN = 64 * WGN, NW = WGM * WGN, NT = 64 * NW;
     static constexpr int L_UNITS = 8 * KS * TM, R_UNITS = 8 * KS * TN;   // 16-byte units per stage
-    static constexpr int LI = L_UNITS / NT, RI = R_UNITS / NT;           // units per thread
     static constexpr int STAGE_UNITS = L_UNITS + R_UNITS;
-    static constexpr size_t LDS_BYTES = 2 * (size_t)STAGE_UNITS * 16;
-    static_assert(NT % TM == 0 && NT % TN == 0, "a thread keeps one row for all its units");
-    static_assert(L_UNITS % NT == 0 && R_UNITS % NT == 0, "units divide evenly");
+    static constexpr size_t LDS_BYTES = (size_t)NS * STAGE_UNITS * 16;
+    // Tiles are loaded in chunks of 64 rows x 16 bytes (one wave-wide load).
+    // Wave w loads digits w, w+NW, ... (DPW of them) of every k block and row
+    // chunk: load j <-> digit w + NW*(j % DPW), k block (j / DPW) % KS,
+    // row chunk j / (DPW * KS).
+    static constexpr int RCM = TM / 64, RCN = TN / 64;
+    static constexpr int DPW = 8 / NW;
+    static constexpr int LPW = DPW * KS * RCM, RPW = DPW * KS * RCN;     // loads per wave per stage
+    static_assert(TM % 64 == 0, "left tile is a whole number of 64-row chunks");
+    static_assert(8 % NW == 0, "digits divide evenly over waves");
 };
 
-// Byte offset of the 16-byte unit (row-of-thread, k block kb) inside one digit
-// plane of the left operand, or -1 for a zero unit (conv padding / pad taps).
-struct LeftRow {
-    long long base;      // plain: clamped row; conv: pixel index of tap (0,0), may be negative
-    unsigned long long valid;   // conv: bit per tap
-};
+template <typename F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
-template <int WGM, int WGN>
-__global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 8) ? 1 : 2)
+// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding)
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+
+// One wave-wide direct global->LDS load: lane l's 16 bytes at base + voff(l)
+// land at lds_slot + LDS_OFF + 16*l.  Issued through inline assembly so that
+// completion is tracked by this kernel's own vmcnt waits (see the main loop).
+template <int LDS_OFF>
+__device__ __forceinline__ void load_lds16(const u8* base, unsigned voff, unsigned lds_slot)
+{
+    asm volatile("s_add_u32 m0, %0, %1\n\tglobal_load_lds_dwordx4 %2, %3"
+                 :: "s"(lds_slot), "n"(LDS_OFF), "v"(voff), "s"(base) : "memory", "scc");
+}
+
+template <int WGM, int WGN, bool CONV>
+__global__ __launch_bounds__(64 * WGM * WGN, 1)
 void k_limb_gemm(GemmArgs g)
 {
     using C = Cfg<WGM, WGN>;
     extern __shared__ uint4 lds[];
+    const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WGM, wn = wave / WGM;
     const int i32 = lane & 31, g2 = lane >> 5;
     const int party = blockIdx.z % g.nparty;
     const int bidx = blockIdx.z / g.nparty;
     const int m0 = blockIdx.x * C::TM, n0 = blockIdx.y * C::TN;
 
-    // ---- loader geometry: this thread's row in the left / right tiles
-    const int lrow = tid % C::TM, lq = tid / C::TM;     // unit j: q = lq + j * (NT/TM)
-    const int rrow = tid % C::TN, rq = tid / C::TN;
-    LeftRow lr;
-    {
-        int m = m0 + lrow; if (m > g.M - 1) m = g.M - 1;
-        if (g.conv.enabled) {
+    // ---- per-party operands as scalars
+    const GemmSeg& sg0 = party ? g.seg[1][0] : g.seg[0][0];
+    const GemmSeg& sg1 = party ? g.seg[1][1] : g.seg[0][1];
+    const int KB0 = sg0.KB, KB1 = g.nseg > 1 ? sg1.KB : 0;
+    const int T = (KB0 + KB1) / KS;
+    const long long krowL = (long long)g.rows_L * 16;      // bytes between k blocks of a left plane
+    const long long krowR = (long long)g.N * 16;
+
+    // ---- per-lane constant byte offsets
+    // conv: pixel index of filter tap (0,0), biased so that it is never negative
+    const int bias = CONV ? g.conv.pad * g.conv.W + g.conv.pad : 0;
+    unsigned voffL[C::RCM];
+    unsigned long long lvalid[C::RCM];      // conv: bit per filter tap that hits the image
+#pragma unroll
+    for (int rc = 0; rc < C::RCM; ++rc) {
+        int m = m0 + rc * 64 + lane; if (m > g.M - 1) m = g.M - 1;
+        if (CONV) {
             const int wo = m % g.conv.Wo; const int t = m / g.conv.Wo;
             const int ho = t % g.conv.Ho; const int b = t / g.conv.Ho;
             const int hi0 = ho * g.conv.stride - g.conv.pad, wi0 = wo * g.conv.stride - g.conv.pad;
-            lr.base = ((long long)b * g.conv.H + hi0) * g.conv.W + wi0;
+            const long long pix00 = ((long long)b * g.conv.H + hi0) * g.conv.W + wi0;
+            voffL[rc] = (unsigned)((pix00 + bias) * 16);
             unsigned long long v = 0;
             for (int kh = 0; kh < g.conv.KH; ++kh)
                 for (int kw = 0; kw < g.conv.KW; ++kw) {
@@ -77,130 +126,208 @@ void k_limb_gemm(GemmArgs g)
                     if (hi >= 0 && hi < g.conv.H && wi >= 0 && wi < g.conv.W)
                         v |= 1ull << (kh * g.conv.KW + kw);
                 }
-            lr.valid = v;
+            lvalid[rc] = v;
         } else {
-            lr.base = m; lr.valid = ~0ull;
+            voffL[rc] = (unsigned)m * 16u; lvalid[rc] = ~0ull;
         }
     }
-    int nrow = n0 + rrow; if (nrow > g.N - 1) nrow = g.N - 1;
-
-    uint4 stL[C::LI], stR[C::RI];
-
-    auto load_stage = [&](int seg, int kb0) {
-        const GemmSeg& s = g.seg[party][seg];
-        const u8* Lb = s.L + (size_t)bidx * s.L_bstride;
-        const u8* Rb = s.R + (size_t)bidx * s.R_bstride;
+    unsigned voffR[C::RCN];
 #pragma unroll
-        for (int j = 0; j < C::LI; ++j) {
-            const int q = lq + j * (C::NT / C::TM);
-            const int kk = q % KS, d = q / KS;
-            const int kb = kb0 + kk;
-            const u8* p;
-            if (g.conv.enabled) {
-                const int tap = kb / g.conv.CB, cb = kb - tap * g.conv.CB;
-                const bool ok = tap < g.conv.KH * g.conv.KW && ((lr.valid >> tap) & 1);
-                const int kh = tap / g.conv.KW, kw = tap - kh * g.conv.KW;
-                const long long pix = lr.base + (long long)kh * g.conv.W + kw;
-                p = ok ? Lb + (size_t)d * s.L_dstride + ((size_t)cb * g.conv.npix + (size_t)pix) * 16
-                       : g.zero16;
-            } else {
-                p = Lb + (size_t)d * s.L_dstride + ((size_t)kb * g.rows_L + (size_t)lr.base) * 16;
+    for (int rc = 0; rc < C::RCN; ++rc) {
+        int n = n0 + rc * 64 + lane; if (n > g.N - 1) n = g.N - 1;
+        voffR[rc] = (unsigned)n * 16u;
+    }
+    const int ntaps = CONV ? g.conv.KH * g.conv.KW : 0;
+    const int CB = CONV ? g.conv.CB : 1, KWf = CONV ? g.conv.KW : 1, Wimg = CONV ? g.conv.W : 0;
+    const long long npix = CONV ? g.conv.npix : 0;          // the zero row of a plane has index npix
+
+    // ---- loader state (all scalar).  segL / segR already point at this wave's
+    // first digit plane; dsL / dsR are the byte strides between the digit
+    // planes a wave loads (NW planes apart).
+    const u8 *segL, *segR; long long dsL, dsR;
+    auto set_segment = [&](int seg) {
+        const GemmSeg& q = seg ? sg1 : sg0;
+        segL = q.L + (size_t)bidx * q.L_bstride + (long long)wave * q.L_dstride;
+        segR = q.R + (size_t)bidx * q.R_bstride + (long long)wave * q.R_dstride;
+        dsL = q.L_dstride * C::NW; dsR = q.R_dstride * C::NW;
+    };
+    set_segment(0);
+    int c_seg = 0, c_kb = 0, c_tap = 0, c_cb = 0, c_dpix = 0, c_kw = 0;
+    long long c_offL = 0, c_offR = 0;       // c_kb * krowL / krowR
+    auto cursor_next = [&]() {      // advance by one k block
+        ++c_kb; c_offL += krowL; c_offR += krowR;
+        if (CONV) {
+            if (++c_cb == CB) {
+                c_cb = 0; ++c_tap;
+                if (++c_kw == KWf) { c_kw = 0; c_dpix += Wimg - (KWf - 1); } else ++c_dpix;
             }
-            stL[j] = *reinterpret_cast<const uint4*>(p);
         }
-#pragma unroll
-        for (int j = 0; j < C::RI; ++j) {
-            const int q = rq + j * (C::NT / C::TN);
-            const int kk = q % KS, d = q / KS;
-            const u8* p = Rb + (size_t)d * s.R_dstride + ((size_t)(kb0 + kk) * g.N + (size_t)nrow) * 16;
-            stR[j] = *reinterpret_cast<const uint4*>(p);
+        if (c_seg == 0 && c_kb == KB0) {
+            c_seg = 1; c_kb = 0; c_tap = 0; c_cb = 0; c_dpix = 0; c_kw = 0; c_offL = 0; c_offR = 0;
+            set_segment(1);
         }
     };
 
-    auto store_stage = [&](int buf) {
-        uint4* Ls = lds + (size_t)buf * C::STAGE_UNITS;
-        uint4* Rs = Ls + C::L_UNITS;
+    // State of the stage being issued, captured once per stage; the stage's
+    // loads are then issued one by one between MFMAs.
+    const u8* s_L[KS]; const u8* s_R[KS];
+    unsigned s_zoff[KS]; int s_tap[KS];
+    unsigned s_slotL, s_slotR; long long s_dsL, s_dsR;
+    auto stage_begin = [&](int slot) {
+        // KS divides every segment, so a stage never straddles two segments
+        // (the cursor may move on to the next segment at the end of this stage)
+        s_dsL = dsL; s_dsR = dsR;
+        s_slotL = lds_base + (unsigned)(slot * C::STAGE_UNITS * 16) + (unsigned)(wave * KS * C::TM * 16);
+        s_slotR = lds_base + (unsigned)((slot * C::STAGE_UNITS + C::L_UNITS) * 16) + (unsigned)(wave * KS * C::TN * 16);
 #pragma unroll
-        for (int j = 0; j < C::LI; ++j) {
-            const int q = lq + j * (C::NT / C::TM);       // q = d*KS + kk
-            Ls[q * C::TM + lrow] = stL[j];
+        for (int kk = 0; kk < KS; ++kk) {
+            s_R[kk] = segR + c_offR;
+            if (CONV) {
+                // base such that base + (pix00 + bias)*16 is the tap pixel's unit in channel block c_cb
+                s_L[kk] = segL + ((long long)c_cb * (npix + 1) + c_dpix - bias) * 16;
+                s_zoff[kk] = (unsigned)((npix - c_dpix + bias) * 16);   // lands on the zero row instead
+                s_tap[kk] = c_tap;
+            } else {
+                s_L[kk] = segL + c_offL;
+            }
+            cursor_next();
         }
+    };
+    // q-th load of the stage (left tile first), q a compile-time constant
+    auto issue_one = [&](auto q_tag) {
+        constexpr int q = decltype(q_tag)::value;
+        if constexpr (q < C::LPW) {
+            constexpr int dj = q % C::DPW, kk = (q / C::DPW) % KS, rc = q / (C::DPW * KS);
+            unsigned voff = voffL[rc];
+            if (CONV) {
+                const bool ok = s_tap[kk] < ntaps && ((lvalid[rc] >> (s_tap[kk] & 63)) & 1);
+                voff = ok ? voff : s_zoff[kk];
+            }
+            // destination unit: ((d*KS + kk)*TM + rc*64) with d = wave + NW*dj
+            load_lds16<((C::NW * dj * KS + kk) * C::TM + rc * 64) * 16>(s_L[kk] + dj * s_dsL, voff, s_slotL);
+        } else {
+            constexpr int r = q - C::LPW;
+            constexpr int dj = r % C::DPW, kk = (r / C::DPW) % KS, rc = r / (C::DPW * KS);
+            load_lds16<((C::NW * dj * KS + kk) * C::TN + rc * 64) * 16>(s_R[kk] + dj * s_dsR, voffR[rc], s_slotR);
+        }
+    };
+    constexpr int PER_STAGE = C::LPW + C::RPW;
+    auto issue_all = [&](int slot) {
+        stage_begin(slot);
+        static_for<PER_STAGE>([&](auto q) { issue_one(q); });
+    };
+
+    v16i acc[2][8];
 #pragma unroll
-        for (int j = 0; j < C::RI; ++j) {
-            const int q = rq + j * (C::NT / C::TN);
-            Rs[q * C::TN + rrow] = stR[j];
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[c][s][v] = 0;
+
+    v4i A[8], B[2][8];
+    auto read_A = [&](int slot, int d) {
+        const uint4 a = lds[(size_t)slot * C::STAGE_UNITS + (d * KS + g2) * C::TM + wm * 32 + i32];
+        A[d] = v4i{ (int)a.x, (int)a.y, (int)a.z, (int)a.w };
+    };
+    auto read_B = [&](int slot, int d) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const uint4 b = lds[(size_t)slot * C::STAGE_UNITS + C::L_UNITS + (d * KS + g2) * C::TN + wn * 64 + c * 32 + i32];
+            B[c][d] = v4i{ (int)b.x, (int)b.y, (int)b.z, (int)b.w };
         }
     };
 
-    v16i acc[8];
-#pragma unroll
-    for (int s = 0; s < 8; ++s)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[s][v] = 0;
-
-    auto compute_stage = [&](int buf) {
-        const uint4* Ls = lds + (size_t)buf * C::STAGE_UNITS;
-        const uint4* Rs = Ls + C::L_UNITS;
-        v4i A[8], B[8];
-#pragma unroll
-        for (int d = 0; d < 8; ++d) {
-            const uint4 a = Ls[(d * KS + g2) * C::TM + wm * 32 + i32];
-            const uint4 b = Rs[(d * KS + g2) * C::TN + wn * 32 + i32];
-            A[d] = v4i{ (int)a.x, (int)a.y, (int)a.z, (int)a.w };
-            B[d] = v4i{ (int)b.x, (int)b.y, (int)b.z, (int)b.w };
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-            for (int j = 0; j < 8 - i; ++j)
-                acc[i + j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[i], B[j], acc[i + j], 0, 0, 0);
-    };
-
-    // ---- main loop over (segment, k block) stages
-    int seg = 0, kb0 = 0;
-    auto advance = [&]() { kb0 += KS; if (kb0 >= g.seg[party][seg].KB) { kb0 = 0; ++seg; } };
-    int total = 0;
-    for (int s = 0; s < g.nseg; ++s) total += g.seg[party][s].KB / KS;
-
-    load_stage(seg, kb0); advance();
-    store_stage(0);
+    // ---- main loop.  Ring slot t%NS holds K step t.  At the top of step t the
+    // slot of step t+1 must have landed (this wave's loads: all but the most
+    // recent PER_STAGE); the barrier makes every wave's part visible and
+    // retires slot t%NS, whose operands every wave already holds in registers,
+    // so the loads of step t+NS can go there.  Inside the step the MFMAs run
+    // block by block over the right-operand digit j (left digits 7-j .. 0);
+    // an operand register is refilled from the next slot right after its last
+    // use, in an order that gives every refill at least ~14 MFMAs of cover,
+    // and one global->LDS load is issued after every fourth MFMA: a wave can
+    // issue one instruction per four cycles, so everything that is not an MFMA
+    // has to sit in the seven free issue slots an 8-pass MFMA leaves behind.
+    issue_all(0);
+    if (1 < T) issue_all(1);
+    if (2 < T) issue_all(2);
+    if (T > 2)      __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * PER_STAGE));
+    else if (T > 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(1 * PER_STAGE));
+    else            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
-    for (int t = 0; t < total; ++t) {
-        const bool more = t + 1 < total;
-        if (more) { load_stage(seg, kb0); advance(); }
-        compute_stage(t & 1);
-        if (more) store_stage((t + 1) & 1);
+#pragma unroll
+    for (int d = 0; d < 8; ++d) { read_A(0, d); read_B(0, d); }
+
+    int slot = 0;                        // t % NS
+    // FULL: steps with both a successor to prefetch operands from and a stage to issue
+    auto step = [&](auto full_tag, int t) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        const bool have_next = FULL || t + 1 < T, fill = FULL || t + NS < T;
+        if (FULL || t + 2 < T) __builtin_amdgcn_s_waitcnt(vmcnt_imm(PER_STAGE));
+        else if (have_next)    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
         __syncthreads();
-    }
+        const int nslot = slot + 1 == NS ? 0 : slot + 1;
+        if (fill) stage_begin(slot);
+        // MFMA number n (0..71) <-> block j, left digit i, column half c
+        static_for<8>([&](auto jt) {
+            constexpr int j = decltype(jt)::value;
+            static_for<8 - j>([&](auto it) {
+                constexpr int i = 7 - j - decltype(it)::value;
+                static_for<2>([&](auto ct) {
+                    constexpr int c = decltype(ct)::value;
+                    // MFMAs before this block: sum_{j'<j} 2*(8-j') = j*(17-j)
+                    constexpr int n = j * (17 - j) + 2 * (7 - j - i) + c;
+                    acc[c][i + j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[i], B[c][j], acc[c][i + j], 0, 0, 0);
+                    if constexpr (n % 4 == 1 && n / 4 < PER_STAGE) {
+                        if (fill) issue_one(std::integral_constant<int, n / 4>{});
+                    }
+                });
+                if (i == 7 - j && have_next) read_A(nslot, i);       // last use of A[7-j] in this step
+                // keep this interleaving: without the fence the scheduler packs the
+                // MFMAs back to back and everything else into one exposed cluster
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            if (have_next) read_B(nslot, j);                          // last use of B[.][j]
+        });
+        slot = nslot;
+    };
+    int t = 0;
+    for (; t + NS < T; ++t) step(std::true_type{}, t);
+    for (; t < T; ++t) step(std::false_type{}, t);
 
     // ---- epilogue: recombine, add, truncate, store
     const u64* addend = g.addend[party] ? g.addend[party] + (size_t)bidx * g.out_bstride : nullptr;
     const u64* addend2 = g.addend2[party] ? g.addend2[party] + (size_t)bidx * g.out_bstride : nullptr;
     u64* out = g.out[party] + (size_t)bidx * g.out_bstride;
-    const int col = n0 + wn * 32 + i32;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm * 32 + (v >> 2) * 8 + g2 * 4 + (v & 3);
-        u64 z = 0;
+    for (int c = 0; c < 2; ++c) {
+        const int col = n0 + wn * 64 + c * 32 + i32;
 #pragma unroll
-        for (int s = 0; s < 8; ++s) z += (u64)(long long)acc[s][v] << (8 * s);
-        if (row < g.M && col < g.N) {
-            const size_t idx = (size_t)row * g.N + col;
-            if (addend) z += addend[idx];
-            if (addend2) z += addend2[idx];
-            if (g.trunc_bits) z = party == 0 ? (z >> g.trunc_bits) : (u64)0 - (((u64)0 - z) >> g.trunc_bits);
-            out[idx] = z;
+        for (int v = 0; v < 16; ++v) {
+            const int row = m0 + wm * 32 + (v >> 2) * 8 + g2 * 4 + (v & 3);
+            u64 z = 0;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) z += (u64)(long long)acc[c][s][v] << (8 * s);
+            if (row < g.M && col < g.N) {
+                const size_t idx = (size_t)row * g.N + col;
+                if (addend) z += addend[idx];
+                if (addend2) z += addend2[idx];
+                if (g.trunc_bits) z = party == 0 ? (z >> g.trunc_bits) : (u64)0 - (((u64)0 - z) >> g.trunc_bits);
+                out[idx] = z;
+            }
         }
     }
 }
 
-template <int WGM, int WGN>
+template <int WGM, int WGN, bool CONV>
 int launch_cfg(mpc_ctx* c, hipStream_t st, const GemmArgs& g)
 {
     using C = Cfg<WGM, WGN>;
     static bool attr_set[16] = { false };
-    auto kern = k_limb_gemm<WGM, WGN>;
-    if (c->device >= 0 && c->device < 16 && !attr_set[c->device]) {
+    auto kern = k_limb_gemm<WGM, WGN, CONV>;
+    if (c->device < 0 || c->device >= 16) return MPC_EINVAL;
+    if (!attr_set[c->device]) {
         MPC_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
         attr_set[c->device] = true;
@@ -220,8 +347,8 @@ int launch_limb_gemm(mpc_ctx* c, hipStream_t st, const GemmArgs& g)
     for (int p = 0; p < g.nparty; ++p)
         for (int s = 0; s < g.nseg; ++s)
             if (g.seg[p][s].KB <= 0 || g.seg[p][s].KB % KS) return MPC_EINVAL;
-    // large problems: 128x64 workgroup tiles (8 waves); small ones: 64x64 (4 waves)
-    const long long tiles_big = (long long)((g.M + 127) / 128) * ((g.N + 63) / 64) * g.batch * g.nparty;
-    if (tiles_big >= 256) return launch_cfg<4, 2>(c, st, g);
-    return launch_cfg<2, 2>(c, st, g);
+    // per-lane byte offsets inside one k block of a plane are 32-bit
+    if ((long long)g.rows_L * 16 >= (1ll << 32) || (long long)g.N * 16 >= (1ll << 32)) return MPC_EINVAL;
+    if (g.conv.enabled) return launch_cfg<2, 2, true>(c, st, g);
+    return launch_cfg<2, 2, false>(c, st, g);
 }

@@ -13,7 +13,7 @@ struct LinearShape {
     int B, H, W, Cin, Cout, KH, KW, pad, stride, Ho, Wo, CB;
     // derived
     size_t nx, nw, nz;           // words in x / w / z per party (all batch items)
-    int rowsL;                   // rows of a left plane (M, or B*H*W pixels)
+    int rowsL;                   // rows of a left plane (M, or B*H*W pixels + 1 zero row)
     int KB_L;                    // k blocks stored per left plane row
     int KB;                      // k blocks contracted per segment (even)
     size_t L_plane, R_plane;     // bytes of one digit plane (one batch item)
@@ -38,7 +38,7 @@ LinearShape shape_conv(int B, int H, int W, int Cin, int Cout, int KH, int KW, i
     s.CB = (Cin + 15) / 16;
     s.M = B * s.Ho * s.Wo; s.K = KH * KW * Cin; s.N = Cout; s.batch = 1;
     s.nx = (size_t)B * H * W * Cin; s.nw = (size_t)KH * KW * Cin * Cout; s.nz = (size_t)s.M * Cout;
-    s.rowsL = B * H * W; s.KB_L = s.CB;
+    s.rowsL = B * H * W + 1; s.KB_L = s.CB;      // + the all-zero row that padding taps read
     s.KB = (KH * KW * s.CB + 1) & ~1;
     s.L_plane = plane_bytes(s.rowsL, s.KB_L); s.R_plane = plane_bytes(Cout, s.KB);
     return s;
@@ -72,8 +72,8 @@ RecodeArgs recode_left(const LinearShape& s, const u64* src, const u64* src2, u8
     RecodeArgs a{};
     a.src = src; a.src2 = src2; a.src3 = nullptr; a.dst = dst;
     a.k_stride = 1; a.tap_stride = 0; a.ntaps = 1; a.batch = s.batch;
-    if (s.conv) { a.rows = s.rowsL; a.K = s.Cin; a.row_stride = s.Cin; a.KB_tap = s.CB; a.KB_total = s.CB; }
-    else        { a.rows = s.M; a.K = s.K; a.row_stride = s.K; a.KB_tap = (s.K + 15) / 16; a.KB_total = s.KB; }
+    if (s.conv) { a.rows = s.rowsL - 1; a.plane_rows = s.rowsL; a.K = s.Cin; a.row_stride = s.Cin; a.KB_tap = s.CB; a.KB_total = s.CB; }
+    else        { a.rows = s.M; a.plane_rows = s.M; a.K = s.K; a.row_stride = s.K; a.KB_tap = (s.K + 15) / 16; a.KB_total = s.KB; }
     a.digit_stride = (long long)s.L_plane;
     a.src_batch_stride = (long long)s.M * s.K;          // unused for conv (batch == 1)
     a.dst_batch_stride = (long long)(8 * s.L_plane);
@@ -84,7 +84,7 @@ RecodeArgs recode_right(const LinearShape& s, const u64* src, const u64* src2, c
 {
     RecodeArgs a{};
     a.src = src; a.src2 = src2; a.src3 = src3; a.dst = dst;
-    a.rows = s.N; a.row_stride = 1; a.k_stride = s.N; a.batch = s.batch;
+    a.rows = s.N; a.plane_rows = s.N; a.row_stride = 1; a.k_stride = s.N; a.batch = s.batch;
     if (s.conv) { a.K = s.Cin; a.KB_tap = s.CB; a.ntaps = s.KH * s.KW; a.tap_stride = (long long)s.Cin * s.Cout; }
     else        { a.K = s.K; a.KB_tap = (s.K + 15) / 16; a.ntaps = 1; a.tap_stride = 0; }
     a.KB_total = s.KB;
@@ -104,7 +104,7 @@ void fill_geom(const LinearShape& s, const LinearWs& w, GemmArgs& g)
     if (s.conv) {
         g.conv.enabled = 1; g.conv.H = s.H; g.conv.W = s.W; g.conv.Ho = s.Ho; g.conv.Wo = s.Wo;
         g.conv.CB = s.CB; g.conv.KH = s.KH; g.conv.KW = s.KW; g.conv.pad = s.pad; g.conv.stride = s.stride;
-        g.conv.npix = (long long)s.rowsL;
+        g.conv.npix = (long long)s.rowsL - 1;
     }
 }
 
