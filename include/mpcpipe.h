@@ -84,6 +84,17 @@ int mpc_ctx_sync(mpc_ctx* ctx);
  * far on the party streams of `after`; used to chain layers across lanes. */
 int mpc_ctx_wait(mpc_ctx* ctx, mpc_ctx* after);
 
+/* Optional timing for benchmarks.  While enabled, the lane brackets three
+ * kinds of region with timing-enabled HIP events on the stream that executes
+ * them: which = 0 the digit-plane GEMM kernel alone, 1 a whole secure linear
+ * call (mask, exchange, recode, GEMM), 2 a whole secure ReLU call.
+ * mpc_ctx_profile synchronises the lane, returns the summed duration and the
+ * number of regions recorded since the last mpc_ctx_profile_reset. */
+enum { MPC_PROF_GEMM_KERNEL = 0, MPC_PROF_LINEAR = 1, MPC_PROF_RELU = 2 };
+int mpc_ctx_set_profiling(mpc_ctx* ctx, int enable);
+int mpc_ctx_profile(mpc_ctx* ctx, int which, double* total_ms, int* count);
+int mpc_ctx_profile_reset(mpc_ctx* ctx);
+
 int mpc_last_hip_error(const mpc_ctx* ctx);
 const char* mpc_strerror(int code);
 

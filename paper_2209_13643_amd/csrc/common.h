@@ -6,6 +6,9 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <utility>
+#include <vector>
+
 #include "../../include/mpcpipe.h"
 
 typedef uint64_t u64;
@@ -24,6 +27,8 @@ struct mpc_ctx {
     u8* ws;                  // caller-owned workspace
     size_t ws_bytes;
     int last_hip;
+    bool profiling;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> prof[3];   // timing event pairs per region kind
 };
 
 static inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
@@ -77,6 +82,23 @@ static inline int lane_join(mpc_ctx* c)
         for (int j = 0; j < 3; ++j)
             if (i != j) MPC_HIP(c, hipStreamWaitEvent(c->s[i], e[j], 0));
     return MPC_OK;
+}
+
+// Timing regions (no-ops unless profiling is on): prof_begin records a start
+// event on `st` and returns its index, prof_end records the matching stop.
+static inline int prof_begin(mpc_ctx* c, int which, hipStream_t st)
+{
+    if (!c->profiling) return -1;
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) return -1;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return -1; }
+    (void)hipEventRecord(a, st);
+    c->prof[which].push_back({ a, b });
+    return (int)c->prof[which].size() - 1;
+}
+static inline void prof_end(mpc_ctx* c, int which, int idx, hipStream_t st)
+{
+    if (idx >= 0) (void)hipEventRecord(c->prof[which][idx].second, st);
 }
 
 // Bump allocator over the workspace.

@@ -11,7 +11,7 @@ int mpc_ctx_create(mpc_ctx** out, int device, int frac_bits)
     mpc_ctx* c = new (std::nothrow) mpc_ctx();
     if (!c) return MPC_ENOMEM;
     c->device = device; c->frac_bits = frac_bits; c->ev_next = 0;
-    c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0;
+    c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0; c->profiling = false;
     for (int i = 0; i < 3; ++i) { c->s[i] = nullptr; c->own_stream[i] = false; }
     for (int i = 0; i < kEventPool; ++i) c->ev[i] = nullptr;
     hipError_t e = hipSetDevice(device);
@@ -38,6 +38,7 @@ int mpc_ctx_destroy(mpc_ctx* c)
         if (c->s[i]) (void)hipStreamSynchronize(c->s[i]);
     for (int i = 0; i < kEventPool; ++i)
         if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+    (void)mpc_ctx_profile_reset(c);
     for (int i = 0; i < 3; ++i)
         if (c->own_stream[i] && c->s[i]) (void)hipStreamDestroy(c->s[i]);
     delete c;
@@ -89,6 +90,38 @@ int mpc_ctx_wait(mpc_ctx* c, mpc_ctx* after)
         hipEvent_t e = next_event(after);
         MPC_HIP(after, hipEventRecord(e, after->s[i]));
         for (int j = 0; j < 2; ++j) MPC_HIP(c, hipStreamWaitEvent(c->s[j], e, 0));
+    }
+    return MPC_OK;
+}
+
+int mpc_ctx_set_profiling(mpc_ctx* c, int enable)
+{
+    if (!c) return MPC_EINVAL;
+    c->profiling = enable != 0;
+    return MPC_OK;
+}
+
+int mpc_ctx_profile(mpc_ctx* c, int which, double* total_ms, int* count)
+{
+    if (!c || which < 0 || which > 2 || !total_ms || !count) return MPC_EINVAL;
+    MPC_TRY(mpc_ctx_sync(c));
+    double sum = 0.0;
+    for (auto& pr : c->prof[which]) {
+        float ms = 0.f;
+        MPC_HIP(c, hipEventElapsedTime(&ms, pr.first, pr.second));
+        sum += ms;
+    }
+    *total_ms = sum;
+    *count = (int)c->prof[which].size();
+    return MPC_OK;
+}
+
+int mpc_ctx_profile_reset(mpc_ctx* c)
+{
+    if (!c) return MPC_EINVAL;
+    for (int k = 0; k < 3; ++k) {
+        for (auto& pr : c->prof[k]) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
+        c->prof[k].clear();
     }
     return MPC_OK;
 }

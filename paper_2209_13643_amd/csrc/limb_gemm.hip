@@ -333,7 +333,9 @@ int launch_cfg(mpc_ctx* c, hipStream_t st, const GemmArgs& g)
         attr_set[c->device] = true;
     }
     dim3 grid((g.M + C::TM - 1) / C::TM, (g.N + C::TN - 1) / C::TN, g.batch * g.nparty);
+    const int pi = prof_begin(c, MPC_PROF_GEMM_KERNEL, st);
     hipLaunchKernelGGL(kern, grid, dim3(C::NT), C::LDS_BYTES, st, g);
+    prof_end(c, MPC_PROF_GEMM_KERNEL, pi, st);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
 }

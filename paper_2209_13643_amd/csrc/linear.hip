@@ -152,6 +152,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
     const int trunc = (flags & MPC_TRUNCATE) ? c->frac_bits : 0;
 
     MPC_TRY(lane_join(c));
+    const int pi = prof_begin(c, MPC_PROF_LINEAR, P0);
     MPC_TRY(launch_fill_zero(c, P0, w.zero, 256));
 
     // -- Alg. 1 line 1-2 / Alg. 3 line 2-3: mask and start the exchange, chunk by chunk
@@ -230,6 +231,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         g.trunc_bits = trunc;
         MPC_TRY(launch_limb_gemm(c, P0, g));
     }
+    prof_end(c, MPC_PROF_LINEAR, pi, P0);
     // party 1's output was produced by the joint launch on party 0's stream
     MPC_TRY(chain(c, P0, P1));
     return MPC_OK;

@@ -467,10 +467,16 @@ int mpc_relu(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat, mpc_share y
     ReluWs w = carve_relu(c->ws, c->ws_bytes, n);
     if (!w.ok) return MPC_ENOMEM;
     MPC_TRY(lane_join(c));
+    const int pi = prof_begin(c, MPC_PROF_RELU, c->s[0]);
     ReluParty pp[2];
     for (int i = 0; i < 2; ++i)
         fill_party(pp[i], i, x.p[i], mat, w, y.p[i], s_bit ? s_bit[i] : nullptr, s_arith ? s_arith[i] : nullptr, n);
-    return relu_run(c, pp, n, n_chunks);
+    MPC_TRY(relu_run(c, pp, n, n_chunks));
+    if (pi >= 0) {      // the region ends when both parties' last kernels are done
+        MPC_TRY(chain(c, c->s[1], c->s[0]));
+        prof_end(c, MPC_PROF_RELU, pi, c->s[0]);
+    }
+    return MPC_OK;
 }
 
 int mpc_maxpool2x2(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat1, const mpc_relu_material* mat2,

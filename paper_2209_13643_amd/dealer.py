@@ -1,0 +1,93 @@
+"""Device-side synthetic dealer: the stand-in for the offline phase.
+
+Produces, directly in HBM, the inputs of the online phase for a workload:
+additive shares of fixed-point tensors, Beaver triples (C = A*B through the
+library's own plain ring product, `mpc_ring_matmul` / `mpc_ring_conv2d`), and
+secure-ReLU material.  Everything here runs before the timed region; the paper
+excludes the offline phase from its measurements as well (Sec. 5.2, Sec. 5.9).
+torch is used as a random-number source and for the element-wise relations the
+material has to satisfy; none of this is on the online path.
+"""
+from __future__ import annotations
+
+import math
+
+import torch
+
+from . import mpc
+
+FRAC_BITS = 16
+
+
+def gen(seed: int, device) -> torch.Generator:
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    return g
+
+
+def rand_words(g, shape, device):
+    """Uniform 64-bit words (as int64 bit patterns)."""
+    hi = torch.randint(-(1 << 31), 1 << 31, shape, generator=g, device=device, dtype=torch.int64)
+    lo = torch.randint(0, 1 << 32, shape, generator=g, device=device, dtype=torch.int64)
+    return (hi << 32) | lo
+
+
+def normal_fixed(g, shape, std, device):
+    v = torch.randn(shape, generator=g, device=device, dtype=torch.float64) * std
+    return torch.round(v * float(1 << FRAC_BITS)).to(torch.int64)
+
+
+def share(g, value):
+    s0 = rand_words(g, value.shape, value.device)
+    return s0, value - s0
+
+
+def share_xor(g, value):
+    s0 = rand_words(g, value.shape, value.device)
+    return s0, value ^ s0
+
+
+def conv_layer(lane: "mpc.Lane", g, B, H, W, Cin, Cout, KH, KW, pad, stride, x_std, w_std):
+    dev = lane.device
+    X = normal_fixed(g, (B, H, W, Cin), x_std, dev)
+    Wt = normal_fixed(g, (KH, KW, Cin, Cout), w_std, dev)
+    A = rand_words(g, X.shape, dev); Bm = rand_words(g, Wt.shape, dev)
+    C = lane.ring_conv2d(A, Bm, pad, stride)
+    lane.sync()
+    d = dict(X=X, W=Wt, x=share(g, X), w=share(g, Wt), a=share(g, A), b=share(g, Bm), c=share(g, C))
+    d["f_public"] = Wt - Bm          # epsilon = W - B, opened ahead of time (Alg. 3)
+    return d
+
+
+def matmul_layer(lane: "mpc.Lane", g, M, K, N, x_std, w_std, batch=None):
+    dev = lane.device
+    xs = (M, K) if batch is None else (batch, M, K)
+    ws = (K, N) if batch is None else (batch, K, N)
+    X = normal_fixed(g, xs, x_std, dev); Wt = normal_fixed(g, ws, w_std, dev)
+    A = rand_words(g, xs, dev); Bm = rand_words(g, ws, dev)
+    C = lane.ring_matmul(A, Bm)
+    lane.sync()
+    d = dict(X=X, W=Wt, x=share(g, X), w=share(g, Wt), a=share(g, A), b=share(g, Bm), c=share(g, C))
+    d["f_public"] = Wt - Bm
+    return d
+
+
+def relu_material(g, n: int, device) -> dict:
+    m = {}
+    m["r"] = (rand_words(g, (n,), device), rand_words(g, (n,), device))
+    a = (rand_words(g, (mpc.N_AND_TRIPLES, n), device), rand_words(g, (mpc.N_AND_TRIPLES, n), device))
+    b = (rand_words(g, (mpc.N_AND_TRIPLES, n), device), rand_words(g, (mpc.N_AND_TRIPLES, n), device))
+    m["and_a"], m["and_b"] = a, b
+    m["and_c"] = share_xor(g, (a[0] ^ a[1]) & (b[0] ^ b[1]))
+    rb = tuple(torch.randint(0, 2, (n,), generator=g, device=device, dtype=torch.uint8) for _ in range(2))
+    m["rb"] = rb
+    m["ra"] = share(g, (rb[0] ^ rb[1]).to(torch.int64))
+    ma = (rand_words(g, (n,), device), rand_words(g, (n,), device))
+    mb = (rand_words(g, (n,), device), rand_words(g, (n,), device))
+    m["ma"], m["mb"] = ma, mb
+    m["mc"] = share(g, (ma[0] + ma[1]) * (mb[0] + mb[1]))
+    return m
+
+
+def he_std(fan_in: int) -> float:
+    return math.sqrt(2.0 / fan_in)

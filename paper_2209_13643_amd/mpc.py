@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libmpcpipe.so")
 
 MPC_TRUNCATE = 1
 MPC_TWO_PHASE = 2
+PROF_GEMM_KERNEL, PROF_LINEAR, PROF_RELU = 0, 1, 2
 N_AND_TRIPLES = 12
 
 _P64 = POINTER(c_uint64)
@@ -36,6 +37,7 @@ class ReluMaterial(ctypes.Structure):
 EXPORTS = [
     "mpc_ctx_create", "mpc_ctx_destroy", "mpc_ctx_set_streams", "mpc_ctx_stream", "mpc_ctx_set_workspace",
     "mpc_ctx_sync", "mpc_ctx_wait", "mpc_last_hip_error", "mpc_strerror",
+    "mpc_ctx_set_profiling", "mpc_ctx_profile", "mpc_ctx_profile_reset",
     "mpc_matmul_workspace_bytes", "mpc_conv2d_workspace_bytes", "mpc_relu_workspace_bytes",
     "mpc_maxpool_workspace_bytes", "mpc_open", "mpc_beaver_matmul", "mpc_conv2d", "mpc_truncate",
     "mpc_relu", "mpc_maxpool2x2", "mpc_ring_matmul", "mpc_ring_conv2d",
@@ -59,6 +61,9 @@ def lib():
     L.mpc_ctx_set_workspace.argtypes = [c_void_p, c_void_p, c_size_t]
     L.mpc_ctx_sync.argtypes = [c_void_p]
     L.mpc_ctx_wait.argtypes = [c_void_p, c_void_p]
+    L.mpc_ctx_set_profiling.argtypes = [c_void_p, c_int]
+    L.mpc_ctx_profile.argtypes = [c_void_p, c_int, POINTER(ctypes.c_double), POINTER(c_int)]
+    L.mpc_ctx_profile_reset.argtypes = [c_void_p]
     L.mpc_last_hip_error.argtypes = [c_void_p]
     L.mpc_strerror.argtypes = [c_int]; L.mpc_strerror.restype = ctypes.c_char_p
     L.mpc_matmul_workspace_bytes.argtypes = [c_int] * 4; L.mpc_matmul_workspace_bytes.restype = c_size_t
@@ -170,6 +175,18 @@ class Lane:
 
     def sync(self):
         self._check(lib().mpc_ctx_sync(self._h))
+
+    def set_profiling(self, on: bool):
+        self._check(lib().mpc_ctx_set_profiling(self._h, 1 if on else 0))
+
+    def profile(self, which: int):
+        """(total milliseconds, region count) for PROF_GEMM_KERNEL / PROF_LINEAR / PROF_RELU."""
+        ms, cnt = ctypes.c_double(), c_int()
+        self._check(lib().mpc_ctx_profile(self._h, which, byref(ms), byref(cnt)))
+        return ms.value, cnt.value
+
+    def profile_reset(self):
+        self._check(lib().mpc_ctx_profile_reset(self._h))
 
     def wait_for(self, other: "Lane"):
         self._check(lib().mpc_ctx_wait(self._h, other._h))
