@@ -73,6 +73,7 @@ static inline int chain(mpc_ctx* c, hipStream_t from, hipStream_t to)
 // previous call's outputs of either party.
 static inline int lane_join(mpc_ctx* c)
 {
+    if (c->s[0] == c->s[1] && c->s[1] == c->s[2]) return MPC_OK;   // one in-order queue: nothing to join
     hipEvent_t e[3];
     for (int i = 0; i < 3; ++i) {
         e[i] = next_event(c);
@@ -80,7 +81,7 @@ static inline int lane_join(mpc_ctx* c)
     }
     for (int i = 0; i < 3; ++i)
         for (int j = 0; j < 3; ++j)
-            if (i != j) MPC_HIP(c, hipStreamWaitEvent(c->s[i], e[j], 0));
+            if (i != j && c->s[i] != c->s[j]) MPC_HIP(c, hipStreamWaitEvent(c->s[i], e[j], 0));
     return MPC_OK;
 }
 

@@ -50,7 +50,7 @@ int mpc_ctx_set_streams(mpc_ctx* c, void* s0, void* s1, void* sw)
     if (!c) return MPC_EINVAL;
     void* in[3] = { s0, s1, sw };
     for (int i = 0; i < 3; ++i) {
-        if (!in[i]) continue;
+        if (!in[i] || in[i] == (void*)c->s[i]) continue;
         if (c->own_stream[i]) {
             MPC_HIP(c, hipStreamSynchronize(c->s[i]));
             MPC_HIP(c, hipStreamDestroy(c->s[i]));

@@ -59,6 +59,36 @@ template <> struct Pack<2> {
     }
 };
 
+template <> struct Pack<4> {
+    u64 v[4];
+    __device__ static Pack ld(const u64* p, size_t i)
+    {
+        const u64x2 t = *reinterpret_cast<const u64x2*>(p + i), u = *reinterpret_cast<const u64x2*>(p + i + 2);
+        Pack r; r.v[0] = t.a; r.v[1] = t.b; r.v[2] = u.a; r.v[3] = u.b; return r;
+    }
+    __device__ void st(u64* p, size_t i) const
+    {
+        u64x2 t, u; t.a = v[0]; t.b = v[1]; u.a = v[2]; u.b = v[3];
+        *reinterpret_cast<u64x2*>(p + i) = t; *reinterpret_cast<u64x2*>(p + i + 2) = u;
+    }
+};
+
+// V consecutive bytes (one per element): a single 16- or 32-bit access when V is 2 or 4
+template <int V> __device__ __forceinline__ void ld_bytes(const u8* p, size_t i, u8 (&out)[V])
+{
+    if constexpr (V == 4) { const uint32_t w = *reinterpret_cast<const uint32_t*>(p + i);
+                            out[0] = (u8)w; out[1] = (u8)(w >> 8); out[2] = (u8)(w >> 16); out[3] = (u8)(w >> 24); }
+    else if constexpr (V == 2) { const uint16_t w = *reinterpret_cast<const uint16_t*>(p + i);
+                                 out[0] = (u8)w; out[1] = (u8)(w >> 8); }
+    else out[0] = p[i];
+}
+template <int V> __device__ __forceinline__ void st_bytes(u8* p, size_t i, const u8 (&in)[V])
+{
+    if constexpr (V == 4) *reinterpret_cast<uint32_t*>(p + i) = (uint32_t)in[0] | ((uint32_t)in[1] << 8) | ((uint32_t)in[2] << 16) | ((uint32_t)in[3] << 24);
+    else if constexpr (V == 2) *reinterpret_cast<uint16_t*>(p + i) = (uint16_t)((uint16_t)in[0] | ((uint16_t)in[1] << 8));
+    else p[i] = in[0];
+}
+
 // Beaver AND, one party's side (Eq. 4; Alg. 4 for the party that adds d & g):
 // d, g are the opened masked operands, (a, b, c) this party's triple words.
 template <int PARTY>
@@ -75,7 +105,7 @@ __device__ __forceinline__ u64 and_finish(u64 d, u64 g, u64 a, u64 b, u64 c)
 
 // ---- K_first ------------------------------------------------------------------
 template <int PARTY, int V>
-__global__ __launch_bounds__(kThreads) void k_first(ReluParty p, size_t lo, size_t hi)
+__device__ __forceinline__ void b_first(const ReluParty& p, size_t lo, size_t hi)
 {
     const size_t n = p.n;
     FOR_ELEMS(V) {
@@ -94,8 +124,7 @@ __global__ __launch_bounds__(kThreads) void k_first(ReluParty p, size_t lo, size
             top[k] = (u8)(P.v[k] >> 63);
         }
         d.st(p.send, i); g.st(p.send + n, i); P.st(p.P, i);
-#pragma unroll
-        for (int k = 0; k < V; ++k) p.p63[i + k] = top[k];
+        st_bytes<V>(p.p63, i, top);
     }
 }
 
@@ -104,7 +133,7 @@ __global__ __launch_bounds__(kThreads) void k_first(ReluParty p, size_t lo, size
 // buffer); LEVEL l > 0 finishes the two ANDs of level l-1 from the carried
 // (G, P).  Then masks the operands of level LEVEL.
 template <int PARTY, int LEVEL, int V>
-__global__ __launch_bounds__(kThreads) void k_level(ReluParty p, size_t lo, size_t hi)
+__device__ __forceinline__ void b_level(const ReluParty& p, size_t lo, size_t hi)
 {
     const size_t n = p.n;
     constexpr int sh = 1 << LEVEL;
@@ -158,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void k_level(ReluParty p, size_t lo, size
 
 // ---- K_sign -------------------------------------------------------------------
 template <int PARTY, int V>
-__global__ __launch_bounds__(kThreads) void k_sign(ReluParty p, size_t lo, size_t hi)
+__device__ __forceinline__ void b_sign(const ReluParty& p, size_t lo, size_t hi)
 {
     const size_t n = p.n;
     constexpr int t1 = 11, psh = 32;
@@ -167,31 +196,36 @@ __global__ __launch_bounds__(kThreads) void k_sign(ReluParty p, size_t lo, size_
         const Pack<V> rd1 = Pack<V>::ld(p.recv, i), rg1 = Pack<V>::ld(p.recv + n, i);
         const Pack<V> a1 = Pack<V>::ld(p.ta + t1 * n, i), b1 = Pack<V>::ld(p.tb + t1 * n, i),
                       c1 = Pack<V>::ld(p.tc + t1 * n, i);
+        u8 top[V], rb[V], sb[V], mb[V];
+        ld_bytes<V>(p.p63, i, top); ld_bytes<V>(p.rb, i, rb);
 #pragma unroll
         for (int k = 0; k < V; ++k) {
             const u64 d1 = (Po.v[k] ^ a1.v[k]) ^ rd1.v[k];
             const u64 g1 = ((Go.v[k] << psh) ^ b1.v[k]) ^ rg1.v[k];
             const u64 G = Go.v[k] ^ and_finish<PARTY>(d1, g1, a1.v[k], b1.v[k], c1.v[k]);
             // bit 63 of the sum = bit 63 of U^V xor the carry out of bits [0..62]
-            const u8 s = (u8)(p.p63[i + k] ^ (u8)((G >> 62) & 1));
-            if (p.s_bit) p.s_bit[i + k] = s;
-            p.sendb[i + k] = (u8)(s ^ p.rb[i + k]);
+            sb[k] = (u8)(top[k] ^ (u8)((G >> 62) & 1));
+            mb[k] = (u8)(sb[k] ^ rb[k]);
         }
+        if (p.s_bit) st_bytes<V>(p.s_bit, i, sb);
+        st_bytes<V>(p.sendb, i, mb);
     }
 }
 
 // ---- K_b2a --------------------------------------------------------------------
 template <int PARTY, int V>
-__global__ __launch_bounds__(kThreads) void k_b2a(ReluParty p, size_t lo, size_t hi)
+__device__ __forceinline__ void b_b2a(const ReluParty& p, size_t lo, size_t hi)
 {
     const size_t n = p.n;
     FOR_ELEMS(V) {
         const Pack<V> x = Pack<V>::ld(p.x, i), ra = Pack<V>::ld(p.ra, i);
         const Pack<V> ma = Pack<V>::ld(p.ma, i), mb = Pack<V>::ld(p.mb, i);
         Pack<V> e, f, sa;
+        u8 own[V], got[V];
+        ld_bytes<V>(p.sendb, i, own); ld_bytes<V>(p.recvb, i, got);
 #pragma unroll
         for (int k = 0; k < V; ++k) {
-            const u64 v = (u64)(p.sendb[i + k] ^ p.recvb[i + k]);     // opened s ^ rb
+            const u64 v = (u64)(own[k] ^ got[k]);                      // opened s ^ rb
             // s = v xor rb = v + rb - 2 v rb on additive shares of rb
             sa.v[k] = ra.v[k] - 2 * v * ra.v[k] + (PARTY == 0 ? v : 0);
             const u64 m = (PARTY == 0 ? (u64)1 : (u64)0) - sa.v[k];    // shares of 1 - s
@@ -205,7 +239,7 @@ __global__ __launch_bounds__(kThreads) void k_b2a(ReluParty p, size_t lo, size_t
 
 // ---- K_select -----------------------------------------------------------------
 template <int PARTY, int V>
-__global__ __launch_bounds__(kThreads) void k_select(ReluParty p, size_t lo, size_t hi)
+__device__ __forceinline__ void b_select(const ReluParty& p, size_t lo, size_t hi)
 {
     const size_t n = p.n;
     FOR_ELEMS(V) {
@@ -225,9 +259,12 @@ __global__ __launch_bounds__(kThreads) void k_select(ReluParty p, size_t lo, siz
 }
 
 // rows x len words, both sides with pitch `pitch` words: the per-round wire copy
-__global__ __launch_bounds__(kThreads) void k_wire_words(const u64* __restrict__ src, u64* __restrict__ dst,
+// blockIdx.y selects the direction: 0 = party 0 -> party 1, 1 = party 1 -> party 0
+__global__ __launch_bounds__(kThreads) void k_wire_words(const u64* __restrict__ src0, u64* __restrict__ dst0,
+                                                         const u64* __restrict__ src1, u64* __restrict__ dst1,
                                                          size_t pitch, size_t lo, size_t hi, int rows)
 {
+    const u64* src = blockIdx.y ? src1 : src0; u64* dst = blockIdx.y ? dst1 : dst0;
     const size_t stride = (size_t)gridDim.x * blockDim.x * 2;
     for (int r = 0; r < rows; ++r) {
         const u64* s = src + (size_t)r * pitch; u64* d = dst + (size_t)r * pitch;
@@ -235,17 +272,21 @@ __global__ __launch_bounds__(kThreads) void k_wire_words(const u64* __restrict__
             *reinterpret_cast<u64x2*>(d + i) = *reinterpret_cast<const u64x2*>(s + i);
     }
 }
-__global__ __launch_bounds__(kThreads) void k_wire_words1(const u64* __restrict__ src, u64* __restrict__ dst,
+__global__ __launch_bounds__(kThreads) void k_wire_words1(const u64* __restrict__ src0, u64* __restrict__ dst0,
+                                                          const u64* __restrict__ src1, u64* __restrict__ dst1,
                                                           size_t pitch, size_t lo, size_t hi, int rows)
 {
+    const u64* src = blockIdx.y ? src1 : src0; u64* dst = blockIdx.y ? dst1 : dst0;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (int r = 0; r < rows; ++r)
         for (size_t i = lo + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < hi; i += stride)
             dst[(size_t)r * pitch + i] = src[(size_t)r * pitch + i];
 }
-__global__ __launch_bounds__(kThreads) void k_wire_bytes(const u8* __restrict__ src, u8* __restrict__ dst,
+__global__ __launch_bounds__(kThreads) void k_wire_bytes(const u8* __restrict__ src0, u8* __restrict__ dst0,
+                                                         const u8* __restrict__ src1, u8* __restrict__ dst1,
                                                          size_t lo, size_t hi)
 {
+    const u8* src = blockIdx.y ? src1 : src0; u8* dst = blockIdx.y ? dst1 : dst0;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = lo + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < hi; i += stride) dst[i] = src[i];
 }
@@ -280,21 +321,47 @@ ReluWs carve_relu(u8* base, size_t cap, size_t n)
 
 enum Stage { ST_FIRST = 0, ST_LEVEL0 = 1, ST_SIGN = 7, ST_B2A = 8, ST_SELECT = 9, ST_COUNT = 10 };
 
-template <int PARTY, int V>
-void launch_stage(int stage, hipStream_t st, const ReluParty& p, size_t lo, size_t hi)
+// One launch runs a protocol stage for both parties (blockIdx.y = party) or,
+// when the parties live on different streams, for party `only` alone.
+template <int STAGE, int PARTY, int V>
+__device__ __forceinline__ void stage_body(const ReluParty& p, size_t lo, size_t hi)
 {
-    const dim3 grid(grid_for((hi - lo + V - 1) / V)), block(kThreads);
+    if constexpr (STAGE == 0) b_first<PARTY, V>(p, lo, hi);
+    else if constexpr (STAGE >= 1 && STAGE <= 6) b_level<PARTY, STAGE - 1, V>(p, lo, hi);
+    else if constexpr (STAGE == 7) b_sign<PARTY, V>(p, lo, hi);
+    else if constexpr (STAGE == 8) b_b2a<PARTY, V>(p, lo, hi);
+    else b_select<PARTY, V>(p, lo, hi);
+}
+
+template <int STAGE, int V>
+__global__ __launch_bounds__(kThreads) void k_relu_stage(ReluParty p0, ReluParty p1, int only, size_t lo, size_t hi)
+{
+    const int party = only >= 0 ? only : (int)blockIdx.y;
+    if (party == 0) stage_body<STAGE, 0, V>(p0, lo, hi);
+    else            stage_body<STAGE, 1, V>(p1, lo, hi);
+}
+
+template <int STAGE, int V>
+void launch_stage_t(hipStream_t st, const ReluParty& p0, const ReluParty& p1, int only, size_t lo, size_t hi)
+{
+    const dim3 grid(grid_for((hi - lo + V - 1) / V), only >= 0 ? 1 : 2), block(kThreads);
+    hipLaunchKernelGGL((k_relu_stage<STAGE, V>), grid, block, 0, st, p0, p1, only, lo, hi);
+}
+
+template <int V>
+void launch_stage(int stage, hipStream_t st, const ReluParty& p0, const ReluParty& p1, int only, size_t lo, size_t hi)
+{
     switch (stage) {
-    case 0: hipLaunchKernelGGL((k_first<PARTY, V>), grid, block, 0, st, p, lo, hi); break;
-    case 1: hipLaunchKernelGGL((k_level<PARTY, 0, V>), grid, block, 0, st, p, lo, hi); break;
-    case 2: hipLaunchKernelGGL((k_level<PARTY, 1, V>), grid, block, 0, st, p, lo, hi); break;
-    case 3: hipLaunchKernelGGL((k_level<PARTY, 2, V>), grid, block, 0, st, p, lo, hi); break;
-    case 4: hipLaunchKernelGGL((k_level<PARTY, 3, V>), grid, block, 0, st, p, lo, hi); break;
-    case 5: hipLaunchKernelGGL((k_level<PARTY, 4, V>), grid, block, 0, st, p, lo, hi); break;
-    case 6: hipLaunchKernelGGL((k_level<PARTY, 5, V>), grid, block, 0, st, p, lo, hi); break;
-    case 7: hipLaunchKernelGGL((k_sign<PARTY, V>), grid, block, 0, st, p, lo, hi); break;
-    case 8: hipLaunchKernelGGL((k_b2a<PARTY, V>), grid, block, 0, st, p, lo, hi); break;
-    case 9: hipLaunchKernelGGL((k_select<PARTY, V>), grid, block, 0, st, p, lo, hi); break;
+    case 0: launch_stage_t<0, V>(st, p0, p1, only, lo, hi); break;
+    case 1: launch_stage_t<1, V>(st, p0, p1, only, lo, hi); break;
+    case 2: launch_stage_t<2, V>(st, p0, p1, only, lo, hi); break;
+    case 3: launch_stage_t<3, V>(st, p0, p1, only, lo, hi); break;
+    case 4: launch_stage_t<4, V>(st, p0, p1, only, lo, hi); break;
+    case 5: launch_stage_t<5, V>(st, p0, p1, only, lo, hi); break;
+    case 6: launch_stage_t<6, V>(st, p0, p1, only, lo, hi); break;
+    case 7: launch_stage_t<7, V>(st, p0, p1, only, lo, hi); break;
+    case 8: launch_stage_t<8, V>(st, p0, p1, only, lo, hi); break;
+    case 9: launch_stage_t<9, V>(st, p0, p1, only, lo, hi); break;
     default: break;
     }
 }
@@ -310,13 +377,17 @@ inline int words_after(int stage)
     return -1;  // select: nothing to send
 }
 
-int wire_words(mpc_ctx* c, const u64* src, u64* dst, size_t pitch, size_t lo, size_t hi, int rows, bool vec)
+// one exchange: party 0's words to party 1's receive buffer and vice versa
+int wire_words(mpc_ctx* c, const u64* src0, u64* dst0, const u64* src1, u64* dst1,
+               size_t pitch, size_t lo, size_t hi, int rows, bool vec)
 {
     const size_t len = hi - lo;
     if (vec)
-        hipLaunchKernelGGL(k_wire_words, dim3(grid_for(len / 2)), dim3(kThreads), 0, c->s[2], src, dst, pitch, lo, hi, rows);
+        hipLaunchKernelGGL(k_wire_words, dim3(grid_for(len / 2), 2), dim3(kThreads), 0, c->s[2],
+                           src0, dst0, src1, dst1, pitch, lo, hi, rows);
     else
-        hipLaunchKernelGGL(k_wire_words1, dim3(grid_for(len)), dim3(kThreads), 0, c->s[2], src, dst, pitch, lo, hi, rows);
+        hipLaunchKernelGGL(k_wire_words1, dim3(grid_for(len), 2), dim3(kThreads), 0, c->s[2],
+                           src0, dst0, src1, dst1, pitch, lo, hi, rows);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
 }
@@ -325,56 +396,65 @@ int wire_words(mpc_ctx* c, const u64* src, u64* dst, size_t pitch, size_t lo, si
 int relu_run(mpc_ctx* c, ReluParty (&pp)[2], size_t n, int n_chunks)
 {
     if (n_chunks > kMaxChunks) n_chunks = kMaxChunks;
-    if ((size_t)n_chunks > (n + 1) / 2) n_chunks = (int)((n + 1) / 2);
+    if ((size_t)n_chunks > (n + 3) / 4) n_chunks = (int)((n + 3) / 4);
     if (n_chunks < 1) n_chunks = 1;
-    // 16-byte accesses need even n (so that every [k][n] row stays aligned) and aligned bases
+    // 16-byte accesses need even n (so that every [k][n] row stays aligned) and aligned bases;
+    // four elements per thread additionally need n % 4 == 0 and 4-byte aligned byte arrays
     bool vec = (n % 2 == 0);
     for (int i = 0; i < 2 && vec; ++i) {
         const void* ptrs[] = { pp[i].x, pp[i].r, pp[i].ta, pp[i].tb, pp[i].tc, pp[i].ra, pp[i].ma,
                                pp[i].mb, pp[i].mc, pp[i].y, pp[i].s_arith };
         for (const void* q : ptrs) if (q && ((uintptr_t)q & 15)) vec = false;
     }
+    bool vec4 = vec && (n % 4 == 0);
+    for (int i = 0; i < 2 && vec4; ++i)
+        if (((uintptr_t)pp[i].rb & 3) || (pp[i].s_bit && ((uintptr_t)pp[i].s_bit & 3))) vec4 = false;
     size_t lo[kMaxChunks], hi[kMaxChunks];
     for (int m = 0; m < n_chunks; ++m) {
-        lo[m] = (n * m / n_chunks) & ~(size_t)1;
-        hi[m] = (m == n_chunks - 1) ? n : ((n * (m + 1) / n_chunks) & ~(size_t)1);
+        lo[m] = (n * m / n_chunks) & ~(size_t)3;
+        hi[m] = (m == n_chunks - 1) ? n : ((n * (m + 1) / n_chunks) & ~(size_t)3);
     }
     hipStream_t P[2] = { c->s[0], c->s[1] }, Wr = c->s[2];
     hipEvent_t got[kMaxChunks];
+    const bool one_queue = P[0] == P[1] && P[1] == Wr;      // in-order queue: no events needed
 
     // Alg. 2: each party sends the mask half of the XOR sharing of its own share
     for (int m = 0; m < n_chunks; ++m) {
         if (hi[m] <= lo[m]) continue;
-        for (int i = 0; i < 2; ++i)
-            MPC_TRY(wire_words(c, pp[i].r, const_cast<u64*>(pp[1 - i].recv), n, lo[m], hi[m], 1, vec));
-        got[m] = next_event(c);
-        MPC_HIP(c, hipEventRecord(got[m], Wr));
+        MPC_TRY(wire_words(c, pp[0].r, const_cast<u64*>(pp[1].recv), pp[1].r, const_cast<u64*>(pp[0].recv),
+                           n, lo[m], hi[m], 1, vec));
+        if (!one_queue) { got[m] = next_event(c); MPC_HIP(c, hipEventRecord(got[m], Wr)); }
     }
     for (int stage = 0; stage < ST_COUNT; ++stage) {
         const int rows = words_after(stage);
         for (int m = 0; m < n_chunks; ++m) {
             if (hi[m] <= lo[m]) continue;
-            for (int i = 0; i < 2; ++i) {
-                MPC_HIP(c, hipStreamWaitEvent(P[i], got[m], 0));
-                if (i == 0) { if (vec) launch_stage<0, 2>(stage, P[0], pp[0], lo[m], hi[m]);
-                              else     launch_stage<0, 1>(stage, P[0], pp[0], lo[m], hi[m]); }
-                else        { if (vec) launch_stage<1, 2>(stage, P[1], pp[1], lo[m], hi[m]);
-                              else     launch_stage<1, 1>(stage, P[1], pp[1], lo[m], hi[m]); }
+            if (one_queue) {                 // both parties in one launch
+                if (vec4)     launch_stage<4>(stage, P[0], pp[0], pp[1], -1, lo[m], hi[m]);
+                else if (vec) launch_stage<2>(stage, P[0], pp[0], pp[1], -1, lo[m], hi[m]);
+                else          launch_stage<1>(stage, P[0], pp[0], pp[1], -1, lo[m], hi[m]);
                 MPC_HIP(c, hipGetLastError());
-                if (rows >= 0) MPC_TRY(chain(c, P[i], Wr));
-            }
-            if (rows < 0) continue;
-            for (int i = 0; i < 2; ++i) {
-                if (rows == 0) {
-                    hipLaunchKernelGGL(k_wire_bytes, dim3(grid_for(hi[m] - lo[m])), dim3(kThreads), 0, Wr,
-                                       pp[i].sendb, const_cast<u8*>(pp[1 - i].recvb), lo[m], hi[m]);
+            } else {
+                for (int i = 0; i < 2; ++i) {
+                    MPC_HIP(c, hipStreamWaitEvent(P[i], got[m], 0));
+                    if (vec4)     launch_stage<4>(stage, P[i], pp[0], pp[1], i, lo[m], hi[m]);
+                    else if (vec) launch_stage<2>(stage, P[i], pp[0], pp[1], i, lo[m], hi[m]);
+                    else          launch_stage<1>(stage, P[i], pp[0], pp[1], i, lo[m], hi[m]);
                     MPC_HIP(c, hipGetLastError());
-                } else {
-                    MPC_TRY(wire_words(c, pp[i].send, const_cast<u64*>(pp[1 - i].recv), n, lo[m], hi[m], rows, vec));
+                    if (rows >= 0) MPC_TRY(chain(c, P[i], Wr));
                 }
             }
-            got[m] = next_event(c);
-            MPC_HIP(c, hipEventRecord(got[m], Wr));
+            if (rows < 0) continue;
+            if (rows == 0) {
+                hipLaunchKernelGGL(k_wire_bytes, dim3(grid_for(hi[m] - lo[m]), 2), dim3(kThreads), 0, Wr,
+                                   pp[0].sendb, const_cast<u8*>(pp[1].recvb), pp[1].sendb, const_cast<u8*>(pp[0].recvb),
+                                   lo[m], hi[m]);
+                MPC_HIP(c, hipGetLastError());
+            } else {
+                MPC_TRY(wire_words(c, pp[0].send, const_cast<u64*>(pp[1].recv), pp[1].send, const_cast<u64*>(pp[0].recv),
+                                   n, lo[m], hi[m], rows, vec));
+            }
+            if (!one_queue) { got[m] = next_event(c); MPC_HIP(c, hipEventRecord(got[m], Wr)); }
         }
     }
     return MPC_OK;

@@ -191,6 +191,11 @@ class Lane:
     def wait_for(self, other: "Lane"):
         self._check(lib().mpc_ctx_wait(self._h, other._h))
 
+    def use_single_queue(self):
+        """Issue both parties and the wire on party 0's stream (one in-order queue)."""
+        s0 = self.stream(0)
+        self._check(lib().mpc_ctx_set_streams(self._h, c_void_p(s0), c_void_p(s0), c_void_p(s0)))
+
     def stream(self, which: int) -> int:
         return lib().mpc_ctx_stream(self._h, which) or 0
 

@@ -19,9 +19,13 @@ def mpc():
     return m
 
 
-@pytest.fixture()
-def lane(mpc):
+@pytest.fixture(params=["three-streams", "single-queue"])
+def lane(mpc, request):
+    """Both issue modes of a lane: party 0 / party 1 / wire on three streams
+    ordered by events, or everything on one in-order queue (merged launches)."""
     ln = mpc.Lane(0)
+    if request.param == "single-queue":
+        ln.use_single_queue()
     yield ln
     ln.sync()
     ln.close()
