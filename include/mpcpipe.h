@@ -113,6 +113,12 @@ size_t mpc_maxpool_workspace_bytes(int B, int H, int W, int C);
  * 0's stream.  Needs 16*n bytes of workspace. */
 int mpc_open(mpc_ctx* ctx, mpc_cshare s, uint64_t* out_public, size_t n);
 
+/* Share-wise difference out_i = x_i - a_i (shares are linear, Eq. 1); with x a
+ * weight and a the B part of its layer's triple this is the masked weight
+ * that Alg. 3 (line 2-3) broadcasts one layer ahead: follow it with mpc_open
+ * to obtain f_public. */
+int mpc_sub(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_share out, size_t n);
+
 /* --------------------------------------------------- Beaver matmul (Alg. 1) */
 
 /* z = x * y on additive shares with the triple (a, b, c), C = A*B:

@@ -147,6 +147,18 @@ struct RecodeArgs {
     int batch;
 };
 int launch_recode(mpc_ctx* c, hipStream_t st, const RecodeArgs& a);
+constexpr int kMaxRecodeSets = 6;
+struct RecodeBatch { RecodeArgs a[kMaxRecodeSets]; int batch; };
+int launch_recode_multi(mpc_ctx* c, hipStream_t st, const RecodeArgs* sets, int count);
+
+// several element-wise jobs in one launch (single-queue lanes)
+constexpr int kMaxSegs = 4;
+struct SubSeg { const u64* x; const u64* a; u64* out; size_t n; int vec; };
+struct SubBatch { SubSeg s[kMaxSegs]; };
+struct CopySeg { const u8* src; u8* dst; size_t bytes; int vec; };
+struct CopyBatch { CopySeg s[kMaxSegs]; };
+int launch_sub_multi(mpc_ctx* c, hipStream_t st, const SubSeg* segs, int count);
+int launch_copy_multi(mpc_ctx* c, hipStream_t st, const CopySeg* segs, int count);
 
 // ---- limb GEMM (limb_gemm.hip) --------------------------------------------------
 struct GemmSeg {

@@ -159,6 +159,15 @@ int mpc_open(mpc_ctx* c, mpc_cshare s, uint64_t* out, size_t n)
     return MPC_OK;
 }
 
+int mpc_sub(mpc_ctx* c, mpc_cshare x, mpc_cshare a, mpc_share out, size_t n)
+{
+    if (!c || n == 0) return MPC_EINVAL;
+    for (int i = 0; i < 2; ++i) if (!x.p[i] || !a.p[i] || !out.p[i]) return MPC_EINVAL;
+    MPC_TRY(lane_join(c));
+    for (int i = 0; i < 2; ++i) MPC_TRY(launch_sub(c, c->s[i], x.p[i], a.p[i], out.p[i], n));
+    return MPC_OK;
+}
+
 int mpc_truncate(mpc_ctx* c, mpc_share z, size_t n, int bits)
 {
     if (!c || !z.p[0] || !z.p[1] || n == 0 || bits < 0 || bits > 63) return MPC_EINVAL;

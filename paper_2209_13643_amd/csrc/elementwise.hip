@@ -90,10 +90,8 @@ __device__ __forceinline__ u64 balanced_digits(u64 x)
 // One thread recodes one (row, k-block): 16 ring words in, one 16-byte unit
 // out per digit plane.  Consecutive lanes take consecutive rows so that the
 // plane stores are contiguous.
-__global__ __launch_bounds__(kThreads) void k_recode(RecodeArgs a)
+__device__ __forceinline__ void recode_body(const RecodeArgs& a, int tap /* == ntaps: zero padding block(s) */, int b)
 {
-    const int tap = blockIdx.y;                       // == ntaps: zero padding block(s)
-    const int b = blockIdx.z;
     const u64* src = a.src + (size_t)b * a.src_batch_stride;
     const u64* src2 = a.src2 ? a.src2 + (size_t)b * a.src_batch_stride : nullptr;
     const u64* src3 = a.src3 ? a.src3 + (size_t)b * a.src_batch_stride : nullptr;
@@ -133,6 +131,54 @@ __global__ __launch_bounds__(kThreads) void k_recode(RecodeArgs a)
             }
             *reinterpret_cast<uint4*>(out + (size_t)d * a.digit_stride) = make_uint4(w[0], w[1], w[2], w[3]);
         }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_recode(RecodeArgs a)
+{
+    recode_body(a, blockIdx.y, blockIdx.z);
+}
+
+// Several recodings in one launch: blockIdx.z = set * batch + batch item.
+__global__ __launch_bounds__(kThreads) void k_recode_multi(RecodeBatch rb)
+{
+    const int set = blockIdx.z / rb.batch, b = blockIdx.z - set * rb.batch;
+    const RecodeArgs& a = rb.a[set];
+    const int taps = a.ntaps + (a.KB_total > a.ntaps * a.KB_tap ? 1 : 0);
+    if ((int)blockIdx.y < taps) recode_body(a, blockIdx.y, b);
+}
+
+// Several element-wise subtractions / copies in one launch: blockIdx.y = segment.
+__global__ __launch_bounds__(kThreads) void k_sub_multi(SubBatch sb)
+{
+    const SubSeg& q = sb.s[blockIdx.y];
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    if (q.vec) {
+        const size_t n2 = q.n / 2;
+        const u64x2* x2 = reinterpret_cast<const u64x2*>(q.x);
+        const u64x2* y2 = reinterpret_cast<const u64x2*>(q.a);
+        u64x2* o2 = reinterpret_cast<u64x2*>(q.out);
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n2; i += stride) {
+            u64x2 p = x2[i], r = y2[i];
+            p.a -= r.a; p.b -= r.b;
+            o2[i] = p;
+        }
+        if ((q.n & 1) && blockIdx.x == 0 && threadIdx.x == 0) q.out[q.n - 1] = q.x[q.n - 1] - q.a[q.n - 1];
+    } else {
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < q.n; i += stride) q.out[i] = q.x[i] - q.a[i];
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_copy_multi(CopyBatch cb)
+{
+    const CopySeg& q = cb.s[blockIdx.y];
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    if (q.vec) {
+        const uint4* s4 = reinterpret_cast<const uint4*>(q.src); uint4* d4 = reinterpret_cast<uint4*>(q.dst);
+        const size_t n16 = q.bytes / 16;
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) d4[i] = s4[i];
+    } else {
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < q.bytes; i += stride) q.dst[i] = q.src[i];
     }
 }
 
@@ -190,6 +236,55 @@ int launch_fill_zero(mpc_ctx* c, hipStream_t st, void* dst, size_t bytes)
 int launch_truncate(mpc_ctx* c, hipStream_t st, u64* z, size_t n, int bits, int party)
 {
     hipLaunchKernelGGL(k_truncate, dim3(grid_for(n)), dim3(kThreads), 0, st, z, n, bits, party);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+int launch_recode_multi(mpc_ctx* c, hipStream_t st, const RecodeArgs* sets, int count)
+{
+    if (count < 1 || count > kMaxRecodeSets) return MPC_EINVAL;
+    RecodeBatch rb{};
+    size_t items = 0; int taps = 0;
+    for (int i = 0; i < count; ++i) {
+        rb.a[i] = sets[i];
+        if (sets[i].batch != sets[0].batch) return MPC_EINVAL;
+        const size_t it = (size_t)sets[i].KB_tap * sets[i].plane_rows;
+        if (it > items) items = it;
+        const int t = sets[i].ntaps + (sets[i].KB_total > sets[i].ntaps * sets[i].KB_tap ? 1 : 0);
+        if (t > taps) taps = t;
+    }
+    rb.batch = sets[0].batch;
+    if ((size_t)count * rb.batch > 65535) return MPC_EINVAL;
+    dim3 grid(grid_for(items), taps, count * rb.batch);
+    hipLaunchKernelGGL(k_recode_multi, grid, dim3(kThreads), 0, st, rb);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+int launch_sub_multi(mpc_ctx* c, hipStream_t st, const SubSeg* segs, int count)
+{
+    if (count < 1 || count > kMaxSegs) return MPC_EINVAL;
+    SubBatch sb{}; size_t nmax = 0;
+    for (int i = 0; i < count; ++i) {
+        sb.s[i] = segs[i];
+        sb.s[i].vec = aligned16(segs[i].x) && aligned16(segs[i].a) && aligned16(segs[i].out);
+        if (segs[i].n > nmax) nmax = segs[i].n;
+    }
+    hipLaunchKernelGGL(k_sub_multi, dim3(grid_for(nmax / 2 + 1), count), dim3(kThreads), 0, st, sb);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+int launch_copy_multi(mpc_ctx* c, hipStream_t st, const CopySeg* segs, int count)
+{
+    if (count < 1 || count > kMaxSegs) return MPC_EINVAL;
+    CopyBatch cb{}; size_t bmax = 0;
+    for (int i = 0; i < count; ++i) {
+        cb.s[i] = segs[i];
+        cb.s[i].vec = aligned16(segs[i].src) && aligned16(segs[i].dst) && segs[i].bytes % 16 == 0;
+        if (segs[i].bytes > bmax) bmax = segs[i].bytes;
+    }
+    hipLaunchKernelGGL(k_copy_multi, dim3(grid_for(bmax / 16 + 1), count), dim3(kThreads), 0, st, cb);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
 }

@@ -153,7 +153,70 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
 
     MPC_TRY(lane_join(c));
     const int pi = prof_begin(c, MPC_PROF_LINEAR, P0);
-    MPC_TRY(launch_fill_zero(c, P0, w.zero, 256));
+
+    if (P0 == P1 && P1 == Wr) {
+        // One in-order queue: same steps, same order, but jobs of equal kind share a launch.
+        GemmArgs g{};
+        fill_geom(s, w, g);
+        g.nparty = 2;
+        if ((size_t)n_chunks > s.nx) n_chunks = (int)s.nx;
+        for (int ch = 0; ch < n_chunks; ++ch) {
+            size_t lo = (s.nx * ch / n_chunks) & ~(size_t)1, hi = (s.nx * (ch + 1) / n_chunks) & ~(size_t)1;
+            if (ch == n_chunks - 1) hi = s.nx;
+            if (hi <= lo) continue;
+            SubSeg sub[4]; CopySeg cp[4]; int ns = 0;
+            for (int i = 0; i < 2; ++i) {
+                sub[ns] = SubSeg{ x.p[i] + lo, a.p[i] + lo, w.se[i] + lo, hi - lo, 0 };
+                cp[ns] = CopySeg{ (const u8*)(w.se[i] + lo), (u8*)(w.re[1 - i] + lo), (hi - lo) * sizeof(u64), 0 };
+                ++ns;
+            }
+            if (!f_public && ch == 0)
+                for (int i = 0; i < 2; ++i) {
+                    sub[ns] = SubSeg{ y.p[i], b.p[i], w.sf[i], s.nw, 0 };
+                    cp[ns] = CopySeg{ (const u8*)w.sf[i], (u8*)w.rf[1 - i], s.nw * sizeof(u64), 0 };
+                    ++ns;
+                }
+            MPC_TRY(launch_sub_multi(c, P0, sub, ns));       // Alg. 1: mask
+            MPC_TRY(launch_copy_multi(c, P0, cp, ns));       // Alg. 1: exchange
+        }
+        const u64* f0 = f_public ? f_public : w.sf[0];
+        const u64* f1 = f_public ? nullptr : w.rf[0];
+        RecodeArgs rc[6];
+        rc[0] = recode_left(s, a.p[0], nullptr, w.pl_a[0]);
+        rc[1] = recode_left(s, a.p[1], nullptr, w.pl_a[1]);
+        rc[2] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
+        rc[3] = recode_right(s, f0, f1, nullptr, w.pr_f);
+        rc[4] = recode_right(s, b.p[0], f0, f1, w.pr_b[0]);
+        rc[5] = recode_left(s, w.se[0], w.re[0], w.pl_e);
+        if (two_phase && f_public) {
+            MPC_TRY(launch_recode_multi(c, P0, rc, 6));
+            g.nseg = 1;
+            for (int i = 0; i < 2; ++i) {
+                g.seg[i][0] = make_seg(s, w.pl_a[i], w.pr_f);
+                g.addend[i] = nullptr; g.addend2[i] = nullptr; g.out[i] = z.p[i];
+            }
+            g.trunc_bits = 0;
+            MPC_TRY(launch_limb_gemm(c, P0, g));
+            for (int i = 0; i < 2; ++i) {
+                g.seg[i][0] = make_seg(s, w.pl_e, w.pr_b[i]);
+                g.addend[i] = cc.p[i]; g.addend2[i] = z.p[i];
+            }
+            g.trunc_bits = trunc;
+            MPC_TRY(launch_limb_gemm(c, P0, g));
+        } else {
+            MPC_TRY(launch_recode_multi(c, P0, rc, 6));
+            g.nseg = 2;
+            for (int i = 0; i < 2; ++i) {
+                g.seg[i][0] = make_seg(s, w.pl_e, w.pr_b[i]);
+                g.seg[i][1] = make_seg(s, w.pl_a[i], w.pr_f);
+                g.addend[i] = cc.p[i]; g.addend2[i] = nullptr; g.out[i] = z.p[i];
+            }
+            g.trunc_bits = trunc;
+            MPC_TRY(launch_limb_gemm(c, P0, g));
+        }
+        prof_end(c, MPC_PROF_LINEAR, pi, P0);
+        return MPC_OK;
+    }
 
     // -- Alg. 1 line 1-2 / Alg. 3 line 2-3: mask and start the exchange, chunk by chunk
     if (!f_public) {
@@ -245,7 +308,6 @@ int ring_product(mpc_ctx* c, const LinearShape& s, const u64* L, const u64* R, u
     if (!w.ok) return MPC_ENOMEM;
     hipStream_t P0 = c->s[0];
     MPC_TRY(lane_join(c));
-    MPC_TRY(launch_fill_zero(c, P0, w.zero, 256));
     MPC_TRY(launch_recode(c, P0, recode_left(s, L, nullptr, w.pl_e)));
     MPC_TRY(launch_recode(c, P0, recode_right(s, R, nullptr, nullptr, w.pr_f)));
     GemmArgs g{};

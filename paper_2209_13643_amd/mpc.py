@@ -39,7 +39,7 @@ EXPORTS = [
     "mpc_ctx_sync", "mpc_ctx_wait", "mpc_last_hip_error", "mpc_strerror",
     "mpc_ctx_set_profiling", "mpc_ctx_profile", "mpc_ctx_profile_reset",
     "mpc_matmul_workspace_bytes", "mpc_conv2d_workspace_bytes", "mpc_relu_workspace_bytes",
-    "mpc_maxpool_workspace_bytes", "mpc_open", "mpc_beaver_matmul", "mpc_conv2d", "mpc_truncate",
+    "mpc_maxpool_workspace_bytes", "mpc_open", "mpc_sub", "mpc_beaver_matmul", "mpc_conv2d", "mpc_truncate",
     "mpc_relu", "mpc_maxpool2x2", "mpc_ring_matmul", "mpc_ring_conv2d",
 ]
 
@@ -71,6 +71,7 @@ def lib():
     L.mpc_relu_workspace_bytes.argtypes = [c_size_t]; L.mpc_relu_workspace_bytes.restype = c_size_t
     L.mpc_maxpool_workspace_bytes.argtypes = [c_int] * 4; L.mpc_maxpool_workspace_bytes.restype = c_size_t
     L.mpc_open.argtypes = [c_void_p, CShare, _P64, c_size_t]
+    L.mpc_sub.argtypes = [c_void_p, CShare, CShare, CShare, c_size_t]
     L.mpc_beaver_matmul.argtypes = [c_void_p] + [CShare] * 6 + [c_int] * 4 + [_P64, c_int, c_int]
     L.mpc_conv2d.argtypes = [c_void_p] + [CShare] * 6 + [c_int] * 9 + [_P64, c_int, c_int]
     L.mpc_truncate.argtypes = [c_void_p, CShare, c_size_t, c_int]
@@ -217,6 +218,11 @@ class Lane:
         self.reserve(2 * (n * 8 + 256))
         out = torch.empty_like(s[0])
         self._check(lib().mpc_open(self._h, _share(s), _p64(out), n))
+        return out
+
+    def sub(self, x, a):
+        out = (torch.empty_like(x[0]), torch.empty_like(x[1]))
+        self._check(lib().mpc_sub(self._h, _share(x), _share(a), _share(out), x[0].numel()))
         return out
 
     def beaver_matmul(self, x, y, a, b, c, f_public=None, n_chunks=1, flags=MPC_TRUNCATE, out=None):

@@ -55,3 +55,53 @@ def deal_conv(rng, B, H, W, Cin, Cout, KH, KW, pad, stride, x_std=None, w_std=No
 def oracle_conv(d, truncate_bits=16):
     z = oracle.beaver_conv2d(d["x"], d["y"], d["a"], d["b"], d["c"], d["pad"], d["stride"])
     return oracle.truncate(z, truncate_bits) if truncate_bits else z
+
+
+# ----------------------------------------------------------- whole networks (host)
+def deal_network_host(rng, layers, weights=None):
+    """Per-layer shares / triples / material as numpy arrays for one micro-batch.
+    `weights`: list of (W, (w0, w1)) to reuse across micro-batches, or None to draw them."""
+    states, wout = [], []
+    for li, L in enumerate(layers):
+        conv = isinstance(L, synth.Conv)
+        wshape = (L.KH, L.KW, L.Cin, L.Cout) if conv else (L.K, L.N)
+        if weights is None:
+            W = synth.normal_fixed(rng, wshape, L.w_std); wsh = synth.share_additive(rng, W)
+        else:
+            W, wsh = weights[li]
+        wout.append((W, wsh))
+        if conv:
+            prod = lambda A, Bf, L=L: oracle.ring_conv2d(A, Bf, L.pad, L.stride)
+            a, b, c = synth.deal_product_triple(rng, (L.B, L.H, L.W, L.Cin), wshape, prod)
+            n_out = L.B * L.Ho * L.Wo * L.Cout
+        else:
+            a, b, c = synth.deal_product_triple(rng, (L.M, L.K), wshape, oracle.ring_matmul)
+            n_out = L.M * L.N
+        st = dict(W=W, w=wsh, a=a, b=b, c=c, relu=None, pool1=None, pool2=None)
+        if L.relu:
+            st["relu"] = synth.deal_relu_material(rng, n_out)
+        if conv and L.pool:
+            n_pool = L.B * (L.Ho // 2) * (L.Wo // 2) * L.Cout
+            st["pool1"] = synth.deal_relu_material(rng, 2 * n_pool)
+            st["pool2"] = synth.deal_relu_material(rng, n_pool)
+        states.append(st)
+    return states, wout
+
+
+def oracle_forward(layers, states, x):
+    """Oracle run of the whole network; returns the list of every layer's output shares."""
+    outs = []
+    for L, st in zip(layers, states):
+        if isinstance(L, synth.Conv):
+            xs = (x[0].reshape(L.B, L.H, L.W, L.Cin), x[1].reshape(L.B, L.H, L.W, L.Cin))
+            z = oracle.truncate(oracle.beaver_conv2d(xs, st["w"], st["a"], st["b"], st["c"], L.pad, L.stride), 16)
+        else:
+            xs = (x[0].reshape(L.M, L.K), x[1].reshape(L.M, L.K))
+            z = oracle.truncate(oracle.beaver_matmul(xs, st["w"], st["a"], st["b"], st["c"]), 16)
+        if st["relu"] is not None:
+            z = oracle.relu(z, st["relu"]).y
+        if st["pool1"] is not None:
+            z = oracle.maxpool2x2(z, st["pool1"], st["pool2"])
+        outs.append(z)
+        x = z
+    return outs
