@@ -137,7 +137,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[1] vgg16-cifar-conv-block: batch 64, 128x16x16, conv3x3 128->128 pad 1 "
                                "= Beaver GEMM [16384x1152]x[1152x128] + truncation + secure ReLU on 2097152 elements",
-                   "parties": 2, "frac_bits": 16, "n_chunks": 1, "lane": "single in-order queue",
+                   "parties": 2, "frac_bits": 16, "n_chunks": 1, "relu_chunks": "auto (about 2^20 elements each)", "lane": "single in-order queue",
                    "ms_beaver_conv_call": lin_ms, "ms_gemm_kernel": gemm_ms, "ms_relu_call": relu_ms,
                    "max_abs_err_vs_float64": err},
         "roofline": {"kernel": "k_limb_gemm<2,2,true> (both parties, [e|a_i] x [b_i';f], fused add-c + truncation)",

@@ -179,7 +179,10 @@ typedef struct {
  *   -> y = x * (1 - s) by element-wise Alg. 1 (no rescale).
  * n_chunks >= 1 tiles every round's exchange as in Alg. 4: all chunks' mask
  *   kernels and wire copies are issued back to back, then each chunk's gate
- *   evaluation waits only for its own copy.  Results do not depend on it.
+ *   evaluation waits only for its own copy.  On a lane whose three streams
+ *   are one queue the chunks run one after the other through all rounds
+ *   instead (same element ranges, same results).  n_chunks = 0 lets the
+ *   library choose.  Results do not depend on it.
  * s_bit[i] (n bytes) / s_arith[i] (n words): optional per-party outputs of
  *   the sign's XOR share and additive share; NULL to skip. */
 int mpc_relu(mpc_ctx* ctx, mpc_cshare x, const mpc_relu_material* mat, mpc_share y,

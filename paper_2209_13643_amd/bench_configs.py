@@ -1,0 +1,134 @@
+"""Per-config measurements on one MI355X: `python -m paper_2209_13643_amd.bench_configs [indices]`.
+
+For every workload of `synth.CONFIGS` the secure layers are dealt on the device,
+run a few times on a single-queue lane, and reported per layer: Beaver GEMM call
+time, secure MACs/s, int8-MFMA fraction of the GEMM kernel, secure ReLU elems/s
+and HBM fraction.  Config 4 (VGG16 on CIFAR shapes, batch 128 as 4 micro-batches
+of 32) is additionally timed serial vs inter-batch pipelined (Sec. 4.3).
+"""
+from __future__ import annotations
+
+import json
+import sys
+import time
+
+import torch
+
+from . import dealer, mpc, pipeline, synth
+
+INT8_PEAK = 5.0e15
+HBM_PEAK = 8.0e12
+RELU_BYTES = 3514
+
+
+def layer_macs(L):
+    if isinstance(L, synth.Conv):
+        M, K, N = L.gemm_mkn
+        return M * K * N
+    return L.M * L.K * L.N * max(L.batch, 1)
+
+
+def bench_layers(idx: int, reps: int = 5):
+    wl = synth.CONFIGS[idx]()
+    lane = mpc.Lane(0); lane.use_single_queue()
+    dev = lane.device
+    g = dealer.gen(synth.BASE_SEED + idx, dev)
+    rows = []
+    for L in wl.layers:
+        if isinstance(L, synth.Conv):
+            d = dealer.conv_layer(lane, g, L.B, L.H, L.W, L.Cin, L.Cout, L.KH, L.KW, L.pad, L.stride, L.x_std, L.w_std)
+            run = lambda: lane.conv2d(d["x"], d["w"], d["a"], d["b"], d["c"], L.pad, L.stride, out=z)
+            n_out = L.B * L.Ho * L.Wo * L.Cout
+            z = tuple(torch.empty((L.B, L.Ho, L.Wo, L.Cout), dtype=torch.int64, device=dev) for _ in range(2))
+            shape = "x".join(map(str, L.gemm_mkn))
+        else:
+            d = dealer.matmul_layer(lane, g, L.M, L.K, L.N, L.x_std, L.w_std, batch=L.batch if L.batch > 1 else None)
+            run = lambda: lane.beaver_matmul(d["x"], d["w"], d["a"], d["b"], d["c"], out=z)
+            n_out = L.M * L.N * max(L.batch, 1)
+            z = (torch.empty_like(d["c"][0]), torch.empty_like(d["c"][1]))
+            shape = f"{L.M}x{L.K}x{L.N}" + (f" x{L.batch}" if L.batch > 1 else "")
+        mat = dealer.relu_material(g, n_out, dev) if L.relu else None
+        y = (torch.empty_like(z[0]), torch.empty_like(z[1])) if L.relu else None
+        for _ in range(2):
+            run()
+            if mat: lane.relu(z, mat, out=y)
+        lane.sync(); lane.set_profiling(True); lane.profile_reset()
+        for _ in range(reps):
+            run()
+            if mat: lane.relu(z, mat, out=y)
+        lane.sync(); lane.set_profiling(False)
+        gk, gn = lane.profile(mpc.PROF_GEMM_KERNEL); lin, ln = lane.profile(mpc.PROF_LINEAR)
+        macs = layer_macs(L)
+        row = dict(layer=L.name, gemm=shape, call_ms=lin / ln, kernel_ms=gk / gn,
+                   secure_macs_per_s=macs / (lin / ln * 1e-3), mfma_frac=288 * macs / (gk / gn * 1e-3) / INT8_PEAK)
+        if mat:
+            rl, rn = lane.profile(mpc.PROF_RELU)
+            row.update(relu_n=n_out, relu_ms=rl / rn, relu_elems_per_s=n_out / (rl / rn * 1e-3),
+                       hbm_frac=RELU_BYTES * n_out / (rl / rn * 1e-3) / HBM_PEAK)
+        rows.append(row)
+        del d, mat, z, y
+        torch.cuda.empty_cache()
+    lane.close()
+    return wl.name, rows
+
+
+def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3):
+    """Config 4: serial (one lane, micro-batches one after the other) vs pipelined (one lane each)."""
+    wl = synth.config_vgg16_pipeline(micro_batch)
+    layers = wl.layers
+    lanes = [mpc.Lane(0) for _ in range(n_mb)]
+    for ln in lanes:
+        ln.use_single_queue()
+    dev = lanes[0].device
+    g = dealer.gen(synth.BASE_SEED + wl.index, dev)
+    weights = pipeline.deal_weights(g, layers, dev)
+    states, xs = [], []
+    for m in range(n_mb):
+        states.append(pipeline.deal_microbatch(lanes[m], g, layers, weights))
+        X = dealer.normal_fixed(g, (micro_batch, 32, 32, 3), 1.0, dev)
+        xs.append(dealer.share(g, X))
+        pipeline.preopen_weights(lanes[m], states[m])
+    res = {}
+    for mode in ("serial", "pipelined"):
+        best = None
+        for _ in range(reps + 1):
+            keep = []
+            torch.cuda.synchronize(); t0 = time.perf_counter()
+            if mode == "serial":
+                for m in range(n_mb):
+                    pipeline.forward(lanes[0], layers, states[m], xs[m], keep)
+                lanes[0].sync()
+            else:
+                pipeline.forward_pipelined(lanes, layers, states, xs, keep)
+                for ln in lanes:
+                    ln.sync()
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+            del keep
+        res[mode] = dict(ms=best * 1e3, images_per_s=n_mb * micro_batch / best)
+    res["macs_per_image"] = sum(layer_macs(L) for L in layers) // micro_batch
+    for ln in lanes:
+        ln.close()
+    return res
+
+
+def main(argv):
+    which = [int(a) for a in argv] if argv else list(range(len(synth.CONFIGS)))
+    for idx in which:
+        name, rows = bench_layers(idx) if idx != 4 else bench_layers(4, reps=3)
+        print(f"== config {idx}: {name}")
+        for r in rows:
+            line = (f"  {r['layer']:10s} {r['gemm']:22s} call {r['call_ms']:8.3f} ms  {r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s"
+                    f"  kernel {r['kernel_ms']:8.3f} ms  mfma {100 * r['mfma_frac']:5.1f}%")
+            if "relu_ms" in r:
+                line += f"  | relu {r['relu_n']:9d} el {r['relu_ms']:7.3f} ms {r['relu_elems_per_s'] / 1e9:5.2f} G/s hbm {100 * r['hbm_frac']:5.1f}%"
+            print(line, flush=True)
+        if idx == 4:
+            p = bench_pipeline()
+            print(f"  inter-batch pipeline, batch 128 = 4 x 32: serial {p['serial']['ms']:.2f} ms ({p['serial']['images_per_s']:.0f} img/s), "
+                  f"pipelined {p['pipelined']['ms']:.2f} ms ({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)
+        print(json.dumps({"config": idx, "layers": rows}), file=sys.stderr)
+
+
+if __name__ == "__main__":
+    main(sys.argv[1:])

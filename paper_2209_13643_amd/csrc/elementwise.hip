@@ -139,6 +139,72 @@ __global__ __launch_bounds__(kThreads) void k_recode(RecodeArgs a)
     recode_body(a, blockIdx.y, blockIdx.z);
 }
 
+// Recoding of a matrix whose k index is contiguous in memory (left operands,
+// NHWC activations): a workgroup takes a 64-row x 64-k tile, reads it with
+// lanes along k (coalesced 16-byte loads), scatters the digits into LDS in
+// plane order, and writes each plane's 16-byte units with lanes along rows
+// (coalesced again).  blockIdx = (row tile, group of 4 k blocks, set*batch).
+__global__ __launch_bounds__(kThreads) void k_recode_rows(RecodeBatch rb)
+{
+    __shared__ uint32_t tile[8][4][64][4];
+    const int set = blockIdx.z / rb.batch, b = blockIdx.z - set * rb.batch;
+    const RecodeArgs& a = rb.a[set];
+    const int row0 = blockIdx.x * 64, kb0 = blockIdx.y * 4;
+    if (row0 >= a.plane_rows || kb0 >= a.KB_total) return;      // uniform per workgroup
+    const u64* src = a.src + (size_t)b * a.src_batch_stride;
+    const u64* src2 = a.src2 ? a.src2 + (size_t)b * a.src_batch_stride : nullptr;
+    const u64* src3 = a.src3 ? a.src3 + (size_t)b * a.src_batch_stride : nullptr;
+    u8* dst = a.dst + (size_t)b * a.dst_batch_stride;
+    const bool vec_ok = (a.row_stride % 2 == 0) && (((uintptr_t)src & 15) == 0) &&
+                        (!src2 || ((uintptr_t)src2 & 15) == 0) && (!src3 || ((uintptr_t)src3 & 15) == 0);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int seg = threadIdx.x + 256 * p;
+        const int row = seg >> 4, s4 = seg & 15;
+        const int r = row0 + row, k = kb0 * 16 + s4 * 4;
+        u64 v[4] = { 0, 0, 0, 0 };
+        if (r < a.rows && k < a.K) {
+            const size_t idx = (size_t)r * a.row_stride + k;
+            if (vec_ok && k + 3 < a.K) {
+                const u64x2 p0 = *reinterpret_cast<const u64x2*>(src + idx), p1 = *reinterpret_cast<const u64x2*>(src + idx + 2);
+                v[0] = p0.a; v[1] = p0.b; v[2] = p1.a; v[3] = p1.b;
+                if (src2) { const u64x2 q0 = *reinterpret_cast<const u64x2*>(src2 + idx), q1 = *reinterpret_cast<const u64x2*>(src2 + idx + 2);
+                            v[0] += q0.a; v[1] += q0.b; v[2] += q1.a; v[3] += q1.b; }
+                if (src3) { const u64x2 q0 = *reinterpret_cast<const u64x2*>(src3 + idx), q1 = *reinterpret_cast<const u64x2*>(src3 + idx + 2);
+                            v[0] += q0.a; v[1] += q0.b; v[2] += q1.a; v[3] += q1.b; }
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (k + t < a.K) {
+                        v[t] = src[idx + t];
+                        if (src2) v[t] += src2[idx + t];
+                        if (src3) v[t] += src3[idx + t];
+                    }
+            }
+        }
+        u64 dg[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) dg[t] = balanced_digits(v[t]);
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) w |= (uint32_t)((dg[t] >> (8 * d)) & 0xff) << (8 * t);
+            tile[d][s4 >> 2][row][s4 & 3] = w;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int u = threadIdx.x + 256 * q;
+        const int d = u >> 8, kbl = (u >> 6) & 3, row = u & 63;
+        if (row0 + row < a.plane_rows && kb0 + kbl < a.KB_total) {
+            const uint4 val = *reinterpret_cast<const uint4*>(&tile[d][kbl][row][0]);
+            *reinterpret_cast<uint4*>(dst + (size_t)d * a.digit_stride + ((size_t)(kb0 + kbl) * a.plane_rows + row0 + row) * 16) = val;
+        }
+    }
+}
+
 // Several recodings in one launch: blockIdx.z = set * batch + batch item.
 __global__ __launch_bounds__(kThreads) void k_recode_multi(RecodeBatch rb)
 {
@@ -243,6 +309,24 @@ int launch_truncate(mpc_ctx* c, hipStream_t st, u64* z, size_t n, int bits, int 
 int launch_recode_multi(mpc_ctx* c, hipStream_t st, const RecodeArgs* sets, int count)
 {
     if (count < 1 || count > kMaxRecodeSets) return MPC_EINVAL;
+    bool rows_kind = true;          // every set a plain matrix with contiguous k?
+    for (int i = 0; i < count; ++i)
+        if (sets[i].k_stride != 1 || sets[i].ntaps != 1 || sets[i].batch != sets[0].batch) rows_kind = false;
+    if (rows_kind) {
+        RecodeBatch rb{};
+        int rows = 0, kb = 0;
+        for (int i = 0; i < count; ++i) {
+            rb.a[i] = sets[i];
+            if (sets[i].plane_rows > rows) rows = sets[i].plane_rows;
+            if (sets[i].KB_total > kb) kb = sets[i].KB_total;
+        }
+        rb.batch = sets[0].batch;
+        if ((size_t)count * rb.batch > 65535 || (kb + 3) / 4 > 65535) return MPC_EINVAL;
+        dim3 grid((rows + 63) / 64, (kb + 3) / 4, count * rb.batch);
+        hipLaunchKernelGGL(k_recode_rows, grid, dim3(kThreads), 0, st, rb);
+        MPC_HIP(c, hipGetLastError());
+        return MPC_OK;
+    }
     RecodeBatch rb{};
     size_t items = 0; int taps = 0;
     for (int i = 0; i < count; ++i) {
@@ -291,6 +375,7 @@ int launch_copy_multi(mpc_ctx* c, hipStream_t st, const CopySeg* segs, int count
 
 int launch_recode(mpc_ctx* c, hipStream_t st, const RecodeArgs& a)
 {
+    if (a.k_stride == 1 && a.ntaps == 1) return launch_recode_multi(c, st, &a, 1);
     const bool has_pad = a.KB_total > a.ntaps * a.KB_tap;
     const size_t items = (size_t)a.KB_tap * a.plane_rows;
     dim3 grid(grid_for(items), a.ntaps + (has_pad ? 1 : 0), a.batch);

@@ -296,26 +296,46 @@ void k_limb_gemm(GemmArgs g)
     for (; t + NS < T; ++t) step(std::true_type{}, t);
     for (; t < T; ++t) step(std::false_type{}, t);
 
-    // ---- epilogue: recombine, add, truncate, store
+    // ---- epilogue: recombine, add, truncate, store.  The addend loads are
+    // issued unconditionally (indices clamped into the matrix) and all at once
+    // per 32-column half, so their latency is paid once, not once per element.
     const u64* addend = g.addend[party] ? g.addend[party] + (size_t)bidx * g.out_bstride : nullptr;
     const u64* addend2 = g.addend2[party] ? g.addend2[party] + (size_t)bidx * g.out_bstride : nullptr;
     u64* out = g.out[party] + (size_t)bidx * g.out_bstride;
+    const int rbase = m0 + wm * 32 + g2 * 4;
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
         const int col = n0 + wn * 64 + c * 32 + i32;
+        const int colc = col < g.N ? col : g.N - 1;
+        u64 add[16];
+        if (addend) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = rbase + (v >> 2) * 8 + (v & 3);
+                const int rowc = row < g.M ? row : g.M - 1;
+                add[v] = addend[(size_t)rowc * g.N + colc];
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) add[v] = 0;
+        }
+        if (addend2) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = rbase + (v >> 2) * 8 + (v & 3);
+                const int rowc = row < g.M ? row : g.M - 1;
+                add[v] += addend2[(size_t)rowc * g.N + colc];
+            }
+        }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int row = m0 + wm * 32 + (v >> 2) * 8 + g2 * 4 + (v & 3);
+            const int row = rbase + (v >> 2) * 8 + (v & 3);
             u64 z = 0;
 #pragma unroll
-            for (int s = 0; s < 8; ++s) z += (u64)(long long)acc[c][s][v] << (8 * s);
-            if (row < g.M && col < g.N) {
-                const size_t idx = (size_t)row * g.N + col;
-                if (addend) z += addend[idx];
-                if (addend2) z += addend2[idx];
-                if (g.trunc_bits) z = party == 0 ? (z >> g.trunc_bits) : (u64)0 - (((u64)0 - z) >> g.trunc_bits);
-                out[idx] = z;
-            }
+            for (int s = 7; s >= 0; --s) z = (z << 8) + (u64)(long long)acc[c][s][v];
+            z += add[v];
+            if (g.trunc_bits) z = party == 0 ? (z >> g.trunc_bits) : (u64)0 - (((u64)0 - z) >> g.trunc_bits);
+            if (row < g.M && col < g.N) out[(size_t)row * g.N + col] = z;
         }
     }
 }
@@ -351,6 +371,8 @@ int launch_limb_gemm(mpc_ctx* c, hipStream_t st, const GemmArgs& g)
             if (g.seg[p][s].KB <= 0 || g.seg[p][s].KB % KS) return MPC_EINVAL;
     // per-lane byte offsets inside one k block of a plane are 32-bit
     if ((long long)g.rows_L * 16 >= (1ll << 32) || (long long)g.N * 16 >= (1ll << 32)) return MPC_EINVAL;
-    if (g.conv.enabled) return launch_cfg<2, 2, true>(c, st, g);
-    return launch_cfg<2, 2, false>(c, st, g);
+    // 64x128 workgroup tiles, or 128x64 when a second 64-column half would be empty
+    const bool narrow = ((g.N - 1) % 128) < 64 && (g.N <= 64 || g.M >= 4096);
+    if (g.conv.enabled) return narrow ? launch_cfg<4, 1, true>(c, st, g) : launch_cfg<2, 2, true>(c, st, g);
+    return narrow ? launch_cfg<4, 1, false>(c, st, g) : launch_cfg<2, 2, false>(c, st, g);
 }

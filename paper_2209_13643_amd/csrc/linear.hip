@@ -181,15 +181,16 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         }
         const u64* f0 = f_public ? f_public : w.sf[0];
         const u64* f1 = f_public ? nullptr : w.rf[0];
-        RecodeArgs rc[6];
-        rc[0] = recode_left(s, a.p[0], nullptr, w.pl_a[0]);
-        rc[1] = recode_left(s, a.p[1], nullptr, w.pl_a[1]);
-        rc[2] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
-        rc[3] = recode_right(s, f0, f1, nullptr, w.pr_f);
-        rc[4] = recode_right(s, b.p[0], f0, f1, w.pr_b[0]);
-        rc[5] = recode_left(s, w.se[0], w.re[0], w.pl_e);
+        RecodeArgs rl[3], rr[3];
+        rl[0] = recode_left(s, a.p[0], nullptr, w.pl_a[0]);
+        rl[1] = recode_left(s, a.p[1], nullptr, w.pl_a[1]);
+        rl[2] = recode_left(s, w.se[0], w.re[0], w.pl_e);
+        rr[0] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
+        rr[1] = recode_right(s, f0, f1, nullptr, w.pr_f);
+        rr[2] = recode_right(s, b.p[0], f0, f1, w.pr_b[0]);
+        MPC_TRY(launch_recode_multi(c, P0, rl, 3));
+        MPC_TRY(launch_recode_multi(c, P0, rr, 3));
         if (two_phase && f_public) {
-            MPC_TRY(launch_recode_multi(c, P0, rc, 6));
             g.nseg = 1;
             for (int i = 0; i < 2; ++i) {
                 g.seg[i][0] = make_seg(s, w.pl_a[i], w.pr_f);
@@ -204,7 +205,6 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
             g.trunc_bits = trunc;
             MPC_TRY(launch_limb_gemm(c, P0, g));
         } else {
-            MPC_TRY(launch_recode_multi(c, P0, rc, 6));
             g.nseg = 2;
             for (int i = 0; i < 2; ++i) {
                 g.seg[i][0] = make_seg(s, w.pl_e, w.pr_b[i]);

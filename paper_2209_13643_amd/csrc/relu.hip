@@ -21,7 +21,8 @@
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxChunks = 32;
+constexpr int kMaxChunks = 64;
+constexpr size_t kAutoChunkElems = (size_t)1 << 20;   // chunk size picked when the caller passes n_chunks = 0
 
 struct alignas(16) u64x2 { u64 a, b; };
 
@@ -395,6 +396,12 @@ int wire_words(mpc_ctx* c, const u64* src0, u64* dst0, const u64* src1, u64* dst
 // The protocol on n elements whose buffers are described by parties[2].
 int relu_run(mpc_ctx* c, ReluParty (&pp)[2], size_t n, int n_chunks)
 {
+    if (n_chunks == 0) {
+        // automatic: about a million elements per chunk on a single queue (the chunk's
+        // state then survives in the last-level cache from round to round), one chunk otherwise
+        const bool one_q = c->s[0] == c->s[1] && c->s[1] == c->s[2];
+        n_chunks = one_q ? (int)((n + kAutoChunkElems / 2) / kAutoChunkElems) : 1;
+    }
     if (n_chunks > kMaxChunks) n_chunks = kMaxChunks;
     if ((size_t)n_chunks > (n + 3) / 4) n_chunks = (int)((n + 3) / 4);
     if (n_chunks < 1) n_chunks = 1;
@@ -417,6 +424,34 @@ int relu_run(mpc_ctx* c, ReluParty (&pp)[2], size_t n, int n_chunks)
     hipStream_t P[2] = { c->s[0], c->s[1] }, Wr = c->s[2];
     hipEvent_t got[kMaxChunks];
     const bool one_queue = P[0] == P[1] && P[1] == Wr;      // in-order queue: no events needed
+
+    if (one_queue) {
+        // One in-order queue: chunk-major order.  A chunk runs through all ten
+        // rounds before the next one starts, so its carried state and exchange
+        // buffers are still in the last-level cache when the next round reads them.
+        for (int m = 0; m < n_chunks; ++m) {
+            if (hi[m] <= lo[m]) continue;
+            MPC_TRY(wire_words(c, pp[0].r, const_cast<u64*>(pp[1].recv), pp[1].r, const_cast<u64*>(pp[0].recv),
+                               n, lo[m], hi[m], 1, vec));
+            for (int stage = 0; stage < ST_COUNT; ++stage) {
+                const int rows = words_after(stage);
+                if (vec4)     launch_stage<4>(stage, P[0], pp[0], pp[1], -1, lo[m], hi[m]);
+                else if (vec) launch_stage<2>(stage, P[0], pp[0], pp[1], -1, lo[m], hi[m]);
+                else          launch_stage<1>(stage, P[0], pp[0], pp[1], -1, lo[m], hi[m]);
+                MPC_HIP(c, hipGetLastError());
+                if (rows == 0) {
+                    hipLaunchKernelGGL(k_wire_bytes, dim3(grid_for(hi[m] - lo[m]), 2), dim3(kThreads), 0, Wr,
+                                       pp[0].sendb, const_cast<u8*>(pp[1].recvb), pp[1].sendb, const_cast<u8*>(pp[0].recvb),
+                                       lo[m], hi[m]);
+                    MPC_HIP(c, hipGetLastError());
+                } else if (rows > 0) {
+                    MPC_TRY(wire_words(c, pp[0].send, const_cast<u64*>(pp[1].recv), pp[1].send, const_cast<u64*>(pp[0].recv),
+                                       n, lo[m], hi[m], rows, vec));
+                }
+            }
+        }
+        return MPC_OK;
+    }
 
     // Alg. 2: each party sends the mask half of the XOR sharing of its own share
     for (int m = 0; m < n_chunks; ++m) {
@@ -542,7 +577,7 @@ size_t mpc_maxpool_workspace_bytes(int B, int H, int W, int C)
 int mpc_relu(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat, mpc_share y, size_t n, int n_chunks,
              uint8_t* const s_bit[2], uint64_t* const s_arith[2])
 {
-    if (!c || n == 0 || n_chunks < 1 || !x.p[0] || !x.p[1] || !y.p[0] || !y.p[1]) return MPC_EINVAL;
+    if (!c || n == 0 || n_chunks < 0 || !x.p[0] || !x.p[1] || !y.p[0] || !y.p[1]) return MPC_EINVAL;
     MPC_TRY(check_material(mat));
     ReluWs w = carve_relu(c->ws, c->ws_bytes, n);
     if (!w.ok) return MPC_ENOMEM;
@@ -562,7 +597,7 @@ int mpc_relu(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat, mpc_share y
 int mpc_maxpool2x2(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat1, const mpc_relu_material* mat2,
                    mpc_share y, int B, int H, int W, int C, int n_chunks)
 {
-    if (!c || B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1) || n_chunks < 1 ||
+    if (!c || B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1) || n_chunks < 0 ||
         !x.p[0] || !x.p[1] || !y.p[0] || !y.p[1])
         return MPC_EINVAL;
     MPC_TRY(check_material(mat1));

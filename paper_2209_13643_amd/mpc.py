@@ -251,7 +251,7 @@ class Lane:
         self._check(lib().mpc_truncate(self._h, _share(z), z[0].numel(), bits))
         return z
 
-    def relu(self, x, mat, n_chunks=1, want_sign=False, out=None):
+    def relu(self, x, mat, n_chunks=0, want_sign=False, out=None):
         n = x[0].numel()
         self.reserve(lib().mpc_relu_workspace_bytes(n))
         y = out if out is not None else (torch.empty_like(x[0]), torch.empty_like(x[1]))
@@ -265,7 +265,7 @@ class Lane:
         self._check(lib().mpc_relu(self._h, _share(x), byref(m), _share(y), n, n_chunks, None, None))
         return y
 
-    def maxpool2x2(self, x, mat1, mat2, n_chunks=1):
+    def maxpool2x2(self, x, mat1, mat2, n_chunks=0):
         B, H, W, C = x[0].shape
         n_out = B * (H // 2) * (W // 2) * C
         self.reserve(lib().mpc_maxpool_workspace_bytes(B, H, W, C))

@@ -86,7 +86,7 @@ def preopen_weights(lane: mpc.Lane, states):
     lane.sync()
 
 
-def run_layer(lane: mpc.Lane, L, st: LayerState, x, n_chunks=1, flags=mpc.MPC_TRUNCATE):
+def run_layer(lane: mpc.Lane, L, st: LayerState, x, n_chunks=1, relu_chunks=0, flags=mpc.MPC_TRUNCATE):
     """One secure layer on one lane: linear (+ ReLU) (+ 2x2 max-pool).  Returns output shares."""
     y_arg = None if st.f_public is not None else st.w
     if isinstance(L, synth.Conv):
@@ -98,9 +98,9 @@ def run_layer(lane: mpc.Lane, L, st: LayerState, x, n_chunks=1, flags=mpc.MPC_TR
         z = lane.beaver_matmul(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public, n_chunks=n_chunks, flags=flags)
     outs = [z]
     if st.relu is not None:
-        z = lane.relu(z, st.relu, n_chunks=n_chunks); outs.append(z)
+        z = lane.relu(z, st.relu, n_chunks=relu_chunks); outs.append(z)
     if st.pool1 is not None:
-        z = lane.maxpool2x2(z, st.pool1, st.pool2, n_chunks=n_chunks); outs.append(z)
+        z = lane.maxpool2x2(z, st.pool1, st.pool2, n_chunks=relu_chunks); outs.append(z)
     run_layer.last_intermediates = outs      # kept alive by the caller through `keep`
     return z
 

@@ -84,7 +84,7 @@ def test_pipeline_invariance(mods, dealt, mode):
         for ln, sts in zip(lanes, states):
             pipeline.preopen_weights(ln, sts)
     if mode == "pipelined-two-phase-chunked":
-        kw = dict(n_chunks=3, flags=mpc.MPC_TRUNCATE | mpc.MPC_TWO_PHASE)
+        kw = dict(n_chunks=3, relu_chunks=3, flags=mpc.MPC_TRUNCATE | mpc.MPC_TWO_PHASE)
     keep = []
     if mode == "serial-3stream":
         outs = [pipeline.forward(lanes[m], layers, states[m], xs[m], keep) for m in range(len(mbs))]
