@@ -87,6 +87,7 @@ def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3):
         states.append(pipeline.deal_microbatch(lanes[m], g, layers, weights))
         X = dealer.normal_fixed(g, (micro_batch, 32, 32, 3), 1.0, dev)
         xs.append(dealer.share(g, X))
+        torch.cuda.synchronize()
         pipeline.preopen_weights(lanes[m], states[m])
     res = {}
     for mode in ("serial", "pipelined"):

@@ -38,6 +38,9 @@ def normal_fixed(g, shape, std, device):
 
 
 def share(g, value):
+    """Additive shares.  Like everything in this module the result is produced by
+    torch on torch's current stream: synchronise (or Lane.wait_torch()) before a
+    lane reads it."""
     s0 = rand_words(g, value.shape, value.device)
     return s0, value - s0
 
@@ -56,6 +59,7 @@ def conv_layer(lane: "mpc.Lane", g, B, H, W, Cin, Cout, KH, KW, pad, stride, x_s
     lane.sync()
     d = dict(X=X, W=Wt, x=share(g, X), w=share(g, Wt), a=share(g, A), b=share(g, Bm), c=share(g, C))
     d["f_public"] = Wt - Bm          # epsilon = W - B, opened ahead of time (Alg. 3)
+    torch.cuda.synchronize(dev)
     return d
 
 
@@ -69,6 +73,7 @@ def matmul_layer(lane: "mpc.Lane", g, M, K, N, x_std, w_std, batch=None):
     lane.sync()
     d = dict(X=X, W=Wt, x=share(g, X), w=share(g, Wt), a=share(g, A), b=share(g, Bm), c=share(g, C))
     d["f_public"] = Wt - Bm
+    torch.cuda.synchronize(dev)
     return d
 
 
@@ -86,6 +91,7 @@ def relu_material(g, n: int, device) -> dict:
     mb = (rand_words(g, (n,), device), rand_words(g, (n,), device))
     m["ma"], m["mb"] = ma, mb
     m["mc"] = share(g, (ma[0] + ma[1]) * (mb[0] + mb[1]))
+    torch.cuda.synchronize(device)      # torch filled these on its own stream; the lanes use theirs
     return m
 
 

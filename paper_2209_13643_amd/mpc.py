@@ -192,6 +192,13 @@ class Lane:
     def wait_for(self, other: "Lane"):
         self._check(lib().mpc_ctx_wait(self._h, other._h))
 
+    def wait_torch(self):
+        """Order the lane after the work torch has enqueued on its current stream
+        (inputs produced by torch ops are otherwise not ordered with the lane's queues)."""
+        cur = torch.cuda.current_stream(self.device)
+        for s in {self.stream(0), self.stream(1), self.stream(2)}:
+            torch.cuda.ExternalStream(s, device=self.device).wait_stream(cur)
+
     def use_single_queue(self):
         """Issue both parties and the wire on party 0's stream (one in-order queue)."""
         s0 = self.stream(0)

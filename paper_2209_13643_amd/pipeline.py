@@ -75,6 +75,7 @@ def deal_microbatch(lane: mpc.Lane, g, layers, weights) -> list:
             st.pool1 = dealer.relu_material(g, 2 * n_pool, dev)
             st.pool2 = dealer.relu_material(g, n_pool, dev)
         states.append(st)
+    torch.cuda.synchronize(dev)
     return states
 
 

@@ -1,0 +1,193 @@
+"""Parity at the full sizes of the five workloads, in the launch configuration
+the benchmark times (single-queue lane, automatic ReLU chunking).
+
+Linear layers: inputs and triples are dealt on the host (triple products by the
+oracle) and every output share is compared bit for bit.  Secure ReLU at sizes
+whose offline material does not fit a host array comfortably: material is drawn
+on the device by the seeded dealer (a random-number source, not the code under
+test), the oracle recomputes a random sample of elements from the downloaded
+material slices, and the whole output is checked through the property
+rec(y) == max(rec(x), 0)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import deal_conv, deal_matmul, oracle_conv, oracle_matmul, rec
+from paper_2209_13643_amd import synth
+
+pytestmark = pytest.mark.gpu
+U64 = np.uint64
+TOL = 2.0 ** -12
+
+
+@pytest.fixture(scope="module")
+def mods():
+    from paper_2209_13643_amd import dealer, mpc, pipeline
+    return mpc, dealer, pipeline
+
+
+@pytest.fixture()
+def lane(mods):
+    ln = mods[0].Lane(0)
+    ln.use_single_queue()
+    yield ln
+    ln.sync()
+    ln.close()
+
+
+def dev(mpc, pair):
+    return (mpc.to_device(pair[0]), mpc.to_device(pair[1]))
+
+
+def assert_equal_shares(mpc, got, want, what):
+    for i in range(2):
+        g = mpc.to_host(got[i]).reshape(want[i].shape)
+        assert np.array_equal(g, want[i]), f"{what}: party {i}: {(g != want[i]).sum()} of {g.size} words differ"
+
+
+def relu_sampled_check(mpc, dealer, lane, z, seed, n_sample=200_000):
+    """Full-size secure ReLU on device shares z: sampled oracle parity + exact property."""
+    n = z[0].numel()
+    g = dealer.gen(seed, lane.device)
+    mat = dealer.relu_material(g, n, lane.device)
+    y, sb, sa = lane.relu(z, mat, want_sign=True)
+    lane.sync()
+    rz = (z[0] + z[1]).view(-1); ry = (y[0] + y[1]).view(-1)
+    assert torch.equal(ry, torch.clamp(rz, min=0)), "rec(y) != max(rec(x), 0)"
+    assert torch.equal((sb[0] ^ sb[1]).view(-1).bool(), rz < 0)
+    assert torch.equal((sa[0] + sa[1]).view(-1), (rz < 0).to(torch.int64))
+    idx = torch.randperm(n, device=lane.device, generator=g)[:n_sample].sort().values
+    take = lambda t: mpc.to_host(t.view(-1)[idx])
+    take12 = lambda t: mpc.to_host(t.view(12, n)[:, idx])
+    sub = {k: (take(mat[k][0]), take(mat[k][1])) for k in ("r", "rb", "ra", "ma", "mb", "mc")}
+    for k in ("and_a", "and_b", "and_c"):
+        sub[k] = (take12(mat[k][0]), take12(mat[k][1]))
+    want = oracle.relu((take(z[0]), take(z[1])), sub)
+    assert_equal_shares(mpc, (y[0].view(-1)[idx], y[1].view(-1)[idx]), want.y, "relu sample")
+    assert_equal_shares(mpc, (sa[0].view(-1)[idx], sa[1].view(-1)[idx]), want.s_arith, "sign share sample")
+    return y
+
+
+def float_check(d, z_rec_u64, conv):
+    """Decoded output within 2^-12 of float64 on the decoded inputs (sampled rows)."""
+    got = oracle.decode(z_rec_u64)
+    if conv:
+        x = torch.from_numpy(oracle.decode(d["X"])).permute(0, 3, 1, 2)[:2]
+        w = torch.from_numpy(oracle.decode(d["Y"])).permute(3, 2, 0, 1)
+        ref = torch.nn.functional.conv2d(x, w, padding=d["pad"], stride=d["stride"]).permute(0, 2, 3, 1).numpy()
+        got = got[:2]
+    else:
+        ref = oracle.decode(d["X"])[..., :64, :] @ oracle.decode(d["Y"])
+        got = got[..., :64, :]
+    assert np.abs(got - ref).max() <= TOL
+
+
+def test_config1_vgg_block_full(mods, lane):
+    mpc, dealer, _ = mods
+    L = synth.config_vgg_block().layers[0]
+    print("config 1 full: conv 64x16x16x128 -> 128 + relu", flush=True)
+    rng = synth.rng_for(1)
+    d = deal_conv(rng, L.B, L.H, L.W, L.Cin, L.Cout, L.KH, L.KW, L.pad, L.stride, x_std=L.x_std, w_std=L.w_std)
+    z = lane.conv2d(dev(mpc, d["x"]), dev(mpc, d["y"]), dev(mpc, d["a"]), dev(mpc, d["b"]), dev(mpc, d["c"]), L.pad, L.stride)
+    lane.sync()
+    want = oracle_conv(d)
+    assert_equal_shares(mpc, z, want, "conv")
+    assert not oracle.truncation_wraps(rec(oracle_conv(d, 0)), rec(want)).any()
+    float_check(d, rec(want), conv=True)
+    # the ReLU of this config fits on the host: full bit-exact comparison
+    mat = synth.deal_relu_material(rng, L.B * L.Ho * L.Wo * L.Cout)
+    y = lane.relu(z, mpc.material_to_device(mat))
+    lane.sync()
+    assert_equal_shares(mpc, y, oracle.relu(want, mat).y, "relu")
+
+
+def test_config2_resnet_bottleneck_full(mods, lane):
+    mpc, dealer, _ = mods
+    rng = synth.rng_for(2)
+    for li, L in enumerate(synth.config_resnet_bottleneck().layers):
+        print(f"config 2 full: {L.name} {L.gemm_mkn}", flush=True)
+        d = deal_conv(rng, L.B, L.H, L.W, L.Cin, L.Cout, L.KH, L.KW, L.pad, L.stride, x_std=L.x_std, w_std=L.w_std)
+        z = lane.conv2d(dev(mpc, d["x"]), dev(mpc, d["y"]), dev(mpc, d["a"]), dev(mpc, d["b"]), dev(mpc, d["c"]), L.pad, L.stride)
+        lane.sync()
+        want = oracle_conv(d)
+        assert_equal_shares(mpc, z, want, L.name)
+        float_check(d, rec(want), conv=True)
+        relu_sampled_check(mpc, dealer, lane, z, seed=200 + li)
+        del d, z, want
+        torch.cuda.empty_cache()
+
+
+def test_config3_transformer_full(mods, lane):
+    mpc, dealer, _ = mods
+    rng = synth.rng_for(3)
+    for li, L in enumerate(synth.config_transformer().layers):
+        print(f"config 3 full: {L.name} {L.M}x{L.K}x{L.N} batch {L.batch}", flush=True)
+        d = deal_matmul(rng, L.M, L.K, L.N, batch=L.batch if L.batch > 1 else None, x_std=L.x_std, w_std=L.w_std)
+        z = lane.beaver_matmul(dev(mpc, d["x"]), dev(mpc, d["y"]), dev(mpc, d["a"]), dev(mpc, d["b"]), dev(mpc, d["c"]))
+        lane.sync()
+        want = oracle_matmul(d)
+        assert_equal_shares(mpc, z, want, L.name)
+        float_check(d, rec(want), conv=False)
+        if L.relu:
+            relu_sampled_check(mpc, dealer, lane, z, seed=300 + li)
+        del d, z, want
+        torch.cuda.empty_cache()
+
+
+def test_config4_vgg16_pipeline_full(mods):
+    """Batch 128 = 4 micro-batches of 32 through the whole VGG16-CIFAR network:
+    the inter-batch pipeline (one lane per micro-batch) gives exactly the shares
+    of the serial run, and every layer's reconstructed output equals the plain
+    fixed-point layer on its reconstructed input (conv within +-1 ulp of the
+    truncation, ReLU and max-pool exact)."""
+    mpc, dealer, pipeline = mods
+    wl = synth.config_vgg16_pipeline(32)
+    layers = wl.layers
+    n_mb = 4
+    print("config 4 full: VGG16-CIFAR, 4 x 32 images", flush=True)
+    lanes = [mpc.Lane(0) for _ in range(n_mb)]
+    for ln in lanes:
+        ln.use_single_queue()
+    g = dealer.gen(synth.BASE_SEED + wl.index, lanes[0].device)
+    weights = pipeline.deal_weights(g, layers, lanes[0].device)
+    states, xs = [], []
+    for m in range(n_mb):
+        states.append(pipeline.deal_microbatch(lanes[m], g, layers, weights))
+        xs.append(dealer.share(g, dealer.normal_fixed(g, (32, 32, 32, 3), 1.0, lanes[0].device)))
+    torch.cuda.synchronize()
+    keep_a, keep_b = [], []
+    serial = [pipeline.forward(lanes[0], layers, states[m], xs[m], keep_a) for m in range(n_mb)]
+    lanes[0].sync()
+    piped = pipeline.forward_pipelined(lanes, layers, states, xs, keep_b)
+    for ln in lanes:
+        ln.sync()
+    for m in range(n_mb):
+        for i in range(2):
+            assert torch.equal(serial[m][i], piped[m][i]), f"micro-batch {m}, party {i}: pipelined != serial"
+    # layer-by-layer properties on micro-batch 0 (keep_a holds its intermediates first)
+    x = xs[0]
+    it = iter(keep_a)
+    for L, st, (W, _) in zip(layers, states[0], weights):
+        z = next(it)
+        rx = (x[0] + x[1]); rz = (z[0] + z[1])
+        if isinstance(L, synth.Conv):
+            xin = rx.view(L.B, L.H, L.W, L.Cin).double().permute(0, 3, 1, 2)
+            ref = torch.nn.functional.conv2d(xin.cpu(), W.double().permute(3, 2, 0, 1).cpu(), padding=L.pad).permute(0, 2, 3, 1)
+        else:
+            ref = rx.view(L.M, L.K).double().cpu() @ W.double().cpu()
+        exact = torch.floor(ref / 65536.0)           # products are exact in float64 at these magnitudes
+        diff = rz.view(ref.shape).cpu().double() - exact
+        assert diff.min() >= 0 and diff.max() <= 1, f"{L.name}: truncated product off by {diff.min()}..{diff.max()}"
+        x = z
+        if st.relu is not None:
+            y = next(it)
+            assert torch.equal(y[0] + y[1], torch.clamp(rz, min=0)), f"{L.name}: relu"
+            x = y
+        if st.pool1 is not None:
+            p = next(it)
+            ry = (x[0] + x[1]).view(L.B, L.Ho // 2, 2, L.Wo // 2, 2, L.Cout)
+            assert torch.equal((p[0] + p[1]), ry.amax(dim=(2, 4))), f"{L.name}: max-pool"
+            x = p
+    for ln in lanes:
+        ln.close()
