@@ -184,5 +184,9 @@ struct GemmArgs {
     int rows_L;                       // rows of the left planes (plain: M)
     ConvGeom conv;
     const u8* zero16;                 // 16 readable zero bytes (conv padding)
+    int ksplit;                       // > 1: split the contraction over this many workgroups per tile
+    int steps_per_split;              // filled by the launcher
+    u64* partial;                     // [ksplit][nparty][batch][M][N] partial products (ksplit > 1)
 };
+int gemm_ksplit(int M, int N, int batch, int nparty, int total_steps);
 int launch_limb_gemm(mpc_ctx* c, hipStream_t st, const GemmArgs& g);

@@ -93,15 +93,21 @@ void k_limb_gemm(GemmArgs g)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WGM, wn = wave / WGM;
     const int i32 = lane & 31, g2 = lane >> 5;
+    // blockIdx.z = (k split * batch + batch item) * nparty + party
     const int party = blockIdx.z % g.nparty;
-    const int bidx = blockIdx.z / g.nparty;
+    const int bidx = (blockIdx.z / g.nparty) % g.batch;
+    const int split = blockIdx.z / (g.nparty * g.batch);
     const int m0 = blockIdx.x * C::TM, n0 = blockIdx.y * C::TN;
 
     // ---- per-party operands as scalars
     const GemmSeg& sg0 = party ? g.seg[1][0] : g.seg[0][0];
     const GemmSeg& sg1 = party ? g.seg[1][1] : g.seg[0][1];
     const int KB0 = sg0.KB, KB1 = g.nseg > 1 ? sg1.KB : 0;
-    const int T = (KB0 + KB1) / KS;
+    // K steps of this workgroup: all of them, or one slice when the contraction is split
+    const int T_all = (KB0 + KB1) / KS;
+    const int st0 = split * g.steps_per_split;
+    const int T = T_all - st0 < g.steps_per_split ? T_all - st0 : g.steps_per_split;
+    if (T <= 0) return;             // cannot happen with the launcher's slicing
     const long long krowL = (long long)g.rows_L * 16;      // bytes between k blocks of a left plane
     const long long krowR = (long long)g.N * 16;
 
@@ -151,9 +157,14 @@ void k_limb_gemm(GemmArgs g)
         segR = q.R + (size_t)bidx * q.R_bstride + (long long)wave * q.R_dstride;
         dsL = q.L_dstride * C::NW; dsR = q.R_dstride * C::NW;
     };
-    set_segment(0);
-    int c_seg = 0, c_kb = 0, c_tap = 0, c_cb = 0, c_dpix = 0, c_kw = 0;
-    long long c_offL = 0, c_offR = 0;       // c_kb * krowL / krowR
+    // cursor at K step st0
+    int c_seg = st0 * KS >= KB0 ? 1 : 0;
+    int c_kb = st0 * KS - (c_seg ? KB0 : 0);
+    int c_tap = CONV ? c_kb / CB : 0, c_cb = CONV ? c_kb - c_tap * CB : 0;
+    int c_kw = CONV ? c_tap % KWf : 0;
+    int c_dpix = CONV ? (c_tap / KWf) * Wimg + c_kw : 0;
+    long long c_offL = (long long)c_kb * krowL, c_offR = (long long)c_kb * krowR;       // c_kb * krowL / krowR
+    set_segment(c_seg);
     auto cursor_next = [&]() {      // advance by one k block
         ++c_kb; c_offL += krowL; c_offR += krowR;
         if (CONV) {
@@ -302,6 +313,11 @@ void k_limb_gemm(GemmArgs g)
     const u64* addend = g.addend[party] ? g.addend[party] + (size_t)bidx * g.out_bstride : nullptr;
     const u64* addend2 = g.addend2[party] ? g.addend2[party] + (size_t)bidx * g.out_bstride : nullptr;
     u64* out = g.out[party] + (size_t)bidx * g.out_bstride;
+    const bool partial = g.ksplit > 1;      // raw partial products go to the workspace; a second kernel finishes
+    if (partial) {
+        addend = nullptr; addend2 = nullptr;
+        out = g.partial + (((size_t)split * g.nparty + party) * g.batch + bidx) * g.out_bstride;
+    }
     const int rbase = m0 + wm * 32 + g2 * 4;
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
@@ -334,9 +350,28 @@ void k_limb_gemm(GemmArgs g)
 #pragma unroll
             for (int s = 7; s >= 0; --s) z = (z << 8) + (u64)(long long)acc[c][s][v];
             z += add[v];
-            if (g.trunc_bits) z = party == 0 ? (z >> g.trunc_bits) : (u64)0 - (((u64)0 - z) >> g.trunc_bits);
+            if (g.trunc_bits && !partial) z = party == 0 ? (z >> g.trunc_bits) : (u64)0 - (((u64)0 - z) >> g.trunc_bits);
             if (row < g.M && col < g.N) out[(size_t)row * g.N + col] = z;
         }
+    }
+}
+
+// Second pass of a split contraction: out = sum over splits of the partial
+// products + addends, then truncation.  One thread per output word.
+__global__ __launch_bounds__(256) void k_splitk_finish(GemmArgs g)
+{
+    const size_t per = (size_t)g.batch * g.out_bstride;            // words per party
+    const size_t total = per * g.nparty;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int party = (int)(i / per);
+        const size_t w = i - (size_t)party * per;
+        u64 z = 0;
+        for (int sp = 0; sp < g.ksplit; ++sp) z += g.partial[((size_t)sp * g.nparty + party) * per + w];
+        if (g.addend[party]) z += g.addend[party][w];
+        if (g.addend2[party]) z += g.addend2[party][w];
+        if (g.trunc_bits) z = party == 0 ? (z >> g.trunc_bits) : (u64)0 - (((u64)0 - z) >> g.trunc_bits);
+        g.out[party][w] = z;
     }
 }
 
@@ -352,9 +387,14 @@ int launch_cfg(mpc_ctx* c, hipStream_t st, const GemmArgs& g)
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
         attr_set[c->device] = true;
     }
-    dim3 grid((g.M + C::TM - 1) / C::TM, (g.N + C::TN - 1) / C::TN, g.batch * g.nparty);
+    dim3 grid((g.M + C::TM - 1) / C::TM, (g.N + C::TN - 1) / C::TN, g.batch * g.nparty * g.ksplit);
     const int pi = prof_begin(c, MPC_PROF_GEMM_KERNEL, st);
     hipLaunchKernelGGL(kern, grid, dim3(C::NT), C::LDS_BYTES, st, g);
+    if (g.ksplit > 1) {
+        const size_t total = (size_t)g.batch * g.out_bstride * g.nparty;
+        size_t blocks = (total + 255) / 256; if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(k_splitk_finish, dim3((unsigned)blocks), dim3(256), 0, st, g);
+    }
     prof_end(c, MPC_PROF_GEMM_KERNEL, pi, st);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
@@ -362,8 +402,33 @@ int launch_cfg(mpc_ctx* c, hipStream_t st, const GemmArgs& g)
 
 }  // namespace
 
-int launch_limb_gemm(mpc_ctx* c, hipStream_t st, const GemmArgs& g)
+// How many ways to split the contraction so that a small output still fills
+// the chip: aim for about 256 workgroups, keep at least 4 K steps per slice.
+int gemm_ksplit(int M, int N, int batch, int nparty, int total_steps)
 {
+    const bool narrow = ((N - 1) % 128) < 64 && (N <= 64 || M >= 4096);
+    const long long tiles = (long long)((M + (narrow ? 127 : 63)) / (narrow ? 128 : 64)) *
+                            ((N + (narrow ? 63 : 127)) / (narrow ? 64 : 128)) * batch * nparty;
+    if (tiles >= 160 || total_steps < 8) return 1;
+    int s = (int)((256 + tiles - 1) / tiles);
+    if (s > total_steps / 4) s = total_steps / 4;
+    if (s > 32) s = 32;
+    if (s < 1) s = 1;
+    const int per = (total_steps + s - 1) / s;
+    return (total_steps + per - 1) / per;          // no empty slice
+}
+
+int launch_limb_gemm(mpc_ctx* c, hipStream_t st, const GemmArgs& g_in)
+{
+    GemmArgs g = g_in;
+    {
+        int total_steps = 0;
+        for (int s = 0; s < g.nseg; ++s) total_steps += g.seg[0][s].KB / KS;
+        if (g.ksplit < 1 || !g.partial) g.ksplit = 1;
+        g.steps_per_split = (total_steps + g.ksplit - 1) / g.ksplit;
+        g.ksplit = (total_steps + g.steps_per_split - 1) / g.steps_per_split;      // no empty slice
+        if ((long long)g.batch * g.nparty * g.ksplit > 65535) return MPC_EINVAL;
+    }
     if (g.M <= 0 || g.N <= 0 || g.batch <= 0 || g.nseg < 1 || g.nseg > 2) return MPC_EINVAL;
     if ((size_t)g.batch * g.nparty > 65535) return MPC_EINVAL;
     for (int p = 0; p < g.nparty; ++p)

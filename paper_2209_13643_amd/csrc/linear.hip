@@ -50,6 +50,7 @@ struct LinearWs {
     u64 *sf[2], *rf[2];        // masked y shares
     u8 *pl_e, *pl_a[2];        // left digit planes
     u8 *pr_f, *pr_b[2];        // right digit planes
+    u64* partial; int ksplit;  // split-contraction partial products
     size_t bytes; bool ok;
 };
 
@@ -63,6 +64,9 @@ LinearWs carve(u8* base, size_t cap, const LinearShape& s)
     const size_t lp = 8 * s.L_plane * s.batch, rp = 8 * s.R_plane * s.batch;
     r.pl_e = w.take<u8>(lp); r.pl_a[0] = w.take<u8>(lp); r.pl_a[1] = w.take<u8>(lp);
     r.pr_f = w.take<u8>(rp); r.pr_b[0] = w.take<u8>(rp); r.pr_b[1] = w.take<u8>(rp);
+    // the two-segment, two-party launch is the one that decides the split
+    r.ksplit = gemm_ksplit(s.M, s.N, s.batch, 2, 2 * s.KB / 2);
+    r.partial = r.ksplit > 1 ? w.take<u64>((size_t)r.ksplit * 2 * s.batch * s.M * s.N) : nullptr;
     r.bytes = w.off; r.ok = w.ok;
     return r;
 }
@@ -100,6 +104,7 @@ void fill_geom(const LinearShape& s, const LinearWs& w, GemmArgs& g)
     g.out_bstride = (long long)s.M * s.N;
     g.rows_L = s.rowsL;
     g.zero16 = w.zero;
+    g.ksplit = w.ksplit; g.partial = w.partial;
     g.conv = ConvGeom{};
     if (s.conv) {
         g.conv.enabled = 1; g.conv.H = s.H; g.conv.W = s.W; g.conv.Ho = s.Ho; g.conv.Wo = s.Wo;

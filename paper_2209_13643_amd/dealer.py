@@ -55,6 +55,7 @@ def conv_layer(lane: "mpc.Lane", g, B, H, W, Cin, Cout, KH, KW, pad, stride, x_s
     X = normal_fixed(g, (B, H, W, Cin), x_std, dev)
     Wt = normal_fixed(g, (KH, KW, Cin, Cout), w_std, dev)
     A = rand_words(g, X.shape, dev); Bm = rand_words(g, Wt.shape, dev)
+    lane.wait_torch()                # A, Bm were written on torch's stream
     C = lane.ring_conv2d(A, Bm, pad, stride)
     lane.sync()
     d = dict(X=X, W=Wt, x=share(g, X), w=share(g, Wt), a=share(g, A), b=share(g, Bm), c=share(g, C))
@@ -69,6 +70,7 @@ def matmul_layer(lane: "mpc.Lane", g, M, K, N, x_std, w_std, batch=None):
     ws = (K, N) if batch is None else (batch, K, N)
     X = normal_fixed(g, xs, x_std, dev); Wt = normal_fixed(g, ws, w_std, dev)
     A = rand_words(g, xs, dev); Bm = rand_words(g, ws, dev)
+    lane.wait_torch()
     C = lane.ring_matmul(A, Bm)
     lane.sync()
     d = dict(X=X, W=Wt, x=share(g, X), w=share(g, Wt), a=share(g, A), b=share(g, Bm), c=share(g, C))

@@ -60,10 +60,12 @@ def deal_microbatch(lane: mpc.Lane, g, layers, weights) -> list:
     for L, (W, wsh) in zip(layers, weights):
         if isinstance(L, synth.Conv):
             A = dealer.rand_words(g, (L.B, L.H, L.W, L.Cin), dev); Bm = dealer.rand_words(g, W.shape, dev)
+            lane.wait_torch()            # A, Bm were written on torch's stream
             C = lane.ring_conv2d(A, Bm, L.pad, L.stride)
             n_out = L.B * L.Ho * L.Wo * L.Cout
         else:
             A = dealer.rand_words(g, (L.M, L.K), dev); Bm = dealer.rand_words(g, W.shape, dev)
+            lane.wait_torch()
             C = lane.ring_matmul(A, Bm)
             n_out = L.M * L.N
         lane.sync()
