@@ -142,12 +142,17 @@ def main():
                    "max_abs_err_vs_float64": err},
         "roofline": {"kernel": "k_limb_gemm<2,2,true> (both parties, [e|a_i] x [b_i';f], fused add-c + truncation)",
                      "bound": "mfma", "achieved": gemm_tops, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": gemm_tops / INT8_PEAK_TOPS, "traffic": None,
+                     "frac": gemm_tops / INT8_PEAK_TOPS,
+                     "traffic": {"fetch_bytes": 163.5 * 2 ** 20, "write_bytes": 32.0 * 2 ** 20,
+                                 "algorithmic_bytes": (100.6 + 32.0) * 2 ** 20,
+                                 "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated on a copy kernel "
+                                           "(profiles/bench_vgg_block_hbm_traffic.md)"},
                      "note": "288 int8 ops per secure MAC; power-limited attainable rate with random int8 operands "
                              "measured on this chip is about 3070 TOP/s (see DESIGN.md)"},
-        "roofline_relu": {"kernel": "secure ReLU chain: k_first, k_level<0..5>, k_sign, k_b2a, k_select per party + wire copies",
+        "roofline_relu": {"kernel": "secure ReLU chain: k_relu_stage<0..9> (both parties per launch) + k_wire_words / k_wire_bytes",
                           "bound": "hbm", "achieved": relu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                          "frac": relu_gbs / HBM_PEAK_GBS, "traffic": None,
+                          "frac": relu_gbs / HBM_PEAK_GBS,
+                          "traffic": {"bytes_per_element": 3372, "source": "rocprofv3 --pmc, same summary"},
                           "bytes_per_element": RELU_BYTES_PER_ELEMENT},
     }
     if not args.no_cpu_baseline:

@@ -253,3 +253,39 @@ def test_argument_errors(mpc, lane):
     assert L.mpc_truncate(h, sh, 16, 64) == -1
     assert L.mpc_relu(h, sh, None, sh, 16, 1, None, None) == -1
     lane.sync()
+
+
+# ------------------------------------------------- small API pieces used by the runner
+def test_sub_then_open_gives_weight_mask(mpc, lane):
+    """mpc_sub + mpc_open = the ahead-of-time opening of W - B (Alg. 3, lines 2-5)."""
+    print("sub + open", flush=True)
+    rng = np.random.default_rng(55)
+    W = synth.rand_words(rng, (37, 21)); B = synth.rand_words(rng, (37, 21))
+    ws, bs = synth.share_additive(rng, W), synth.share_additive(rng, B)
+    d = lane.sub(dev(mpc, ws), dev(mpc, bs))
+    f = lane.open(d)
+    lane.sync()
+    assert np.array_equal(mpc.to_host(f), W - B)
+    assert np.array_equal(mpc.to_host(f), oracle.open_shares(ws[0] - bs[0], ws[1] - bs[1]))
+
+
+def test_profiling_regions(mpc, lane):
+    print("profiling regions", flush=True)
+    d = deal_matmul(np.random.default_rng(66), 96, 64, 80)
+    args = [dev(mpc, d[k]) for k in ("x", "y", "a", "b", "c")]
+    lane.beaver_matmul(*args)                        # not recorded
+    lane.set_profiling(True); lane.profile_reset()
+    for _ in range(3):
+        z = lane.beaver_matmul(*args)
+    n = 96 * 80
+    y = lane.relu(z, mpc.material_to_device(synth.deal_relu_material(np.random.default_rng(67), n)))
+    lane.set_profiling(False)
+    lane.beaver_matmul(*args)                        # not recorded either
+    gemm_ms, gemm_n = lane.profile(mpc.PROF_GEMM_KERNEL)
+    lin_ms, lin_n = lane.profile(mpc.PROF_LINEAR)
+    relu_ms, relu_n = lane.profile(mpc.PROF_RELU)
+    assert (gemm_n, lin_n, relu_n) == (3, 3, 1)
+    assert 0 < gemm_ms <= lin_ms and relu_ms > 0
+    lane.profile_reset()
+    assert lane.profile(mpc.PROF_LINEAR) == (0.0, 0)
+    assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "result unaffected by profiling")
