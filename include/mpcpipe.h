@@ -104,6 +104,8 @@ size_t mpc_conv2d_workspace_bytes(int B, int H, int W, int Cin, int Cout,
                                   int KH, int KW, int pad, int stride);
 size_t mpc_relu_workspace_bytes(size_t n);
 size_t mpc_maxpool_workspace_bytes(int B, int H, int W, int C);
+size_t mpc_relu_msb_workspace_bytes(size_t n);
+size_t mpc_maxpool_msb_workspace_bytes(int B, int H, int W, int C);
 
 /* ------------------------------------------------------------------ opening */
 
@@ -196,6 +198,46 @@ int mpc_relu(mpc_ctx* ctx, mpc_cshare x, const mpc_relu_material* mat, mpc_share
 int mpc_maxpool2x2(mpc_ctx* ctx, mpc_cshare x, const mpc_relu_material* mat1,
                    const mpc_relu_material* mat2, mpc_share y,
                    int B, int H, int W, int C, int n_chunks);
+
+/* ------------------- secure ReLU on the sign's carry chain only (Sec. 4.2) */
+
+/* The sign needs one output of the adder circuit of Sec. 4.2: the carry into
+ * bit 63.  Of the Kogge-Stone network that mpc_relu evaluates on whole words,
+ * prefix level l (shift 2^l) then contributes only the bit positions
+ * p = 2^(l+1) - 2 (mod 2^(l+1)), p <= 62: 32, 16, 8, 4, 2, 1 positions for
+ * l = 0..5.  mpc_relu_msb evaluates exactly those gates, with the same triple
+ * bit at every gate as mpc_relu, so all outputs (y, s_bit, s_arith) are the
+ * same words bit for bit; what changes is the layout: 2^(l+1) consecutive
+ * elements share one word at level l, so the triples of a level, its masked
+ * operands and its exchange are 2^(l+1) times smaller.
+ *
+ * Packed word j of level l holds elements j*2^(l+1) + k, k = 0..2^(l+1)-1,
+ * as OR_k rotl(w_k & mask_l, k), mask_l = the positions above.
+ *
+ * Material: an mpc_relu_material whose and_a / and_b / and_c each point to
+ * mpc_relu_packed_words(n) words (16-byte aligned) instead of [12][n]:
+ *   triple 0 (G = U & V): n plain words, padded to a multiple of 4;
+ *   triple t = 1..11 (level l = (t-1)/2): ceil64(n) / 2^(l+1) packed words,
+ *   padded to a multiple of 4; segments follow one another in triple order.
+ * mpc_relu_pack_triples converts one [12][n] array pair into this layout on
+ * the device (an offline-phase helper: runs on the party streams, allocates
+ * nothing).  All other material fields are as for mpc_relu.
+ *
+ * Opening rounds, chunking (chunk boundaries fall on multiples of 256
+ * elements) and optional outputs are as for mpc_relu.  Errors: MPC_EINVAL for
+ * null pointers, n == 0 or misaligned packed triples; MPC_ENOMEM if the
+ * workspace is smaller than mpc_relu_msb_workspace_bytes(n). */
+size_t mpc_relu_packed_words(size_t n);
+int mpc_relu_pack_triples(mpc_ctx* ctx, mpc_cshare words, mpc_share packed, size_t n);
+int mpc_relu_msb(mpc_ctx* ctx, mpc_cshare x, const mpc_relu_material* mat, mpc_share y,
+                 size_t n, int n_chunks,
+                 uint8_t* const s_bit[2], uint64_t* const s_arith[2]);
+
+/* mpc_maxpool2x2 with both conversions on the pruned chain; mat1 / mat2 carry
+ * packed triples for 2*n_out and n_out elements. */
+int mpc_maxpool2x2_msb(mpc_ctx* ctx, mpc_cshare x, const mpc_relu_material* mat1,
+                       const mpc_relu_material* mat2, mpc_share y,
+                       int B, int H, int W, int C, int n_chunks);
 
 /* -------------------------------------------------- dealer helper (offline) */
 

@@ -113,7 +113,37 @@ def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3):
     return res
 
 
+def sweep_tiles(n: int = 2097152, reps: int = 10):
+    """Tile-count ablation of the inner-layer pipeline (Alg. 4; Sec. 4.2 "the number of tiles")
+    on one secure ReLU: the Alg. 4 order on three streams, and the chunk-major order on one queue."""
+    dev = torch.device("cuda", 0)
+    g = dealer.gen(synth.BASE_SEED + 100, dev)
+    x = dealer.share(g, dealer.normal_fixed(g, (n,), 1.0, dev))
+    mats = {False: dealer.relu_material(g, n, dev), True: dealer.relu_material(g, n, dev, packed=True)}
+    y = (torch.empty_like(x[0]), torch.empty_like(x[1]))
+    torch.cuda.synchronize()
+    for packed in (False, True):
+        for mode in ("three streams (Alg. 4 order)", "one queue (chunk-major)"):
+            lane = mpc.Lane(0)
+            if mode.startswith("one"):
+                lane.use_single_queue()
+            for tiles in (1, 2, 4, 8, 16, 32):
+                for _ in range(3):
+                    lane.relu(x, mats[packed], n_chunks=tiles, out=y, packed=packed)
+                lane.sync(); t0 = time.perf_counter()
+                for _ in range(reps):
+                    lane.relu(x, mats[packed], n_chunks=tiles, out=y, packed=packed)
+                lane.sync(); dt = (time.perf_counter() - t0) / reps
+                print(f"  {'sign-only packed' if packed else 'whole-word':16s} {mode:30s} tiles={tiles:2d}: "
+                      f"{dt * 1e3:7.3f} ms  {n / dt / 1e9:5.2f} G elems/s", flush=True)
+            lane.close()
+
+
 def main(argv):
+    if argv and argv[0] == "sweep":
+        print("== tile-count sweep, secure ReLU on 2097152 elements")
+        sweep_tiles()
+        return
     which = [int(a) for a in argv] if argv else list(range(len(synth.CONFIGS)))
     for idx in which:
         name, rows = bench_layers(idx) if idx != 4 else bench_layers(4, reps=3)

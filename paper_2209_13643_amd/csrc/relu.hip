@@ -16,6 +16,13 @@
 // carries (G, P) as state, and writes what it sends.  Chunks (Alg. 4's tiles)
 // are disjoint element ranges; all chunks of a round are launched back to
 // back and chunk m of the next round waits only for chunk m's copy.
+//
+// mpc_relu_msb is the same protocol with the carry network pruned to what the
+// sign needs (the circuit of Sec. 4.2 evaluated only where bit 63 depends on
+// it): prefix level l keeps the bit positions p = 2^(l+1)-2 (mod 2^(l+1)), so
+// 2^(l+1) consecutive elements share one word, element k rotated left by k.
+// The triples of the levels arrive packed the same way, and every exchange
+// after G = U & V shrinks by the same factor.  Bit for bit the same shares.
 #include "common.h"
 
 namespace {
@@ -23,6 +30,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kMaxChunks = 64;
 constexpr size_t kAutoChunkElems = (size_t)1 << 20;   // chunk size picked when the caller passes n_chunks = 0
+constexpr size_t kAutoChunkElemsPacked = (size_t)1 << 22;   // the same on the packed path (a third of the bytes per element)
 
 struct alignas(16) u64x2 { u64 a, b; };
 
@@ -36,6 +44,8 @@ struct ReluParty {
     const u64* recv;   // [4][n] words received from the other party
     u8* sendb; const u8* recvb;    // byte exchange (B2A)
     u64* G; u64* P; u8* p63;       // carried state
+    u64* sendL; const u64* recvL;  // packed levels (mpc_relu_msb): per level a [4][pw] block
+    u64* gsel;                     // packed levels: the G bits a level keeps
     u64* y; u8* s_bit; u64* s_arith;
     size_t n;       // total elements (stride of the [12][n] / [4][n] arrays)
 };
@@ -259,6 +269,194 @@ __device__ __forceinline__ void b_select(const ReluParty& p, size_t lo, size_t h
     }
 }
 
+// ---- MSB-only carry chain on packed words -------------------------------------
+// Level l (shift d = 2^l, group s = 2d) needs G', P' only at the positions
+// S_l = { p : p = s-2 (mod s), p <= 62 }.  pack_l puts s consecutive elements in
+// one word: element k contributes rotl(word & mask_l, k).  A level reads its
+// operands from two words of pack_(l-1) (elements 0..d-1 and d..2d-1 of the
+// group; pack_(-1) is the plain word) where S_(l-1) splits into the positions
+// p (kept: sel_mask) and p - d (shifted in: low_mask).
+constexpr u64 rotl_c(u64 x, int k) { k &= 63; return k ? (x << k) | (x >> (64 - k)) : x; }
+constexpr u64 msb_mask(int level)
+{
+    const int s = 2 << level; u64 m = 0;
+    for (int p = s - 2; p < 63; p += s) m |= (u64)1 << p;
+    return m;
+}
+constexpr u64 sel_mask(int level)
+{
+    u64 a = 0;
+    for (int k = 0; k < (1 << level); ++k) a |= rotl_c(msb_mask(level), k);
+    return a;
+}
+constexpr u64 low_mask(int level)
+{
+    u64 b = 0;
+    for (int k = 0; k < (1 << level); ++k) b |= rotl_c(msb_mask(level) >> (1 << level), k);
+    return b;
+}
+template <int K> __device__ __forceinline__ u64 rotl(u64 x)
+{
+    constexpr int k = K & 63;
+    if constexpr (k == 0) return x; else return (x << k) | (x >> (64 - k));
+}
+
+// Word counts and offsets of the packed arrays for n elements.
+struct MsbGeom {
+    size_t n;
+    size_t pw[6];      // words of level l's packed arrays: ceil64(n) / 2^(l+1), rounded up to 4
+    size_t toff[12];   // offset of triple t inside a packed and_a / and_b / and_c buffer
+    size_t loff[6];    // offset of level l's [4][pw] block inside sendL / recvL
+    size_t goff[6];    // offset of level l's words inside gsel
+    size_t words_triples, words_level_blocks, words_gsel;
+};
+
+MsbGeom msb_geom(size_t n)
+{
+    MsbGeom g{};
+    g.n = n;
+    const size_t n64 = (n + 63) / 64 * 64;
+    size_t lo = 0, go = 0;
+    for (int l = 0; l < 6; ++l) {
+        g.pw[l] = ((n64 >> (l + 1)) + 3) / 4 * 4;
+        g.loff[l] = lo; lo += 4 * g.pw[l];
+        g.goff[l] = go; go += g.pw[l];
+    }
+    g.toff[0] = 0;
+    size_t to = (n + 3) / 4 * 4;
+    for (int t = 1; t < 12; ++t) { g.toff[t] = to; to += g.pw[(t - 1) / 2]; }
+    g.words_triples = to; g.words_level_blocks = lo; g.words_gsel = go;
+    return g;
+}
+
+template <int V> __device__ __forceinline__ Pack<V> ld_upto(const u64* p, size_t i, size_t n)
+{
+    if constexpr (V == 4) return Pack<4>::ld(p, i);      // the caller guarantees i + 3 < n
+    else { Pack<V> r;
+#pragma unroll
+           for (int k = 0; k < V; ++k) r.v[k] = i + k < n ? p[i + k] : 0;
+           return r; }
+}
+
+// Stage 1 + LEVEL of the packed chain: finish the previous round's ANDs for the
+// 2 W input words behind W output words, regroup, and mask this level's operands.
+template <int PARTY, int LEVEL, int W>
+__device__ __forceinline__ void b_plevel(const ReluParty& p, const MsbGeom& g, size_t lo, size_t hi)
+{
+    constexpr int d = 1 << LEVEL, s = 2 * d;
+    constexpr u64 A = sel_mask(LEVEL), B = low_mask(LEVEL);
+    const size_t wlo = lo >> (LEVEL + 1), whi = (hi + s - 1) >> (LEVEL + 1);
+    const size_t stride = (size_t)gridDim.x * blockDim.x * W;
+    for (size_t j = wlo + ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * W; j < whi; j += stride) {
+        Pack<2 * W> G, P;
+        if constexpr (LEVEL == 0) {
+            const size_t n = p.n, e = 2 * j;
+            const Pack<2 * W> sd = ld_upto<2 * W>(p.send, e, n), sg = ld_upto<2 * W>(p.send + n, e, n);
+            const Pack<2 * W> rd = ld_upto<2 * W>(p.recv, e, n), rg = ld_upto<2 * W>(p.recv + n, e, n);
+            const Pack<2 * W> a = ld_upto<2 * W>(p.ta, e, n), b = ld_upto<2 * W>(p.tb, e, n), c = ld_upto<2 * W>(p.tc, e, n);
+            P = ld_upto<2 * W>(p.P, e, n);
+#pragma unroll
+            for (int k = 0; k < 2 * W; ++k)
+                G.v[k] = and_finish<PARTY>(sd.v[k] ^ rd.v[k], sg.v[k] ^ rg.v[k], a.v[k], b.v[k], c.v[k]);
+        } else {
+            static_assert(LEVEL == 0 || W == 2, "packed levels run two output words per thread");
+            constexpr int q = LEVEL - 1, t1 = 1 + 2 * q, t2 = 2 + 2 * q;
+            const size_t w = 2 * j, pq = g.pw[q];
+            const u64* sp = p.sendL + g.loff[q]; const u64* rp = p.recvL + g.loff[q];
+            const Pack<4> gs = Pack<4>::ld(p.gsel + g.goff[q], w);
+            const Pack<4> sd1 = Pack<4>::ld(sp, w), sg1 = Pack<4>::ld(sp + pq, w);
+            const Pack<4> sd2 = Pack<4>::ld(sp + 2 * pq, w), sg2 = Pack<4>::ld(sp + 3 * pq, w);
+            const Pack<4> rd1 = Pack<4>::ld(rp, w), rg1 = Pack<4>::ld(rp + pq, w);
+            const Pack<4> rd2 = Pack<4>::ld(rp + 2 * pq, w), rg2 = Pack<4>::ld(rp + 3 * pq, w);
+            const Pack<4> a1 = Pack<4>::ld(p.ta + g.toff[t1], w), b1 = Pack<4>::ld(p.tb + g.toff[t1], w),
+                          c1 = Pack<4>::ld(p.tc + g.toff[t1], w);
+            const Pack<4> a2 = Pack<4>::ld(p.ta + g.toff[t2], w), b2 = Pack<4>::ld(p.tb + g.toff[t2], w),
+                          c2 = Pack<4>::ld(p.tc + g.toff[t2], w);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                G.v[k] = gs.v[k] ^ and_finish<PARTY>(sd1.v[k] ^ rd1.v[k], sg1.v[k] ^ rg1.v[k], a1.v[k], b1.v[k], c1.v[k]);
+                P.v[k] = and_finish<PARTY>(sd2.v[k] ^ rd2.v[k], sg2.v[k] ^ rg2.v[k], a2.v[k], b2.v[k], c2.v[k]);
+            }
+        }
+        Pack<W> X, Gk, Y1, Y2;
+#pragma unroll
+        for (int k = 0; k < W; ++k) {
+            const u64 Glo = G.v[2 * k], Ghi = G.v[2 * k + 1], Plo = P.v[2 * k], Phi = P.v[2 * k + 1];
+            X.v[k] = (Plo & A) | rotl<d>(Phi & A);           // P[p]
+            Gk.v[k] = (Glo & A) | rotl<d>(Ghi & A);          // G[p]
+            Y1.v[k] = rotl<d>(Glo & B) | rotl<2 * d>(Ghi & B);   // G[p - d] moved to p
+            Y2.v[k] = rotl<d>(Plo & B) | rotl<2 * d>(Phi & B);   // P[p - d] moved to p
+        }
+        constexpr int u1 = 1 + 2 * LEVEL, u2 = 2 + 2 * LEVEL;
+        const size_t pl = g.pw[LEVEL];
+        u64* so = p.sendL + g.loff[LEVEL];
+        const Pack<W> na1 = Pack<W>::ld(p.ta + g.toff[u1], j), nb1 = Pack<W>::ld(p.tb + g.toff[u1], j);
+        Pack<W> d1, g1;
+#pragma unroll
+        for (int k = 0; k < W; ++k) { d1.v[k] = X.v[k] ^ na1.v[k]; g1.v[k] = Y1.v[k] ^ nb1.v[k]; }
+        d1.st(so, j); g1.st(so + pl, j);
+        if constexpr (LEVEL < 5) {
+            const Pack<W> na2 = Pack<W>::ld(p.ta + g.toff[u2], j), nb2 = Pack<W>::ld(p.tb + g.toff[u2], j);
+            Pack<W> d2, g2;
+#pragma unroll
+            for (int k = 0; k < W; ++k) { d2.v[k] = X.v[k] ^ na2.v[k]; g2.v[k] = Y2.v[k] ^ nb2.v[k]; }
+            d2.st(so + 2 * pl, j); g2.st(so + 3 * pl, j);
+        }
+        Gk.st(p.gsel + g.goff[LEVEL], j);
+    }
+}
+
+// Packed K_sign: finish level 5; element i's carry into bit 63 sits at bit
+// (62 + i) mod 64 of word i / 64.
+template <int PARTY, int V>
+__device__ __forceinline__ void b_psign(const ReluParty& p, const MsbGeom& g, size_t lo, size_t hi)
+{
+    const size_t p5 = g.pw[5];
+    const u64* sp = p.sendL + g.loff[5]; const u64* rp = p.recvL + g.loff[5];
+    const u64* gs = p.gsel + g.goff[5];
+    const u64 *a = p.ta + g.toff[11], *b = p.tb + g.toff[11], *c = p.tc + g.toff[11];
+    FOR_ELEMS(V) {
+        u8 top[V], rb[V], sb[V], mb[V];
+        ld_bytes<V>(p.p63, i, top); ld_bytes<V>(p.rb, i, rb);
+        size_t w_have = ~(size_t)0; u64 Gw = 0;
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            const size_t w = (i + k) >> 6;
+            if (w != w_have) {
+                Gw = gs[w] ^ and_finish<PARTY>(sp[w] ^ rp[w], sp[p5 + w] ^ rp[p5 + w], a[w], b[w], c[w]);
+                w_have = w;
+            }
+            sb[k] = (u8)(top[k] ^ (u8)((Gw >> ((62 + i + k) & 63)) & 1));
+            mb[k] = (u8)(sb[k] ^ rb[k]);
+        }
+        if (p.s_bit) st_bytes<V>(p.s_bit, i, sb);
+        st_bytes<V>(p.sendb, i, mb);
+    }
+}
+
+// Offline helper: triple-major [12][n] words -> the packed layout (blockIdx.y = triple).
+__global__ __launch_bounds__(kThreads) void k_pack_triples(const u64* __restrict__ in, u64* __restrict__ out, MsbGeom g)
+{
+    const int t = blockIdx.y;
+    const size_t n = g.n, stride = (size_t)gridDim.x * blockDim.x;
+    const size_t first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t == 0) {
+        for (size_t i = first; i < g.toff[1]; i += stride) out[i] = i < n ? in[i] : 0;
+        return;
+    }
+    const int l = (t - 1) / 2, s = 2 << l;
+    u64 m = 0;
+    for (int q = s - 2; q < 63; q += s) m |= (u64)1 << q;
+    for (size_t j = first; j < g.pw[l]; j += stride) {
+        u64 acc = 0;
+        for (int k = 0; k < s; ++k) {
+            const size_t e = j * s + k;
+            if (e < n) { const u64 v = in[(size_t)t * n + e] & m; acc |= k ? (v << k) | (v >> (64 - k)) : v; }
+        }
+        out[g.toff[t] + j] = acc;
+    }
+}
+
 // rows x len words, both sides with pitch `pitch` words: the per-round wire copy
 // blockIdx.y selects the direction: 0 = party 0 -> party 1, 1 = party 1 -> party 0
 __global__ __launch_bounds__(kThreads) void k_wire_words(const u64* __restrict__ src0, u64* __restrict__ dst0,
@@ -304,6 +502,7 @@ struct ReluWs {
     u64 *send[2], *recv[2];     // [4][n]
     u8 *sendb[2], *recvb[2];
     u64 *G[2], *P[2]; u8* p63[2];
+    u64 *sendL[2], *recvL[2], *gsel[2];     // packed levels only
     size_t bytes; bool ok;
 };
 
@@ -315,6 +514,21 @@ ReluWs carve_relu(u8* base, size_t cap, size_t n)
         r.send[i] = w.take<u64>(4 * n); r.recv[i] = w.take<u64>(4 * n);
         r.sendb[i] = w.take<u8>(n); r.recvb[i] = w.take<u8>(n);
         r.G[i] = w.take<u64>(n); r.P[i] = w.take<u64>(n); r.p63[i] = w.take<u8>(n);
+    }
+    r.bytes = w.off; r.ok = w.ok;
+    return r;
+}
+
+ReluWs carve_relu_msb(u8* base, size_t cap, size_t n, const MsbGeom& g)
+{
+    WsAlloc w(base, cap);
+    ReluWs r{};
+    for (int i = 0; i < 2; ++i) {
+        r.send[i] = w.take<u64>(2 * n); r.recv[i] = w.take<u64>(2 * n);
+        r.sendb[i] = w.take<u8>(n); r.recvb[i] = w.take<u8>(n);
+        r.P[i] = w.take<u64>(n); r.p63[i] = w.take<u8>(n);
+        r.sendL[i] = w.take<u64>(g.words_level_blocks); r.recvL[i] = w.take<u64>(g.words_level_blocks);
+        r.gsel[i] = w.take<u64>(g.words_gsel);
     }
     r.bytes = w.off; r.ok = w.ok;
     return r;
@@ -367,6 +581,62 @@ void launch_stage(int stage, hipStream_t st, const ReluParty& p0, const ReluPart
     }
 }
 
+// The packed chain: stages 1..7 work on packed words, the others are shared.
+template <int STAGE, int PARTY, int V>
+__device__ __forceinline__ void stage_body_msb(const ReluParty& p, const MsbGeom& g, size_t lo, size_t hi)
+{
+    if constexpr (STAGE == 0) b_first<PARTY, V>(p, lo, hi);
+    else if constexpr (STAGE == 1) b_plevel<PARTY, 0, (V == 4 ? 2 : 1)>(p, g, lo, hi);
+    else if constexpr (STAGE >= 2 && STAGE <= 6) b_plevel<PARTY, STAGE - 1, 2>(p, g, lo, hi);
+    else if constexpr (STAGE == 7) b_psign<PARTY, V>(p, g, lo, hi);
+    else if constexpr (STAGE == 8) b_b2a<PARTY, V>(p, lo, hi);
+    else b_select<PARTY, V>(p, lo, hi);
+}
+
+template <int STAGE, int V>
+__global__ __launch_bounds__(kThreads) void k_relu_msb_stage(ReluParty p0, ReluParty p1, MsbGeom g, int only,
+                                                             size_t lo, size_t hi)
+{
+    const int party = only >= 0 ? only : (int)blockIdx.y;
+    if (party == 0) stage_body_msb<STAGE, 0, V>(p0, g, lo, hi);
+    else            stage_body_msb<STAGE, 1, V>(p1, g, lo, hi);
+}
+
+template <int STAGE, int V>
+void launch_msb_stage_t(hipStream_t st, const ReluParty& p0, const ReluParty& p1, const MsbGeom& g, int only,
+                        size_t lo, size_t hi)
+{
+    size_t threads;
+    if (STAGE >= 1 && STAGE <= 6) {
+        const int level = STAGE - 1, per_thread = (STAGE == 1 && V != 4) ? 1 : 2;
+        const size_t words = ((hi + ((size_t)2 << level) - 1) >> (level + 1)) - (lo >> (level + 1));
+        threads = (words + per_thread - 1) / per_thread;
+    } else {
+        threads = (hi - lo + V - 1) / V;
+    }
+    const dim3 grid(grid_for(threads), only >= 0 ? 1 : 2), block(kThreads);
+    hipLaunchKernelGGL((k_relu_msb_stage<STAGE, V>), grid, block, 0, st, p0, p1, g, only, lo, hi);
+}
+
+template <int V>
+void launch_msb_stage(int stage, hipStream_t st, const ReluParty& p0, const ReluParty& p1, const MsbGeom& g,
+                      int only, size_t lo, size_t hi)
+{
+    switch (stage) {
+    case 0: launch_msb_stage_t<0, V>(st, p0, p1, g, only, lo, hi); break;
+    case 1: launch_msb_stage_t<1, V>(st, p0, p1, g, only, lo, hi); break;
+    case 2: launch_msb_stage_t<2, V>(st, p0, p1, g, only, lo, hi); break;
+    case 3: launch_msb_stage_t<3, V>(st, p0, p1, g, only, lo, hi); break;
+    case 4: launch_msb_stage_t<4, V>(st, p0, p1, g, only, lo, hi); break;
+    case 5: launch_msb_stage_t<5, V>(st, p0, p1, g, only, lo, hi); break;
+    case 6: launch_msb_stage_t<6, V>(st, p0, p1, g, only, lo, hi); break;
+    case 7: launch_msb_stage_t<7, V>(st, p0, p1, g, only, lo, hi); break;
+    case 8: launch_msb_stage_t<8, V>(st, p0, p1, g, only, lo, hi); break;
+    case 9: launch_msb_stage_t<9, V>(st, p0, p1, g, only, lo, hi); break;
+    default: break;
+    }
+}
+
 // words (rows of the [4][n] buffer) exchanged after each stage; 0 = byte exchange
 inline int words_after(int stage)
 {
@@ -393,17 +663,22 @@ int wire_words(mpc_ctx* c, const u64* src0, u64* dst0, const u64* src1, u64* dst
     return MPC_OK;
 }
 
-// The protocol on n elements whose buffers are described by parties[2].
-int relu_run(mpc_ctx* c, ReluParty (&pp)[2], size_t n, int n_chunks)
+// The protocol on n elements whose buffers are described by parties[2].  With
+// `geom` the carry chain runs on packed words (mpc_relu_msb), without it on
+// whole words.
+int relu_run(mpc_ctx* c, ReluParty (&pp)[2], size_t n, int n_chunks, const MsbGeom* geom = nullptr)
 {
-    if (n_chunks == 0) {
+    const bool one_queue = c->s[0] == c->s[1] && c->s[1] == c->s[2];   // in-order queue: no events needed
+    // chunk boundaries: multiples of four elements, and of 256 on the packed path
+    // (four whole words of the deepest level)
+    const size_t align = geom ? 256 : 4;
+    const size_t auto_elems = geom ? kAutoChunkElemsPacked : kAutoChunkElems;
+    if (n_chunks == 0)
         // automatic: about a million elements per chunk on a single queue (the chunk's
         // state then survives in the last-level cache from round to round), one chunk otherwise
-        const bool one_q = c->s[0] == c->s[1] && c->s[1] == c->s[2];
-        n_chunks = one_q ? (int)((n + kAutoChunkElems / 2) / kAutoChunkElems) : 1;
-    }
+        n_chunks = one_queue ? (int)((n + auto_elems / 2) / auto_elems) : 1;
     if (n_chunks > kMaxChunks) n_chunks = kMaxChunks;
-    if ((size_t)n_chunks > (n + 3) / 4) n_chunks = (int)((n + 3) / 4);
+    if ((size_t)n_chunks > (n + align - 1) / align) n_chunks = (int)((n + align - 1) / align);
     if (n_chunks < 1) n_chunks = 1;
     // 16-byte accesses need even n (so that every [k][n] row stays aligned) and aligned bases;
     // four elements per thread additionally need n % 4 == 0 and 4-byte aligned byte arrays
@@ -418,12 +693,54 @@ int relu_run(mpc_ctx* c, ReluParty (&pp)[2], size_t n, int n_chunks)
         if (((uintptr_t)pp[i].rb & 3) || (pp[i].s_bit && ((uintptr_t)pp[i].s_bit & 3))) vec4 = false;
     size_t lo[kMaxChunks], hi[kMaxChunks];
     for (int m = 0; m < n_chunks; ++m) {
-        lo[m] = (n * m / n_chunks) & ~(size_t)3;
-        hi[m] = (m == n_chunks - 1) ? n : ((n * (m + 1) / n_chunks) & ~(size_t)3);
+        lo[m] = (n * m / n_chunks) & ~(align - 1);
+        hi[m] = (m == n_chunks - 1) ? n : ((n * (m + 1) / n_chunks) & ~(align - 1));
     }
     hipStream_t P[2] = { c->s[0], c->s[1] }, Wr = c->s[2];
     hipEvent_t got[kMaxChunks];
-    const bool one_queue = P[0] == P[1] && P[1] == Wr;      // in-order queue: no events needed
+
+    // stage `stage` on elements [l, h): both parties in one launch (only = -1) or party `only`
+    auto launch = [&](int stage, hipStream_t st, int only, size_t l, size_t h) -> int {
+        if (geom) {
+            if (vec4)     launch_msb_stage<4>(stage, st, pp[0], pp[1], *geom, only, l, h);
+            else if (vec) launch_msb_stage<2>(stage, st, pp[0], pp[1], *geom, only, l, h);
+            else          launch_msb_stage<1>(stage, st, pp[0], pp[1], *geom, only, l, h);
+        } else {
+            if (vec4)     launch_stage<4>(stage, st, pp[0], pp[1], only, l, h);
+            else if (vec) launch_stage<2>(stage, st, pp[0], pp[1], only, l, h);
+            else          launch_stage<1>(stage, st, pp[0], pp[1], only, l, h);
+        }
+        MPC_HIP(c, hipGetLastError());
+        return MPC_OK;
+    };
+    // the exchange that follows `stage` (-1: the A2B masks); *sent = false if the stage sends nothing
+    auto exchange = [&](int stage, size_t l, size_t h, bool* sent) -> int {
+        *sent = true;
+        if (stage < 0)
+            return wire_words(c, pp[0].r, const_cast<u64*>(pp[1].recv), pp[1].r, const_cast<u64*>(pp[0].recv),
+                              n, l, h, 1, vec);
+        const int rows = words_after(stage);
+        if (rows < 0) { *sent = false; return MPC_OK; }
+        if (rows == 0) {
+            hipLaunchKernelGGL(k_wire_bytes, dim3(grid_for(h - l), 2), dim3(kThreads), 0, Wr,
+                               pp[0].sendb, const_cast<u8*>(pp[1].recvb), pp[1].sendb, const_cast<u8*>(pp[0].recvb), l, h);
+            MPC_HIP(c, hipGetLastError());
+            return MPC_OK;
+        }
+        if (geom && stage >= ST_LEVEL0 && stage < ST_SIGN) {
+            // packed level: `rows` rows of pw words; the range is rounded to whole 16-byte units
+            const int level = stage - ST_LEVEL0;
+            const size_t wl = l >> (level + 1);
+            const size_t wh = ((((h + ((size_t)2 << level) - 1) >> (level + 1)) + 1) & ~(size_t)1);
+            const size_t off = geom->loff[level];
+            return wire_words(c, pp[0].sendL + off, const_cast<u64*>(pp[1].recvL) + off,
+                              pp[1].sendL + off, const_cast<u64*>(pp[0].recvL) + off,
+                              geom->pw[level], wl, wh, rows, true);
+        }
+        return wire_words(c, pp[0].send, const_cast<u64*>(pp[1].recv), pp[1].send, const_cast<u64*>(pp[0].recv),
+                          n, l, h, rows, vec);
+    };
+    bool sent;
 
     if (one_queue) {
         // One in-order queue: chunk-major order.  A chunk runs through all ten
@@ -431,65 +748,34 @@ int relu_run(mpc_ctx* c, ReluParty (&pp)[2], size_t n, int n_chunks)
         // buffers are still in the last-level cache when the next round reads them.
         for (int m = 0; m < n_chunks; ++m) {
             if (hi[m] <= lo[m]) continue;
-            MPC_TRY(wire_words(c, pp[0].r, const_cast<u64*>(pp[1].recv), pp[1].r, const_cast<u64*>(pp[0].recv),
-                               n, lo[m], hi[m], 1, vec));
+            MPC_TRY(exchange(-1, lo[m], hi[m], &sent));
             for (int stage = 0; stage < ST_COUNT; ++stage) {
-                const int rows = words_after(stage);
-                if (vec4)     launch_stage<4>(stage, P[0], pp[0], pp[1], -1, lo[m], hi[m]);
-                else if (vec) launch_stage<2>(stage, P[0], pp[0], pp[1], -1, lo[m], hi[m]);
-                else          launch_stage<1>(stage, P[0], pp[0], pp[1], -1, lo[m], hi[m]);
-                MPC_HIP(c, hipGetLastError());
-                if (rows == 0) {
-                    hipLaunchKernelGGL(k_wire_bytes, dim3(grid_for(hi[m] - lo[m]), 2), dim3(kThreads), 0, Wr,
-                                       pp[0].sendb, const_cast<u8*>(pp[1].recvb), pp[1].sendb, const_cast<u8*>(pp[0].recvb),
-                                       lo[m], hi[m]);
-                    MPC_HIP(c, hipGetLastError());
-                } else if (rows > 0) {
-                    MPC_TRY(wire_words(c, pp[0].send, const_cast<u64*>(pp[1].recv), pp[1].send, const_cast<u64*>(pp[0].recv),
-                                       n, lo[m], hi[m], rows, vec));
-                }
+                MPC_TRY(launch(stage, P[0], -1, lo[m], hi[m]));
+                MPC_TRY(exchange(stage, lo[m], hi[m], &sent));
             }
         }
         return MPC_OK;
     }
 
-    // Alg. 2: each party sends the mask half of the XOR sharing of its own share
+    // Alg. 4 order on three queues.  Alg. 2 first: each party sends the mask half
+    // of the XOR sharing of its own share
     for (int m = 0; m < n_chunks; ++m) {
         if (hi[m] <= lo[m]) continue;
-        MPC_TRY(wire_words(c, pp[0].r, const_cast<u64*>(pp[1].recv), pp[1].r, const_cast<u64*>(pp[0].recv),
-                           n, lo[m], hi[m], 1, vec));
-        if (!one_queue) { got[m] = next_event(c); MPC_HIP(c, hipEventRecord(got[m], Wr)); }
+        MPC_TRY(exchange(-1, lo[m], hi[m], &sent));
+        got[m] = next_event(c); MPC_HIP(c, hipEventRecord(got[m], Wr));
     }
     for (int stage = 0; stage < ST_COUNT; ++stage) {
-        const int rows = words_after(stage);
+        const bool sends = words_after(stage) >= 0;
         for (int m = 0; m < n_chunks; ++m) {
             if (hi[m] <= lo[m]) continue;
-            if (one_queue) {                 // both parties in one launch
-                if (vec4)     launch_stage<4>(stage, P[0], pp[0], pp[1], -1, lo[m], hi[m]);
-                else if (vec) launch_stage<2>(stage, P[0], pp[0], pp[1], -1, lo[m], hi[m]);
-                else          launch_stage<1>(stage, P[0], pp[0], pp[1], -1, lo[m], hi[m]);
-                MPC_HIP(c, hipGetLastError());
-            } else {
-                for (int i = 0; i < 2; ++i) {
-                    MPC_HIP(c, hipStreamWaitEvent(P[i], got[m], 0));
-                    if (vec4)     launch_stage<4>(stage, P[i], pp[0], pp[1], i, lo[m], hi[m]);
-                    else if (vec) launch_stage<2>(stage, P[i], pp[0], pp[1], i, lo[m], hi[m]);
-                    else          launch_stage<1>(stage, P[i], pp[0], pp[1], i, lo[m], hi[m]);
-                    MPC_HIP(c, hipGetLastError());
-                    if (rows >= 0) MPC_TRY(chain(c, P[i], Wr));
-                }
+            for (int i = 0; i < 2; ++i) {
+                MPC_HIP(c, hipStreamWaitEvent(P[i], got[m], 0));
+                MPC_TRY(launch(stage, P[i], i, lo[m], hi[m]));
+                if (sends) MPC_TRY(chain(c, P[i], Wr));
             }
-            if (rows < 0) continue;
-            if (rows == 0) {
-                hipLaunchKernelGGL(k_wire_bytes, dim3(grid_for(hi[m] - lo[m]), 2), dim3(kThreads), 0, Wr,
-                                   pp[0].sendb, const_cast<u8*>(pp[1].recvb), pp[1].sendb, const_cast<u8*>(pp[0].recvb),
-                                   lo[m], hi[m]);
-                MPC_HIP(c, hipGetLastError());
-            } else {
-                MPC_TRY(wire_words(c, pp[0].send, const_cast<u64*>(pp[1].recv), pp[1].send, const_cast<u64*>(pp[0].recv),
-                                   n, lo[m], hi[m], rows, vec));
-            }
-            if (!one_queue) { got[m] = next_event(c); MPC_HIP(c, hipEventRecord(got[m], Wr)); }
+            if (!sends) continue;
+            MPC_TRY(exchange(stage, lo[m], hi[m], &sent));
+            got[m] = next_event(c); MPC_HIP(c, hipEventRecord(got[m], Wr));
         }
     }
     return MPC_OK;
@@ -514,6 +800,7 @@ void fill_party(ReluParty& p, int i, const u64* x, const mpc_relu_material* m, c
     p.ma = m->ma.p[i]; p.mb = m->mb.p[i]; p.mc = m->mc.p[i];
     p.send = w.send[i]; p.recv = w.recv[i]; p.sendb = w.sendb[i]; p.recvb = w.recvb[i];
     p.G = w.G[i]; p.P = w.P[i]; p.p63 = w.p63[i];
+    p.sendL = w.sendL[i]; p.recvL = w.recvL[i]; p.gsel = w.gsel[i];
     p.y = y; p.s_bit = s_bit; p.s_arith = s_arith; p.n = n;
 }
 
@@ -556,6 +843,96 @@ __global__ __launch_bounds__(kThreads) void k_pool_l2(const u64* __restrict__ x,
     }
 }
 
+// Shared body of the two entry points; `packed` selects the MSB-only chain.
+int relu_entry(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat, mpc_share y, size_t n, int n_chunks,
+               uint8_t* const s_bit[2], uint64_t* const s_arith[2], bool packed)
+{
+    if (!c || n == 0 || n_chunks < 0 || !x.p[0] || !x.p[1] || !y.p[0] || !y.p[1]) return MPC_EINVAL;
+    MPC_TRY(check_material(mat));
+    MsbGeom g{};
+    ReluWs w;
+    if (packed) {
+        for (int i = 0; i < 2; ++i)
+            if (((uintptr_t)mat->and_a.p[i] | (uintptr_t)mat->and_b.p[i] | (uintptr_t)mat->and_c.p[i]) & 15) return MPC_EINVAL;
+        g = msb_geom(n);
+        w = carve_relu_msb(c->ws, c->ws_bytes, n, g);
+    } else {
+        w = carve_relu(c->ws, c->ws_bytes, n);
+    }
+    if (!w.ok) return MPC_ENOMEM;
+    MPC_TRY(lane_join(c));
+    const int pi = prof_begin(c, MPC_PROF_RELU, c->s[0]);
+    ReluParty pp[2];
+    for (int i = 0; i < 2; ++i)
+        fill_party(pp[i], i, x.p[i], mat, w, y.p[i], s_bit ? s_bit[i] : nullptr, s_arith ? s_arith[i] : nullptr, n);
+    MPC_TRY(relu_run(c, pp, n, n_chunks, packed ? &g : nullptr));
+    if (pi >= 0) {      // the region ends when both parties' last kernels are done
+        MPC_TRY(chain(c, c->s[1], c->s[0]));
+        prof_end(c, MPC_PROF_RELU, pi, c->s[0]);
+    }
+    return MPC_OK;
+}
+
+size_t maxpool_ws(int B, int H, int W, int C, bool packed)
+{
+    if (B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1)) return 0;
+    const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
+    // per party: d1 (2 n_out), r1 (2 n_out), v (n_out), d2 (n_out); then the ReLU's own scratch
+    const size_t relu = packed ? carve_relu_msb(nullptr, 0, 2 * n_out, msb_geom(2 * n_out)).bytes
+                               : carve_relu(nullptr, 0, 2 * n_out).bytes;
+    return 2 * (align_up(2 * n_out * 8) * 2 + align_up(n_out * 8) * 2) + relu;
+}
+
+int maxpool_entry(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat1, const mpc_relu_material* mat2,
+                  mpc_share y, int B, int H, int W, int C, int n_chunks, bool packed)
+{
+    if (!c || B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1) || n_chunks < 0 ||
+        !x.p[0] || !x.p[1] || !y.p[0] || !y.p[1])
+        return MPC_EINVAL;
+    MPC_TRY(check_material(mat1));
+    MPC_TRY(check_material(mat2));
+    if (packed)
+        for (const mpc_relu_material* m : { mat1, mat2 })
+            for (int i = 0; i < 2; ++i)
+                if (((uintptr_t)m->and_a.p[i] | (uintptr_t)m->and_b.p[i] | (uintptr_t)m->and_c.p[i]) & 15) return MPC_EINVAL;
+    const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
+    WsAlloc wa(c->ws, c->ws_bytes);
+    u64 *d1[2], *r1[2], *v[2], *d2[2];
+    for (int i = 0; i < 2; ++i) {
+        d1[i] = wa.take<u64>(2 * n_out); r1[i] = wa.take<u64>(2 * n_out);
+        v[i] = wa.take<u64>(n_out); d2[i] = wa.take<u64>(n_out);
+    }
+    if (!wa.ok) return MPC_ENOMEM;
+    const MsbGeom g1 = msb_geom(2 * n_out), g2 = msb_geom(n_out);
+    // both conversions use the scratch carved for the larger one
+    const ReluWs w1 = packed ? carve_relu_msb(c->ws + wa.off, c->ws_bytes - wa.off, 2 * n_out, g1)
+                             : carve_relu(c->ws + wa.off, c->ws_bytes - wa.off, 2 * n_out);
+    const ReluWs w2 = packed ? carve_relu_msb(c->ws + wa.off, c->ws_bytes - wa.off, n_out, g2) : w1;
+    if (!w1.ok || !w2.ok) return MPC_ENOMEM;
+    MPC_TRY(lane_join(c));
+    const dim3 grid(grid_for(n_out)), block(kThreads);
+    ReluParty pp[2];
+    // first tournament level: max(p00, p01) and max(p10, p11)
+    for (int i = 0; i < 2; ++i) {
+        hipLaunchKernelGGL(k_pool_l1, grid, block, 0, c->s[i], x.p[i], d1[i], B, H, W, C);
+        MPC_HIP(c, hipGetLastError());
+        fill_party(pp[i], i, d1[i], mat1, w1, r1[i], nullptr, nullptr, 2 * n_out);
+    }
+    MPC_TRY(lane_join(c));
+    MPC_TRY(relu_run(c, pp, 2 * n_out, n_chunks, packed ? &g1 : nullptr));
+    // second level: max of the two winners; out = v + ReLU(u - v)
+    for (int i = 0; i < 2; ++i) {
+        hipLaunchKernelGGL(k_pool_l2, grid, block, 0, c->s[i], x.p[i], r1[i], v[i], d2[i], B, H, W, C);
+        MPC_HIP(c, hipGetLastError());
+        fill_party(pp[i], i, d2[i], mat2, w2, y.p[i], nullptr, nullptr, n_out);
+    }
+    MPC_TRY(lane_join(c));
+    MPC_TRY(relu_run(c, pp, n_out, n_chunks, packed ? &g2 : nullptr));
+    for (int i = 0; i < 2; ++i)
+        MPC_TRY(launch_add(c, c->s[i], y.p[i], v[i], y.p[i], n_out));
+    return MPC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -566,30 +943,38 @@ size_t mpc_relu_workspace_bytes(size_t n)
     return carve_relu(nullptr, 0, n).bytes;
 }
 
-size_t mpc_maxpool_workspace_bytes(int B, int H, int W, int C)
+size_t mpc_relu_msb_workspace_bytes(size_t n)
 {
-    if (B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1)) return 0;
-    const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
-    // per party: d1 (2 n_out), r1 (2 n_out), v (n_out), d2 (n_out); then the ReLU's own scratch
-    return 2 * (align_up(2 * n_out * 8) * 2 + align_up(n_out * 8) * 2) + carve_relu(nullptr, 0, 2 * n_out).bytes;
+    if (n == 0) return 0;
+    return carve_relu_msb(nullptr, 0, n, msb_geom(n)).bytes;
 }
+
+size_t mpc_relu_packed_words(size_t n) { return n ? msb_geom(n).words_triples : 0; }
+
+size_t mpc_maxpool_workspace_bytes(int B, int H, int W, int C) { return maxpool_ws(B, H, W, C, false); }
+size_t mpc_maxpool_msb_workspace_bytes(int B, int H, int W, int C) { return maxpool_ws(B, H, W, C, true); }
 
 int mpc_relu(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat, mpc_share y, size_t n, int n_chunks,
              uint8_t* const s_bit[2], uint64_t* const s_arith[2])
 {
-    if (!c || n == 0 || n_chunks < 0 || !x.p[0] || !x.p[1] || !y.p[0] || !y.p[1]) return MPC_EINVAL;
-    MPC_TRY(check_material(mat));
-    ReluWs w = carve_relu(c->ws, c->ws_bytes, n);
-    if (!w.ok) return MPC_ENOMEM;
+    return relu_entry(c, x, mat, y, n, n_chunks, s_bit, s_arith, false);
+}
+
+int mpc_relu_msb(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat, mpc_share y, size_t n, int n_chunks,
+                 uint8_t* const s_bit[2], uint64_t* const s_arith[2])
+{
+    return relu_entry(c, x, mat, y, n, n_chunks, s_bit, s_arith, true);
+}
+
+int mpc_relu_pack_triples(mpc_ctx* c, mpc_cshare words, mpc_share packed, size_t n)
+{
+    if (!c || n == 0 || !words.p[0] || !words.p[1] || !packed.p[0] || !packed.p[1]) return MPC_EINVAL;
+    const MsbGeom g = msb_geom(n);
     MPC_TRY(lane_join(c));
-    const int pi = prof_begin(c, MPC_PROF_RELU, c->s[0]);
-    ReluParty pp[2];
-    for (int i = 0; i < 2; ++i)
-        fill_party(pp[i], i, x.p[i], mat, w, y.p[i], s_bit ? s_bit[i] : nullptr, s_arith ? s_arith[i] : nullptr, n);
-    MPC_TRY(relu_run(c, pp, n, n_chunks));
-    if (pi >= 0) {      // the region ends when both parties' last kernels are done
-        MPC_TRY(chain(c, c->s[1], c->s[0]));
-        prof_end(c, MPC_PROF_RELU, pi, c->s[0]);
+    for (int i = 0; i < 2; ++i) {
+        hipLaunchKernelGGL(k_pack_triples, dim3(grid_for(n), MPC_N_AND_TRIPLES), dim3(kThreads), 0, c->s[i],
+                           words.p[i], packed.p[i], g);
+        MPC_HIP(c, hipGetLastError());
     }
     return MPC_OK;
 }
@@ -597,43 +982,13 @@ int mpc_relu(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat, mpc_share y
 int mpc_maxpool2x2(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat1, const mpc_relu_material* mat2,
                    mpc_share y, int B, int H, int W, int C, int n_chunks)
 {
-    if (!c || B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1) || n_chunks < 0 ||
-        !x.p[0] || !x.p[1] || !y.p[0] || !y.p[1])
-        return MPC_EINVAL;
-    MPC_TRY(check_material(mat1));
-    MPC_TRY(check_material(mat2));
-    const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
-    WsAlloc wa(c->ws, c->ws_bytes);
-    u64 *d1[2], *r1[2], *v[2], *d2[2];
-    for (int i = 0; i < 2; ++i) {
-        d1[i] = wa.take<u64>(2 * n_out); r1[i] = wa.take<u64>(2 * n_out);
-        v[i] = wa.take<u64>(n_out); d2[i] = wa.take<u64>(n_out);
-    }
-    if (!wa.ok) return MPC_ENOMEM;
-    ReluWs w = carve_relu(c->ws + wa.off, c->ws_bytes - wa.off, 2 * n_out);
-    if (!w.ok) return MPC_ENOMEM;
-    MPC_TRY(lane_join(c));
-    const dim3 grid(grid_for(n_out)), block(kThreads);
-    ReluParty pp[2];
-    // first tournament level: max(p00, p01) and max(p10, p11)
-    for (int i = 0; i < 2; ++i) {
-        hipLaunchKernelGGL(k_pool_l1, grid, block, 0, c->s[i], x.p[i], d1[i], B, H, W, C);
-        MPC_HIP(c, hipGetLastError());
-        fill_party(pp[i], i, d1[i], mat1, w, r1[i], nullptr, nullptr, 2 * n_out);
-    }
-    MPC_TRY(lane_join(c));
-    MPC_TRY(relu_run(c, pp, 2 * n_out, n_chunks));
-    // second level: max of the two winners; out = v + ReLU(u - v)
-    for (int i = 0; i < 2; ++i) {
-        hipLaunchKernelGGL(k_pool_l2, grid, block, 0, c->s[i], x.p[i], r1[i], v[i], d2[i], B, H, W, C);
-        MPC_HIP(c, hipGetLastError());
-        fill_party(pp[i], i, d2[i], mat2, w, y.p[i], nullptr, nullptr, n_out);
-    }
-    MPC_TRY(lane_join(c));
-    MPC_TRY(relu_run(c, pp, n_out, n_chunks));
-    for (int i = 0; i < 2; ++i)
-        MPC_TRY(launch_add(c, c->s[i], y.p[i], v[i], y.p[i], n_out));
-    return MPC_OK;
+    return maxpool_entry(c, x, mat1, mat2, y, B, H, W, C, n_chunks, false);
+}
+
+int mpc_maxpool2x2_msb(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat1, const mpc_relu_material* mat2,
+                       mpc_share y, int B, int H, int W, int C, int n_chunks)
+{
+    return maxpool_entry(c, x, mat1, mat2, y, B, H, W, C, n_chunks, true);
 }
 
 }  // extern "C"

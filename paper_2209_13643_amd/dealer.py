@@ -79,11 +79,15 @@ def matmul_layer(lane: "mpc.Lane", g, M, K, N, x_std, w_std, batch=None):
     return d
 
 
-def relu_material(g, n: int, device) -> dict:
+def relu_material(g, n: int, device, packed: bool = False) -> dict:
+    """Secure-ReLU material for n elements.  packed=True draws the AND triples
+    directly in the packed layout of mpc_relu_msb (uniform words satisfy the
+    bit-wise triple relation in any layout)."""
     m = {}
     m["r"] = (rand_words(g, (n,), device), rand_words(g, (n,), device))
-    a = (rand_words(g, (mpc.N_AND_TRIPLES, n), device), rand_words(g, (mpc.N_AND_TRIPLES, n), device))
-    b = (rand_words(g, (mpc.N_AND_TRIPLES, n), device), rand_words(g, (mpc.N_AND_TRIPLES, n), device))
+    tshape = (mpc.lib().mpc_relu_packed_words(n),) if packed else (mpc.N_AND_TRIPLES, n)
+    a = (rand_words(g, tshape, device), rand_words(g, tshape, device))
+    b = (rand_words(g, tshape, device), rand_words(g, tshape, device))
     m["and_a"], m["and_b"] = a, b
     m["and_c"] = share_xor(g, (a[0] ^ a[1]) & (b[0] ^ b[1]))
     rb = tuple(torch.randint(0, 2, (n,), generator=g, device=device, dtype=torch.uint8) for _ in range(2))

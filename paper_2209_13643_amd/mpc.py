@@ -41,6 +41,8 @@ EXPORTS = [
     "mpc_matmul_workspace_bytes", "mpc_conv2d_workspace_bytes", "mpc_relu_workspace_bytes",
     "mpc_maxpool_workspace_bytes", "mpc_open", "mpc_sub", "mpc_beaver_matmul", "mpc_conv2d", "mpc_truncate",
     "mpc_relu", "mpc_maxpool2x2", "mpc_ring_matmul", "mpc_ring_conv2d",
+    "mpc_relu_msb_workspace_bytes", "mpc_maxpool_msb_workspace_bytes", "mpc_relu_packed_words",
+    "mpc_relu_pack_triples", "mpc_relu_msb", "mpc_maxpool2x2_msb",
 ]
 
 _lib = None
@@ -70,6 +72,10 @@ def lib():
     L.mpc_conv2d_workspace_bytes.argtypes = [c_int] * 9; L.mpc_conv2d_workspace_bytes.restype = c_size_t
     L.mpc_relu_workspace_bytes.argtypes = [c_size_t]; L.mpc_relu_workspace_bytes.restype = c_size_t
     L.mpc_maxpool_workspace_bytes.argtypes = [c_int] * 4; L.mpc_maxpool_workspace_bytes.restype = c_size_t
+    L.mpc_relu_msb_workspace_bytes.argtypes = [c_size_t]; L.mpc_relu_msb_workspace_bytes.restype = c_size_t
+    L.mpc_maxpool_msb_workspace_bytes.argtypes = [c_int] * 4; L.mpc_maxpool_msb_workspace_bytes.restype = c_size_t
+    L.mpc_relu_packed_words.argtypes = [c_size_t]; L.mpc_relu_packed_words.restype = c_size_t
+    L.mpc_relu_pack_triples.argtypes = [c_void_p, CShare, CShare, c_size_t]
     L.mpc_open.argtypes = [c_void_p, CShare, _P64, c_size_t]
     L.mpc_sub.argtypes = [c_void_p, CShare, CShare, CShare, c_size_t]
     L.mpc_beaver_matmul.argtypes = [c_void_p] + [CShare] * 6 + [c_int] * 4 + [_P64, c_int, c_int]
@@ -79,6 +85,8 @@ def lib():
                            POINTER(_P8 * 2), POINTER(_P64 * 2)]
     L.mpc_maxpool2x2.argtypes = [c_void_p, CShare, POINTER(ReluMaterial), POINTER(ReluMaterial), CShare,
                                  c_int, c_int, c_int, c_int, c_int]
+    L.mpc_relu_msb.argtypes = L.mpc_relu.argtypes
+    L.mpc_maxpool2x2_msb.argtypes = L.mpc_maxpool2x2.argtypes
     L.mpc_ring_matmul.argtypes = [c_void_p, _P64, _P64, _P64] + [c_int] * 4
     L.mpc_ring_conv2d.argtypes = [c_void_p, _P64, _P64, _P64] + [c_int] * 9
     _lib = L
@@ -131,13 +139,15 @@ def material_to_device(mat: dict, device="cuda:0") -> dict:
     return {k: (to_device(v[0], device), to_device(v[1], device)) for k, v in mat.items()}
 
 
-def _material(mat: dict, n: int) -> ReluMaterial:
+def _material(mat: dict, n: int, packed: bool = False) -> ReluMaterial:
+    """Marshal a material dict; `packed`: and_a/b/c hold the packed layout of mpc_relu_msb."""
     m = ReluMaterial()
+    n_and = lib().mpc_relu_packed_words(n) if packed else N_AND_TRIPLES * n
     for key in ("r", "ra", "ma", "mb", "mc"):
         assert mat[key][0].numel() == n and mat[key][1].numel() == n, key
         setattr(m, key, _share(mat[key]))
     for key in ("and_a", "and_b", "and_c"):
-        assert mat[key][0].numel() == N_AND_TRIPLES * n and mat[key][1].numel() == N_AND_TRIPLES * n, key
+        assert mat[key][0].numel() == n_and and mat[key][1].numel() == n_and, key
         setattr(m, key, _share(mat[key]))
     assert mat["rb"][0].numel() == n and mat["rb"][1].numel() == n
     m.rb[0], m.rb[1] = _p8(mat["rb"][0]), _p8(mat["rb"][1])
@@ -258,27 +268,43 @@ class Lane:
         self._check(lib().mpc_truncate(self._h, _share(z), z[0].numel(), bits))
         return z
 
-    def relu(self, x, mat, n_chunks=0, want_sign=False, out=None):
+    def pack_material(self, mat: dict) -> dict:
+        """Offline helper: the same material with and_a/b/c in the packed layout of relu_msb."""
+        n = mat["r"][0].numel()
+        words = lib().mpc_relu_packed_words(n)
+        out = dict(mat)
+        for key in ("and_a", "and_b", "and_c"):
+            pk = tuple(torch.empty(words, dtype=torch.int64, device=self.device) for _ in range(2))
+            self._check(lib().mpc_relu_pack_triples(self._h, _share(mat[key]), _share(pk), n))
+            out[key] = pk
+        self.sync()
+        return out
+
+    def relu(self, x, mat, n_chunks=0, want_sign=False, out=None, packed=False):
+        """Secure ReLU; packed=True runs the sign-only carry chain on packed material (mpc_relu_msb)."""
         n = x[0].numel()
-        self.reserve(lib().mpc_relu_workspace_bytes(n))
+        fn = lib().mpc_relu_msb if packed else lib().mpc_relu
+        self.reserve(lib().mpc_relu_msb_workspace_bytes(n) if packed else lib().mpc_relu_workspace_bytes(n))
         y = out if out is not None else (torch.empty_like(x[0]), torch.empty_like(x[1]))
-        m = _material(mat, n)
+        m = _material(mat, n, packed)
         if want_sign:
             sb = tuple(torch.empty(n, dtype=torch.uint8, device=self.device) for _ in range(2))
             sa = tuple(torch.empty(n, dtype=torch.int64, device=self.device) for _ in range(2))
             sbp = (_P8 * 2)(_p8(sb[0]), _p8(sb[1])); sap = (_P64 * 2)(_p64(sa[0]), _p64(sa[1]))
-            self._check(lib().mpc_relu(self._h, _share(x), byref(m), _share(y), n, n_chunks, byref(sbp), byref(sap)))
+            self._check(fn(self._h, _share(x), byref(m), _share(y), n, n_chunks, byref(sbp), byref(sap)))
             return y, sb, sa
-        self._check(lib().mpc_relu(self._h, _share(x), byref(m), _share(y), n, n_chunks, None, None))
+        self._check(fn(self._h, _share(x), byref(m), _share(y), n, n_chunks, None, None))
         return y
 
-    def maxpool2x2(self, x, mat1, mat2, n_chunks=0):
+    def maxpool2x2(self, x, mat1, mat2, n_chunks=0, packed=False):
         B, H, W, C = x[0].shape
         n_out = B * (H // 2) * (W // 2) * C
-        self.reserve(lib().mpc_maxpool_workspace_bytes(B, H, W, C))
+        ws = lib().mpc_maxpool_msb_workspace_bytes if packed else lib().mpc_maxpool_workspace_bytes
+        self.reserve(ws(B, H, W, C))
         y = tuple(torch.empty((B, H // 2, W // 2, C), dtype=torch.int64, device=self.device) for _ in range(2))
-        m1, m2 = _material(mat1, 2 * n_out), _material(mat2, n_out)
-        self._check(lib().mpc_maxpool2x2(self._h, _share(x), byref(m1), byref(m2), _share(y), B, H, W, C, n_chunks))
+        m1, m2 = _material(mat1, 2 * n_out, packed), _material(mat2, n_out, packed)
+        fn = lib().mpc_maxpool2x2_msb if packed else lib().mpc_maxpool2x2
+        self._check(fn(self._h, _share(x), byref(m1), byref(m2), _share(y), B, H, W, C, n_chunks))
         return y
 
     # -- dealer helpers (offline phase stand-in)
