@@ -12,7 +12,9 @@ Prints one JSON line.  `value` is secure MACs/s of the Beaver convolution call
 (mask, exchange, digit recoding, int8-MFMA GEMM, truncation); the secure ReLU
 rate and the whole-step time are reported beside it.  `roofline` describes the
 digit-plane GEMM kernel against the int8 MFMA peak, `roofline_relu` the ReLU
-chain against HBM bandwidth; `cpu_baseline` is the CPU oracle timed on this
+chain against HBM bandwidth, `roofline_relu_msb` the same ReLU evaluated on the
+sign's carry chain only with bit-packed triples (mpc_relu_msb, timed on its own
+after the steps); `cpu_baseline` is the CPU oracle timed on this
 box's host cores on the same workload (a reported baseline, not a target).
 """
 from __future__ import annotations
@@ -31,6 +33,8 @@ INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_OPS_PER_SECURE_MAC = 288          # 2 parties x 2 ring GEMMs x 36 digit products x 2 ops
 RELU_BYTES_PER_ELEMENT = 86 * 8 + 2 + 216 * 8 + 137 * 8   # compulsory + openings + carried state, both parties
+# the sign-only packed chain (mpc_relu_msb), same three classes: 31.72 W + 2 B, 71.25 W + 8 B, 41.56 W + 6 B
+RELU_MSB_BYTES_PER_ELEMENT = (31.71875 + 71.25 + 41.5625) * 8 + 16
 
 
 def cpu_baseline(layer, budget_s=12.0):
@@ -125,6 +129,23 @@ def main():
     err = (rec_z[:2].double() / 65536 - ref).abs().max().item()
     assert err <= 2.0 ** -12, f"decoded conv output off by {err}"
 
+    # the sign-only packed chain on the same conv output, timed on its own
+    mat_p = dealer.relu_material(g, n, dev, packed=True)
+    y2 = tuple(torch.empty_like(z[0]) for _ in range(2))
+    torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        lane.relu(z, mat_p, out=y2, packed=True)
+    lane.sync()
+    lane.set_profiling(True); lane.profile_reset()
+    for _ in range(args.steps):
+        lane.relu(z, mat_p, out=y2, packed=True)
+    lane.sync(); torch.cuda.synchronize()
+    lane.set_profiling(False)
+    msb_ms, msb_n = lane.profile(mpc.PROF_RELU)
+    msb_ms /= msb_n
+    assert torch.equal(y2[0] + y2[1], torch.clamp(rec_z, min=0)), "mpc_relu_msb output does not reconstruct to max(z, 0)"
+    msb_gbs = RELU_MSB_BYTES_PER_ELEMENT * n / (msb_ms * 1e-3) / 1e9
+
     macs = M * K * N
     gemm_tops = INT8_OPS_PER_SECURE_MAC * macs / (gemm_ms * 1e-3) / 1e12
     relu_gbs = RELU_BYTES_PER_ELEMENT * n / (relu_ms * 1e-3) / 1e9
@@ -132,6 +153,7 @@ def main():
         "metric": "secure Z_2^64 MACs/s (Beaver GEMM) + secure ReLU elems/s, 1 GPU, online",
         "value": macs / (lin_ms * 1e-3), "unit": "secure MACs/s",
         "relu_value": n / (relu_ms * 1e-3), "relu_unit": "secure ReLU elems/s",
+        "relu_msb_value": n / (msb_ms * 1e-3),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64 ring (int8 digits, int32 accumulate)",
         "data": "synthetic",
@@ -139,6 +161,7 @@ def main():
                                "= Beaver GEMM [16384x1152]x[1152x128] + truncation + secure ReLU on 2097152 elements",
                    "parties": 2, "frac_bits": 16, "n_chunks": 1, "relu_chunks": "auto (about 2^20 elements each)", "lane": "single in-order queue",
                    "ms_beaver_conv_call": lin_ms, "ms_gemm_kernel": gemm_ms, "ms_relu_call": relu_ms,
+                   "ms_relu_msb_call": msb_ms,
                    "max_abs_err_vs_float64": err},
         "roofline": {"kernel": "k_limb_gemm<2,2,true> (both parties, [e|a_i] x [b_i';f], fused add-c + truncation)",
                      "bound": "mfma", "achieved": gemm_tops, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
@@ -152,8 +175,13 @@ def main():
         "roofline_relu": {"kernel": "secure ReLU chain: k_relu_stage<0..9> (both parties per launch) + k_wire_words / k_wire_bytes",
                           "bound": "hbm", "achieved": relu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                           "frac": relu_gbs / HBM_PEAK_GBS,
-                          "traffic": {"bytes_per_element": 3372, "source": "rocprofv3 --pmc, same summary"},
+                          "traffic": {"bytes_per_element": 3395, "source": "rocprofv3 --pmc, same summary"},
                           "bytes_per_element": RELU_BYTES_PER_ELEMENT},
+        "roofline_relu_msb": {"kernel": "sign-only packed ReLU chain: k_relu_msb_stage<0..9> + k_wire_words / k_wire_bytes",
+                              "bound": "hbm", "achieved": msb_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": msb_gbs / HBM_PEAK_GBS,
+                              "traffic": {"bytes_per_element": 1169, "source": "rocprofv3 --pmc, same summary"},
+                              "bytes_per_element": RELU_MSB_BYTES_PER_ELEMENT},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L)

@@ -19,6 +19,7 @@ from . import dealer, mpc, pipeline, synth
 INT8_PEAK = 5.0e15
 HBM_PEAK = 8.0e12
 RELU_BYTES = 3514
+RELU_MSB_BYTES = 1172.25      # the sign-only packed chain
 
 
 def layer_macs(L):
@@ -65,6 +66,18 @@ def bench_layers(idx: int, reps: int = 5):
             rl, rn = lane.profile(mpc.PROF_RELU)
             row.update(relu_n=n_out, relu_ms=rl / rn, relu_elems_per_s=n_out / (rl / rn * 1e-3),
                        hbm_frac=RELU_BYTES * n_out / (rl / rn * 1e-3) / HBM_PEAK)
+            # the same ReLU on the sign's carry chain only, packed material
+            del mat
+            mat = dealer.relu_material(g, n_out, dev, packed=True)
+            for _ in range(2):
+                lane.relu(z, mat, out=y, packed=True)
+            lane.sync(); lane.set_profiling(True); lane.profile_reset()
+            for _ in range(reps):
+                lane.relu(z, mat, out=y, packed=True)
+            lane.sync(); lane.set_profiling(False)
+            rl, rn = lane.profile(mpc.PROF_RELU)
+            row.update(msb_ms=rl / rn, msb_elems_per_s=n_out / (rl / rn * 1e-3),
+                       msb_hbm_frac=RELU_MSB_BYTES * n_out / (rl / rn * 1e-3) / HBM_PEAK)
         rows.append(row)
         del d, mat, z, y
         torch.cuda.empty_cache()
@@ -72,7 +85,7 @@ def bench_layers(idx: int, reps: int = 5):
     return wl.name, rows
 
 
-def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3):
+def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = False):
     """Config 4: serial (one lane, micro-batches one after the other) vs pipelined (one lane each)."""
     wl = synth.config_vgg16_pipeline(micro_batch)
     layers = wl.layers
@@ -84,7 +97,7 @@ def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3):
     weights = pipeline.deal_weights(g, layers, dev)
     states, xs = [], []
     for m in range(n_mb):
-        states.append(pipeline.deal_microbatch(lanes[m], g, layers, weights))
+        states.append(pipeline.deal_microbatch(lanes[m], g, layers, weights, packed_relu=packed_relu))
         X = dealer.normal_fixed(g, (micro_batch, 32, 32, 3), 1.0, dev)
         xs.append(dealer.share(g, X))
         torch.cuda.synchronize()
@@ -153,11 +166,14 @@ def main(argv):
                     f"  kernel {r['kernel_ms']:8.3f} ms  mfma {100 * r['mfma_frac']:5.1f}%")
             if "relu_ms" in r:
                 line += f"  | relu {r['relu_n']:9d} el {r['relu_ms']:7.3f} ms {r['relu_elems_per_s'] / 1e9:5.2f} G/s hbm {100 * r['hbm_frac']:5.1f}%"
+                line += f"  | sign-only {r['msb_ms']:7.3f} ms {r['msb_elems_per_s'] / 1e9:5.2f} G/s hbm {100 * r['msb_hbm_frac']:5.1f}%"
             print(line, flush=True)
         if idx == 4:
-            p = bench_pipeline()
-            print(f"  inter-batch pipeline, batch 128 = 4 x 32: serial {p['serial']['ms']:.2f} ms ({p['serial']['images_per_s']:.0f} img/s), "
-                  f"pipelined {p['pipelined']['ms']:.2f} ms ({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)
+            for packed in (False, True):
+                p = bench_pipeline(packed_relu=packed)
+                print(f"  inter-batch pipeline, batch 128 = 4 x 32, {'sign-only packed' if packed else 'whole-word'} ReLU: "
+                      f"serial {p['serial']['ms']:.2f} ms ({p['serial']['images_per_s']:.0f} img/s), "
+                      f"pipelined {p['pipelined']['ms']:.2f} ms ({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)
         print(json.dumps({"config": idx, "layers": rows}), file=sys.stderr)
 
 

@@ -29,6 +29,7 @@ class LayerState:
     relu: dict | None = None
     pool1: dict | None = None
     pool2: dict | None = None
+    packed: bool = False          # ReLU / pool material in the packed layout of mpc_relu_msb
 
 
 def with_batch(layers, batch: int):
@@ -53,8 +54,9 @@ def deal_weights(g, layers, device):
     return ws
 
 
-def deal_microbatch(lane: mpc.Lane, g, layers, weights) -> list:
-    """Triples and ReLU / pool material for one micro-batch (offline phase stand-in)."""
+def deal_microbatch(lane: mpc.Lane, g, layers, weights, packed_relu: bool = False) -> list:
+    """Triples and ReLU / pool material for one micro-batch (offline phase stand-in).
+    packed_relu: material for the sign-only carry chain (mpc_relu_msb / mpc_maxpool2x2_msb)."""
     dev = lane.device
     states = []
     for L, (W, wsh) in zip(layers, weights):
@@ -69,13 +71,13 @@ def deal_microbatch(lane: mpc.Lane, g, layers, weights) -> list:
             C = lane.ring_matmul(A, Bm)
             n_out = L.M * L.N
         lane.sync()
-        st = LayerState(w=wsh, a=dealer.share(g, A), b=dealer.share(g, Bm), c=dealer.share(g, C))
+        st = LayerState(w=wsh, a=dealer.share(g, A), b=dealer.share(g, Bm), c=dealer.share(g, C), packed=packed_relu)
         if L.relu:
-            st.relu = dealer.relu_material(g, n_out, dev)
+            st.relu = dealer.relu_material(g, n_out, dev, packed=packed_relu)
         if isinstance(L, synth.Conv) and L.pool:
             n_pool = L.B * (L.Ho // 2) * (L.Wo // 2) * L.Cout
-            st.pool1 = dealer.relu_material(g, 2 * n_pool, dev)
-            st.pool2 = dealer.relu_material(g, n_pool, dev)
+            st.pool1 = dealer.relu_material(g, 2 * n_pool, dev, packed=packed_relu)
+            st.pool2 = dealer.relu_material(g, n_pool, dev, packed=packed_relu)
         states.append(st)
     torch.cuda.synchronize(dev)
     return states
@@ -101,9 +103,9 @@ def run_layer(lane: mpc.Lane, L, st: LayerState, x, n_chunks=1, relu_chunks=0, f
         z = lane.beaver_matmul(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public, n_chunks=n_chunks, flags=flags)
     outs = [z]
     if st.relu is not None:
-        z = lane.relu(z, st.relu, n_chunks=relu_chunks); outs.append(z)
+        z = lane.relu(z, st.relu, n_chunks=relu_chunks, packed=st.packed); outs.append(z)
     if st.pool1 is not None:
-        z = lane.maxpool2x2(z, st.pool1, st.pool2, n_chunks=relu_chunks); outs.append(z)
+        z = lane.maxpool2x2(z, st.pool1, st.pool2, n_chunks=relu_chunks, packed=st.packed); outs.append(z)
     run_layer.last_intermediates = outs      # kept alive by the caller through `keep`
     return z
 

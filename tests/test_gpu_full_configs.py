@@ -66,6 +66,16 @@ def relu_sampled_check(mpc, dealer, lane, z, seed, n_sample=200_000):
     want = oracle.relu((take(z[0]), take(z[1])), sub)
     assert_equal_shares(mpc, (y[0].view(-1)[idx], y[1].view(-1)[idx]), want.y, "relu sample")
     assert_equal_shares(mpc, (sa[0].view(-1)[idx], sa[1].view(-1)[idx]), want.s_arith, "sign share sample")
+    # the sign-only packed chain on the same material, packed on the device: every word of
+    # every output equals the whole-word protocol's, which was just checked
+    packed = lane.pack_material(mat)
+    for k in ("and_a", "and_b", "and_c"):
+        del mat[k]
+    y2, sb2, sa2 = lane.relu(z, packed, want_sign=True, packed=True)
+    lane.sync()
+    for i in range(2):
+        assert torch.equal(y2[i], y[i]) and torch.equal(sb2[i], sb[i]) and torch.equal(sa2[i], sa[i]), \
+            f"mpc_relu_msb differs from mpc_relu, party {i}"
     return y
 
 
@@ -97,9 +107,14 @@ def test_config1_vgg_block_full(mods, lane):
     float_check(d, rec(want), conv=True)
     # the ReLU of this config fits on the host: full bit-exact comparison
     mat = synth.deal_relu_material(rng, L.B * L.Ho * L.Wo * L.Cout)
-    y = lane.relu(z, mpc.material_to_device(mat))
+    md = mpc.material_to_device(mat)
+    y = lane.relu(z, md)
     lane.sync()
-    assert_equal_shares(mpc, y, oracle.relu(want, mat).y, "relu")
+    want_y = oracle.relu(want, mat).y
+    assert_equal_shares(mpc, y, want_y, "relu")
+    y2 = lane.relu(z, lane.pack_material(md), packed=True)
+    lane.sync()
+    assert_equal_shares(mpc, y2, want_y, "relu, sign-only packed chain")
 
 
 def test_config2_resnet_bottleneck_full(mods, lane):
@@ -135,7 +150,8 @@ def test_config3_transformer_full(mods, lane):
         torch.cuda.empty_cache()
 
 
-def test_config4_vgg16_pipeline_full(mods):
+@pytest.mark.parametrize("packed_relu", [False, True], ids=["whole-word-relu", "sign-only-packed-relu"])
+def test_config4_vgg16_pipeline_full(mods, packed_relu):
     """Batch 128 = 4 micro-batches of 32 through the whole VGG16-CIFAR network:
     the inter-batch pipeline (one lane per micro-batch) gives exactly the shares
     of the serial run, and every layer's reconstructed output equals the plain
@@ -153,7 +169,7 @@ def test_config4_vgg16_pipeline_full(mods):
     weights = pipeline.deal_weights(g, layers, lanes[0].device)
     states, xs = [], []
     for m in range(n_mb):
-        states.append(pipeline.deal_microbatch(lanes[m], g, layers, weights))
+        states.append(pipeline.deal_microbatch(lanes[m], g, layers, weights, packed_relu=packed_relu))
         xs.append(dealer.share(g, dealer.normal_fixed(g, (32, 32, 32, 3), 1.0, lanes[0].device)))
     torch.cuda.synchronize()
     keep_a, keep_b = [], []

@@ -35,11 +35,18 @@ def dealt():
     return layers, mbs
 
 
-def to_state(mpc, pipeline, st):
+def to_state(mpc, pipeline, st, pack_lane=None):
+    """Upload one layer's host-dealt state; with `pack_lane` the ReLU / pool triples are
+    packed on the device for the sign-only chain."""
     dv = lambda p: (mpc.to_device(p[0]), mpc.to_device(p[1]))
-    mat = lambda m: None if m is None else mpc.material_to_device(m)
+    def mat(m):
+        if m is None:
+            return None
+        md = mpc.material_to_device(m)
+        return pack_lane.pack_material(md) if pack_lane is not None else md
     return pipeline.LayerState(w=dv(st["w"]), a=dv(st["a"]), b=dv(st["b"]), c=dv(st["c"]),
-                               relu=mat(st["relu"]), pool1=mat(st["pool1"]), pool2=mat(st["pool2"]))
+                               relu=mat(st["relu"]), pool1=mat(st["pool1"]), pool2=mat(st["pool2"]),
+                               packed=pack_lane is not None)
 
 
 def check(mpc, got_pair, want_pair, what):
@@ -48,13 +55,14 @@ def check(mpc, got_pair, want_pair, what):
         assert np.array_equal(g, want_pair[i]), f"{what}: party {i} differs in {(g != want_pair[i]).sum()} elements"
 
 
-def test_vgg16_every_layer_matches_oracle(mods, dealt):
+@pytest.mark.parametrize("packed_relu", [False, True], ids=["whole-word-relu", "sign-only-packed-relu"])
+def test_vgg16_every_layer_matches_oracle(mods, dealt, packed_relu):
     mpc, pipeline = mods
     layers, mbs = dealt
-    print("vgg16 per-layer parity", flush=True)
+    print(f"vgg16 per-layer parity, packed_relu={packed_relu}", flush=True)
     lane = mpc.Lane(0); lane.use_single_queue()
     mb = mbs[0]
-    states = [to_state(mpc, pipeline, st) for st in mb["states"]]
+    states = [to_state(mpc, pipeline, st, lane if packed_relu else None) for st in mb["states"]]
     x = (mpc.to_device(mb["x"][0]), mpc.to_device(mb["x"][1]))
     keep = []
     for li, (L, st) in enumerate(zip(layers, states)):
@@ -68,7 +76,8 @@ def test_vgg16_every_layer_matches_oracle(mods, dealt):
     lane.close()
 
 
-@pytest.mark.parametrize("mode", ["serial-3stream", "pipelined", "pipelined-preopened", "pipelined-two-phase-chunked"])
+@pytest.mark.parametrize("mode", ["serial-3stream", "pipelined", "pipelined-preopened", "pipelined-two-phase-chunked",
+                                  "pipelined-packed-relu"])
 def test_pipeline_invariance(mods, dealt, mode):
     mpc, pipeline = mods
     layers, mbs = dealt
@@ -77,7 +86,8 @@ def test_pipeline_invariance(mods, dealt, mode):
     if mode != "serial-3stream":
         for ln in lanes:
             ln.use_single_queue()
-    states = [[to_state(mpc, pipeline, st) for st in mb["states"]] for mb in mbs]
+    pk = lanes[0] if mode == "pipelined-packed-relu" else None
+    states = [[to_state(mpc, pipeline, st, pk) for st in mb["states"]] for mb in mbs]
     xs = [(mpc.to_device(mb["x"][0]), mpc.to_device(mb["x"][1])) for mb in mbs]
     kw = {}
     if mode in ("pipelined-preopened", "pipelined-two-phase-chunked"):
