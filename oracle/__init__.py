@@ -153,6 +153,56 @@ def truncate(z, bits=16):
     return z0, z1
 
 
+# ---------------------------------------------------------------- backward pass
+def ring_conv2d_grad_x(g, w, x_shape, pad, stride):
+    """Gradient of ring_conv2d w.r.t. its input: the transpose of the forward sum."""
+    g, pg = _w(g); w, pw = _w(w)
+    B, H, W, Cin = x_shape; KH, KW, Cin2, Cout = w.shape
+    assert Cin == Cin2 and g.shape == (B,) + conv_out_hw(H, W, KH, KW, pad, stride) + (Cout,)
+    gx = np.empty((B, H, W, Cin), dtype=U64)
+    lib().orc_ring_conv2d_grad_x(pg, pw, gx.ctypes.data_as(_P64), B, H, W, Cin, Cout, KH, KW, pad, stride)
+    return gx
+
+
+def ring_conv2d_grad_w(x, g, KH, KW, pad, stride):
+    """Gradient of ring_conv2d w.r.t. its filter."""
+    x, px = _w(x); g, pg = _w(g)
+    B, H, W, Cin = x.shape; Cout = g.shape[-1]
+    assert g.shape == (B,) + conv_out_hw(H, W, KH, KW, pad, stride) + (Cout,)
+    gw = np.empty((KH, KW, Cin, Cout), dtype=U64)
+    lib().orc_ring_conv2d_grad_w(px, pg, gw.ctypes.data_as(_P64), B, H, W, Cin, Cout, KH, KW, pad, stride)
+    return gw
+
+
+def beaver_bilinear(product, p, q, a, b, c):
+    """Alg. 1 / Eq. 3 with any bilinear `product(left, right)` in place of Conv:
+    open e = p - a and f = q - b, then [z_0] = [c_0] + product(e, [b_0]) + product([a_0], f)
+    + product(e, f) and [z_1] = [c_1] + product(e, [b_1]) + product([a_1], f).
+    Used for the two gradient products of a layer (Sec. 4.1, backward pass)."""
+    e = open_shares(np.asarray(p[0], U64) - np.asarray(a[0], U64), np.asarray(p[1], U64) - np.asarray(a[1], U64))
+    f = open_shares(np.asarray(q[0], U64) - np.asarray(b[0], U64), np.asarray(q[1], U64) - np.asarray(b[1], U64))
+    z0 = np.asarray(c[0], U64) + product(e, b[0]) + product(a[0], f) + product(e, f)
+    z1 = np.asarray(c[1], U64) + product(e, b[1]) + product(a[1], f)
+    return z0, z1
+
+
+def beaver_mul(x, y, a, b, c):
+    """Alg. 1 element by element (no rescale)."""
+    arrs = [_w(v[i]) for v in (x, y, a, b, c) for i in range(2)]
+    z0 = np.empty_like(arrs[0][0]); z1 = np.empty_like(z0)
+    lib().orc_beaver_mul(*[p for _, p in arrs], z0.ctypes.data_as(_P64), z1.ctypes.data_as(_P64), ctypes.c_size_t(z0.size))
+    return z0, z1
+
+
+def relu_backward(g, s_arith, a, b, c):
+    """Backward of ReLU (Sec. 4.2 / 5.3): output gradient times the input mask
+    1 - s, the mask shares being [1 - s]_0 = 1 - [s]_0, [1 - s]_1 = -[s]_1 kept
+    from the forward conversion.  One element-wise Alg. 1, no rescale (the mask
+    is an integer)."""
+    m = (U64(1) - np.asarray(s_arith[0], U64), U64(0) - np.asarray(s_arith[1], U64))
+    return beaver_mul(g, m, a, b, c)
+
+
 # ------------------------------------------------------------------ binary side
 def beaver_and(X, Y, a, b, c):
     """Beaver AND on one word pair: all arguments are 2-sequences of ints."""

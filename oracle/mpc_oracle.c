@@ -77,6 +77,75 @@ void orc_ring_conv2d(const u64* x, const u64* w, u64* z,
             }
 }
 
+/* Gradients of that convolution, for the backward pass (Sec. 4.1 and 5.3:
+ * the gradient w.r.t. the input is a convolution of the output gradients with
+ * the weights, the gradient w.r.t. the weights one of the output gradients
+ * with the stored activation).  Both are written as the transpose of the
+ * forward sum: the same seven index ranges, the product accumulated into the
+ * other operand's position.
+ *   gx[b][hi][wi][ci]  = sum_{ho,wo,kh,kw,co : hi = ho*s+kh-p, wi = wo*s+kw-p} g[b][ho][wo][co] * w[kh][kw][ci][co]
+ *   gw[kh][kw][ci][co] = sum_{b,ho,wo}  x[b][ho*s+kh-p][wo*s+kw-p][ci] * g[b][ho][wo][co]          */
+void orc_ring_conv2d_grad_x(const u64* g, const u64* w, u64* gx,
+                            int B, int H, int W, int Cin, int Cout,
+                            int KH, int KW, int pad, int stride)
+{
+    const int Ho = (H + 2 * pad - KH) / stride + 1;
+    const int Wo = (W + 2 * pad - KW) / stride + 1;
+    memset(gx, 0, (size_t)B * H * W * Cin * sizeof(u64));
+#pragma omp parallel for schedule(static)
+    for (int b = 0; b < B; ++b)
+        for (int ho = 0; ho < Ho; ++ho)
+            for (int wo = 0; wo < Wo; ++wo) {
+                const u64* go = g + (((size_t)b * Ho + ho) * Wo + wo) * Cout;
+                for (int kh = 0; kh < KH; ++kh) {
+                    const int hi = ho * stride + kh - pad;
+                    if (hi < 0 || hi >= H) continue;
+                    for (int kw = 0; kw < KW; ++kw) {
+                        const int wi = wo * stride + kw - pad;
+                        if (wi < 0 || wi >= W) continue;
+                        u64* xo = gx + (((size_t)b * H + hi) * W + wi) * Cin;
+                        const u64* wk = w + ((size_t)kh * KW + kw) * Cin * Cout;
+                        for (int ci = 0; ci < Cin; ++ci) {
+                            const u64* wr = wk + (size_t)ci * Cout;
+                            u64 acc = 0;
+                            for (int co = 0; co < Cout; ++co) acc += go[co] * wr[co];
+                            xo[ci] += acc;
+                        }
+                    }
+                }
+            }
+}
+
+void orc_ring_conv2d_grad_w(const u64* x, const u64* g, u64* gw,
+                            int B, int H, int W, int Cin, int Cout,
+                            int KH, int KW, int pad, int stride)
+{
+    const int Ho = (H + 2 * pad - KH) / stride + 1;
+    const int Wo = (W + 2 * pad - KW) / stride + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int kh = 0; kh < KH; ++kh)
+        for (int kw = 0; kw < KW; ++kw) {
+            u64* wk = gw + ((size_t)kh * KW + kw) * Cin * Cout;
+            for (size_t i = 0; i < (size_t)Cin * Cout; ++i) wk[i] = 0;
+            for (int b = 0; b < B; ++b)
+                for (int ho = 0; ho < Ho; ++ho) {
+                    const int hi = ho * stride + kh - pad;
+                    if (hi < 0 || hi >= H) continue;
+                    for (int wo = 0; wo < Wo; ++wo) {
+                        const int wi = wo * stride + kw - pad;
+                        if (wi < 0 || wi >= W) continue;
+                        const u64* xi = x + (((size_t)b * H + hi) * W + wi) * Cin;
+                        const u64* go = g + (((size_t)b * Ho + ho) * Wo + wo) * Cout;
+                        for (int ci = 0; ci < Cin; ++ci) {
+                            const u64 xv = xi[ci];
+                            u64* wr = wk + (size_t)ci * Cout;
+                            for (int co = 0; co < Cout; ++co) wr[co] += xv * go[co];
+                        }
+                    }
+                }
+        }
+}
+
 /* Explicit im2col of an NHWC tensor: row (b,ho,wo), column (kh,kw,ci).
  * Only used by tests to pin conv == im2col-then-matmul. */
 void orc_im2col(const u64* x, u64* col, int B, int H, int W, int Cin,
@@ -115,6 +184,21 @@ void orc_mask(const u64* x, const u64* a, u64* e, size_t n)
 void orc_open(const u64* s0, const u64* s1, u64* out, size_t n)
 {
     for (size_t i = 0; i < n; ++i) out[i] = s0[i] + s1[i];
+}
+
+/* Alg. 1 element by element (the products of the non-linear layers' backward
+ * pass, Sec. 4.2 and 5.3: output gradient times the stored input mask):
+ *   [z_0] = [c_0] + e*[b_0] + [a_0]*f + e*f,   [z_1] = [c_1] + e*[b_1] + [a_1]*f. */
+void orc_beaver_mul(const u64* x0, const u64* x1, const u64* y0, const u64* y1,
+                    const u64* a0, const u64* a1, const u64* b0, const u64* b1,
+                    const u64* c0, const u64* c1, u64* z0, u64* z1, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) {
+        const u64 e = (x0[i] - a0[i]) + (x1[i] - a1[i]);
+        const u64 f = (y0[i] - b0[i]) + (y1[i] - b1[i]);
+        z0[i] = c0[i] + e * b0[i] + a0[i] * f + e * f;
+        z1[i] = c1[i] + e * b1[i] + a1[i] * f;
+    }
 }
 
 static u64* alloc_words(size_t n) { return (u64*)malloc(n * sizeof(u64)); }

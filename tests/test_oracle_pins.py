@@ -150,6 +150,115 @@ def test_beaver_conv_reconstructs_conv(case):
     assert np.array_equal(rec(z), conv_via_bigint(X, Wt))
 
 
+# ------------------------------------------------- backward pass (Sec. 4.1, 4.2, 5.3)
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_gradients_match_torch_autograd(case):
+    """Small integers keep float64 exact: autograd's gradients of conv2d are an
+    independent definition of both transposed sums."""
+    B, H, W, Cin, Cout, KH, KW, pad, stride = case
+    rng = np.random.default_rng(70)
+    xi = rng.integers(-300, 300, size=(B, H, W, Cin)); wi = rng.integers(-300, 300, size=(KH, KW, Cin, Cout))
+    xt = torch.from_numpy(xi).double().permute(0, 3, 1, 2).requires_grad_()
+    wt = torch.from_numpy(wi).double().permute(3, 2, 0, 1).requires_grad_()
+    out = torch.nn.functional.conv2d(xt, wt, padding=pad, stride=stride)
+    gi = rng.integers(-300, 300, size=tuple(out.permute(0, 2, 3, 1).shape))
+    out.backward(torch.from_numpy(gi).double().permute(0, 3, 1, 2))
+    u = lambda v: v.astype(np.int64).view(U64)
+    gx = oracle.ring_conv2d_grad_x(u(gi), u(wi), xi.shape, pad, stride)
+    gw = oracle.ring_conv2d_grad_w(u(xi), u(gi), KH, KW, pad, stride)
+    assert np.array_equal(oracle.to_signed(gx), xt.grad.permute(0, 2, 3, 1).numpy().astype(np.int64))
+    assert np.array_equal(oracle.to_signed(gw), wt.grad.permute(2, 3, 1, 0).numpy().astype(np.int64))
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_gradients_are_the_adjoints_in_the_ring(case):
+    """<Conv(x, w), g> = <x, grad_x(g, w)> = <w, grad_w(x, g)> holds exactly mod 2^64 for
+    arbitrary 64-bit words; the forward conv is pinned above."""
+    B, H, W, Cin, Cout, KH, KW, pad, stride = case
+    rng = np.random.default_rng(71)
+    x = synth.rand_words(rng, (B, H, W, Cin)); w = synth.rand_words(rng, (KH, KW, Cin, Cout))
+    z = oracle.ring_conv2d(x, w, pad, stride)
+    g = synth.rand_words(rng, z.shape)
+    dot = lambda p, q: int(sum(int(a) * int(b) for a, b in zip(p.ravel(), q.ravel())) % (1 << 64))
+    lhs = dot(z, g)
+    assert dot(x, oracle.ring_conv2d_grad_x(g, w, x.shape, pad, stride)) == lhs
+    assert dot(w, oracle.ring_conv2d_grad_w(x, g, KH, KW, pad, stride)) == lhs
+
+
+def test_conv_gradients_brute_force_tiny():
+    B, H, W, Cin, Cout, KH, KW, pad, stride = 1, 4, 3, 2, 2, 3, 3, 1, 1
+    rng = np.random.default_rng(72)
+    x = synth.rand_words(rng, (B, H, W, Cin)); w = synth.rand_words(rng, (KH, KW, Cin, Cout))
+    Ho, Wo = oracle.conv_out_hw(H, W, KH, KW, pad, stride)
+    g = synth.rand_words(rng, (B, Ho, Wo, Cout))
+    gx = np.zeros(x.shape, dtype=object); gw = np.zeros(w.shape, dtype=object)
+    for b, ho, wo, kh, kw, ci, co in itertools.product(range(B), range(Ho), range(Wo), range(KH), range(KW),
+                                                       range(Cin), range(Cout)):
+        hi, wi = ho * stride + kh - pad, wo * stride + kw - pad
+        if 0 <= hi < H and 0 <= wi < W:
+            gx[b, hi, wi, ci] += int(g[b, ho, wo, co]) * int(w[kh, kw, ci, co])
+            gw[kh, kw, ci, co] += int(x[b, hi, wi, ci]) * int(g[b, ho, wo, co])
+    mod = np.vectorize(lambda v: v % (1 << 64), otypes=[object])
+    assert np.array_equal(oracle.ring_conv2d_grad_x(g, w, x.shape, pad, stride), mod(gx).astype(U64))
+    assert np.array_equal(oracle.ring_conv2d_grad_w(x, g, KH, KW, pad, stride), mod(gw).astype(U64))
+
+
+@pytest.mark.parametrize("case", CONV_CASES[:3])
+def test_beaver_bilinear_reconstructs_both_conv_gradients(case):
+    B, H, W, Cin, Cout, KH, KW, pad, stride = case
+    rng = np.random.default_rng(73)
+    X = synth.rand_words(rng, (B, H, W, Cin)); Wt = synth.rand_words(rng, (KH, KW, Cin, Cout))
+    Ho, Wo = oracle.conv_out_hw(H, W, KH, KW, pad, stride)
+    G = synth.rand_words(rng, (B, Ho, Wo, Cout))
+    xs, ws, gs = (synth.share_additive(rng, v) for v in (X, Wt, G))
+    fx = lambda g, w: oracle.ring_conv2d_grad_x(g, w, X.shape, pad, stride)
+    fw = lambda x, g: oracle.ring_conv2d_grad_w(x, g, KH, KW, pad, stride)
+    a, b, c = synth.deal_product_triple(rng, G.shape, Wt.shape, fx)
+    assert np.array_equal(rec(oracle.beaver_bilinear(fx, gs, ws, a, b, c)), fx(G, Wt))
+    a, b, c = synth.deal_product_triple(rng, X.shape, G.shape, fw)
+    assert np.array_equal(rec(oracle.beaver_bilinear(fw, xs, gs, a, b, c)), fw(X, G))
+
+
+def test_beaver_bilinear_with_the_matrix_product_is_alg1():
+    """With product = ring_matmul the generic form must give the very shares of beaver_matmul."""
+    rng = np.random.default_rng(74)
+    M, K, N = 5, 7, 3
+    xs = synth.share_additive(rng, synth.rand_words(rng, (M, K))); ys = synth.share_additive(rng, synth.rand_words(rng, (K, N)))
+    a, b, c = synth.deal_product_triple(rng, (M, K), (K, N), oracle.ring_matmul)
+    got = oracle.beaver_bilinear(oracle.ring_matmul, xs, ys, a, b, c)
+    want = oracle.beaver_matmul(xs, ys, a, b, c)
+    assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
+
+
+def test_beaver_mul_elementwise():
+    rng = np.random.default_rng(75)
+    n = 1000
+    X = synth.rand_words(rng, n); Y = synth.rand_words(rng, n)
+    xs, ys = synth.share_additive(rng, X), synth.share_additive(rng, Y)
+    a, b, c = synth.deal_product_triple(rng, (n,), (n,), lambda p, q: p * q)
+    z = oracle.beaver_mul(xs, ys, a, b, c)
+    assert np.array_equal(rec(z), X * Y)
+    # the literal five terms of Alg. 1, in big integers
+    e = [int(v) for v in (xs[0] - a[0]) + (xs[1] - a[1])]; f = [int(v) for v in (ys[0] - b[0]) + (ys[1] - b[1])]
+    for i in range(0, n, 97):
+        z0 = (int(c[0][i]) + e[i] * int(b[0][i]) + int(a[0][i]) * f[i] + e[i] * f[i]) % (1 << 64)
+        z1 = (int(c[1][i]) + e[i] * int(b[1][i]) + int(a[1][i]) * f[i]) % (1 << 64)
+        assert (int(z[0][i]), int(z[1][i])) == (z0, z1)
+
+
+def test_relu_backward_passes_gradient_where_input_positive():
+    rng = np.random.default_rng(76)
+    n = 2000
+    X = synth.normal_fixed(rng, (n,), 1.0); X[:3] = np.array([0, 1, -1], dtype=np.int64).view(U64)
+    G = synth.normal_fixed(rng, (n,), 0.5)
+    xs, gs = synth.share_additive(rng, X), synth.share_additive(rng, G)
+    fwd = oracle.relu(xs, synth.deal_relu_material(rng, n))
+    a, b, c = synth.deal_product_triple(rng, (n,), (n,), lambda p, q: p * q)
+    gx = oracle.relu_backward(gs, fwd.s_arith, a, b, c)
+    want = np.where(oracle.to_signed(X) >= 0, G, U64(0))
+    assert np.array_equal(rec(gx), want)
+
+
 # -------------------------------------------------------------------- truncation
 def test_truncation_within_one_lsb_and_wrap_flag():
     rng = np.random.default_rng(9)
