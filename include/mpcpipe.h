@@ -48,16 +48,21 @@ enum {
     MPC_ERANGE = -4    /* contraction too long for exact int32 digit sums      */
 };
 
-/* flags for mpc_beaver_matmul / mpc_conv2d */
+/* flags for mpc_beaver_matmul / mpc_conv2d and the gradient products */
 enum {
     MPC_TRUNCATE = 1,     /* rescale the product by 2^-frac_bits (local truncation)       */
-    MPC_TWO_PHASE = 2     /* Alg. 3 ordering: [a_i]*f first, while e is still "in flight" */
+    MPC_TWO_PHASE = 2,    /* Alg. 3 ordering: [a_i]*f first, while e is still "in flight" */
+    MPC_TRANS_X = 4,      /* mpc_beaver_matmul: x, a are stored [K][M] (left operand = their transpose)  */
+    MPC_TRANS_Y = 8       /* mpc_beaver_matmul: y, b, f_public are stored [N][K]                          */
 };
 
 #define MPC_N_AND_TRIPLES 12
-/* Longest contraction (K, or KH*KW*Cin padded to 16 per filter tap) accepted:
- * with 2K terms per digit-sum group the int32 sums stay exact below this. */
+/* Longest contraction (K, or KH*KW*Cin padded to 16 per filter tap) one
+ * workgroup sums exactly in int32 digit sums.  Longer contractions, up to
+ * MPC_MAX_K_TOTAL, are cut into slices whose 64-bit partial products are added
+ * by a finishing kernel (workspace grows accordingly); beyond that MPC_ERANGE. */
 #define MPC_MAX_K 16368
+#define MPC_MAX_K_TOTAL 4194304
 
 /* ------------------------------------------------------------------ context */
 
@@ -133,8 +138,14 @@ int mpc_sub(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_share out, size_t n);
  * n_chunks >= 1 splits the opening of e by rows into that many pieces whose
  *   mask kernels and wire copies are issued back to back (Alg. 4's tiling
  *   applied to the linear layer's exchange); results do not depend on it.
- * flags: MPC_TRUNCATE, MPC_TWO_PHASE.
- * Errors: MPC_EINVAL (null / non-positive), MPC_ERANGE (K > MPC_MAX_K),
+ * flags: MPC_TRUNCATE, MPC_TWO_PHASE; MPC_TRANS_X / MPC_TRANS_Y read the left
+ *   / right operand from transposed storage (x, a as [batch][K][M]; y, b,
+ *   f_public as [batch][N][K]).  These give the two gradient products of a
+ *   dense layer without moving data (Sec. 5.3: x^T * grad and grad * w^T):
+ *   grad_w = matmul(x, grad) with M' = K, K' = M and MPC_TRANS_X;
+ *   grad_x = matmul(grad, w) with K' = N, N' = K and MPC_TRANS_Y, where
+ *   f_public may be the forward pass's opened w - b.
+ * Errors: MPC_EINVAL (null / non-positive), MPC_ERANGE (K > MPC_MAX_K_TOTAL),
  *   MPC_ENOMEM (workspace < mpc_matmul_workspace_bytes). */
 int mpc_beaver_matmul(mpc_ctx* ctx, mpc_cshare x, mpc_cshare y,
                       mpc_cshare a, mpc_cshare b, mpc_cshare c, mpc_share z,
@@ -151,6 +162,56 @@ int mpc_conv2d(mpc_ctx* ctx, mpc_cshare x, mpc_cshare w,
                int B, int H, int W, int Cin, int Cout, int KH, int KW,
                int pad, int stride,
                const uint64_t* f_public, int n_chunks, int flags);
+
+/* Backward pass of mpc_conv2d (Sec. 4.1 "Application to the backward pass",
+ * Sec. 5.3): both gradients are Alg. 1 / Eq. 3 with another bilinear product
+ * in place of Conv, on operands that are available before the backward pass
+ * starts, so their masks can be opened ahead of time.
+ *
+ * mpc_conv2d_grad_x: gradient w.r.t. the input,
+ *     gx[b][hi][wi][ci] = sum g[b][ho][wo][co] * w[kh][kw][ci][co]
+ *   over all (ho, wo, kh, kw, co) with hi = ho + kh - pad, wi = wo + kw - pad.
+ *   g, a: [B][Ho][Wo][Cout] (output gradient and its mask); w, b: the forward
+ *   filter layout [KH][KW][Cin][Cout]; c, gx: [B][H][W][Cin].  f_public: NULL
+ *   or w - b as opened for the forward pass (same layout as w).  stride must
+ *   be 1 and KH == KW (else MPC_EINVAL).  Runs as a convolution of g with the
+ *   filter read in reverse tap order, padding KH - 1 - pad.
+ * mpc_conv2d_grad_w: gradient w.r.t. the filter,
+ *     gw[kh][kw][ci][co] = sum_{b,ho,wo} x[b][ho*s+kh-pad][wo*s+kw-pad][ci] * g[b][ho][wo][co].
+ *   x, a: [B][H][W][Cin] (the stored activation and the mask it was opened
+ *   with); g, b: [B][Ho][Wo][Cout]; c, gw: [KH][KW][Cin][Cout].  e_public:
+ *   NULL, or x - a as opened in the forward pass; x may then be {NULL, NULL}.
+ *   The contraction runs over the B*Ho*Wo output pixels.
+ * n_chunks, MPC_TRUNCATE as for mpc_conv2d; errors likewise. */
+size_t mpc_conv2d_grad_x_workspace_bytes(int B, int H, int W, int Cin, int Cout,
+                                         int KH, int KW, int pad, int stride);
+size_t mpc_conv2d_grad_w_workspace_bytes(int B, int H, int W, int Cin, int Cout,
+                                         int KH, int KW, int pad, int stride);
+int mpc_conv2d_grad_x(mpc_ctx* ctx, mpc_cshare g, mpc_cshare w,
+                      mpc_cshare a, mpc_cshare b, mpc_cshare c, mpc_share gx,
+                      int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                      int pad, int stride,
+                      const uint64_t* f_public, int n_chunks, int flags);
+int mpc_conv2d_grad_w(mpc_ctx* ctx, mpc_cshare x, mpc_cshare g,
+                      mpc_cshare a, mpc_cshare b, mpc_cshare c, mpc_share gw,
+                      int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                      int pad, int stride,
+                      const uint64_t* e_public, int n_chunks, int flags);
+
+/* Element-wise Alg. 1 on n words: z = x * y with the triple (a, b, c),
+ * c = a * b element by element; flags: 0 or MPC_TRUNCATE.  Workspace:
+ * mpc_mul_workspace_bytes(n).
+ * mpc_relu_backward: the backward pass of ReLU (Sec. 4.2, Sec. 5.3): output
+ * gradient times the input mask 1 - s, where s_arith are the additive sign
+ * shares mpc_relu / mpc_relu_msb returned in the forward pass; the mask shares
+ * are [1 - s]_0 = 1 - [s]_0, [1 - s]_1 = -[s]_1, b masks them.  No rescale. */
+size_t mpc_mul_workspace_bytes(size_t n);
+int mpc_mul(mpc_ctx* ctx, mpc_cshare x, mpc_cshare y,
+            mpc_cshare a, mpc_cshare b, mpc_cshare c, mpc_share z,
+            size_t n, int flags);
+int mpc_relu_backward(mpc_ctx* ctx, mpc_cshare g, mpc_cshare s_arith,
+                      mpc_cshare a, mpc_cshare b, mpc_cshare c, mpc_share gx,
+                      size_t n);
 
 /* Local fixed-point rescale of a two-party sharing, in place (the paper only
  * requires fixed-point operands, Sec. 1.1; this is the usual local protocol):

@@ -151,6 +151,28 @@ constexpr int kMaxRecodeSets = 6;
 struct RecodeBatch { RecodeArgs a[kMaxRecodeSets]; int batch; };
 int launch_recode_multi(mpc_ctx* c, hipStream_t st, const RecodeArgs* sets, int count);
 
+// transposed im2col planes of an NHWC tensor (left operand of the filter-gradient product)
+struct Im2colTArgs {
+    const u64* src; const u64* src2;      // [B][H][W][Cin]; optional addend with the same indexing
+    u8* dst;                              // planes: rows = KH*KW*Cin, k = output pixel
+    int B, H, W, Cin, KH, KW, pad, stride, Ho, Wo;
+    int KB_total;                         // padded k blocks (>= ceil(B*Ho*Wo / 16))
+    long long digit_stride;
+};
+struct Im2colTBatch { Im2colTArgs a[3]; };
+int launch_recode_im2col_t(mpc_ctx* c, hipStream_t st, const Im2colTArgs* sets, int count);
+
+// element-wise Alg. 1 (mask kernel, then finish kernel after the exchange)
+struct MulArgs {
+    const u64 *x[2], *y[2], *a[2], *b[2], *c[2];
+    u64 *se[2], *sf[2];                   // own masked words
+    const u64 *re[2], *rf[2];             // received masked words
+    u64* z[2];
+    size_t n; int trunc_bits; int mask_from_sign;
+};
+int launch_mul_mask(mpc_ctx* c, hipStream_t st, const MulArgs& q);
+int launch_mul_finish(mpc_ctx* c, hipStream_t st, const MulArgs& q);
+
 // several element-wise jobs in one launch (single-queue lanes)
 constexpr int kMaxSegs = 4;
 struct SubSeg { const u64* x; const u64* a; u64* out; size_t n; int vec; };

@@ -168,6 +168,56 @@ int mpc_sub(mpc_ctx* c, mpc_cshare x, mpc_cshare a, mpc_share out, size_t n)
     return MPC_OK;
 }
 
+size_t mpc_mul_workspace_bytes(size_t n) { return n ? 8 * align_up(n * sizeof(u64)) : 0; }
+
+// Element-wise Alg. 1.  Both parties' mask and finish kernels share a launch on
+// party 0's stream; the exchange of the masked words runs on the wire stream.
+static int mul_entry(mpc_ctx* c, mpc_cshare x, mpc_cshare y, mpc_cshare a, mpc_cshare b, mpc_cshare cc,
+                     mpc_share z, size_t n, int flags, int mask_from_sign)
+{
+    if (!c || n == 0 || (flags & ~MPC_TRUNCATE)) return MPC_EINVAL;
+    for (int i = 0; i < 2; ++i)
+        if (!x.p[i] || !y.p[i] || !a.p[i] || !b.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
+    WsAlloc ws(c->ws, c->ws_bytes);
+    MulArgs q{};
+    u64 *re[2], *rf[2];
+    for (int i = 0; i < 2; ++i) {
+        q.se[i] = ws.take<u64>(n); q.sf[i] = ws.take<u64>(n);
+        re[i] = ws.take<u64>(n); rf[i] = ws.take<u64>(n);
+    }
+    if (!ws.ok) return MPC_ENOMEM;
+    for (int i = 0; i < 2; ++i) {
+        q.x[i] = x.p[i]; q.y[i] = y.p[i]; q.a[i] = a.p[i]; q.b[i] = b.p[i]; q.c[i] = cc.p[i]; q.z[i] = z.p[i];
+        q.re[i] = re[i]; q.rf[i] = rf[i];
+    }
+    q.n = n; q.trunc_bits = (flags & MPC_TRUNCATE) ? c->frac_bits : 0; q.mask_from_sign = mask_from_sign;
+    MPC_TRY(lane_join(c));
+    MPC_TRY(launch_mul_mask(c, c->s[0], q));
+    MPC_TRY(chain(c, c->s[0], c->s[2]));
+    CopySeg cp[4];
+    for (int i = 0; i < 2; ++i) {
+        cp[2 * i] = CopySeg{ (const u8*)q.se[i], (u8*)re[1 - i], n * sizeof(u64), 0 };
+        cp[2 * i + 1] = CopySeg{ (const u8*)q.sf[i], (u8*)rf[1 - i], n * sizeof(u64), 0 };
+    }
+    MPC_TRY(launch_copy_multi(c, c->s[2], cp, 4));
+    MPC_TRY(chain(c, c->s[2], c->s[0]));
+    MPC_TRY(launch_mul_finish(c, c->s[0], q));
+    MPC_TRY(chain(c, c->s[0], c->s[1]));
+    return MPC_OK;
+}
+
+int mpc_mul(mpc_ctx* c, mpc_cshare x, mpc_cshare y, mpc_cshare a, mpc_cshare b, mpc_cshare cc, mpc_share z,
+            size_t n, int flags)
+{
+    return mul_entry(c, x, y, a, b, cc, z, n, flags, 0);
+}
+
+int mpc_relu_backward(mpc_ctx* c, mpc_cshare g, mpc_cshare s_arith, mpc_cshare a, mpc_cshare b, mpc_cshare cc,
+                      mpc_share gx, size_t n)
+{
+    return mul_entry(c, g, s_arith, a, b, cc, gx, n, 0, 1);
+}
+
 int mpc_truncate(mpc_ctx* c, mpc_share z, size_t n, int bits)
 {
     if (!c || !z.p[0] || !z.p[1] || n == 0 || bits < 0 || bits > 63) return MPC_EINVAL;

@@ -110,7 +110,8 @@ __device__ __forceinline__ void recode_body(const RecodeArgs& a, int tap /* == n
             const int k = kbl * 16 + t;
             u64 v = 0;
             if (!padtap && k < a.K && row < a.rows) {
-                const size_t idx = (size_t)row * a.row_stride + (size_t)k * a.k_stride + (size_t)tap * a.tap_stride;
+                // tap_stride may be negative (filters read in reverse tap order)
+                const long long idx = (long long)row * a.row_stride + (long long)k * a.k_stride + (long long)tap * a.tap_stride;
                 v = src[idx];
                 if (src2) v += src2[idx];
                 if (src3) v += src3[idx];
@@ -202,6 +203,87 @@ __global__ __launch_bounds__(kThreads) void k_recode_rows(RecodeBatch rb)
             const uint4 val = *reinterpret_cast<const uint4*>(&tile[d][kbl][row][0]);
             *reinterpret_cast<uint4*>(dst + (size_t)d * a.digit_stride + ((size_t)(kb0 + kbl) * a.plane_rows + row0 + row) * 16) = val;
         }
+    }
+}
+
+// Digit planes of the transposed im2col matrix of an NHWC tensor: plane row
+// (tap, ci), contraction index = output pixel (b, ho, wo).  One thread fills
+// one 16-byte unit per digit: 16 consecutive output pixels of one (tap, ci).
+// Lanes run along the rows, i.e. along ci, so loads and stores are contiguous.
+__global__ __launch_bounds__(kThreads) void k_recode_im2col_t(Im2colTBatch bt)
+{
+    const Im2colTArgs& a = bt.a[blockIdx.z];
+    const int rows = a.KH * a.KW * a.Cin;
+    const long long npix = (long long)a.B * a.Ho * a.Wo;
+    const size_t items = (size_t)a.KB_total * rows;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t it = (size_t)blockIdx.x * blockDim.x + threadIdx.x; it < items; it += stride) {
+        const int kb = (int)(it / rows);
+        const int row = (int)(it - (size_t)kb * rows);
+        const int tap = row / a.Cin, ci = row - tap * a.Cin;
+        const int dy = tap / a.KW, dx = tap - dy * a.KW;
+        long long m = (long long)kb * 16;
+        int wo = (int)(m % a.Wo); long long t2 = m / a.Wo;
+        int ho = (int)(t2 % a.Ho); int b = (int)(t2 / a.Ho);
+        u64 dg[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            u64 v = 0;
+            if (m + t < npix) {
+                const int hi = ho * a.stride + dy - a.pad, wi = wo * a.stride + dx - a.pad;
+                if (hi >= 0 && hi < a.H && wi >= 0 && wi < a.W) {
+                    const size_t idx = (((size_t)b * a.H + hi) * a.W + wi) * a.Cin + ci;
+                    v = a.src[idx];
+                    if (a.src2) v += a.src2[idx];
+                }
+            }
+            dg[t] = balanced_digits(v);
+            if (++wo == a.Wo) { wo = 0; if (++ho == a.Ho) { ho = 0; ++b; } }
+        }
+        u8* out = a.dst + ((size_t)kb * rows + row) * 16;
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            uint32_t w[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint32_t v = 0;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    v |= (uint32_t)((dg[q * 4 + t] >> (8 * d)) & 0xff) << (8 * t);
+                w[q] = v;
+            }
+            *reinterpret_cast<uint4*>(out + (size_t)d * a.digit_stride) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+}
+
+// Element-wise Alg. 1 after the exchange (blockIdx.y = party): e, f from the
+// own and the received masked words, z_i = c_i + e*b_i + a_i*f (+ e*f), then the
+// optional local truncation.  With `mask_from_sign` the second operand is the
+// ReLU input mask 1 - s formed from the additive sign shares in y.
+__global__ __launch_bounds__(kThreads) void k_mul_finish(MulArgs q)
+{
+    const int i = blockIdx.y;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < q.n; k += stride) {
+        const u64 e = q.se[i][k] + q.re[i][k], f = q.sf[i][k] + q.rf[i][k];
+        u64 z = q.c[i][k] + e * q.b[i][k] + q.a[i][k] * f;
+        if (i == 0) z += e * f;
+        if (q.trunc_bits) z = i == 0 ? (z >> q.trunc_bits) : (u64)0 - (((u64)0 - z) >> q.trunc_bits);
+        q.z[i][k] = z;
+    }
+}
+
+// masks of the element-wise product (blockIdx.y = party): se = x - a, sf = y - b
+__global__ __launch_bounds__(kThreads) void k_mul_mask(MulArgs q)
+{
+    const int i = blockIdx.y;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < q.n; k += stride) {
+        u64 y = q.y[i][k];
+        if (q.mask_from_sign) y = (i == 0 ? (u64)1 : (u64)0) - y;
+        q.se[i][k] = q.x[i][k] - q.a[i][k];
+        q.sf[i][k] = y - q.b[i][k];
     }
 }
 
@@ -369,6 +451,31 @@ int launch_copy_multi(mpc_ctx* c, hipStream_t st, const CopySeg* segs, int count
         if (segs[i].bytes > bmax) bmax = segs[i].bytes;
     }
     hipLaunchKernelGGL(k_copy_multi, dim3(grid_for(bmax / 16 + 1), count), dim3(kThreads), 0, st, cb);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+int launch_recode_im2col_t(mpc_ctx* c, hipStream_t st, const Im2colTArgs* sets, int count)
+{
+    if (count < 1 || count > 3) return MPC_EINVAL;
+    Im2colTBatch bt{};
+    for (int i = 0; i < count; ++i) bt.a[i] = sets[i];
+    const size_t items = (size_t)sets[0].KB_total * sets[0].KH * sets[0].KW * sets[0].Cin;
+    hipLaunchKernelGGL(k_recode_im2col_t, dim3(grid_for(items), 1, count), dim3(kThreads), 0, st, bt);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+int launch_mul_mask(mpc_ctx* c, hipStream_t st, const MulArgs& q)
+{
+    hipLaunchKernelGGL(k_mul_mask, dim3(grid_for(q.n), 2), dim3(kThreads), 0, st, q);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+int launch_mul_finish(mpc_ctx* c, hipStream_t st, const MulArgs& q)
+{
+    hipLaunchKernelGGL(k_mul_finish, dim3(grid_for(q.n), 2), dim3(kThreads), 0, st, q);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
 }

@@ -404,16 +404,25 @@ int launch_cfg(mpc_ctx* c, hipStream_t st, const GemmArgs& g)
 
 // How many ways to split the contraction so that a small output still fills
 // the chip: aim for about 256 workgroups, keep at least 4 K steps per slice.
+// 32 k per step; with balanced digits (|d| <= 128) the digit-sum groups that
+// matter beyond their low 32 bits hold at most four pairs, so 4 * 2^14 * k < 2^31.
+constexpr int kMaxStepsExact = 1023;
+
 int gemm_ksplit(int M, int N, int batch, int nparty, int total_steps)
 {
     const bool narrow = ((N - 1) % 128) < 64 && (N <= 64 || M >= 4096);
     const long long tiles = (long long)((M + (narrow ? 127 : 63)) / (narrow ? 128 : 64)) *
                             ((N + (narrow ? 63 : 127)) / (narrow ? 64 : 128)) * batch * nparty;
-    if (tiles >= 160 || total_steps < 8) return 1;
-    int s = (int)((256 + tiles - 1) / tiles);
-    if (s > total_steps / 4) s = total_steps / 4;
-    if (s > 32) s = 32;
-    if (s < 1) s = 1;
+    // the int32 digit sums of one workgroup stay exact for at most kMaxStepsExact steps
+    const int s_exact = (total_steps + kMaxStepsExact - 1) / kMaxStepsExact;
+    int s = 1;
+    if (tiles < 160 && total_steps >= 8) {
+        s = (int)((256 + tiles - 1) / tiles);
+        if (s > total_steps / 4) s = total_steps / 4;
+        if (s > 32) s = 32;
+    }
+    if (s < s_exact) s = s_exact;
+    if (s <= 1) return 1;
     const int per = (total_steps + s - 1) / s;
     return (total_steps + per - 1) / per;          // no empty slice
 }
@@ -427,6 +436,7 @@ int launch_limb_gemm(mpc_ctx* c, hipStream_t st, const GemmArgs& g_in)
         if (g.ksplit < 1 || !g.partial) g.ksplit = 1;
         g.steps_per_split = (total_steps + g.ksplit - 1) / g.ksplit;
         g.ksplit = (total_steps + g.steps_per_split - 1) / g.steps_per_split;      // no empty slice
+        if (g.steps_per_split > kMaxStepsExact) return MPC_ERANGE;
         if ((long long)g.batch * g.nparty * g.ksplit > 65535) return MPC_EINVAL;
     }
     if (g.M <= 0 || g.N <= 0 || g.batch <= 0 || g.nseg < 1 || g.nseg > 2) return MPC_EINVAL;

@@ -13,16 +13,21 @@ struct LinearShape {
     int B, H, W, Cin, Cout, KH, KW, pad, stride, Ho, Wo, CB;
     // derived
     size_t nx, nw, nz;           // words in x / w / z per party (all batch items)
+    bool transX, transY;         // matmul operands stored transposed ([K][M] / [N][K])
+    bool wflip;                  // conv: filter stored [KH][KW][N][Cin'] and read in reverse tap order (input gradient)
+    bool im2colT;                // left operand = transposed im2col of an NHWC tensor (filter gradient)
+    int gB, gH, gW, gCin, gKH, gKW, gpad, gstride, gHo, gWo;    // geometry of that tensor
     int rowsL;                   // rows of a left plane (M, or B*H*W pixels + 1 zero row)
     int KB_L;                    // k blocks stored per left plane row
     int KB;                      // k blocks contracted per segment (even)
     size_t L_plane, R_plane;     // bytes of one digit plane (one batch item)
 };
 
-LinearShape shape_matmul(int M, int K, int N, int batch)
+LinearShape shape_matmul(int M, int K, int N, int batch, int flags = 0)
 {
     LinearShape s{};
     s.conv = false; s.M = M; s.K = K; s.N = N; s.batch = batch;
+    s.transX = (flags & MPC_TRANS_X) != 0; s.transY = (flags & MPC_TRANS_Y) != 0;
     s.nx = (size_t)batch * M * K; s.nw = (size_t)batch * K * N; s.nz = (size_t)batch * M * N;
     s.rowsL = M; s.KB = kblocks(K); s.KB_L = s.KB;
     s.L_plane = plane_bytes(M, s.KB); s.R_plane = plane_bytes(N, s.KB);
@@ -41,6 +46,30 @@ LinearShape shape_conv(int B, int H, int W, int Cin, int Cout, int KH, int KW, i
     s.rowsL = B * H * W + 1; s.KB_L = s.CB;      // + the all-zero row that padding taps read
     s.KB = (KH * KW * s.CB + 1) & ~1;
     s.L_plane = plane_bytes(s.rowsL, s.KB_L); s.R_plane = plane_bytes(Cout, s.KB);
+    return s;
+}
+
+// Input gradient of a stride-1 convolution with a square filter: itself a
+// convolution of the output gradient [B][Ho][Wo][Cout] with the filter read
+// in reverse tap order and with its channel roles swapped, padding KH-1-pad.
+LinearShape shape_conv_grad_x(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad)
+{
+    const int Ho = H + 2 * pad - KH + 1, Wo = W + 2 * pad - KW + 1;
+    LinearShape s = shape_conv(B, Ho, Wo, Cout, Cin, KH, KW, KH - 1 - pad, 1);
+    s.wflip = true;
+    return s;
+}
+
+// Filter gradient: [KH*KW*Cin x B*Ho*Wo] (transposed im2col of x) times
+// [B*Ho*Wo x Cout] (the output gradient as it is stored).
+LinearShape shape_conv_grad_w(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    const int Ho = (H + 2 * pad - KH) / stride + 1, Wo = (W + 2 * pad - KW) / stride + 1;
+    LinearShape s = shape_matmul(KH * KW * Cin, B * Ho * Wo, Cout, 1);
+    s.im2colT = true;
+    s.gB = B; s.gH = H; s.gW = W; s.gCin = Cin; s.gKH = KH; s.gKW = KW; s.gpad = pad; s.gstride = stride;
+    s.gHo = Ho; s.gWo = Wo;
+    s.nx = (size_t)B * H * W * Cin;             // x and its mask keep their NHWC shape
     return s;
 }
 
@@ -78,10 +107,32 @@ RecodeArgs recode_left(const LinearShape& s, const u64* src, const u64* src2, u8
     a.k_stride = 1; a.tap_stride = 0; a.ntaps = 1; a.batch = s.batch;
     if (s.conv) { a.rows = s.rowsL - 1; a.plane_rows = s.rowsL; a.K = s.Cin; a.row_stride = s.Cin; a.KB_tap = s.CB; a.KB_total = s.CB; }
     else        { a.rows = s.M; a.plane_rows = s.M; a.K = s.K; a.row_stride = s.K; a.KB_tap = (s.K + 15) / 16; a.KB_total = s.KB; }
+    if (s.transX) { a.row_stride = 1; a.k_stride = s.M; }       // stored [K][M]
     a.digit_stride = (long long)s.L_plane;
     a.src_batch_stride = (long long)s.M * s.K;          // unused for conv (batch == 1)
     a.dst_batch_stride = (long long)(8 * s.L_plane);
     return a;
+}
+
+// Left digit planes of up to three sources in one launch.
+int launch_left(mpc_ctx* c, hipStream_t st, const LinearShape& s, int count,
+                const u64* const src[], const u64* const src2[], u8* const dst[])
+{
+    if (s.im2colT) {
+        Im2colTArgs t[3];
+        for (int i = 0; i < count; ++i)
+            t[i] = Im2colTArgs{ src[i], src2[i], dst[i], s.gB, s.gH, s.gW, s.gCin, s.gKH, s.gKW, s.gpad, s.gstride,
+                                s.gHo, s.gWo, s.KB, (long long)s.L_plane };
+        return launch_recode_im2col_t(c, st, t, count);
+    }
+    RecodeArgs r[3];
+    for (int i = 0; i < count; ++i) r[i] = recode_left(s, src[i], src2[i], dst[i]);
+    return count == 1 ? launch_recode(c, st, r[0]) : launch_recode_multi(c, st, r, count);
+}
+int launch_left1(mpc_ctx* c, hipStream_t st, const LinearShape& s, const u64* src, const u64* src2, u8* dst)
+{
+    const u64* a[1] = { src }; const u64* b[1] = { src2 }; u8* d[1] = { dst };
+    return launch_left(c, st, s, 1, a, b, d);
 }
 
 RecodeArgs recode_right(const LinearShape& s, const u64* src, const u64* src2, const u64* src3, u8* dst)
@@ -91,6 +142,14 @@ RecodeArgs recode_right(const LinearShape& s, const u64* src, const u64* src2, c
     a.rows = s.N; a.plane_rows = s.N; a.row_stride = 1; a.k_stride = s.N; a.batch = s.batch;
     if (s.conv) { a.K = s.Cin; a.KB_tap = s.CB; a.ntaps = s.KH * s.KW; a.tap_stride = (long long)s.Cin * s.Cout; }
     else        { a.K = s.K; a.KB_tap = (s.K + 15) / 16; a.ntaps = 1; a.tap_stride = 0; }
+    if (s.transY) { a.row_stride = s.K; a.k_stride = 1; }       // stored [N][K]
+    if (s.wflip) {
+        // stored [tap][n][k] (the forward filter [KH][KW][Cin][Cout] with n = Cin, k = Cout), taps reversed
+        const long long tap_words = (long long)s.N * s.Cin;
+        a.row_stride = s.Cin; a.k_stride = 1; a.tap_stride = -tap_words;
+        const long long last = (long long)(s.KH * s.KW - 1) * tap_words;
+        a.src = src + last; a.src2 = src2 ? src2 + last : nullptr; a.src3 = src3 ? src3 + last : nullptr;
+    }
     a.KB_total = s.KB;
     a.digit_stride = (long long)s.R_plane;
     a.src_batch_stride = (long long)s.K * s.N;
@@ -130,8 +189,9 @@ int check_shape(const LinearShape& s)
         if (s.B <= 0 || s.H <= 0 || s.W <= 0 || s.Cin <= 0 || s.Cout <= 0 || s.KH <= 0 || s.KW <= 0 ||
             s.pad < 0 || s.stride <= 0 || s.Ho <= 0 || s.Wo <= 0 || s.KH * s.KW > 64)
             return MPC_EINVAL;
-        if ((long long)s.KH * s.KW * s.CB * 16 > MPC_MAX_K) return MPC_ERANGE;
-    } else if (s.K > MPC_MAX_K) return MPC_ERANGE;
+        if ((long long)s.KH * s.KW * s.CB * 16 > MPC_MAX_K_TOTAL) return MPC_ERANGE;
+    } else if (s.K > MPC_MAX_K_TOTAL) return MPC_ERANGE;
+    if ((long long)s.M * s.N * s.batch > (1ll << 40)) return MPC_ERANGE;
     if ((long long)s.batch * 2 > 65535) return MPC_EINVAL;
     return MPC_OK;
 }
@@ -139,13 +199,14 @@ int check_shape(const LinearShape& s)
 // The whole secure linear layer.  See mpc_beaver_matmul in the public header.
 int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
                   mpc_cshare a, mpc_cshare b, mpc_cshare cc, mpc_share z,
-                  const u64* f_public, int n_chunks, int flags)
+                  const u64* f_public, int n_chunks, int flags, const u64* x_public = nullptr)
 {
     if (!c) return MPC_EINVAL;
     MPC_TRY(check_shape(s));
     if (n_chunks < 1) return MPC_EINVAL;
     for (int i = 0; i < 2; ++i) {
-        if (!x.p[i] || !a.p[i] || !b.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
+        if (!a.p[i] || !b.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
+        if (!x_public && !x.p[i]) return MPC_EINVAL;
         if (!f_public && !y.p[i]) return MPC_EINVAL;
     }
     LinearWs w = carve(c->ws, c->ws_bytes, s);
@@ -170,7 +231,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
             if (ch == n_chunks - 1) hi = s.nx;
             if (hi <= lo) continue;
             SubSeg sub[4]; CopySeg cp[4]; int ns = 0;
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < 2 && !x_public; ++i) {
                 sub[ns] = SubSeg{ x.p[i] + lo, a.p[i] + lo, w.se[i] + lo, hi - lo, 0 };
                 cp[ns] = CopySeg{ (const u8*)(w.se[i] + lo), (u8*)(w.re[1 - i] + lo), (hi - lo) * sizeof(u64), 0 };
                 ++ns;
@@ -181,19 +242,20 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
                     cp[ns] = CopySeg{ (const u8*)w.sf[i], (u8*)w.rf[1 - i], s.nw * sizeof(u64), 0 };
                     ++ns;
                 }
+            if (ns == 0) continue;                           // both operands were opened ahead of time
             MPC_TRY(launch_sub_multi(c, P0, sub, ns));       // Alg. 1: mask
             MPC_TRY(launch_copy_multi(c, P0, cp, ns));       // Alg. 1: exchange
         }
         const u64* f0 = f_public ? f_public : w.sf[0];
         const u64* f1 = f_public ? nullptr : w.rf[0];
-        RecodeArgs rl[3], rr[3];
-        rl[0] = recode_left(s, a.p[0], nullptr, w.pl_a[0]);
-        rl[1] = recode_left(s, a.p[1], nullptr, w.pl_a[1]);
-        rl[2] = recode_left(s, w.se[0], w.re[0], w.pl_e);
+        RecodeArgs rr[3];
+        const u64* lsrc[3] = { a.p[0], a.p[1], x_public ? x_public : w.se[0] };
+        const u64* lsrc2[3] = { nullptr, nullptr, x_public ? nullptr : w.re[0] };
+        u8* ldst[3] = { w.pl_a[0], w.pl_a[1], w.pl_e };
         rr[0] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
         rr[1] = recode_right(s, f0, f1, nullptr, w.pr_f);
         rr[2] = recode_right(s, b.p[0], f0, f1, w.pr_b[0]);
-        MPC_TRY(launch_recode_multi(c, P0, rl, 3));
+        MPC_TRY(launch_left(c, P0, s, 3, lsrc, lsrc2, ldst));
         MPC_TRY(launch_recode_multi(c, P0, rr, 3));
         if (two_phase && f_public) {
             g.nseg = 1;
@@ -238,6 +300,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         size_t lo = (s.nx * ch / n_chunks) & ~(size_t)1, hi = (s.nx * (ch + 1) / n_chunks) & ~(size_t)1;
         if (ch == n_chunks - 1) hi = s.nx;
         if (hi <= lo) continue;
+        if (x_public) break;
         for (int i = 0; i < 2; ++i) {
             MPC_TRY(launch_sub(c, P[i], x.p[i] + lo, a.p[i] + lo, w.se[i] + lo, hi - lo));
             MPC_TRY(chain(c, P[i], Wr));
@@ -245,10 +308,12 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         for (int i = 0; i < 2; ++i)
             MPC_TRY(launch_copy(c, Wr, w.se[i] + lo, w.re[1 - i] + lo, (hi - lo) * sizeof(u64)));
     }
+    const u64* e_src = x_public ? x_public : w.se[0];
+    const u64* e_src2 = x_public ? nullptr : w.re[0];
 
     // -- digit planes that do not depend on the exchange: [a_i] (and b_1)
     for (int i = 0; i < 2; ++i)
-        MPC_TRY(launch_recode(c, P[i], recode_left(s, a.p[i], nullptr, w.pl_a[i])));
+        MPC_TRY(launch_left1(c, P[i], s, a.p[i], nullptr, w.pl_a[i]));
     MPC_TRY(launch_recode(c, P1, recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1])));
 
     GemmArgs g{};
@@ -270,7 +335,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         MPC_TRY(launch_limb_gemm(c, P0, g));
         // Alg. 3 lines 7-10: wait for Delta, add [c_i] + Conv(Delta, [b_i]) (+ Conv(Delta, epsilon))
         MPC_TRY(chain(c, Wr, P0));
-        MPC_TRY(launch_recode(c, P0, recode_left(s, w.se[0], w.re[0], w.pl_e)));
+        MPC_TRY(launch_left1(c, P0, s, e_src, e_src2, w.pl_e));
         for (int i = 0; i < 2; ++i) {
             g.seg[i][0] = make_seg(s, w.pl_e, w.pr_b[i]);
             g.addend[i] = cc.p[i]; g.addend2[i] = z.p[i];
@@ -281,7 +346,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         // Alg. 1 lines 3-7: wait for the exchange, open, one fused contraction
         // [e | a_i] x [b_i (+ f for party 0) ; f] per party.
         MPC_TRY(chain(c, Wr, P0));
-        MPC_TRY(launch_recode(c, P0, recode_left(s, w.se[0], w.re[0], w.pl_e)));
+        MPC_TRY(launch_left1(c, P0, s, e_src, e_src2, w.pl_e));
         if (f_public) {
             MPC_TRY(launch_recode(c, P0, recode_right(s, f_public, nullptr, nullptr, w.pr_f)));
             MPC_TRY(launch_recode(c, P0, recode_right(s, b.p[0], f_public, nullptr, w.pr_b[0])));
@@ -313,7 +378,7 @@ int ring_product(mpc_ctx* c, const LinearShape& s, const u64* L, const u64* R, u
     if (!w.ok) return MPC_ENOMEM;
     hipStream_t P0 = c->s[0];
     MPC_TRY(lane_join(c));
-    MPC_TRY(launch_recode(c, P0, recode_left(s, L, nullptr, w.pl_e)));
+    MPC_TRY(launch_left1(c, P0, s, L, nullptr, w.pl_e));
     MPC_TRY(launch_recode(c, P0, recode_right(s, R, nullptr, nullptr, w.pr_f)));
     GemmArgs g{};
     fill_geom(s, w, g);
@@ -349,7 +414,45 @@ int mpc_beaver_matmul(mpc_ctx* ctx, mpc_cshare x, mpc_cshare y, mpc_cshare a, mp
                       const uint64_t* f_public, int n_chunks, int flags)
 {
     if (M <= 0 || K <= 0 || N <= 0 || batch <= 0) return MPC_EINVAL;
-    return beaver_linear(ctx, shape_matmul(M, K, N, batch), x, y, a, b, c, z, f_public, n_chunks, flags);
+    return beaver_linear(ctx, shape_matmul(M, K, N, batch, flags), x, y, a, b, c, z, f_public, n_chunks, flags);
+}
+
+size_t mpc_conv2d_grad_x_workspace_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (stride != 1 || KH != KW || KH <= 0 || pad < 0 || pad > KH - 1 || H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return 0;
+    LinearShape s = shape_conv_grad_x(B, H, W, Cin, Cout, KH, KW, pad);
+    if (check_shape(s) != MPC_OK) return 0;
+    return carve(nullptr, 0, s).bytes;
+}
+
+size_t mpc_conv2d_grad_w_workspace_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (stride <= 0 || KH <= 0 || KW <= 0 || pad < 0 || H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return 0;
+    LinearShape s = shape_conv_grad_w(B, H, W, Cin, Cout, KH, KW, pad, stride);
+    if (check_shape(s) != MPC_OK) return 0;
+    return carve(nullptr, 0, s).bytes;
+}
+
+int mpc_conv2d_grad_x(mpc_ctx* ctx, mpc_cshare g, mpc_cshare w, mpc_cshare a, mpc_cshare b, mpc_cshare c,
+                      mpc_share gx, int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride,
+                      const uint64_t* f_public, int n_chunks, int flags)
+{
+    if (B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0) return MPC_EINVAL;
+    if (stride != 1 || KH != KW || pad > KH - 1 || H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return MPC_EINVAL;
+    if (flags & (MPC_TRANS_X | MPC_TRANS_Y)) return MPC_EINVAL;
+    return beaver_linear(ctx, shape_conv_grad_x(B, H, W, Cin, Cout, KH, KW, pad), g, w, a, b, c, gx,
+                         f_public, n_chunks, flags);
+}
+
+int mpc_conv2d_grad_w(mpc_ctx* ctx, mpc_cshare x, mpc_cshare g, mpc_cshare a, mpc_cshare b, mpc_cshare c,
+                      mpc_share gw, int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride,
+                      const uint64_t* e_public, int n_chunks, int flags)
+{
+    if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
+        return MPC_EINVAL;
+    if (H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0 || (flags & (MPC_TRANS_X | MPC_TRANS_Y | MPC_TWO_PHASE))) return MPC_EINVAL;
+    return beaver_linear(ctx, shape_conv_grad_w(B, H, W, Cin, Cout, KH, KW, pad, stride), x, g, a, b, c, gw,
+                         nullptr, n_chunks, flags, e_public);
 }
 
 int mpc_conv2d(mpc_ctx* ctx, mpc_cshare x, mpc_cshare w, mpc_cshare a, mpc_cshare b, mpc_cshare c,
@@ -358,6 +461,7 @@ int mpc_conv2d(mpc_ctx* ctx, mpc_cshare x, mpc_cshare w, mpc_cshare a, mpc_cshar
 {
     if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
         return MPC_EINVAL;
+    if (flags & (MPC_TRANS_X | MPC_TRANS_Y)) return MPC_EINVAL;
     return beaver_linear(ctx, shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride), x, w, a, b, c, z,
                          f_public, n_chunks, flags);
 }

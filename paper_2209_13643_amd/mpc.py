@@ -17,6 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmpcpipe.so")
 
 MPC_TRUNCATE = 1
+MPC_TRANS_X = 4
+MPC_TRANS_Y = 8
 MPC_TWO_PHASE = 2
 PROF_GEMM_KERNEL, PROF_LINEAR, PROF_RELU = 0, 1, 2
 N_AND_TRIPLES = 12
@@ -43,6 +45,8 @@ EXPORTS = [
     "mpc_relu", "mpc_maxpool2x2", "mpc_ring_matmul", "mpc_ring_conv2d",
     "mpc_relu_msb_workspace_bytes", "mpc_maxpool_msb_workspace_bytes", "mpc_relu_packed_words",
     "mpc_relu_pack_triples", "mpc_relu_msb", "mpc_maxpool2x2_msb",
+    "mpc_conv2d_grad_x_workspace_bytes", "mpc_conv2d_grad_w_workspace_bytes", "mpc_conv2d_grad_x",
+    "mpc_conv2d_grad_w", "mpc_mul_workspace_bytes", "mpc_mul", "mpc_relu_backward",
 ]
 
 _lib = None
@@ -81,6 +85,13 @@ def lib():
     L.mpc_beaver_matmul.argtypes = [c_void_p] + [CShare] * 6 + [c_int] * 4 + [_P64, c_int, c_int]
     L.mpc_conv2d.argtypes = [c_void_p] + [CShare] * 6 + [c_int] * 9 + [_P64, c_int, c_int]
     L.mpc_truncate.argtypes = [c_void_p, CShare, c_size_t, c_int]
+    for name in ("mpc_conv2d_grad_x_workspace_bytes", "mpc_conv2d_grad_w_workspace_bytes"):
+        getattr(L, name).argtypes = [c_int] * 9; getattr(L, name).restype = c_size_t
+    L.mpc_conv2d_grad_x.argtypes = L.mpc_conv2d.argtypes
+    L.mpc_conv2d_grad_w.argtypes = L.mpc_conv2d.argtypes
+    L.mpc_mul_workspace_bytes.argtypes = [c_size_t]; L.mpc_mul_workspace_bytes.restype = c_size_t
+    L.mpc_mul.argtypes = [c_void_p] + [CShare] * 6 + [c_size_t, c_int]
+    L.mpc_relu_backward.argtypes = [c_void_p] + [CShare] * 6 + [c_size_t]
     L.mpc_relu.argtypes = [c_void_p, CShare, POINTER(ReluMaterial), CShare, c_size_t, c_int,
                            POINTER(_P8 * 2), POINTER(_P64 * 2)]
     L.mpc_maxpool2x2.argtypes = [c_void_p, CShare, POINTER(ReluMaterial), POINTER(ReluMaterial), CShare,
@@ -243,11 +254,12 @@ class Lane:
         return out
 
     def beaver_matmul(self, x, y, a, b, c, f_public=None, n_chunks=1, flags=MPC_TRUNCATE, out=None):
+        """x, a: [.., M, K] ([.., K, M] with MPC_TRANS_X); y, b: [.., K, N] ([.., N, K] with MPC_TRANS_Y)."""
         shp = a[0].shape
         batch = 1 if len(shp) == 2 else shp[0]
-        M, K = shp[-2], shp[-1]
-        N = b[0].shape[-1]
-        assert b[0].shape[-2] == K and c[0].shape[-2:] == (M, N)
+        M, K = (shp[-1], shp[-2]) if flags & MPC_TRANS_X else (shp[-2], shp[-1])
+        K2, N = (b[0].shape[-1], b[0].shape[-2]) if flags & MPC_TRANS_Y else (b[0].shape[-2], b[0].shape[-1])
+        assert K2 == K and c[0].shape[-2:] == (M, N)
         self.reserve(lib().mpc_matmul_workspace_bytes(M, K, N, batch))
         z = out if out is not None else (torch.empty_like(c[0]), torch.empty_like(c[1]))
         self._check(lib().mpc_beaver_matmul(self._h, _share(x), _share(y), _share(a), _share(b), _share(c),
@@ -263,6 +275,45 @@ class Lane:
         self._check(lib().mpc_conv2d(self._h, _share(x), _share(w), _share(a), _share(b), _share(c), _share(z),
                                      B, H, W, Cin, Cout, KH, KW, pad, stride, _p64(f_public), n_chunks, flags))
         return z
+
+    def conv2d_grad_x(self, g, w, a, b, c, pad, stride=1, f_public=None, n_chunks=1, flags=MPC_TRUNCATE, out=None):
+        """Input gradient of conv2d: g, a [B,Ho,Wo,Cout]; w, b [KH,KW,Cin,Cout]; c and result [B,H,W,Cin]."""
+        B, H, W, Cin = c[0].shape
+        KH, KW, Cin2, Cout = b[0].shape
+        assert Cin == Cin2 and a[0].shape[-1] == Cout
+        self.reserve(lib().mpc_conv2d_grad_x_workspace_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride))
+        gx = out if out is not None else (torch.empty_like(c[0]), torch.empty_like(c[1]))
+        self._check(lib().mpc_conv2d_grad_x(self._h, _share(g), _share(w), _share(a), _share(b), _share(c), _share(gx),
+                                            B, H, W, Cin, Cout, KH, KW, pad, stride, _p64(f_public), n_chunks, flags))
+        return gx
+
+    def conv2d_grad_w(self, x, g, a, b, c, pad, stride, e_public=None, n_chunks=1, flags=MPC_TRUNCATE, out=None):
+        """Filter gradient of conv2d: x, a [B,H,W,Cin]; g, b [B,Ho,Wo,Cout]; c and result [KH,KW,Cin,Cout]."""
+        B, H, W, Cin = a[0].shape
+        KH, KW, Cin2, Cout = c[0].shape
+        assert Cin == Cin2 and b[0].shape[-1] == Cout
+        self.reserve(lib().mpc_conv2d_grad_w_workspace_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride))
+        gw = out if out is not None else (torch.empty_like(c[0]), torch.empty_like(c[1]))
+        self._check(lib().mpc_conv2d_grad_w(self._h, _share(x), _share(g), _share(a), _share(b), _share(c), _share(gw),
+                                            B, H, W, Cin, Cout, KH, KW, pad, stride, _p64(e_public), n_chunks, flags))
+        return gw
+
+    def mul(self, x, y, a, b, c, flags=0, out=None):
+        """Element-wise Alg. 1."""
+        n = x[0].numel()
+        self.reserve(lib().mpc_mul_workspace_bytes(n))
+        z = out if out is not None else (torch.empty_like(x[0]), torch.empty_like(x[1]))
+        self._check(lib().mpc_mul(self._h, _share(x), _share(y), _share(a), _share(b), _share(c), _share(z), n, flags))
+        return z
+
+    def relu_backward(self, g, s_arith, a, b, c, out=None):
+        """Output gradient times the ReLU input mask 1 - s (s_arith from the forward relu)."""
+        n = g[0].numel()
+        self.reserve(lib().mpc_mul_workspace_bytes(n))
+        gx = out if out is not None else (torch.empty_like(g[0]), torch.empty_like(g[1]))
+        self._check(lib().mpc_relu_backward(self._h, _share(g), _share(s_arith), _share(a), _share(b), _share(c),
+                                            _share(gx), n))
+        return gx
 
     def truncate(self, z, bits=16):
         self._check(lib().mpc_truncate(self._h, _share(z), z[0].numel(), bits))

@@ -51,7 +51,8 @@ def test_workspace_queries(lib):
     assert ws >= 3 * 8 * M * K + 3 * 8 * K * N + 4 * 8 * M * K + 4 * 8 * K * N
     assert lib.mpc_matmul_workspace_bytes(M, K, N, 2) > ws
     assert lib.mpc_matmul_workspace_bytes(0, K, N, 1) == 0
-    assert lib.mpc_matmul_workspace_bytes(M, 1 << 20, N, 1) == 0          # beyond the exactness bound
+    assert lib.mpc_matmul_workspace_bytes(M, 1 << 20, N, 1) > ws          # long contractions are cut into exact slices
+    assert lib.mpc_matmul_workspace_bytes(M, (1 << 22) + 1, N, 1) == 0    # beyond MPC_MAX_K_TOTAL
     assert lib.mpc_conv2d_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 1) > 0
     assert lib.mpc_conv2d_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 0) == 0
     assert lib.mpc_relu_workspace_bytes(1000) >= 2 * (8 * 1000 * 8 + 2 * 1000 * 8)

@@ -248,7 +248,7 @@ def test_argument_errors(mpc, lane):
     assert L.mpc_beaver_matmul(h, sh, sh, sh, sh, sh, sh, 0, 4, 4, 1, None, 1, 0) == -1
     assert L.mpc_beaver_matmul(h, sh, sh, sh, sh, sh, sh, 4, 4, 4, 1, None, 0, 0) == -1
     assert L.mpc_beaver_matmul(h, sh, null, sh, sh, sh, sh, 4, 2, 2, 1, None, 1, 0) == -1   # no y and no f_public
-    assert L.mpc_beaver_matmul(h, sh, sh, sh, sh, sh, sh, 4, 20000, 4, 1, None, 1, 0) == -4  # K too long
+    assert L.mpc_beaver_matmul(h, sh, sh, sh, sh, sh, sh, 4, 5000000, 4, 1, None, 1, 0) == -4  # K too long
     assert L.mpc_beaver_matmul(h, sh, sh, sh, sh, sh, sh, 4096, 4096, 4096, 1, None, 1, 0) == -2  # workspace
     assert L.mpc_truncate(h, sh, 16, 64) == -1
     assert L.mpc_relu(h, sh, None, sh, 16, 1, None, None) == -1
