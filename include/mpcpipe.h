@@ -300,6 +300,26 @@ int mpc_maxpool2x2_msb(mpc_ctx* ctx, mpc_cshare x, const mpc_relu_material* mat1
                        const mpc_relu_material* mat2, mpc_share y,
                        int B, int H, int W, int C, int n_chunks);
 
+/* Max-pool for training.  mpc_maxpool2x2_signs is mpc_maxpool2x2 (packed = 0)
+ * or mpc_maxpool2x2_msb (packed != 0) that also returns the additive sign
+ * shares of its two conversions: s1[i] 2*n_out words (pairs interleaved as in
+ * mat1), s2[i] n_out words.  mpc_maxpool2x2_backward routes the output
+ * gradient g [B][H/2][W/2][C] to the window maxima (Sec. 5.3: element-wise
+ * products with the stored masks): with m = 1 - s,
+ *   grad_u = g * m2, grad_v = g - grad_u                       (triple a2, b2, c2 on n_out words)
+ *   grad_p00 = grad_u * m1, grad_p01 = grad_u - grad_p00, and the same for
+ *   (grad_v; p10, p11)                                         (triple a1, b1, c1 on 2*n_out words)
+ * gx: [B][H][W][C].  Workspace: mpc_maxpool_backward_workspace_bytes. */
+int mpc_maxpool2x2_signs(mpc_ctx* ctx, mpc_cshare x, const mpc_relu_material* mat1,
+                         const mpc_relu_material* mat2, mpc_share y,
+                         uint64_t* const s1[2], uint64_t* const s2[2],
+                         int B, int H, int W, int C, int n_chunks, int packed);
+size_t mpc_maxpool_backward_workspace_bytes(int B, int H, int W, int C);
+int mpc_maxpool2x2_backward(mpc_ctx* ctx, mpc_cshare g, mpc_cshare s1, mpc_cshare s2,
+                            mpc_cshare a1, mpc_cshare b1, mpc_cshare c1,
+                            mpc_cshare a2, mpc_cshare b2, mpc_cshare c2,
+                            mpc_share gx, int B, int H, int W, int C);
+
 /* -------------------------------------------------- dealer helper (offline) */
 
 /* Plain ring product Z = L*R mod 2^64 on public device arrays, computed with
@@ -311,6 +331,14 @@ int mpc_ring_matmul(mpc_ctx* ctx, const uint64_t* L, const uint64_t* R, uint64_t
 int mpc_ring_conv2d(mpc_ctx* ctx, const uint64_t* x, const uint64_t* w, uint64_t* z,
                     int B, int H, int W, int Cin, int Cout, int KH, int KW,
                     int pad, int stride);
+/* The two gradient products of a convolution on public arrays (layouts as for
+ * mpc_conv2d_grad_x / mpc_conv2d_grad_w): C = F(A, B) of their triples. */
+int mpc_ring_conv2d_grad_x(mpc_ctx* ctx, const uint64_t* g, const uint64_t* w, uint64_t* gx,
+                           int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                           int pad, int stride);
+int mpc_ring_conv2d_grad_w(mpc_ctx* ctx, const uint64_t* x, const uint64_t* g, uint64_t* gw,
+                           int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                           int pad, int stride);
 
 #ifdef __cplusplus
 }

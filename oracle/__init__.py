@@ -293,16 +293,43 @@ def pool_level2(x, r1):
     return v, d2
 
 
-def maxpool2x2(x, mat1, mat2):
+def maxpool2x2(x, mat1, mat2, want_signs=False):
     """max over 2x2 windows by max(p,q) = q + ReLU(p-q), two tournament levels.
-    mat1 covers 2*n_out elements, mat2 n_out elements.  Returns output shares."""
+    mat1 covers 2*n_out elements, mat2 n_out elements.  Returns output shares;
+    with want_signs also the additive sign shares of the two conversions (what the
+    backward pass keeps)."""
     B, H, W, C = np.shape(x[0])
     d1 = (pool_level1(x[0]), pool_level1(x[1]))
-    r1 = relu(d1, mat1).y
+    c1 = relu(d1, mat1); r1 = c1.y
     v0, d20 = pool_level2(x[0], r1[0]); v1, d21 = pool_level2(x[1], r1[1])
-    r2 = relu((d20, d21), mat2).y
+    c2 = relu((d20, d21), mat2); r2 = c2.y
     shp = (B, H // 2, W // 2, C)
-    return ((v0 + r2[0]).reshape(shp), (v1 + r2[1]).reshape(shp))
+    y = ((v0 + r2[0]).reshape(shp), (v1 + r2[1]).reshape(shp))
+    return (y, c1.s_arith, c2.s_arith) if want_signs else y
+
+
+def maxpool2x2_backward(g, s1, s2, t1, t2, x_shape):
+    """Backward of maxpool2x2 (Sec. 5.3: element-wise products with the masks kept
+    from the forward conversions).  With m = 1 - s the mask of a conversion,
+    out = v + ReLU(u - v) gives grad_u = g*m2, grad_v = g - grad_u; one level down
+    u = p01 + ReLU(p00 - p01) gives grad_p00 = grad_u*m1, grad_p01 = grad_u - grad_p00,
+    and likewise v with (p10, p11).  t2 / t1: element-wise triples on n_out / 2*n_out
+    words (pairs interleaved as in pool_level1).  Returns shares shaped like the input."""
+    B, H, W, C = x_shape
+    g0, g1 = (np.asarray(v, U64).reshape(-1) for v in g)
+    gu = relu_backward((g0, g1), s2, *t2)
+    gv = (g0 - gu[0], g1 - gu[1])
+    G1 = tuple(np.stack([gu[i], gv[i]], axis=1).reshape(-1) for i in range(2))
+    P = relu_backward(G1, s1, *t1)
+    out = []
+    for i in range(2):
+        Pi = P[i].reshape(B, H // 2, W // 2, C, 2)
+        gui = gu[i].reshape(B, H // 2, W // 2, C); gvi = gv[i].reshape(B, H // 2, W // 2, C)
+        gx = np.empty((B, H // 2, 2, W // 2, 2, C), dtype=U64)
+        gx[:, :, 0, :, 0, :] = Pi[..., 0];       gx[:, :, 0, :, 1, :] = gui - Pi[..., 0]
+        gx[:, :, 1, :, 0, :] = Pi[..., 1];       gx[:, :, 1, :, 1, :] = gvi - Pi[..., 1]
+        out.append(gx.reshape(B, H, W, C))
+    return tuple(out)
 
 
 # --------------------------------------------- checkers on reconstructed values

@@ -85,6 +85,63 @@ def bench_layers(idx: int, reps: int = 5):
     return wl.name, rows
 
 
+def bench_backward(idx: int, reps: int = 5):
+    """Per layer: the two gradient products (weight / activation masks opened in the forward
+    pass reused) and the ReLU backward, timed with host clocks around a synchronised lane."""
+    wl = synth.CONFIGS[idx]()
+    lane = mpc.Lane(0); lane.use_single_queue()
+    dev = lane.device
+    g = dealer.gen(synth.BASE_SEED + 50 + idx, dev)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        lane.sync(); t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        lane.sync()
+        return (time.perf_counter() - t0) / reps
+
+    rows = []
+    for L in wl.layers:
+        macs = layer_macs(L)
+        if isinstance(L, synth.Conv):
+            f = dealer.conv_layer(lane, g, L.B, L.H, L.W, L.Cin, L.Cout, L.KH, L.KW, L.pad, L.stride, L.x_std, L.w_std)
+            b = dealer.conv_backward(lane, g, f, L.pad, L.stride)
+            n_out = L.B * L.Ho * L.Wo * L.Cout
+            gx = tuple(torch.empty_like(f["x"][0]) for _ in range(2)); gw = tuple(torch.empty_like(f["w"][0]) for _ in range(2))
+            t_x = timed(lambda: lane.conv2d_grad_x(b["g"], None, b["gx"]["a"], b["gx"]["b"], b["gx"]["c"], L.pad, L.stride,
+                                                   f_public=b["gx"]["f_public"], out=gx)) if "gx" in b else float("nan")
+            t_w = timed(lambda: lane.conv2d_grad_w(None, b["g"], b["gw"]["a"], b["gw"]["b"], b["gw"]["c"], L.pad, L.stride,
+                                                   e_public=b["gw"]["e_public"], out=gw))
+            shape = "x".join(map(str, L.gemm_mkn))
+        else:
+            f = dealer.matmul_layer(lane, g, L.M, L.K, L.N, L.x_std, L.w_std, batch=L.batch if L.batch > 1 else None)
+            b = dealer.matmul_backward(lane, g, f)
+            n_out = L.M * L.N * max(L.batch, 1)
+            gx = tuple(torch.empty_like(f["x"][0]) for _ in range(2)); gw = tuple(torch.empty_like(f["w"][0]) for _ in range(2))
+            t_x = timed(lambda: lane.beaver_matmul(b["g"], None, b["gx"]["a"], b["gx"]["b"], b["gx"]["c"],
+                                                   f_public=b["gx"]["f_public"], flags=mpc.MPC_TRUNCATE | mpc.MPC_TRANS_Y, out=gx))
+            t_w = timed(lambda: lane.beaver_matmul(f["x"], b["g"], b["gw"]["a"], b["gw"]["b"], b["gw"]["c"],
+                                                   flags=mpc.MPC_TRUNCATE | mpc.MPC_TRANS_X, out=gw))
+            shape = f"{L.M}x{L.K}x{L.N}" + (f" x{L.batch}" if L.batch > 1 else "")
+        row = dict(layer=L.name, gemm=shape, grad_x_ms=t_x * 1e3, grad_w_ms=t_w * 1e3,
+                   grad_x_macs_per_s=macs / t_x, grad_w_macs_per_s=macs / t_w)
+        if L.relu:
+            ta, tb, tc = dealer.mul_triple(g, n_out, dev)
+            sa = dealer.share(g, torch.randint(0, 2, (n_out,), generator=g, device=dev, dtype=torch.int64))
+            gr = tuple(torch.empty(n_out, dtype=torch.int64, device=dev) for _ in range(2))
+            gflat = (b["g"][0].view(-1), b["g"][1].view(-1))
+            torch.cuda.synchronize()
+            t_r = timed(lambda: lane.relu_backward(gflat, sa, ta, tb, tc, out=gr))
+            row.update(relu_bwd_ms=t_r * 1e3, relu_bwd_elems_per_s=n_out / t_r)
+        rows.append(row)
+        del f, b, gx, gw
+        torch.cuda.empty_cache()
+    lane.close()
+    return wl.name, rows
+
+
 def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = False):
     """Config 4: serial (one lane, micro-batches one after the other) vs pipelined (one lane each)."""
     wl = synth.config_vgg16_pipeline(micro_batch)
@@ -156,6 +213,17 @@ def main(argv):
     if argv and argv[0] == "sweep":
         print("== tile-count sweep, secure ReLU on 2097152 elements")
         sweep_tiles()
+        return
+    if argv and argv[0] == "backward":
+        for idx in ([int(a) for a in argv[1:]] or [1, 2, 3]):
+            name, rows = bench_backward(idx)
+            print(f"== backward products, config {idx}: {name}")
+            for r in rows:
+                line = (f"  {r['layer']:10s} {r['gemm']:22s} grad_x {r['grad_x_ms']:8.3f} ms {r['grad_x_macs_per_s'] / 1e12:6.2f} T MAC/s"
+                        f"  | grad_w {r['grad_w_ms']:8.3f} ms {r['grad_w_macs_per_s'] / 1e12:6.2f} T MAC/s")
+                if "relu_bwd_ms" in r:
+                    line += f"  | relu bwd {r['relu_bwd_ms']:7.3f} ms {r['relu_bwd_elems_per_s'] / 1e9:6.2f} G elems/s"
+                print(line, flush=True)
         return
     which = [int(a) for a in argv] if argv else list(range(len(synth.CONFIGS)))
     for idx in which:

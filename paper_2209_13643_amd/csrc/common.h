@@ -173,6 +173,17 @@ struct MulArgs {
 int launch_mul_mask(mpc_ctx* c, hipStream_t st, const MulArgs& q);
 int launch_mul_finish(mpc_ctx* c, hipStream_t st, const MulArgs& q);
 
+// max-pool backward: the local steps around its two element-wise products
+struct PoolBwdArgs {
+    const u64* g[2]; const u64* gu[2];    // output gradient, grad_u = g * mask2
+    u64* pairs[2];                        // [2*n_out] (grad_u, grad_v) interleaved
+    const u64* prod[2];                   // pairs * mask1
+    u64* gx[2];                           // [B][H][W][C]
+    size_t n_out; int B, H, W, C;
+};
+int launch_poolbwd_pairs(mpc_ctx* c, hipStream_t st, const PoolBwdArgs& q);
+int launch_poolbwd_scatter(mpc_ctx* c, hipStream_t st, const PoolBwdArgs& q);
+
 // several element-wise jobs in one launch (single-queue lanes)
 constexpr int kMaxSegs = 4;
 struct SubSeg { const u64* x; const u64* a; u64* out; size_t n; int vec; };

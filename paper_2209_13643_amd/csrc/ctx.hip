@@ -173,12 +173,13 @@ size_t mpc_mul_workspace_bytes(size_t n) { return n ? 8 * align_up(n * sizeof(u6
 // Element-wise Alg. 1.  Both parties' mask and finish kernels share a launch on
 // party 0's stream; the exchange of the masked words runs on the wire stream.
 static int mul_entry(mpc_ctx* c, mpc_cshare x, mpc_cshare y, mpc_cshare a, mpc_cshare b, mpc_cshare cc,
-                     mpc_share z, size_t n, int flags, int mask_from_sign)
+                     mpc_share z, size_t n, int flags, int mask_from_sign, size_t ws_off = 0)
 {
     if (!c || n == 0 || (flags & ~MPC_TRUNCATE)) return MPC_EINVAL;
     for (int i = 0; i < 2; ++i)
         if (!x.p[i] || !y.p[i] || !a.p[i] || !b.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
-    WsAlloc ws(c->ws, c->ws_bytes);
+    if (ws_off > c->ws_bytes) return MPC_ENOMEM;
+    WsAlloc ws(c->ws ? c->ws + ws_off : nullptr, c->ws_bytes - ws_off);
     MulArgs q{};
     u64 *re[2], *rf[2];
     for (int i = 0; i < 2; ++i) {
@@ -216,6 +217,47 @@ int mpc_relu_backward(mpc_ctx* c, mpc_cshare g, mpc_cshare s_arith, mpc_cshare a
                       mpc_share gx, size_t n)
 {
     return mul_entry(c, g, s_arith, a, b, cc, gx, n, 0, 1);
+}
+
+size_t mpc_maxpool_backward_workspace_bytes(int B, int H, int W, int C)
+{
+    if (B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1)) return 0;
+    const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
+    // per party grad_u (n_out), pairs and their product (2 n_out each); then the larger product's scratch
+    return 2 * (align_up(n_out * 8) + 2 * align_up(2 * n_out * 8)) + mpc_mul_workspace_bytes(2 * n_out);
+}
+
+// Backward of mpc_maxpool2x2: two element-wise products with the masks of the
+// two conversions and local sums around them.
+int mpc_maxpool2x2_backward(mpc_ctx* c, mpc_cshare g, mpc_cshare s1, mpc_cshare s2,
+                            mpc_cshare a1, mpc_cshare b1, mpc_cshare c1,
+                            mpc_cshare a2, mpc_cshare b2, mpc_cshare c2,
+                            mpc_share gx, int B, int H, int W, int C)
+{
+    if (!c || B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1)) return MPC_EINVAL;
+    for (int i = 0; i < 2; ++i)
+        if (!g.p[i] || !s1.p[i] || !s2.p[i] || !gx.p[i]) return MPC_EINVAL;
+    const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
+    WsAlloc ws(c->ws, c->ws_bytes);
+    mpc_share gu, pairs, prod;
+    for (int i = 0; i < 2; ++i) {
+        gu.p[i] = ws.take<u64>(n_out); pairs.p[i] = ws.take<u64>(2 * n_out); prod.p[i] = ws.take<u64>(2 * n_out);
+    }
+    if (!ws.ok) return MPC_ENOMEM;
+    const size_t off = ws.off;
+    const mpc_cshare gu_c = { { gu.p[0], gu.p[1] } }, pairs_c = { { pairs.p[0], pairs.p[1] } };
+    // grad_u = g * (1 - s2)
+    MPC_TRY(mul_entry(c, g, s2, a2, b2, c2, gu, n_out, 0, 1, off));
+    PoolBwdArgs q{};
+    for (int i = 0; i < 2; ++i) { q.g[i] = g.p[i]; q.gu[i] = gu.p[i]; q.pairs[i] = pairs.p[i]; q.prod[i] = prod.p[i]; q.gx[i] = gx.p[i]; }
+    q.n_out = n_out; q.B = B; q.H = H; q.W = W; q.C = C;
+    MPC_TRY(launch_poolbwd_pairs(c, c->s[0], q));
+    MPC_TRY(chain(c, c->s[0], c->s[1]));
+    // (grad_p00, grad_p10) = (grad_u, grad_v) * (1 - s1)
+    MPC_TRY(mul_entry(c, pairs_c, s1, a1, b1, c1, prod, 2 * n_out, 0, 1, off));
+    MPC_TRY(launch_poolbwd_scatter(c, c->s[0], q));
+    MPC_TRY(chain(c, c->s[0], c->s[1]));
+    return MPC_OK;
 }
 
 int mpc_truncate(mpc_ctx* c, mpc_share z, size_t n, int bits)

@@ -287,6 +287,41 @@ __global__ __launch_bounds__(kThreads) void k_mul_mask(MulArgs q)
     }
 }
 
+// Max-pool backward, between its two products (blockIdx.y = party):
+// grad_v = g - grad_u, and the pair (grad_u, grad_v) interleaved as the first
+// tournament level stored its pairs.
+__global__ __launch_bounds__(kThreads) void k_poolbwd_pairs(PoolBwdArgs q)
+{
+    const int i = blockIdx.y;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < q.n_out; o += stride) {
+        const u64 gu = q.gu[i][o];
+        q.pairs[i][2 * o] = gu;
+        q.pairs[i][2 * o + 1] = q.g[i][o] - gu;
+    }
+}
+
+// ... and after the second product P = pairs * mask1: the four window positions
+// receive P[2o], grad_u - P[2o], P[2o+1], grad_v - P[2o+1] (NHWC input layout).
+__global__ __launch_bounds__(kThreads) void k_poolbwd_scatter(PoolBwdArgs q)
+{
+    const int i = blockIdx.y;
+    const int Ho = q.H / 2, Wo = q.W / 2;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < q.n_out; o += stride) {
+        const int ch = (int)(o % q.C); size_t t = o / q.C;
+        const int wo = (int)(t % Wo); t /= Wo;
+        const int ho = (int)(t % Ho); const int b = (int)(t / Ho);
+        const size_t base = (((size_t)b * q.H + 2 * ho) * q.W + 2 * wo) * q.C + ch;
+        const size_t dw = q.C, dh = (size_t)q.W * q.C;
+        const u64 p0 = q.prod[i][2 * o], p1 = q.prod[i][2 * o + 1];
+        const u64 gu = q.pairs[i][2 * o], gv = q.pairs[i][2 * o + 1];
+        u64* gx = q.gx[i];
+        gx[base] = p0;            gx[base + dw] = gu - p0;
+        gx[base + dh] = p1;       gx[base + dh + dw] = gv - p1;
+    }
+}
+
 // Several recodings in one launch: blockIdx.z = set * batch + batch item.
 __global__ __launch_bounds__(kThreads) void k_recode_multi(RecodeBatch rb)
 {
@@ -476,6 +511,20 @@ int launch_mul_mask(mpc_ctx* c, hipStream_t st, const MulArgs& q)
 int launch_mul_finish(mpc_ctx* c, hipStream_t st, const MulArgs& q)
 {
     hipLaunchKernelGGL(k_mul_finish, dim3(grid_for(q.n), 2), dim3(kThreads), 0, st, q);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+int launch_poolbwd_pairs(mpc_ctx* c, hipStream_t st, const PoolBwdArgs& q)
+{
+    hipLaunchKernelGGL(k_poolbwd_pairs, dim3(grid_for(q.n_out), 2), dim3(kThreads), 0, st, q);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+int launch_poolbwd_scatter(mpc_ctx* c, hipStream_t st, const PoolBwdArgs& q)
+{
+    hipLaunchKernelGGL(k_poolbwd_scatter, dim3(grid_for(q.n_out), 2), dim3(kThreads), 0, st, q);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
 }

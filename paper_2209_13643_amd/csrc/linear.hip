@@ -481,4 +481,21 @@ int mpc_ring_conv2d(mpc_ctx* ctx, const uint64_t* x, const uint64_t* w, uint64_t
     return ring_product(ctx, shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride), x, w, z);
 }
 
+int mpc_ring_conv2d_grad_x(mpc_ctx* ctx, const uint64_t* g, const uint64_t* w, uint64_t* gx,
+                           int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0) return MPC_EINVAL;
+    if (stride != 1 || KH != KW || pad > KH - 1 || H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return MPC_EINVAL;
+    return ring_product(ctx, shape_conv_grad_x(B, H, W, Cin, Cout, KH, KW, pad), g, w, gx);
+}
+
+int mpc_ring_conv2d_grad_w(mpc_ctx* ctx, const uint64_t* x, const uint64_t* g, uint64_t* gw,
+                           int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
+        return MPC_EINVAL;
+    if (H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return MPC_EINVAL;
+    return ring_product(ctx, shape_conv_grad_w(B, H, W, Cin, Cout, KH, KW, pad, stride), x, g, gw);
+}
+
 }  // extern "C"

@@ -884,7 +884,8 @@ size_t maxpool_ws(int B, int H, int W, int C, bool packed)
 }
 
 int maxpool_entry(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat1, const mpc_relu_material* mat2,
-                  mpc_share y, int B, int H, int W, int C, int n_chunks, bool packed)
+                  mpc_share y, int B, int H, int W, int C, int n_chunks, bool packed,
+                  uint64_t* const s1[2] = nullptr, uint64_t* const s2[2] = nullptr)
 {
     if (!c || B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1) || n_chunks < 0 ||
         !x.p[0] || !x.p[1] || !y.p[0] || !y.p[1])
@@ -916,7 +917,7 @@ int maxpool_entry(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat1, const
     for (int i = 0; i < 2; ++i) {
         hipLaunchKernelGGL(k_pool_l1, grid, block, 0, c->s[i], x.p[i], d1[i], B, H, W, C);
         MPC_HIP(c, hipGetLastError());
-        fill_party(pp[i], i, d1[i], mat1, w1, r1[i], nullptr, nullptr, 2 * n_out);
+        fill_party(pp[i], i, d1[i], mat1, w1, r1[i], nullptr, s1 ? s1[i] : nullptr, 2 * n_out);
     }
     MPC_TRY(lane_join(c));
     MPC_TRY(relu_run(c, pp, 2 * n_out, n_chunks, packed ? &g1 : nullptr));
@@ -924,7 +925,7 @@ int maxpool_entry(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat1, const
     for (int i = 0; i < 2; ++i) {
         hipLaunchKernelGGL(k_pool_l2, grid, block, 0, c->s[i], x.p[i], r1[i], v[i], d2[i], B, H, W, C);
         MPC_HIP(c, hipGetLastError());
-        fill_party(pp[i], i, d2[i], mat2, w2, y.p[i], nullptr, nullptr, n_out);
+        fill_party(pp[i], i, d2[i], mat2, w2, y.p[i], nullptr, s2 ? s2[i] : nullptr, n_out);
     }
     MPC_TRY(lane_join(c));
     MPC_TRY(relu_run(c, pp, n_out, n_chunks, packed ? &g2 : nullptr));
@@ -989,6 +990,14 @@ int mpc_maxpool2x2_msb(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat1, 
                        mpc_share y, int B, int H, int W, int C, int n_chunks)
 {
     return maxpool_entry(c, x, mat1, mat2, y, B, H, W, C, n_chunks, true);
+}
+
+int mpc_maxpool2x2_signs(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat1, const mpc_relu_material* mat2,
+                         mpc_share y, uint64_t* const s1[2], uint64_t* const s2[2],
+                         int B, int H, int W, int C, int n_chunks, int packed)
+{
+    if (!s1 || !s2 || !s1[0] || !s1[1] || !s2[0] || !s2[1]) return MPC_EINVAL;
+    return maxpool_entry(c, x, mat1, mat2, y, B, H, W, C, n_chunks, packed != 0, s1, s2);
 }
 
 }  // extern "C"

@@ -79,6 +79,52 @@ def matmul_layer(lane: "mpc.Lane", g, M, K, N, x_std, w_std, batch=None):
     return d
 
 
+def conv_backward(lane: "mpc.Lane", g, fwd: dict, pad: int, stride: int, g_std: float = 0.5) -> dict:
+    """Output-gradient shares and the two gradient triples of a conv layer dealt by
+    conv_layer: the input-gradient triple reuses the forward weight mask (so the
+    opened W - B serves again), the filter-gradient triple the forward activation mask."""
+    dev = lane.device
+    A = fwd["a"][0] + fwd["a"][1]; Bm = fwd["b"][0] + fwd["b"][1]
+    KH, KW = Bm.shape[0], Bm.shape[1]
+    G = normal_fixed(g, fwd["c"][0].shape, g_std, dev)
+    Ag = rand_words(g, G.shape, dev); Bg = rand_words(g, G.shape, dev)
+    lane.wait_torch()
+    d = dict(G=G, g=share(g, G))
+    if stride == 1 and KH == KW:
+        Cx = lane.ring_conv2d_grad_x(Ag, Bm, A.shape, pad, stride); lane.sync()
+        d["gx"] = dict(a=share(g, Ag), b=fwd["b"], c=share(g, Cx), f_public=fwd["f_public"])
+    Cw = lane.ring_conv2d_grad_w(A, Bg, KH, KW, pad, stride); lane.sync()
+    d["gw"] = dict(a=fwd["a"], b=share(g, Bg), c=share(g, Cw), e_public=fwd["X"] - A)
+    torch.cuda.synchronize(dev)
+    return d
+
+
+def matmul_backward(lane: "mpc.Lane", g, fwd: dict, g_std: float = 0.5) -> dict:
+    """The same for a dense layer dealt by matmul_layer (2-D or batched):
+    grad_x = g w^T (triple A_g, B^T -> C), grad_w = x^T g (triple A^T, B_g -> C)."""
+    dev = lane.device
+    A = fwd["a"][0] + fwd["a"][1]; Bm = fwd["b"][0] + fwd["b"][1]
+    G = normal_fixed(g, fwd["c"][0].shape, g_std, dev)
+    Ag = rand_words(g, G.shape, dev); Bg = rand_words(g, G.shape, dev)
+    BmT = Bm.transpose(-1, -2).contiguous(); AT = A.transpose(-1, -2).contiguous()
+    lane.wait_torch()
+    Cx = lane.ring_matmul(Ag, BmT); lane.sync()
+    Cw = lane.ring_matmul(AT, Bg); lane.sync()
+    d = dict(G=G, g=share(g, G),
+             gx=dict(a=share(g, Ag), b=fwd["b"], c=share(g, Cx), f_public=fwd["f_public"]),
+             gw=dict(a=fwd["a"], b=share(g, Bg), c=share(g, Cw)))
+    torch.cuda.synchronize(dev)
+    return d
+
+
+def mul_triple(g, n: int, device):
+    """Element-wise multiplication triple on n words."""
+    a = rand_words(g, (n,), device); b = rand_words(g, (n,), device)
+    t = (share(g, a), share(g, b), share(g, a * b))
+    torch.cuda.synchronize(device)
+    return t
+
+
 def relu_material(g, n: int, device, packed: bool = False) -> dict:
     """Secure-ReLU material for n elements.  packed=True draws the AND triples
     directly in the packed layout of mpc_relu_msb (uniform words satisfy the

@@ -47,6 +47,8 @@ EXPORTS = [
     "mpc_relu_pack_triples", "mpc_relu_msb", "mpc_maxpool2x2_msb",
     "mpc_conv2d_grad_x_workspace_bytes", "mpc_conv2d_grad_w_workspace_bytes", "mpc_conv2d_grad_x",
     "mpc_conv2d_grad_w", "mpc_mul_workspace_bytes", "mpc_mul", "mpc_relu_backward",
+    "mpc_ring_conv2d_grad_x", "mpc_ring_conv2d_grad_w",
+    "mpc_maxpool2x2_signs", "mpc_maxpool_backward_workspace_bytes", "mpc_maxpool2x2_backward",
 ]
 
 _lib = None
@@ -90,6 +92,8 @@ def lib():
     L.mpc_conv2d_grad_x.argtypes = L.mpc_conv2d.argtypes
     L.mpc_conv2d_grad_w.argtypes = L.mpc_conv2d.argtypes
     L.mpc_mul_workspace_bytes.argtypes = [c_size_t]; L.mpc_mul_workspace_bytes.restype = c_size_t
+    L.mpc_ring_conv2d_grad_x.argtypes = [c_void_p, _P64, _P64, _P64] + [c_int] * 9
+    L.mpc_ring_conv2d_grad_w.argtypes = [c_void_p, _P64, _P64, _P64] + [c_int] * 9
     L.mpc_mul.argtypes = [c_void_p] + [CShare] * 6 + [c_size_t, c_int]
     L.mpc_relu_backward.argtypes = [c_void_p] + [CShare] * 6 + [c_size_t]
     L.mpc_relu.argtypes = [c_void_p, CShare, POINTER(ReluMaterial), CShare, c_size_t, c_int,
@@ -97,6 +101,11 @@ def lib():
     L.mpc_maxpool2x2.argtypes = [c_void_p, CShare, POINTER(ReluMaterial), POINTER(ReluMaterial), CShare,
                                  c_int, c_int, c_int, c_int, c_int]
     L.mpc_relu_msb.argtypes = L.mpc_relu.argtypes
+    L.mpc_maxpool2x2_signs.argtypes = [c_void_p, CShare, POINTER(ReluMaterial), POINTER(ReluMaterial), CShare,
+                                       POINTER(_P64 * 2), POINTER(_P64 * 2)] + [c_int] * 6
+    L.mpc_maxpool_backward_workspace_bytes.argtypes = [c_int] * 4
+    L.mpc_maxpool_backward_workspace_bytes.restype = c_size_t
+    L.mpc_maxpool2x2_backward.argtypes = [c_void_p] + [CShare] * 10 + [c_int] * 4
     L.mpc_maxpool2x2_msb.argtypes = L.mpc_maxpool2x2.argtypes
     L.mpc_ring_matmul.argtypes = [c_void_p, _P64, _P64, _P64] + [c_int] * 4
     L.mpc_ring_conv2d.argtypes = [c_void_p, _P64, _P64, _P64] + [c_int] * 9
@@ -315,6 +324,16 @@ class Lane:
                                             _share(gx), n))
         return gx
 
+    def maxpool2x2_backward(self, g, s1, s2, t1, t2, x_shape):
+        """Gradient of maxpool2x2 w.r.t. its input; t1 / t2: element-wise triples (a, b, c) on 2*n_out / n_out words."""
+        B, H, W, C = x_shape
+        self.reserve(lib().mpc_maxpool_backward_workspace_bytes(B, H, W, C))
+        gx = tuple(torch.empty(tuple(x_shape), dtype=torch.int64, device=self.device) for _ in range(2))
+        self._check(lib().mpc_maxpool2x2_backward(self._h, _share(g), _share(s1), _share(s2),
+                                                  _share(t1[0]), _share(t1[1]), _share(t1[2]),
+                                                  _share(t2[0]), _share(t2[1]), _share(t2[2]), _share(gx), B, H, W, C))
+        return gx
+
     def truncate(self, z, bits=16):
         self._check(lib().mpc_truncate(self._h, _share(z), z[0].numel(), bits))
         return z
@@ -347,13 +366,21 @@ class Lane:
         self._check(fn(self._h, _share(x), byref(m), _share(y), n, n_chunks, None, None))
         return y
 
-    def maxpool2x2(self, x, mat1, mat2, n_chunks=0, packed=False):
+    def maxpool2x2(self, x, mat1, mat2, n_chunks=0, packed=False, want_signs=False):
+        """2x2 max-pool; want_signs=True also returns the sign shares (s1, s2) the backward pass needs."""
         B, H, W, C = x[0].shape
         n_out = B * (H // 2) * (W // 2) * C
         ws = lib().mpc_maxpool_msb_workspace_bytes if packed else lib().mpc_maxpool_workspace_bytes
         self.reserve(ws(B, H, W, C))
         y = tuple(torch.empty((B, H // 2, W // 2, C), dtype=torch.int64, device=self.device) for _ in range(2))
         m1, m2 = _material(mat1, 2 * n_out, packed), _material(mat2, n_out, packed)
+        if want_signs:
+            s1 = tuple(torch.empty(2 * n_out, dtype=torch.int64, device=self.device) for _ in range(2))
+            s2 = tuple(torch.empty(n_out, dtype=torch.int64, device=self.device) for _ in range(2))
+            p1 = (_P64 * 2)(_p64(s1[0]), _p64(s1[1])); p2 = (_P64 * 2)(_p64(s2[0]), _p64(s2[1]))
+            self._check(lib().mpc_maxpool2x2_signs(self._h, _share(x), byref(m1), byref(m2), _share(y), byref(p1), byref(p2),
+                                                   B, H, W, C, n_chunks, int(packed)))
+            return y, s1, s2
         fn = lib().mpc_maxpool2x2_msb if packed else lib().mpc_maxpool2x2
         self._check(fn(self._h, _share(x), byref(m1), byref(m2), _share(y), B, H, W, C, n_chunks))
         return y
@@ -367,6 +394,20 @@ class Lane:
         Z = torch.empty(shp[:-1] + (N,), dtype=torch.int64, device=self.device)
         self._check(lib().mpc_ring_matmul(self._h, _p64(L), _p64(R), _p64(Z), M, K, N, batch))
         return Z
+
+    def ring_conv2d_grad_x(self, g, w, x_shape, pad, stride=1):
+        B, H, W, Cin = x_shape; KH, KW, _, Cout = w.shape
+        self.reserve(lib().mpc_conv2d_grad_x_workspace_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride))
+        gx = torch.empty(tuple(x_shape), dtype=torch.int64, device=self.device)
+        self._check(lib().mpc_ring_conv2d_grad_x(self._h, _p64(g), _p64(w), _p64(gx), B, H, W, Cin, Cout, KH, KW, pad, stride))
+        return gx
+
+    def ring_conv2d_grad_w(self, x, g, KH, KW, pad, stride):
+        B, H, W, Cin = x.shape; Cout = g.shape[-1]
+        self.reserve(lib().mpc_conv2d_grad_w_workspace_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride))
+        gw = torch.empty((KH, KW, Cin, Cout), dtype=torch.int64, device=self.device)
+        self._check(lib().mpc_ring_conv2d_grad_w(self._h, _p64(x), _p64(g), _p64(gw), B, H, W, Cin, Cout, KH, KW, pad, stride))
+        return gw
 
     def ring_conv2d(self, x, w, pad, stride):
         B, H, W, Cin = x.shape; KH, KW, _, Cout = w.shape

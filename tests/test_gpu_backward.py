@@ -235,6 +235,34 @@ def test_relu_forward_then_backward(mpc, lane, n, packed):
     assert np.array_equal(rec(got), np.where(oracle.to_signed(X) >= 0, G, U64(0)))
 
 
+@pytest.mark.parametrize("shape", [(1, 2, 2, 1), (2, 6, 4, 3), (3, 8, 8, 16), (2, 16, 16, 64)])
+@pytest.mark.parametrize("packed", [False, True])
+def test_maxpool_forward_signs_then_backward(mpc, lane, shape, packed):
+    print(f"maxpool backward {shape} packed={packed}", flush=True)
+    B, H, W, C = shape
+    rng = np.random.default_rng(sum(shape))
+    X = rng.integers(-(1 << 30), 1 << 30, size=shape).astype(np.int64)
+    n_out = B * (H // 2) * (W // 2) * C
+    G = synth.normal_fixed(rng, (B, H // 2, W // 2, C), 0.5)
+    xs, gs = synth.share_additive(rng, X.view(U64)), synth.share_additive(rng, G)
+    m1, m2 = synth.deal_relu_material(rng, 2 * n_out), synth.deal_relu_material(rng, n_out)
+    mul = lambda p, q: p * q
+    t1 = synth.deal_product_triple(rng, (2 * n_out,), (2 * n_out,), mul)
+    t2 = synth.deal_product_triple(rng, (n_out,), (n_out,), mul)
+    want_y, ws1, ws2 = oracle.maxpool2x2(xs, m1, m2, want_signs=True)
+    want_gx = oracle.maxpool2x2_backward(gs, ws1, ws2, t1, t2, shape)
+    d1, d2 = mpc.material_to_device(m1), mpc.material_to_device(m2)
+    if packed:
+        d1, d2 = lane.pack_material(d1), lane.pack_material(d2)
+    y, s1, s2 = lane.maxpool2x2(dev(mpc, xs), d1, d2, packed=packed, want_signs=True)
+    gx = lane.maxpool2x2_backward(dev(mpc, gs), s1, s2, [dev(mpc, t) for t in t1], [dev(mpc, t) for t in t2], shape)
+    lane.sync()
+    assert_shares_equal(host(mpc, lane, y), want_y, "maxpool forward")
+    assert_shares_equal(host(mpc, lane, s1), ws1, "level-1 sign shares")
+    assert_shares_equal(host(mpc, lane, s2), ws2, "level-2 sign shares")
+    assert_shares_equal(host(mpc, lane, gx), want_gx, "maxpool backward")
+
+
 def test_backward_argument_errors(mpc, lane):
     print("backward argument errors", flush=True)
     import torch

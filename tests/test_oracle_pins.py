@@ -259,6 +259,26 @@ def test_relu_backward_passes_gradient_where_input_positive():
     assert np.array_equal(rec(gx), want)
 
 
+
+def test_maxpool_backward_routes_gradient_to_the_window_maximum():
+    """Against autograd of torch's max_pool2d on integers with a unique maximum per window."""
+    rng = np.random.default_rng(77)
+    B, H, W, C = 2, 6, 4, 3
+    Xi = rng.permutation(B * H * W * C).reshape(B, H, W, C).astype(np.int64) - 70       # all values distinct
+    Gi = rng.integers(-1000, 1000, size=(B, H // 2, W // 2, C))
+    xs = synth.share_additive(rng, Xi.view(U64)); gs = synth.share_additive(rng, Gi.astype(np.int64).view(U64))
+    n_out = Gi.size
+    y, s1, s2 = oracle.maxpool2x2(xs, synth.deal_relu_material(rng, 2 * n_out), synth.deal_relu_material(rng, n_out),
+                                  want_signs=True)
+    mul = lambda p, q: p * q
+    t1 = synth.deal_product_triple(rng, (2 * n_out,), (2 * n_out,), mul)
+    t2 = synth.deal_product_triple(rng, (n_out,), (n_out,), mul)
+    gx = oracle.maxpool2x2_backward(gs, s1, s2, t1, t2, Xi.shape)
+    xt = torch.from_numpy(Xi).double().permute(0, 3, 1, 2).requires_grad_()
+    torch.nn.functional.max_pool2d(xt, 2).backward(torch.from_numpy(Gi).double().permute(0, 3, 1, 2))
+    assert np.array_equal(oracle.to_signed(rec(gx)), xt.grad.permute(0, 2, 3, 1).numpy().astype(np.int64))
+    assert np.array_equal(oracle.to_signed(rec(y)), Xi.reshape(B, H // 2, 2, W // 2, 2, C).max(axis=(2, 4)))
+
 # -------------------------------------------------------------------- truncation
 def test_truncation_within_one_lsb_and_wrap_flag():
     rng = np.random.default_rng(9)
