@@ -257,8 +257,9 @@ class Lane:
         self._check(lib().mpc_open(self._h, _share(s), _p64(out), n))
         return out
 
-    def sub(self, x, a):
-        out = (torch.empty_like(x[0]), torch.empty_like(x[1]))
+    def sub(self, x, a, out=None):
+        if out is None:
+            out = (torch.empty_like(x[0]), torch.empty_like(x[1]))
         self._check(lib().mpc_sub(self._h, _share(x), _share(a), _share(out), x[0].numel()))
         return out
 

@@ -129,3 +129,124 @@ def forward_pipelined(lanes, layers, states_per_mb, xs, keep: list, **kw):
             cur[m] = run_layer(lane, L, states_per_mb[m][li], cur[m], **kw)
             keep.extend(run_layer.last_intermediates)
     return cur
+
+
+# ------------------------------------------------------------------ training step
+@dataclass
+class BackwardState:
+    """Gradient triples of one layer for one micro-batch (offline material)."""
+    gx: dict | None               # input gradient: a (mask of g), b (= forward weight mask), c
+    gw: dict                      # weight gradient: a (= forward activation mask), b (mask of g), c
+    relu_t: tuple | None = None   # element-wise triple of the ReLU backward
+    pool_t1: tuple | None = None  # element-wise triples of the max-pool backward (2 n_out / n_out words)
+    pool_t2: tuple | None = None
+
+
+def deal_backward(lane: mpc.Lane, g, layers, states) -> list:
+    """Gradient triples for every layer; the forward masks of weights and activations are
+    reused, so the values opened in the forward pass serve again (Sec. 4.1, backward pass)."""
+    dev = lane.device
+    out = []
+    for li, (L, st) in enumerate(zip(layers, states)):
+        A = st.a[0] + st.a[1]; Bm = st.b[0] + st.b[1]
+        conv = isinstance(L, synth.Conv)
+        gshape = (L.B, L.Ho, L.Wo, L.Cout) if conv else (L.M, L.N)
+        n_out = A.new_empty(gshape).numel()
+        Ag = dealer.rand_words(g, gshape, dev); Bg = dealer.rand_words(g, gshape, dev)
+        lane.wait_torch()
+        if conv:
+            Cw = lane.ring_conv2d_grad_w(A, Bg, L.KH, L.KW, L.pad, L.stride)
+            Cx = lane.ring_conv2d_grad_x(Ag, Bm, A.shape, L.pad, L.stride) if li > 0 else None
+        else:
+            AT = A.transpose(0, 1).contiguous(); BT = Bm.transpose(0, 1).contiguous()
+            lane.wait_torch()
+            Cw = lane.ring_matmul(AT, Bg)
+            Cx = lane.ring_matmul(Ag, BT) if li > 0 else None
+        lane.sync()
+        bs = BackwardState(gx=None if Cx is None else dict(a=dealer.share(g, Ag), b=st.b, c=dealer.share(g, Cx)),
+                           gw=dict(a=st.a, b=dealer.share(g, Bg), c=dealer.share(g, Cw)))
+        if st.relu is not None:
+            bs.relu_t = dealer.mul_triple(g, n_out, dev)
+        if st.pool1 is not None:
+            n_pool = n_out // 4
+            bs.pool_t1 = dealer.mul_triple(g, 2 * n_pool, dev); bs.pool_t2 = dealer.mul_triple(g, n_pool, dev)
+        out.append(bs)
+    torch.cuda.synchronize(dev)
+    return out
+
+
+def forward_train(lane: mpc.Lane, layers, states, x, keep: list, **kw):
+    """Forward pass that keeps what the backward pass reuses: every layer's input
+    shares and the sign shares of its ReLU / max-pool conversions (the tape)."""
+    tape = []
+    for L, st in zip(layers, states):
+        rec = dict(x=x)
+        y_arg = None if st.f_public is not None else st.w
+        if isinstance(L, synth.Conv):
+            xs = (x[0].view(L.B, L.H, L.W, L.Cin), x[1].view(L.B, L.H, L.W, L.Cin))
+            z = lane.conv2d(xs, y_arg, st.a, st.b, st.c, L.pad, L.stride, f_public=st.f_public)
+        else:
+            xs = (x[0].view(L.M, L.K), x[1].view(L.M, L.K))
+            z = lane.beaver_matmul(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public)
+        keep.append(z)
+        if st.relu is not None:
+            z, sb, sa = lane.relu(z, st.relu, want_sign=True, packed=st.packed, **kw)
+            rec["relu_sign"] = sa; keep.extend([z, sb, sa])
+        if st.pool1 is not None:
+            rec["pool_in_shape"] = tuple(z[0].shape)
+            z, s1, s2 = lane.maxpool2x2(z, st.pool1, st.pool2, packed=st.packed, want_signs=True)
+            rec["pool_signs"] = (s1, s2); keep.extend([z, s1, s2])
+        tape.append(rec)
+        x = z
+    return x, tape
+
+
+def backward(lane: mpc.Lane, layers, states, bstates, tape, gout, keep: list):
+    """Backward pass: per layer (last to first) max-pool backward, ReLU backward, then the
+    weight gradient x^T g / Conv-gradient and the input gradient (Sec. 5.3).  Returns the
+    list of weight-gradient shares, first layer first."""
+    g = gout
+    grads = [None] * len(layers)
+    for li in range(len(layers) - 1, -1, -1):
+        L, st, bs, rec = layers[li], states[li], bstates[li], tape[li]
+        conv = isinstance(L, synth.Conv)
+        if st.pool1 is not None:
+            B, H, W, C = rec["pool_in_shape"]
+            gp = (g[0].view(B, H // 2, W // 2, C), g[1].view(B, H // 2, W // 2, C))
+            g = lane.maxpool2x2_backward(gp, rec["pool_signs"][0], rec["pool_signs"][1], bs.pool_t1, bs.pool_t2, (B, H, W, C))
+            keep.append(g)
+        if st.relu is not None:
+            gf = (g[0].reshape(-1), g[1].reshape(-1))
+            g = lane.relu_backward(gf, rec["relu_sign"], *bs.relu_t)
+            keep.append(g)
+        x = rec["x"]
+        if conv:
+            gs = (g[0].view(L.B, L.Ho, L.Wo, L.Cout), g[1].view(L.B, L.Ho, L.Wo, L.Cout))
+            xs = (x[0].view(L.B, L.H, L.W, L.Cin), x[1].view(L.B, L.H, L.W, L.Cin))
+            gw = lane.conv2d_grad_w(xs, gs, bs.gw["a"], bs.gw["b"], bs.gw["c"], L.pad, L.stride)
+            gx = None
+            if bs.gx is not None:
+                gx = lane.conv2d_grad_x(gs, None if st.f_public is not None else st.w, bs.gx["a"], bs.gx["b"], bs.gx["c"],
+                                        L.pad, L.stride, f_public=st.f_public)
+        else:
+            gs = (g[0].view(L.M, L.N), g[1].view(L.M, L.N))
+            xs = (x[0].view(L.M, L.K), x[1].view(L.M, L.K))
+            gw = lane.beaver_matmul(xs, gs, bs.gw["a"], bs.gw["b"], bs.gw["c"], flags=mpc.MPC_TRUNCATE | mpc.MPC_TRANS_X)
+            gx = None
+            if bs.gx is not None:
+                gx = lane.beaver_matmul(gs, None if st.f_public is not None else st.w, bs.gx["a"], bs.gx["b"], bs.gx["c"],
+                                        f_public=st.f_public, flags=mpc.MPC_TRUNCATE | mpc.MPC_TRANS_Y)
+        grads[li] = gw
+        keep.extend([gw, gx])
+        g = gx
+    return grads
+
+
+def sgd_step(lane: mpc.Lane, states, grads, lr_shift: int):
+    """w <- w - 2^-lr_shift * grad_w on shares: a local truncation of the gradient (in
+    place) and a local subtraction.  Weight masks opened ahead of time are opened again."""
+    for st, gw in zip(states, grads):
+        lane.truncate(gw, lr_shift)
+        lane.sub(st.w, (gw[0].view(st.w[0].shape), gw[1].view(st.w[1].shape)), out=st.w)
+        if st.f_public is not None:
+            st.f_public = lane.open(lane.sub(st.w, st.b))

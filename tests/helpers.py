@@ -105,3 +105,83 @@ def oracle_forward(layers, states, x):
         outs.append(z)
         x = z
     return outs
+
+
+# ------------------------------------------------------- whole networks: training
+def deal_backward_host(rng, layers, states):
+    """Gradient triples per layer: forward masks of weights / activations reused."""
+    mul = lambda p, q: p * q
+    out = []
+    for li, (L, st) in enumerate(zip(layers, states)):
+        conv = isinstance(L, synth.Conv)
+        A = rec(st["a"]); Bm = rec(st["b"])
+        gshape = (L.B, L.Ho, L.Wo, L.Cout) if conv else (L.M, L.N)
+        n_out = int(np.prod(gshape))
+        Ag = synth.rand_words(rng, gshape); Bg = synth.rand_words(rng, gshape)
+        if conv:
+            Cw = oracle.ring_conv2d_grad_w(A, Bg, L.KH, L.KW, L.pad, L.stride)
+            Cx = oracle.ring_conv2d_grad_x(Ag, Bm, A.shape, L.pad, L.stride) if li > 0 else None
+        else:
+            Cw = oracle.ring_matmul(np.ascontiguousarray(A.T), Bg)
+            Cx = oracle.ring_matmul(Ag, np.ascontiguousarray(Bm.T)) if li > 0 else None
+        bs = dict(gw=dict(a=st["a"], b=synth.share_additive(rng, Bg), c=synth.share_additive(rng, Cw)),
+                  gx=None if Cx is None else dict(a=synth.share_additive(rng, Ag), b=st["b"], c=synth.share_additive(rng, Cx)),
+                  relu_t=None, pool_t1=None, pool_t2=None)
+        if st["relu"] is not None:
+            bs["relu_t"] = synth.deal_product_triple(rng, (n_out,), (n_out,), mul)
+        if st["pool1"] is not None:
+            n_pool = n_out // 4
+            bs["pool_t1"] = synth.deal_product_triple(rng, (2 * n_pool,), (2 * n_pool,), mul)
+            bs["pool_t2"] = synth.deal_product_triple(rng, (n_pool,), (n_pool,), mul)
+        out.append(bs)
+    return out
+
+
+def oracle_train_step(layers, states, bstates, x, gout):
+    """Oracle forward (keeping inputs and sign shares) and backward; returns the final
+    forward output and the per-layer weight-gradient shares."""
+    tape = []
+    for L, st in zip(layers, states):
+        t = dict(x=x)
+        if isinstance(L, synth.Conv):
+            xs = (x[0].reshape(L.B, L.H, L.W, L.Cin), x[1].reshape(L.B, L.H, L.W, L.Cin))
+            z = oracle.truncate(oracle.beaver_conv2d(xs, st["w"], st["a"], st["b"], st["c"], L.pad, L.stride), 16)
+        else:
+            xs = (x[0].reshape(L.M, L.K), x[1].reshape(L.M, L.K))
+            z = oracle.truncate(oracle.beaver_matmul(xs, st["w"], st["a"], st["b"], st["c"]), 16)
+        if st["relu"] is not None:
+            r = oracle.relu(z, st["relu"]); z = r.y; t["relu_sign"] = r.s_arith
+        if st["pool1"] is not None:
+            t["pool_in_shape"] = z[0].shape
+            z, s1, s2 = oracle.maxpool2x2(z, st["pool1"], st["pool2"], want_signs=True); t["pool_signs"] = (s1, s2)
+        tape.append(t); x = z
+    out = x
+    g = gout
+    grads = [None] * len(layers)
+    tp = lambda pair: tuple(np.ascontiguousarray(p.T) for p in pair)
+    for li in range(len(layers) - 1, -1, -1):
+        L, st, bs, t = layers[li], states[li], bstates[li], tape[li]
+        if st["pool1"] is not None:
+            g = oracle.maxpool2x2_backward(g, t["pool_signs"][0], t["pool_signs"][1], bs["pool_t1"], bs["pool_t2"], t["pool_in_shape"])
+        if st["relu"] is not None:
+            g = oracle.relu_backward((g[0].reshape(-1), g[1].reshape(-1)), t["relu_sign"], *bs["relu_t"])
+        xin = t["x"]
+        if isinstance(L, synth.Conv):
+            gs = (g[0].reshape(L.B, L.Ho, L.Wo, L.Cout), g[1].reshape(L.B, L.Ho, L.Wo, L.Cout))
+            xs = (xin[0].reshape(L.B, L.H, L.W, L.Cin), xin[1].reshape(L.B, L.H, L.W, L.Cin))
+            fw = lambda p, q, L=L: oracle.ring_conv2d_grad_w(p, q, L.KH, L.KW, L.pad, L.stride)
+            gw = oracle.truncate(oracle.beaver_bilinear(fw, xs, gs, bs["gw"]["a"], bs["gw"]["b"], bs["gw"]["c"]), 16)
+            gx = None
+            if bs["gx"] is not None:
+                fx = lambda p, q, L=L: oracle.ring_conv2d_grad_x(p, q, (L.B, L.H, L.W, L.Cin), L.pad, L.stride)
+                gx = oracle.truncate(oracle.beaver_bilinear(fx, gs, st["w"], bs["gx"]["a"], bs["gx"]["b"], bs["gx"]["c"]), 16)
+        else:
+            gs = (g[0].reshape(L.M, L.N), g[1].reshape(L.M, L.N))
+            xs = (xin[0].reshape(L.M, L.K), xin[1].reshape(L.M, L.K))
+            gw = oracle.truncate(oracle.beaver_matmul(tp(xs), gs, tp(bs["gw"]["a"]), bs["gw"]["b"], bs["gw"]["c"]), 16)
+            gx = None
+            if bs["gx"] is not None:
+                gx = oracle.truncate(oracle.beaver_matmul(gs, tp(st["w"]), bs["gx"]["a"], tp(bs["gx"]["b"]), bs["gx"]["c"]), 16)
+        grads[li] = gw
+        g = gx
+    return out, grads

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import deal_network_host, oracle_forward, rec
+from helpers import deal_backward_host, deal_network_host, oracle_forward, oracle_train_step, rec
 from paper_2209_13643_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -106,3 +106,46 @@ def test_pipeline_invariance(mods, dealt, mode):
         check(mpc, outs[m], mb["want"][-1], f"micro-batch {m} logits ({mode})")
     for ln in lanes:
         ln.close()
+
+
+@pytest.mark.parametrize("packed_relu", [False, True], ids=["whole-word-relu", "sign-only-packed-relu"])
+def test_vgg16_training_step_matches_oracle(mods, dealt, packed_relu):
+    """Forward with the tape, backward through max-pool, ReLU, conv and dense layers, then
+    an SGD step: logits, every layer's weight-gradient shares and the updated weight
+    shares against the oracle run of the same step (Sec. 5.3)."""
+    mpc, pipeline = mods
+    layers, mbs = dealt
+    print(f"vgg16 training step, packed_relu={packed_relu}", flush=True)
+    mb = mbs[0]
+    rng = synth.rng_for(4, 12)
+    bhost = deal_backward_host(rng, layers, mb["states"])
+    Gout = synth.normal_fixed(rng, (2, 10), 0.5)
+    gout = synth.share_additive(rng, Gout)
+    want_out, want_grads = oracle_train_step(layers, mb["states"], bhost, mb["x"], gout)
+    check_pair = lambda got, want, what: check(mpc, got, want, what)
+
+    lane = mpc.Lane(0); lane.use_single_queue()
+    dv = lambda p: (mpc.to_device(p[0]), mpc.to_device(p[1]))
+    states = [to_state(mpc, pipeline, st, lane if packed_relu else None) for st in mb["states"]]
+    bstates = []
+    for st, bs in zip(states, bhost):
+        trip = lambda t: None if t is None else tuple(dv(q) for q in t)
+        bstates.append(pipeline.BackwardState(
+            gx=None if bs["gx"] is None else dict(a=dv(bs["gx"]["a"]), b=st.b, c=dv(bs["gx"]["c"])),
+            gw=dict(a=st.a, b=dv(bs["gw"]["b"]), c=dv(bs["gw"]["c"])),
+            relu_t=trip(bs["relu_t"]), pool_t1=trip(bs["pool_t1"]), pool_t2=trip(bs["pool_t2"])))
+    keep = []
+    out, tape = pipeline.forward_train(lane, layers, states, dv(mb["x"]), keep)
+    grads = pipeline.backward(lane, layers, states, bstates, tape, dv(gout), keep)
+    lane.sync()
+    check_pair(out, want_out, "logits")
+    for li, L in enumerate(layers):
+        check_pair(grads[li], want_grads[li], f"weight gradient of layer {li} ({L.name})")
+    # SGD step with learning rate 2^-6
+    pipeline.sgd_step(lane, states, grads, 6)
+    lane.sync()
+    for li, (L, st) in enumerate(zip(layers, mb["states"])):
+        step = oracle.truncate(want_grads[li], 6)
+        want_w = (st["w"][0] - step[0].reshape(st["w"][0].shape), st["w"][1] - step[1].reshape(st["w"][1].shape))
+        check_pair(states[li].w, want_w, f"updated weights of layer {li} ({L.name})")
+    lane.close()
