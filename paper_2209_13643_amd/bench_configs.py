@@ -142,6 +142,45 @@ def bench_backward(idx: int, reps: int = 5):
     return wl.name, rows
 
 
+def bench_training(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = True):
+    """Config 4 as a training step: forward with tape, backward, SGD update, per micro-batch;
+    serial on one lane vs one lane per micro-batch."""
+    wl = synth.config_vgg16_pipeline(micro_batch)
+    layers = wl.layers
+    lanes = [mpc.Lane(0) for _ in range(n_mb)]
+    for ln in lanes:
+        ln.use_single_queue()
+    dev = lanes[0].device
+    g = dealer.gen(synth.BASE_SEED + 70, dev)
+    weights = pipeline.deal_weights(g, layers, dev)
+    states, bstates, xs, gouts = [], [], [], []
+    for m in range(n_mb):
+        states.append(pipeline.deal_microbatch(lanes[m], g, layers, weights, packed_relu=packed_relu))
+        bstates.append(pipeline.deal_backward(lanes[m], g, layers, states[m]))
+        xs.append(dealer.share(g, dealer.normal_fixed(g, (micro_batch, 32, 32, 3), 1.0, dev)))
+        gouts.append(dealer.share(g, dealer.normal_fixed(g, (micro_batch, 10), 0.1, dev)))
+    torch.cuda.synchronize()
+    res = {}
+    for mode in ("serial", "pipelined"):
+        best = None
+        for _ in range(reps + 1):
+            keep = []
+            torch.cuda.synchronize(); t0 = time.perf_counter()
+            for m in range(n_mb):
+                ln = lanes[0] if mode == "serial" else lanes[m]
+                out, tape = pipeline.forward_train(ln, layers, states[m], xs[m], keep)
+                pipeline.backward(ln, layers, states[m], bstates[m], tape, gouts[m], keep)
+            for ln in lanes:
+                ln.sync()
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+            del keep
+        res[mode] = dict(ms=best * 1e3, images_per_s=n_mb * micro_batch / best)
+    for ln in lanes:
+        ln.close()
+    return res
+
+
 def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = False):
     """Config 4: serial (one lane, micro-batches one after the other) vs pipelined (one lane each)."""
     wl = synth.config_vgg16_pipeline(micro_batch)
@@ -224,6 +263,14 @@ def main(argv):
                 if "relu_bwd_ms" in r:
                     line += f"  | relu bwd {r['relu_bwd_ms']:7.3f} ms {r['relu_bwd_elems_per_s'] / 1e9:6.2f} G elems/s"
                 print(line, flush=True)
+        return
+    if argv and argv[0] == "train":
+        for packed in (False, True):
+            p = bench_training(packed_relu=packed)
+            print(f"  VGG16-CIFAR training step (forward + backward), batch 128 = 4 x 32, "
+                  f"{'sign-only packed' if packed else 'whole-word'} ReLU: serial {p['serial']['ms']:.2f} ms "
+                  f"({p['serial']['images_per_s']:.0f} img/s), one lane per micro-batch {p['pipelined']['ms']:.2f} ms "
+                  f"({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)
         return
     which = [int(a) for a in argv] if argv else list(range(len(synth.CONFIGS)))
     for idx in which:
