@@ -244,11 +244,15 @@ class ReluResult:
     s_arith: tuple    # additive shares of the sign bit
 
 
-def relu(x, mat) -> ReluResult:
+ADDERS = {"kogge-stone": 0, "tree": 1}
+
+
+def relu(x, mat, adder="kogge-stone") -> ReluResult:
     """Secure ReLU on additive shares x = (x_0, x_1).
 
     ``mat`` is a mapping with keys r, and_a, and_b, and_c ([12, n] each),
-    rb (uint8), ra, ma, mb, mc; every value a pair (party 0, party 1)."""
+    rb (uint8), ra, ma, mb, mc; every value a pair (party 0, party 1).
+    ``adder``: "kogge-stone", or "tree" for the prefix tree of the listing in Sec. 4.2."""
     x0, px0 = _w(np.ravel(x[0])); x1, px1 = _w(np.ravel(x[1]))
     n = x0.size
     keep = []
@@ -268,12 +272,24 @@ def relu(x, mat) -> ReluResult:
     y0 = np.empty(n, dtype=U64); y1 = np.empty(n, dtype=U64)
     sb0 = np.empty(n, dtype=np.uint8); sb1 = np.empty(n, dtype=np.uint8)
     sa0 = np.empty(n, dtype=U64); sa1 = np.empty(n, dtype=U64)
-    lib().orc_relu(px0, px1, ctypes.byref(m), y0.ctypes.data_as(_P64), y1.ctypes.data_as(_P64),
-                   ctypes.c_size_t(n), sb0.ctypes.data_as(_P8), sb1.ctypes.data_as(_P8),
-                   sa0.ctypes.data_as(_P64), sa1.ctypes.data_as(_P64))
+    lib().orc_relu_adder(px0, px1, ctypes.byref(m), y0.ctypes.data_as(_P64), y1.ctypes.data_as(_P64),
+                         ctypes.c_size_t(n), sb0.ctypes.data_as(_P8), sb1.ctypes.data_as(_P8),
+                         sa0.ctypes.data_as(_P64), sa1.ctypes.data_as(_P64), ctypes.c_int(ADDERS[adder]))
     shp = np.shape(x[0])
     return ReluResult((y0.reshape(shp), y1.reshape(shp)), (sb0.reshape(shp), sb1.reshape(shp)),
                       (sa0.reshape(shp), sa1.reshape(shp)))
+
+
+def tree_carries(U, V, ta, tb, tc):
+    """Carry shares of the listing's prefix tree for one XOR-shared word pair;
+    ta, tb, tc: (12 words of party 0, 12 words of party 1)."""
+    arr = lambda v: np.array(v, dtype=U64)
+    Ua, Va = arr(U), arr(V)
+    t = [arr(q[p]) for q in (ta, tb, tc) for p in range(2)]
+    G = np.zeros(2, dtype=U64)
+    lib().orc_tree_carries(Ua.ctypes.data_as(_P64), Va.ctypes.data_as(_P64), *[q.ctypes.data_as(_P64) for q in t],
+                           G.ctypes.data_as(_P64))
+    return int(G[0]), int(G[1])
 
 
 # ------------------------------------------------------------------ max-pooling
@@ -293,16 +309,16 @@ def pool_level2(x, r1):
     return v, d2
 
 
-def maxpool2x2(x, mat1, mat2, want_signs=False):
+def maxpool2x2(x, mat1, mat2, want_signs=False, adder="kogge-stone"):
     """max over 2x2 windows by max(p,q) = q + ReLU(p-q), two tournament levels.
     mat1 covers 2*n_out elements, mat2 n_out elements.  Returns output shares;
     with want_signs also the additive sign shares of the two conversions (what the
     backward pass keeps)."""
     B, H, W, C = np.shape(x[0])
     d1 = (pool_level1(x[0]), pool_level1(x[1]))
-    c1 = relu(d1, mat1); r1 = c1.y
+    c1 = relu(d1, mat1, adder); r1 = c1.y
     v0, d20 = pool_level2(x[0], r1[0]); v1, d21 = pool_level2(x[1], r1[1])
-    c2 = relu((d20, d21), mat2); r2 = c2.y
+    c2 = relu((d20, d21), mat2, adder); r2 = c2.y
     shp = (B, H // 2, W // 2, C)
     y = ((v0 + r2[0]).reshape(shp), (v1 + r2[1]).reshape(shp))
     return (y, c1.s_arith, c2.s_arith) if want_signs else y

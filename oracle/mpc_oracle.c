@@ -350,6 +350,56 @@ static void ks_adder(const u64 U[2], const u64 V[2], int w,
     }
 }
 
+/* The same carries by the divide-and-conquer prefix tree of the listing in
+ * Sec. 4.2 (level i joins blocks of 2^i bits into blocks of 2^(i+1)); the
+ * constants are not printed there and follow from that description:
+ *   im_i  the top bit of every lower half,  om_i  every upper half,
+ *   spread_i(w) = (w & im_i) * (2 + 4 + ... + 2^(2^i)): that bit copied over its upper half.
+ *   for i = 0 .. 5:   X  = P & om_i
+ *       G <- G ^ (X & spread_i(G))                        (triple 1 + 2i)
+ *       P <- (P & ~om_i) ^ (X & spread_i(P))   unless last (triple 2 + 2i)
+ * Masks and spreads act on each XOR share (no two copied bits meet, so the
+ * multiply adds nothing).  64-bit words only. */
+static void tree_adder(const u64 U[2], const u64 V[2],
+                       const u64 (*ta)[2], const u64 (*tb)[2], const u64 (*tc)[2],
+                       u64 G[2], u64 P0_out[2])
+{
+    u64 P[2] = { U[0] ^ V[0], U[1] ^ V[1] };
+    P0_out[0] = P[0]; P0_out[1] = P[1];
+    beaver_and(U, V, ta[0], tb[0], tc[0], G);
+    for (int i = 0; i < 6; ++i) {
+        const int half = 1 << i, blk = 2 << i;
+        u64 im = 0, om = 0, mu = 0;
+        for (int base = 0; base < 64; base += blk) {
+            im |= (u64)1 << (base + half - 1);
+            om |= ((half == 64 ? ~(u64)0 : (((u64)1 << half) - 1))) << (base + half);
+        }
+        for (int k = 1; k <= half; ++k) mu |= (u64)1 << k;
+        const u64 X[2] = { P[0] & om, P[1] & om };
+        const u64 Gs[2] = { (G[0] & im) * mu, (G[1] & im) * mu };
+        const u64 Ps[2] = { (P[0] & im) * mu, (P[1] & im) * mu };
+        u64 T[2], Pn[2];
+        beaver_and(X, Gs, ta[1 + 2 * i], tb[1 + 2 * i], tc[1 + 2 * i], T);
+        if (i < 5) beaver_and(X, Ps, ta[2 + 2 * i], tb[2 + 2 * i], tc[2 + 2 * i], Pn);
+        G[0] ^= T[0]; G[1] ^= T[1];
+        if (i < 5) { P[0] = (P[0] & ~om) ^ Pn[0]; P[1] = (P[1] & ~om) ^ Pn[1]; }
+    }
+}
+
+/* Exported for tests: the tree's carry shares for one word pair, 12 triple words per party. */
+void orc_tree_carries(const u64* U, const u64* V,
+                      const u64* ta0, const u64* ta1, const u64* tb0, const u64* tb1,
+                      const u64* tc0, const u64* tc1, u64* G)
+{
+    u64 ta[12][2], tb[12][2], tc[12][2], P0[2];
+    for (int t = 0; t < 12; ++t) {
+        ta[t][0] = ta0[t]; ta[t][1] = ta1[t];
+        tb[t][0] = tb0[t]; tb[t][1] = tb1[t];
+        tc[t][0] = tc0[t]; tc[t][1] = tc1[t];
+    }
+    tree_adder(U, V, ta, tb, tc, G, P0);
+}
+
 /* Exported for tests: XOR shares of (U + V) mod 2^w given XOR shares of U, V.
  * Triples: arrays of 2*levels words per party, ta0 = party 0's a words, ... */
 void orc_ks_add(const u64* U, const u64* V, int w,
@@ -394,10 +444,11 @@ typedef struct {
  *        [s]_0 = ra_0 + v - 2 v ra_0,   [s]_1 = ra_1 - 2 v ra_1
  *   5. m = 1 - s:  m_0 = 1 - [s]_0, m_1 = -[s]_1
  *   6. y = x * m by element-wise Alg. 1 (no rescale: m is an integer 0/1)
- * Optional outputs: s_bit[i] (n bytes), s_arith[i] (n words). */
-void orc_relu(const u64* x0, const u64* x1, const orc_relu_material* mt,
-              u64* y0, u64* y1, size_t n,
-              u8* s_bit0, u8* s_bit1, u64* s_ar0, u64* s_ar1)
+ * Optional outputs: s_bit[i] (n bytes), s_arith[i] (n words).
+ * adder: 0 = Kogge-Stone network, 1 = the listing's prefix tree. */
+void orc_relu_adder(const u64* x0, const u64* x1, const orc_relu_material* mt,
+                    u64* y0, u64* y1, size_t n,
+                    u8* s_bit0, u8* s_bit1, u64* s_ar0, u64* s_ar1, int adder)
 {
 #pragma omp parallel for schedule(static)
     for (size_t i = 0; i < n; ++i) {
@@ -412,7 +463,8 @@ void orc_relu(const u64* x0, const u64* x1, const orc_relu_material* mt,
                 tc[t][p] = mt->tc[p][(size_t)t * n + i];
             }
         a2b_distribute(x, r, U, V);
-        ks_adder(U, V, 64, ta, tb, tc, G, P0);
+        if (adder == 1) tree_adder(U, V, ta, tb, tc, G, P0);
+        else            ks_adder(U, V, 64, ta, tb, tc, G, P0);
         /* sum bit 63 = u63 ^ v63 ^ carry into 63 = P0 bit 63 ^ G bit 62 */
         const u64 s[2] = { (P0[0] >> 63) ^ ((G[0] >> 62) & 1),
                            (P0[1] >> 63) ^ ((G[1] >> 62) & 1) };
@@ -435,6 +487,13 @@ void orc_relu(const u64* x0, const u64* x1, const orc_relu_material* mt,
         if (s_ar0) s_ar0[i] = sa[0];
         if (s_ar1) s_ar1[i] = sa[1];
     }
+}
+
+void orc_relu(const u64* x0, const u64* x1, const orc_relu_material* mt,
+              u64* y0, u64* y1, size_t n,
+              u8* s_bit0, u8* s_bit1, u64* s_ar0, u64* s_ar1)
+{
+    orc_relu_adder(x0, x1, mt, y0, y1, n, s_bit0, s_bit1, s_ar0, s_ar1, 0);
 }
 
 /* B2A step alone, scalar, for exhaustive tests. */

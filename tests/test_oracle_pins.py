@@ -396,6 +396,53 @@ def test_listing_tree_on_shares_with_beaver_and():
         assert (U ^ V ^ ((carries << 1) & (MOD - 1))) == (U + V) % MOD
 
 
+def test_tree_adder_on_shares_equals_the_listing_transcription():
+    """The share-level tree of the oracle's ReLU against the independent python
+    transcription of the listing, gate by gate with the same triples: identical
+    carry shares for both parties."""
+    rng = np.random.default_rng(17)
+    M64 = MOD - 1
+    for _ in range(50):
+        U, V = int(rng.integers(0, 1 << 64, dtype=U64)), int(rng.integers(0, 1 << 64, dtype=U64))
+        u0, v0 = int(rng.integers(0, 1 << 64, dtype=U64)), int(rng.integers(0, 1 << 64, dtype=U64))
+        a, b, c = _adder_triples(rng, 64)
+        got = oracle.tree_carries((u0, U ^ u0), (v0, V ^ v0), a, b, c)
+        # the transcription runs on pairs of shares; its gates take the triples in order 0, 1, 2, ...
+        # but it evaluates the dead P update of the last level too: give that gate a throw-away triple
+        order = iter(list(range(12)) + [None])
+        def and_fn(p, q):
+            t = next(order)
+            if t is None:
+                return (0, 0)
+            o = oracle.beaver_and(p, q, (a[0][t], a[1][t]), (b[0][t], b[1][t]), (c[0][t], c[1][t]))
+            return (int(o[0]), int(o[1]))
+
+        class Pair(tuple):        # share pairs under the public-constant operations the tree uses
+            def __and__(self, m): return Pair((self[0] & m, self[1] & m))
+            def __xor__(self, o): return Pair((self[0] ^ o[0], self[1] ^ o[1])) if isinstance(o, tuple) else Pair((self[0] ^ o, self[1]))
+            def __mul__(self, m): return Pair(((self[0] * m) & M64, (self[1] * m) & M64))
+        want = oracle.spk_tree_carries(Pair((u0, U ^ u0)), Pair((v0, V ^ v0)), lambda p, q: Pair(and_fn(p, q)))
+        assert got == (want[0], want[1])
+        assert ((got[0] ^ got[1]) << 1) & M64 == (U ^ V) ^ ((U + V) & M64)
+
+
+def test_relu_with_the_listing_tree():
+    """Same reconstructed sign as with the Kogge-Stone network from different sign-bit
+    shares; everything after the B2A opening depends on the opened value only, so the
+    arithmetic sign shares and the outputs are the same words."""
+    rng = np.random.default_rng(19)
+    vals = np.concatenate([np.arange(-2048, 2049), rng.integers(-(1 << 62), 1 << 62, size=2000)]).astype(np.int64)
+    X = vals.view(U64)
+    xs = synth.share_additive(rng, X)
+    mat = synth.deal_relu_material(rng, X.size)
+    ks, tree = oracle.relu(xs, mat), oracle.relu(xs, mat, adder="tree")
+    assert np.array_equal(rec(tree.y), np.maximum(vals, 0).view(U64))
+    assert np.array_equal(tree.s_bit[0] ^ tree.s_bit[1], (vals < 0).astype(np.uint8))
+    assert np.array_equal(rec(tree.s_arith), (vals < 0).astype(U64))
+    assert np.array_equal(tree.y[0], ks.y[0]) and np.array_equal(tree.s_arith[1], ks.s_arith[1])
+    assert not np.array_equal(tree.s_bit[0], ks.s_bit[0])
+
+
 # --------------------------------------------------------------------------- B2A
 def test_b2a_exhaustive():
     rng = np.random.default_rng(17)
