@@ -100,6 +100,17 @@ int mpc_ctx_set_profiling(mpc_ctx* ctx, int enable);
 int mpc_ctx_profile(mpc_ctx* ctx, int which, double* total_ms, int* count);
 int mpc_ctx_profile_reset(mpc_ctx* ctx);
 
+/* Carry network of the whole-word secure ReLU (mpc_relu, mpc_maxpool2x2):
+ * MPC_ADDER_KOGGE_STONE (default), or MPC_ADDER_TREE, the divide-and-conquer
+ * prefix tree of the listing in Sec. 4.2 (level i joins blocks of 2^i bits:
+ * the upper half of each 2^(i+1)-bit block is combined with the top bit of
+ * its lower half, copied over the upper half by an integer multiply).  Same
+ * rounds, triples (1 + 6 + 5 word ANDs) and exchanged words; the sign-bit
+ * shares differ between the two, every output after the B2A opening does not.
+ * mpc_relu_msb always evaluates the pruned Kogge-Stone chain. */
+enum { MPC_ADDER_KOGGE_STONE = 0, MPC_ADDER_TREE = 1 };
+int mpc_ctx_set_adder(mpc_ctx* ctx, int adder);
+
 int mpc_last_hip_error(const mpc_ctx* ctx);
 const char* mpc_strerror(int code);
 

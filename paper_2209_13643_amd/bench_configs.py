@@ -246,6 +246,16 @@ def sweep_tiles(n: int = 2097152, reps: int = 10):
                 print(f"  {'sign-only packed' if packed else 'whole-word':16s} {mode:30s} tiles={tiles:2d}: "
                       f"{dt * 1e3:7.3f} ms  {n / dt / 1e9:5.2f} G elems/s", flush=True)
             lane.close()
+    # the listing's prefix tree as the carry network (same rounds and bytes as Kogge-Stone)
+    lane = mpc.Lane(0); lane.use_single_queue(); lane.set_adder("tree")
+    for _ in range(3):
+        lane.relu(x, mats[False], n_chunks=2, out=y)
+    lane.sync(); t0 = time.perf_counter()
+    for _ in range(reps):
+        lane.relu(x, mats[False], n_chunks=2, out=y)
+    lane.sync(); dt = (time.perf_counter() - t0) / reps
+    print(f"  {'whole-word, tree':16s} {'one queue (chunk-major)':30s} tiles= 2: {dt * 1e3:7.3f} ms  {n / dt / 1e9:5.2f} G elems/s", flush=True)
+    lane.close()
 
 
 def main(argv):

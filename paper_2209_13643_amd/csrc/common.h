@@ -27,6 +27,7 @@ struct mpc_ctx {
     u8* ws;                  // caller-owned workspace
     size_t ws_bytes;
     int last_hip;
+    int adder;               // carry network of mpc_relu / mpc_maxpool2x2: MPC_ADDER_*
     bool profiling;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> prof[3];   // timing event pairs per region kind
 };

@@ -94,6 +94,13 @@ int mpc_ctx_wait(mpc_ctx* c, mpc_ctx* after)
     return MPC_OK;
 }
 
+int mpc_ctx_set_adder(mpc_ctx* c, int adder)
+{
+    if (!c || (adder != MPC_ADDER_KOGGE_STONE && adder != MPC_ADDER_TREE)) return MPC_EINVAL;
+    c->adder = adder;
+    return MPC_OK;
+}
+
 int mpc_ctx_set_profiling(mpc_ctx* c, int enable)
 {
     if (!c) return MPC_EINVAL;

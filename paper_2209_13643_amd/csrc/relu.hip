@@ -139,15 +139,37 @@ __device__ __forceinline__ void b_first(const ReluParty& p, size_t lo, size_t hi
     }
 }
 
+// ---- adder topologies -----------------------------------------------------------
+// TOPO 0: Kogge-Stone, level l combines every position p with p - 2^l.
+// TOPO 1: the prefix tree of the listing in Sec. 4.2, level l joins blocks of
+// 2^l bits: the upper half of each 2^(l+1)-bit block (om) combines with the top
+// bit of its lower half (im), copied over the upper half by a multiply (mu).
+constexpr u64 tree_im(int l) { u64 m = 0; for (int b = 0; b < 64; b += 2 << l) m |= (u64)1 << (b + (1 << l) - 1); return m; }
+constexpr u64 tree_om(int l)
+{
+    const int half = 1 << l; u64 m = 0;
+    for (int b = 0; b < 64; b += 2 * half) m |= (half == 64 ? ~(u64)0 : (((u64)1 << half) - 1)) << (b + half);
+    return m;
+}
+constexpr u64 tree_mu(int l) { u64 m = 0; for (int k = 1; k <= (1 << l); ++k) m |= (u64)1 << k; return m; }
+// left operand of a level's ANDs, from P
+template <int TOPO, int L> __device__ __forceinline__ u64 op_x(u64 P) { if constexpr (TOPO) return P & tree_om(L); else return P; }
+// right operand, from G (first AND) or P (second AND)
+template <int TOPO, int L> __device__ __forceinline__ u64 op_y(u64 w)
+{
+    if constexpr (TOPO) return (w & tree_im(L)) * tree_mu(L); else return w << (1 << L);
+}
+// the part of P a level leaves untouched
+template <int TOPO, int L> __device__ __forceinline__ u64 keep_p(u64 P) { if constexpr (TOPO) return P & ~tree_om(L); else return 0; }
+
 // ---- K_level ------------------------------------------------------------------
 // LEVEL 0 finishes G = U & V (triple 0, own masked words re-read from the send
 // buffer); LEVEL l > 0 finishes the two ANDs of level l-1 from the carried
 // (G, P).  Then masks the operands of level LEVEL.
-template <int PARTY, int LEVEL, int V>
+template <int PARTY, int LEVEL, int V, int TOPO>
 __device__ __forceinline__ void b_level(const ReluParty& p, size_t lo, size_t hi)
 {
     const size_t n = p.n;
-    constexpr int sh = 1 << LEVEL;
     FOR_ELEMS(V) {
         Pack<V> G, P;
         if constexpr (LEVEL == 0) {
@@ -159,8 +181,8 @@ __device__ __forceinline__ void b_level(const ReluParty& p, size_t lo, size_t hi
             for (int k = 0; k < V; ++k)
                 G.v[k] = and_finish<PARTY>(sd.v[k] ^ rd.v[k], sg.v[k] ^ rg.v[k], a.v[k], b.v[k], c.v[k]);
         } else {
-            constexpr int psh = 1 << (LEVEL - 1);
-            constexpr int t1 = 1 + 2 * (LEVEL - 1), t2 = 2 + 2 * (LEVEL - 1);
+            constexpr int q = LEVEL - 1;
+            constexpr int t1 = 1 + 2 * q, t2 = 2 + 2 * q;
             const Pack<V> Go = Pack<V>::ld(p.G, i), Po = Pack<V>::ld(p.P, i);
             const Pack<V> rd1 = Pack<V>::ld(p.recv, i), rg1 = Pack<V>::ld(p.recv + n, i);
             const Pack<V> rd2 = Pack<V>::ld(p.recv + 2 * n, i), rg2 = Pack<V>::ld(p.recv + 3 * n, i);
@@ -171,25 +193,26 @@ __device__ __forceinline__ void b_level(const ReluParty& p, size_t lo, size_t hi
 #pragma unroll
             for (int k = 0; k < V; ++k) {
                 // own masked words are recomputed from the carried state
-                const u64 d1 = (Po.v[k] ^ a1.v[k]) ^ rd1.v[k];
-                const u64 g1 = ((Go.v[k] << psh) ^ b1.v[k]) ^ rg1.v[k];
-                const u64 d2 = (Po.v[k] ^ a2.v[k]) ^ rd2.v[k];
-                const u64 g2 = ((Po.v[k] << psh) ^ b2.v[k]) ^ rg2.v[k];
+                const u64 X = op_x<TOPO, q>(Po.v[k]);
+                const u64 d1 = (X ^ a1.v[k]) ^ rd1.v[k];
+                const u64 g1 = (op_y<TOPO, q>(Go.v[k]) ^ b1.v[k]) ^ rg1.v[k];
+                const u64 d2 = (X ^ a2.v[k]) ^ rd2.v[k];
+                const u64 g2 = (op_y<TOPO, q>(Po.v[k]) ^ b2.v[k]) ^ rg2.v[k];
                 G.v[k] = Go.v[k] ^ and_finish<PARTY>(d1, g1, a1.v[k], b1.v[k], c1.v[k]);
-                P.v[k] = and_finish<PARTY>(d2, g2, a2.v[k], b2.v[k], c2.v[k]);
+                P.v[k] = keep_p<TOPO, q>(Po.v[k]) ^ and_finish<PARTY>(d2, g2, a2.v[k], b2.v[k], c2.v[k]);
             }
         }
         constexpr int u1 = 1 + 2 * LEVEL, u2 = 2 + 2 * LEVEL;
         const Pack<V> na1 = Pack<V>::ld(p.ta + u1 * n, i), nb1 = Pack<V>::ld(p.tb + u1 * n, i);
         Pack<V> d1, g1;
 #pragma unroll
-        for (int k = 0; k < V; ++k) { d1.v[k] = P.v[k] ^ na1.v[k]; g1.v[k] = (G.v[k] << sh) ^ nb1.v[k]; }
+        for (int k = 0; k < V; ++k) { d1.v[k] = op_x<TOPO, LEVEL>(P.v[k]) ^ na1.v[k]; g1.v[k] = op_y<TOPO, LEVEL>(G.v[k]) ^ nb1.v[k]; }
         d1.st(p.send, i); g1.st(p.send + n, i);
         if constexpr (LEVEL < 5) {
             const Pack<V> na2 = Pack<V>::ld(p.ta + u2 * n, i), nb2 = Pack<V>::ld(p.tb + u2 * n, i);
             Pack<V> d2, g2;
 #pragma unroll
-            for (int k = 0; k < V; ++k) { d2.v[k] = P.v[k] ^ na2.v[k]; g2.v[k] = (P.v[k] << sh) ^ nb2.v[k]; }
+            for (int k = 0; k < V; ++k) { d2.v[k] = op_x<TOPO, LEVEL>(P.v[k]) ^ na2.v[k]; g2.v[k] = op_y<TOPO, LEVEL>(P.v[k]) ^ nb2.v[k]; }
             d2.st(p.send + 2 * n, i); g2.st(p.send + 3 * n, i);
         }
         G.st(p.G, i); P.st(p.P, i);
@@ -197,11 +220,11 @@ __device__ __forceinline__ void b_level(const ReluParty& p, size_t lo, size_t hi
 }
 
 // ---- K_sign -------------------------------------------------------------------
-template <int PARTY, int V>
+template <int PARTY, int V, int TOPO>
 __device__ __forceinline__ void b_sign(const ReluParty& p, size_t lo, size_t hi)
 {
     const size_t n = p.n;
-    constexpr int t1 = 11, psh = 32;
+    constexpr int t1 = 11;
     FOR_ELEMS(V) {
         const Pack<V> Go = Pack<V>::ld(p.G, i), Po = Pack<V>::ld(p.P, i);
         const Pack<V> rd1 = Pack<V>::ld(p.recv, i), rg1 = Pack<V>::ld(p.recv + n, i);
@@ -211,8 +234,8 @@ __device__ __forceinline__ void b_sign(const ReluParty& p, size_t lo, size_t hi)
         ld_bytes<V>(p.p63, i, top); ld_bytes<V>(p.rb, i, rb);
 #pragma unroll
         for (int k = 0; k < V; ++k) {
-            const u64 d1 = (Po.v[k] ^ a1.v[k]) ^ rd1.v[k];
-            const u64 g1 = ((Go.v[k] << psh) ^ b1.v[k]) ^ rg1.v[k];
+            const u64 d1 = (op_x<TOPO, 5>(Po.v[k]) ^ a1.v[k]) ^ rd1.v[k];
+            const u64 g1 = (op_y<TOPO, 5>(Go.v[k]) ^ b1.v[k]) ^ rg1.v[k];
             const u64 G = Go.v[k] ^ and_finish<PARTY>(d1, g1, a1.v[k], b1.v[k], c1.v[k]);
             // bit 63 of the sum = bit 63 of U^V xor the carry out of bits [0..62]
             sb[k] = (u8)(top[k] ^ (u8)((G >> 62) & 1));
@@ -538,45 +561,49 @@ enum Stage { ST_FIRST = 0, ST_LEVEL0 = 1, ST_SIGN = 7, ST_B2A = 8, ST_SELECT = 9
 
 // One launch runs a protocol stage for both parties (blockIdx.y = party) or,
 // when the parties live on different streams, for party `only` alone.
-template <int STAGE, int PARTY, int V>
+template <int STAGE, int PARTY, int V, int TOPO>
 __device__ __forceinline__ void stage_body(const ReluParty& p, size_t lo, size_t hi)
 {
     if constexpr (STAGE == 0) b_first<PARTY, V>(p, lo, hi);
-    else if constexpr (STAGE >= 1 && STAGE <= 6) b_level<PARTY, STAGE - 1, V>(p, lo, hi);
-    else if constexpr (STAGE == 7) b_sign<PARTY, V>(p, lo, hi);
+    else if constexpr (STAGE >= 1 && STAGE <= 6) b_level<PARTY, STAGE - 1, V, TOPO>(p, lo, hi);
+    else if constexpr (STAGE == 7) b_sign<PARTY, V, TOPO>(p, lo, hi);
     else if constexpr (STAGE == 8) b_b2a<PARTY, V>(p, lo, hi);
     else b_select<PARTY, V>(p, lo, hi);
 }
 
-template <int STAGE, int V>
+template <int STAGE, int V, int TOPO>
 __global__ __launch_bounds__(kThreads) void k_relu_stage(ReluParty p0, ReluParty p1, int only, size_t lo, size_t hi)
 {
     const int party = only >= 0 ? only : (int)blockIdx.y;
-    if (party == 0) stage_body<STAGE, 0, V>(p0, lo, hi);
-    else            stage_body<STAGE, 1, V>(p1, lo, hi);
+    if (party == 0) stage_body<STAGE, 0, V, TOPO>(p0, lo, hi);
+    else            stage_body<STAGE, 1, V, TOPO>(p1, lo, hi);
 }
 
 template <int STAGE, int V>
-void launch_stage_t(hipStream_t st, const ReluParty& p0, const ReluParty& p1, int only, size_t lo, size_t hi)
+void launch_stage_t(hipStream_t st, const ReluParty& p0, const ReluParty& p1, int only, size_t lo, size_t hi, int topo)
 {
     const dim3 grid(grid_for((hi - lo + V - 1) / V), only >= 0 ? 1 : 2), block(kThreads);
-    hipLaunchKernelGGL((k_relu_stage<STAGE, V>), grid, block, 0, st, p0, p1, only, lo, hi);
+    // only the carry-network stages depend on the topology
+    if (topo && STAGE >= 1 && STAGE <= 7)
+        hipLaunchKernelGGL((k_relu_stage<STAGE, V, (STAGE >= 1 && STAGE <= 7) ? 1 : 0>), grid, block, 0, st, p0, p1, only, lo, hi);
+    else
+        hipLaunchKernelGGL((k_relu_stage<STAGE, V, 0>), grid, block, 0, st, p0, p1, only, lo, hi);
 }
 
 template <int V>
-void launch_stage(int stage, hipStream_t st, const ReluParty& p0, const ReluParty& p1, int only, size_t lo, size_t hi)
+void launch_stage(int stage, hipStream_t st, const ReluParty& p0, const ReluParty& p1, int only, size_t lo, size_t hi, int topo)
 {
     switch (stage) {
-    case 0: launch_stage_t<0, V>(st, p0, p1, only, lo, hi); break;
-    case 1: launch_stage_t<1, V>(st, p0, p1, only, lo, hi); break;
-    case 2: launch_stage_t<2, V>(st, p0, p1, only, lo, hi); break;
-    case 3: launch_stage_t<3, V>(st, p0, p1, only, lo, hi); break;
-    case 4: launch_stage_t<4, V>(st, p0, p1, only, lo, hi); break;
-    case 5: launch_stage_t<5, V>(st, p0, p1, only, lo, hi); break;
-    case 6: launch_stage_t<6, V>(st, p0, p1, only, lo, hi); break;
-    case 7: launch_stage_t<7, V>(st, p0, p1, only, lo, hi); break;
-    case 8: launch_stage_t<8, V>(st, p0, p1, only, lo, hi); break;
-    case 9: launch_stage_t<9, V>(st, p0, p1, only, lo, hi); break;
+    case 0: launch_stage_t<0, V>(st, p0, p1, only, lo, hi, topo); break;
+    case 1: launch_stage_t<1, V>(st, p0, p1, only, lo, hi, topo); break;
+    case 2: launch_stage_t<2, V>(st, p0, p1, only, lo, hi, topo); break;
+    case 3: launch_stage_t<3, V>(st, p0, p1, only, lo, hi, topo); break;
+    case 4: launch_stage_t<4, V>(st, p0, p1, only, lo, hi, topo); break;
+    case 5: launch_stage_t<5, V>(st, p0, p1, only, lo, hi, topo); break;
+    case 6: launch_stage_t<6, V>(st, p0, p1, only, lo, hi, topo); break;
+    case 7: launch_stage_t<7, V>(st, p0, p1, only, lo, hi, topo); break;
+    case 8: launch_stage_t<8, V>(st, p0, p1, only, lo, hi, topo); break;
+    case 9: launch_stage_t<9, V>(st, p0, p1, only, lo, hi, topo); break;
     default: break;
     }
 }
@@ -706,9 +733,9 @@ int relu_run(mpc_ctx* c, ReluParty (&pp)[2], size_t n, int n_chunks, const MsbGe
             else if (vec) launch_msb_stage<2>(stage, st, pp[0], pp[1], *geom, only, l, h);
             else          launch_msb_stage<1>(stage, st, pp[0], pp[1], *geom, only, l, h);
         } else {
-            if (vec4)     launch_stage<4>(stage, st, pp[0], pp[1], only, l, h);
-            else if (vec) launch_stage<2>(stage, st, pp[0], pp[1], only, l, h);
-            else          launch_stage<1>(stage, st, pp[0], pp[1], only, l, h);
+            if (vec4)     launch_stage<4>(stage, st, pp[0], pp[1], only, l, h, c->adder);
+            else if (vec) launch_stage<2>(stage, st, pp[0], pp[1], only, l, h, c->adder);
+            else          launch_stage<1>(stage, st, pp[0], pp[1], only, l, h, c->adder);
         }
         MPC_HIP(c, hipGetLastError());
         return MPC_OK;

@@ -49,6 +49,7 @@ EXPORTS = [
     "mpc_conv2d_grad_w", "mpc_mul_workspace_bytes", "mpc_mul", "mpc_relu_backward",
     "mpc_ring_conv2d_grad_x", "mpc_ring_conv2d_grad_w",
     "mpc_maxpool2x2_signs", "mpc_maxpool_backward_workspace_bytes", "mpc_maxpool2x2_backward",
+    "mpc_ctx_set_adder",
 ]
 
 _lib = None
@@ -64,6 +65,7 @@ def lib():
     L = ctypes.CDLL(LIB_PATH)
     L.mpc_ctx_create.argtypes = [POINTER(c_void_p), c_int, c_int]
     L.mpc_ctx_destroy.argtypes = [c_void_p]
+    L.mpc_ctx_set_adder.argtypes = [c_void_p, c_int]
     L.mpc_ctx_set_streams.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
     L.mpc_ctx_stream.argtypes = [c_void_p, c_int]; L.mpc_ctx_stream.restype = c_void_p
     L.mpc_ctx_set_workspace.argtypes = [c_void_p, c_void_p, c_size_t]
@@ -228,6 +230,10 @@ class Lane:
         cur = torch.cuda.current_stream(self.device)
         for s in {self.stream(0), self.stream(1), self.stream(2)}:
             torch.cuda.ExternalStream(s, device=self.device).wait_stream(cur)
+
+    def set_adder(self, name: str):
+        """Carry network of relu / maxpool2x2: "kogge-stone" (default) or "tree" (the listing of Sec. 4.2)."""
+        self._check(lib().mpc_ctx_set_adder(self._h, {"kogge-stone": 0, "tree": 1}[name]))
 
     def use_single_queue(self):
         """Issue both parties and the wire on party 0's stream (one in-order queue)."""

@@ -192,6 +192,45 @@ def test_relu(mpc, lane, n, n_chunks):
     assert np.array_equal(rec(got).view(np.int64), np.maximum(X.view(np.int64), 0))
 
 
+@pytest.mark.parametrize("n", [1, 2, 63, 1000, 4097, 70000])
+def test_relu_with_the_listing_tree(mpc, lane, n):
+    """The prefix tree of the Sec. 4.2 listing as the carry network: its sign-bit shares
+    differ from the Kogge-Stone ones and must equal the oracle's tree."""
+    print(f"relu tree n={n}", flush=True)
+    rng = np.random.default_rng(500 + n)
+    X = rng.integers(-(1 << 62), 1 << 62, size=n).astype(np.int64).view(U64)
+    X[: min(n, 9)] = np.array([0, 1, -1, 1 << 62, -(1 << 63), (1 << 63) - 1, -65536, 65536, 5],
+                              dtype=np.int64).view(U64)[: min(n, 9)]
+    xs = synth.share_additive(rng, X)
+    mat = synth.deal_relu_material(rng, n)
+    want = oracle.relu(xs, mat, adder="tree")
+    lane.set_adder("tree")
+    y, sb, sa = lane.relu(dev(mpc, xs), mpc.material_to_device(mat), n_chunks=2, want_sign=True)
+    lane.sync()
+    lane.set_adder("kogge-stone")
+    assert_shares_equal((mpc.to_host(sb[0]), mpc.to_host(sb[1])), want.s_bit, "sign bit share (tree)")
+    assert_shares_equal((mpc.to_host(sa[0]), mpc.to_host(sa[1])), want.s_arith, "sign arithmetic share (tree)")
+    assert_shares_equal((mpc.to_host(y[0]), mpc.to_host(y[1])), want.y, "relu output (tree)")
+    if n >= 63:
+        assert not np.array_equal(want.s_bit[0], oracle.relu(xs, mat).s_bit[0])
+
+
+def test_maxpool_with_the_listing_tree(mpc, lane):
+    print("maxpool tree", flush=True)
+    B, H, W, C = 2, 6, 4, 3
+    rng = np.random.default_rng(41)
+    X = rng.integers(-(1 << 30), 1 << 30, size=(B, H, W, C)).astype(np.int64)
+    xs = synth.share_additive(rng, X.view(U64))
+    n_out = B * (H // 2) * (W // 2) * C
+    m1, m2 = synth.deal_relu_material(rng, 2 * n_out), synth.deal_relu_material(rng, n_out)
+    lane.set_adder("tree")
+    y = lane.maxpool2x2(dev(mpc, xs), mpc.material_to_device(m1), mpc.material_to_device(m2))
+    got = host(mpc, lane, y)
+    lane.set_adder("kogge-stone")
+    assert_shares_equal(got, oracle.maxpool2x2(xs, m1, m2, adder="tree"), "maxpool (tree)")
+    assert np.array_equal(rec(got).view(np.int64), X.reshape(B, H // 2, 2, W // 2, 2, C).max(axis=(2, 4)))
+
+
 def test_relu_exhaustive_small_magnitude(mpc, lane):
     print("relu exhaustive", flush=True)
     rng = np.random.default_rng(123)
