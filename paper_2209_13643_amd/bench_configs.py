@@ -29,8 +29,8 @@ def layer_macs(L):
     return L.M * L.K * L.N * max(L.batch, 1)
 
 
-def bench_layers(idx: int, reps: int = 5):
-    wl = synth.CONFIGS[idx]()
+def bench_layers(idx: int, reps: int = 5, workload=None):
+    wl = workload if workload is not None else synth.CONFIGS[idx]()
     lane = mpc.Lane(0); lane.use_single_queue()
     dev = lane.device
     g = dealer.gen(synth.BASE_SEED + idx, dev)
@@ -60,7 +60,7 @@ def bench_layers(idx: int, reps: int = 5):
         lane.sync(); lane.set_profiling(False)
         gk, gn = lane.profile(mpc.PROF_GEMM_KERNEL); lin, ln = lane.profile(mpc.PROF_LINEAR)
         macs = layer_macs(L)
-        row = dict(layer=L.name, gemm=shape, call_ms=lin / ln, kernel_ms=gk / gn,
+        row = dict(layer=L.name, gemm=shape, repeat=L.repeat, call_ms=lin / ln, kernel_ms=gk / gn,
                    secure_macs_per_s=macs / (lin / ln * 1e-3), mfma_frac=288 * macs / (gk / gn * 1e-3) / INT8_PEAK)
         if mat:
             rl, rn = lane.profile(mpc.PROF_RELU)
@@ -273,6 +273,25 @@ def main(argv):
                 if "relu_bwd_ms" in r:
                     line += f"  | relu bwd {r['relu_bwd_ms']:7.3f} ms {r['relu_bwd_elems_per_s'] / 1e9:6.2f} G elems/s"
                 print(line, flush=True)
+        return
+    if argv and argv[0] == "paper":
+        # the layer shapes of the models the paper evaluates (Sec. 5.2), forward pass
+        for make in synth.PAPER_MODELS:
+            wl = make()
+            name, rows = bench_layers(wl.index, workload=wl)
+            print(f"== {name}")
+            tot_lin = tot_relu = tot_msb = 0.0
+            for r in rows:
+                line = (f"  {r['layer']:16s} x{r['repeat']:<2d} {r['gemm']:22s} call {r['call_ms']:8.3f} ms "
+                        f"{r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s  mfma {100 * r['mfma_frac']:5.1f}%")
+                tot_lin += r['call_ms'] * r['repeat']
+                if "relu_ms" in r:
+                    line += (f"  | relu {r['relu_n']:9d} el {r['relu_ms']:7.3f} ms hbm {100 * r['hbm_frac']:5.1f}%"
+                             f"  | sign-only {r['msb_ms']:7.3f} ms hbm {100 * r['msb_hbm_frac']:5.1f}%")
+                    tot_relu += r['relu_ms'] * r['repeat']; tot_msb += r['msb_ms'] * r['repeat']
+                print(line, flush=True)
+            print(f"  sum over layers (x multiplicity): linear {tot_lin:.2f} ms, ReLU {tot_relu:.2f} ms whole-word / "
+                  f"{tot_msb:.2f} ms sign-only", flush=True)
         return
     if argv and argv[0] == "train":
         for packed in (False, True):

@@ -98,6 +98,7 @@ class Gemm:
     w_std: float
     batch: int = 1
     relu: bool = False
+    repeat: int = 1       # how many layers of this shape the model has (benchmark tables only)
 
 
 @dataclass
@@ -117,6 +118,7 @@ class Conv:
     w_std: float = 1.0
     relu: bool = True
     pool: bool = False
+    repeat: int = 1
 
     @property
     def Ho(self): return (self.H + 2 * self.pad - self.KH) // self.stride + 1
@@ -188,6 +190,57 @@ def config_vgg16_pipeline(micro_batch: int = 32) -> Workload:
                Gemm("fc3", micro_batch, 512, 10, 1.0, he_std(512))]
     return Workload(4, "vgg16-cifar-inter-batch-pipeline", layers)
 
+
+# ---- the models of the paper's own evaluation (Sec. 5.2), layer shapes only --------------
+def config_paper_transformer(batch: int = 8) -> Workload:
+    # one encoder layer, H = 1024, A = 16, sequence length 512 (the BERT-large configuration)
+    T, H, A, dh = batch * 512, 1024, 16, 64
+    return Workload(5, "paper-transformer-encoder-h1024-a16",
+                    [Gemm("qkv", T, H, 3 * H, 1.0, 0.02),
+                     Gemm("qk^t", 512, dh, 512, 1.0, 1.0, batch=batch * A),
+                     Gemm("av", 512, 512, dh, 1.0, 1.0, batch=batch * A),
+                     Gemm("out", T, H, H, 1.0, 0.02),
+                     Gemm("ffn1", T, H, 4 * H, 1.0, 0.02, relu=True),
+                     Gemm("ffn2", T, 4 * H, H, 1.0, 0.02)])
+
+
+def config_vgg16_imagenet(batch: int = 2) -> Workload:
+    # VGG16 on 224x224x3 inputs: the CIFAR channel plan at ImageNet resolution, 25088-4096-4096-1000 head
+    layers, hw = [], 224
+    for i, (cin, cout, pool) in enumerate(VGG16_CIFAR):
+        layers.append(Conv(f"conv{i + 1}", batch, hw, hw, cin, cout,
+                           x_std=1.0, w_std=he_std(9 * cin), relu=True, pool=pool))
+        if pool:
+            hw //= 2
+    layers += [Gemm("fc1", batch, 512 * 7 * 7, 4096, 1.0, he_std(512 * 49), relu=True),
+               Gemm("fc2", batch, 4096, 4096, 1.0, he_std(4096), relu=True),
+               Gemm("fc3", batch, 4096, 1000, 1.0, he_std(4096))]
+    return Workload(6, "paper-vgg16-imagenet", layers)
+
+
+def config_resnet50_imagenet(batch: int = 2) -> Workload:
+    # ResNet-50 on 224x224x3: every distinct convolution shape with its multiplicity
+    # (no batch-norm, no residual adds, the 3x3 max-pool after conv1 left out: shapes only)
+    def c(name, hw, cin, cout, k, stride, repeat=1, relu=True):
+        return Conv(name, batch, hw, hw, cin, cout, k, k, k // 2, stride, 1.0, he_std(k * k * cin), relu, False, repeat)
+    layers = [c("conv1_7x7s2", 224, 3, 64, 7, 2)]
+    hw, cin = 56, 64
+    for stage, (mid, blocks) in enumerate([(64, 3), (128, 4), (256, 6), (512, 3)], start=2):
+        out = 4 * mid
+        s = 1 if stage == 2 else 2
+        layers += [c(f"s{stage}_first_1x1a", hw, cin, mid, 1, 1),
+                   c(f"s{stage}_first_3x3", hw, mid, mid, 3, s),
+                   c(f"s{stage}_down_1x1", hw, cin, out, 1, s, relu=False)]
+        hw //= s
+        layers += [c(f"s{stage}_1x1b", hw, mid, out, 1, 1, repeat=blocks),
+                   c(f"s{stage}_1x1a", hw, out, mid, 1, 1, repeat=blocks - 1),
+                   c(f"s{stage}_3x3", hw, mid, mid, 3, 1, repeat=blocks - 1)]
+        cin = out
+    layers.append(Gemm("fc", batch, 2048, 1000, 1.0, he_std(2048)))
+    return Workload(7, "paper-resnet50-imagenet", layers)
+
+
+PAPER_MODELS = [config_paper_transformer, config_vgg16_imagenet, config_resnet50_imagenet]
 
 CONFIGS = [config_tiny, config_vgg_block, config_resnet_bottleneck, config_transformer,
            config_vgg16_pipeline]
