@@ -111,6 +111,18 @@ int mpc_ctx_profile_reset(mpc_ctx* ctx);
 enum { MPC_ADDER_KOGGE_STONE = 0, MPC_ADDER_TREE = 1 };
 int mpc_ctx_set_adder(mpc_ctx* ctx, int adder);
 
+/* How the secure ReLU's rounds exchange their masked words.
+ * MPC_EXCHANGE_COPY (default): a copy kernel on the wire stream moves every
+ *   party's send buffer into the other party's receive buffer after each round.
+ * MPC_EXCHANGE_PUT: the kernel that forms the masked words also stores them
+ *   into the peer's receive buffer (what a peer-to-peer store would be between
+ *   two devices); the next round starts when that kernel has ended.  One launch
+ *   per round instead of two and one traversal less per exchanged word.  Takes
+ *   effect on lanes whose three streams are one queue; elsewhere the copy
+ *   kernels are used.  Results are identical. */
+enum { MPC_EXCHANGE_COPY = 0, MPC_EXCHANGE_PUT = 1 };
+int mpc_ctx_set_exchange(mpc_ctx* ctx, int mode);
+
 int mpc_last_hip_error(const mpc_ctx* ctx);
 const char* mpc_strerror(int code);
 

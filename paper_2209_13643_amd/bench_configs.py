@@ -232,10 +232,12 @@ def sweep_tiles(n: int = 2097152, reps: int = 10):
     y = (torch.empty_like(x[0]), torch.empty_like(x[1]))
     torch.cuda.synchronize()
     for packed in (False, True):
-        for mode in ("three streams (Alg. 4 order)", "one queue (chunk-major)"):
+        for mode in ("three streams (Alg. 4 order)", "one queue (chunk-major)", "one queue, remote-store exchange"):
             lane = mpc.Lane(0)
             if mode.startswith("one"):
                 lane.use_single_queue()
+            if "remote-store" in mode:
+                lane.set_exchange("put")
             for tiles in (1, 2, 4, 8, 16, 32):
                 for _ in range(3):
                     lane.relu(x, mats[packed], n_chunks=tiles, out=y, packed=packed)
@@ -246,6 +248,23 @@ def sweep_tiles(n: int = 2097152, reps: int = 10):
                 print(f"  {'sign-only packed' if packed else 'whole-word':16s} {mode:30s} tiles={tiles:2d}: "
                       f"{dt * 1e3:7.3f} ms  {n / dt / 1e9:5.2f} G elems/s", flush=True)
             lane.close()
+    # small inputs: the fixed cost per launch dominates; remote-store exchange halves the launches
+    for packed in (False, True):
+        for ns in (50176, 200704, 802816):
+            line = f"  {'sign-only packed' if packed else 'whole-word':16s} n={ns:7d}:"
+            for ex in ("copy", "put"):
+                lane = mpc.Lane(0); lane.use_single_queue(); lane.set_exchange(ex)
+                xs = (x[0][:ns], x[1][:ns]); ys = (y[0][:ns], y[1][:ns])
+                ms = dealer.relu_material(g, ns, dev, packed=packed)
+                for _ in range(3):
+                    lane.relu(xs, ms, out=ys, packed=packed)
+                lane.sync(); t0 = time.perf_counter()
+                for _ in range(20):
+                    lane.relu(xs, ms, out=ys, packed=packed)
+                lane.sync(); dt = (time.perf_counter() - t0) / 20
+                line += f"  {'copy kernels' if ex == 'copy' else 'remote store'} {dt * 1e3:6.3f} ms"
+                lane.close()
+            print(line, flush=True)
     # the listing's prefix tree as the carry network (same rounds and bytes as Kogge-Stone)
     lane = mpc.Lane(0); lane.use_single_queue(); lane.set_adder("tree")
     for _ in range(3):

@@ -94,6 +94,13 @@ int mpc_ctx_wait(mpc_ctx* c, mpc_ctx* after)
     return MPC_OK;
 }
 
+int mpc_ctx_set_exchange(mpc_ctx* c, int mode)
+{
+    if (!c || (mode != MPC_EXCHANGE_COPY && mode != MPC_EXCHANGE_PUT)) return MPC_EINVAL;
+    c->exchange_put = mode == MPC_EXCHANGE_PUT;
+    return MPC_OK;
+}
+
 int mpc_ctx_set_adder(mpc_ctx* c, int adder)
 {
     if (!c || (adder != MPC_ADDER_KOGGE_STONE && adder != MPC_ADDER_TREE)) return MPC_EINVAL;

@@ -44,6 +44,8 @@ struct ReluParty {
     const u64* recv;   // [4][n] words received from the other party
     u8* sendb; const u8* recvb;    // byte exchange (B2A)
     u64* G; u64* P; u8* p63;       // carried state
+    u64* put; u8* putb; u64* putL; // exchange by remote store: the peer's receive buffers (null: copy kernels)
+    u64* recv_alt;                 // second receive buffer, alternating with recv from stage to stage in that mode
     u64* sendL; const u64* recvL;  // packed levels (mpc_relu_msb): per level a [4][pw] block
     u64* gsel;                     // packed levels: the G bits a level keeps
     u64* y; u8* s_bit; u64* s_arith;
@@ -135,6 +137,7 @@ __device__ __forceinline__ void b_first(const ReluParty& p, size_t lo, size_t hi
             top[k] = (u8)(P.v[k] >> 63);
         }
         d.st(p.send, i); g.st(p.send + n, i); P.st(p.P, i);
+        if (p.put) { d.st(p.put, i); g.st(p.put + n, i); }
         st_bytes<V>(p.p63, i, top);
     }
 }
@@ -208,12 +211,14 @@ __device__ __forceinline__ void b_level(const ReluParty& p, size_t lo, size_t hi
 #pragma unroll
         for (int k = 0; k < V; ++k) { d1.v[k] = op_x<TOPO, LEVEL>(P.v[k]) ^ na1.v[k]; g1.v[k] = op_y<TOPO, LEVEL>(G.v[k]) ^ nb1.v[k]; }
         d1.st(p.send, i); g1.st(p.send + n, i);
+        if (p.put) { d1.st(p.put, i); g1.st(p.put + n, i); }
         if constexpr (LEVEL < 5) {
             const Pack<V> na2 = Pack<V>::ld(p.ta + u2 * n, i), nb2 = Pack<V>::ld(p.tb + u2 * n, i);
             Pack<V> d2, g2;
 #pragma unroll
             for (int k = 0; k < V; ++k) { d2.v[k] = op_x<TOPO, LEVEL>(P.v[k]) ^ na2.v[k]; g2.v[k] = op_y<TOPO, LEVEL>(P.v[k]) ^ nb2.v[k]; }
             d2.st(p.send + 2 * n, i); g2.st(p.send + 3 * n, i);
+            if (p.put) { d2.st(p.put + 2 * n, i); g2.st(p.put + 3 * n, i); }
         }
         G.st(p.G, i); P.st(p.P, i);
     }
@@ -243,6 +248,7 @@ __device__ __forceinline__ void b_sign(const ReluParty& p, size_t lo, size_t hi)
         }
         if (p.s_bit) st_bytes<V>(p.s_bit, i, sb);
         st_bytes<V>(p.sendb, i, mb);
+        if (p.putb) st_bytes<V>(p.putb, i, mb);
     }
 }
 
@@ -267,6 +273,7 @@ __device__ __forceinline__ void b_b2a(const ReluParty& p, size_t lo, size_t hi)
             f.v[k] = m - mb.v[k];
         }
         e.st(p.send, i); f.st(p.send + n, i);
+        if (p.put) { e.st(p.put, i); f.st(p.put + n, i); }
         if (p.s_arith) sa.st(p.s_arith, i);
     }
 }
@@ -417,13 +424,16 @@ __device__ __forceinline__ void b_plevel(const ReluParty& p, const MsbGeom& g, s
         Pack<W> d1, g1;
 #pragma unroll
         for (int k = 0; k < W; ++k) { d1.v[k] = X.v[k] ^ na1.v[k]; g1.v[k] = Y1.v[k] ^ nb1.v[k]; }
+        u64* po = p.putL ? p.putL + g.loff[LEVEL] : nullptr;
         d1.st(so, j); g1.st(so + pl, j);
+        if (po) { d1.st(po, j); g1.st(po + pl, j); }
         if constexpr (LEVEL < 5) {
             const Pack<W> na2 = Pack<W>::ld(p.ta + g.toff[u2], j), nb2 = Pack<W>::ld(p.tb + g.toff[u2], j);
             Pack<W> d2, g2;
 #pragma unroll
             for (int k = 0; k < W; ++k) { d2.v[k] = X.v[k] ^ na2.v[k]; g2.v[k] = Y2.v[k] ^ nb2.v[k]; }
             d2.st(so + 2 * pl, j); g2.st(so + 3 * pl, j);
+            if (po) { d2.st(po + 2 * pl, j); g2.st(po + 3 * pl, j); }
         }
         Gk.st(p.gsel + g.goff[LEVEL], j);
     }
@@ -454,6 +464,7 @@ __device__ __forceinline__ void b_psign(const ReluParty& p, const MsbGeom& g, si
         }
         if (p.s_bit) st_bytes<V>(p.s_bit, i, sb);
         st_bytes<V>(p.sendb, i, mb);
+        if (p.putb) st_bytes<V>(p.putb, i, mb);
     }
 }
 
@@ -525,6 +536,7 @@ struct ReluWs {
     u64 *send[2], *recv[2];     // [4][n]
     u8 *sendb[2], *recvb[2];
     u64 *G[2], *P[2]; u8* p63[2];
+    u64* recv2[2];                          // second receive buffer (exchange by remote store alternates)
     u64 *sendL[2], *recvL[2], *gsel[2];     // packed levels only
     size_t bytes; bool ok;
 };
@@ -534,7 +546,7 @@ ReluWs carve_relu(u8* base, size_t cap, size_t n)
     WsAlloc w(base, cap);
     ReluWs r{};
     for (int i = 0; i < 2; ++i) {
-        r.send[i] = w.take<u64>(4 * n); r.recv[i] = w.take<u64>(4 * n);
+        r.send[i] = w.take<u64>(4 * n); r.recv[i] = w.take<u64>(4 * n); r.recv2[i] = w.take<u64>(4 * n);
         r.sendb[i] = w.take<u8>(n); r.recvb[i] = w.take<u8>(n);
         r.G[i] = w.take<u64>(n); r.P[i] = w.take<u64>(n); r.p63[i] = w.take<u8>(n);
     }
@@ -547,7 +559,7 @@ ReluWs carve_relu_msb(u8* base, size_t cap, size_t n, const MsbGeom& g)
     WsAlloc w(base, cap);
     ReluWs r{};
     for (int i = 0; i < 2; ++i) {
-        r.send[i] = w.take<u64>(2 * n); r.recv[i] = w.take<u64>(2 * n);
+        r.send[i] = w.take<u64>(2 * n); r.recv[i] = w.take<u64>(2 * n); r.recv2[i] = w.take<u64>(2 * n);
         r.sendb[i] = w.take<u8>(n); r.recvb[i] = w.take<u8>(n);
         r.P[i] = w.take<u64>(n); r.p63[i] = w.take<u8>(n);
         r.sendL[i] = w.take<u64>(g.words_level_blocks); r.recvL[i] = w.take<u64>(g.words_level_blocks);
@@ -727,18 +739,21 @@ int relu_run(mpc_ctx* c, ReluParty (&pp)[2], size_t n, int n_chunks, const MsbGe
     hipEvent_t got[kMaxChunks];
 
     // stage `stage` on elements [l, h): both parties in one launch (only = -1) or party `only`
-    auto launch = [&](int stage, hipStream_t st, int only, size_t l, size_t h) -> int {
+    auto launch_with = [&](const ReluParty (&q)[2], int stage, hipStream_t st, int only, size_t l, size_t h) -> int {
         if (geom) {
-            if (vec4)     launch_msb_stage<4>(stage, st, pp[0], pp[1], *geom, only, l, h);
-            else if (vec) launch_msb_stage<2>(stage, st, pp[0], pp[1], *geom, only, l, h);
-            else          launch_msb_stage<1>(stage, st, pp[0], pp[1], *geom, only, l, h);
+            if (vec4)     launch_msb_stage<4>(stage, st, q[0], q[1], *geom, only, l, h);
+            else if (vec) launch_msb_stage<2>(stage, st, q[0], q[1], *geom, only, l, h);
+            else          launch_msb_stage<1>(stage, st, q[0], q[1], *geom, only, l, h);
         } else {
-            if (vec4)     launch_stage<4>(stage, st, pp[0], pp[1], only, l, h, c->adder);
-            else if (vec) launch_stage<2>(stage, st, pp[0], pp[1], only, l, h, c->adder);
-            else          launch_stage<1>(stage, st, pp[0], pp[1], only, l, h, c->adder);
+            if (vec4)     launch_stage<4>(stage, st, q[0], q[1], only, l, h, c->adder);
+            else if (vec) launch_stage<2>(stage, st, q[0], q[1], only, l, h, c->adder);
+            else          launch_stage<1>(stage, st, q[0], q[1], only, l, h, c->adder);
         }
         MPC_HIP(c, hipGetLastError());
         return MPC_OK;
+    };
+    auto launch = [&](int stage, hipStream_t st, int only, size_t l, size_t h) -> int {
+        return launch_with(pp, stage, st, only, l, h);
     };
     // the exchange that follows `stage` (-1: the A2B masks); *sent = false if the stage sends nothing
     auto exchange = [&](int stage, size_t l, size_t h, bool* sent) -> int {
@@ -777,6 +792,22 @@ int relu_run(mpc_ctx* c, ReluParty (&pp)[2], size_t n, int n_chunks, const MsbGe
             if (hi[m] <= lo[m]) continue;
             MPC_TRY(exchange(-1, lo[m], hi[m], &sent));
             for (int stage = 0; stage < ST_COUNT; ++stage) {
+                if (c->exchange_put) {
+                    // Exchange by remote store: the stage kernel writes its masked words into the
+                    // peer's receive buffer as well; the word buffers alternate so that a stage
+                    // never stores where the peer's same stage still reads.
+                    ReluParty q[2] = { pp[0], pp[1] };
+                    for (int i = 0; i < 2; ++i) {
+                        u64* mine[2] = { const_cast<u64*>(pp[i].recv), pp[i].recv_alt };
+                        u64* peer[2] = { const_cast<u64*>(pp[1 - i].recv), pp[1 - i].recv_alt };
+                        q[i].recv = mine[stage & 1];
+                        q[i].put = peer[(stage + 1) & 1];
+                        q[i].putb = const_cast<u8*>(pp[1 - i].recvb);
+                        q[i].putL = const_cast<u64*>(pp[1 - i].recvL);
+                    }
+                    MPC_TRY(launch_with(q, stage, P[0], -1, lo[m], hi[m]));
+                    continue;
+                }
                 MPC_TRY(launch(stage, P[0], -1, lo[m], hi[m]));
                 MPC_TRY(exchange(stage, lo[m], hi[m], &sent));
             }
@@ -826,6 +857,7 @@ void fill_party(ReluParty& p, int i, const u64* x, const mpc_relu_material* m, c
     p.rb = m->rb[i]; p.ra = m->ra.p[i];
     p.ma = m->ma.p[i]; p.mb = m->mb.p[i]; p.mc = m->mc.p[i];
     p.send = w.send[i]; p.recv = w.recv[i]; p.sendb = w.sendb[i]; p.recvb = w.recvb[i];
+    p.put = nullptr; p.putb = nullptr; p.putL = nullptr; p.recv_alt = w.recv2[i];
     p.G = w.G[i]; p.P = w.P[i]; p.p63 = w.p63[i];
     p.sendL = w.sendL[i]; p.recvL = w.recvL[i]; p.gsel = w.gsel[i];
     p.y = y; p.s_bit = s_bit; p.s_arith = s_arith; p.n = n;

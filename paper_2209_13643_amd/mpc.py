@@ -49,7 +49,7 @@ EXPORTS = [
     "mpc_conv2d_grad_w", "mpc_mul_workspace_bytes", "mpc_mul", "mpc_relu_backward",
     "mpc_ring_conv2d_grad_x", "mpc_ring_conv2d_grad_w",
     "mpc_maxpool2x2_signs", "mpc_maxpool_backward_workspace_bytes", "mpc_maxpool2x2_backward",
-    "mpc_ctx_set_adder",
+    "mpc_ctx_set_adder", "mpc_ctx_set_exchange",
 ]
 
 _lib = None
@@ -66,6 +66,7 @@ def lib():
     L.mpc_ctx_create.argtypes = [POINTER(c_void_p), c_int, c_int]
     L.mpc_ctx_destroy.argtypes = [c_void_p]
     L.mpc_ctx_set_adder.argtypes = [c_void_p, c_int]
+    L.mpc_ctx_set_exchange.argtypes = [c_void_p, c_int]
     L.mpc_ctx_set_streams.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
     L.mpc_ctx_stream.argtypes = [c_void_p, c_int]; L.mpc_ctx_stream.restype = c_void_p
     L.mpc_ctx_set_workspace.argtypes = [c_void_p, c_void_p, c_size_t]
@@ -230,6 +231,11 @@ class Lane:
         cur = torch.cuda.current_stream(self.device)
         for s in {self.stream(0), self.stream(1), self.stream(2)}:
             torch.cuda.ExternalStream(s, device=self.device).wait_stream(cur)
+
+    def set_exchange(self, mode: str):
+        """Secure-ReLU exchange: "copy" (copy kernels on the wire stream) or "put" (the producing
+        kernel stores into the peer's receive buffer; single-queue lanes only)."""
+        self._check(lib().mpc_ctx_set_exchange(self._h, {"copy": 0, "put": 1}[mode]))
 
     def set_adder(self, name: str):
         """Carry network of relu / maxpool2x2: "kogge-stone" (default) or "tree" (the listing of Sec. 4.2)."""
