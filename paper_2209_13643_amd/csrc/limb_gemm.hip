@@ -415,13 +415,19 @@ int gemm_ksplit(int M, int N, int batch, int nparty, int total_steps)
                             ((N + (narrow ? 63 : 127)) / (narrow ? 64 : 128)) * batch * nparty;
     // the int32 digit sums of one workgroup stay exact for at most kMaxStepsExact steps
     const int s_exact = (total_steps + kMaxStepsExact - 1) / kMaxStepsExact;
-    int s = 1;
+    int s = s_exact;
     if (tiles < 160 && total_steps >= 8) {
-        s = (int)((256 + tiles - 1) / tiles);
-        if (s > total_steps / 4) s = total_steps / 4;
-        if (s > 32) s = 32;
+        // One workgroup per compute unit at a time: pick the slice count that minimises
+        // (rounds of workgroups over the 256 units) x (steps per slice + fixed cost per
+        // workgroup: pipeline fill, epilogue, its share of the finishing pass).
+        long long best = -1;
+        const int s_max = total_steps / 4 < 32 ? total_steps / 4 : 32;
+        for (int q = s_exact < 1 ? 1 : s_exact; q <= s_max; ++q) {
+            const long long rounds = (tiles * q + 255) / 256;
+            const long long cost = rounds * ((total_steps + q - 1) / q + 6);
+            if (best < 0 || cost < best) { best = cost; s = q; }
+        }
     }
-    if (s < s_exact) s = s_exact;
     if (s <= 1) return 1;
     const int per = (total_steps + s - 1) / s;
     return (total_steps + per - 1) / per;          // no empty slice
