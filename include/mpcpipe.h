@@ -66,7 +66,12 @@ enum {
 
 /* ------------------------------------------------------------------ context */
 
-/* Creates a lane on `device` with its own three non-blocking streams (default
+/* A context ("lane") is used by one host thread at a time; different lanes
+ * may be driven from different threads.  Calls only enqueue work: outputs are
+ * valid after mpc_ctx_sync (or after waiting on the lane's streams), and no
+ * buffer passed to a call may be freed or rewritten before that.
+ *
+ * Creates a lane on `device` with its own three non-blocking streams (default
  * priority).  frac_bits in [0, 62] is the fixed-point scale used by
  * MPC_TRUNCATE.  Host-side allocation only. */
 int mpc_ctx_create(mpc_ctx** out, int device, int frac_bits);

@@ -27,6 +27,7 @@
 // gathers filter taps from NHWC activation planes (implicit im2col); taps
 // that fall into the zero padding read the all-zero row that ends every
 // activation plane.
+#include <atomic>
 #include "common.h"
 
 #include <type_traits>
@@ -379,13 +380,14 @@ template <int WGM, int WGN, bool CONV>
 int launch_cfg(mpc_ctx* c, hipStream_t st, const GemmArgs& g)
 {
     using C = Cfg<WGM, WGN>;
-    static bool attr_set[16] = { false };
+    // once per device and kernel: allow the large dynamic LDS allocation (lanes may live on several host threads)
+    static std::atomic<bool> attr_set[16];
     auto kern = k_limb_gemm<WGM, WGN, CONV>;
     if (c->device < 0 || c->device >= 16) return MPC_EINVAL;
-    if (!attr_set[c->device]) {
+    if (!attr_set[c->device].load(std::memory_order_acquire)) {
         MPC_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
-        attr_set[c->device] = true;
+        attr_set[c->device].store(true, std::memory_order_release);
     }
     dim3 grid((g.M + C::TM - 1) / C::TM, (g.N + C::TN - 1) / C::TN, g.batch * g.nparty * g.ksplit);
     const int pi = prof_begin(c, MPC_PROF_GEMM_KERNEL, st);
