@@ -117,7 +117,7 @@ __device__ __forceinline__ u64 and_finish(u64 d, u64 g, u64 a, u64 b, u64 c)
     for (size_t i = lo + ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * V; i < hi; i += stride_)
 
 // ---- K_first ------------------------------------------------------------------
-template <int PARTY, int V>
+template <int PARTY, int V, bool PUT>
 __device__ __forceinline__ void b_first(const ReluParty& p, size_t lo, size_t hi)
 {
     const size_t n = p.n;
@@ -137,7 +137,7 @@ __device__ __forceinline__ void b_first(const ReluParty& p, size_t lo, size_t hi
             top[k] = (u8)(P.v[k] >> 63);
         }
         d.st(p.send, i); g.st(p.send + n, i); P.st(p.P, i);
-        if (p.put) { d.st(p.put, i); g.st(p.put + n, i); }
+        if constexpr (PUT) { d.st(p.put, i); g.st(p.put + n, i); }
         st_bytes<V>(p.p63, i, top);
     }
 }
@@ -169,7 +169,7 @@ template <int TOPO, int L> __device__ __forceinline__ u64 keep_p(u64 P) { if con
 // LEVEL 0 finishes G = U & V (triple 0, own masked words re-read from the send
 // buffer); LEVEL l > 0 finishes the two ANDs of level l-1 from the carried
 // (G, P).  Then masks the operands of level LEVEL.
-template <int PARTY, int LEVEL, int V, int TOPO>
+template <int PARTY, int LEVEL, int V, int TOPO, bool PUT>
 __device__ __forceinline__ void b_level(const ReluParty& p, size_t lo, size_t hi)
 {
     const size_t n = p.n;
@@ -211,21 +211,21 @@ __device__ __forceinline__ void b_level(const ReluParty& p, size_t lo, size_t hi
 #pragma unroll
         for (int k = 0; k < V; ++k) { d1.v[k] = op_x<TOPO, LEVEL>(P.v[k]) ^ na1.v[k]; g1.v[k] = op_y<TOPO, LEVEL>(G.v[k]) ^ nb1.v[k]; }
         d1.st(p.send, i); g1.st(p.send + n, i);
-        if (p.put) { d1.st(p.put, i); g1.st(p.put + n, i); }
+        if constexpr (PUT) { d1.st(p.put, i); g1.st(p.put + n, i); }
         if constexpr (LEVEL < 5) {
             const Pack<V> na2 = Pack<V>::ld(p.ta + u2 * n, i), nb2 = Pack<V>::ld(p.tb + u2 * n, i);
             Pack<V> d2, g2;
 #pragma unroll
             for (int k = 0; k < V; ++k) { d2.v[k] = op_x<TOPO, LEVEL>(P.v[k]) ^ na2.v[k]; g2.v[k] = op_y<TOPO, LEVEL>(P.v[k]) ^ nb2.v[k]; }
             d2.st(p.send + 2 * n, i); g2.st(p.send + 3 * n, i);
-            if (p.put) { d2.st(p.put + 2 * n, i); g2.st(p.put + 3 * n, i); }
+            if constexpr (PUT) { d2.st(p.put + 2 * n, i); g2.st(p.put + 3 * n, i); }
         }
         G.st(p.G, i); P.st(p.P, i);
     }
 }
 
 // ---- K_sign -------------------------------------------------------------------
-template <int PARTY, int V, int TOPO>
+template <int PARTY, int V, int TOPO, bool PUT>
 __device__ __forceinline__ void b_sign(const ReluParty& p, size_t lo, size_t hi)
 {
     const size_t n = p.n;
@@ -248,12 +248,12 @@ __device__ __forceinline__ void b_sign(const ReluParty& p, size_t lo, size_t hi)
         }
         if (p.s_bit) st_bytes<V>(p.s_bit, i, sb);
         st_bytes<V>(p.sendb, i, mb);
-        if (p.putb) st_bytes<V>(p.putb, i, mb);
+        if constexpr (PUT) st_bytes<V>(p.putb, i, mb);
     }
 }
 
 // ---- K_b2a --------------------------------------------------------------------
-template <int PARTY, int V>
+template <int PARTY, int V, bool PUT>
 __device__ __forceinline__ void b_b2a(const ReluParty& p, size_t lo, size_t hi)
 {
     const size_t n = p.n;
@@ -273,7 +273,7 @@ __device__ __forceinline__ void b_b2a(const ReluParty& p, size_t lo, size_t hi)
             f.v[k] = m - mb.v[k];
         }
         e.st(p.send, i); f.st(p.send + n, i);
-        if (p.put) { e.st(p.put, i); f.st(p.put + n, i); }
+        if constexpr (PUT) { e.st(p.put, i); f.st(p.put + n, i); }
         if (p.s_arith) sa.st(p.s_arith, i);
     }
 }
@@ -370,7 +370,7 @@ template <int V> __device__ __forceinline__ Pack<V> ld_upto(const u64* p, size_t
 
 // Stage 1 + LEVEL of the packed chain: finish the previous round's ANDs for the
 // 2 W input words behind W output words, regroup, and mask this level's operands.
-template <int PARTY, int LEVEL, int W>
+template <int PARTY, int LEVEL, int W, bool PUT>
 __device__ __forceinline__ void b_plevel(const ReluParty& p, const MsbGeom& g, size_t lo, size_t hi)
 {
     constexpr int d = 1 << LEVEL, s = 2 * d;
@@ -424,16 +424,16 @@ __device__ __forceinline__ void b_plevel(const ReluParty& p, const MsbGeom& g, s
         Pack<W> d1, g1;
 #pragma unroll
         for (int k = 0; k < W; ++k) { d1.v[k] = X.v[k] ^ na1.v[k]; g1.v[k] = Y1.v[k] ^ nb1.v[k]; }
-        u64* po = p.putL ? p.putL + g.loff[LEVEL] : nullptr;
+        u64* po = PUT ? p.putL + g.loff[LEVEL] : nullptr;
         d1.st(so, j); g1.st(so + pl, j);
-        if (po) { d1.st(po, j); g1.st(po + pl, j); }
+        if constexpr (PUT) { d1.st(po, j); g1.st(po + pl, j); }
         if constexpr (LEVEL < 5) {
             const Pack<W> na2 = Pack<W>::ld(p.ta + g.toff[u2], j), nb2 = Pack<W>::ld(p.tb + g.toff[u2], j);
             Pack<W> d2, g2;
 #pragma unroll
             for (int k = 0; k < W; ++k) { d2.v[k] = X.v[k] ^ na2.v[k]; g2.v[k] = Y2.v[k] ^ nb2.v[k]; }
             d2.st(so + 2 * pl, j); g2.st(so + 3 * pl, j);
-            if (po) { d2.st(po + 2 * pl, j); g2.st(po + 3 * pl, j); }
+            if constexpr (PUT) { d2.st(po + 2 * pl, j); g2.st(po + 3 * pl, j); }
         }
         Gk.st(p.gsel + g.goff[LEVEL], j);
     }
@@ -441,7 +441,7 @@ __device__ __forceinline__ void b_plevel(const ReluParty& p, const MsbGeom& g, s
 
 // Packed K_sign: finish level 5; element i's carry into bit 63 sits at bit
 // (62 + i) mod 64 of word i / 64.
-template <int PARTY, int V>
+template <int PARTY, int V, bool PUT>
 __device__ __forceinline__ void b_psign(const ReluParty& p, const MsbGeom& g, size_t lo, size_t hi)
 {
     const size_t p5 = g.pw[5];
@@ -464,7 +464,7 @@ __device__ __forceinline__ void b_psign(const ReluParty& p, const MsbGeom& g, si
         }
         if (p.s_bit) st_bytes<V>(p.s_bit, i, sb);
         st_bytes<V>(p.sendb, i, mb);
-        if (p.putb) st_bytes<V>(p.putb, i, mb);
+        if constexpr (PUT) st_bytes<V>(p.putb, i, mb);
     }
 }
 
@@ -546,10 +546,11 @@ ReluWs carve_relu(u8* base, size_t cap, size_t n)
     WsAlloc w(base, cap);
     ReluWs r{};
     for (int i = 0; i < 2; ++i) {
-        r.send[i] = w.take<u64>(4 * n); r.recv[i] = w.take<u64>(4 * n); r.recv2[i] = w.take<u64>(4 * n);
+        r.send[i] = w.take<u64>(4 * n); r.recv[i] = w.take<u64>(4 * n);
         r.sendb[i] = w.take<u8>(n); r.recvb[i] = w.take<u8>(n);
         r.G[i] = w.take<u64>(n); r.P[i] = w.take<u64>(n); r.p63[i] = w.take<u8>(n);
     }
+    for (int i = 0; i < 2; ++i) r.recv2[i] = w.take<u64>(4 * n);      // only touched by the remote-store exchange
     r.bytes = w.off; r.ok = w.ok;
     return r;
 }
@@ -559,12 +560,13 @@ ReluWs carve_relu_msb(u8* base, size_t cap, size_t n, const MsbGeom& g)
     WsAlloc w(base, cap);
     ReluWs r{};
     for (int i = 0; i < 2; ++i) {
-        r.send[i] = w.take<u64>(2 * n); r.recv[i] = w.take<u64>(2 * n); r.recv2[i] = w.take<u64>(2 * n);
+        r.send[i] = w.take<u64>(2 * n); r.recv[i] = w.take<u64>(2 * n);
         r.sendb[i] = w.take<u8>(n); r.recvb[i] = w.take<u8>(n);
         r.P[i] = w.take<u64>(n); r.p63[i] = w.take<u8>(n);
         r.sendL[i] = w.take<u64>(g.words_level_blocks); r.recvL[i] = w.take<u64>(g.words_level_blocks);
         r.gsel[i] = w.take<u64>(g.words_gsel);
     }
+    for (int i = 0; i < 2; ++i) r.recv2[i] = w.take<u64>(2 * n);
     r.bytes = w.off; r.ok = w.ok;
     return r;
 }
@@ -573,33 +575,39 @@ enum Stage { ST_FIRST = 0, ST_LEVEL0 = 1, ST_SIGN = 7, ST_B2A = 8, ST_SELECT = 9
 
 // One launch runs a protocol stage for both parties (blockIdx.y = party) or,
 // when the parties live on different streams, for party `only` alone.
-template <int STAGE, int PARTY, int V, int TOPO>
+template <int STAGE, int PARTY, int V, int TOPO, bool PUT>
 __device__ __forceinline__ void stage_body(const ReluParty& p, size_t lo, size_t hi)
 {
-    if constexpr (STAGE == 0) b_first<PARTY, V>(p, lo, hi);
-    else if constexpr (STAGE >= 1 && STAGE <= 6) b_level<PARTY, STAGE - 1, V, TOPO>(p, lo, hi);
-    else if constexpr (STAGE == 7) b_sign<PARTY, V, TOPO>(p, lo, hi);
-    else if constexpr (STAGE == 8) b_b2a<PARTY, V>(p, lo, hi);
+    if constexpr (STAGE == 0) b_first<PARTY, V, PUT>(p, lo, hi);
+    else if constexpr (STAGE >= 1 && STAGE <= 6) b_level<PARTY, STAGE - 1, V, TOPO, PUT>(p, lo, hi);
+    else if constexpr (STAGE == 7) b_sign<PARTY, V, TOPO, PUT>(p, lo, hi);
+    else if constexpr (STAGE == 8) b_b2a<PARTY, V, PUT>(p, lo, hi);
     else b_select<PARTY, V>(p, lo, hi);
 }
 
-template <int STAGE, int V, int TOPO>
+template <int STAGE, int V, int TOPO, bool PUT>
 __global__ __launch_bounds__(kThreads) void k_relu_stage(ReluParty p0, ReluParty p1, int only, size_t lo, size_t hi)
 {
     const int party = only >= 0 ? only : (int)blockIdx.y;
-    if (party == 0) stage_body<STAGE, 0, V, TOPO>(p0, lo, hi);
-    else            stage_body<STAGE, 1, V, TOPO>(p1, lo, hi);
+    if (party == 0) stage_body<STAGE, 0, V, TOPO, PUT>(p0, lo, hi);
+    else            stage_body<STAGE, 1, V, TOPO, PUT>(p1, lo, hi);
 }
 
 template <int STAGE, int V>
 void launch_stage_t(hipStream_t st, const ReluParty& p0, const ReluParty& p1, int only, size_t lo, size_t hi, int topo)
 {
     const dim3 grid(grid_for((hi - lo + V - 1) / V), only >= 0 ? 1 : 2), block(kThreads);
-    // only the carry-network stages depend on the topology
-    if (topo && STAGE >= 1 && STAGE <= 7)
-        hipLaunchKernelGGL((k_relu_stage<STAGE, V, (STAGE >= 1 && STAGE <= 7) ? 1 : 0>), grid, block, 0, st, p0, p1, only, lo, hi);
-    else
-        hipLaunchKernelGGL((k_relu_stage<STAGE, V, 0>), grid, block, 0, st, p0, p1, only, lo, hi);
+    // only the carry-network stages depend on the topology; the last stage sends nothing
+    constexpr int T1 = (STAGE >= 1 && STAGE <= 7) ? 1 : 0;
+    constexpr bool P1 = STAGE <= 8;
+    const bool put = p0.put != nullptr && P1;
+    if (topo && T1) {
+        if (put) hipLaunchKernelGGL((k_relu_stage<STAGE, V, T1, P1>), grid, block, 0, st, p0, p1, only, lo, hi);
+        else     hipLaunchKernelGGL((k_relu_stage<STAGE, V, T1, false>), grid, block, 0, st, p0, p1, only, lo, hi);
+    } else {
+        if (put) hipLaunchKernelGGL((k_relu_stage<STAGE, V, 0, P1>), grid, block, 0, st, p0, p1, only, lo, hi);
+        else     hipLaunchKernelGGL((k_relu_stage<STAGE, V, 0, false>), grid, block, 0, st, p0, p1, only, lo, hi);
+    }
 }
 
 template <int V>
@@ -621,24 +629,24 @@ void launch_stage(int stage, hipStream_t st, const ReluParty& p0, const ReluPart
 }
 
 // The packed chain: stages 1..7 work on packed words, the others are shared.
-template <int STAGE, int PARTY, int V>
+template <int STAGE, int PARTY, int V, bool PUT>
 __device__ __forceinline__ void stage_body_msb(const ReluParty& p, const MsbGeom& g, size_t lo, size_t hi)
 {
-    if constexpr (STAGE == 0) b_first<PARTY, V>(p, lo, hi);
-    else if constexpr (STAGE == 1) b_plevel<PARTY, 0, (V == 4 ? 2 : 1)>(p, g, lo, hi);
-    else if constexpr (STAGE >= 2 && STAGE <= 6) b_plevel<PARTY, STAGE - 1, 2>(p, g, lo, hi);
-    else if constexpr (STAGE == 7) b_psign<PARTY, V>(p, g, lo, hi);
-    else if constexpr (STAGE == 8) b_b2a<PARTY, V>(p, lo, hi);
+    if constexpr (STAGE == 0) b_first<PARTY, V, PUT>(p, lo, hi);
+    else if constexpr (STAGE == 1) b_plevel<PARTY, 0, (V == 4 ? 2 : 1), PUT>(p, g, lo, hi);
+    else if constexpr (STAGE >= 2 && STAGE <= 6) b_plevel<PARTY, STAGE - 1, 2, PUT>(p, g, lo, hi);
+    else if constexpr (STAGE == 7) b_psign<PARTY, V, PUT>(p, g, lo, hi);
+    else if constexpr (STAGE == 8) b_b2a<PARTY, V, PUT>(p, lo, hi);
     else b_select<PARTY, V>(p, lo, hi);
 }
 
-template <int STAGE, int V>
+template <int STAGE, int V, bool PUT>
 __global__ __launch_bounds__(kThreads) void k_relu_msb_stage(ReluParty p0, ReluParty p1, MsbGeom g, int only,
                                                              size_t lo, size_t hi)
 {
     const int party = only >= 0 ? only : (int)blockIdx.y;
-    if (party == 0) stage_body_msb<STAGE, 0, V>(p0, g, lo, hi);
-    else            stage_body_msb<STAGE, 1, V>(p1, g, lo, hi);
+    if (party == 0) stage_body_msb<STAGE, 0, V, PUT>(p0, g, lo, hi);
+    else            stage_body_msb<STAGE, 1, V, PUT>(p1, g, lo, hi);
 }
 
 template <int STAGE, int V>
@@ -654,7 +662,9 @@ void launch_msb_stage_t(hipStream_t st, const ReluParty& p0, const ReluParty& p1
         threads = (hi - lo + V - 1) / V;
     }
     const dim3 grid(grid_for(threads), only >= 0 ? 1 : 2), block(kThreads);
-    hipLaunchKernelGGL((k_relu_msb_stage<STAGE, V>), grid, block, 0, st, p0, p1, g, only, lo, hi);
+    constexpr bool P1 = STAGE <= 8;
+    if (p0.put != nullptr && P1) hipLaunchKernelGGL((k_relu_msb_stage<STAGE, V, P1>), grid, block, 0, st, p0, p1, g, only, lo, hi);
+    else                         hipLaunchKernelGGL((k_relu_msb_stage<STAGE, V, false>), grid, block, 0, st, p0, p1, g, only, lo, hi);
 }
 
 template <int V>
