@@ -150,6 +150,68 @@ def test_config3_transformer_full(mods, lane):
         torch.cuda.empty_cache()
 
 
+def test_config1_backward_full(mods, lane):
+    """Both gradient products of the configs[1] convolution at full size, opened masks of the
+    forward pass reused, and the ReLU backward on its 2 097 152 outputs: every share bit for bit."""
+    mpc, dealer, _ = mods
+    L = synth.config_vgg_block().layers[0]
+    print("config 1 backward, full size", flush=True)
+    rng = synth.rng_for(1, 5)
+    X = synth.normal_fixed(rng, (L.B, L.H, L.W, L.Cin), L.x_std); Wt = synth.normal_fixed(rng, (L.KH, L.KW, L.Cin, L.Cout), L.w_std)
+    G = synth.normal_fixed(rng, (L.B, L.Ho, L.Wo, L.Cout), 0.5)
+    xs, ws, gs = (synth.share_additive(rng, v) for v in (X, Wt, G))
+    fx = lambda g, w: oracle.ring_conv2d_grad_x(g, w, X.shape, L.pad, L.stride)
+    fw = lambda x, g: oracle.ring_conv2d_grad_w(x, g, L.KH, L.KW, L.pad, L.stride)
+    a, b, c = synth.deal_product_triple(rng, G.shape, Wt.shape, fx)
+    want = oracle.truncate(oracle.beaver_bilinear(fx, gs, ws, a, b, c), 16)
+    f_public = mpc.to_device((ws[0] - b[0]) + (ws[1] - b[1]))
+    gx = lane.conv2d_grad_x(dev(mpc, gs), None, dev(mpc, a), dev(mpc, b), dev(mpc, c), L.pad, L.stride, f_public=f_public)
+    lane.sync()
+    assert_equal_shares(mpc, gx, want, "grad_x")
+    a, b, c = synth.deal_product_triple(rng, X.shape, G.shape, fw)
+    want = oracle.truncate(oracle.beaver_bilinear(fw, xs, gs, a, b, c), 16)
+    e_public = mpc.to_device((xs[0] - a[0]) + (xs[1] - a[1]))
+    gw = lane.conv2d_grad_w(None, dev(mpc, gs), dev(mpc, a), dev(mpc, b), dev(mpc, c), L.pad, L.stride, e_public=e_public)
+    lane.sync()
+    assert_equal_shares(mpc, gw, want, "grad_w")
+    ref = torch.nn.functional.conv2d(torch.from_numpy(oracle.decode(X)).permute(3, 0, 1, 2),
+                                     torch.from_numpy(oracle.decode(G)).permute(3, 0, 1, 2), padding=L.pad).permute(2, 3, 0, 1).numpy()
+    assert np.abs(oracle.decode(rec(want)) - ref).max() <= 2.0 ** -12 * 4   # 16384-term sums of truncated products
+    # ReLU backward
+    n = G.size
+    s = (rng.integers(0, 2, size=n) == 1)
+    sa = synth.share_additive(rng, s.astype(U64))
+    t = synth.deal_product_triple(rng, (n,), (n,), lambda p, q: p * q)
+    gflat = (gs[0].reshape(-1), gs[1].reshape(-1))
+    got = lane.relu_backward(dev(mpc, gflat), dev(mpc, sa), *[dev(mpc, q) for q in t])
+    lane.sync()
+    assert_equal_shares(mpc, got, oracle.relu_backward(gflat, sa, *t), "relu backward")
+
+
+def test_config3_dense_backward_full(mods, lane):
+    """x^T g and g w^T of the BERT-base output projection (4096 x 768 x 768) at full size."""
+    mpc, dealer, _ = mods
+    L = [l for l in synth.config_transformer().layers if l.name == "out"][0]
+    print("config 3 dense backward, full size", flush=True)
+    rng = synth.rng_for(3, 5)
+    X = synth.normal_fixed(rng, (L.M, L.K), 1.0); Wt = synth.normal_fixed(rng, (L.K, L.N), L.w_std)
+    G = synth.normal_fixed(rng, (L.M, L.N), 0.5)
+    xs, ws, gs = (synth.share_additive(rng, v) for v in (X, Wt, G))
+    tp = lambda pair: tuple(np.ascontiguousarray(p.T) for p in pair)
+    a, b, c = synth.deal_product_triple(rng, (L.K, L.M), (L.M, L.N), oracle.ring_matmul)
+    want = oracle.truncate(oracle.beaver_matmul(tp(xs), gs, a, b, c), 16)
+    gw = lane.beaver_matmul(dev(mpc, xs), dev(mpc, gs), dev(mpc, tp(a)), dev(mpc, b), dev(mpc, c),
+                            flags=mpc.MPC_TRUNCATE | mpc.MPC_TRANS_X)
+    lane.sync()
+    assert_equal_shares(mpc, gw, want, "grad_w")
+    a, bt, c = synth.deal_product_triple(rng, (L.M, L.N), (L.N, L.K), oracle.ring_matmul)
+    want = oracle.truncate(oracle.beaver_matmul(gs, tp(ws), a, bt, c), 16)
+    gx = lane.beaver_matmul(dev(mpc, gs), dev(mpc, ws), dev(mpc, a), dev(mpc, tp(bt)), dev(mpc, c),
+                            flags=mpc.MPC_TRUNCATE | mpc.MPC_TRANS_Y)
+    lane.sync()
+    assert_equal_shares(mpc, gx, want, "grad_x")
+
+
 @pytest.mark.parametrize("packed_relu", [False, True], ids=["whole-word-relu", "sign-only-packed-relu"])
 def test_config4_vgg16_pipeline_full(mods, packed_relu):
     """Batch 128 = 4 micro-batches of 32 through the whole VGG16-CIFAR network:
