@@ -166,7 +166,7 @@ def main():
         "roofline": {"kernel": "k_limb_gemm<2,2,true> (both parties, [e|a_i] x [b_i';f], fused add-c + truncation)",
                      "bound": "mfma", "achieved": gemm_tops, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                      "frac": gemm_tops / INT8_PEAK_TOPS,
-                     "traffic": {"fetch_bytes": 163.5 * 2 ** 20, "write_bytes": 32.0 * 2 ** 20,
+                     "traffic": {"fetch_bytes": 135.0 * 2 ** 20, "write_bytes": 32.0 * 2 ** 20,
                                  "algorithmic_bytes": (100.6 + 32.0) * 2 ** 20,
                                  "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated on a copy kernel "
                                            "(profiles/bench_vgg_block_hbm_traffic.md)"},
@@ -175,12 +175,12 @@ def main():
         "roofline_relu": {"kernel": "secure ReLU chain: k_relu_stage<0..9> (both parties per launch) + k_wire_words / k_wire_bytes",
                           "bound": "hbm", "achieved": relu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                           "frac": relu_gbs / HBM_PEAK_GBS,
-                          "traffic": {"bytes_per_element": 3389, "source": "rocprofv3 --pmc, same summary"},
+                          "traffic": {"bytes_per_element": 3397, "source": "rocprofv3 --pmc, same summary"},
                           "bytes_per_element": RELU_BYTES_PER_ELEMENT},
         "roofline_relu_msb": {"kernel": "sign-only packed ReLU chain: k_relu_msb_stage<0..9> + k_wire_words / k_wire_bytes",
                               "bound": "hbm", "achieved": msb_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": msb_gbs / HBM_PEAK_GBS,
-                              "traffic": {"bytes_per_element": 1163, "source": "rocprofv3 --pmc, same summary"},
+                              "traffic": {"bytes_per_element": 1164, "source": "rocprofv3 --pmc, same summary"},
                               "bytes_per_element": RELU_MSB_BYTES_PER_ELEMENT},
     }
     if not args.no_cpu_baseline:

@@ -221,6 +221,7 @@ struct GemmArgs {
     const u8* zero16;                 // 16 readable zero bytes (conv padding)
     int ksplit;                       // > 1: split the contraction over this many workgroups per tile
     int steps_per_split;              // filled by the launcher
+    int tiles_m, tiles_n, tiles_total;   // filled by the launcher: output tiles per matrix, all tiles (x batch x ksplit)
     u64* partial;                     // [ksplit][nparty][batch][M][N] partial products (ksplit > 1)
 };
 int gemm_ksplit(int M, int N, int batch, int nparty, int total_steps);
