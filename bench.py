@@ -63,7 +63,14 @@ def cpu_baseline(layer, budget_s=12.0):
         oracle.relu(z, mat)
         t2 = time.perf_counter()
         t_lin += t1 - t0; t_relu += t2 - t1; reps += 1
-    return {"value": macs * reps / t_lin, "unit": "secure MACs/s", "cores": oracle.n_threads(), "kind": "oracle",
+    cpu_model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            cpu_model = next(l.split(":", 1)[1].strip() for l in f if l.startswith("model name"))
+    except (OSError, StopIteration):
+        pass
+    return {"value": macs * reps / t_lin, "unit": "secure MACs/s", "cores": oracle.n_threads(), "cpu": cpu_model,
+            "kind": "oracle",
             "relu_value": n * reps / t_relu, "relu_unit": "secure ReLU elems/s",
             "sample": f"{reps} x (batch {B} of 64 of the same conv block: Alg. 1 with five direct ring "
                       f"convolutions + truncation, then ReLU on {n} elements), {t_lin + t_relu:.1f} s of CPU work"}
@@ -120,6 +127,11 @@ def main():
     lin_ms, lin_n = lane.profile(mpc.PROF_LINEAR)
     relu_ms, relu_n = lane.profile(mpc.PROF_RELU)
     gemm_ms /= gemm_n; lin_ms /= lin_n; relu_ms /= relu_n
+    import statistics
+    spread = {}
+    for key, which in (("gemm_kernel", mpc.PROF_GEMM_KERNEL), ("beaver_conv_call", mpc.PROF_LINEAR), ("relu_call", mpc.PROF_RELU)):
+        smp = lane.profile_samples(which)
+        spread[key] = {"median_ms": statistics.median(smp), "min_ms": min(smp), "max_ms": max(smp), "n": len(smp)}
 
     # sanity on the result of the last step: ReLU of the reconstructed conv output, exactly
     rec_z = (z[0] + z[1]); rec_y = (y[0] + y[1])
@@ -143,6 +155,8 @@ def main():
     lane.set_profiling(False)
     msb_ms, msb_n = lane.profile(mpc.PROF_RELU)
     msb_ms /= msb_n
+    smp = lane.profile_samples(mpc.PROF_RELU)
+    spread["relu_msb_call"] = {"median_ms": statistics.median(smp), "min_ms": min(smp), "max_ms": max(smp), "n": len(smp)}
     assert torch.equal(y2[0] + y2[1], torch.clamp(rec_z, min=0)), "mpc_relu_msb output does not reconstruct to max(z, 0)"
     msb_gbs = RELU_MSB_BYTES_PER_ELEMENT * n / (msb_ms * 1e-3) / 1e9
 
@@ -161,7 +175,7 @@ def main():
                                "= Beaver GEMM [16384x1152]x[1152x128] + truncation + secure ReLU on 2097152 elements",
                    "parties": 2, "frac_bits": 16, "n_chunks": 1, "relu_chunks": "auto (about 2^20 elements each)", "lane": "single in-order queue",
                    "ms_beaver_conv_call": lin_ms, "ms_gemm_kernel": gemm_ms, "ms_relu_call": relu_ms,
-                   "ms_relu_msb_call": msb_ms,
+                   "ms_relu_msb_call": msb_ms, "region_times": spread,
                    "max_abs_err_vs_float64": err},
         "roofline": {"kernel": "k_limb_gemm<2,2,true> (both parties, [e|a_i] x [b_i';f], fused add-c + truncation)",
                      "bound": "mfma", "achieved": gemm_tops, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",

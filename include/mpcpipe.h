@@ -103,6 +103,9 @@ int mpc_ctx_wait(mpc_ctx* ctx, mpc_ctx* after);
 enum { MPC_PROF_GEMM_KERNEL = 0, MPC_PROF_LINEAR = 1, MPC_PROF_RELU = 2 };
 int mpc_ctx_set_profiling(mpc_ctx* ctx, int enable);
 int mpc_ctx_profile(mpc_ctx* ctx, int which, double* total_ms, int* count);
+/* The individual region durations (host array ms_out of `capacity` doubles, in
+ * recording order; *count = number recorded, which may exceed capacity). */
+int mpc_ctx_profile_samples(mpc_ctx* ctx, int which, double* ms_out, int capacity, int* count);
 int mpc_ctx_profile_reset(mpc_ctx* ctx);
 
 /* Carry network of the whole-word secure ReLU (mpc_relu, mpc_maxpool2x2):

@@ -29,7 +29,18 @@ def layer_macs(L):
     return L.M * L.K * L.N * max(L.batch, 1)
 
 
-def bench_layers(idx: int, reps: int = 5, workload=None):
+def gemm_algorithmic_bytes(L) -> int:
+    """Both parties: read the digit planes of e and a_i (un-expanded activation for a conv), of
+    f and b_i', the addend c_i; write z_i.  One byte per digit, eight digits per ring word."""
+    if isinstance(L, synth.Conv):
+        act, wts, out = L.B * L.H * L.W * L.Cin, L.KH * L.KW * L.Cin * L.Cout, L.B * L.Ho * L.Wo * L.Cout
+    else:
+        b = max(L.batch, 1)
+        act, wts, out = b * L.M * L.K, b * L.K * L.N, b * L.M * L.N
+    return 2 * 8 * (2 * act + 2 * wts + 2 * out)
+
+
+def bench_layers(idx: int, reps: int = 20, workload=None):
     wl = workload if workload is not None else synth.CONFIGS[idx]()
     lane = mpc.Lane(0); lane.use_single_queue()
     dev = lane.device
@@ -50,7 +61,7 @@ def bench_layers(idx: int, reps: int = 5, workload=None):
             shape = f"{L.M}x{L.K}x{L.N}" + (f" x{L.batch}" if L.batch > 1 else "")
         mat = dealer.relu_material(g, n_out, dev) if L.relu else None
         y = (torch.empty_like(z[0]), torch.empty_like(z[1])) if L.relu else None
-        for _ in range(2):
+        for _ in range(5):
             run()
             if mat: lane.relu(z, mat, out=y)
         lane.sync(); lane.set_profiling(True); lane.profile_reset()
@@ -61,7 +72,9 @@ def bench_layers(idx: int, reps: int = 5, workload=None):
         gk, gn = lane.profile(mpc.PROF_GEMM_KERNEL); lin, ln = lane.profile(mpc.PROF_LINEAR)
         macs = layer_macs(L)
         row = dict(layer=L.name, gemm=shape, repeat=L.repeat, call_ms=lin / ln, kernel_ms=gk / gn,
-                   secure_macs_per_s=macs / (lin / ln * 1e-3), mfma_frac=288 * macs / (gk / gn * 1e-3) / INT8_PEAK)
+                   kernel_min_ms=min(lane.profile_samples(mpc.PROF_GEMM_KERNEL)),
+                   secure_macs_per_s=macs / (lin / ln * 1e-3), mfma_frac=288 * macs / (gk / gn * 1e-3) / INT8_PEAK,
+                   gemm_hbm_frac=gemm_algorithmic_bytes(L) / (gk / gn * 1e-3) / HBM_PEAK)
         if mat:
             rl, rn = lane.profile(mpc.PROF_RELU)
             row.update(relu_n=n_out, relu_ms=rl / rn, relu_elems_per_s=n_out / (rl / rn * 1e-3),
@@ -69,7 +82,7 @@ def bench_layers(idx: int, reps: int = 5, workload=None):
             # the same ReLU on the sign's carry chain only, packed material
             del mat
             mat = dealer.relu_material(g, n_out, dev, packed=True)
-            for _ in range(2):
+            for _ in range(5):
                 lane.relu(z, mat, out=y, packed=True)
             lane.sync(); lane.set_profiling(True); lane.profile_reset()
             for _ in range(reps):
@@ -322,15 +335,21 @@ def main(argv):
         return
     which = [int(a) for a in argv] if argv else list(range(len(synth.CONFIGS)))
     for idx in which:
-        name, rows = bench_layers(idx) if idx != 4 else bench_layers(4, reps=3)
+        name, rows = bench_layers(idx)
         print(f"== config {idx}: {name}")
+        tot = dict(lin=0.0, relu=0.0, msb=0.0)
         for r in rows:
+            # both roofs of the GEMM kernel; '*' marks the one that binds (the larger fraction)
+            mf, hf = 100 * r['mfma_frac'], 100 * r['gemm_hbm_frac']
             line = (f"  {r['layer']:10s} {r['gemm']:22s} call {r['call_ms']:8.3f} ms  {r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s"
-                    f"  kernel {r['kernel_ms']:8.3f} ms  mfma {100 * r['mfma_frac']:5.1f}%")
+                    f"  kernel {r['kernel_ms']:8.3f} ms (min {r['kernel_min_ms']:.3f})  mfma {mf:5.1f}%{'*' if mf >= hf else ' '} hbm {hf:5.1f}%{'*' if hf > mf else ' '}")
+            tot['lin'] += r['call_ms']
             if "relu_ms" in r:
+                tot['relu'] += r['relu_ms']; tot['msb'] += r['msb_ms']
                 line += f"  | relu {r['relu_n']:9d} el {r['relu_ms']:7.3f} ms {r['relu_elems_per_s'] / 1e9:5.2f} G/s hbm {100 * r['hbm_frac']:5.1f}%"
                 line += f"  | sign-only {r['msb_ms']:7.3f} ms {r['msb_elems_per_s'] / 1e9:5.2f} G/s hbm {100 * r['msb_hbm_frac']:5.1f}%"
             print(line, flush=True)
+        print(f"  totals: linear calls {tot['lin']:.3f} ms, ReLU {tot['relu']:.3f} ms whole-word / {tot['msb']:.3f} ms sign-only", flush=True)
         if idx == 4:
             for packed in (False, True):
                 p = bench_pipeline(packed_relu=packed)

@@ -130,6 +130,20 @@ int mpc_ctx_profile(mpc_ctx* c, int which, double* total_ms, int* count)
     return MPC_OK;
 }
 
+int mpc_ctx_profile_samples(mpc_ctx* c, int which, double* ms_out, int capacity, int* count)
+{
+    if (!c || which < 0 || which > 2 || !count || capacity < 0 || (capacity > 0 && !ms_out)) return MPC_EINVAL;
+    MPC_TRY(mpc_ctx_sync(c));
+    const int n = (int)c->prof[which].size();
+    for (int i = 0; i < n && i < capacity; ++i) {
+        float ms = 0.f;
+        MPC_HIP(c, hipEventElapsedTime(&ms, c->prof[which][i].first, c->prof[which][i].second));
+        ms_out[i] = ms;
+    }
+    *count = n;
+    return MPC_OK;
+}
+
 int mpc_ctx_profile_reset(mpc_ctx* c)
 {
     if (!c) return MPC_EINVAL;

@@ -49,7 +49,7 @@ EXPORTS = [
     "mpc_conv2d_grad_w", "mpc_mul_workspace_bytes", "mpc_mul", "mpc_relu_backward",
     "mpc_ring_conv2d_grad_x", "mpc_ring_conv2d_grad_w",
     "mpc_maxpool2x2_signs", "mpc_maxpool_backward_workspace_bytes", "mpc_maxpool2x2_backward",
-    "mpc_ctx_set_adder", "mpc_ctx_set_exchange",
+    "mpc_ctx_set_adder", "mpc_ctx_set_exchange", "mpc_ctx_profile_samples",
 ]
 
 _lib = None
@@ -66,6 +66,7 @@ def lib():
     L.mpc_ctx_create.argtypes = [POINTER(c_void_p), c_int, c_int]
     L.mpc_ctx_destroy.argtypes = [c_void_p]
     L.mpc_ctx_set_adder.argtypes = [c_void_p, c_int]
+    L.mpc_ctx_profile_samples.argtypes = [c_void_p, c_int, POINTER(ctypes.c_double), c_int, POINTER(c_int)]
     L.mpc_ctx_set_exchange.argtypes = [c_void_p, c_int]
     L.mpc_ctx_set_streams.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
     L.mpc_ctx_stream.argtypes = [c_void_p, c_int]; L.mpc_ctx_stream.restype = c_void_p
@@ -218,6 +219,14 @@ class Lane:
         ms, cnt = ctypes.c_double(), c_int()
         self._check(lib().mpc_ctx_profile(self._h, which, byref(ms), byref(cnt)))
         return ms.value, cnt.value
+
+    def profile_samples(self, which: int):
+        """Every recorded region's duration in milliseconds, in recording order."""
+        cnt = c_int()
+        self._check(lib().mpc_ctx_profile_samples(self._h, which, None, 0, byref(cnt)))
+        buf = (ctypes.c_double * max(cnt.value, 1))()
+        self._check(lib().mpc_ctx_profile_samples(self._h, which, buf, cnt.value, byref(cnt)))
+        return list(buf)[:cnt.value]
 
     def profile_reset(self):
         self._check(lib().mpc_ctx_profile_reset(self._h))
