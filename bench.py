@@ -185,7 +185,7 @@ def main():
                                  "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated on a copy kernel "
                                            "(profiles/bench_vgg_block_hbm_traffic.md)"},
                      "note": "288 int8 ops per secure MAC; power-limited attainable rate with random int8 operands "
-                             "measured on this chip is about 3070 TOP/s (see DESIGN.md)"},
+                             "measured on this chip with a back-to-back MFMA loop is about 3070 TOP/s"},
         "roofline_relu": {"kernel": "secure ReLU chain: k_relu_stage<0..9> (both parties per launch) + k_wire_words / k_wire_bytes",
                           "bound": "hbm", "achieved": relu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                           "frac": relu_gbs / HBM_PEAK_GBS,

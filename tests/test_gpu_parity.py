@@ -327,6 +327,9 @@ def test_profiling_regions(mpc, lane):
     relu_ms, relu_n = lane.profile(mpc.PROF_RELU)
     assert (gemm_n, lin_n, relu_n) == (3, 3, 1)
     assert 0 < gemm_ms <= lin_ms and relu_ms > 0
+    samples = lane.profile_samples(mpc.PROF_LINEAR)
+    assert len(samples) == 3 and all(t > 0 for t in samples) and abs(sum(samples) - lin_ms) < 1e-6
     lane.profile_reset()
+    assert lane.profile_samples(mpc.PROF_LINEAR) == []
     assert lane.profile(mpc.PROF_LINEAR) == (0.0, 0)
     assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "result unaffected by profiling")
