@@ -153,7 +153,7 @@ int mpc_open(mpc_ctx* ctx, mpc_cshare s, uint64_t* out_public, size_t n);
 
 /* Share-wise difference out_i = x_i - a_i (shares are linear, Eq. 1); with x a
  * weight and a the B part of its layer's triple this is the masked weight
- * that Alg. 3 (line 2-3) broadcasts one layer ahead: follow it with mpc_open
+ * that Alg. 3 broadcasts one layer ahead: follow it with mpc_open
  * to obtain f_public. */
 int mpc_sub(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_share out, size_t n);
 

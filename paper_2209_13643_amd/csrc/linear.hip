@@ -285,7 +285,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         return MPC_OK;
     }
 
-    // -- Alg. 1 line 1-2 / Alg. 3 line 2-3: mask and start the exchange, chunk by chunk
+    // -- Alg. 1 / Alg. 3, masking step: mask and start the exchange, chunk by chunk
     if (!f_public) {
         for (int i = 0; i < 2; ++i) {
             MPC_TRY(launch_sub(c, P[i], y.p[i], b.p[i], w.sf[i], s.nw));
@@ -321,7 +321,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
     g.nparty = 2;
 
     if (two_phase && f_public) {
-        // Alg. 3 lines 4-6: epsilon is already here; z_i = Conv([a_i], epsilon)
+        // Alg. 3, first product: epsilon is already here; z_i = Conv([a_i], epsilon)
         // runs while the masked inputs are still crossing the wire.
         MPC_TRY(launch_recode(c, P0, recode_right(s, f_public, nullptr, nullptr, w.pr_f)));
         MPC_TRY(launch_recode(c, P0, recode_right(s, b.p[0], f_public, nullptr, w.pr_b[0])));
@@ -333,7 +333,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         }
         g.trunc_bits = 0;
         MPC_TRY(launch_limb_gemm(c, P0, g));
-        // Alg. 3 lines 7-10: wait for Delta, add [c_i] + Conv(Delta, [b_i]) (+ Conv(Delta, epsilon))
+        // Alg. 3, after the wait for Delta: add [c_i] + Conv(Delta, [b_i]) (+ Conv(Delta, epsilon))
         MPC_TRY(chain(c, Wr, P0));
         MPC_TRY(launch_left1(c, P0, s, e_src, e_src2, w.pl_e));
         for (int i = 0; i < 2; ++i) {
@@ -343,7 +343,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         g.trunc_bits = trunc;
         MPC_TRY(launch_limb_gemm(c, P0, g));
     } else {
-        // Alg. 1 lines 3-7: wait for the exchange, open, one fused contraction
+        // Alg. 1 after the masking step: wait for the exchange, open, one fused contraction
         // [e | a_i] x [b_i (+ f for party 0) ; f] per party.
         MPC_TRY(chain(c, Wr, P0));
         MPC_TRY(launch_left1(c, P0, s, e_src, e_src2, w.pl_e));

@@ -84,7 +84,7 @@ def deal_microbatch(lane: mpc.Lane, g, layers, weights, packed_relu: bool = Fals
 
 
 def preopen_weights(lane: mpc.Lane, states):
-    """Alg. 3, lines 2-5, ahead of the forward pass: open W - B of every layer."""
+    """Alg. 3's early broadcast of the weight masks, ahead of the forward pass: open W - B of every layer."""
     for st in states:
         d = lane.sub(st.w, st.b)
         st.f_public = lane.open(d)

@@ -298,7 +298,7 @@ def test_argument_errors(mpc, lane):
 
 # ------------------------------------------------- small API pieces used by the runner
 def test_sub_then_open_gives_weight_mask(mpc, lane):
-    """mpc_sub + mpc_open = the ahead-of-time opening of W - B (Alg. 3, lines 2-5)."""
+    """mpc_sub + mpc_open = the ahead-of-time opening of W - B (Alg. 3, the early broadcast)."""
     print("sub + open", flush=True)
     rng = np.random.default_rng(55)
     W = synth.rand_words(rng, (37, 21)); B = synth.rand_words(rng, (37, 21))
