@@ -157,6 +157,11 @@ int mpc_open(mpc_ctx* ctx, mpc_cshare s, uint64_t* out_public, size_t n);
  * to obtain f_public. */
 int mpc_sub(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_share out, size_t n);
 
+/* out_i = x_i + y_i: the local sum of two sharings (residual connections,
+ * shared biases; addition of secret-shared values needs no communication,
+ * Sec. 3.1).  out may alias x or y. */
+int mpc_add(mpc_ctx* ctx, mpc_cshare x, mpc_cshare y, mpc_share out, size_t n);
+
 /* --------------------------------------------------- Beaver matmul (Alg. 1) */
 
 /* z = x * y on additive shares with the triple (a, b, c), C = A*B:

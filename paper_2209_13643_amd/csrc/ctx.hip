@@ -196,6 +196,15 @@ int mpc_sub(mpc_ctx* c, mpc_cshare x, mpc_cshare a, mpc_share out, size_t n)
     return MPC_OK;
 }
 
+int mpc_add(mpc_ctx* c, mpc_cshare x, mpc_cshare y, mpc_share out, size_t n)
+{
+    if (!c || n == 0) return MPC_EINVAL;
+    for (int i = 0; i < 2; ++i) if (!x.p[i] || !y.p[i] || !out.p[i]) return MPC_EINVAL;
+    MPC_TRY(lane_join(c));
+    for (int i = 0; i < 2; ++i) MPC_TRY(launch_add(c, c->s[i], x.p[i], y.p[i], out.p[i], n));
+    return MPC_OK;
+}
+
 size_t mpc_mul_workspace_bytes(size_t n) { return n ? 8 * align_up(n * sizeof(u64)) : 0; }
 
 // Element-wise Alg. 1.  Both parties' mask and finish kernels share a launch on

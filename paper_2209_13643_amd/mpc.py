@@ -49,7 +49,7 @@ EXPORTS = [
     "mpc_conv2d_grad_w", "mpc_mul_workspace_bytes", "mpc_mul", "mpc_relu_backward",
     "mpc_ring_conv2d_grad_x", "mpc_ring_conv2d_grad_w",
     "mpc_maxpool2x2_signs", "mpc_maxpool_backward_workspace_bytes", "mpc_maxpool2x2_backward",
-    "mpc_ctx_set_adder", "mpc_ctx_set_exchange", "mpc_ctx_profile_samples",
+    "mpc_ctx_set_adder", "mpc_ctx_set_exchange", "mpc_ctx_profile_samples", "mpc_add",
 ]
 
 _lib = None
@@ -66,6 +66,7 @@ def lib():
     L.mpc_ctx_create.argtypes = [POINTER(c_void_p), c_int, c_int]
     L.mpc_ctx_destroy.argtypes = [c_void_p]
     L.mpc_ctx_set_adder.argtypes = [c_void_p, c_int]
+    L.mpc_add.argtypes = [c_void_p, CShare, CShare, CShare, c_size_t]
     L.mpc_ctx_profile_samples.argtypes = [c_void_p, c_int, POINTER(ctypes.c_double), c_int, POINTER(c_int)]
     L.mpc_ctx_set_exchange.argtypes = [c_void_p, c_int]
     L.mpc_ctx_set_streams.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
@@ -276,6 +277,13 @@ class Lane:
         self.reserve(2 * (n * 8 + 256))
         out = torch.empty_like(s[0])
         self._check(lib().mpc_open(self._h, _share(s), _p64(out), n))
+        return out
+
+    def add(self, x, y, out=None):
+        """Local sum of two sharings."""
+        if out is None:
+            out = (torch.empty_like(x[0]), torch.empty_like(x[1]))
+        self._check(lib().mpc_add(self._h, _share(x), _share(y), _share(out), x[0].numel()))
         return out
 
     def sub(self, x, a, out=None):

@@ -310,6 +310,17 @@ def test_sub_then_open_gives_weight_mask(mpc, lane):
     assert np.array_equal(mpc.to_host(f), oracle.open_shares(ws[0] - bs[0], ws[1] - bs[1]))
 
 
+def test_add_is_the_local_sum(mpc, lane):
+    print("add", flush=True)
+    rng = np.random.default_rng(68)
+    n = 4099
+    X, Y = synth.rand_words(rng, n), synth.rand_words(rng, n)
+    xs, ys = synth.share_additive(rng, X), synth.share_additive(rng, Y)
+    got = host(mpc, lane, lane.add(dev(mpc, xs), dev(mpc, ys)))
+    assert_shares_equal(got, (xs[0] + ys[0], xs[1] + ys[1]), "add")
+    assert np.array_equal(rec(got), X + Y)
+
+
 def test_profiling_regions(mpc, lane):
     print("profiling regions", flush=True)
     d = deal_matmul(np.random.default_rng(66), 96, 64, 80)
