@@ -96,6 +96,25 @@ def test_ring_matmul_extreme_digits(mpc, lane):
     assert np.array_equal(mpc.to_host(Z), oracle.ring_matmul(L, R))
 
 
+def test_ring_matmul_longest_exact_pass_worst_case(mpc):
+    """The longest contraction one workgroup sums without slicing (32 736 terms), with every
+    digit of many rows and columns at -128: the int32 digit sums reach 4 * 32736 * 2^14, the
+    largest value the exactness bound allows.  160 output tiles keep the contraction unsplit."""
+    print("ring_matmul worst-case digit sums", flush=True)
+    M, K, N = 640, 32736, 2048
+    lane = mpc.Lane(0); lane.use_single_queue()
+    rng = np.random.default_rng(6)
+    lo, hi = np.uint64(0x8080808080808080), np.uint64(0x7F7F7F7F7F7F7F7F)
+    L = np.where(rng.integers(0, 2, size=(M, K)) == 1, lo, hi)
+    R = np.where(rng.integers(0, 2, size=(K, N)) == 1, lo, hi)
+    L[::2] = lo; R[:, ::2] = lo                          # whole rows / columns of -128 digits
+    L[1] = hi; R[:, 1] = hi                              # and of +127 digits
+    Z = lane.ring_matmul(mpc.to_device(L), mpc.to_device(R))
+    lane.sync()
+    assert np.array_equal(mpc.to_host(Z), oracle.ring_matmul(L, R))
+    lane.close()
+
+
 def test_ring_matmul_batched(mpc, lane):
     print("ring_matmul batched", flush=True)
     rng = np.random.default_rng(6)
