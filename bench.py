@@ -12,7 +12,9 @@ Prints one JSON line.  `value` is secure MACs/s of the Beaver convolution call
 (mask, exchange, digit recoding, int8-MFMA GEMM, truncation); the secure ReLU
 rate and the whole-step time are reported beside it.  `roofline` describes the
 digit-plane GEMM kernel against the int8 MFMA peak, `roofline_relu` the ReLU
-chain against HBM bandwidth, `roofline_relu_msb` the same ReLU evaluated on the
+chain against HBM bandwidth, `value_prepared_planes` the convolution call when
+the digit planes of the triple and of the opened weight mask were recoded ahead
+of time (mpc_conv2d_prepared), `roofline_relu_msb` the same ReLU evaluated on the
 sign's carry chain only with bit-packed triples (mpc_relu_msb, timed on its own
 after the steps); `cpu_baseline` is the CPU oracle timed on this
 box's host cores on the same workload (a reported baseline, not a target).
@@ -160,6 +162,20 @@ def main():
     assert torch.equal(y2[0] + y2[1], torch.clamp(rec_z, min=0)), "mpc_relu_msb output does not reconstruct to max(z, 0)"
     msb_gbs = RELU_MSB_BYTES_PER_ELEMENT * n / (msb_ms * 1e-3) / 1e9
 
+    # the Beaver convolution with the input-independent operands' digit planes recoded ahead of time
+    right, left = lane.prepare_conv2d(d["a"], d["b"], d["f_public"], L.pad, L.stride)
+    for _ in range(args.warmup):
+        lane.conv2d_prepared(d["x"], d["a"], d["c"], right, left, L.KH, L.KW, L.pad, L.stride, out=y2)
+    lane.sync()
+    lane.set_profiling(True); lane.profile_reset()
+    for _ in range(args.steps):
+        lane.conv2d_prepared(d["x"], d["a"], d["c"], right, left, L.KH, L.KW, L.pad, L.stride, out=y2)
+    lane.sync(); torch.cuda.synchronize()
+    lane.set_profiling(False)
+    prep_ms, prep_n = lane.profile(mpc.PROF_LINEAR)
+    prep_ms /= prep_n
+    assert torch.equal(y2[0], z[0]) and torch.equal(y2[1], z[1]), "prepared-plane convolution differs from the plain call"
+
     macs = M * K * N
     gemm_tops = INT8_OPS_PER_SECURE_MAC * macs / (gemm_ms * 1e-3) / 1e12
     relu_gbs = RELU_BYTES_PER_ELEMENT * n / (relu_ms * 1e-3) / 1e9
@@ -168,6 +184,7 @@ def main():
         "value": macs / (lin_ms * 1e-3), "unit": "secure MACs/s",
         "relu_value": n / (relu_ms * 1e-3), "relu_unit": "secure ReLU elems/s",
         "relu_msb_value": n / (msb_ms * 1e-3),
+        "value_prepared_planes": M * K * N / (prep_ms * 1e-3),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64 ring (int8 digits, int32 accumulate)",
         "data": "synthetic",
@@ -175,7 +192,7 @@ def main():
                                "= Beaver GEMM [16384x1152]x[1152x128] + truncation + secure ReLU on 2097152 elements",
                    "parties": 2, "frac_bits": 16, "n_chunks": 1, "relu_chunks": "auto (about 2^20 elements each)", "lane": "single in-order queue",
                    "ms_beaver_conv_call": lin_ms, "ms_gemm_kernel": gemm_ms, "ms_relu_call": relu_ms,
-                   "ms_relu_msb_call": msb_ms, "region_times": spread,
+                   "ms_relu_msb_call": msb_ms, "ms_beaver_conv_call_prepared_planes": prep_ms, "region_times": spread,
                    "max_abs_err_vs_float64": err},
         "roofline": {"kernel": "k_limb_gemm<2,2,true> (both parties, [e|a_i] x [b_i';f], fused add-c + truncation)",
                      "bound": "mfma", "achieved": gemm_tops, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",

@@ -199,6 +199,39 @@ int mpc_conv2d(mpc_ctx* ctx, mpc_cshare x, mpc_cshare w,
                int pad, int stride,
                const uint64_t* f_public, int n_chunks, int flags);
 
+/* Prepared layers.  The GEMM consumes digit planes; those of the operands that
+ * do not depend on the input - the triple's [a_i] on the left, and on the right
+ * the opened weight mask f = w - b (Alg. 3 sends it ahead of time), b_0 + f and
+ * b_1 - can be recoded once, when the offline material and the weights are in
+ * place, and kept resident: a call then only masks and exchanges x, recodes the
+ * opened e and runs the GEMM.  Results are the same words as from
+ * mpc_beaver_matmul / mpc_conv2d with f_public.
+ *   mpc_*_prepared_bytes: sizes of the two caller-owned device buffers
+ *     (right: three plane tensors; left: two); either pointer may be NULL.
+ *   mpc_*_prepare: fill them.  right_planes needs b and f_public, left_planes
+ *     needs a; pass NULL for the one not wanted.  Buffers 16-byte aligned.
+ *     flags: MPC_TRANS_X / MPC_TRANS_Y as for mpc_beaver_matmul (storage of a / of b, f).
+ *   mpc_beaver_matmul_prepared / mpc_conv2d_prepared: the online call.
+ *     right_planes is required; left_planes may be NULL (then [a_i] is recoded
+ *     in the call).  Other arguments, workspace and errors as for the plain calls. */
+int mpc_matmul_prepared_bytes(int M, int K, int N, int batch, size_t* right, size_t* left);
+int mpc_conv2d_prepared_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                              int pad, int stride, size_t* right, size_t* left);
+int mpc_matmul_prepare(mpc_ctx* ctx, mpc_cshare a, mpc_cshare b, const uint64_t* f_public,
+                       void* right_planes, void* left_planes,
+                       int M, int K, int N, int batch, int flags);
+int mpc_conv2d_prepare(mpc_ctx* ctx, mpc_cshare a, mpc_cshare b, const uint64_t* f_public,
+                       void* right_planes, void* left_planes,
+                       int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                       int pad, int stride);
+int mpc_beaver_matmul_prepared(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_cshare c, mpc_share z,
+                               const void* right_planes, const void* left_planes,
+                               int M, int K, int N, int batch, int n_chunks, int flags);
+int mpc_conv2d_prepared(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_cshare c, mpc_share z,
+                        const void* right_planes, const void* left_planes,
+                        int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                        int pad, int stride, int n_chunks, int flags);
+
 /* Backward pass of mpc_conv2d (Sec. 4.1 "Application to the backward pass",
  * Sec. 5.3): both gradients are Alg. 1 / Eq. 3 with another bilinear product
  * in place of Conv, on operands that are available before the backward pass

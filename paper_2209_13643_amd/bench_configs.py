@@ -59,6 +59,22 @@ def bench_layers(idx: int, reps: int = 20, workload=None):
             n_out = L.M * L.N * max(L.batch, 1)
             z = (torch.empty_like(d["c"][0]), torch.empty_like(d["c"][1]))
             shape = f"{L.M}x{L.K}x{L.N}" + (f" x{L.batch}" if L.batch > 1 else "")
+        # the same call on prepared planes (input-independent operands recoded ahead of time)
+        if isinstance(L, synth.Conv):
+            right, left = lane.prepare_conv2d(d["a"], d["b"], d["f_public"], L.pad, L.stride)
+            run_prep = lambda: lane.conv2d_prepared(d["x"], d["a"], d["c"], right, left, L.KH, L.KW, L.pad, L.stride, out=z)
+        else:
+            right, left = lane.prepare_matmul(d["a"], d["b"], d["f_public"])
+            run_prep = lambda: lane.beaver_matmul_prepared(d["x"], d["a"], d["c"], right, left, out=z)
+        for _ in range(5):
+            run_prep()
+        lane.sync(); lane.set_profiling(True); lane.profile_reset()
+        for _ in range(reps):
+            run_prep()
+        lane.sync(); lane.set_profiling(False)
+        prep_ms, prep_n = lane.profile(mpc.PROF_LINEAR)
+        prep_ms /= prep_n
+        del right, left
         mat = dealer.relu_material(g, n_out, dev) if L.relu else None
         y = (torch.empty_like(z[0]), torch.empty_like(z[1])) if L.relu else None
         for _ in range(5):
@@ -71,7 +87,7 @@ def bench_layers(idx: int, reps: int = 20, workload=None):
         lane.sync(); lane.set_profiling(False)
         gk, gn = lane.profile(mpc.PROF_GEMM_KERNEL); lin, ln = lane.profile(mpc.PROF_LINEAR)
         macs = layer_macs(L)
-        row = dict(layer=L.name, gemm=shape, repeat=L.repeat, call_ms=lin / ln, kernel_ms=gk / gn,
+        row = dict(layer=L.name, gemm=shape, repeat=L.repeat, call_ms=lin / ln, prepared_call_ms=prep_ms, kernel_ms=gk / gn,
                    kernel_min_ms=min(lane.profile_samples(mpc.PROF_GEMM_KERNEL)),
                    secure_macs_per_s=macs / (lin / ln * 1e-3), mfma_frac=288 * macs / (gk / gn * 1e-3) / INT8_PEAK,
                    gemm_hbm_frac=gemm_algorithmic_bytes(L) / (gk / gn * 1e-3) / HBM_PEAK)
@@ -194,7 +210,7 @@ def bench_training(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_r
     return res
 
 
-def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = False):
+def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = False, prepared: bool = False):
     """Config 4: serial (one lane, micro-batches one after the other) vs pipelined (one lane each)."""
     wl = synth.config_vgg16_pipeline(micro_batch)
     layers = wl.layers
@@ -211,6 +227,8 @@ def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_r
         xs.append(dealer.share(g, X))
         torch.cuda.synchronize()
         pipeline.preopen_weights(lanes[m], states[m])
+        if prepared:
+            pipeline.prepare_layers(lanes[m], layers, states[m])
     res = {}
     for mode in ("serial", "pipelined"):
         best = None
@@ -312,17 +330,17 @@ def main(argv):
             wl = make()
             name, rows = bench_layers(wl.index, workload=wl)
             print(f"== {name}")
-            tot_lin = tot_relu = tot_msb = 0.0
+            tot_lin = tot_relu = tot_msb = tot_prep = 0.0
             for r in rows:
                 line = (f"  {r['layer']:16s} x{r['repeat']:<2d} {r['gemm']:22s} call {r['call_ms']:8.3f} ms "
-                        f"{r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s  mfma {100 * r['mfma_frac']:5.1f}%")
-                tot_lin += r['call_ms'] * r['repeat']
+                        f"{r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s  prepared {r['prepared_call_ms']:7.3f} ms  mfma {100 * r['mfma_frac']:5.1f}%")
+                tot_lin += r['call_ms'] * r['repeat']; tot_prep += r['prepared_call_ms'] * r['repeat']
                 if "relu_ms" in r:
                     line += (f"  | relu {r['relu_n']:9d} el {r['relu_ms']:7.3f} ms hbm {100 * r['hbm_frac']:5.1f}%"
                              f"  | sign-only {r['msb_ms']:7.3f} ms hbm {100 * r['msb_hbm_frac']:5.1f}%")
                     tot_relu += r['relu_ms'] * r['repeat']; tot_msb += r['msb_ms'] * r['repeat']
                 print(line, flush=True)
-            print(f"  sum over layers (x multiplicity): linear {tot_lin:.2f} ms, ReLU {tot_relu:.2f} ms whole-word / "
+            print(f"  sum over layers (x multiplicity): linear {tot_lin:.2f} ms ({tot_prep:.2f} ms on prepared planes), ReLU {tot_relu:.2f} ms whole-word / "
                   f"{tot_msb:.2f} ms sign-only", flush=True)
         return
     if argv and argv[0] == "train":
@@ -342,18 +360,20 @@ def main(argv):
             # both roofs of the GEMM kernel; '*' marks the one that binds (the larger fraction)
             mf, hf = 100 * r['mfma_frac'], 100 * r['gemm_hbm_frac']
             line = (f"  {r['layer']:10s} {r['gemm']:22s} call {r['call_ms']:8.3f} ms  {r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s"
+                    f"  prepared {r['prepared_call_ms']:7.3f} ms"
                     f"  kernel {r['kernel_ms']:8.3f} ms (min {r['kernel_min_ms']:.3f})  mfma {mf:5.1f}%{'*' if mf >= hf else ' '} hbm {hf:5.1f}%{'*' if hf > mf else ' '}")
-            tot['lin'] += r['call_ms']
+            tot['lin'] += r['call_ms']; tot['prep'] = tot.get('prep', 0.0) + r['prepared_call_ms']
             if "relu_ms" in r:
                 tot['relu'] += r['relu_ms']; tot['msb'] += r['msb_ms']
                 line += f"  | relu {r['relu_n']:9d} el {r['relu_ms']:7.3f} ms {r['relu_elems_per_s'] / 1e9:5.2f} G/s hbm {100 * r['hbm_frac']:5.1f}%"
                 line += f"  | sign-only {r['msb_ms']:7.3f} ms {r['msb_elems_per_s'] / 1e9:5.2f} G/s hbm {100 * r['msb_hbm_frac']:5.1f}%"
             print(line, flush=True)
-        print(f"  totals: linear calls {tot['lin']:.3f} ms, ReLU {tot['relu']:.3f} ms whole-word / {tot['msb']:.3f} ms sign-only", flush=True)
+        print(f"  totals: linear calls {tot['lin']:.3f} ms ({tot['prep']:.3f} ms on prepared planes), ReLU {tot['relu']:.3f} ms whole-word / {tot['msb']:.3f} ms sign-only", flush=True)
         if idx == 4:
-            for packed in (False, True):
-                p = bench_pipeline(packed_relu=packed)
-                print(f"  inter-batch pipeline, batch 128 = 4 x 32, {'sign-only packed' if packed else 'whole-word'} ReLU: "
+            for packed, prepared in ((False, False), (True, False), (True, True)):
+                p = bench_pipeline(packed_relu=packed, prepared=prepared)
+                print(f"  inter-batch pipeline, batch 128 = 4 x 32, {'sign-only packed' if packed else 'whole-word'} ReLU"
+                      f"{', prepared planes' if prepared else ''}: "
                       f"serial {p['serial']['ms']:.2f} ms ({p['serial']['images_per_s']:.0f} img/s), "
                       f"pipelined {p['pipelined']['ms']:.2f} ms ({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)
         print(json.dumps({"config": idx, "layers": rows}), file=sys.stderr)

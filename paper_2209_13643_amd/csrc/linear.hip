@@ -199,18 +199,32 @@ int check_shape(const LinearShape& s)
 // The whole secure linear layer.  See mpc_beaver_matmul in the public header.
 int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
                   mpc_cshare a, mpc_cshare b, mpc_cshare cc, mpc_share z,
-                  const u64* f_public, int n_chunks, int flags, const u64* x_public = nullptr)
+                  const u64* f_public, int n_chunks, int flags, const u64* x_public = nullptr,
+                  const u8* prep_right = nullptr, const u8* prep_left = nullptr)
 {
     if (!c) return MPC_EINVAL;
     MPC_TRY(check_shape(s));
     if (n_chunks < 1) return MPC_EINVAL;
+    // prepared planes: digit planes of the input-independent operands, recoded ahead of time
+    const bool skip_right = prep_right != nullptr, skip_left = prep_left != nullptr;
     for (int i = 0; i < 2; ++i) {
-        if (!a.p[i] || !b.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
+        if (!a.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
+        if (!skip_right && !b.p[i]) return MPC_EINVAL;
         if (!x_public && !x.p[i]) return MPC_EINVAL;
-        if (!f_public && !y.p[i]) return MPC_EINVAL;
+        if (!skip_right && !f_public && !y.p[i]) return MPC_EINVAL;
     }
+    if ((skip_right && ((uintptr_t)prep_right & 15)) || (skip_left && ((uintptr_t)prep_left & 15))) return MPC_EINVAL;
     LinearWs w = carve(c->ws, c->ws_bytes, s);
     if (!w.ok) return MPC_ENOMEM;
+    if (skip_right) {
+        const size_t rp = align_up(8 * s.R_plane * s.batch);
+        w.pr_f = const_cast<u8*>(prep_right); w.pr_b[0] = w.pr_f + rp; w.pr_b[1] = w.pr_f + 2 * rp;
+    }
+    if (skip_left) {
+        const size_t lp = align_up(8 * s.L_plane * s.batch);
+        w.pl_a[0] = const_cast<u8*>(prep_left); w.pl_a[1] = w.pl_a[0] + lp;
+    }
+    const bool have_f = f_public != nullptr || skip_right;     // the weight mask needs no exchange in this call
 
     hipStream_t P0 = c->s[0], P1 = c->s[1], Wr = c->s[2];
     hipStream_t P[2] = { P0, P1 };
@@ -236,7 +250,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
                 cp[ns] = CopySeg{ (const u8*)(w.se[i] + lo), (u8*)(w.re[1 - i] + lo), (hi - lo) * sizeof(u64), 0 };
                 ++ns;
             }
-            if (!f_public && ch == 0)
+            if (!have_f && ch == 0)
                 for (int i = 0; i < 2; ++i) {
                     sub[ns] = SubSeg{ y.p[i], b.p[i], w.sf[i], s.nw, 0 };
                     cp[ns] = CopySeg{ (const u8*)w.sf[i], (u8*)w.rf[1 - i], s.nw * sizeof(u64), 0 };
@@ -252,12 +266,18 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         const u64* lsrc[3] = { a.p[0], a.p[1], x_public ? x_public : w.se[0] };
         const u64* lsrc2[3] = { nullptr, nullptr, x_public ? nullptr : w.re[0] };
         u8* ldst[3] = { w.pl_a[0], w.pl_a[1], w.pl_e };
-        rr[0] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
-        rr[1] = recode_right(s, f0, f1, nullptr, w.pr_f);
-        rr[2] = recode_right(s, b.p[0], f0, f1, w.pr_b[0]);
-        MPC_TRY(launch_left(c, P0, s, 3, lsrc, lsrc2, ldst));
-        MPC_TRY(launch_recode_multi(c, P0, rr, 3));
-        if (two_phase && f_public) {
+        if (skip_left) {
+            MPC_TRY(launch_left(c, P0, s, 1, lsrc + 2, lsrc2 + 2, ldst + 2));
+        } else {
+            MPC_TRY(launch_left(c, P0, s, 3, lsrc, lsrc2, ldst));
+        }
+        if (!skip_right) {
+            rr[0] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
+            rr[1] = recode_right(s, f0, f1, nullptr, w.pr_f);
+            rr[2] = recode_right(s, b.p[0], f0, f1, w.pr_b[0]);
+            MPC_TRY(launch_recode_multi(c, P0, rr, 3));
+        }
+        if (two_phase && have_f) {
             g.nseg = 1;
             for (int i = 0; i < 2; ++i) {
                 g.seg[i][0] = make_seg(s, w.pl_a[i], w.pr_f);
@@ -286,7 +306,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
     }
 
     // -- Alg. 1 / Alg. 3, masking step: mask and start the exchange, chunk by chunk
-    if (!f_public) {
+    if (!have_f) {
         for (int i = 0; i < 2; ++i) {
             MPC_TRY(launch_sub(c, P[i], y.p[i], b.p[i], w.sf[i], s.nw));
             MPC_TRY(chain(c, P[i], Wr));
@@ -312,19 +332,21 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
     const u64* e_src2 = x_public ? nullptr : w.re[0];
 
     // -- digit planes that do not depend on the exchange: [a_i] (and b_1)
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2 && !skip_left; ++i)
         MPC_TRY(launch_left1(c, P[i], s, a.p[i], nullptr, w.pl_a[i]));
-    MPC_TRY(launch_recode(c, P1, recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1])));
+    if (!skip_right) MPC_TRY(launch_recode(c, P1, recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1])));
 
     GemmArgs g{};
     fill_geom(s, w, g);
     g.nparty = 2;
 
-    if (two_phase && f_public) {
+    if (two_phase && have_f) {
         // Alg. 3, first product: epsilon is already here; z_i = Conv([a_i], epsilon)
         // runs while the masked inputs are still crossing the wire.
-        MPC_TRY(launch_recode(c, P0, recode_right(s, f_public, nullptr, nullptr, w.pr_f)));
-        MPC_TRY(launch_recode(c, P0, recode_right(s, b.p[0], f_public, nullptr, w.pr_b[0])));
+        if (!skip_right) {
+            MPC_TRY(launch_recode(c, P0, recode_right(s, f_public, nullptr, nullptr, w.pr_f)));
+            MPC_TRY(launch_recode(c, P0, recode_right(s, b.p[0], f_public, nullptr, w.pr_b[0])));
+        }
         MPC_TRY(chain(c, P1, P0));
         g.nseg = 1;
         for (int i = 0; i < 2; ++i) {
@@ -347,7 +369,9 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         // [e | a_i] x [b_i (+ f for party 0) ; f] per party.
         MPC_TRY(chain(c, Wr, P0));
         MPC_TRY(launch_left1(c, P0, s, e_src, e_src2, w.pl_e));
-        if (f_public) {
+        if (skip_right) {
+            // the right-operand planes were recoded ahead of time
+        } else if (f_public) {
             MPC_TRY(launch_recode(c, P0, recode_right(s, f_public, nullptr, nullptr, w.pr_f)));
             MPC_TRY(launch_recode(c, P0, recode_right(s, b.p[0], f_public, nullptr, w.pr_b[0])));
         } else {
@@ -367,6 +391,41 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
     prof_end(c, MPC_PROF_LINEAR, pi, P0);
     // party 1's output was produced by the joint launch on party 0's stream
     MPC_TRY(chain(c, P0, P1));
+    return MPC_OK;
+}
+
+// Digit planes of the input-independent operands of a layer, recoded once:
+// right = [f | b_0 + f | b_1] (needs the opened weight mask f), left = [a_0 | a_1].
+void prepared_sizes(const LinearShape& s, size_t* right, size_t* left)
+{
+    if (right) *right = 3 * align_up(8 * s.R_plane * s.batch);
+    if (left) *left = 2 * align_up(8 * s.L_plane * s.batch);
+}
+
+int prepare_planes(mpc_ctx* c, const LinearShape& s, mpc_cshare a, mpc_cshare b, const u64* f_public,
+                   u8* right, u8* left)
+{
+    if (!c || (!right && !left)) return MPC_EINVAL;
+    MPC_TRY(check_shape(s));
+    if (right && (!f_public || !b.p[0] || !b.p[1] || ((uintptr_t)right & 15))) return MPC_EINVAL;
+    if (left && (!a.p[0] || !a.p[1] || ((uintptr_t)left & 15))) return MPC_EINVAL;
+    hipStream_t P0 = c->s[0];
+    MPC_TRY(lane_join(c));
+    if (left) {
+        const size_t lp = align_up(8 * s.L_plane * s.batch);
+        const u64* src[2] = { a.p[0], a.p[1] }; const u64* src2[2] = { nullptr, nullptr };
+        u8* dst[2] = { left, left + lp };
+        MPC_TRY(launch_left(c, P0, s, 2, src, src2, dst));
+    }
+    if (right) {
+        const size_t rp = align_up(8 * s.R_plane * s.batch);
+        RecodeArgs rr[3];
+        rr[0] = recode_right(s, f_public, nullptr, nullptr, right);
+        rr[1] = recode_right(s, b.p[0], f_public, nullptr, right + rp);
+        rr[2] = recode_right(s, b.p[1], nullptr, nullptr, right + 2 * rp);
+        MPC_TRY(launch_recode_multi(c, P0, rr, 3));
+    }
+    MPC_TRY(chain(c, P0, c->s[1]));
     return MPC_OK;
 }
 
@@ -415,6 +474,66 @@ int mpc_beaver_matmul(mpc_ctx* ctx, mpc_cshare x, mpc_cshare y, mpc_cshare a, mp
 {
     if (M <= 0 || K <= 0 || N <= 0 || batch <= 0) return MPC_EINVAL;
     return beaver_linear(ctx, shape_matmul(M, K, N, batch, flags), x, y, a, b, c, z, f_public, n_chunks, flags);
+}
+
+int mpc_matmul_prepared_bytes(int M, int K, int N, int batch, size_t* right, size_t* left)
+{
+    if (M <= 0 || K <= 0 || N <= 0 || batch <= 0) return MPC_EINVAL;
+    LinearShape s = shape_matmul(M, K, N, batch);
+    MPC_TRY(check_shape(s));
+    prepared_sizes(s, right, left);
+    return MPC_OK;
+}
+
+int mpc_conv2d_prepared_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride,
+                              size_t* right, size_t* left)
+{
+    if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
+        return MPC_EINVAL;
+    LinearShape s = shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride);
+    MPC_TRY(check_shape(s));
+    prepared_sizes(s, right, left);
+    return MPC_OK;
+}
+
+int mpc_matmul_prepare(mpc_ctx* ctx, mpc_cshare a, mpc_cshare b, const uint64_t* f_public,
+                       void* right_planes, void* left_planes, int M, int K, int N, int batch, int flags)
+{
+    if (M <= 0 || K <= 0 || N <= 0 || batch <= 0) return MPC_EINVAL;
+    return prepare_planes(ctx, shape_matmul(M, K, N, batch, flags), a, b, f_public, (u8*)right_planes, (u8*)left_planes);
+}
+
+int mpc_conv2d_prepare(mpc_ctx* ctx, mpc_cshare a, mpc_cshare b, const uint64_t* f_public,
+                       void* right_planes, void* left_planes,
+                       int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
+        return MPC_EINVAL;
+    return prepare_planes(ctx, shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride), a, b, f_public,
+                          (u8*)right_planes, (u8*)left_planes);
+}
+
+int mpc_beaver_matmul_prepared(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_cshare c, mpc_share z,
+                               const void* right_planes, const void* left_planes,
+                               int M, int K, int N, int batch, int n_chunks, int flags)
+{
+    if (M <= 0 || K <= 0 || N <= 0 || batch <= 0 || !right_planes) return MPC_EINVAL;
+    const mpc_cshare none = { { nullptr, nullptr } };
+    return beaver_linear(ctx, shape_matmul(M, K, N, batch, flags), x, none, a, none, c, z, nullptr, n_chunks, flags,
+                         nullptr, (const u8*)right_planes, (const u8*)left_planes);
+}
+
+int mpc_conv2d_prepared(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_cshare c, mpc_share z,
+                        const void* right_planes, const void* left_planes,
+                        int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride,
+                        int n_chunks, int flags)
+{
+    if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0 ||
+        !right_planes || (flags & (MPC_TRANS_X | MPC_TRANS_Y)))
+        return MPC_EINVAL;
+    const mpc_cshare none = { { nullptr, nullptr } };
+    return beaver_linear(ctx, shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride), x, none, a, none, c, z,
+                         nullptr, n_chunks, flags, nullptr, (const u8*)right_planes, (const u8*)left_planes);
 }
 
 size_t mpc_conv2d_grad_x_workspace_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)

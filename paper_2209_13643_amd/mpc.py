@@ -50,6 +50,8 @@ EXPORTS = [
     "mpc_ring_conv2d_grad_x", "mpc_ring_conv2d_grad_w",
     "mpc_maxpool2x2_signs", "mpc_maxpool_backward_workspace_bytes", "mpc_maxpool2x2_backward",
     "mpc_ctx_set_adder", "mpc_ctx_set_exchange", "mpc_ctx_profile_samples", "mpc_add",
+    "mpc_matmul_prepared_bytes", "mpc_conv2d_prepared_bytes", "mpc_matmul_prepare", "mpc_conv2d_prepare",
+    "mpc_beaver_matmul_prepared", "mpc_conv2d_prepared",
 ]
 
 _lib = None
@@ -67,6 +69,12 @@ def lib():
     L.mpc_ctx_destroy.argtypes = [c_void_p]
     L.mpc_ctx_set_adder.argtypes = [c_void_p, c_int]
     L.mpc_add.argtypes = [c_void_p, CShare, CShare, CShare, c_size_t]
+    L.mpc_matmul_prepared_bytes.argtypes = [c_int] * 4 + [POINTER(c_size_t)] * 2
+    L.mpc_conv2d_prepared_bytes.argtypes = [c_int] * 9 + [POINTER(c_size_t)] * 2
+    L.mpc_matmul_prepare.argtypes = [c_void_p, CShare, CShare, _P64, c_void_p, c_void_p] + [c_int] * 5
+    L.mpc_conv2d_prepare.argtypes = [c_void_p, CShare, CShare, _P64, c_void_p, c_void_p] + [c_int] * 9
+    L.mpc_beaver_matmul_prepared.argtypes = [c_void_p, CShare, CShare, CShare, CShare, c_void_p, c_void_p] + [c_int] * 6
+    L.mpc_conv2d_prepared.argtypes = [c_void_p, CShare, CShare, CShare, CShare, c_void_p, c_void_p] + [c_int] * 11
     L.mpc_ctx_profile_samples.argtypes = [c_void_p, c_int, POINTER(ctypes.c_double), c_int, POINTER(c_int)]
     L.mpc_ctx_set_exchange.argtypes = [c_void_p, c_int]
     L.mpc_ctx_set_streams.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
@@ -313,6 +321,53 @@ class Lane:
         z = out if out is not None else (torch.empty_like(c[0]), torch.empty_like(c[1]))
         self._check(lib().mpc_conv2d(self._h, _share(x), _share(w), _share(a), _share(b), _share(c), _share(z),
                                      B, H, W, Cin, Cout, KH, KW, pad, stride, _p64(f_public), n_chunks, flags))
+        return z
+
+    # -- prepared layers: digit planes of the input-independent operands, recoded once
+    def _planes(self, nbytes):
+        return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=self.device)
+
+    def prepare_matmul(self, a, b, f_public, flags=0, left=True):
+        """Returns (right_planes, left_planes or None) for beaver_matmul_prepared."""
+        shp = a[0].shape
+        batch = 1 if len(shp) == 2 else shp[0]
+        M, K = (shp[-1], shp[-2]) if flags & MPC_TRANS_X else (shp[-2], shp[-1])
+        N = b[0].shape[-2] if flags & MPC_TRANS_Y else b[0].shape[-1]
+        r, l = c_size_t(), c_size_t()
+        self._check(lib().mpc_matmul_prepared_bytes(M, K, N, batch, byref(r), byref(l)))
+        right = self._planes(r.value); lp = self._planes(l.value) if left else None
+        self._check(lib().mpc_matmul_prepare(self._h, _share(a), _share(b), _p64(f_public), right.data_ptr(),
+                                             lp.data_ptr() if left else None, M, K, N, batch, flags))
+        return right, lp
+
+    def beaver_matmul_prepared(self, x, a, c, right, left=None, n_chunks=1, flags=MPC_TRUNCATE, out=None):
+        shp = a[0].shape
+        batch = 1 if len(shp) == 2 else shp[0]
+        M, K = (shp[-1], shp[-2]) if flags & MPC_TRANS_X else (shp[-2], shp[-1])
+        N = c[0].shape[-1]
+        self.reserve(lib().mpc_matmul_workspace_bytes(M, K, N, batch))
+        z = out if out is not None else (torch.empty_like(c[0]), torch.empty_like(c[1]))
+        self._check(lib().mpc_beaver_matmul_prepared(self._h, _share(x), _share(a), _share(c), _share(z), right.data_ptr(),
+                                                     left.data_ptr() if left is not None else None,
+                                                     M, K, N, batch, n_chunks, flags))
+        return z
+
+    def prepare_conv2d(self, a, b, f_public, pad, stride, left=True):
+        B, H, W, Cin = a[0].shape; KH, KW, _, Cout = b[0].shape
+        r, l = c_size_t(), c_size_t()
+        self._check(lib().mpc_conv2d_prepared_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride, byref(r), byref(l)))
+        right = self._planes(r.value); lp = self._planes(l.value) if left else None
+        self._check(lib().mpc_conv2d_prepare(self._h, _share(a), _share(b), _p64(f_public), right.data_ptr(),
+                                             lp.data_ptr() if left else None, B, H, W, Cin, Cout, KH, KW, pad, stride))
+        return right, lp
+
+    def conv2d_prepared(self, x, a, c, right, left, KH, KW, pad, stride, n_chunks=1, flags=MPC_TRUNCATE, out=None):
+        B, H, W, Cin = a[0].shape; Cout = c[0].shape[-1]
+        self.reserve(lib().mpc_conv2d_workspace_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride))
+        z = out if out is not None else (torch.empty_like(c[0]), torch.empty_like(c[1]))
+        self._check(lib().mpc_conv2d_prepared(self._h, _share(x), _share(a), _share(c), _share(z), right.data_ptr(),
+                                              left.data_ptr() if left is not None else None,
+                                              B, H, W, Cin, Cout, KH, KW, pad, stride, n_chunks, flags))
         return z
 
     def conv2d_grad_x(self, g, w, a, b, c, pad, stride=1, f_public=None, n_chunks=1, flags=MPC_TRUNCATE, out=None):

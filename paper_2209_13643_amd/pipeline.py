@@ -30,6 +30,8 @@ class LayerState:
     pool1: dict | None = None
     pool2: dict | None = None
     packed: bool = False          # ReLU / pool material in the packed layout of mpc_relu_msb
+    right: torch.Tensor | None = None   # prepared digit planes of f, b_0 + f, b_1 (prepare_layers)
+    left: torch.Tensor | None = None    # prepared digit planes of a_0, a_1
 
 
 def with_batch(layers, batch: int):
@@ -91,16 +93,37 @@ def preopen_weights(lane: mpc.Lane, states):
     lane.sync()
 
 
+def prepare_layers(lane: mpc.Lane, layers, states):
+    """Recode the input-independent operands of every layer once (the triples' [a_i] and, from the
+    opened weight mask, f, b_0 + f, b_1) and keep their digit planes resident: run_layer then only
+    masks, exchanges and recodes the activation.  Opens the weight masks first if that was not done."""
+    if any(st.f_public is None for st in states):
+        preopen_weights(lane, states)
+    for L, st in zip(layers, states):
+        if isinstance(L, synth.Conv):
+            st.right, st.left = lane.prepare_conv2d(st.a, st.b, st.f_public, L.pad, L.stride)
+        else:
+            st.right, st.left = lane.prepare_matmul(st.a, st.b, st.f_public)
+    lane.sync()
+
+
 def run_layer(lane: mpc.Lane, L, st: LayerState, x, n_chunks=1, relu_chunks=0, flags=mpc.MPC_TRUNCATE):
     """One secure layer on one lane: linear (+ ReLU) (+ 2x2 max-pool).  Returns output shares."""
     y_arg = None if st.f_public is not None else st.w
     if isinstance(L, synth.Conv):
         xs = (x[0].view(L.B, L.H, L.W, L.Cin), x[1].view(L.B, L.H, L.W, L.Cin))
-        z = lane.conv2d(xs, y_arg, st.a, st.b, st.c, L.pad, L.stride, f_public=st.f_public,
-                        n_chunks=n_chunks, flags=flags)
+        if st.right is not None:
+            z = lane.conv2d_prepared(xs, st.a, st.c, st.right, st.left, L.KH, L.KW, L.pad, L.stride,
+                                     n_chunks=n_chunks, flags=flags)
+        else:
+            z = lane.conv2d(xs, y_arg, st.a, st.b, st.c, L.pad, L.stride, f_public=st.f_public,
+                            n_chunks=n_chunks, flags=flags)
     else:
         xs = (x[0].view(L.M, L.K), x[1].view(L.M, L.K))
-        z = lane.beaver_matmul(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public, n_chunks=n_chunks, flags=flags)
+        if st.right is not None:
+            z = lane.beaver_matmul_prepared(xs, st.a, st.c, st.right, st.left, n_chunks=n_chunks, flags=flags)
+        else:
+            z = lane.beaver_matmul(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public, n_chunks=n_chunks, flags=flags)
     outs = [z]
     if st.relu is not None:
         z = lane.relu(z, st.relu, n_chunks=relu_chunks, packed=st.packed); outs.append(z)

@@ -77,7 +77,7 @@ def test_vgg16_every_layer_matches_oracle(mods, dealt, packed_relu):
 
 
 @pytest.mark.parametrize("mode", ["serial-3stream", "pipelined", "pipelined-preopened", "pipelined-two-phase-chunked",
-                                  "pipelined-packed-relu"])
+                                  "pipelined-packed-relu", "pipelined-prepared-planes"])
 def test_pipeline_invariance(mods, dealt, mode):
     mpc, pipeline = mods
     layers, mbs = dealt
@@ -93,6 +93,9 @@ def test_pipeline_invariance(mods, dealt, mode):
     if mode in ("pipelined-preopened", "pipelined-two-phase-chunked"):
         for ln, sts in zip(lanes, states):
             pipeline.preopen_weights(ln, sts)
+    if mode == "pipelined-prepared-planes":
+        for ln, sts in zip(lanes, states):
+            pipeline.prepare_layers(ln, layers, sts)
     if mode == "pipelined-two-phase-chunked":
         kw = dict(n_chunks=3, relu_chunks=3, flags=mpc.MPC_TRUNCATE | mpc.MPC_TWO_PHASE)
     keep = []

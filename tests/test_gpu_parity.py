@@ -329,6 +329,36 @@ def test_sub_then_open_gives_weight_mask(mpc, lane):
     assert np.array_equal(mpc.to_host(f), oracle.open_shares(ws[0] - bs[0], ws[1] - bs[1]))
 
 
+@pytest.mark.parametrize("shape", [(5, 7, 3), (64, 256, 128), (130, 70, 200)])
+@pytest.mark.parametrize("left", [True, False])
+def test_beaver_matmul_prepared_planes(mpc, lane, shape, left):
+    """Planes of [a_i], f, b_0 + f, b_1 recoded ahead of time: the same shares as the plain call."""
+    M, K, N = shape
+    print(f"prepared matmul {shape} left={left}", flush=True)
+    d = deal_matmul(np.random.default_rng(M * K + N), M, K, N, x_std=1.0, w_std=0.1)
+    f_public = mpc.to_device((d["y"][0] - d["b"][0]) + (d["y"][1] - d["b"][1]))
+    a, b, c = dev(mpc, d["a"]), dev(mpc, d["b"]), dev(mpc, d["c"])
+    right, lp = lane.prepare_matmul(a, b, f_public, left=left)
+    for _ in range(2):                                   # the planes are reusable
+        z = lane.beaver_matmul_prepared(dev(mpc, d["x"]), a, c, right, lp)
+        assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "prepared matmul")
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv2d_prepared_planes(mpc, lane, case):
+    B, H, W, Cin, Cout, KH, KW, pad, stride = case
+    print(f"prepared conv {case}", flush=True)
+    d = deal_conv(np.random.default_rng(sum(case) + 3), B, H, W, Cin, Cout, KH, KW, pad, stride, x_std=1.0, w_std=0.1)
+    f_public = mpc.to_device((d["y"][0] - d["b"][0]) + (d["y"][1] - d["b"][1]))
+    a, b, c = dev(mpc, d["a"]), dev(mpc, d["b"]), dev(mpc, d["c"])
+    right, lp = lane.prepare_conv2d(a, b, f_public, pad, stride)
+    z = lane.conv2d_prepared(dev(mpc, d["x"]), a, c, right, lp, KH, KW, pad, stride)
+    assert_shares_equal(host(mpc, lane, z), oracle_conv(d), "prepared conv")
+    z = lane.conv2d_prepared(dev(mpc, d["x"]), a, c, right, None, KH, KW, pad, stride, n_chunks=3,
+                             flags=mpc.MPC_TRUNCATE | mpc.MPC_TWO_PHASE)
+    assert_shares_equal(host(mpc, lane, z), oracle_conv(d), "prepared conv, two-phase, chunked")
+
+
 def test_add_is_the_local_sum(mpc, lane):
     print("add", flush=True)
     rng = np.random.default_rng(68)
