@@ -119,7 +119,8 @@ int mpc_ctx_profile_reset(mpc_ctx* ctx);
 enum { MPC_ADDER_KOGGE_STONE = 0, MPC_ADDER_TREE = 1 };
 int mpc_ctx_set_adder(mpc_ctx* ctx, int adder);
 
-/* How the secure ReLU's rounds exchange their masked words.
+/* How masked words are exchanged (the rounds of the secure ReLU, and the masked
+ * operands of the Beaver products).
  * MPC_EXCHANGE_COPY (default): a copy kernel on the wire stream moves every
  *   party's send buffer into the other party's receive buffer after each round.
  * MPC_EXCHANGE_PUT: the kernel that forms the masked words also stores them

@@ -188,7 +188,7 @@ int launch_poolbwd_scatter(mpc_ctx* c, hipStream_t st, const PoolBwdArgs& q);
 
 // several element-wise jobs in one launch (single-queue lanes)
 constexpr int kMaxSegs = 4;
-struct SubSeg { const u64* x; const u64* a; u64* out; size_t n; int vec; };
+struct SubSeg { const u64* x; const u64* a; u64* out; size_t n; int vec; u64* out2; };   // out2: optional second destination
 struct SubBatch { SubSeg s[kMaxSegs]; };
 struct CopySeg { const u8* src; u8* dst; size_t bytes; int vec; };
 struct CopyBatch { CopySeg s[kMaxSegs]; };

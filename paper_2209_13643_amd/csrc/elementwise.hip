@@ -332,6 +332,9 @@ __global__ __launch_bounds__(kThreads) void k_recode_multi(RecodeBatch rb)
 }
 
 // Several element-wise subtractions / copies in one launch: blockIdx.y = segment.
+// PUT: every difference is also stored into out2, the peer's receive buffer
+// (exchange by remote store: the mask kernel is the sender).
+template <bool PUT>
 __global__ __launch_bounds__(kThreads) void k_sub_multi(SubBatch sb)
 {
     const SubSeg& q = sb.s[blockIdx.y];
@@ -341,14 +344,23 @@ __global__ __launch_bounds__(kThreads) void k_sub_multi(SubBatch sb)
         const u64x2* x2 = reinterpret_cast<const u64x2*>(q.x);
         const u64x2* y2 = reinterpret_cast<const u64x2*>(q.a);
         u64x2* o2 = reinterpret_cast<u64x2*>(q.out);
+        u64x2* p2 = reinterpret_cast<u64x2*>(q.out2);
         for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n2; i += stride) {
             u64x2 p = x2[i], r = y2[i];
             p.a -= r.a; p.b -= r.b;
             o2[i] = p;
+            if constexpr (PUT) p2[i] = p;
         }
-        if ((q.n & 1) && blockIdx.x == 0 && threadIdx.x == 0) q.out[q.n - 1] = q.x[q.n - 1] - q.a[q.n - 1];
+        if ((q.n & 1) && blockIdx.x == 0 && threadIdx.x == 0) {
+            q.out[q.n - 1] = q.x[q.n - 1] - q.a[q.n - 1];
+            if constexpr (PUT) q.out2[q.n - 1] = q.out[q.n - 1];
+        }
     } else {
-        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < q.n; i += stride) q.out[i] = q.x[i] - q.a[i];
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < q.n; i += stride) {
+            const u64 v = q.x[i] - q.a[i];
+            q.out[i] = v;
+            if constexpr (PUT) q.out2[i] = v;
+        }
     }
 }
 
@@ -468,10 +480,13 @@ int launch_sub_multi(mpc_ctx* c, hipStream_t st, const SubSeg* segs, int count)
     SubBatch sb{}; size_t nmax = 0;
     for (int i = 0; i < count; ++i) {
         sb.s[i] = segs[i];
-        sb.s[i].vec = aligned16(segs[i].x) && aligned16(segs[i].a) && aligned16(segs[i].out);
+        sb.s[i].vec = aligned16(segs[i].x) && aligned16(segs[i].a) && aligned16(segs[i].out) &&
+                      (!segs[i].out2 || aligned16(segs[i].out2));
         if (segs[i].n > nmax) nmax = segs[i].n;
+        if ((segs[i].out2 != nullptr) != (segs[0].out2 != nullptr)) return MPC_EINVAL;    // all or none
     }
-    hipLaunchKernelGGL(k_sub_multi, dim3(grid_for(nmax / 2 + 1), count), dim3(kThreads), 0, st, sb);
+    if (segs[0].out2) hipLaunchKernelGGL(k_sub_multi<true>, dim3(grid_for(nmax / 2 + 1), count), dim3(kThreads), 0, st, sb);
+    else              hipLaunchKernelGGL(k_sub_multi<false>, dim3(grid_for(nmax / 2 + 1), count), dim3(kThreads), 0, st, sb);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
 }

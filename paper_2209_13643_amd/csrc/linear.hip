@@ -246,19 +246,20 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
             if (hi <= lo) continue;
             SubSeg sub[4]; CopySeg cp[4]; int ns = 0;
             for (int i = 0; i < 2 && !x_public; ++i) {
-                sub[ns] = SubSeg{ x.p[i] + lo, a.p[i] + lo, w.se[i] + lo, hi - lo, 0 };
+                sub[ns] = SubSeg{ x.p[i] + lo, a.p[i] + lo, w.se[i] + lo, hi - lo, 0,
+                                  c->exchange_put ? w.re[1 - i] + lo : nullptr };
                 cp[ns] = CopySeg{ (const u8*)(w.se[i] + lo), (u8*)(w.re[1 - i] + lo), (hi - lo) * sizeof(u64), 0 };
                 ++ns;
             }
             if (!have_f && ch == 0)
                 for (int i = 0; i < 2; ++i) {
-                    sub[ns] = SubSeg{ y.p[i], b.p[i], w.sf[i], s.nw, 0 };
+                    sub[ns] = SubSeg{ y.p[i], b.p[i], w.sf[i], s.nw, 0, c->exchange_put ? w.rf[1 - i] : nullptr };
                     cp[ns] = CopySeg{ (const u8*)w.sf[i], (u8*)w.rf[1 - i], s.nw * sizeof(u64), 0 };
                     ++ns;
                 }
             if (ns == 0) continue;                           // both operands were opened ahead of time
-            MPC_TRY(launch_sub_multi(c, P0, sub, ns));       // Alg. 1: mask
-            MPC_TRY(launch_copy_multi(c, P0, cp, ns));       // Alg. 1: exchange
+            MPC_TRY(launch_sub_multi(c, P0, sub, ns));       // Alg. 1: mask (and, by remote store, send)
+            if (!c->exchange_put) MPC_TRY(launch_copy_multi(c, P0, cp, ns));       // Alg. 1: exchange
         }
         const u64* f0 = f_public ? f_public : w.sf[0];
         const u64* f1 = f_public ? nullptr : w.rf[0];
