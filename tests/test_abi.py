@@ -68,3 +68,43 @@ def test_null_context_is_rejected(lib):
     assert lib.mpc_ctx_create(None, 0, 16) == -1
     h = ctypes.c_void_p()
     assert lib.mpc_ctx_create(ctypes.byref(h), 0, 99) == -1              # frac_bits out of range
+
+
+def test_packed_triple_layout_size(lib):
+    """mpc_relu_packed_words against the layout as the header states it: triple 0 on plain
+    words, triple t = 1..11 on ceil64(n) / 2^(l+1) words with l = (t-1)/2, every segment
+    padded to a multiple of four words."""
+    r4 = lambda v: (v + 3) // 4 * 4
+    for n in (1, 2, 63, 64, 65, 1000, 4096, 4097, 1 << 20, (1 << 21) + 5):
+        n64 = (n + 63) // 64 * 64
+        want = r4(n) + sum(r4(n64 >> ((t - 1) // 2 + 1)) for t in range(1, 12))
+        assert lib.mpc_relu_packed_words(n) == want, n
+    assert lib.mpc_relu_packed_words(0) == 0
+    assert lib.mpc_relu_msb_workspace_bytes(1 << 20) > 0 and lib.mpc_relu_msb_workspace_bytes(0) == 0
+    assert lib.mpc_maxpool_msb_workspace_bytes(1, 3, 4, 2) == 0
+
+
+def test_prepared_plane_sizes(lib):
+    """Three right and two left plane tensors, eight digit planes of [rows][K padded to 32] bytes each."""
+    r, l = ctypes.c_size_t(), ctypes.c_size_t()
+    M, K, N = 96, 100, 40
+    assert lib.mpc_matmul_prepared_bytes(M, K, N, 1, ctypes.byref(r), ctypes.byref(l)) == 0
+    kpad = (K + 31) // 32 * 32
+    up = lambda v: (v + 255) // 256 * 256
+    assert r.value == 3 * up(8 * N * kpad) and l.value == 2 * up(8 * M * kpad)
+    assert lib.mpc_matmul_prepared_bytes(M, K, N, 3, ctypes.byref(r), None) == 0 and r.value == 3 * up(3 * 8 * N * kpad)
+    assert lib.mpc_matmul_prepared_bytes(0, K, N, 1, ctypes.byref(r), ctypes.byref(l)) == -1
+    # conv: activation planes are not expanded by the filter taps (plus one zero row)
+    assert lib.mpc_conv2d_prepared_bytes(2, 8, 8, 16, 32, 3, 3, 1, 1, ctypes.byref(r), ctypes.byref(l)) == 0
+    assert l.value == 2 * up(8 * (2 * 8 * 8 + 1) * 16)
+    assert lib.mpc_conv2d_prepared_bytes(2, 8, 8, 16, 32, 3, 3, 1, 0, ctypes.byref(r), ctypes.byref(l)) == -1
+
+
+def test_gradient_and_elementwise_workspace_queries(lib):
+    assert lib.mpc_conv2d_grad_x_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 1) > 0
+    assert lib.mpc_conv2d_grad_x_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 2) == 0      # strided: no input-gradient path
+    assert lib.mpc_conv2d_grad_x_workspace_bytes(2, 8, 8, 3, 16, 3, 5, 1, 1) == 0      # non-square filter
+    assert lib.mpc_conv2d_grad_w_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 2) > 0
+    assert lib.mpc_mul_workspace_bytes(1000) >= 8 * 1000 * 8
+    assert lib.mpc_maxpool_backward_workspace_bytes(1, 4, 4, 2) > lib.mpc_mul_workspace_bytes(16)
+    assert lib.mpc_maxpool_backward_workspace_bytes(1, 4, 5, 2) == 0
