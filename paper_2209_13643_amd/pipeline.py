@@ -144,6 +144,24 @@ def forward(lane: mpc.Lane, layers, states, x, keep: list, **kw):
     return x
 
 
+def forward_interlinear(lane: mpc.Lane, wlane: mpc.Lane, layers, states, x, keep: list, **kw):
+    """Inter-linear pipeline across layers (Alg. 3, Sec. 4.1): the weight mask W - B of layer l+1 is
+    opened on a second lane while layer l computes; the compute lane waits (on the device) for that
+    opening only when it reaches layer l+1.  Same shares as forward()."""
+    def open_mask(st):
+        d = wlane.sub(st.w, st.b)
+        st.f_public = wlane.open(d)
+        keep.extend([d, st.f_public])
+    open_mask(states[0])
+    for li, (L, st) in enumerate(zip(layers, states)):
+        lane.wait_for(wlane)                       # this layer's mask has arrived
+        if li + 1 < len(layers):
+            open_mask(states[li + 1])              # next layer's mask travels while this layer computes
+        x = run_layer(lane, L, st, x, **kw)
+        keep.extend(run_layer.last_intermediates)
+    return x
+
+
 def forward_pipelined(lanes, layers, states_per_mb, xs, keep: list, **kw):
     """Inter-batch pipeline: micro-batch m on lanes[m]; layer-major issue order."""
     cur = list(xs)

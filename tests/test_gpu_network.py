@@ -111,6 +111,26 @@ def test_pipeline_invariance(mods, dealt, mode):
         ln.close()
 
 
+@pytest.mark.parametrize("queues", ["three-streams", "single-queue"])
+def test_interlinear_lookahead_across_layers(mods, dealt, queues):
+    """Alg. 3 across layers: each weight mask is opened one layer ahead on a second lane and the
+    compute lane waits for it on the device (mpc_ctx_wait); logits as in the oracle run."""
+    mpc, pipeline = mods
+    layers, mbs = dealt
+    print(f"inter-linear look-ahead, {queues}", flush=True)
+    lane, wlane = mpc.Lane(0), mpc.Lane(0)
+    if queues == "single-queue":
+        lane.use_single_queue(); wlane.use_single_queue()
+    mb = mbs[1]
+    states = [to_state(mpc, pipeline, st) for st in mb["states"]]
+    keep = []
+    out = pipeline.forward_interlinear(lane, wlane, layers, states, (mpc.to_device(mb["x"][0]), mpc.to_device(mb["x"][1])), keep)
+    lane.sync(); wlane.sync()
+    check(mpc, out, mb["want"][-1], "logits with one-layer-ahead weight masks")
+    assert all(st.f_public is not None for st in states)
+    lane.close(); wlane.close()
+
+
 @pytest.mark.parametrize("packed_relu", [False, True], ids=["whole-word-relu", "sign-only-packed-relu"])
 def test_vgg16_training_step_matches_oracle(mods, dealt, packed_relu):
     """Forward with the tape, backward through max-pool, ReLU, conv and dense layers, then
