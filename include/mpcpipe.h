@@ -240,12 +240,14 @@ int mpc_conv2d_prepared(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_cshare c, 
  *
  * mpc_conv2d_grad_x: gradient w.r.t. the input,
  *     gx[b][hi][wi][ci] = sum g[b][ho][wo][co] * w[kh][kw][ci][co]
- *   over all (ho, wo, kh, kw, co) with hi = ho + kh - pad, wi = wo + kw - pad.
+ *   over all (ho, wo, kh, kw, co) with hi = ho*s + kh - pad, wi = wo*s + kw - pad.
  *   g, a: [B][Ho][Wo][Cout] (output gradient and its mask); w, b: the forward
  *   filter layout [KH][KW][Cin][Cout]; c, gx: [B][H][W][Cin].  f_public: NULL
- *   or w - b as opened for the forward pass (same layout as w).  stride must
- *   be 1 and KH == KW (else MPC_EINVAL).  Runs as a convolution of g with the
- *   filter read in reverse tap order, padding KH - 1 - pad.
+ *   or w - b as opened for the forward pass (same layout as w).  KH == KW is
+ *   required (else MPC_EINVAL).  Runs as a stride-1 convolution of g with the
+ *   filter read in reverse tap order, padding KH - 1 - pad; for a strided
+ *   layer g and its mask are first scattered into a zero-filled grid with
+ *   stride-1 gaps (workspace grows by four such tensors).
  * mpc_conv2d_grad_w: gradient w.r.t. the filter,
  *     gw[kh][kw][ci][co] = sum_{b,ho,wo} x[b][ho*s+kh-pad][wo*s+kw-pad][ci] * g[b][ho][wo][co].
  *   x, a: [B][H][W][Cin] (the stored activation and the mask it was opened

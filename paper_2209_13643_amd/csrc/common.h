@@ -186,6 +186,10 @@ struct PoolBwdArgs {
 int launch_poolbwd_pairs(mpc_ctx* c, hipStream_t st, const PoolBwdArgs& q);
 int launch_poolbwd_scatter(mpc_ctx* c, hipStream_t st, const PoolBwdArgs& q);
 
+// scatter of up to four [B][Ho][Wo][C] tensors into zero-filled [B][Hd][Wd][C] grids at pixel (ho*stride, wo*stride)
+struct DilateArgs { const u64* src[4]; u64* dst[4]; int B, Ho, Wo, Hd, Wd, C, stride; };
+int launch_dilate(mpc_ctx* c, hipStream_t st, const DilateArgs& q);
+
 // several element-wise jobs in one launch (single-queue lanes)
 constexpr int kMaxSegs = 4;
 struct SubSeg { const u64* x; const u64* a; u64* out; size_t n; int vec; u64* out2; };   // out2: optional second destination

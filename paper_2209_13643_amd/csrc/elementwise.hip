@@ -322,6 +322,27 @@ __global__ __launch_bounds__(kThreads) void k_poolbwd_scatter(PoolBwdArgs q)
     }
 }
 
+// Zero-dilation for the input gradient of a strided convolution (blockIdx.y = tensor):
+// every destination word is written, a source word where its pixel is a multiple of the stride.
+__global__ __launch_bounds__(kThreads) void k_dilate(DilateArgs q)
+{
+    const u64* src = q.src[blockIdx.y]; u64* dst = q.dst[blockIdx.y];
+    if (!src) return;
+    const size_t total = (size_t)q.B * q.Hd * q.Wd * q.C;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < total; o += stride) {
+        const int ch = (int)(o % q.C); size_t t = o / q.C;
+        const int wd = (int)(t % q.Wd); t /= q.Wd;
+        const int hd = (int)(t % q.Hd); const int b = (int)(t / q.Hd);
+        u64 v = 0;
+        if (hd % q.stride == 0 && wd % q.stride == 0) {
+            const int ho = hd / q.stride, wo = wd / q.stride;
+            if (ho < q.Ho && wo < q.Wo) v = src[(((size_t)b * q.Ho + ho) * q.Wo + wo) * q.C + ch];
+        }
+        dst[o] = v;
+    }
+}
+
 // Several recodings in one launch: blockIdx.z = set * batch + batch item.
 __global__ __launch_bounds__(kThreads) void k_recode_multi(RecodeBatch rb)
 {
@@ -526,6 +547,14 @@ int launch_mul_mask(mpc_ctx* c, hipStream_t st, const MulArgs& q)
 int launch_mul_finish(mpc_ctx* c, hipStream_t st, const MulArgs& q)
 {
     hipLaunchKernelGGL(k_mul_finish, dim3(grid_for(q.n), 2), dim3(kThreads), 0, st, q);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+int launch_dilate(mpc_ctx* c, hipStream_t st, const DilateArgs& q)
+{
+    const size_t total = (size_t)q.B * q.Hd * q.Wd * q.C;
+    hipLaunchKernelGGL(k_dilate, dim3(grid_for(total), 4), dim3(kThreads), 0, st, q);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
 }

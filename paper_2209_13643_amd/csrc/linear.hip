@@ -60,6 +60,19 @@ LinearShape shape_conv_grad_x(int B, int H, int W, int Cin, int Cout, int KH, in
     return s;
 }
 
+// Strided convolutions: the input gradient is the stride-1 one of the output gradient
+// with stride-1 zeros between its pixels (and as many zero rows / columns at the far
+// edge as the forward pass left unused), so the same path serves after a scatter.
+struct DilatedGeom { int Ho, Wo, Hd, Wd; size_t words; };
+DilatedGeom dilated_geom(int B, int H, int W, int Cout, int KH, int KW, int pad, int stride)
+{
+    DilatedGeom d{};
+    d.Ho = (H + 2 * pad - KH) / stride + 1; d.Wo = (W + 2 * pad - KW) / stride + 1;
+    d.Hd = H + 2 * pad - KH + 1; d.Wd = W + 2 * pad - KW + 1;        // = (Ho-1)*stride + 1 + unused remainder
+    d.words = (size_t)B * d.Hd * d.Wd * Cout;
+    return d;
+}
+
 // Filter gradient: [KH*KW*Cin x B*Ho*Wo] (transposed im2col of x) times
 // [B*Ho*Wo x Cout] (the output gradient as it is stored).
 LinearShape shape_conv_grad_w(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
@@ -200,7 +213,7 @@ int check_shape(const LinearShape& s)
 int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
                   mpc_cshare a, mpc_cshare b, mpc_cshare cc, mpc_share z,
                   const u64* f_public, int n_chunks, int flags, const u64* x_public = nullptr,
-                  const u8* prep_right = nullptr, const u8* prep_left = nullptr)
+                  const u8* prep_right = nullptr, const u8* prep_left = nullptr, size_t ws_off = 0)
 {
     if (!c) return MPC_EINVAL;
     MPC_TRY(check_shape(s));
@@ -214,7 +227,8 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         if (!skip_right && !f_public && !y.p[i]) return MPC_EINVAL;
     }
     if ((skip_right && ((uintptr_t)prep_right & 15)) || (skip_left && ((uintptr_t)prep_left & 15))) return MPC_EINVAL;
-    LinearWs w = carve(c->ws, c->ws_bytes, s);
+    if (ws_off > c->ws_bytes) return MPC_ENOMEM;
+    LinearWs w = carve(c->ws ? c->ws + ws_off : nullptr, c->ws_bytes - ws_off, s);
     if (!w.ok) return MPC_ENOMEM;
     if (skip_right) {
         const size_t rp = align_up(8 * s.R_plane * s.batch);
@@ -430,11 +444,12 @@ int prepare_planes(mpc_ctx* c, const LinearShape& s, mpc_cshare a, mpc_cshare b,
     return MPC_OK;
 }
 
-int ring_product(mpc_ctx* c, const LinearShape& s, const u64* L, const u64* R, u64* Z)
+int ring_product(mpc_ctx* c, const LinearShape& s, const u64* L, const u64* R, u64* Z, size_t ws_off = 0)
 {
     if (!c || !L || !R || !Z) return MPC_EINVAL;
     MPC_TRY(check_shape(s));
-    LinearWs w = carve(c->ws, c->ws_bytes, s);
+    if (ws_off > c->ws_bytes) return MPC_ENOMEM;
+    LinearWs w = carve(c->ws ? c->ws + ws_off : nullptr, c->ws_bytes - ws_off, s);
     if (!w.ok) return MPC_ENOMEM;
     hipStream_t P0 = c->s[0];
     MPC_TRY(lane_join(c));
@@ -539,10 +554,12 @@ int mpc_conv2d_prepared(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_cshare c, 
 
 size_t mpc_conv2d_grad_x_workspace_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
 {
-    if (stride != 1 || KH != KW || KH <= 0 || pad < 0 || pad > KH - 1 || H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return 0;
+    if (stride <= 0 || KH != KW || KH <= 0 || pad < 0 || pad > KH - 1 || H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return 0;
     LinearShape s = shape_conv_grad_x(B, H, W, Cin, Cout, KH, KW, pad);
     if (check_shape(s) != MPC_OK) return 0;
-    return carve(nullptr, 0, s).bytes;
+    // a strided layer first scatters g_i and its mask a_i (both parties) into the dilated grid
+    const size_t extra = stride > 1 ? 4 * align_up(dilated_geom(B, H, W, Cout, KH, KW, pad, stride).words * sizeof(u64)) : 0;
+    return extra + carve(nullptr, 0, s).bytes;
 }
 
 size_t mpc_conv2d_grad_w_workspace_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
@@ -557,11 +574,26 @@ int mpc_conv2d_grad_x(mpc_ctx* ctx, mpc_cshare g, mpc_cshare w, mpc_cshare a, mp
                       mpc_share gx, int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride,
                       const uint64_t* f_public, int n_chunks, int flags)
 {
-    if (B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0) return MPC_EINVAL;
-    if (stride != 1 || KH != KW || pad > KH - 1 || H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return MPC_EINVAL;
+    if (!ctx || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0 || stride <= 0) return MPC_EINVAL;
+    if (KH != KW || pad > KH - 1 || H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return MPC_EINVAL;
     if (flags & (MPC_TRANS_X | MPC_TRANS_Y)) return MPC_EINVAL;
-    return beaver_linear(ctx, shape_conv_grad_x(B, H, W, Cin, Cout, KH, KW, pad), g, w, a, b, c, gx,
-                         f_public, n_chunks, flags);
+    const LinearShape s = shape_conv_grad_x(B, H, W, Cin, Cout, KH, KW, pad);
+    if (stride == 1)
+        return beaver_linear(ctx, s, g, w, a, b, c, gx, f_public, n_chunks, flags);
+    for (int i = 0; i < 2; ++i) if (!g.p[i] || !a.p[i]) return MPC_EINVAL;
+    const DilatedGeom d = dilated_geom(B, H, W, Cout, KH, KW, pad, stride);
+    WsAlloc wa(ctx->ws, ctx->ws_bytes);
+    u64* gd[2]; u64* ad[2];
+    for (int i = 0; i < 2; ++i) { gd[i] = wa.take<u64>(d.words); ad[i] = wa.take<u64>(d.words); }
+    if (!wa.ok) return MPC_ENOMEM;
+    MPC_TRY(lane_join(ctx));
+    DilateArgs q{};
+    for (int i = 0; i < 2; ++i) { q.src[2 * i] = g.p[i]; q.dst[2 * i] = gd[i]; q.src[2 * i + 1] = a.p[i]; q.dst[2 * i + 1] = ad[i]; }
+    q.B = B; q.Ho = d.Ho; q.Wo = d.Wo; q.Hd = d.Hd; q.Wd = d.Wd; q.C = Cout; q.stride = stride;
+    MPC_TRY(launch_dilate(ctx, ctx->s[0], q));
+    MPC_TRY(chain(ctx, ctx->s[0], ctx->s[1]));
+    const mpc_cshare gs = { { gd[0], gd[1] } }, as = { { ad[0], ad[1] } };
+    return beaver_linear(ctx, s, gs, w, as, b, c, gx, f_public, n_chunks, flags, nullptr, nullptr, nullptr, wa.off);
 }
 
 int mpc_conv2d_grad_w(mpc_ctx* ctx, mpc_cshare x, mpc_cshare g, mpc_cshare a, mpc_cshare b, mpc_cshare c,
@@ -604,9 +636,21 @@ int mpc_ring_conv2d(mpc_ctx* ctx, const uint64_t* x, const uint64_t* w, uint64_t
 int mpc_ring_conv2d_grad_x(mpc_ctx* ctx, const uint64_t* g, const uint64_t* w, uint64_t* gx,
                            int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
 {
-    if (B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0) return MPC_EINVAL;
-    if (stride != 1 || KH != KW || pad > KH - 1 || H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return MPC_EINVAL;
-    return ring_product(ctx, shape_conv_grad_x(B, H, W, Cin, Cout, KH, KW, pad), g, w, gx);
+    if (!ctx || !g || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0 || stride <= 0) return MPC_EINVAL;
+    if (KH != KW || pad > KH - 1 || H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return MPC_EINVAL;
+    const LinearShape s = shape_conv_grad_x(B, H, W, Cin, Cout, KH, KW, pad);
+    if (stride == 1) return ring_product(ctx, s, g, w, gx);
+    const DilatedGeom d = dilated_geom(B, H, W, Cout, KH, KW, pad, stride);
+    WsAlloc wa(ctx->ws, ctx->ws_bytes);
+    u64* gd = wa.take<u64>(d.words);
+    if (!wa.ok) return MPC_ENOMEM;
+    MPC_TRY(lane_join(ctx));
+    DilateArgs q{};
+    q.src[0] = g; q.dst[0] = gd;
+    q.B = B; q.Ho = d.Ho; q.Wo = d.Wo; q.Hd = d.Hd; q.Wd = d.Wd; q.C = Cout; q.stride = stride;
+    MPC_TRY(launch_dilate(ctx, ctx->s[0], q));
+    // ring_product needs 3x align of its own; the query above reserves 4 dilated buffers, one is used here
+    return ring_product(ctx, s, gd, w, gx, wa.off);
 }
 
 int mpc_ring_conv2d_grad_w(mpc_ctx* ctx, const uint64_t* x, const uint64_t* g, uint64_t* gw,

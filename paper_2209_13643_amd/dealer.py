@@ -90,7 +90,7 @@ def conv_backward(lane: "mpc.Lane", g, fwd: dict, pad: int, stride: int, g_std: 
     Ag = rand_words(g, G.shape, dev); Bg = rand_words(g, G.shape, dev)
     lane.wait_torch()
     d = dict(G=G, g=share(g, G))
-    if stride == 1 and KH == KW:
+    if KH == KW:
         Cx = lane.ring_conv2d_grad_x(Ag, Bm, A.shape, pad, stride); lane.sync()
         d["gx"] = dict(a=share(g, Ag), b=fwd["b"], c=share(g, Cx), f_public=fwd["f_public"])
     Cw = lane.ring_conv2d_grad_w(A, Bg, KH, KW, pad, stride); lane.sync()

@@ -102,7 +102,7 @@ def test_prepared_plane_sizes(lib):
 
 def test_gradient_and_elementwise_workspace_queries(lib):
     assert lib.mpc_conv2d_grad_x_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 1) > 0
-    assert lib.mpc_conv2d_grad_x_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 2) == 0      # strided: no input-gradient path
+    assert lib.mpc_conv2d_grad_x_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 2) > 0       # strided: plus the dilated gradient
     assert lib.mpc_conv2d_grad_x_workspace_bytes(2, 8, 8, 3, 16, 3, 5, 1, 1) == 0      # non-square filter
     assert lib.mpc_conv2d_grad_w_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 2) > 0
     assert lib.mpc_mul_workspace_bytes(1000) >= 8 * 1000 * 8

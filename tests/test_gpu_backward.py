@@ -144,7 +144,7 @@ def deal_grad(rng, case):
     return X, Wt, G, tuple(synth.share_additive(rng, v) for v in (X, Wt, G))
 
 
-@pytest.mark.parametrize("case", [c for c in GRAD_CASES if c[8] == 1])
+@pytest.mark.parametrize("case", GRAD_CASES + [(2, 9, 9, 4, 6, 3, 3, 1, 3), (1, 8, 8, 16, 16, 1, 1, 0, 2), (2, 12, 10, 8, 8, 3, 3, 1, 2)])
 @pytest.mark.parametrize("preopened", [False, True])
 def test_conv_grad_x(mpc, lane, case, preopened):
     B, H, W, Cin, Cout, KH, KW, pad, stride = case
@@ -273,9 +273,9 @@ def test_backward_argument_errors(mpc, lane):
     sh = mpc._share((t, t))
     lane.reserve(1 << 20)
     h = lane._h
-    # stride 2 and non-square filters have no input-gradient path
-    assert L.mpc_conv2d_grad_x(h, sh, sh, sh, sh, sh, sh, 1, 8, 8, 2, 2, 3, 3, 1, 2, None, 1, 0) == -1
+    # non-square filters have no input-gradient path; stride 0 is no stride
     assert L.mpc_conv2d_grad_x(h, sh, sh, sh, sh, sh, sh, 1, 8, 8, 2, 2, 3, 1, 0, 1, None, 1, 0) == -1
+    assert L.mpc_conv2d_grad_x(h, sh, sh, sh, sh, sh, sh, 1, 8, 8, 2, 2, 3, 3, 1, 0, None, 1, 0) == -1
     assert L.mpc_conv2d_grad_w(h, sh, sh, sh, sh, sh, sh, 1, 8, 8, 2, 2, 3, 3, 1, 0, None, 1, 0) == -1
     assert L.mpc_conv2d_grad_w(h, mpc._share(None), sh, sh, sh, sh, sh, 1, 8, 8, 2, 2, 3, 3, 1, 1, None, 1, 0) == -1
     assert L.mpc_mul(h, sh, sh, sh, sh, sh, sh, 0, 0) == -1
@@ -283,5 +283,5 @@ def test_backward_argument_errors(mpc, lane):
     small = mpc.Lane(0); small.reserve(256)
     assert L.mpc_mul(small._h, sh, sh, sh, sh, sh, sh, 4096, 0) == -2
     small.close()
-    assert L.mpc_conv2d_grad_x_workspace_bytes(1, 8, 8, 2, 2, 3, 3, 1, 2) == 0
+    assert L.mpc_conv2d_grad_x_workspace_bytes(1, 8, 8, 2, 2, 3, 3, 1, 2) > L.mpc_conv2d_grad_x_workspace_bytes(1, 8, 8, 2, 2, 3, 3, 1, 1)
     assert L.mpc_mul_workspace_bytes(0) == 0
