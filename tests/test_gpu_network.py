@@ -172,3 +172,40 @@ def test_vgg16_training_step_matches_oracle(mods, dealt, packed_relu):
         want_w = (st["w"][0] - step[0].reshape(st["w"][0].shape), st["w"][1] - step[1].reshape(st["w"][1].shape))
         check_pair(states[li].w, want_w, f"updated weights of layer {li} ({L.name})")
     lane.close()
+
+
+def test_strided_network_training_step(mods):
+    """A small network with a strided 3x3 convolution, a strided 1x1 shortcut-like convolution,
+    a pooled layer and a dense head: forward, backward and the weight gradients against the oracle."""
+    mpc, pipeline = mods
+    print("strided network training step", flush=True)
+    B = 3
+    layers = [synth.Conv("c1", B, 12, 12, 3, 8, 3, 3, 1, 2, 1.0, synth.he_std(27), True, False),
+              synth.Conv("c2", B, 6, 6, 8, 8, 1, 1, 0, 2, 1.0, synth.he_std(8), True, False),
+              synth.Conv("c3", B, 3, 3, 8, 16, 3, 3, 1, 1, 1.0, synth.he_std(72), True, False),
+              synth.Conv("c4", B, 3, 3, 16, 16, 3, 3, 1, 1, 1.0, synth.he_std(144), True, False)]
+    layers.append(synth.Gemm("fc", B, 3 * 3 * 16, 10, 1.0, synth.he_std(144)))
+    rng = synth.rng_for(9, 1)
+    states, _ = deal_network_host(rng, layers)
+    bhost = deal_backward_host(rng, layers, states)
+    X = synth.normal_fixed(rng, (B, 12, 12, 3), 1.0); xs = synth.share_additive(rng, X)
+    gout = synth.share_additive(rng, synth.normal_fixed(rng, (B, 10), 0.5))
+    want_out, want_grads = oracle_train_step(layers, states, bhost, xs, gout)
+    lane = mpc.Lane(0); lane.use_single_queue()
+    dv = lambda p: (mpc.to_device(p[0]), mpc.to_device(p[1]))
+    dstates = [to_state(mpc, pipeline, st) for st in states]
+    bstates = []
+    for st, bs in zip(dstates, bhost):
+        trip = lambda t: None if t is None else tuple(dv(q) for q in t)
+        bstates.append(pipeline.BackwardState(
+            gx=None if bs["gx"] is None else dict(a=dv(bs["gx"]["a"]), b=st.b, c=dv(bs["gx"]["c"])),
+            gw=dict(a=st.a, b=dv(bs["gw"]["b"]), c=dv(bs["gw"]["c"])),
+            relu_t=trip(bs["relu_t"]), pool_t1=trip(bs["pool_t1"]), pool_t2=trip(bs["pool_t2"])))
+    keep = []
+    out, tape = pipeline.forward_train(lane, layers, dstates, dv(xs), keep)
+    grads = pipeline.backward(lane, layers, dstates, bstates, tape, dv(gout), keep)
+    lane.sync()
+    check(mpc, out, want_out, "logits")
+    for li, L in enumerate(layers):
+        check(mpc, grads[li], want_grads[li], f"weight gradient of layer {li} ({L.name})")
+    lane.close()
