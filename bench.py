@@ -78,12 +78,59 @@ def cpu_baseline(layer, budget_s=12.0):
                       f"convolutions + truncation, then ReLU on {n} elements), {t_lin + t_relu:.1f} s of CPU work"}
 
 
+def cpu_baseline_all_configs():
+    """The oracle on a bounded sample of every layer of the five workloads (rows of a dense layer,
+    images of a convolution; at most 2^18 ReLU elements): secure MACs/s and ReLU elements/s per layer.
+    Only with --cpu-all-configs: it adds about a minute of CPU work."""
+    import numpy as np
+    import oracle
+    from paper_2209_13643_amd import synth
+
+    out = []
+    for make in synth.CONFIGS:
+        wl = make()
+        rng = synth.rng_for(wl.index, 8)
+        for L in wl.layers:
+            if isinstance(L, synth.Conv):
+                Bs = max(1, min(L.B, (1 << 28) // max(1, L.Ho * L.Wo * L.KH * L.KW * L.Cin * L.Cout)))
+                xs = tuple(synth.rand_words(rng, (Bs, L.H, L.W, L.Cin)) for _ in range(2))
+                ws = tuple(synth.rand_words(rng, (L.KH, L.KW, L.Cin, L.Cout)) for _ in range(2))
+                cs = tuple(synth.rand_words(rng, (Bs, L.Ho, L.Wo, L.Cout)) for _ in range(2))
+                t0 = time.perf_counter()
+                z = oracle.truncate(oracle.beaver_conv2d(xs, ws, xs, ws, cs, L.pad, L.stride), 16)
+                dt = time.perf_counter() - t0
+                macs = Bs * L.Ho * L.Wo * L.KH * L.KW * L.Cin * L.Cout
+                sample = f"{Bs} of {L.B} images"
+            else:
+                Ms = max(1, min(L.M, (1 << 28) // max(1, L.K * L.N)))
+                xs = tuple(synth.rand_words(rng, (Ms, L.K)) for _ in range(2))
+                ws = tuple(synth.rand_words(rng, (L.K, L.N)) for _ in range(2))
+                cs = tuple(synth.rand_words(rng, (Ms, L.N)) for _ in range(2))
+                t0 = time.perf_counter()
+                z = oracle.truncate(oracle.beaver_matmul(xs, ws, xs, ws, cs), 16)
+                dt = time.perf_counter() - t0
+                macs = Ms * L.K * L.N
+                sample = f"{Ms} of {L.M} rows" + (f", 1 of {L.batch} batch items" if L.batch > 1 else "")
+            row = {"config": wl.index, "layer": L.name, "secure_macs_per_s": macs / dt, "sample": sample}
+            if L.relu:
+                n = min(z[0].size, 1 << 18)
+                zz = (z[0].reshape(-1)[:n], z[1].reshape(-1)[:n])
+                mat = synth.deal_relu_material(rng, n)
+                t0 = time.perf_counter()
+                oracle.relu(zz, mat)
+                row["relu_elems_per_s"] = n / (time.perf_counter() - t0)
+            out.append(row)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-all-configs", action="store_true",
+                    help="also time the oracle on a sample of every layer of all five workloads")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build simulates both parties on a single MI355X and has no "
@@ -216,6 +263,8 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L)
+        if args.cpu_all_configs:
+            out["cpu_baseline"]["per_layer"] = cpu_baseline_all_configs()
     lane.close()
     print(json.dumps(out))
 
