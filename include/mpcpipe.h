@@ -119,6 +119,22 @@ int mpc_ctx_profile_reset(mpc_ctx* ctx);
 enum { MPC_ADDER_KOGGE_STONE = 0, MPC_ADDER_TREE = 1 };
 int mpc_ctx_set_adder(mpc_ctx* ctx, int adder);
 
+/* Graph capture.  On a lane whose three streams are one queue, the calls made
+ * between mpc_ctx_capture_begin and mpc_ctx_capture_end are recorded into a HIP
+ * graph instead of being executed; mpc_graph_launch enqueues one replay on the
+ * given lane (any single-queue or three-stream lane of the same device).  A
+ * replay reads and writes the very buffers (and workspace) the recorded calls
+ * were given: keep them allocated and in place, refill the inputs, replay.
+ * Run the sequence once eagerly first (kernel attributes, workspace size).
+ * While a capture is open mpc_ctx_sync, mpc_ctx_set_workspace,
+ * mpc_ctx_set_streams and profiling return MPC_EINVAL; profiling must be off.
+ * The library records kernel launches only (no memset or copy nodes). */
+typedef struct mpc_graph mpc_graph;
+int mpc_ctx_capture_begin(mpc_ctx* ctx);
+int mpc_ctx_capture_end(mpc_ctx* ctx, mpc_graph** out);
+int mpc_graph_launch(mpc_graph* graph, mpc_ctx* ctx);
+int mpc_graph_destroy(mpc_graph* graph);
+
 /* How masked words are exchanged (the rounds of the secure ReLU, and the masked
  * operands of the Beaver products).
  * MPC_EXCHANGE_COPY (default): a copy kernel on the wire stream moves every

@@ -210,6 +210,84 @@ def bench_training(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_r
     return res
 
 
+def bench_graph(reps: int = 50):
+    """Eager issue vs replay of a captured HIP graph: the tiny secure layer (configs[0]) and one
+    VGG16-CIFAR micro-batch forward (sign-only packed ReLU, prepared planes)."""
+    res = {}
+    lane = mpc.Lane(0); lane.use_single_queue()
+    dev = lane.device
+    g = dealer.gen(synth.BASE_SEED + 90, dev)
+    L = synth.config_tiny().layers[0]
+    d = dealer.matmul_layer(lane, g, L.M, L.K, L.N, L.x_std, L.w_std)
+    mat = dealer.relu_material(g, L.M * L.N, dev)
+    z = (torch.empty_like(d["c"][0]), torch.empty_like(d["c"][1])); y = (torch.empty_like(z[0]), torch.empty_like(z[1]))
+
+    def tiny():
+        lane.beaver_matmul(d["x"], d["w"], d["a"], d["b"], d["c"], out=z)
+        lane.relu(z, mat, out=y)
+
+    def timed(fn, n):
+        for _ in range(5):
+            fn()
+        lane.sync(); t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        lane.sync()
+        return (time.perf_counter() - t0) / n * 1e3
+
+    res["tiny_eager_ms"] = timed(tiny, 4 * reps)
+    with lane.capture() as cap:
+        tiny()
+    res["tiny_graph_ms"] = timed(lambda: cap.graph.launch(lane), 4 * reps)
+
+    wl = synth.config_vgg16_pipeline(32)
+    weights = pipeline.deal_weights(g, wl.layers, dev)
+    states = pipeline.deal_microbatch(lane, g, wl.layers, weights, packed_relu=True)
+    pipeline.prepare_layers(lane, wl.layers, states)
+    x = dealer.share(g, dealer.normal_fixed(g, (32, 32, 32, 3), 1.0, dev))
+    torch.cuda.synchronize()
+    keep = []
+    res["vgg16_eager_ms"] = timed(lambda: pipeline.forward(lane, wl.layers, states, x, keep), reps // 5)
+    keep.clear()
+    kept = []
+    with lane.capture() as cap2:
+        out = pipeline.forward(lane, wl.layers, states, x, kept)        # `kept` pins every tensor the replay touches
+    res["vgg16_graph_ms"] = timed(lambda: cap2.graph.launch(lane), reps // 5)
+    lane.sync()
+    eager = pipeline.forward(lane, wl.layers, states, x, keep); lane.sync()
+    assert torch.equal(eager[0], out[0]) and torch.equal(eager[1], out[1]), "graph replay differs from eager forward"
+    # inter-batch pipeline with one recorded graph per micro-batch lane
+    lanes = [lane] + [mpc.Lane(0) for _ in range(3)]
+    graphs, pins = [cap2.graph], [kept]
+    for ln in lanes[1:]:
+        ln.use_single_queue()
+        st = pipeline.deal_microbatch(ln, g, wl.layers, weights, packed_relu=True)
+        pipeline.prepare_layers(ln, wl.layers, st)
+        xm = dealer.share(g, dealer.normal_fixed(g, (32, 32, 32, 3), 1.0, dev))
+        torch.cuda.synchronize()
+        warm = []; pipeline.forward(ln, wl.layers, st, xm, warm); ln.sync(); del warm
+        pin = []
+        with ln.capture() as cp:
+            pipeline.forward(ln, wl.layers, st, xm, pin)
+        graphs.append(cp.graph); pins.append((pin, st, xm))
+    def replay_all():
+        for gr, ln in zip(graphs, lanes):
+            gr.launch(ln)
+    for _ in range(3):
+        replay_all()
+    for ln in lanes:
+        ln.sync()
+    t0 = time.perf_counter()
+    for _ in range(reps // 5):
+        replay_all()
+    for ln in lanes:
+        ln.sync()
+    res["vgg16_4lanes_graph_ms"] = (time.perf_counter() - t0) / (reps // 5) * 1e3
+    for ln in lanes:
+        ln.close()
+    return res
+
+
 def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = False, prepared: bool = False):
     """Config 4: serial (one lane, micro-batches one after the other) vs pipelined (one lane each)."""
     wl = synth.config_vgg16_pipeline(micro_batch)
@@ -342,6 +420,13 @@ def main(argv):
                 print(line, flush=True)
             print(f"  sum over layers (x multiplicity): linear {tot_lin:.2f} ms ({tot_prep:.2f} ms on prepared planes), ReLU {tot_relu:.2f} ms whole-word / "
                   f"{tot_msb:.2f} ms sign-only", flush=True)
+        return
+    if argv and argv[0] == "graph":
+        r = bench_graph()
+        print(f"  configs[0] secure layer (matmul + ReLU): eager {r['tiny_eager_ms']:.4f} ms, graph replay {r['tiny_graph_ms']:.4f} ms")
+        print(f"  VGG16-CIFAR forward, 32 images (packed ReLU, prepared planes): eager {r['vgg16_eager_ms']:.3f} ms, "
+              f"graph replay {r['vgg16_graph_ms']:.3f} ms; batch 128 = 4 x 32 as four recorded graphs on four lanes: "
+              f"{r['vgg16_4lanes_graph_ms']:.2f} ms ({128 / r['vgg16_4lanes_graph_ms'] * 1e3:.0f} img/s)", flush=True)
         return
     if argv and argv[0] == "train":
         for packed in (False, True):

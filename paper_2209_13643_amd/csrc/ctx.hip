@@ -47,7 +47,7 @@ int mpc_ctx_destroy(mpc_ctx* c)
 
 int mpc_ctx_set_streams(mpc_ctx* c, void* s0, void* s1, void* sw)
 {
-    if (!c) return MPC_EINVAL;
+    if (!c || c->capturing) return MPC_EINVAL;
     void* in[3] = { s0, s1, sw };
     for (int i = 0; i < 3; ++i) {
         if (!in[i] || in[i] == (void*)c->s[i]) continue;
@@ -69,7 +69,7 @@ void* mpc_ctx_stream(mpc_ctx* c, int which)
 
 int mpc_ctx_set_workspace(mpc_ctx* c, void* p, size_t bytes)
 {
-    if (!c) return MPC_EINVAL;
+    if (!c || c->capturing) return MPC_EINVAL;
     if (p && ((uintptr_t)p % kAlign) != 0) return MPC_EINVAL;
     c->ws = (u8*)p;
     c->ws_bytes = p ? bytes : 0;
@@ -78,7 +78,7 @@ int mpc_ctx_set_workspace(mpc_ctx* c, void* p, size_t bytes)
 
 int mpc_ctx_sync(mpc_ctx* c)
 {
-    if (!c) return MPC_EINVAL;
+    if (!c || c->capturing) return MPC_EINVAL;      // a capturing queue cannot be waited for
     for (int i = 0; i < 3; ++i) MPC_HIP(c, hipStreamSynchronize(c->s[i]));
     return MPC_OK;
 }
@@ -91,6 +91,52 @@ int mpc_ctx_wait(mpc_ctx* c, mpc_ctx* after)
         MPC_HIP(after, hipEventRecord(e, after->s[i]));
         for (int j = 0; j < 2; ++j) MPC_HIP(c, hipStreamWaitEvent(c->s[j], e, 0));
     }
+    return MPC_OK;
+}
+
+// ---- graph capture: a sequence of calls on a single-queue lane recorded once, replayed many times
+struct mpc_graph { hipGraph_t graph; hipGraphExec_t exec; };
+
+int mpc_ctx_capture_begin(mpc_ctx* c)
+{
+    if (!c || c->capturing || c->profiling) return MPC_EINVAL;
+    if (!(c->s[0] == c->s[1] && c->s[1] == c->s[2])) return MPC_EINVAL;      // events between streams are not recorded
+    MPC_HIP(c, hipStreamBeginCapture(c->s[0], hipStreamCaptureModeRelaxed));
+    c->capturing = true;
+    return MPC_OK;
+}
+
+int mpc_ctx_capture_end(mpc_ctx* c, mpc_graph** out)
+{
+    if (!c || !out || !c->capturing) return MPC_EINVAL;
+    c->capturing = false;
+    hipGraph_t g = nullptr;
+    MPC_HIP(c, hipStreamEndCapture(c->s[0], &g));
+    if (!g) return MPC_EHIP;
+    hipGraphExec_t e = nullptr;
+    const hipError_t err = hipGraphInstantiate(&e, g, nullptr, nullptr, 0);
+    if (err != hipSuccess) { c->last_hip = (int)err; (void)hipGraphDestroy(g); return MPC_EHIP; }
+    mpc_graph* mg = new (std::nothrow) mpc_graph{ g, e };
+    if (!mg) { (void)hipGraphExecDestroy(e); (void)hipGraphDestroy(g); return MPC_ENOMEM; }
+    *out = mg;
+    return MPC_OK;
+}
+
+int mpc_graph_launch(mpc_graph* g, mpc_ctx* c)
+{
+    if (!g || !c || c->capturing) return MPC_EINVAL;
+    MPC_TRY(lane_join(c));
+    MPC_HIP(c, hipGraphLaunch(g->exec, c->s[0]));
+    MPC_TRY(chain(c, c->s[0], c->s[1]));
+    return MPC_OK;
+}
+
+int mpc_graph_destroy(mpc_graph* g)
+{
+    if (!g) return MPC_EINVAL;
+    (void)hipGraphExecDestroy(g->exec);
+    (void)hipGraphDestroy(g->graph);
+    delete g;
     return MPC_OK;
 }
 
@@ -110,7 +156,7 @@ int mpc_ctx_set_adder(mpc_ctx* c, int adder)
 
 int mpc_ctx_set_profiling(mpc_ctx* c, int enable)
 {
-    if (!c) return MPC_EINVAL;
+    if (!c || c->capturing) return MPC_EINVAL;
     c->profiling = enable != 0;
     return MPC_OK;
 }

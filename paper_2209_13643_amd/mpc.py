@@ -52,6 +52,7 @@ EXPORTS = [
     "mpc_ctx_set_adder", "mpc_ctx_set_exchange", "mpc_ctx_profile_samples", "mpc_add",
     "mpc_matmul_prepared_bytes", "mpc_conv2d_prepared_bytes", "mpc_matmul_prepare", "mpc_conv2d_prepare",
     "mpc_beaver_matmul_prepared", "mpc_conv2d_prepared",
+    "mpc_ctx_capture_begin", "mpc_ctx_capture_end", "mpc_graph_launch", "mpc_graph_destroy",
 ]
 
 _lib = None
@@ -69,6 +70,10 @@ def lib():
     L.mpc_ctx_destroy.argtypes = [c_void_p]
     L.mpc_ctx_set_adder.argtypes = [c_void_p, c_int]
     L.mpc_add.argtypes = [c_void_p, CShare, CShare, CShare, c_size_t]
+    L.mpc_ctx_capture_begin.argtypes = [c_void_p]
+    L.mpc_ctx_capture_end.argtypes = [c_void_p, POINTER(c_void_p)]
+    L.mpc_graph_launch.argtypes = [c_void_p, c_void_p]
+    L.mpc_graph_destroy.argtypes = [c_void_p]
     L.mpc_matmul_prepared_bytes.argtypes = [c_int] * 4 + [POINTER(c_size_t)] * 2
     L.mpc_conv2d_prepared_bytes.argtypes = [c_int] * 9 + [POINTER(c_size_t)] * 2
     L.mpc_matmul_prepare.argtypes = [c_void_p, CShare, CShare, _P64, c_void_p, c_void_p] + [c_int] * 5
@@ -187,6 +192,42 @@ def _material(mat: dict, n: int, packed: bool = False) -> ReluMaterial:
     return m
 
 
+class Graph:
+    """A recorded sequence of lane calls (Lane.capture); launch() enqueues one replay."""
+
+    def __init__(self, handle, keep):
+        self._h = handle
+        self._keep = keep          # tensors the recorded calls allocated: must stay in place
+
+    def launch(self, lane: "Lane"):
+        lane._check(lib().mpc_graph_launch(self._h, lane._h))
+
+    def close(self):
+        if self._h:
+            lib().mpc_graph_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+
+class _Capture:
+    def __init__(self, lane):
+        self.lane = lane; self.graph = None
+
+    def __enter__(self):
+        self.lane._check(lib().mpc_ctx_capture_begin(self.lane._h))
+        return self
+
+    def __exit__(self, exc_type, exc, tb):
+        h = c_void_p()
+        rc = lib().mpc_ctx_capture_end(self.lane._h, byref(h))
+        if exc_type is None:
+            self.lane._check(rc)
+            self.graph = Graph(h, [self.lane._ws])
+        return False
+
+
 class Lane:
     """One execution lane: a library context plus a grow-only workspace."""
 
@@ -249,6 +290,12 @@ class Lane:
         cur = torch.cuda.current_stream(self.device)
         for s in {self.stream(0), self.stream(1), self.stream(2)}:
             torch.cuda.ExternalStream(s, device=self.device).wait_stream(cur)
+
+    def capture(self):
+        """Context manager: record the lane calls made inside it into a Graph (`.graph` afterwards).
+        Single-queue lanes only; run the sequence once eagerly first and pass `out=` buffers, since
+        a replay reuses the very tensors the recorded calls touched."""
+        return _Capture(self)
 
     def set_exchange(self, mode: str):
         """Secure-ReLU exchange: "copy" (copy kernels on the wire stream) or "put" (the producing

@@ -111,6 +111,35 @@ def test_pipeline_invariance(mods, dealt, mode):
         ln.close()
 
 
+def test_whole_network_as_a_recorded_graph(mods, dealt):
+    """The VGG16 forward of one micro-batch recorded into a HIP graph and replayed on both
+    micro-batches' inputs (copied into the recorded input buffers): logits as in the oracle run."""
+    import torch
+    mpc, pipeline = mods
+    layers, mbs = dealt
+    print("whole network as a graph", flush=True)
+    lane = mpc.Lane(0); lane.use_single_queue()
+    # both micro-batches share weights but not triples: record micro-batch 0's states, replay it twice
+    # (second time after other eager work), then check against its oracle logits
+    mb = mbs[0]
+    states = [to_state(mpc, pipeline, st, lane) for st in mb["states"]]
+    pipeline.prepare_layers(lane, layers, states)
+    x = (mpc.to_device(mb["x"][0]), mpc.to_device(mb["x"][1]))
+    warm = []; pipeline.forward(lane, layers, states, x, warm); lane.sync(); del warm
+    pin = []
+    with lane.capture() as cap:
+        out = pipeline.forward(lane, layers, states, x, pin)
+    for rep in range(2):
+        for t in out:
+            t.zero_()
+        torch.cuda.synchronize()
+        cap.graph.launch(lane); lane.sync()
+        check(mpc, out, mb["want"][-1], f"logits of graph replay {rep}")
+        between = lane.add(x, x); lane.sync()                  # eager work between the replays
+        assert torch.equal(between[0], x[0] + x[0])
+    cap.graph.close(); lane.close()
+
+
 @pytest.mark.parametrize("queues", ["three-streams", "single-queue"])
 def test_interlinear_lookahead_across_layers(mods, dealt, queues):
     """Alg. 3 across layers: each weight mask is opened one layer ahead on a second lane and the

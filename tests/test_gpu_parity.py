@@ -359,6 +359,49 @@ def test_conv2d_prepared_planes(mpc, lane, case):
     assert_shares_equal(host(mpc, lane, z), oracle_conv(d), "prepared conv, two-phase, chunked")
 
 
+def test_graph_capture_replays(mpc):
+    """A secure layer (Beaver matmul + ReLU) recorded once and replayed on fresh inputs in the same
+    buffers, with eager work and synchronisation between the replays: every replay equals the oracle."""
+    import torch
+    print("graph capture", flush=True)
+    lane = mpc.Lane(0); lane.use_single_queue()
+    M, K, N = 64, 256, 128
+    rng = np.random.default_rng(77)
+    deals = [deal_matmul(rng, M, K, N, x_std=1.0, w_std=1.0 / 16) for _ in range(3)]
+    mat = synth.deal_relu_material(rng, M * N)
+    md = mpc.material_to_device(mat)
+    d0 = deals[0]
+    buf = {k: dev(mpc, d0[k]) for k in ("x", "y", "a", "b", "c")}
+    z = (torch.empty_like(buf["c"][0]), torch.empty_like(buf["c"][1]))
+    y = (torch.empty_like(z[0]), torch.empty_like(z[1]))
+
+    def layer():
+        lane.beaver_matmul(buf["x"], buf["y"], buf["a"], buf["b"], buf["c"], out=z)
+        lane.relu(z, md, out=y)
+    layer(); lane.sync()                                  # eager warm-up: attributes set, workspace sized
+    with lane.capture() as cap:
+        layer()
+    graph = cap.graph
+    assert mpc.lib().mpc_ctx_capture_end(lane._h, None) == -1            # no capture open any more
+    for d in deals:
+        for k in buf:
+            for i in range(2):
+                buf[k][i].copy_(mpc.to_device(d[k][i]))
+        torch.cuda.synchronize()
+        graph.launch(lane)
+        lane.sync()
+        want = oracle.relu(oracle_matmul(d), mat).y
+        assert_shares_equal((mpc.to_host(y[0]), mpc.to_host(y[1])), want, "graph replay")
+        # eager work between replays, on the same lane and workspace
+        other = lane.relu(dev(mpc, d["c"]), md)
+        lane.sync()
+        assert_shares_equal((mpc.to_host(other[0]), mpc.to_host(other[1])), oracle.relu(d["c"], mat).y, "eager between replays")
+    three = mpc.Lane(0)
+    assert mpc.lib().mpc_ctx_capture_begin(three._h) == -1               # three streams: not capturable
+    three.close()
+    graph.close(); lane.close()
+
+
 def test_add_is_the_local_sum(mpc, lane):
     print("add", flush=True)
     rng = np.random.default_rng(68)
