@@ -107,8 +107,11 @@ def prepare_layers(lane: mpc.Lane, layers, states):
     lane.sync()
 
 
-def run_layer(lane: mpc.Lane, L, st: LayerState, x, n_chunks=1, relu_chunks=0, flags=mpc.MPC_TRUNCATE):
-    """One secure layer on one lane: linear (+ ReLU) (+ 2x2 max-pool).  Returns output shares."""
+def run_layer(lane: mpc.Lane, L, st: LayerState, x, keep: list, n_chunks=1, relu_chunks=0, flags=mpc.MPC_TRUNCATE):
+    """One secure layer on one lane: linear (+ ReLU) (+ 2x2 max-pool).  Returns output shares.
+    Every tensor the layer produces is appended to `keep`: the calls only enqueue work and torch's
+    allocator knows nothing about the lane's queue, so nothing may be freed (and handed out again)
+    before the caller has synchronised the lane."""
     y_arg = None if st.f_public is not None else st.w
     if isinstance(L, synth.Conv):
         xs = (x[0].view(L.B, L.H, L.W, L.Cin), x[1].view(L.B, L.H, L.W, L.Cin))
@@ -129,7 +132,7 @@ def run_layer(lane: mpc.Lane, L, st: LayerState, x, n_chunks=1, relu_chunks=0, f
         z = lane.relu(z, st.relu, n_chunks=relu_chunks, packed=st.packed); outs.append(z)
     if st.pool1 is not None:
         z = lane.maxpool2x2(z, st.pool1, st.pool2, n_chunks=relu_chunks, packed=st.packed); outs.append(z)
-    run_layer.last_intermediates = outs      # kept alive by the caller through `keep`
+    keep.extend(outs)
     return z
 
 
@@ -139,8 +142,7 @@ def forward(lane: mpc.Lane, layers, states, x, keep: list, **kw):
     lane's queue, so nothing may be freed (and handed out again) until the
     caller has synchronised the lane."""
     for L, st in zip(layers, states):
-        x = run_layer(lane, L, st, x, **kw)
-        keep.extend(run_layer.last_intermediates)
+        x = run_layer(lane, L, st, x, keep, **kw)
     return x
 
 
@@ -157,8 +159,7 @@ def forward_interlinear(lane: mpc.Lane, wlane: mpc.Lane, layers, states, x, keep
         lane.wait_for(wlane)                       # this layer's mask has arrived
         if li + 1 < len(layers):
             open_mask(states[li + 1])              # next layer's mask travels while this layer computes
-        x = run_layer(lane, L, st, x, **kw)
-        keep.extend(run_layer.last_intermediates)
+        x = run_layer(lane, L, st, x, keep, **kw)
     return x
 
 
@@ -167,8 +168,7 @@ def forward_pipelined(lanes, layers, states_per_mb, xs, keep: list, **kw):
     cur = list(xs)
     for li, L in enumerate(layers):
         for m, lane in enumerate(lanes):
-            cur[m] = run_layer(lane, L, states_per_mb[m][li], cur[m], **kw)
-            keep.extend(run_layer.last_intermediates)
+            cur[m] = run_layer(lane, L, states_per_mb[m][li], cur[m], keep, **kw)
     return cur
 
 

@@ -66,8 +66,7 @@ def test_vgg16_every_layer_matches_oracle(mods, dealt, packed_relu):
     x = (mpc.to_device(mb["x"][0]), mpc.to_device(mb["x"][1]))
     keep = []
     for li, (L, st) in enumerate(zip(layers, states)):
-        x = pipeline.run_layer(lane, L, st, x)
-        keep.extend(pipeline.run_layer.last_intermediates)
+        x = pipeline.run_layer(lane, L, st, x, keep)
         lane.sync()
         check(mpc, x, mb["want"][li], f"layer {li} ({L.name})")
     # decoded logits close to a float64 run of the same quantised network
