@@ -493,16 +493,20 @@ __global__ __launch_bounds__(kThreads) void k_pack_triples(const u64* __restrict
 
 // rows x len words, both sides with pitch `pitch` words: the per-round wire copy
 // blockIdx.y selects the direction: 0 = party 0 -> party 1, 1 = party 1 -> party 0
+// All rows of a position are loaded before any is stored, so a thread keeps ROWS loads in flight.
+template <int ROWS>
 __global__ __launch_bounds__(kThreads) void k_wire_words(const u64* __restrict__ src0, u64* __restrict__ dst0,
                                                          const u64* __restrict__ src1, u64* __restrict__ dst1,
-                                                         size_t pitch, size_t lo, size_t hi, int rows)
+                                                         size_t pitch, size_t lo, size_t hi)
 {
     const u64* src = blockIdx.y ? src1 : src0; u64* dst = blockIdx.y ? dst1 : dst0;
     const size_t stride = (size_t)gridDim.x * blockDim.x * 2;
-    for (int r = 0; r < rows; ++r) {
-        const u64* s = src + (size_t)r * pitch; u64* d = dst + (size_t)r * pitch;
-        for (size_t i = lo + ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 2; i < hi; i += stride)
-            *reinterpret_cast<u64x2*>(d + i) = *reinterpret_cast<const u64x2*>(s + i);
+    for (size_t i = lo + ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 2; i < hi; i += stride) {
+        u64x2 v[ROWS];
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) v[r] = *reinterpret_cast<const u64x2*>(src + (size_t)r * pitch + i);
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) *reinterpret_cast<u64x2*>(dst + (size_t)r * pitch + i) = v[r];
     }
 }
 __global__ __launch_bounds__(kThreads) void k_wire_words1(const u64* __restrict__ src0, u64* __restrict__ dst0,
@@ -702,9 +706,12 @@ int wire_words(mpc_ctx* c, const u64* src0, u64* dst0, const u64* src1, u64* dst
                size_t pitch, size_t lo, size_t hi, int rows, bool vec)
 {
     const size_t len = hi - lo;
-    if (vec)
-        hipLaunchKernelGGL(k_wire_words, dim3(grid_for(len / 2), 2), dim3(kThreads), 0, c->s[2],
-                           src0, dst0, src1, dst1, pitch, lo, hi, rows);
+    if (vec && rows == 4)
+        hipLaunchKernelGGL(k_wire_words<4>, dim3(grid_for(len / 2), 2), dim3(kThreads), 0, c->s[2], src0, dst0, src1, dst1, pitch, lo, hi);
+    else if (vec && rows == 2)
+        hipLaunchKernelGGL(k_wire_words<2>, dim3(grid_for(len / 2), 2), dim3(kThreads), 0, c->s[2], src0, dst0, src1, dst1, pitch, lo, hi);
+    else if (vec && rows == 1)
+        hipLaunchKernelGGL(k_wire_words<1>, dim3(grid_for(len / 2), 2), dim3(kThreads), 0, c->s[2], src0, dst0, src1, dst1, pitch, lo, hi);
     else
         hipLaunchKernelGGL(k_wire_words1, dim3(grid_for(len), 2), dim3(kThreads), 0, c->s[2],
                            src0, dst0, src1, dst1, pitch, lo, hi, rows);
