@@ -22,9 +22,7 @@ int mpc_ctx_create(mpc_ctx** out, int device, int frac_bits)
     for (int i = 0; i < kEventPool && e == hipSuccess; ++i)
         e = hipEventCreateWithFlags(&c->ev[i], hipEventDisableTiming);
     if (e != hipSuccess) {
-        int code = (int)e;
-        mpc_ctx_destroy(c);
-        (void)code;
+        (void)mpc_ctx_destroy(c);       // releases whatever was created; the HIP code is lost with the context
         return MPC_EHIP;
     }
     *out = c;

@@ -208,7 +208,10 @@ class Graph:
             self._h = None
 
     def __del__(self):
-        self.close()
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class _Capture:
