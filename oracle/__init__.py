@@ -1,4 +1,5 @@
-"""CPU oracle for the secure-layer hot path (two parties, ring Z_2^64).
+"""CPU oracle for the secure-layer hot path (two parties, ring Z_2^64; the
+three-party forms of Alg. 1 / Alg. 2 at the end).
 
 TEST INFRASTRUCTURE ONLY.  Imported by ``tests/``, by ``__graft_entry__.smoke``
 and by the ``cpu_baseline`` leg of ``bench.py``; never by the GPU library or its
@@ -346,6 +347,119 @@ def maxpool2x2_backward(g, s1, s2, t1, t2, x_shape):
         gx[:, :, 1, :, 0, :] = Pi[..., 1];       gx[:, :, 1, :, 1, :] = gvi - Pi[..., 1]
         out.append(gx.reshape(B, H, W, C))
     return tuple(out)
+
+
+# ---------------------------------------------------------------- three parties
+_PP64 = ctypes.c_void_p * 3
+
+
+def _w3(arrs):
+    """Three contiguous uint64 arrays and the array of their pointers."""
+    keep = [np.ascontiguousarray(a, dtype=U64) for a in arrs]
+    assert len(keep) == 3
+    return keep, _PP64(*[a.ctypes.data for a in keep])
+
+
+def _out3(shape, dtype=U64):
+    keep = [np.empty(shape, dtype=dtype) for _ in range(3)]
+    return keep, _PP64(*[a.ctypes.data for a in keep])
+
+
+def open3(s):
+    """Reconstruct a three-party additive sharing (Sec. 3.1)."""
+    k, ps = _w3(s)
+    out = np.empty_like(k[0])
+    lib().orc3_open(ps, out.ctypes.data_as(_P64), ctypes.c_size_t(out.size))
+    return out
+
+
+def beaver_mul3(x, y, a, b, c):
+    """Alg. 1 element by element; every argument a triple (party 0, 1, 2)."""
+    kx, px = _w3(x); ky, py = _w3(y); ka, pa = _w3(a); kb, pb = _w3(b); kc, pc = _w3(c)
+    z, pz = _out3(kx[0].shape)
+    lib().orc3_beaver_mul(px, py, pa, pb, pc, pz, ctypes.c_size_t(kx[0].size))
+    return tuple(z)
+
+
+def beaver_matmul3(x, y, a, b, c):
+    """Alg. 1 on matrices with three parties."""
+    kx, px = _w3(x); ky, py = _w3(y); ka, pa = _w3(a); kb, pb = _w3(b); kc, pc = _w3(c)
+    M, K = kx[0].shape; _, N = ky[0].shape
+    z, pz = _out3((M, N))
+    lib().orc3_beaver_matmul(px, py, pa, pb, pc, pz, M, K, N)
+    return tuple(z)
+
+
+def beaver_conv2d3(x, w, a, b, c, pad, stride):
+    """Eq. 3 with three parties.  NHWC / [KH,KW,Cin,Cout]."""
+    kx, px = _w3(x); kw, pw = _w3(w); ka, pa = _w3(a); kb, pb = _w3(b); kc, pc = _w3(c)
+    B, H, W, Cin = kx[0].shape; KH, KW, _, Cout = kw[0].shape
+    Ho, Wo = conv_out_hw(H, W, KH, KW, pad, stride)
+    z, pz = _out3((B, Ho, Wo, Cout))
+    lib().orc3_beaver_conv2d(px, pw, pa, pb, pc, pz, B, H, W, Cin, Cout, KH, KW, pad, stride)
+    return tuple(z)
+
+
+def truncate3(z, r, rt, bits=16):
+    """Masked three-party truncation with the offline pair ([r], [r >> bits]); returns new arrays."""
+    kz = [np.array(v, dtype=U64, copy=True) for v in z]
+    pz = _PP64(*[a.ctypes.data for a in kz])
+    kr, pr = _w3(r); kt, pt = _w3(rt)
+    lib().orc3_truncate(pz, pr, pt, ctypes.c_size_t(kz[0].size), bits)
+    return tuple(kz)
+
+
+def beaver_and3(X, Y, a, b, c):
+    """One Beaver AND on XOR-shared words; every argument three python ints."""
+    arrs = [np.array(v, dtype=U64) for v in (X, Y, a, b, c)]
+    out = np.zeros(3, dtype=U64)
+    lib().orc3_beaver_and(*[q.ctypes.data_as(_P64) for q in arrs], out.ctypes.data_as(_P64))
+    return tuple(int(v) for v in out)
+
+
+def add3(U, V, W, w, ta, tb, tc):
+    """XOR shares of (U + V + W) mod 2^w from XOR shares (three ints each) of the
+    addends; ta, tb, tc: [1 + 2*log2(w)][3] triple words."""
+    arrs = [np.array(v, dtype=U64) for v in (U, V, W)]
+    t = [np.ascontiguousarray(v, dtype=U64) for v in (ta, tb, tc)]
+    S = np.zeros(3, dtype=U64)
+    lib().orc3_add3(arrs[0].ctypes.data_as(_P64), arrs[1].ctypes.data_as(_P64), arrs[2].ctypes.data_as(_P64),
+                    ctypes.c_int(w), *[q.ctypes.data_as(_P64) for q in t], S.ctypes.data_as(_P64))
+    return tuple(int(v) for v in S)
+
+
+def b2a3(s, rb, ra):
+    sa = np.array(s, dtype=np.uint8); rba = np.array(rb, dtype=np.uint8)
+    raa = np.array(ra, dtype=U64); out = np.zeros(3, dtype=U64)
+    lib().orc3_b2a(sa.ctypes.data_as(_P8), rba.ctypes.data_as(_P8),
+                   raa.ctypes.data_as(_P64), out.ctypes.data_as(_P64))
+    return tuple(int(v) for v in out)
+
+
+class _Relu3MaterialC(ctypes.Structure):
+    _fields_ = [(k, _PP64) for k in ("r0", "r1", "ta", "tb", "tc", "rb", "ra", "ma", "mb", "mc")]
+
+
+def relu3(x, mat) -> ReluResult:
+    """Secure ReLU with three parties.  ``mat``: keys r0, r1, and_a, and_b, and_c
+    ([13, n] each), rb (uint8), ra, ma, mb, mc; every value a triple of arrays."""
+    kx, px = _w3([np.ravel(v) for v in x])
+    n = kx[0].size
+    keep = []
+    m = _Relu3MaterialC()
+    for field, key, dt, size in (("r0", "r0", U64, n), ("r1", "r1", U64, n), ("ta", "and_a", U64, 13 * n),
+                                 ("tb", "and_b", U64, 13 * n), ("tc", "and_c", U64, 13 * n),
+                                 ("rb", "rb", np.uint8, n), ("ra", "ra", U64, n),
+                                 ("ma", "ma", U64, n), ("mb", "mb", U64, n), ("mc", "mc", U64, n)):
+        arrs = [np.ascontiguousarray(np.ravel(v), dtype=dt) for v in mat[key]]
+        assert len(arrs) == 3 and all(a.size == size for a in arrs), key
+        keep.append(arrs)
+        setattr(m, field, _PP64(*[a.ctypes.data for a in arrs]))
+    y, py = _out3(n); sb, psb = _out3(n, np.uint8); sa, psa = _out3(n)
+    lib().orc3_relu(px, ctypes.byref(m), py, ctypes.c_size_t(n), psb, psa)
+    shp = np.shape(x[0])
+    return ReluResult(tuple(v.reshape(shp) for v in y), tuple(v.reshape(shp) for v in sb),
+                      tuple(v.reshape(shp) for v in sa))
 
 
 # --------------------------------------------- checkers on reconstructed values

@@ -538,3 +538,240 @@ void orc_pool_level2(const u64* x, const u64* r1, u64* v_out, u64* d2,
     }
 #undef PX
 }
+
+/* ========================================================= three parties
+ *
+ * Alg. 1 and Alg. 2 are written for N parties (Sec. 3.2; Sec. 3.3 on the
+ * number of parties; Sec. 5.6 measures three).  Below, N = 3: an additive
+ * sharing is x = x_0 + x_1 + x_2, a binary one X = X_0 ^ X_1 ^ X_2, and a
+ * masked value is opened by summing (XORing) what all three parties
+ * broadcast.  Party 0 is again the paper's "Party #1".  Arguments are arrays
+ * of three pointers, one per party.
+ */
+#define NP 3
+
+/* Sec. 3.1: reconstruct an additive sharing. */
+void orc3_open(const u64* const s[NP], u64* out, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = s[0][i] + s[1][i] + s[2][i];
+}
+
+/* Alg. 1, element by element, three parties. */
+void orc3_beaver_mul(const u64* const x[NP], const u64* const y[NP],
+                     const u64* const a[NP], const u64* const b[NP], const u64* const c[NP],
+                     u64* const z[NP], size_t n)
+{
+    for (size_t i = 0; i < n; ++i) {
+        u64 e = 0, f = 0;
+        for (int p = 0; p < NP; ++p) { e += x[p][i] - a[p][i]; f += y[p][i] - b[p][i]; }
+        for (int p = 0; p < NP; ++p) {
+            u64 v = c[p][i] + e * b[p][i] + a[p][i] * f;
+            if (p == 0) v += e * f;
+            z[p][i] = v;
+        }
+    }
+}
+
+/* Alg. 1 on matrices, literally: Delta and epsilon are the sums of the three
+ * broadcast differences; party 0 adds Delta*epsilon (seven ring products). */
+void orc3_beaver_matmul(const u64* const x[NP], const u64* const y[NP],
+                        const u64* const a[NP], const u64* const b[NP], const u64* const c[NP],
+                        u64* const z[NP], int M, int K, int N)
+{
+    const size_t mk = (size_t)M * K, kn = (size_t)K * N, mn = (size_t)M * N;
+    u64 *e = alloc_words(mk), *f = alloc_words(kn), *t = alloc_words(mn);
+    for (size_t i = 0; i < mk; ++i) { e[i] = 0; for (int p = 0; p < NP; ++p) e[i] += x[p][i] - a[p][i]; }
+    for (size_t i = 0; i < kn; ++i) { f[i] = 0; for (int p = 0; p < NP; ++p) f[i] += y[p][i] - b[p][i]; }
+    for (int p = 0; p < NP; ++p) {
+        for (size_t i = 0; i < mn; ++i) z[p][i] = c[p][i];
+        orc_ring_matmul(e, b[p], t, M, K, N);  for (size_t i = 0; i < mn; ++i) z[p][i] += t[i];
+        orc_ring_matmul(a[p], f, t, M, K, N);  for (size_t i = 0; i < mn; ++i) z[p][i] += t[i];
+        if (p == 0) { orc_ring_matmul(e, f, t, M, K, N); for (size_t i = 0; i < mn; ++i) z[p][i] += t[i]; }
+    }
+    free(e); free(f); free(t);
+}
+
+/* Eq. 3 with three parties. */
+void orc3_beaver_conv2d(const u64* const x[NP], const u64* const w[NP],
+                        const u64* const a[NP], const u64* const b[NP], const u64* const c[NP],
+                        u64* const z[NP], int B, int H, int W, int Cin, int Cout,
+                        int KH, int KW, int pad, int stride)
+{
+    const int Ho = (H + 2 * pad - KH) / stride + 1;
+    const int Wo = (W + 2 * pad - KW) / stride + 1;
+    const size_t nx = (size_t)B * H * W * Cin, nw = (size_t)KH * KW * Cin * Cout;
+    const size_t nz = (size_t)B * Ho * Wo * Cout;
+    u64 *e = alloc_words(nx), *f = alloc_words(nw), *t = alloc_words(nz);
+    for (size_t i = 0; i < nx; ++i) { e[i] = 0; for (int p = 0; p < NP; ++p) e[i] += x[p][i] - a[p][i]; }
+    for (size_t i = 0; i < nw; ++i) { f[i] = 0; for (int p = 0; p < NP; ++p) f[i] += w[p][i] - b[p][i]; }
+#define CONV(in, flt) orc_ring_conv2d(in, flt, t, B, H, W, Cin, Cout, KH, KW, pad, stride)
+    for (int p = 0; p < NP; ++p) {
+        for (size_t i = 0; i < nz; ++i) z[p][i] = c[p][i];
+        CONV(e, b[p]);  for (size_t i = 0; i < nz; ++i) z[p][i] += t[i];
+        CONV(a[p], f);  for (size_t i = 0; i < nz; ++i) z[p][i] += t[i];
+        if (p == 0) { CONV(e, f); for (size_t i = 0; i < nz; ++i) z[p][i] += t[i]; }
+    }
+#undef CONV
+    free(e); free(f); free(t);
+}
+
+/* Fixed-point rescale with three parties.  Shifting each share locally is
+ * only sound for two parties; the paper gives no rescale at all (Sec. 1.1
+ * names fixed point, nothing more), so the reading taken here is the usual
+ * masked one with an offline pair ([r], [r >> bits]), r uniform in [0, 2^63):
+ *   parties 1 and 2 send z_i + r_i to party 0, which forms
+ *       m = z + r + 2^62                 (z in [-2^62, 2^62): no wrap mod 2^64)
+ *   [t_0] = (m >> bits) - 2^(62-bits) - [rt_0],   [t_i] = -[rt_i].
+ * m >> bits = (z + 2^62 >> bits) + (r >> bits) + carry of the low parts, so
+ * the result reconstructs to floor(z / 2^bits) + {0, 1}. */
+void orc3_truncate(u64* const z[NP], const u64* const r[NP], const u64* const rt[NP],
+                   size_t n, int bits)
+{
+    for (size_t i = 0; i < n; ++i) {
+        u64 m = (u64)1 << 62;
+        for (int p = 0; p < NP; ++p) m += z[p][i] + r[p][i];
+        z[0][i] = (m >> bits) - ((u64)1 << (62 - bits)) - rt[0][i];
+        z[1][i] = (u64)0 - rt[1][i];
+        z[2][i] = (u64)0 - rt[2][i];
+    }
+}
+
+/* Beaver AND with three parties (Alg. 1 with xor for + and and for *). */
+static inline void beaver_and3(const u64 X[NP], const u64 Y[NP],
+                               const u64 a[NP], const u64 b[NP], const u64 c[NP], u64 out[NP])
+{
+    u64 d = 0, g = 0;
+    for (int p = 0; p < NP; ++p) { d ^= X[p] ^ a[p]; g ^= Y[p] ^ b[p]; }
+    for (int p = 0; p < NP; ++p) out[p] = c[p] ^ (d & b[p]) ^ (g & a[p]);
+    out[0] ^= d & g;
+}
+
+void orc3_beaver_and(const u64* X, const u64* Y, const u64* a, const u64* b, const u64* c, u64* out)
+{
+    beaver_and3(X, Y, a, b, c, out);
+}
+
+/* Alg. 2, first half, three parties: party j XOR-shares its own word x_j by
+ * keeping x_j ^ r0_j ^ r1_j, sending r0_j to party j+1 and r1_j to party j+2
+ * (indices mod 3).  Wd[j][p] = party p's share of the word x_j. */
+static inline void a2b_distribute3(const u64 x[NP], const u64 r0[NP], const u64 r1[NP], u64 Wd[NP][NP])
+{
+    for (int j = 0; j < NP; ++j) {
+        Wd[j][j] = x[j] ^ r0[j] ^ r1[j];
+        Wd[j][(j + 1) % NP] = r0[j];
+        Wd[j][(j + 2) % NP] = r1[j];
+    }
+}
+
+/* Alg. 2, last step, three parties: "binary operations" that add the three
+ * binary-shared words.  The paper names no circuit for more than two
+ * addends; the reading taken here is the hardware-adder one: a carry-save
+ * step turns three addends into two,
+ *     S = U ^ V ^ W,   C = maj(U, V, W) = ((U ^ W) & (V ^ W)) ^ W   (triple 0)
+ * and the same Kogge-Stone network as for two parties adds S and C << 1:
+ *     P = S ^ K,  G = S & K with K = C << 1                          (triple 1)
+ *     level l, d = 2^l:  G <- G ^ (P & (G << d))                     (triple 2 + 2l)
+ *                        P <- P & (P << d)    unless last level      (triple 3 + 2l)
+ * 1 + 2*levels triples for width w = 2^levels.  Returns the carries G and
+ * the initial P = S ^ K. */
+static void add3_carries(const u64 U[NP], const u64 V[NP], const u64 W[NP], int w,
+                         const u64 (*ta)[NP], const u64 (*tb)[NP], const u64 (*tc)[NP],
+                         u64 G[NP], u64 P0_out[NP])
+{
+    const u64 wm = width_mask(w);
+    u64 X[NP], Y[NP], T[NP], S[NP], K[NP], P[NP];
+    for (int p = 0; p < NP; ++p) { X[p] = U[p] ^ W[p]; Y[p] = V[p] ^ W[p]; S[p] = U[p] ^ V[p] ^ W[p]; }
+    beaver_and3(X, Y, ta[0], tb[0], tc[0], T);
+    for (int p = 0; p < NP; ++p) { K[p] = ((T[p] ^ W[p]) << 1) & wm; P[p] = S[p] ^ K[p]; P0_out[p] = P[p]; }
+    beaver_and3(S, K, ta[1], tb[1], tc[1], G);
+    int levels = 0; while ((1 << levels) < w) ++levels;
+    for (int l = 0; l < levels; ++l) {
+        const int d = 1 << l;
+        u64 Gs[NP], Ps[NP], Pn[NP];
+        for (int p = 0; p < NP; ++p) { Gs[p] = (G[p] << d) & wm; Ps[p] = (P[p] << d) & wm; }
+        beaver_and3(P, Gs, ta[2 + 2 * l], tb[2 + 2 * l], tc[2 + 2 * l], T);
+        if (l < levels - 1) beaver_and3(P, Ps, ta[3 + 2 * l], tb[3 + 2 * l], tc[3 + 2 * l], Pn);
+        for (int p = 0; p < NP; ++p) { G[p] ^= T[p]; if (l < levels - 1) P[p] = Pn[p]; }
+    }
+}
+
+/* Exported for tests: XOR shares of (U + V + W) mod 2^w.  U, V, W: three
+ * share words each; ta/tb/tc: [1 + 2*levels][3] words, triple-major. */
+void orc3_add3(const u64* U, const u64* V, const u64* W, int w,
+               const u64* ta, const u64* tb, const u64* tc, u64* S)
+{
+    u64 G[NP], P0[NP];
+    add3_carries(U, V, W, w, (const u64 (*)[NP])ta, (const u64 (*)[NP])tb, (const u64 (*)[NP])tc, G, P0);
+    const u64 wm = width_mask(w);
+    for (int p = 0; p < NP; ++p) S[p] = P0[p] ^ ((G[p] << 1) & wm);
+}
+
+/* Per-party material for n elements of the three-party ReLU:
+ *   r0, r1    n words each   A2B masks (sent to the next / the second-next party)
+ *   ta/tb/tc  [13][n]        AND triples, triple-major
+ *   rb        n bytes (0/1)  XOR-shared random bit, ra: additive shares of that bit
+ *   ma/mb/mc  n words        element-wise multiplication triple
+ */
+typedef struct {
+    const u64* r0[NP]; const u64* r1[NP];
+    const u64* ta[NP]; const u64* tb[NP]; const u64* tc[NP];
+    const u8*  rb[NP]; const u64* ra[NP];
+    const u64* ma[NP]; const u64* mb[NP]; const u64* mc[NP];
+} orc3_relu_material;
+
+/* B2A of one XOR-shared bit with a shared random bit, three parties:
+ * open v = s ^ rb; [s]_0 = ra_0 + v - 2 v ra_0, [s]_i = ra_i - 2 v ra_i. */
+static inline void b2a3(const u64 s[NP], const u64 rb[NP], const u64 ra[NP], u64 out[NP])
+{
+    u64 v = 0;
+    for (int p = 0; p < NP; ++p) v ^= s[p] ^ rb[p];
+    for (int p = 0; p < NP; ++p) out[p] = ra[p] - 2 * v * ra[p];
+    out[0] += v;
+}
+
+void orc3_b2a(const u8* s, const u8* rb, const u64* ra, u64* out)
+{
+    const u64 s64[NP] = { s[0], s[1], s[2] }, rb64[NP] = { rb[0], rb[1], rb[2] };
+    b2a3(s64, rb64, ra, out);
+}
+
+/* ReLU(x) = x * (1 - MSB(x)), three parties: A2B distribution, the
+ * three-addend adder above (13 triples), sign share
+ * s_p = bit63(P0_p) ^ bit62(G_p), B2A, m = 1 - s (party 0 holds the 1),
+ * y = x * m by element-wise Alg. 1 without rescale. */
+void orc3_relu(const u64* const x[NP], const orc3_relu_material* mt, u64* const y[NP], size_t n,
+               u8* const s_bit[NP], u64* const s_ar[NP])
+{
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+        u64 xs[NP], r0[NP], r1[NP], Wd[NP][NP], G[NP], P0[NP];
+        u64 ta[13][NP], tb[13][NP], tc[13][NP];
+        for (int p = 0; p < NP; ++p) {
+            xs[p] = x[p][i]; r0[p] = mt->r0[p][i]; r1[p] = mt->r1[p][i];
+            for (int t = 0; t < 13; ++t) {
+                ta[t][p] = mt->ta[p][(size_t)t * n + i];
+                tb[t][p] = mt->tb[p][(size_t)t * n + i];
+                tc[t][p] = mt->tc[p][(size_t)t * n + i];
+            }
+        }
+        a2b_distribute3(xs, r0, r1, Wd);
+        add3_carries(Wd[0], Wd[1], Wd[2], 64, ta, tb, tc, G, P0);
+        u64 s[NP], rb[NP], ra[NP], sa[NP], m[NP];
+        for (int p = 0; p < NP; ++p) {
+            s[p] = (P0[p] >> 63) ^ ((G[p] >> 62) & 1);
+            rb[p] = mt->rb[p][i]; ra[p] = mt->ra[p][i];
+        }
+        b2a3(s, rb, ra, sa);
+        for (int p = 0; p < NP; ++p) m[p] = (u64)(p == 0) - sa[p];
+        u64 e = 0, f = 0;
+        for (int p = 0; p < NP; ++p) { e += xs[p] - mt->ma[p][i]; f += m[p] - mt->mb[p][i]; }
+        for (int p = 0; p < NP; ++p) {
+            u64 v = mt->mc[p][i] + e * mt->mb[p][i] + mt->ma[p][i] * f;
+            if (p == 0) v += e * f;
+            y[p][i] = v;
+            if (s_bit && s_bit[p]) s_bit[p][i] = (u8)s[p];
+            if (s_ar && s_ar[p]) s_ar[p][i] = sa[p];
+        }
+    }
+}
+#undef NP

@@ -86,6 +86,57 @@ def deal_relu_material(rng, n: int) -> dict:
     return m
 
 
+# ---------------------------------------------------------------- three parties
+N_AND_TRIPLES3 = 13  # majority of the carry-save step + the 12 of the two-addend adder
+
+
+def share_additive3(rng, value):
+    """(s0, s1, s2) with s0, s1 uniform and s0 + s1 + s2 = value mod 2^64."""
+    value = np.asarray(value, dtype=U64)
+    s0 = rand_words(rng, value.shape); s1 = rand_words(rng, value.shape)
+    return s0, s1, value - s0 - s1
+
+
+def share_xor3(rng, value):
+    value = np.asarray(value, dtype=U64)
+    s0 = rand_words(rng, value.shape); s1 = rand_words(rng, value.shape)
+    return s0, s1, value ^ s0 ^ s1
+
+
+def deal_product_triple3(rng, a_shape, b_shape, product):
+    A = rand_words(rng, a_shape); B = rand_words(rng, b_shape)
+    C = np.asarray(product(A, B), dtype=U64)
+    return share_additive3(rng, A), share_additive3(rng, B), share_additive3(rng, C)
+
+
+def deal_trunc3_pair(rng, shape, bits: int = FRAC_BITS):
+    """Offline pair of the three-party rescale: shares of r uniform in [0, 2^63) and of r >> bits."""
+    r = rng.integers(0, 1 << 63, size=shape, dtype=U64)
+    return share_additive3(rng, r), share_additive3(rng, r >> U64(bits))
+
+
+def deal_relu3_material(rng, n: int) -> dict:
+    """Offline material for n three-party ReLU elements; every value a (party 0, 1, 2) triple.
+
+    r0, r1   A2B masks party j sends to party j+1 / j+2 (mod 3), n words each
+    and_a/b/c  [13, n] XOR-shared AND triples
+    rb, ra   XOR-shared random bit (uint8) and additive shares of the same bit
+    ma/mb/mc element-wise multiplication triple for the select step
+    """
+    m = {}
+    m["r0"] = tuple(rand_words(rng, n) for _ in range(3))
+    m["r1"] = tuple(rand_words(rng, n) for _ in range(3))
+    A = rand_words(rng, (N_AND_TRIPLES3, n)); B = rand_words(rng, (N_AND_TRIPLES3, n))
+    m["and_a"] = share_xor3(rng, A); m["and_b"] = share_xor3(rng, B); m["and_c"] = share_xor3(rng, A & B)
+    bit = rng.integers(0, 2, size=n, dtype=np.uint8)
+    b0 = rng.integers(0, 2, size=n, dtype=np.uint8); b1 = rng.integers(0, 2, size=n, dtype=np.uint8)
+    m["rb"] = (b0, b1, bit ^ b0 ^ b1)
+    m["ra"] = share_additive3(rng, bit.astype(U64))
+    MA = rand_words(rng, n); MB = rand_words(rng, n)
+    m["ma"] = share_additive3(rng, MA); m["mb"] = share_additive3(rng, MB); m["mc"] = share_additive3(rng, MA * MB)
+    return m
+
+
 # ------------------------------------------------------------------- workloads
 @dataclass
 class Gemm:
