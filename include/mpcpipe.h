@@ -408,6 +408,79 @@ int mpc_maxpool2x2_backward(mpc_ctx* ctx, mpc_cshare g, mpc_cshare s1, mpc_cshar
                             mpc_cshare a2, mpc_cshare b2, mpc_cshare c2,
                             mpc_share gx, int B, int H, int W, int C);
 
+/* ------------------------------------------ three parties (Sec. 3.3, Sec. 5.6) */
+
+/* Alg. 1 and Alg. 2 are stated for N parties.  The calls below run them for
+ * three simulated parties: an additive sharing is x = x_0 + x_1 + x_2, a
+ * masked value is opened by summing what the three parties broadcast, and
+ * party 0 (the paper's "Party #1") adds the Delta*epsilon term.  All work is
+ * issued on the lane's first stream (the other two streams of the lane wait
+ * for it on return), one launch per step for all parties, every exchange a
+ * copy kernel; outputs are valid after any stream of the lane, or
+ * mpc_ctx_sync.  Pointers are device memory, one per party; nothing is
+ * allocated.  Errors as for the two-party calls. */
+typedef struct { const uint64_t* p[3]; } mpc_cshare3;
+typedef struct { uint64_t* p[3]; } mpc_share3;
+
+/* out[k] = s_0[k] + s_1[k] + s_2[k].  Needs 24*n bytes of workspace. */
+int mpc_open3(mpc_ctx* ctx, mpc_cshare3 s, uint64_t* out_public, size_t n);
+
+/* Alg. 1 / Eq. 3 with three parties: z_i = c_i + e*b_i + a_i*f (+ e*f for
+ * i = 0), e and f the sums of the three broadcast differences.  Shapes,
+ * layouts and f_public as for mpc_beaver_matmul / mpc_conv2d; flags:
+ * MPC_TRANS_X, MPC_TRANS_Y only (the rescale needs an exchange with three
+ * parties: follow with mpc_truncate3).  Six ring products on the matrix
+ * cores: parties 0 and 1 in one launch, party 2 in a second one. */
+size_t mpc_matmul3_workspace_bytes(int M, int K, int N, int batch);
+int mpc_beaver_matmul3(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 y,
+                       mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 c, mpc_share3 z,
+                       int M, int K, int N, int batch,
+                       const uint64_t* f_public, int flags);
+size_t mpc_conv2d3_workspace_bytes(int B, int H, int W, int Cin, int Cout,
+                                   int KH, int KW, int pad, int stride);
+int mpc_conv2d3(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 w,
+                mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 c, mpc_share3 z,
+                int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                int pad, int stride, const uint64_t* f_public);
+
+/* Fixed-point rescale with three parties, in place.  Shifting every share
+ * locally is sound for two parties only, and the paper states no rescale
+ * (Sec. 1.1 names fixed point, nothing more); this is the usual masked one
+ * with an offline pair: r uniform in [0, 2^63) shared as r, its shift
+ * r >> bits shared as rt.  Parties 1 and 2 send z_i + r_i to party 0, which
+ * forms m = z + r + 2^62 (no wrap for z in [-2^62, 2^62)) and
+ *   z_0 <- (m >> bits) - 2^(62-bits) - rt_0,   z_i <- -rt_i  (i = 1, 2).
+ * The result reconstructs to floor(z / 2^bits) + {0, 1}.  0 <= bits <= 62. */
+size_t mpc_truncate3_workspace_bytes(size_t n);
+int mpc_truncate3(mpc_ctx* ctx, mpc_share3 z, mpc_cshare3 r, mpc_cshare3 rt,
+                  size_t n, int bits);
+
+/* Offline material of the three-party ReLU for n elements:
+ *   r0, r1       n words each  A2B masks: party j keeps x_j ^ r0_j ^ r1_j,
+ *                              sends r0_j to party j+1 and r1_j to party j+2 (mod 3)
+ *   and_a/b/c    [13][n]       XOR-shared AND triples: 0 the majority of the
+ *                              carry-save step, 1 for G = S & K, 2+2l / 3+2l
+ *                              for prefix level l
+ *   rb, ra, ma, mb, mc         as in mpc_relu_material */
+typedef struct {
+    mpc_cshare3 r0, r1;
+    mpc_cshare3 and_a, and_b, and_c;
+    const uint8_t* rb[3];
+    mpc_cshare3 ra;
+    mpc_cshare3 ma, mb, mc;
+} mpc_relu3_material;
+
+/* y = ReLU(x) with three parties.  Alg. 2's last step has to add three
+ * binary-shared words; the paper names no circuit for that, and the one used
+ * is a carry-save step S = U ^ V ^ W, C = ((U ^ W) & (V ^ W)) ^ W (one Beaver
+ * AND) followed by the Kogge-Stone network of mpc_relu on S and C << 1:
+ * 13 word ANDs, 10 word exchanges and one byte exchange, each to both peers.
+ * Sign, B2A and select as in mpc_relu.  s_bit / s_arith: optional outputs
+ * (n bytes / n words per party), NULL to skip.  Whole-word chain, no chunking. */
+size_t mpc_relu3_workspace_bytes(size_t n);
+int mpc_relu3(mpc_ctx* ctx, mpc_cshare3 x, const mpc_relu3_material* mat, mpc_share3 y,
+              size_t n, uint8_t* const s_bit[3], uint64_t* const s_arith[3]);
+
 /* -------------------------------------------------- dealer helper (offline) */
 
 /* Plain ring product Z = L*R mod 2^64 on public device arrays, computed with

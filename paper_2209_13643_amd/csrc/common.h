@@ -88,6 +88,16 @@ static inline int lane_join(mpc_ctx* c)
     return MPC_OK;
 }
 
+// End of an entry point that issued everything on the lane's first stream: the
+// other two streams wait for it, so whichever stream the caller synchronises
+// sees the outputs.
+static inline int lane_fanout(mpc_ctx* c)
+{
+    MPC_TRY(chain(c, c->s[0], c->s[1]));
+    if (c->s[2] != c->s[1]) MPC_TRY(chain(c, c->s[0], c->s[2]));
+    return MPC_OK;
+}
+
 // Timing regions (no-ops unless profiling is on): prof_begin records a start
 // event on `st` and returns its index, prof_end records the matching stop.
 static inline int prof_begin(mpc_ctx* c, int which, hipStream_t st)
@@ -125,6 +135,7 @@ int launch_add(mpc_ctx* c, hipStream_t st, const u64* x, const u64* y, u64* out,
 int launch_copy(mpc_ctx* c, hipStream_t st, const void* src, void* dst, size_t bytes);
 int launch_fill_zero(mpc_ctx* c, hipStream_t st, void* dst, size_t bytes);
 int launch_truncate(mpc_ctx* c, hipStream_t st, u64* z, size_t n, int bits, int party);
+int launch_sum3(mpc_ctx* c, hipStream_t st, const u64* x, const u64* y, const u64* w, u64* out, size_t n);
 
 // ---- digit planes -------------------------------------------------------------
 // A digit-plane tensor stores a [rows][K] ring matrix as eight int8 planes,
@@ -192,7 +203,7 @@ struct DilateArgs { const u64* src[4]; u64* dst[4]; int B, Ho, Wo, Hd, Wd, C, st
 int launch_dilate(mpc_ctx* c, hipStream_t st, const DilateArgs& q);
 
 // several element-wise jobs in one launch (single-queue lanes)
-constexpr int kMaxSegs = 4;
+constexpr int kMaxSegs = 6;
 struct SubSeg { const u64* x; const u64* a; u64* out; size_t n; int vec; u64* out2; };   // out2: optional second destination
 struct SubBatch { SubSeg s[kMaxSegs]; };
 struct CopySeg { const u8* src; u8* dst; size_t bytes; int vec; };

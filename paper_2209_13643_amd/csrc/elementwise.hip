@@ -398,6 +398,14 @@ __global__ __launch_bounds__(kThreads) void k_copy_multi(CopyBatch cb)
     }
 }
 
+// out = x + y + w: the opening of a three-party additive sharing.
+__global__ __launch_bounds__(kThreads) void k_sum3(const u64* __restrict__ x, const u64* __restrict__ y,
+                                                   const u64* __restrict__ w, u64* __restrict__ out, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) out[i] = x[i] + y[i] + w[i];
+}
+
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 template <int OP>
@@ -445,6 +453,14 @@ int launch_fill_zero(mpc_ctx* c, hipStream_t st, void* dst, size_t bytes)
     if (bytes == 0) return MPC_OK;
     if (!aligned16(dst) || bytes % 16) return MPC_EINVAL;
     hipLaunchKernelGGL(k_zero16, dim3(grid_for(bytes / 16)), dim3(kThreads), 0, st, (uint4*)dst, bytes / 16);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+int launch_sum3(mpc_ctx* c, hipStream_t st, const u64* x, const u64* y, const u64* w, u64* out, size_t n)
+{
+    if (n == 0) return MPC_OK;
+    hipLaunchKernelGGL(k_sum3, dim3(grid_for(n)), dim3(kThreads), 0, st, x, y, w, out, n);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
 }

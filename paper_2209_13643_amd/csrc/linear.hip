@@ -409,6 +409,110 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
     return MPC_OK;
 }
 
+// ---- three parties -------------------------------------------------------------
+struct LinearWs3 {
+    u64 *se[3], *re[3][2];     // masked x shares: own, and as received from party+1 / party+2
+    u64 *sf[3], *rf[3][2];     // masked y shares
+    u64 *e_pub, *f_pub;        // opened e, f
+    u8 *pl_e, *pl_a[3];
+    u8 *pr_f, *pr_b[3];        // pr_b[0] holds b_0 + f
+    LinearWs g;                // zero bytes, split count and partial products for the GEMM launches
+    size_t bytes; bool ok;
+};
+
+LinearWs3 carve3(u8* base, size_t cap, const LinearShape& s)
+{
+    WsAlloc w(base, cap);
+    LinearWs3 r{};
+    r.g.zero = w.take<u8>(256);
+    for (int i = 0; i < 3; ++i) { r.se[i] = w.take<u64>(s.nx); r.re[i][0] = w.take<u64>(s.nx); r.re[i][1] = w.take<u64>(s.nx); }
+    for (int i = 0; i < 3; ++i) { r.sf[i] = w.take<u64>(s.nw); r.rf[i][0] = w.take<u64>(s.nw); r.rf[i][1] = w.take<u64>(s.nw); }
+    r.e_pub = w.take<u64>(s.nx); r.f_pub = w.take<u64>(s.nw);
+    const size_t lp = 8 * s.L_plane * s.batch, rp = 8 * s.R_plane * s.batch;
+    r.pl_e = w.take<u8>(lp); for (int i = 0; i < 3; ++i) r.pl_a[i] = w.take<u8>(lp);
+    r.pr_f = w.take<u8>(rp); for (int i = 0; i < 3; ++i) r.pr_b[i] = w.take<u8>(rp);
+    r.g.ksplit = gemm_ksplit(s.M, s.N, s.batch, 2, 2 * s.KB / 2);
+    r.g.partial = r.g.ksplit > 1 ? w.take<u64>((size_t)r.g.ksplit * 2 * s.batch * s.M * s.N) : nullptr;
+    r.bytes = w.off; r.ok = w.ok;
+    return r;
+}
+
+// Alg. 1 / Eq. 3 with three parties, everything on the lane's first stream:
+// mask, broadcast to both peers, open e and f, recode, then the two-segment
+// contraction [e | a_i] x [b_i (+ f for party 0) ; f] for parties 0 and 1 in
+// one launch and for party 2 in a second one.
+int beaver_linear3(mpc_ctx* c, const LinearShape& s, mpc_cshare3 x, mpc_cshare3 y,
+                   mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 cc, mpc_share3 z, const u64* f_public)
+{
+    if (!c) return MPC_EINVAL;
+    MPC_TRY(check_shape(s));
+    for (int i = 0; i < 3; ++i) {
+        if (!x.p[i] || !a.p[i] || !b.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
+        if (!f_public && !y.p[i]) return MPC_EINVAL;
+    }
+    LinearWs3 w = carve3(c->ws, c->ws_bytes, s);
+    if (!w.ok) return MPC_ENOMEM;
+    hipStream_t st = c->s[0];
+    MPC_TRY(lane_join(c));
+    const int pi = prof_begin(c, MPC_PROF_LINEAR, st);
+
+    // Alg. 1: every party masks its shares ...
+    SubSeg sub[6]; int ns = 0;
+    for (int i = 0; i < 3; ++i) sub[ns++] = SubSeg{ x.p[i], a.p[i], w.se[i], s.nx, 0, nullptr };
+    for (int i = 0; i < 3 && !f_public; ++i) sub[ns++] = SubSeg{ y.p[i], b.p[i], w.sf[i], s.nw, 0, nullptr };
+    MPC_TRY(launch_sub_multi(c, st, sub, ns));
+    // ... and broadcasts them: party i receives from party i+1 and party i+2
+    CopySeg cp[6];
+    for (int i = 0; i < 3; ++i)
+        for (int k = 0; k < 2; ++k)
+            cp[2 * i + k] = CopySeg{ (const u8*)w.se[(i + 1 + k) % 3], (u8*)w.re[i][k], s.nx * sizeof(u64), 0 };
+    MPC_TRY(launch_copy_multi(c, st, cp, 6));
+    if (!f_public) {
+        for (int i = 0; i < 3; ++i)
+            for (int k = 0; k < 2; ++k)
+                cp[2 * i + k] = CopySeg{ (const u8*)w.sf[(i + 1 + k) % 3], (u8*)w.rf[i][k], s.nw * sizeof(u64), 0 };
+        MPC_TRY(launch_copy_multi(c, st, cp, 6));
+    }
+    // Delta and epsilon (all parties hold the same three words; formed once, from party 0's buffers)
+    MPC_TRY(launch_sum3(c, st, w.se[0], w.re[0][0], w.re[0][1], w.e_pub, s.nx));
+    const u64* f = f_public;
+    if (!f) { MPC_TRY(launch_sum3(c, st, w.sf[0], w.rf[0][0], w.rf[0][1], w.f_pub, s.nw)); f = w.f_pub; }
+
+    // digit planes
+    {
+        const u64* src[3] = { a.p[0], a.p[1], a.p[2] };
+        const u64* none[3] = { nullptr, nullptr, nullptr };
+        u8* dst[3] = { w.pl_a[0], w.pl_a[1], w.pl_a[2] };
+        MPC_TRY(launch_left(c, st, s, 3, src, none, dst));
+        MPC_TRY(launch_left1(c, st, s, w.e_pub, nullptr, w.pl_e));
+        RecodeArgs rr[4];
+        rr[0] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
+        rr[1] = recode_right(s, b.p[2], nullptr, nullptr, w.pr_b[2]);
+        rr[2] = recode_right(s, f, nullptr, nullptr, w.pr_f);
+        rr[3] = recode_right(s, b.p[0], f, nullptr, w.pr_b[0]);
+        MPC_TRY(launch_recode_multi(c, st, rr, 4));
+    }
+
+    GemmArgs g{};
+    fill_geom(s, w.g, g);
+    g.nseg = 2; g.trunc_bits = 0;
+    g.nparty = 2;
+    for (int i = 0; i < 2; ++i) {
+        g.seg[i][0] = make_seg(s, w.pl_e, w.pr_b[i]);
+        g.seg[i][1] = make_seg(s, w.pl_a[i], w.pr_f);
+        g.addend[i] = cc.p[i]; g.addend2[i] = nullptr; g.out[i] = z.p[i];
+    }
+    MPC_TRY(launch_limb_gemm(c, st, g));
+    g.nparty = 1;
+    g.seg[0][0] = make_seg(s, w.pl_e, w.pr_b[2]);
+    g.seg[0][1] = make_seg(s, w.pl_a[2], w.pr_f);
+    g.addend[0] = cc.p[2]; g.out[0] = z.p[2];
+    g.seg[1][0] = GemmSeg{}; g.seg[1][1] = GemmSeg{}; g.addend[1] = nullptr; g.out[1] = nullptr;
+    MPC_TRY(launch_limb_gemm(c, st, g));
+    prof_end(c, MPC_PROF_LINEAR, pi, st);
+    return lane_fanout(c);
+}
+
 // Digit planes of the input-independent operands of a layer, recoded once:
 // right = [f | b_0 + f | b_1] (needs the opened weight mask f), left = [a_0 | a_1].
 void prepared_sizes(const LinearShape& s, size_t* right, size_t* left)
@@ -660,6 +764,38 @@ int mpc_ring_conv2d_grad_w(mpc_ctx* ctx, const uint64_t* x, const uint64_t* g, u
         return MPC_EINVAL;
     if (H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return MPC_EINVAL;
     return ring_product(ctx, shape_conv_grad_w(B, H, W, Cin, Cout, KH, KW, pad, stride), x, g, gw);
+}
+
+size_t mpc_matmul3_workspace_bytes(int M, int K, int N, int batch)
+{
+    if (M <= 0 || K <= 0 || N <= 0 || batch <= 0) return 0;
+    LinearShape s = shape_matmul(M, K, N, batch);
+    if (check_shape(s) != MPC_OK) return 0;
+    return carve3(nullptr, 0, s).bytes;
+}
+
+int mpc_beaver_matmul3(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 y, mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 c,
+                       mpc_share3 z, int M, int K, int N, int batch, const uint64_t* f_public, int flags)
+{
+    if (M <= 0 || K <= 0 || N <= 0 || batch <= 0 || (flags & ~(MPC_TRANS_X | MPC_TRANS_Y))) return MPC_EINVAL;
+    return beaver_linear3(ctx, shape_matmul(M, K, N, batch, flags), x, y, a, b, c, z, f_public);
+}
+
+size_t mpc_conv2d3_workspace_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (stride <= 0) return 0;
+    LinearShape s = shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride);
+    if (check_shape(s) != MPC_OK) return 0;
+    return carve3(nullptr, 0, s).bytes;
+}
+
+int mpc_conv2d3(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 w, mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 c,
+                mpc_share3 z, int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride,
+                const uint64_t* f_public)
+{
+    if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
+        return MPC_EINVAL;
+    return beaver_linear3(ctx, shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride), x, w, a, b, c, z, f_public);
 }
 
 }  // extern "C"

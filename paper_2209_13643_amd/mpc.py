@@ -36,6 +36,17 @@ class ReluMaterial(ctypes.Structure):
                 ("rb", _P8 * 2), ("ra", CShare), ("ma", CShare), ("mb", CShare), ("mc", CShare)]
 
 
+class CShare3(ctypes.Structure):
+    _fields_ = [("p", _P64 * 3)]
+
+
+class Relu3Material(ctypes.Structure):
+    _fields_ = [("r0", CShare3), ("r1", CShare3), ("and_a", CShare3), ("and_b", CShare3), ("and_c", CShare3),
+                ("rb", _P8 * 3), ("ra", CShare3), ("ma", CShare3), ("mb", CShare3), ("mc", CShare3)]
+
+
+N_AND_TRIPLES3 = 13
+
 EXPORTS = [
     "mpc_ctx_create", "mpc_ctx_destroy", "mpc_ctx_set_streams", "mpc_ctx_stream", "mpc_ctx_set_workspace",
     "mpc_ctx_sync", "mpc_ctx_wait", "mpc_last_hip_error", "mpc_strerror",
@@ -53,6 +64,8 @@ EXPORTS = [
     "mpc_matmul_prepared_bytes", "mpc_conv2d_prepared_bytes", "mpc_matmul_prepare", "mpc_conv2d_prepare",
     "mpc_beaver_matmul_prepared", "mpc_conv2d_prepared",
     "mpc_ctx_capture_begin", "mpc_ctx_capture_end", "mpc_graph_launch", "mpc_graph_destroy",
+    "mpc_open3", "mpc_matmul3_workspace_bytes", "mpc_beaver_matmul3", "mpc_conv2d3_workspace_bytes", "mpc_conv2d3",
+    "mpc_truncate3_workspace_bytes", "mpc_truncate3", "mpc_relu3_workspace_bytes", "mpc_relu3",
 ]
 
 _lib = None
@@ -127,6 +140,16 @@ def lib():
     L.mpc_maxpool2x2_msb.argtypes = L.mpc_maxpool2x2.argtypes
     L.mpc_ring_matmul.argtypes = [c_void_p, _P64, _P64, _P64] + [c_int] * 4
     L.mpc_ring_conv2d.argtypes = [c_void_p, _P64, _P64, _P64] + [c_int] * 9
+    L.mpc_open3.argtypes = [c_void_p, CShare3, _P64, c_size_t]
+    L.mpc_matmul3_workspace_bytes.argtypes = [c_int] * 4; L.mpc_matmul3_workspace_bytes.restype = c_size_t
+    L.mpc_conv2d3_workspace_bytes.argtypes = [c_int] * 9; L.mpc_conv2d3_workspace_bytes.restype = c_size_t
+    L.mpc_beaver_matmul3.argtypes = [c_void_p] + [CShare3] * 6 + [c_int] * 4 + [_P64, c_int]
+    L.mpc_conv2d3.argtypes = [c_void_p] + [CShare3] * 6 + [c_int] * 9 + [_P64]
+    L.mpc_truncate3_workspace_bytes.argtypes = [c_size_t]; L.mpc_truncate3_workspace_bytes.restype = c_size_t
+    L.mpc_truncate3.argtypes = [c_void_p, CShare3, CShare3, CShare3, c_size_t, c_int]
+    L.mpc_relu3_workspace_bytes.argtypes = [c_size_t]; L.mpc_relu3_workspace_bytes.restype = c_size_t
+    L.mpc_relu3.argtypes = [c_void_p, CShare3, POINTER(Relu3Material), CShare3, c_size_t,
+                            POINTER(_P8 * 3), POINTER(_P64 * 3)]
     _lib = L
     return L
 
@@ -157,6 +180,34 @@ def _share(pair):
     return s
 
 
+def _share3(tri):
+    s = CShare3()
+    if tri is None:
+        tri = (None, None, None)
+    if len(tri) != 3:
+        raise ValueError("a three-party sharing is a triple of tensors")
+    for i in range(3):
+        s.p[i] = _p64(tri[i])
+    return s
+
+
+def _material3(mat: dict, n: int) -> Relu3Material:
+    m = Relu3Material()
+    for key in ("r0", "r1", "ra", "ma", "mb", "mc"):
+        if any(t.numel() != n for t in mat[key]):
+            raise ValueError(f"material '{key}': {n} words per party expected")
+        setattr(m, key, _share3(mat[key]))
+    for key in ("and_a", "and_b", "and_c"):
+        if any(t.numel() != N_AND_TRIPLES3 * n for t in mat[key]):
+            raise ValueError(f"material '{key}': [13][{n}] words per party expected")
+        setattr(m, key, _share3(mat[key]))
+    if any(t.numel() != n for t in mat["rb"]):
+        raise ValueError("material 'rb': one byte per element and party expected")
+    for i in range(3):
+        m.rb[i] = _p8(mat["rb"][i])
+    return m
+
+
 def to_device(arr, device="cuda:0"):
     """numpy uint64 / uint8 array -> device tensor with the same bits."""
     import numpy as np
@@ -174,7 +225,7 @@ def to_host(t):
 
 
 def material_to_device(mat: dict, device="cuda:0") -> dict:
-    return {k: (to_device(v[0], device), to_device(v[1], device)) for k, v in mat.items()}
+    return {k: tuple(to_device(q, device) for q in v) for k, v in mat.items()}
 
 
 def _material(mat: dict, n: int, packed: bool = False) -> ReluMaterial:
@@ -241,6 +292,7 @@ class Lane:
         self._h = c_void_p()
         self._check(lib().mpc_ctx_create(byref(self._h), device, frac_bits))
         self._ws = None
+        self._ws_bytes = 0
 
     # -- plumbing
     def _check(self, rc: int):
@@ -321,13 +373,14 @@ class Lane:
         """Make the workspace at least nbytes large (syncs the lane if it has to grow)."""
         if nbytes <= 0:
             raise MpcError("workspace query rejected the shape")
-        if self._ws is None or self._ws.numel() < nbytes:
+        if self._ws is None or self._ws_bytes < nbytes:
             if self._ws is not None:
                 self.sync()
             self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
             base = self._ws.data_ptr()
             off = (-base) % 256
             self._check(lib().mpc_ctx_set_workspace(self._h, c_void_p(base + off), nbytes))
+            self._ws_bytes = nbytes          # what the library was told, not the tensor's padded size
 
     # -- protocol calls
     def open(self, s):
@@ -468,6 +521,62 @@ class Lane:
                                                   _share(t1[0]), _share(t1[1]), _share(t1[2]),
                                                   _share(t2[0]), _share(t2[1]), _share(t2[2]), _share(gx), B, H, W, C))
         return gx
+
+    # -- three parties (every argument a triple of tensors, one per party)
+    def _empty3(self, like):
+        return tuple(torch.empty_like(like) for _ in range(3))
+
+    def open3(self, s):
+        n = s[0].numel()
+        self.reserve(3 * (n * 8 + 256))
+        out = torch.empty_like(s[0])
+        self._check(lib().mpc_open3(self._h, _share3(s), _p64(out), n))
+        return out
+
+    def beaver_matmul3(self, x, y, a, b, c, f_public=None, flags=0, out=None):
+        shp = a[0].shape
+        batch = 1 if len(shp) == 2 else shp[0]
+        M, K = (shp[-1], shp[-2]) if flags & MPC_TRANS_X else (shp[-2], shp[-1])
+        K2, N = (b[0].shape[-1], b[0].shape[-2]) if flags & MPC_TRANS_Y else (b[0].shape[-2], b[0].shape[-1])
+        if K2 != K or tuple(c[0].shape[-2:]) != (M, N):
+            raise ValueError("operand shapes do not match")
+        self.reserve(lib().mpc_matmul3_workspace_bytes(M, K, N, batch))
+        z = out if out is not None else self._empty3(c[0])
+        self._check(lib().mpc_beaver_matmul3(self._h, _share3(x), _share3(y), _share3(a), _share3(b), _share3(c),
+                                             _share3(z), M, K, N, batch, _p64(f_public), flags))
+        return z
+
+    def conv2d3(self, x, w, a, b, c, pad, stride, f_public=None, out=None):
+        B, H, W, Cin = a[0].shape
+        KH, KW, Cin2, Cout = b[0].shape
+        if Cin != Cin2:
+            raise ValueError("operand shapes do not match")
+        self.reserve(lib().mpc_conv2d3_workspace_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride))
+        z = out if out is not None else self._empty3(c[0])
+        self._check(lib().mpc_conv2d3(self._h, _share3(x), _share3(w), _share3(a), _share3(b), _share3(c), _share3(z),
+                                      B, H, W, Cin, Cout, KH, KW, pad, stride, _p64(f_public)))
+        return z
+
+    def truncate3(self, z, r, rt, bits=16):
+        """Masked rescale in place with the offline pair (r, r >> bits)."""
+        n = z[0].numel()
+        self.reserve(lib().mpc_truncate3_workspace_bytes(n))
+        self._check(lib().mpc_truncate3(self._h, _share3(z), _share3(r), _share3(rt), n, bits))
+        return z
+
+    def relu3(self, x, mat, want_sign=False, out=None):
+        n = x[0].numel()
+        self.reserve(lib().mpc_relu3_workspace_bytes(n))
+        y = out if out is not None else self._empty3(x[0])
+        m = _material3(mat, n)
+        if want_sign:
+            sb = tuple(torch.empty(n, dtype=torch.uint8, device=self.device) for _ in range(3))
+            sa = tuple(torch.empty(n, dtype=torch.int64, device=self.device) for _ in range(3))
+            sbp = (_P8 * 3)(*[_p8(t) for t in sb]); sap = (_P64 * 3)(*[_p64(t) for t in sa])
+            self._check(lib().mpc_relu3(self._h, _share3(x), byref(m), _share3(y), n, byref(sbp), byref(sap)))
+            return y, sb, sa
+        self._check(lib().mpc_relu3(self._h, _share3(x), byref(m), _share3(y), n, None, None))
+        return y
 
     def truncate(self, z, bits=16):
         self._check(lib().mpc_truncate(self._h, _share(z), z[0].numel(), bits))

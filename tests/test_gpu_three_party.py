@@ -1,0 +1,194 @@
+"""GPU parity of the three-party calls (Alg. 1 / Eq. 3 / Alg. 2 with N = 3) against
+the CPU oracle on the same seeded inputs: every party's output share bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2209_13643_amd import synth
+
+pytestmark = pytest.mark.gpu
+U64 = np.uint64
+TOL = 2.0 ** -12
+
+
+@pytest.fixture(scope="module")
+def mpc():
+    from paper_2209_13643_amd import mpc as m
+    return m
+
+
+@pytest.fixture(params=["three-streams", "single-queue"])
+def lane(mpc, request):
+    ln = mpc.Lane(0)
+    if request.param == "single-queue":
+        ln.use_single_queue()
+    yield ln
+    ln.sync()
+    ln.close()
+
+
+def dev3(mpc, tri):
+    return tuple(mpc.to_device(v) for v in tri)
+
+
+def host3(mpc, lane, tri):
+    lane.sync()
+    return tuple(mpc.to_host(v) for v in tri)
+
+
+def rec3(t):
+    return np.asarray(t[0], dtype=U64) + np.asarray(t[1], dtype=U64) + np.asarray(t[2], dtype=U64)
+
+
+def assert_shares_equal(got, want, what=""):
+    for i in range(3):
+        g = np.asarray(got[i]).reshape(np.shape(want[i]))
+        if not np.array_equal(g, want[i]):
+            bad = np.argwhere(g != want[i])
+            raise AssertionError(f"{what}: party {i} differs at {len(bad)} of {g.size} elements, first {bad[0]}: "
+                                 f"got {int(g[tuple(bad[0])]):#x} want {int(want[i][tuple(bad[0])]):#x}")
+
+
+def deal_matmul3(rng, shape_x, shape_y, x_std, w_std, product):
+    X = synth.normal_fixed(rng, shape_x, x_std); Y = synth.normal_fixed(rng, shape_y, w_std)
+    d = {"X": X, "Y": Y, "x": synth.share_additive3(rng, X), "y": synth.share_additive3(rng, Y)}
+    d["a"], d["b"], d["c"] = synth.deal_product_triple3(rng, shape_x, shape_y, product)
+    return d
+
+
+@pytest.mark.parametrize("n", [1, 3, 1000, 70001])
+def test_open3_and_truncate3(mpc, lane, n):
+    rng = np.random.default_rng(300 + n)
+    Z = synth.normal_fixed(rng, n, 300.0) * U64(1 << 16)            # a product's scale: 32 fractional bits
+    z = synth.share_additive3(rng, Z)
+    got = lane.open3(dev3(mpc, z)); lane.sync()
+    assert np.array_equal(mpc.to_host(got), oracle.open3(z))
+    r, rt = synth.deal_trunc3_pair(rng, n)
+    want = oracle.truncate3(z, r, rt)
+    t = lane.truncate3(dev3(mpc, z), dev3(mpc, r), dev3(mpc, rt))
+    assert_shares_equal(host3(mpc, lane, t), want, "truncate3")
+    err = rec3(want).view(np.int64) - (Z.view(np.int64) >> 16)
+    assert err.min() >= 0 and err.max() <= 1
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (64, 256, 128), (100, 70, 36), (200, 1030, 130), (33, 2000, 257)])
+def test_beaver_matmul3(mpc, lane, shape):
+    M, K, N = shape
+    rng = np.random.default_rng(310 + M)
+    d = deal_matmul3(rng, (M, K), (K, N), 1.0, 0.1, oracle.ring_matmul)
+    want = oracle.beaver_matmul3(d["x"], d["y"], d["a"], d["b"], d["c"])
+    z = lane.beaver_matmul3(*[dev3(mpc, d[k]) for k in "xyabc"])
+    assert_shares_equal(host3(mpc, lane, z), want, f"beaver_matmul3 {shape}")
+    # rescale and compare with float64 on the decoded inputs
+    r, rt = synth.deal_trunc3_pair(rng, (M, N))
+    t = lane.truncate3(z, dev3(mpc, r), dev3(mpc, rt))
+    got = host3(mpc, lane, t)
+    assert_shares_equal(got, oracle.truncate3(want, r, rt), "truncate3 after matmul3")
+    ref = oracle.decode(d["X"]) @ oracle.decode(d["Y"])
+    assert np.abs(oracle.decode(rec3(got)) - ref).max() <= TOL
+
+
+def test_beaver_matmul3_batched_transposed_and_preopened(mpc, lane):
+    """Batch items, operands read from transposed storage, and the weight mask opened ahead of time (Alg. 3)."""
+    rng = np.random.default_rng(320)
+    Bn, M, K, N = 3, 50, 90, 40
+    d = deal_matmul3(rng, (Bn, M, K), (Bn, K, N), 1.0, 0.1, lambda A, B: np.stack([oracle.ring_matmul(p, q) for p, q in zip(A, B)]))
+    want = tuple(np.stack(v) for v in zip(*[oracle.beaver_matmul3(*[[q[i] for q in d[k]] for k in "xyabc"]) for i in range(Bn)]))
+    z = lane.beaver_matmul3(*[dev3(mpc, d[k]) for k in "xyabc"])
+    assert_shares_equal(host3(mpc, lane, z), want, "batched")
+    # transposed storage of both operands
+    tr = lambda tri: tuple(np.ascontiguousarray(np.swapaxes(v, -1, -2)) for v in tri)
+    z = lane.beaver_matmul3(dev3(mpc, tr(d["x"])), dev3(mpc, tr(d["y"])), dev3(mpc, tr(d["a"])), dev3(mpc, tr(d["b"])),
+                            dev3(mpc, d["c"]), flags=mpc.MPC_TRANS_X | mpc.MPC_TRANS_Y)
+    assert_shares_equal(host3(mpc, lane, z), want, "transposed")
+    # f = y - b opened ahead of time
+    f = oracle.open3(tuple(d["y"][i] - d["b"][i] for i in range(3)))
+    z = lane.beaver_matmul3(dev3(mpc, d["x"]), None, dev3(mpc, d["a"]), dev3(mpc, d["b"]), dev3(mpc, d["c"]),
+                            f_public=mpc.to_device(f))
+    assert_shares_equal(host3(mpc, lane, z), want, "pre-opened f")
+
+
+@pytest.mark.parametrize("case", [(2, 8, 8, 3, 16, 3, 3, 1, 1), (1, 9, 7, 20, 70, 3, 3, 1, 2), (3, 6, 6, 33, 40, 1, 1, 0, 1),
+                                  (2, 12, 12, 16, 130, 5, 5, 2, 1)])
+def test_conv2d3(mpc, lane, case):
+    B, H, W, Cin, Cout, KH, KW, pad, stride = case
+    rng = np.random.default_rng(330 + Cin)
+    conv = lambda A, Bm: oracle.ring_conv2d(A, Bm, pad, stride)
+    d = deal_matmul3(rng, (B, H, W, Cin), (KH, KW, Cin, Cout), 1.0, synth.he_std(KH * KW * Cin), conv)
+    want = oracle.beaver_conv2d3(d["x"], d["y"], d["a"], d["b"], d["c"], pad, stride)
+    z = lane.conv2d3(*[dev3(mpc, d[k]) for k in "xyabc"], pad, stride)
+    assert_shares_equal(host3(mpc, lane, z), want, f"conv2d3 {case}")
+    assert np.array_equal(rec3(want), conv(d["X"], d["Y"]))
+
+
+def test_small_output_long_contraction_is_split(mpc, lane):
+    """Few output tiles and a long contraction: the split-contraction path, both GEMM launches."""
+    rng = np.random.default_rng(340)
+    d = deal_matmul3(rng, (32, 4608), (4608, 64), 1.0, 0.02, oracle.ring_matmul)
+    want = oracle.beaver_matmul3(d["x"], d["y"], d["a"], d["b"], d["c"])
+    z = lane.beaver_matmul3(*[dev3(mpc, d[k]) for k in "xyabc"])
+    assert_shares_equal(host3(mpc, lane, z), want, "split-K")
+
+
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 1000, 4097, 100003])
+def test_relu3(mpc, lane, n):
+    rng = np.random.default_rng(350 + n)
+    X = synth.normal_fixed(rng, n, 4.0)
+    x = synth.share_additive3(rng, X)
+    mat = synth.deal_relu3_material(rng, n)
+    want = oracle.relu3(x, mat)
+    y, sb, sa = lane.relu3(dev3(mpc, x), mpc.material_to_device(mat), want_sign=True)
+    assert_shares_equal(host3(mpc, lane, y), want.y, "relu3 y")
+    assert_shares_equal(host3(mpc, lane, sb), want.s_bit, "relu3 s_bit")
+    assert_shares_equal(host3(mpc, lane, sa), want.s_arith, "relu3 s_arith")
+    assert np.array_equal(rec3(host3(mpc, lane, y)).view(np.int64), np.maximum(X.view(np.int64), 0))
+
+
+def test_relu3_uniform_words_and_carry_patterns(mpc, lane):
+    """Uniform 64-bit values and inputs whose sum ripples a carry through every level."""
+    rng = np.random.default_rng(360)
+    X = np.concatenate([synth.rand_words(rng, 5000),
+                        np.array([0, 1, (1 << 63) - 1, 1 << 63, (1 << 64) - 1, (1 << 62), (1 << 63) + 1], dtype=U64)])
+    n = X.size
+    mat = synth.deal_relu3_material(rng, n)
+    for shares in (synth.share_additive3(rng, X),
+                   (np.full(n, (1 << 64) - 1, dtype=U64), np.ones(n, dtype=U64), X),       # shares that sum with a full ripple
+                   (np.full(n, 1 << 63, dtype=U64), np.full(n, 1 << 63, dtype=U64), X)):
+        want = oracle.relu3(shares, mat)
+        y = lane.relu3(dev3(mpc, shares), mpc.material_to_device(mat))
+        got = host3(mpc, lane, y)
+        assert_shares_equal(got, want.y, "relu3")
+        assert np.array_equal(rec3(got).view(np.int64), np.maximum(X.view(np.int64), 0))
+
+
+def test_secure_layer_three_parties(mpc, lane):
+    """configs[0]'s layer with three parties: matmul, rescale, ReLU; decoded result against float64."""
+    wl = synth.config_tiny(); g = wl.layers[0]
+    rng = synth.rng_for(wl.index, 3)
+    d = deal_matmul3(rng, (g.M, g.K), (g.K, g.N), g.x_std, g.w_std, oracle.ring_matmul)
+    r, rt = synth.deal_trunc3_pair(rng, (g.M, g.N))
+    mat = synth.deal_relu3_material(rng, g.M * g.N)
+    want_t = oracle.truncate3(oracle.beaver_matmul3(d["x"], d["y"], d["a"], d["b"], d["c"]), r, rt)
+    want_y = oracle.relu3(want_t, mat).y
+    z = lane.beaver_matmul3(*[dev3(mpc, d[k]) for k in "xyabc"])
+    t = lane.truncate3(z, dev3(mpc, r), dev3(mpc, rt))
+    y = lane.relu3(t, mpc.material_to_device(mat))
+    got = host3(mpc, lane, y)
+    assert_shares_equal(got, want_y, "secure layer, three parties")
+    ref = np.maximum(oracle.decode(d["X"]) @ oracle.decode(d["Y"]), 0.0)
+    assert np.abs(oracle.decode(rec3(got)).reshape(ref.shape) - ref).max() <= TOL
+
+
+def test_three_party_argument_errors(mpc, lane):
+    rng = np.random.default_rng(370)
+    d = deal_matmul3(rng, (8, 8), (8, 8), 1.0, 0.1, oracle.ring_matmul)
+    args = [dev3(mpc, d[k]) for k in "xyabc"]
+    with pytest.raises(mpc.MpcError):
+        lane.beaver_matmul3(*args, flags=mpc.MPC_TRUNCATE)         # the rescale is a call of its own
+    with pytest.raises(mpc.MpcError):
+        lane.beaver_matmul3(args[0], None, *args[2:])              # no y and no pre-opened f
+    z = lane.beaver_matmul3(*args)
+    r, rt = synth.deal_trunc3_pair(rng, (8, 8))
+    with pytest.raises(mpc.MpcError):
+        lane.truncate3(z, dev3(mpc, r), dev3(mpc, rt), bits=63)
+    lane.sync()
