@@ -404,10 +404,73 @@ def sweep_tiles(n: int = 2097152, reps: int = 10):
     lane.close()
 
 
+def bench_three_parties(reps: int = 20):
+    """configs[1] with three simulated parties: Beaver conv, masked rescale, secure ReLU.
+
+    Algorithmic bytes of the three-party ReLU per element, all parties, by the rules of the two-party
+    accounting (W = 8 B): compulsory I/O + material 3 * (x, y, r0, r1, 39 triple words, ra, ma, mb, mc) =
+    141 W + 3 B; openings: 28 words per party broadcast (written once, then per peer copied = read + write,
+    and read: 7 traversals) and 2 A2B masks per party to one peer each (3 traversals) = 3 * 202 = 606 W + 21 B;
+    carried state per party S, W, P written and read (6), G (12), own masked words read again (28), a and b
+    of every triple read again (26), x again (1) = 3 * 73 = 219 W + 9 B  =>  966 W + 33 B = 7761 B."""
+    wl = synth.CONFIGS[1](); L = wl.layers[0]
+    lane = mpc.Lane(0); lane.use_single_queue()
+    dev = lane.device
+    g = dealer.gen(synth.BASE_SEED + 31, dev)
+    d = dealer.conv_layer3(lane, g, L.B, L.H, L.W, L.Cin, L.Cout, L.KH, L.KW, L.pad, L.stride, L.x_std, L.w_std)
+    M, K, N = L.gemm_mkn
+    n = M * N
+    mat = dealer.relu3_material(g, n, dev)
+    z = tuple(torch.empty_like(d["c"][0]) for _ in range(3))
+    y = tuple(torch.empty_like(d["c"][0]) for _ in range(3))
+
+    def conv():
+        return lane.conv2d3(d["x"], d["w"], d["a"], d["b"], d["c"], L.pad, L.stride, out=z)
+
+    def timed(fn, which):
+        for _ in range(5):
+            fn()
+        lane.sync(); lane.set_profiling(True); lane.profile_reset()
+        for _ in range(reps):
+            fn()
+        lane.sync()
+        s = sorted(lane.profile_samples(which)); k = sorted(lane.profile_samples(mpc.PROF_GEMM_KERNEL))
+        lane.set_profiling(False)
+        return s[len(s) // 2], s[0], (sum(k) / reps if k else 0.0)
+
+    conv_med, conv_min, gemm_ms = timed(conv, mpc.PROF_LINEAR)
+    relu_med, relu_min, _ = timed(lambda: lane.relu3(z, mat, out=y), mpc.PROF_RELU)
+    # the rescale has no region of its own: wall clock around back-to-back calls
+    t = tuple(v.clone() for v in z)
+    for _ in range(5):
+        lane.truncate3(t, d["r"], d["rt"])
+    lane.sync(); t0 = time.perf_counter()
+    for _ in range(reps):
+        lane.truncate3(t, d["r"], d["rt"])
+    lane.sync(); trunc_ms = (time.perf_counter() - t0) / reps * 1e3
+    lane.close()
+    macs = M * K * N
+    relu_bytes = 966 * 8 + 33
+    return dict(gemm=f"{M}x{K}x{N}", conv_ms=conv_med, conv_min_ms=conv_min, gemm_kernels_ms=gemm_ms,
+                secure_macs_per_s=macs / conv_med * 1e3, mfma_frac=432 * macs / (gemm_ms * 1e-3) / 5.0e15,
+                trunc_ms=trunc_ms, relu_n=n, relu_ms=relu_med, relu_min_ms=relu_min,
+                relu_elems_per_s=n / relu_med * 1e3, relu_bytes_per_element=relu_bytes,
+                relu_hbm_frac=relu_bytes * n / (relu_med * 1e-3) / 8.0e12)
+
+
 def main(argv):
     if argv and argv[0] == "sweep":
         print("== tile-count sweep, secure ReLU on 2097152 elements")
         sweep_tiles()
+        return
+    if argv and argv[0] == "parties3":
+        r = bench_three_parties()
+        print("== configs[1] with three simulated parties (432 int8 ops per secure MAC: 3 parties x 2 ring products x 36 x 2)")
+        print(f"  conv3x3 {r['gemm']}: call {r['conv_ms']:.3f} ms (min {r['conv_min_ms']:.3f}), {r['secure_macs_per_s'] / 1e12:.2f} T secure MAC/s; "
+              f"GEMM launches {r['gemm_kernels_ms']:.3f} ms = {100 * r['mfma_frac']:.1f}% of 5.0 POP/s")
+        print(f"  masked rescale of {r['relu_n']} words: {r['trunc_ms']:.3f} ms (host clock around back-to-back calls)")
+        print(f"  secure ReLU, {r['relu_n']} elements: {r['relu_ms']:.3f} ms (min {r['relu_min_ms']:.3f}), {r['relu_elems_per_s'] / 1e9:.2f} G elems/s; "
+              f"{r['relu_bytes_per_element']} B per element -> {100 * r['relu_hbm_frac']:.1f}% of 8 TB/s", flush=True)
         return
     if argv and argv[0] == "backward":
         for idx in ([int(a) for a in argv[1:]] or [1, 2, 3]):

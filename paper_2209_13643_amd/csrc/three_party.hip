@@ -59,7 +59,7 @@ struct Relu3Party {
     u64* y; u8* s_bit; u64* s_arith;     // outputs (the last two optional)
     // workspace
     u64* wrecv[2];                       // this party's shares of the words of party+1 / party+2
-    u64 *S, *Wd, *P, *G; u8* p63;        // carried state
+    u64 *S, *Wd, *P, *G; u8* p63;        // carried state (from level 0 on, P lives in the opened AND of each round)
     u64* send;                           // [4][n] masked words of the current round
     u64* recv[2];                        // [4][n] the same from party+1 / party+2
     u8* vsend; u8* vrecv[2];             // B2A round (one byte per element)
@@ -129,8 +129,7 @@ __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
             constexpr int d = 2 << L;                    // shift of level L + 1
             constexpr int ng = tg + 2, np = tp + 2;
             p.send[i] = P ^ p.ta[ng * n + i];  p.send[n + i] = (G << d) ^ p.tb[ng * n + i];
-            if constexpr (L + 1 < 5) {
-                p.P[i] = P;                              // the last level's P update is not needed
+            if constexpr (L + 1 < 5) {                   // the last level needs no P update
                 p.send[2 * n + i] = P ^ p.ta[np * n + i];  p.send[3 * n + i] = (P << d) ^ p.tb[np * n + i];
             }
         } else if constexpr (STAGE == 8) {

@@ -147,5 +147,47 @@ def relu_material(g, n: int, device, packed: bool = False) -> dict:
     return m
 
 
+# ---------------------------------------------------------------- three parties
+def share3(g, value):
+    s0 = rand_words(g, value.shape, value.device); s1 = rand_words(g, value.shape, value.device)
+    return s0, s1, value - s0 - s1
+
+
+def share_xor3(g, value):
+    s0 = rand_words(g, value.shape, value.device); s1 = rand_words(g, value.shape, value.device)
+    return s0, s1, value ^ s0 ^ s1
+
+
+def conv_layer3(lane: "mpc.Lane", g, B, H, W, Cin, Cout, KH, KW, pad, stride, x_std, w_std):
+    """A convolution layer's inputs, triple and rescale pair for three parties."""
+    dev = lane.device
+    X = normal_fixed(g, (B, H, W, Cin), x_std, dev)
+    Wt = normal_fixed(g, (KH, KW, Cin, Cout), w_std, dev)
+    A = rand_words(g, X.shape, dev); Bm = rand_words(g, Wt.shape, dev)
+    lane.wait_torch()
+    C = lane.ring_conv2d(A, Bm, pad, stride)
+    lane.sync()
+    d = dict(X=X, W=Wt, x=share3(g, X), w=share3(g, Wt), a=share3(g, A), b=share3(g, Bm), c=share3(g, C))
+    r = rand_words(g, C.shape, dev) & ((1 << 63) - 1)          # uniform in [0, 2^63)
+    d["r"], d["rt"] = share3(g, r), share3(g, r >> FRAC_BITS)
+    torch.cuda.synchronize(dev)
+    return d
+
+
+def relu3_material(g, n: int, device) -> dict:
+    """Three-party secure-ReLU material for n elements (13 AND triples, two A2B masks per party)."""
+    w = lambda shape: rand_words(g, shape, device)
+    m = {"r0": tuple(w((n,)) for _ in range(3)), "r1": tuple(w((n,)) for _ in range(3))}
+    A, Bm = w((mpc.N_AND_TRIPLES3, n)), w((mpc.N_AND_TRIPLES3, n))
+    m["and_a"], m["and_b"], m["and_c"] = share_xor3(g, A), share_xor3(g, Bm), share_xor3(g, A & Bm)
+    bits = [torch.randint(0, 2, (n,), generator=g, device=device, dtype=torch.uint8) for _ in range(3)]
+    m["rb"] = tuple(bits)
+    m["ra"] = share3(g, (bits[0] ^ bits[1] ^ bits[2]).to(torch.int64))
+    MA, MB = w((n,)), w((n,))
+    m["ma"], m["mb"], m["mc"] = share3(g, MA), share3(g, MB), share3(g, MA * MB)
+    torch.cuda.synchronize(device)
+    return m
+
+
 def he_std(fan_in: int) -> float:
     return math.sqrt(2.0 / fan_in)

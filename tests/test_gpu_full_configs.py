@@ -269,3 +269,53 @@ def test_config4_vgg16_pipeline_full(mods, packed_relu):
             x = p
     for ln in lanes:
         ln.close()
+
+
+def test_config1_with_three_parties(mods, lane):
+    """configs[1] at full size with three simulated parties: the convolution's three output shares
+    against the oracle word for word (inputs and triple dealt on the host), then the masked rescale
+    and the secure ReLU on device-dealt material: a sampled oracle recomputation plus the
+    properties that hold for every element."""
+    mpc, dealer, _ = mods
+    wl = synth.config_vgg_block(); L = wl.layers[0]
+    rng = synth.rng_for(wl.index, 33)
+    conv = lambda A, Bm: oracle.ring_conv2d(A, Bm, L.pad, L.stride)
+    X = synth.normal_fixed(rng, (L.B, L.H, L.W, L.Cin), L.x_std)
+    Wt = synth.normal_fixed(rng, (L.KH, L.KW, L.Cin, L.Cout), L.w_std)
+    x, w = synth.share_additive3(rng, X), synth.share_additive3(rng, Wt)
+    a, b, c = synth.deal_product_triple3(rng, X.shape, Wt.shape, conv)
+    want = oracle.beaver_conv2d3(x, w, a, b, c, L.pad, L.stride)
+    d3 = lambda tri: tuple(mpc.to_device(v) for v in tri)
+    z = lane.conv2d3(d3(x), d3(w), d3(a), d3(b), d3(c), L.pad, L.stride)
+    lane.sync()
+    for i in range(3):
+        assert np.array_equal(mpc.to_host(z[i]), want[i]), f"conv2d3 party {i}"
+    # rescale
+    n = z[0].numel()
+    r, rt = synth.deal_trunc3_pair(rng, want[0].shape)
+    want_t = oracle.truncate3(want, r, rt)
+    t = lane.truncate3(z, d3(r), d3(rt)); lane.sync()
+    for i in range(3):
+        assert np.array_equal(mpc.to_host(t[i]), want_t[i]), f"truncate3 party {i}"
+    ref = torch.nn.functional.conv2d(torch.from_numpy(oracle.decode(X)).permute(0, 3, 1, 2),
+                                     torch.from_numpy(oracle.decode(Wt)).permute(3, 2, 0, 1), padding=L.pad, stride=L.stride)
+    got = oracle.decode(want_t[0] + want_t[1] + want_t[2])
+    assert np.abs(got - ref.permute(0, 2, 3, 1).numpy()).max() <= TOL
+    # secure ReLU, material drawn on the device
+    g = dealer.gen(4242, lane.device)
+    mat = dealer.relu3_material(g, n, lane.device)
+    y, sb, sa = lane.relu3(t, mat, want_sign=True); lane.sync()
+    rz = (t[0] + t[1] + t[2]).view(-1); ry = (y[0] + y[1] + y[2]).view(-1)
+    assert torch.equal(ry, torch.clamp(rz, min=0)), "rec(y) != max(rec(x), 0)"
+    assert torch.equal((sb[0] ^ sb[1] ^ sb[2]).view(-1).bool(), rz < 0)
+    assert torch.equal((sa[0] + sa[1] + sa[2]).view(-1), (rz < 0).to(torch.int64))
+    idx = torch.randperm(n, device=lane.device, generator=g)[:100_000].sort().values
+    take = lambda q: mpc.to_host(q.view(-1)[idx])
+    take13 = lambda q: mpc.to_host(q.view(13, n)[:, idx])
+    sub = {k: tuple(take(q) for q in mat[k]) for k in ("r0", "r1", "rb", "ra", "ma", "mb", "mc")}
+    for k in ("and_a", "and_b", "and_c"):
+        sub[k] = tuple(take13(q) for q in mat[k])
+    res = oracle.relu3(tuple(take(q) for q in t), sub)
+    for i in range(3):
+        assert np.array_equal(take(y[i]), res.y[i]), f"relu3 sample, party {i}"
+        assert np.array_equal(take(sa[i]), res.s_arith[i]), f"relu3 sign share sample, party {i}"
