@@ -108,3 +108,24 @@ def test_gradient_and_elementwise_workspace_queries(lib):
     assert lib.mpc_mul_workspace_bytes(1000) >= 8 * 1000 * 8
     assert lib.mpc_maxpool_backward_workspace_bytes(1, 4, 4, 2) > lib.mpc_mul_workspace_bytes(16)
     assert lib.mpc_maxpool_backward_workspace_bytes(1, 4, 5, 2) == 0
+
+
+def test_three_party_workspace_queries(lib):
+    M, K, N = 96, 100, 40
+    assert lib.mpc_matmul3_workspace_bytes(M, K, N, 1) > lib.mpc_matmul_workspace_bytes(M, K, N, 1)
+    assert lib.mpc_matmul3_workspace_bytes(0, K, N, 1) == 0
+    assert lib.mpc_conv2d3_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 1) > lib.mpc_conv2d_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 1)
+    assert lib.mpc_conv2d3_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 0) == 0
+    up = lambda v: (v + 255) // 256 * 256
+    assert lib.mpc_truncate3_workspace_bytes(1000) == 4 * up(8000) and lib.mpc_truncate3_workspace_bytes(0) == 0
+    # per party: 18 word arrays (two received A2B words, S, W, P, G, 4 sent and 2 x 4 received words) and 4 byte arrays
+    n = 1000
+    assert lib.mpc_relu3_workspace_bytes(n) == 3 * (6 * up(8 * n) + 3 * up(32 * n) + 4 * up(n))
+    assert lib.mpc_relu3_workspace_bytes(0) == 0
+    # null arguments are rejected before any device work
+    assert lib.mpc_open3(None, mpc_null3(), None, 4) == -1
+
+
+def mpc_null3():
+    from paper_2209_13643_amd import mpc
+    return mpc.CShare3()
