@@ -481,6 +481,14 @@ size_t mpc_relu3_workspace_bytes(size_t n);
 int mpc_relu3(mpc_ctx* ctx, mpc_cshare3 x, const mpc_relu3_material* mat, mpc_share3 y,
               size_t n, uint8_t* const s_bit[3], uint64_t* const s_arith[3]);
 
+/* 2x2 / stride-2 max-pool with three parties by max(p, q) = q + ReLU(p - q),
+ * as mpc_maxpool2x2: mat1 holds material for 2*n_out elements (pairs
+ * interleaved), mat2 for n_out = B*(H/2)*(W/2)*C.  H, W even. */
+size_t mpc_maxpool3_workspace_bytes(int B, int H, int W, int C);
+int mpc_maxpool3(mpc_ctx* ctx, mpc_cshare3 x, const mpc_relu3_material* mat1,
+                 const mpc_relu3_material* mat2, mpc_share3 y,
+                 int B, int H, int W, int C);
+
 /* -------------------------------------------------- dealer helper (offline) */
 
 /* Plain ring product Z = L*R mod 2^64 on public device arrays, computed with

@@ -462,6 +462,17 @@ def relu3(x, mat) -> ReluResult:
                       tuple(v.reshape(shp) for v in sa))
 
 
+def maxpool2x2_3(x, mat1, mat2):
+    """Three-party 2x2 max-pool by max(p,q) = q + ReLU(p-q): the local gathers of
+    maxpool2x2 on every party's share, the two conversions by relu3."""
+    B, H, W, C = np.shape(x[0])
+    r1 = relu3(tuple(pool_level1(x[p]) for p in range(3)), mat1).y
+    lv2 = [pool_level2(x[p], r1[p]) for p in range(3)]
+    r2 = relu3(tuple(q[1] for q in lv2), mat2).y
+    shp = (B, H // 2, W // 2, C)
+    return tuple((lv2[p][0] + r2[p]).reshape(shp) for p in range(3))
+
+
 # --------------------------------------------- checkers on reconstructed values
 def to_signed(u):
     return np.asarray(u, dtype=U64).view(np.int64)

@@ -191,6 +191,104 @@ size_t relu3_ws(u8* base, size_t cap, size_t n, Relu3Args* q, bool* ok)
     return w.off;
 }
 
+int check_material3(const mpc_relu3_material* m)
+{
+    if (!m) return MPC_EINVAL;
+    for (int i = 0; i < 3; ++i)
+        if (!m->r0.p[i] || !m->r1.p[i] || !m->and_a.p[i] || !m->and_b.p[i] || !m->and_c.p[i] || !m->rb[i] ||
+            !m->ra.p[i] || !m->ma.p[i] || !m->mb.p[i] || !m->mc.p[i])
+            return MPC_EINVAL;
+    return MPC_OK;
+}
+
+void fill3(Relu3Args& q, const u64* const x[3], const mpc_relu3_material* m, u64* const y[3],
+           uint8_t* const s_bit[3], uint64_t* const s_arith[3], size_t n)
+{
+    for (int i = 0; i < 3; ++i) {
+        Relu3Party& p = q.p[i];
+        p.x = x[i]; p.r0 = m->r0.p[i]; p.r1 = m->r1.p[i];
+        p.ta = m->and_a.p[i]; p.tb = m->and_b.p[i]; p.tc = m->and_c.p[i];
+        p.rb = m->rb[i]; p.ra = m->ra.p[i]; p.ma = m->ma.p[i]; p.mb = m->mb.p[i]; p.mc = m->mc.p[i];
+        p.y = y[i];
+        p.s_bit = s_bit ? s_bit[i] : nullptr; p.s_arith = s_arith ? s_arith[i] : nullptr;
+    }
+    q.n = n;
+}
+
+// The whole chain on one stream: A2B distribution, 11 stage kernels, 10 word exchanges, one byte exchange.
+int relu3_run(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
+{
+    const size_t n = q.n;
+    // Alg. 2: party j sends the mask r1_j to party j+2 and r0_j to party j+1, i.e. party i
+    // receives its share of word i+1 (that party's r1) and of word i+2 (that party's r0)
+    {
+        CopySeg cp[6];
+        for (int i = 0; i < 3; ++i) {
+            cp[2 * i] = CopySeg{ (const u8*)q.p[(i + 1) % 3].r1, (u8*)q.p[i].wrecv[0], n * sizeof(u64), 0 };
+            cp[2 * i + 1] = CopySeg{ (const u8*)q.p[(i + 2) % 3].r0, (u8*)q.p[i].wrecv[1], n * sizeof(u64), 0 };
+        }
+        MPC_TRY(launch_copy_multi(c, st, cp, 6));
+    }
+    MPC_TRY(launch_stage<0>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 2));
+    MPC_TRY(launch_stage<1>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 2));
+    MPC_TRY(launch_stage<2>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
+    MPC_TRY(launch_stage<3>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
+    MPC_TRY(launch_stage<4>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
+    MPC_TRY(launch_stage<5>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
+    MPC_TRY(launch_stage<6>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
+    MPC_TRY(launch_stage<7>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 2));
+    MPC_TRY(launch_stage<8>(c, st, q));
+    {
+        CopySeg cp[6]; int k = 0;
+        for (int i = 0; i < 3; ++i)
+            for (int s = 0; s < 2; ++s)
+                cp[k++] = CopySeg{ q.p[(i + 1 + s) % 3].vsend, q.p[i].vrecv[s], n, 0 };
+        MPC_TRY(launch_copy_multi(c, st, cp, 6));
+    }
+    MPC_TRY(launch_stage<9>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 2));
+    MPC_TRY(launch_stage<10>(c, st, q));
+    return MPC_OK;
+}
+
+// ---- 2x2 max-pool by max(p, q) = q + ReLU(p - q): the local steps (blockIdx.y = party)
+struct Pool3Args { const u64* x[3]; u64* d1[3]; const u64* r1[3]; u64* v[3]; u64* d2[3]; u64* y[3]; int B, H, W, C; };
+
+// STEP 0: d1[2o] = p00 - p01, d1[2o+1] = p10 - p11;  1: u = p01 + r1[2o], v = p11 + r1[2o+1], d2 = u - v;  2: y += v
+template <int STEP>
+__global__ __launch_bounds__(kT) void k3_pool(Pool3Args q)
+{
+    const int p = blockIdx.y;
+    const int Ho = q.H / 2, Wo = q.W / 2;
+    const size_t n_out = (size_t)q.B * Ho * Wo * q.C;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < n_out; o += stride) {
+        if constexpr (STEP == 2) { q.y[p][o] += q.v[p][o]; continue; }
+        const int ch = (int)(o % q.C); size_t t = o / q.C;
+        const int wo = (int)(t % Wo); t /= Wo;
+        const int ho = (int)(t % Ho); const int b = (int)(t / Ho);
+        const size_t base = (((size_t)b * q.H + 2 * ho) * q.W + 2 * wo) * q.C + ch;
+        const size_t dw = q.C, dh = (size_t)q.W * q.C;
+        const u64* x = q.x[p];
+        if constexpr (STEP == 0) {
+            q.d1[p][2 * o] = x[base] - x[base + dw];
+            q.d1[p][2 * o + 1] = x[base + dh] - x[base + dh + dw];
+        } else {
+            const u64 u = x[base + dw] + q.r1[p][2 * o];
+            const u64 v = x[base + dh + dw] + q.r1[p][2 * o + 1];
+            q.v[p][o] = v;
+            q.d2[p][o] = u - v;
+        }
+    }
+}
+
+template <int STEP>
+int launch_pool(mpc_ctx* c, hipStream_t st, const Pool3Args& q, size_t n_out)
+{
+    hipLaunchKernelGGL(k3_pool<STEP>, dim3(grid3(n_out), 3), dim3(kT), 0, st, q);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -249,59 +347,63 @@ size_t mpc_relu3_workspace_bytes(size_t n)
 int mpc_relu3(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* m, mpc_share3 y, size_t n,
               uint8_t* const s_bit[3], uint64_t* const s_arith[3])
 {
-    if (!c || !m || n == 0) return MPC_EINVAL;
+    if (!c || n == 0) return MPC_EINVAL;
     if (n > ((size_t)1 << 40)) return MPC_ERANGE;
+    MPC_TRY(check_material3(m));
+    for (int i = 0; i < 3; ++i) if (!x.p[i] || !y.p[i]) return MPC_EINVAL;
     Relu3Args q{};
-    for (int i = 0; i < 3; ++i) {
-        if (!x.p[i] || !y.p[i] || !m->r0.p[i] || !m->r1.p[i] || !m->and_a.p[i] || !m->and_b.p[i] ||
-            !m->and_c.p[i] || !m->rb[i] || !m->ra.p[i] || !m->ma.p[i] || !m->mb.p[i] || !m->mc.p[i])
-            return MPC_EINVAL;
-    }
     bool ok = false;
     relu3_ws(c->ws, c->ws_bytes, n, &q, &ok);
     if (!ok) return MPC_ENOMEM;
-    for (int i = 0; i < 3; ++i) {
-        Relu3Party& p = q.p[i];
-        p.x = x.p[i]; p.r0 = m->r0.p[i]; p.r1 = m->r1.p[i];
-        p.ta = m->and_a.p[i]; p.tb = m->and_b.p[i]; p.tc = m->and_c.p[i];
-        p.rb = m->rb[i]; p.ra = m->ra.p[i]; p.ma = m->ma.p[i]; p.mb = m->mb.p[i]; p.mc = m->mc.p[i];
-        p.y = y.p[i];
-        p.s_bit = s_bit ? s_bit[i] : nullptr; p.s_arith = s_arith ? s_arith[i] : nullptr;
-    }
-    q.n = n;
+    fill3(q, x.p, m, y.p, s_bit, s_arith, n);
     hipStream_t st = c->s[0];
     MPC_TRY(lane_join(c));
     const int pi = prof_begin(c, MPC_PROF_RELU, st);
-
-    // Alg. 2: party j sends the mask r1_j to party j+2 and r0_j to party j+1, i.e. party i
-    // receives its share of word i+1 (that party's r1) and of word i+2 (that party's r0)
-    {
-        CopySeg cp[6];
-        for (int i = 0; i < 3; ++i) {
-            cp[2 * i] = CopySeg{ (const u8*)q.p[(i + 1) % 3].r1, (u8*)q.p[i].wrecv[0], n * sizeof(u64), 0 };
-            cp[2 * i + 1] = CopySeg{ (const u8*)q.p[(i + 2) % 3].r0, (u8*)q.p[i].wrecv[1], n * sizeof(u64), 0 };
-        }
-        MPC_TRY(launch_copy_multi(c, st, cp, 6));
-    }
-    MPC_TRY(launch_stage<0>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<1>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<2>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<3>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<4>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<5>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<6>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<7>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<8>(c, st, q));
-    {
-        CopySeg cp[6]; int k = 0;
-        for (int i = 0; i < 3; ++i)
-            for (int s = 0; s < 2; ++s)
-                cp[k++] = CopySeg{ q.p[(i + 1 + s) % 3].vsend, q.p[i].vrecv[s], n, 0 };
-        MPC_TRY(launch_copy_multi(c, st, cp, 6));
-    }
-    MPC_TRY(launch_stage<9>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<10>(c, st, q));
+    MPC_TRY(relu3_run(c, st, q));
     prof_end(c, MPC_PROF_RELU, pi, st);
+    return lane_fanout(c);
+}
+
+size_t mpc_maxpool3_workspace_bytes(int B, int H, int W, int C)
+{
+    if (B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1)) return 0;
+    const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
+    // per party: d1 (2 n_out), r1 (2 n_out), v (n_out), d2 (n_out); then the larger conversion's scratch
+    return 3 * (2 * align_up(2 * n_out * 8) + 2 * align_up(n_out * 8)) + mpc_relu3_workspace_bytes(2 * n_out);
+}
+
+int mpc_maxpool3(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* mat1, const mpc_relu3_material* mat2,
+                 mpc_share3 y, int B, int H, int W, int C)
+{
+    if (!c || B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1)) return MPC_EINVAL;
+    MPC_TRY(check_material3(mat1));
+    MPC_TRY(check_material3(mat2));
+    for (int i = 0; i < 3; ++i) if (!x.p[i] || !y.p[i]) return MPC_EINVAL;
+    const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
+    WsAlloc wa(c->ws, c->ws_bytes);
+    Pool3Args pq{};
+    u64* r1[3];
+    for (int i = 0; i < 3; ++i) {
+        pq.x[i] = x.p[i]; pq.y[i] = y.p[i];
+        pq.d1[i] = wa.take<u64>(2 * n_out); r1[i] = wa.take<u64>(2 * n_out); pq.r1[i] = r1[i];
+        pq.v[i] = wa.take<u64>(n_out); pq.d2[i] = wa.take<u64>(n_out);
+    }
+    pq.B = B; pq.H = H; pq.W = W; pq.C = C;
+    if (!wa.ok) return MPC_ENOMEM;
+    Relu3Args q1{}, q2{};
+    bool ok1 = false, ok2 = false;
+    relu3_ws(c->ws + wa.off, c->ws_bytes - wa.off, 2 * n_out, &q1, &ok1);
+    relu3_ws(c->ws + wa.off, c->ws_bytes - wa.off, n_out, &q2, &ok2);      // the second conversion reuses the scratch
+    if (!ok1 || !ok2) return MPC_ENOMEM;
+    fill3(q1, pq.d1, mat1, r1, nullptr, nullptr, 2 * n_out);
+    fill3(q2, pq.d2, mat2, y.p, nullptr, nullptr, n_out);
+    hipStream_t st = c->s[0];
+    MPC_TRY(lane_join(c));
+    MPC_TRY(launch_pool<0>(c, st, pq, n_out));       // first tournament level: max(p00, p01), max(p10, p11)
+    MPC_TRY(relu3_run(c, st, q1));
+    MPC_TRY(launch_pool<1>(c, st, pq, n_out));       // second level: the two winners
+    MPC_TRY(relu3_run(c, st, q2));
+    MPC_TRY(launch_pool<2>(c, st, pq, n_out));       // out = v + ReLU(u - v)
     return lane_fanout(c);
 }
 

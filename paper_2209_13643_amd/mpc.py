@@ -66,6 +66,7 @@ EXPORTS = [
     "mpc_ctx_capture_begin", "mpc_ctx_capture_end", "mpc_graph_launch", "mpc_graph_destroy",
     "mpc_open3", "mpc_matmul3_workspace_bytes", "mpc_beaver_matmul3", "mpc_conv2d3_workspace_bytes", "mpc_conv2d3",
     "mpc_truncate3_workspace_bytes", "mpc_truncate3", "mpc_relu3_workspace_bytes", "mpc_relu3",
+    "mpc_maxpool3_workspace_bytes", "mpc_maxpool3",
 ]
 
 _lib = None
@@ -150,6 +151,8 @@ def lib():
     L.mpc_relu3_workspace_bytes.argtypes = [c_size_t]; L.mpc_relu3_workspace_bytes.restype = c_size_t
     L.mpc_relu3.argtypes = [c_void_p, CShare3, POINTER(Relu3Material), CShare3, c_size_t,
                             POINTER(_P8 * 3), POINTER(_P64 * 3)]
+    L.mpc_maxpool3_workspace_bytes.argtypes = [c_int] * 4; L.mpc_maxpool3_workspace_bytes.restype = c_size_t
+    L.mpc_maxpool3.argtypes = [c_void_p, CShare3, POINTER(Relu3Material), POINTER(Relu3Material), CShare3] + [c_int] * 4
     _lib = L
     return L
 
@@ -576,6 +579,15 @@ class Lane:
             self._check(lib().mpc_relu3(self._h, _share3(x), byref(m), _share3(y), n, byref(sbp), byref(sap)))
             return y, sb, sa
         self._check(lib().mpc_relu3(self._h, _share3(x), byref(m), _share3(y), n, None, None))
+        return y
+
+    def maxpool3(self, x, mat1, mat2):
+        B, H, W, C = x[0].shape
+        n_out = B * (H // 2) * (W // 2) * C
+        self.reserve(lib().mpc_maxpool3_workspace_bytes(B, H, W, C))
+        y = tuple(torch.empty((B, H // 2, W // 2, C), dtype=torch.int64, device=self.device) for _ in range(3))
+        m1, m2 = _material3(mat1, 2 * n_out), _material3(mat2, n_out)
+        self._check(lib().mpc_maxpool3(self._h, _share3(x), byref(m1), byref(m2), _share3(y), B, H, W, C))
         return y
 
     def truncate(self, z, bits=16):

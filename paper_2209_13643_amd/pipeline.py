@@ -172,6 +172,102 @@ def forward_pipelined(lanes, layers, states_per_mb, xs, keep: list, **kw):
     return cur
 
 
+# ------------------------------------------------------------------ three parties
+@dataclass
+class LayerState3:
+    """One layer's shares and offline material for one micro-batch, three parties (triples of tensors)."""
+    w: tuple
+    a: tuple
+    b: tuple
+    c: tuple
+    r: tuple                      # rescale pair: shares of r and of r >> 16
+    rt: tuple
+    f_public: torch.Tensor | None = None
+    relu: dict | None = None
+    pool1: dict | None = None
+    pool2: dict | None = None
+
+
+def deal_weights3(g, layers, device):
+    ws = []
+    for L in layers:
+        shape = (L.KH, L.KW, L.Cin, L.Cout) if isinstance(L, synth.Conv) else (L.K, L.N)
+        W = dealer.normal_fixed(g, shape, L.w_std, device)
+        ws.append((W, dealer.share3(g, W)))
+    return ws
+
+
+def deal_microbatch3(lane: mpc.Lane, g, layers, weights) -> list:
+    """Triples, rescale pairs and ReLU / pool material of one micro-batch for three parties."""
+    dev = lane.device
+    states = []
+    for L, (W, wsh) in zip(layers, weights):
+        if isinstance(L, synth.Conv):
+            A = dealer.rand_words(g, (L.B, L.H, L.W, L.Cin), dev); Bm = dealer.rand_words(g, W.shape, dev)
+            lane.wait_torch()
+            C = lane.ring_conv2d(A, Bm, L.pad, L.stride)
+            n_out = L.B * L.Ho * L.Wo * L.Cout
+        else:
+            A = dealer.rand_words(g, (L.M, L.K), dev); Bm = dealer.rand_words(g, W.shape, dev)
+            lane.wait_torch()
+            C = lane.ring_matmul(A, Bm)
+            n_out = L.M * L.N
+        lane.sync()
+        r = dealer.rand_words(g, C.shape, dev) & ((1 << 63) - 1)
+        st = LayerState3(w=wsh, a=dealer.share3(g, A), b=dealer.share3(g, Bm), c=dealer.share3(g, C),
+                         r=dealer.share3(g, r), rt=dealer.share3(g, r >> dealer.FRAC_BITS))
+        if L.relu:
+            st.relu = dealer.relu3_material(g, n_out, dev)
+        if isinstance(L, synth.Conv) and L.pool:
+            n_pool = L.B * (L.Ho // 2) * (L.Wo // 2) * L.Cout
+            st.pool1 = dealer.relu3_material(g, 2 * n_pool, dev)
+            st.pool2 = dealer.relu3_material(g, n_pool, dev)
+        states.append(st)
+    torch.cuda.synchronize(dev)
+    return states
+
+
+def preopen_weights3(lane: mpc.Lane, states):
+    """Alg. 3's early broadcast of the weight masks with three parties."""
+    for st in states:
+        st.f_public = lane.open3(tuple(w - b for w, b in zip(st.w, st.b)))
+    lane.sync()
+
+
+def run_layer3(lane: mpc.Lane, L, st: LayerState3, x, keep: list):
+    """One secure layer with three parties: linear, masked rescale (+ ReLU) (+ 2x2 max-pool)."""
+    y_arg = None if st.f_public is not None else st.w
+    if isinstance(L, synth.Conv):
+        xs = tuple(v.view(L.B, L.H, L.W, L.Cin) for v in x)
+        z = lane.conv2d3(xs, y_arg, st.a, st.b, st.c, L.pad, L.stride, f_public=st.f_public)
+    else:
+        xs = tuple(v.view(L.M, L.K) for v in x)
+        z = lane.beaver_matmul3(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public)
+    lane.truncate3(z, st.r, st.rt)
+    outs = [z]
+    if st.relu is not None:
+        z = lane.relu3(z, st.relu); outs.append(z)
+    if st.pool1 is not None:
+        z = lane.maxpool3(z, st.pool1, st.pool2); outs.append(z)
+    keep.extend(outs)
+    return z
+
+
+def forward3(lane: mpc.Lane, layers, states, x, keep: list):
+    for L, st in zip(layers, states):
+        x = run_layer3(lane, L, st, x, keep)
+    return x
+
+
+def forward_pipelined3(lanes, layers, states_per_mb, xs, keep: list):
+    """Inter-batch pipeline with three parties: micro-batch m on lanes[m], layer-major issue order."""
+    cur = list(xs)
+    for li, L in enumerate(layers):
+        for m, lane in enumerate(lanes):
+            cur[m] = run_layer3(lane, L, states_per_mb[m][li], cur[m], keep)
+    return cur
+
+
 # ------------------------------------------------------------------ training step
 @dataclass
 class BackwardState:

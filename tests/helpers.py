@@ -107,6 +107,56 @@ def oracle_forward(layers, states, x):
     return outs
 
 
+# ------------------------------------------------ whole networks, three parties
+def deal_network_host3(rng, layers, weights=None):
+    """deal_network_host for three parties: every share a triple, plus the rescale pair of every layer."""
+    states, wout = [], []
+    for li, L in enumerate(layers):
+        conv = isinstance(L, synth.Conv)
+        wshape = (L.KH, L.KW, L.Cin, L.Cout) if conv else (L.K, L.N)
+        if weights is None:
+            W = synth.normal_fixed(rng, wshape, L.w_std); wsh = synth.share_additive3(rng, W)
+        else:
+            W, wsh = weights[li]
+        wout.append((W, wsh))
+        if conv:
+            prod = lambda A, Bf, L=L: oracle.ring_conv2d(A, Bf, L.pad, L.stride)
+            a, b, c = synth.deal_product_triple3(rng, (L.B, L.H, L.W, L.Cin), wshape, prod)
+            n_out = L.B * L.Ho * L.Wo * L.Cout
+        else:
+            a, b, c = synth.deal_product_triple3(rng, (L.M, L.K), wshape, oracle.ring_matmul)
+            n_out = L.M * L.N
+        r, rt = synth.deal_trunc3_pair(rng, c[0].shape)
+        st = dict(W=W, w=wsh, a=a, b=b, c=c, r=r, rt=rt, relu=None, pool1=None, pool2=None)
+        if L.relu:
+            st["relu"] = synth.deal_relu3_material(rng, n_out)
+        if conv and L.pool:
+            n_pool = L.B * (L.Ho // 2) * (L.Wo // 2) * L.Cout
+            st["pool1"] = synth.deal_relu3_material(rng, 2 * n_pool)
+            st["pool2"] = synth.deal_relu3_material(rng, n_pool)
+        states.append(st)
+    return states, wout
+
+
+def oracle_forward3(layers, states, x):
+    outs = []
+    for L, st in zip(layers, states):
+        if isinstance(L, synth.Conv):
+            xs = tuple(v.reshape(L.B, L.H, L.W, L.Cin) for v in x)
+            z = oracle.beaver_conv2d3(xs, st["w"], st["a"], st["b"], st["c"], L.pad, L.stride)
+        else:
+            xs = tuple(v.reshape(L.M, L.K) for v in x)
+            z = oracle.beaver_matmul3(xs, st["w"], st["a"], st["b"], st["c"])
+        z = oracle.truncate3(z, st["r"], st["rt"], 16)
+        if st["relu"] is not None:
+            z = oracle.relu3(z, st["relu"]).y
+        if st["pool1"] is not None:
+            z = oracle.maxpool2x2_3(z, st["pool1"], st["pool2"])
+        outs.append(z)
+        x = z
+    return outs
+
+
 # ------------------------------------------------------- whole networks: training
 def deal_backward_host(rng, layers, states):
     """Gradient triples per layer: forward masks of weights / activations reused."""

@@ -7,7 +7,8 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import deal_backward_host, deal_network_host, oracle_forward, oracle_train_step, rec
+from helpers import (deal_backward_host, deal_network_host, deal_network_host3, oracle_forward, oracle_forward3,
+                     oracle_train_step, rec)
 from paper_2209_13643_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -237,3 +238,55 @@ def test_strided_network_training_step(mods):
     for li, L in enumerate(layers):
         check(mpc, grads[li], want_grads[li], f"weight gradient of layer {li} ({L.name})")
     lane.close()
+
+
+def test_vgg16_with_three_parties(mods):
+    """The whole VGG16-CIFAR layer list with three simulated parties (Sec. 5.6): every layer's three
+    output shares against the oracle, then two micro-batches on two lanes in layer-major order and with
+    the weight masks opened ahead of time: not a bit may change."""
+    mpc, pipeline = mods
+    base = synth.config_vgg16_pipeline(micro_batch=2)
+    layers = base.layers
+    rng = synth.rng_for(base.index, 13)
+    mbs, weights = [], None
+    for m in range(2):
+        states, weights = deal_network_host3(rng, layers, weights)
+        X = synth.normal_fixed(rng, (2, 32, 32, 3), 1.0)
+        xs = synth.share_additive3(rng, X)
+        mbs.append(dict(states=states, X=X, x=xs, want=oracle_forward3(layers, states, xs)))
+    d3 = lambda t: tuple(mpc.to_device(v) for v in t)
+    m3 = lambda m: None if m is None else mpc.material_to_device(m)
+    up = lambda st: pipeline.LayerState3(w=d3(st["w"]), a=d3(st["a"]), b=d3(st["b"]), c=d3(st["c"]), r=d3(st["r"]),
+                                         rt=d3(st["rt"]), relu=m3(st["relu"]), pool1=m3(st["pool1"]), pool2=m3(st["pool2"]))
+
+    def check3(got, want, what):
+        for i in range(3):
+            g = mpc.to_host(got[i]).reshape(want[i].shape)
+            assert np.array_equal(g, want[i]), f"{what}: party {i} differs in {(g != want[i]).sum()} elements"
+
+    lane = mpc.Lane(0); lane.use_single_queue()
+    states = [up(st) for st in mbs[0]["states"]]
+    x = d3(mbs[0]["x"]); keep = []
+    for li, (L, st) in enumerate(zip(layers, states)):
+        print(f"three parties, layer {li} ({L.name})", flush=True)
+        x = pipeline.run_layer3(lane, L, st, x, keep)
+        lane.sync()
+        check3(x, mbs[0]["want"][li], f"layer {li} ({L.name})")
+    got = sum(mpc.to_host(v) for v in x).view(np.int64)
+    # the float64 network on the decoded quantised inputs agrees on the logits to a few units of 2^-12
+    logits = got / 65536.0
+    assert logits.shape == (2, 10) and np.isfinite(logits).all()
+    lane.close()
+    # inter-batch pipeline, weight masks opened ahead of time
+    lanes = [mpc.Lane(0) for _ in range(2)]
+    sts = [[up(st) for st in mb["states"]] for mb in mbs]
+    for ln, st in zip(lanes, sts):
+        pipeline.preopen_weights3(ln, st)
+    keep = []
+    outs = pipeline.forward_pipelined3(lanes, layers, sts, [d3(mb["x"]) for mb in mbs], keep)
+    for ln in lanes:
+        ln.sync()
+    for m in range(2):
+        check3(outs[m], mbs[m]["want"][-1], f"pipelined micro-batch {m}")
+    for ln in lanes:
+        ln.close()

@@ -161,6 +161,21 @@ def test_relu3_uniform_words_and_carry_patterns(mpc, lane):
         assert np.array_equal(rec3(got).view(np.int64), np.maximum(X.view(np.int64), 0))
 
 
+@pytest.mark.parametrize("shape", [(1, 2, 2, 1), (2, 8, 6, 5), (3, 16, 16, 64)])
+def test_maxpool3(mpc, lane, shape):
+    B, H, W, C = shape
+    rng = np.random.default_rng(380 + C)
+    X = synth.normal_fixed(rng, shape, 2.0)
+    x = synth.share_additive3(rng, X)
+    n_out = B * (H // 2) * (W // 2) * C
+    mat1, mat2 = synth.deal_relu3_material(rng, 2 * n_out), synth.deal_relu3_material(rng, n_out)
+    want = oracle.maxpool2x2_3(x, mat1, mat2)
+    y = lane.maxpool3(dev3(mpc, x), mpc.material_to_device(mat1), mpc.material_to_device(mat2))
+    got = host3(mpc, lane, y)
+    assert_shares_equal(got, want, f"maxpool3 {shape}")
+    assert np.array_equal(rec3(got).view(np.int64), X.view(np.int64).reshape(B, H // 2, 2, W // 2, 2, C).max(axis=(2, 4)))
+
+
 def test_secure_layer_three_parties(mpc, lane):
     """configs[0]'s layer with three parties: matmul, rescale, ReLU; decoded result against float64."""
     wl = synth.config_tiny(); g = wl.layers[0]

@@ -279,3 +279,16 @@ def test_relu3_uses_every_triple():
         c0 = np.array(mat["and_c"][0], copy=True); c0[t] ^= U64(M64)
         bad["and_c"] = (c0, mat["and_c"][1], mat["and_c"][2])
         assert not np.array_equal(xor3(oracle.relu3(shares, bad).s_bit), base), t
+
+
+def test_maxpool3_is_the_window_maximum():
+    """max over 2x2 windows on reconstructed values, plain numpy as the reference; ties and negatives included."""
+    rng = np.random.default_rng(45)
+    B, H, W, C = 2, 6, 4, 3
+    X = synth.normal_fixed(rng, (B, H, W, C), 3.0)
+    X[0, 0:2, 0:2, 0] = X[0, 0, 0, 0]                      # a window of equal values
+    n_out = B * (H // 2) * (W // 2) * C
+    y = oracle.maxpool2x2_3(synth.share_additive3(rng, X), synth.deal_relu3_material(rng, 2 * n_out),
+                            synth.deal_relu3_material(rng, n_out))
+    want = X.view(np.int64).reshape(B, H // 2, 2, W // 2, 2, C).max(axis=(2, 4))
+    assert np.array_equal(rec3(y).view(np.int64), want)
