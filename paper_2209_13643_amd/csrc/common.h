@@ -133,7 +133,6 @@ struct WsAlloc {
 int launch_sub(mpc_ctx* c, hipStream_t st, const u64* x, const u64* a, u64* out, size_t n);
 int launch_add(mpc_ctx* c, hipStream_t st, const u64* x, const u64* y, u64* out, size_t n);
 int launch_copy(mpc_ctx* c, hipStream_t st, const void* src, void* dst, size_t bytes);
-int launch_fill_zero(mpc_ctx* c, hipStream_t st, void* dst, size_t bytes);
 int launch_truncate(mpc_ctx* c, hipStream_t st, u64* z, size_t n, int bits, int party);
 int launch_sum3(mpc_ctx* c, hipStream_t st, const u64* x, const u64* y, const u64* w, u64* out, size_t n);
 
@@ -234,7 +233,6 @@ struct GemmArgs {
     int trunc_bits;                   // 0: none
     int rows_L;                       // rows of the left planes (plain: M)
     ConvGeom conv;
-    const u8* zero16;                 // 16 readable zero bytes (conv padding)
     int ksplit;                       // > 1: split the contraction over this many workgroups per tile
     int steps_per_split;              // filled by the launcher
     int tiles_m, tiles_n, tiles_total;   // filled by the launcher: output tiles per matrix, all tiles (x batch x ksplit)

@@ -326,7 +326,7 @@ int mpc_maxpool2x2_backward(mpc_ctx* c, mpc_cshare g, mpc_cshare s1, mpc_cshare 
     }
     if (!ws.ok) return MPC_ENOMEM;
     const size_t off = ws.off;
-    const mpc_cshare gu_c = { { gu.p[0], gu.p[1] } }, pairs_c = { { pairs.p[0], pairs.p[1] } };
+    const mpc_cshare pairs_c = { { pairs.p[0], pairs.p[1] } };
     // grad_u = g * (1 - s2)
     MPC_TRY(mul_entry(c, g, s2, a2, b2, c2, gu, n_out, 0, 1, off));
     PoolBwdArgs q{};

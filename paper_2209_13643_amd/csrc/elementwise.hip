@@ -61,13 +61,6 @@ __global__ __launch_bounds__(kThreads) void k_copy1(const u8* __restrict__ src, 
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
-__global__ __launch_bounds__(kThreads) void k_zero16(uint4* __restrict__ dst, size_t n16)
-{
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
-        dst[i] = make_uint4(0, 0, 0, 0);
-}
-
 // Local two-party truncation: party 0 shifts, party 1 negates, shifts, negates.
 __global__ __launch_bounds__(kThreads) void k_truncate(u64* __restrict__ z, size_t n, int bits, int party)
 {
@@ -444,15 +437,6 @@ int launch_copy(mpc_ctx* c, hipStream_t st, const void* src, void* dst, size_t b
         hipLaunchKernelGGL(k_copy1, dim3(grid_for(bytes)), dim3(kThreads), 0, st,
                            (const u8*)src, (u8*)dst, bytes);
     }
-    MPC_HIP(c, hipGetLastError());
-    return MPC_OK;
-}
-
-int launch_fill_zero(mpc_ctx* c, hipStream_t st, void* dst, size_t bytes)
-{
-    if (bytes == 0) return MPC_OK;
-    if (!aligned16(dst) || bytes % 16) return MPC_EINVAL;
-    hipLaunchKernelGGL(k_zero16, dim3(grid_for(bytes / 16)), dim3(kThreads), 0, st, (uint4*)dst, bytes / 16);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
 }

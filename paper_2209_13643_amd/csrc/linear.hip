@@ -87,7 +87,6 @@ LinearShape shape_conv_grad_w(int B, int H, int W, int Cin, int Cout, int KH, in
 }
 
 struct LinearWs {
-    u8* zero;                  // 256 zero bytes
     u64 *se[2], *re[2];        // masked x shares: sent / received
     u64 *sf[2], *rf[2];        // masked y shares
     u8 *pl_e, *pl_a[2];        // left digit planes
@@ -100,7 +99,6 @@ LinearWs carve(u8* base, size_t cap, const LinearShape& s)
 {
     WsAlloc w(base, cap);
     LinearWs r{};
-    r.zero = w.take<u8>(256);
     for (int i = 0; i < 2; ++i) { r.se[i] = w.take<u64>(s.nx); r.re[i] = w.take<u64>(s.nx); }
     for (int i = 0; i < 2; ++i) { r.sf[i] = w.take<u64>(s.nw); r.rf[i] = w.take<u64>(s.nw); }
     const size_t lp = 8 * s.L_plane * s.batch, rp = 8 * s.R_plane * s.batch;
@@ -175,7 +173,6 @@ void fill_geom(const LinearShape& s, const LinearWs& w, GemmArgs& g)
     g.M = s.M; g.N = s.N; g.batch = s.batch;
     g.out_bstride = (long long)s.M * s.N;
     g.rows_L = s.rowsL;
-    g.zero16 = w.zero;
     g.ksplit = w.ksplit; g.partial = w.partial;
     g.conv = ConvGeom{};
     if (s.conv) {
@@ -416,7 +413,7 @@ struct LinearWs3 {
     u64 *e_pub, *f_pub;        // opened e, f
     u8 *pl_e, *pl_a[3];
     u8 *pr_f, *pr_b[3];        // pr_b[0] holds b_0 + f
-    LinearWs g;                // zero bytes, split count and partial products for the GEMM launches
+    LinearWs g;                // split count and partial products for the GEMM launches
     size_t bytes; bool ok;
 };
 
@@ -424,7 +421,6 @@ LinearWs3 carve3(u8* base, size_t cap, const LinearShape& s)
 {
     WsAlloc w(base, cap);
     LinearWs3 r{};
-    r.g.zero = w.take<u8>(256);
     for (int i = 0; i < 3; ++i) { r.se[i] = w.take<u64>(s.nx); r.re[i][0] = w.take<u64>(s.nx); r.re[i][1] = w.take<u64>(s.nx); }
     for (int i = 0; i < 3; ++i) { r.sf[i] = w.take<u64>(s.nw); r.rf[i][0] = w.take<u64>(s.nw); r.rf[i][1] = w.take<u64>(s.nw); }
     r.e_pub = w.take<u64>(s.nx); r.f_pub = w.take<u64>(s.nw);

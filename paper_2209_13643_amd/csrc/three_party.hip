@@ -66,10 +66,22 @@ struct Relu3Party {
 };
 struct Relu3Args { Relu3Party p[3]; size_t n; };
 
+// Words are processed one per thread, or two per thread with 16-byte accesses
+// when the element count is even and every array is 16-byte aligned.
+typedef u64 u64v2 __attribute__((ext_vector_type(2)));
+typedef u8 u8v2 __attribute__((ext_vector_type(2)));
+template <typename T> struct ByteOf { typedef u8 type; };
+template <> struct ByteOf<u64v2> { typedef u8v2 type; };
+__device__ __forceinline__ u8 to_bytes(u64 v) { return (u8)v; }
+__device__ __forceinline__ u8v2 to_bytes(u64v2 v) { return __builtin_convertvector(v, u8v2); }
+__device__ __forceinline__ u64 to_words(u8 v) { return v; }
+__device__ __forceinline__ u64v2 to_words(u8v2 v) { return __builtin_convertvector(v, u64v2); }
+
 // One Beaver AND gate finished: own and received masked operands -> this party's share.
-__device__ __forceinline__ u64 and_finish(int party, u64 d, u64 g, u64 a, u64 b, u64 c)
+template <typename T>
+__device__ __forceinline__ T and_finish(int party, T d, T g, T a, T b, T c)
 {
-    u64 t = c ^ (d & b) ^ (g & a);
+    T t = c ^ (d & b) ^ (g & a);
     if (party == 0) t ^= d & g;
     return t;
 }
@@ -81,87 +93,111 @@ __device__ __forceinline__ u64 and_finish(int party, u64 d, u64 g, u64 a, u64 b,
 //       8      : level 5 finished -> sign share, B2A masked
 //       9      : B2A finished -> m = 1 - s, select masked
 //       10     : select finished -> y
-template <int STAGE>
+template <int STAGE, typename T>
 __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
 {
+    typedef typename ByteOf<T>::type B;
     const int party = blockIdx.y;
     const Relu3Party& p = q.p[party];
-    const size_t n = q.n;
+    const size_t n = q.n;                                    // words per row
+    const size_t units = n / (sizeof(T) / sizeof(u64));
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    // row r of a [rows][n] word array, as units
+    auto in = [n](const u64* base, int r) { return reinterpret_cast<const T*>(base + (size_t)r * n); };
+    auto out = [n](u64* base, int r) { return reinterpret_cast<T*>(base + (size_t)r * n); };
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < units; i += stride) {
         // masked words of the previous round, opened
-        u64 o[4] = { 0, 0, 0, 0 };
+        T o[4] = {};
         constexpr int kOpen = (STAGE == 0 || STAGE >= 9) ? 0 : (STAGE >= 3 && STAGE <= 7) ? 4 : 2;
 #pragma unroll
-        for (int k = 0; k < kOpen; ++k) o[k] = p.send[k * n + i] ^ p.recv[0][k * n + i] ^ p.recv[1][k * n + i];
+        for (int k = 0; k < kOpen; ++k) o[k] = in(p.send, k)[i] ^ in(p.recv[0], k)[i] ^ in(p.recv[1], k)[i];
 
         if constexpr (STAGE == 0) {
-            const u64 own = p.x[i] ^ p.r0[i] ^ p.r1[i];
+            const T own = in(p.x, 0)[i] ^ in(p.r0, 0)[i] ^ in(p.r1, 0)[i];
             // party's shares of the words x_0, x_1, x_2
-            const u64 w1 = p.wrecv[0][i], w2 = p.wrecv[1][i];        // words of party+1, party+2
-            const u64 U = party == 0 ? own : party == 1 ? w2 : w1;
-            const u64 V = party == 1 ? own : party == 2 ? w2 : w1;
-            const u64 W = party == 2 ? own : party == 0 ? w2 : w1;
-            p.S[i] = U ^ V ^ W; p.Wd[i] = W;
-            p.send[i] = (U ^ W) ^ p.ta[i];
-            p.send[n + i] = (V ^ W) ^ p.tb[i];
+            const T w1 = in(p.wrecv[0], 0)[i], w2 = in(p.wrecv[1], 0)[i];      // words of party+1, party+2
+            const T U = party == 0 ? own : party == 1 ? w2 : w1;
+            const T V = party == 1 ? own : party == 2 ? w2 : w1;
+            const T W = party == 2 ? own : party == 0 ? w2 : w1;
+            out(p.S, 0)[i] = U ^ V ^ W; out(p.Wd, 0)[i] = W;
+            out(p.send, 0)[i] = (U ^ W) ^ in(p.ta, 0)[i];
+            out(p.send, 1)[i] = (V ^ W) ^ in(p.tb, 0)[i];
         } else if constexpr (STAGE == 1) {
-            const u64 T = and_finish(party, o[0], o[1], p.ta[i], p.tb[i], p.tc[i]);
-            const u64 S = p.S[i];
-            const u64 K = (T ^ p.Wd[i]) << 1;
-            const u64 P = S ^ K;
-            p.P[i] = P; p.p63[i] = (u8)(P >> 63);
-            p.send[i] = S ^ p.ta[n + i];
-            p.send[n + i] = K ^ p.tb[n + i];
+            const T Tm = and_finish<T>(party, o[0], o[1], in(p.ta, 0)[i], in(p.tb, 0)[i], in(p.tc, 0)[i]);
+            const T S = in(p.S, 0)[i];
+            const T K = (Tm ^ in(p.Wd, 0)[i]) << 1;
+            const T P = S ^ K;
+            out(p.P, 0)[i] = P; reinterpret_cast<B*>(p.p63)[i] = to_bytes(P >> 63);
+            out(p.send, 0)[i] = S ^ in(p.ta, 1)[i];
+            out(p.send, 1)[i] = K ^ in(p.tb, 1)[i];
         } else if constexpr (STAGE == 2) {
-            const u64 G = and_finish(party, o[0], o[1], p.ta[n + i], p.tb[n + i], p.tc[n + i]);
-            const u64 P = p.P[i];
-            p.G[i] = G;
-            p.send[i] = P ^ p.ta[2 * n + i];          p.send[n + i] = (G << 1) ^ p.tb[2 * n + i];
-            p.send[2 * n + i] = P ^ p.ta[3 * n + i];  p.send[3 * n + i] = (P << 1) ^ p.tb[3 * n + i];
+            const T G = and_finish<T>(party, o[0], o[1], in(p.ta, 1)[i], in(p.tb, 1)[i], in(p.tc, 1)[i]);
+            const T P = in(p.P, 0)[i];
+            out(p.G, 0)[i] = G;
+            out(p.send, 0)[i] = P ^ in(p.ta, 2)[i];  out(p.send, 1)[i] = (G << 1) ^ in(p.tb, 2)[i];
+            out(p.send, 2)[i] = P ^ in(p.ta, 3)[i];  out(p.send, 3)[i] = (P << 1) ^ in(p.tb, 3)[i];
         } else if constexpr (STAGE >= 3 && STAGE <= 7) {
             constexpr int L = STAGE - 3;                 // level being finished
             constexpr int tg = 2 + 2 * L, tp = 3 + 2 * L;
-            const u64 T1 = and_finish(party, o[0], o[1], p.ta[tg * n + i], p.tb[tg * n + i], p.tc[tg * n + i]);
-            const u64 P = and_finish(party, o[2], o[3], p.ta[tp * n + i], p.tb[tp * n + i], p.tc[tp * n + i]);
-            const u64 G = p.G[i] ^ T1;
-            p.G[i] = G;
+            const T T1 = and_finish<T>(party, o[0], o[1], in(p.ta, tg)[i], in(p.tb, tg)[i], in(p.tc, tg)[i]);
+            const T P = and_finish<T>(party, o[2], o[3], in(p.ta, tp)[i], in(p.tb, tp)[i], in(p.tc, tp)[i]);
+            const T G = in(p.G, 0)[i] ^ T1;
+            out(p.G, 0)[i] = G;
             constexpr int d = 2 << L;                    // shift of level L + 1
             constexpr int ng = tg + 2, np = tp + 2;
-            p.send[i] = P ^ p.ta[ng * n + i];  p.send[n + i] = (G << d) ^ p.tb[ng * n + i];
+            out(p.send, 0)[i] = P ^ in(p.ta, ng)[i];  out(p.send, 1)[i] = (G << d) ^ in(p.tb, ng)[i];
             if constexpr (L + 1 < 5) {                   // the last level needs no P update
-                p.send[2 * n + i] = P ^ p.ta[np * n + i];  p.send[3 * n + i] = (P << d) ^ p.tb[np * n + i];
+                out(p.send, 2)[i] = P ^ in(p.ta, np)[i];  out(p.send, 3)[i] = (P << d) ^ in(p.tb, np)[i];
             }
         } else if constexpr (STAGE == 8) {
-            const u64 T1 = and_finish(party, o[0], o[1], p.ta[12 * n + i], p.tb[12 * n + i], p.tc[12 * n + i]);
-            const u64 G = p.G[i] ^ T1;
-            const u8 s = (u8)(p.p63[i] ^ ((G >> 62) & 1));
-            if (p.s_bit) p.s_bit[i] = s;
-            p.vsend[i] = s ^ p.rb[i];
+            const T T1 = and_finish<T>(party, o[0], o[1], in(p.ta, 12)[i], in(p.tb, 12)[i], in(p.tc, 12)[i]);
+            const T G = in(p.G, 0)[i] ^ T1;
+            const B s = reinterpret_cast<const B*>(p.p63)[i] ^ to_bytes((G >> 62) & 1);
+            if (p.s_bit) reinterpret_cast<B*>(p.s_bit)[i] = s;
+            reinterpret_cast<B*>(p.vsend)[i] = s ^ reinterpret_cast<const B*>(p.rb)[i];
         } else if constexpr (STAGE == 9) {
-            const u64 v = (u64)(p.vsend[i] ^ p.vrecv[0][i] ^ p.vrecv[1][i]);
-            const u64 ra = p.ra[i];
-            u64 sa = ra - 2 * v * ra;
+            const T v = to_words(reinterpret_cast<const B*>(p.vsend)[i] ^ reinterpret_cast<const B*>(p.vrecv[0])[i] ^
+                                 reinterpret_cast<const B*>(p.vrecv[1])[i]);
+            const T ra = in(p.ra, 0)[i];
+            T sa = ra - 2 * v * ra;
             if (party == 0) sa += v;
-            if (p.s_arith) p.s_arith[i] = sa;
-            const u64 m = (party == 0 ? (u64)1 : (u64)0) - sa;
-            p.send[i] = p.x[i] - p.ma[i];
-            p.send[n + i] = m - p.mb[i];
+            if (p.s_arith) out(p.s_arith, 0)[i] = sa;
+            const T m = (party == 0 ? (u64)1 : (u64)0) - sa;
+            out(p.send, 0)[i] = in(p.x, 0)[i] - in(p.ma, 0)[i];
+            out(p.send, 1)[i] = m - in(p.mb, 0)[i];
         } else {
             // additive opening of the select product's masked operands
-            const u64 e = p.send[i] + p.recv[0][i] + p.recv[1][i];
-            const u64 f = p.send[n + i] + p.recv[0][n + i] + p.recv[1][n + i];
-            u64 yv = p.mc[i] + e * p.mb[i] + p.ma[i] * f;
+            const T e = in(p.send, 0)[i] + in(p.recv[0], 0)[i] + in(p.recv[1], 0)[i];
+            const T f = in(p.send, 1)[i] + in(p.recv[0], 1)[i] + in(p.recv[1], 1)[i];
+            const T mb = in(p.mb, 0)[i], ma = in(p.ma, 0)[i];
+            T yv = in(p.mc, 0)[i] + e * mb + ma * f;
             if (party == 0) yv += e * f;
-            p.y[i] = yv;
+            out(p.y, 0)[i] = yv;
         }
     }
 }
 
-template <int STAGE>
-int launch_stage(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
+// 16-byte accesses need an even element count (rows of the [k][n] arrays stay aligned) and aligned arrays
+bool relu3_vectorisable(const Relu3Args& q)
 {
-    hipLaunchKernelGGL(k3_relu<STAGE>, dim3(grid3(q.n), 3), dim3(kT), 0, st, q);
+    if (q.n & 1) return false;
+    uintptr_t w = 0, b = 0;
+    for (int i = 0; i < 3; ++i) {
+        const Relu3Party& p = q.p[i];
+        for (const void* ptr : { (const void*)p.x, (const void*)p.r0, (const void*)p.r1, (const void*)p.ta, (const void*)p.tb,
+                                 (const void*)p.tc, (const void*)p.ra, (const void*)p.ma, (const void*)p.mb, (const void*)p.mc,
+                                 (const void*)p.y, (const void*)p.s_arith })
+            w |= (uintptr_t)ptr;
+        b |= (uintptr_t)p.rb | (uintptr_t)p.s_bit;
+    }
+    return (w & 15) == 0 && (b & 1) == 0;
+}
+
+template <int STAGE>
+int launch_stage(mpc_ctx* c, hipStream_t st, const Relu3Args& q, bool vec)
+{
+    if (vec) hipLaunchKernelGGL((k3_relu<STAGE, u64v2>), dim3(grid3(q.n / 2), 3), dim3(kT), 0, st, q);
+    else     hipLaunchKernelGGL((k3_relu<STAGE, u64>), dim3(grid3(q.n), 3), dim3(kT), 0, st, q);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
 }
@@ -219,6 +255,7 @@ void fill3(Relu3Args& q, const u64* const x[3], const mpc_relu3_material* m, u64
 int relu3_run(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
 {
     const size_t n = q.n;
+    const bool vec = relu3_vectorisable(q);
     // Alg. 2: party j sends the mask r1_j to party j+2 and r0_j to party j+1, i.e. party i
     // receives its share of word i+1 (that party's r1) and of word i+2 (that party's r0)
     {
@@ -229,15 +266,15 @@ int relu3_run(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
         }
         MPC_TRY(launch_copy_multi(c, st, cp, 6));
     }
-    MPC_TRY(launch_stage<0>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<1>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<2>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<3>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<4>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<5>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<6>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<7>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<8>(c, st, q));
+    MPC_TRY(launch_stage<0>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
+    MPC_TRY(launch_stage<1>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
+    MPC_TRY(launch_stage<2>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 4));
+    MPC_TRY(launch_stage<3>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 4));
+    MPC_TRY(launch_stage<4>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 4));
+    MPC_TRY(launch_stage<5>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 4));
+    MPC_TRY(launch_stage<6>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 4));
+    MPC_TRY(launch_stage<7>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
+    MPC_TRY(launch_stage<8>(c, st, q, vec));
     {
         CopySeg cp[6]; int k = 0;
         for (int i = 0; i < 3; ++i)
@@ -245,8 +282,8 @@ int relu3_run(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
                 cp[k++] = CopySeg{ q.p[(i + 1 + s) % 3].vsend, q.p[i].vrecv[s], n, 0 };
         MPC_TRY(launch_copy_multi(c, st, cp, 6));
     }
-    MPC_TRY(launch_stage<9>(c, st, q));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<10>(c, st, q));
+    MPC_TRY(launch_stage<9>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
+    MPC_TRY(launch_stage<10>(c, st, q, vec));
     return MPC_OK;
 }
 

@@ -122,6 +122,8 @@ def test_three_party_workspace_queries(lib):
     n = 1000
     assert lib.mpc_relu3_workspace_bytes(n) == 3 * (6 * up(8 * n) + 3 * up(32 * n) + 4 * up(n))
     assert lib.mpc_relu3_workspace_bytes(0) == 0
+    assert lib.mpc_maxpool3_workspace_bytes(1, 4, 4, 2) > lib.mpc_relu3_workspace_bytes(16)
+    assert lib.mpc_maxpool3_workspace_bytes(1, 3, 4, 2) == 0               # odd height
     # null arguments are rejected before any device work
     assert lib.mpc_open3(None, mpc_null3(), None, 4) == -1
 
