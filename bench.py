@@ -16,7 +16,9 @@ chain against HBM bandwidth, `value_prepared_planes` the convolution call when
 the digit planes of the triple and of the opened weight mask were recoded ahead
 of time (mpc_conv2d_prepared), `roofline_relu_msb` the same ReLU evaluated on the
 sign's carry chain only with bit-packed triples (mpc_relu_msb, timed on its own
-after the steps); `cpu_baseline` is the CPU oracle timed on this
+after the steps); `three_party` the same conv block, masked rescale and ReLU with
+three simulated parties (Alg. 1 / Alg. 2 for N = 3), timed on its own;
+`cpu_baseline` is the CPU oracle timed on this
 box's host cores on the same workload (a reported baseline, not a target).
 """
 from __future__ import annotations
@@ -37,6 +39,61 @@ INT8_OPS_PER_SECURE_MAC = 288          # 2 parties x 2 ring GEMMs x 36 digit pro
 RELU_BYTES_PER_ELEMENT = 86 * 8 + 2 + 216 * 8 + 137 * 8   # compulsory + openings + carried state, both parties
 # the sign-only packed chain (mpc_relu_msb), same three classes: 31.72 W + 2 B, 71.25 W + 8 B, 41.56 W + 6 B
 RELU_MSB_BYTES_PER_ELEMENT = (31.71875 + 71.25 + 41.5625) * 8 + 16
+
+
+RELU3_BYTES_PER_ELEMENT = 966 * 8 + 33      # three parties: 141 W + 3 B, 606 W + 21 B, 219 W + 9 B (same three classes)
+
+
+def three_party_leg(lane, L, steps, warmup):
+    """The step's three calls with three simulated parties, each timed by its own region / the host clock."""
+    import statistics
+
+    import torch
+    from paper_2209_13643_amd import dealer, mpc, synth
+
+    dev = lane.device
+    g = dealer.gen(synth.BASE_SEED + 31, dev)
+    d = dealer.conv_layer3(lane, g, L.B, L.H, L.W, L.Cin, L.Cout, L.KH, L.KW, L.pad, L.stride, L.x_std, L.w_std)
+    M, K, N = L.gemm_mkn
+    n = M * N
+    mat = dealer.relu3_material(g, n, dev)
+    z = tuple(torch.empty_like(d["c"][0]) for _ in range(3))
+    y = tuple(torch.empty_like(d["c"][0]) for _ in range(3))
+
+    def step():
+        lane.conv2d3(d["x"], d["w"], d["a"], d["b"], d["c"], L.pad, L.stride, out=z)
+        lane.truncate3(z, d["r"], d["rt"])               # in place
+        lane.relu3(z, mat, out=y)
+
+    for _ in range(warmup):
+        step()
+    lane.sync(); torch.cuda.synchronize()
+    lane.set_profiling(True); lane.profile_reset()
+    for _ in range(steps):
+        step()
+    lane.sync(); torch.cuda.synchronize()
+    lane.set_profiling(False)
+    lin = statistics.median(lane.profile_samples(mpc.PROF_LINEAR))
+    gemm = sum(lane.profile_samples(mpc.PROF_GEMM_KERNEL)) / steps          # two launches per call
+    relu = statistics.median(lane.profile_samples(mpc.PROF_RELU))
+    # properties that hold for every element: product, rescale band, ReLU
+    zz = lane.conv2d3(d["x"], d["w"], d["a"], d["b"], d["c"], L.pad, L.stride)      # the product before the rescale
+    lane.sync()
+    rz = zz[0] + zz[1] + zz[2]; rt = z[0] + z[1] + z[2]; ry = y[0] + y[1] + y[2]
+    dlt = rt - (rz >> 16)
+    assert int(dlt.min()) >= 0 and int(dlt.max()) <= 1, "three-party rescale left the floor + {0, 1} band"
+    assert torch.equal(ry, torch.clamp(rt, min=0)), "three-party ReLU output does not reconstruct to max(t, 0)"
+    ref = torch.nn.functional.conv2d((d["X"][:2].double() / 65536).permute(0, 3, 1, 2),
+                                     (d["W"].double() / 65536).permute(3, 2, 0, 1), padding=L.pad, stride=L.stride)
+    err = (rt[:2].double() / 65536 - ref.permute(0, 2, 3, 1)).abs().max().item()
+    assert err <= 2.0 ** -12, f"three-party decoded conv output off by {err}"
+    macs = M * K * N
+    return {"parties": 3, "ms_beaver_conv_call": lin, "value": macs / (lin * 1e-3), "unit": "secure MACs/s",
+            "ms_gemm_kernels": gemm, "gemm_frac_of_int8_peak": 432 * macs / (gemm * 1e-3) / 1e12 / INT8_PEAK_TOPS,
+            "ms_relu_call": relu, "relu_value": n / (relu * 1e-3),
+            "relu_bytes_per_element": RELU3_BYTES_PER_ELEMENT,
+            "relu_frac_of_hbm_peak": RELU3_BYTES_PER_ELEMENT * n / (relu * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "max_abs_err_vs_float64": err}
 
 
 def cpu_baseline(layer, budget_s=12.0):
@@ -129,6 +186,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-three-party", action="store_true", help="skip the three-party leg (same workload, N = 3)")
     ap.add_argument("--cpu-all-configs", action="store_true",
                     help="also time the oracle on a sample of every layer of all five workloads")
     args = ap.parse_args()
@@ -261,6 +319,8 @@ def main():
                               "traffic": {"bytes_per_element": 1164, "source": "rocprofv3 --pmc, same summary"},
                               "bytes_per_element": RELU_MSB_BYTES_PER_ELEMENT},
     }
+    if not args.no_three_party:
+        out["three_party"] = three_party_leg(lane, L, args.steps, args.warmup)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L)
         if args.cpu_all_configs:
