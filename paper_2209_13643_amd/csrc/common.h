@@ -163,6 +163,7 @@ int launch_recode(mpc_ctx* c, hipStream_t st, const RecodeArgs& a);
 constexpr int kMaxRecodeSets = 6;
 struct RecodeBatch { RecodeArgs a[kMaxRecodeSets]; int batch; };
 int launch_recode_multi(mpc_ctx* c, hipStream_t st, const RecodeArgs* sets, int count);
+int launch_recode_any(mpc_ctx* c, hipStream_t st, const RecodeArgs* sets, int count);
 
 // transposed im2col planes of an NHWC tensor (left operand of the filter-gradient product)
 struct Im2colTArgs {

@@ -3,6 +3,8 @@
 // All of them are HBM-bound; they use 16-byte accesses and grid-stride loops.
 #include "common.h"
 
+#include <algorithm>
+
 namespace {
 
 constexpr int kThreads = 256;
@@ -83,7 +85,8 @@ __device__ __forceinline__ u64 balanced_digits(u64 x)
 // One thread recodes one (row, k-block): 16 ring words in, one 16-byte unit
 // out per digit plane.  Consecutive lanes take consecutive rows so that the
 // plane stores are contiguous.
-__device__ __forceinline__ void recode_body(const RecodeArgs& a, int tap /* == ntaps: zero padding block(s) */, int b)
+__device__ __forceinline__ void recode_body(const RecodeArgs& a, int tap /* == ntaps: zero padding block(s) */, int b,
+                                            unsigned bx, unsigned nbx)
 {
     const u64* src = a.src + (size_t)b * a.src_batch_stride;
     const u64* src2 = a.src2 ? a.src2 + (size_t)b * a.src_batch_stride : nullptr;
@@ -92,8 +95,8 @@ __device__ __forceinline__ void recode_body(const RecodeArgs& a, int tap /* == n
     const bool padtap = tap >= a.ntaps;
     const int kb_count = padtap ? a.KB_total - a.ntaps * a.KB_tap : a.KB_tap;
     const size_t items = (size_t)kb_count * a.plane_rows;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t it = (size_t)blockIdx.x * blockDim.x + threadIdx.x; it < items; it += stride) {
+    const size_t stride = (size_t)nbx * blockDim.x;
+    for (size_t it = (size_t)bx * blockDim.x + threadIdx.x; it < items; it += stride) {
         const int kbl = (int)(it / a.plane_rows);
         const int row = (int)(it - (size_t)kbl * a.plane_rows);
         const int kb_out = (padtap ? a.ntaps * a.KB_tap : tap * a.KB_tap) + kbl;
@@ -130,7 +133,7 @@ __device__ __forceinline__ void recode_body(const RecodeArgs& a, int tap /* == n
 
 __global__ __launch_bounds__(kThreads) void k_recode(RecodeArgs a)
 {
-    recode_body(a, blockIdx.y, blockIdx.z);
+    recode_body(a, blockIdx.y, blockIdx.z, blockIdx.x, gridDim.x);
 }
 
 // Recoding of a matrix whose k index is contiguous in memory (left operands,
@@ -138,12 +141,9 @@ __global__ __launch_bounds__(kThreads) void k_recode(RecodeArgs a)
 // lanes along k (coalesced 16-byte loads), scatters the digits into LDS in
 // plane order, and writes each plane's 16-byte units with lanes along rows
 // (coalesced again).  blockIdx = (row tile, group of 4 k blocks, set*batch).
-__global__ __launch_bounds__(kThreads) void k_recode_rows(RecodeBatch rb)
+__device__ __forceinline__ void recode_rows_body(const RecodeArgs& a, int b, unsigned bx, unsigned by, uint32_t (*tile)[4][64][4])
 {
-    __shared__ uint32_t tile[8][4][64][4];
-    const int set = blockIdx.z / rb.batch, b = blockIdx.z - set * rb.batch;
-    const RecodeArgs& a = rb.a[set];
-    const int row0 = blockIdx.x * 64, kb0 = blockIdx.y * 4;
+    const int row0 = bx * 64, kb0 = by * 4;
     if (row0 >= a.plane_rows || kb0 >= a.KB_total) return;      // uniform per workgroup
     const u64* src = a.src + (size_t)b * a.src_batch_stride;
     const u64* src2 = a.src2 ? a.src2 + (size_t)b * a.src_batch_stride : nullptr;
@@ -197,6 +197,32 @@ __global__ __launch_bounds__(kThreads) void k_recode_rows(RecodeBatch rb)
             *reinterpret_cast<uint4*>(dst + (size_t)d * a.digit_stride + ((size_t)(kb0 + kbl) * a.plane_rows + row0 + row) * 16) = val;
         }
     }
+}
+
+__global__ __launch_bounds__(kThreads) void k_recode_rows(RecodeBatch rb)
+{
+    __shared__ uint32_t tile[8][4][64][4];
+    const int set = blockIdx.z / rb.batch, b = blockIdx.z - set * rb.batch;
+    recode_rows_body(rb.a[set], b, blockIdx.x, blockIdx.y, tile);
+}
+
+// Sets of both kinds in one launch over a flat list of workgroups: set q owns the
+// ids [first[q], first[q+1]), decoded as (x, y, batch item) with its own extents gx, gy.
+// Contiguous-k sets (rows_kind) use the tile recoder above with (x, y) = (row tile, group
+// of 4 k blocks); generic sets use one thread per (row, k block) with y = tap.
+struct RecodeMixed { RecodeBatch rb; unsigned first[kMaxRecodeSets + 1]; unsigned gx[kMaxRecodeSets], gy[kMaxRecodeSets];
+                     bool rows_kind[kMaxRecodeSets]; int count; };
+__global__ __launch_bounds__(kThreads) void k_recode_mixed(RecodeMixed m)
+{
+    __shared__ uint32_t tile[8][4][64][4];
+    int q = 0;
+    while (q + 1 < m.count && blockIdx.x >= m.first[q + 1]) ++q;       // uniform per workgroup
+    const RecodeArgs& a = m.rb.a[q];
+    unsigned id = blockIdx.x - m.first[q];
+    const unsigned x = id % m.gx[q]; id /= m.gx[q];
+    const unsigned y = id % m.gy[q]; const int b = (int)(id / m.gy[q]);
+    if (m.rows_kind[q]) recode_rows_body(a, b, x, y, tile);
+    else                recode_body(a, (int)y, b, x, m.gx[q]);
 }
 
 // Digit planes of the transposed im2col matrix of an NHWC tensor: plane row
@@ -342,7 +368,7 @@ __global__ __launch_bounds__(kThreads) void k_recode_multi(RecodeBatch rb)
     const int set = blockIdx.z / rb.batch, b = blockIdx.z - set * rb.batch;
     const RecodeArgs& a = rb.a[set];
     const int taps = a.ntaps + (a.KB_total > a.ntaps * a.KB_tap ? 1 : 0);
-    if ((int)blockIdx.y < taps) recode_body(a, blockIdx.y, b);
+    if ((int)blockIdx.y < taps) recode_body(a, blockIdx.y, b, blockIdx.x, gridDim.x);
 }
 
 // Several element-wise subtractions / copies in one launch: blockIdx.y = segment.
@@ -491,6 +517,34 @@ int launch_recode_multi(mpc_ctx* c, hipStream_t st, const RecodeArgs* sets, int 
     if ((size_t)count * rb.batch > 65535) return MPC_EINVAL;
     dim3 grid(grid_for(items), taps, count * rb.batch);
     hipLaunchKernelGGL(k_recode_multi, grid, dim3(kThreads), 0, st, rb);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+// Up to kMaxRecodeSets recodings of either kind (contiguous k, or generic with taps) in one launch.
+int launch_recode_any(mpc_ctx* c, hipStream_t st, const RecodeArgs* sets, int count)
+{
+    if (count < 1 || count > kMaxRecodeSets) return MPC_EINVAL;
+    RecodeMixed m{};
+    unsigned long long total = 0;
+    for (int i = 0; i < count; ++i) {
+        const RecodeArgs& a = sets[i];
+        m.rb.a[i] = a;
+        m.rows_kind[i] = a.k_stride == 1 && a.ntaps == 1;
+        if (m.rows_kind[i]) {
+            m.gx[i] = (unsigned)((a.plane_rows + 63) / 64); m.gy[i] = (unsigned)((a.KB_total + 3) / 4);
+        } else {
+            m.gx[i] = (unsigned)grid_for((size_t)a.KB_tap * a.plane_rows);
+            m.gy[i] = (unsigned)(a.ntaps + (a.KB_total > a.ntaps * a.KB_tap ? 1 : 0));
+        }
+        if (m.gx[i] == 0 || m.gy[i] == 0 || a.batch < 1) return MPC_EINVAL;
+        m.first[i] = (unsigned)total;
+        total += (unsigned long long)m.gx[i] * m.gy[i] * a.batch;
+        if (total >= (1ull << 31)) return MPC_EINVAL;
+    }
+    m.first[count] = (unsigned)total;
+    m.count = count;
+    hipLaunchKernelGGL(k_recode_mixed, dim3((unsigned)total), dim3(kThreads), 0, st, m);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
 }

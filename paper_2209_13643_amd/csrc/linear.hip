@@ -274,21 +274,24 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         }
         const u64* f0 = f_public ? f_public : w.sf[0];
         const u64* f1 = f_public ? nullptr : w.rf[0];
-        RecodeArgs rr[3];
+        RecodeArgs rr[6];
         const u64* lsrc[3] = { a.p[0], a.p[1], x_public ? x_public : w.se[0] };
         const u64* lsrc2[3] = { nullptr, nullptr, x_public ? nullptr : w.re[0] };
         u8* ldst[3] = { w.pl_a[0], w.pl_a[1], w.pl_e };
-        if (skip_left) {
-            MPC_TRY(launch_left(c, P0, s, 1, lsrc + 2, lsrc2 + 2, ldst + 2));
+        // all digit planes of the call in one launch (the transposed-im2col recoder is a kernel of its own)
+        int nr = 0;
+        const int l0 = skip_left ? 2 : 0;
+        if (s.im2colT) {
+            MPC_TRY(launch_left(c, P0, s, 3 - l0, lsrc + l0, lsrc2 + l0, ldst + l0));
         } else {
-            MPC_TRY(launch_left(c, P0, s, 3, lsrc, lsrc2, ldst));
+            for (int i = l0; i < 3; ++i) rr[nr++] = recode_left(s, lsrc[i], lsrc2[i], ldst[i]);
         }
         if (!skip_right) {
-            rr[0] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
-            rr[1] = recode_right(s, f0, f1, nullptr, w.pr_f);
-            rr[2] = recode_right(s, b.p[0], f0, f1, w.pr_b[0]);
-            MPC_TRY(launch_recode_multi(c, P0, rr, 3));
+            rr[nr++] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
+            rr[nr++] = recode_right(s, f0, f1, nullptr, w.pr_f);
+            rr[nr++] = recode_right(s, b.p[0], f0, f1, w.pr_b[0]);
         }
+        if (nr) MPC_TRY(launch_recode_any(c, P0, rr, nr));
         if (two_phase && have_f) {
             g.nseg = 1;
             for (int i = 0; i < 2; ++i) {
