@@ -311,7 +311,7 @@ def main():
         "roofline_relu": {"kernel": "secure ReLU chain: k_relu_stage<0..9> (both parties per launch) + k_wire_words / k_wire_bytes",
                           "bound": "hbm", "achieved": relu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                           "frac": relu_gbs / HBM_PEAK_GBS,
-                          "traffic": {"bytes_per_element": 3385, "source": "rocprofv3 --pmc, same summary"},
+                          "traffic": {"bytes_per_element": 3388, "source": "rocprofv3 --pmc, same summary"},
                           "bytes_per_element": RELU_BYTES_PER_ELEMENT},
         "roofline_relu_msb": {"kernel": "sign-only packed ReLU chain: k_relu_msb_stage<0..9> + k_wire_words / k_wire_bytes",
                               "bound": "hbm", "achieved": msb_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
