@@ -272,6 +272,38 @@ void k_limb_gemm(GemmArgs g)
         }
     };
 
+    // ---- output pointers, and the addend c_i of the epilogue.  Its loads (indices clamped
+    // into the matrix, no per-word branch) are issued all at once: for short contractions,
+    // where the epilogue is a large part of a tile's time, from inside the last step but one
+    // (after that step's counted wait, so no later wait of the ring covers them; they land
+    // while the last two steps compute: 5 % on 64-deep contractions); for long ones at the
+    // start of the epilogue (measured 1 % better there than the extra issue work in the loop).
+    const bool partial = g.ksplit > 1;      // raw partial products go to the workspace; a second kernel finishes
+    const u64* addend = (g.addend[party] && !partial) ? g.addend[party] + (size_t)bidx * g.out_bstride : nullptr;
+    const u64* addend2 = (g.addend2[party] && !partial) ? g.addend2[party] + (size_t)bidx * g.out_bstride : nullptr;
+    u64* out = partial ? g.partial + (((size_t)split * g.nparty + party) * g.batch + bidx) * g.out_bstride
+                       : g.out[party] + (size_t)bidx * g.out_bstride;
+    const int rbase = m0 + wm * 32 + g2 * 4;
+    const int shift = partial ? 0 : g.trunc_bits;
+    const u64 neg = (party != 0 && shift != 0) ? ~(u64)0 : 0;       // two's-complement negation as (z ^ neg) - neg
+    const bool interior = m0 + C::TM <= g.M && n0 + C::TN <= g.N;   // uniform: no per-word bounds checks
+    u64 addw[2][16];
+    auto load_addend = [&]() {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int col = n0 + wn * 64 + c * 32 + i32;
+            const int colc = col < g.N ? col : g.N - 1;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = rbase + (v >> 2) * 8 + (v & 3);
+                const int rowc = row < g.M ? row : g.M - 1;
+                addw[c][v] = addend ? addend[(size_t)rowc * g.N + colc] : 0;
+            }
+        }
+    };
+    const int t_addend = T >= 2 ? T - 2 : 0;        // always one of the last NS steps
+    const bool early_addend = T <= 24;
+
     // ---- main loop.  Ring slot t%NS holds K step t.  At the top of step t the
     // slot of step t+1 must have landed (this wave's loads: all but the most
     // recent PER_STAGE); the barrier makes every wave's part visible and
@@ -301,6 +333,7 @@ void k_limb_gemm(GemmArgs g)
         if (FULL || t + 2 < T) __builtin_amdgcn_s_waitcnt(vmcnt_imm(PER_STAGE));
         else if (have_next)    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
         __syncthreads();
+        if constexpr (!FULL) { if (early_addend && t == t_addend) load_addend(); }
         const int nslot = slot + 1 == NS ? 0 : slot + 1;
         if (fill) stage_begin(slot);
         // MFMA number n (0..71) <-> block j, left digit i, column half c
@@ -330,53 +363,60 @@ void k_limb_gemm(GemmArgs g)
     for (; t + NS < T; ++t) step(std::true_type{}, t);
     for (; t < T; ++t) step(std::false_type{}, t);
 
-    // ---- epilogue: recombine, add, truncate, store.  The addend loads are
-    // issued unconditionally (indices clamped into the matrix) and all at once
-    // per 32-column half, so their latency is paid once, not once per element.
-    const u64* addend = g.addend[party] ? g.addend[party] + (size_t)bidx * g.out_bstride : nullptr;
-    const u64* addend2 = g.addend2[party] ? g.addend2[party] + (size_t)bidx * g.out_bstride : nullptr;
-    u64* out = g.out[party] + (size_t)bidx * g.out_bstride;
-    const bool partial = g.ksplit > 1;      // raw partial products go to the workspace; a second kernel finishes
-    if (partial) {
-        addend = nullptr; addend2 = nullptr;
-        out = g.partial + (((size_t)split * g.nparty + party) * g.batch + bidx) * g.out_bstride;
-    }
-    const int rbase = m0 + wm * 32 + g2 * 4;
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    if (!early_addend) load_addend();
+    // The explicit accumulator reads below are opaque to the compiler's hazard
+    // handling: give the last MFMA (8 passes) time to retire before the first read.
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+
+    // ---- epilogue: recombine, add, truncate, store.
+    static_for<2>([&](auto ct) {
+        constexpr int c = decltype(ct)::value;
         const int col = n0 + wn * 64 + c * 32 + i32;
-        const int colc = col < g.N ? col : g.N - 1;
-        u64 add[16];
-        if (addend) {
+        u64 (&add)[16] = addw[c];
+        if (addend2) {                  // partial sums of a two-phase call: loaded here, all 16 at once
+            const int colc = col < g.N ? col : g.N - 1;
+            u64 more[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = rbase + (v >> 2) * 8 + (v & 3);
                 const int rowc = row < g.M ? row : g.M - 1;
-                add[v] = addend[(size_t)rowc * g.N + colc];
+                more[v] = addend2[(size_t)rowc * g.N + colc];
             }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) add[v] += more[v];
+        }
+        // The accumulators are read out explicitly (left to itself the compiler copies all
+        // 256 accumulator registers into vector registers at the loop exit, which leaves no
+        // room for anything else to stay live across the main loop); the two column halves
+        // are fenced from each other, inside a half the 16 words are independent chains.
+        // Local truncation without a branch: party 1 negates before and after the shift.
+        u64 z[16];
+        static_for<16>([&](auto vt) {
+            constexpr int v = decltype(vt)::value;
+            u64 acc64 = 0;
+            static_for<8>([&](auto st) {
+                constexpr int sg = 7 - decltype(st)::value;
+                int d;
+                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(d) : "a"(acc[c][sg][v]));
+                acc64 = (acc64 << 8) + (u64)(long long)d;
+            });
+            acc64 += add[v];
+            acc64 = (acc64 ^ neg) - neg;
+            acc64 >>= shift;
+            z[v] = (acc64 ^ neg) - neg;
+        });
+        if (interior) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) out[(size_t)(rbase + (v >> 2) * 8 + (v & 3)) * g.N + col] = z[v];
         } else {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) add[v] = 0;
-        }
-        if (addend2) {
-#pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = rbase + (v >> 2) * 8 + (v & 3);
-                const int rowc = row < g.M ? row : g.M - 1;
-                add[v] += addend2[(size_t)rowc * g.N + colc];
+                if (row < g.M && col < g.N) out[(size_t)row * g.N + col] = z[v];
             }
         }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = rbase + (v >> 2) * 8 + (v & 3);
-            u64 z = 0;
-#pragma unroll
-            for (int s = 7; s >= 0; --s) z = (z << 8) + (u64)(long long)acc[c][s][v];
-            z += add[v];
-            if (g.trunc_bits && !partial) z = party == 0 ? (z >> g.trunc_bits) : (u64)0 - (((u64)0 - z) >> g.trunc_bits);
-            if (row < g.M && col < g.N) out[(size_t)row * g.N + col] = z;
-        }
-    }
+        __builtin_amdgcn_sched_barrier(0);
+    });
 }
 
 // Second pass of a split contraction: out = sum over splits of the partial
