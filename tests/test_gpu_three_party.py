@@ -207,3 +207,38 @@ def test_three_party_argument_errors(mpc, lane):
     with pytest.raises(mpc.MpcError):
         lane.truncate3(z, dev3(mpc, r), dev3(mpc, rt), bits=63)
     lane.sync()
+
+
+def test_three_party_layer_as_a_recorded_graph(mpc):
+    """The three-party layer (matmul, rescale, ReLU) recorded once on a single-queue lane and replayed on
+    fresh inputs in the same buffers, with eager three-party work between the replays: every replay equals the oracle."""
+    import torch
+    lane = mpc.Lane(0); lane.use_single_queue()
+    M, K, N = 48, 200, 72
+    rng = np.random.default_rng(390)
+    deals = [deal_matmul3(rng, (M, K), (K, N), 1.0, 0.1, oracle.ring_matmul) for _ in range(3)]
+    r, rt = synth.deal_trunc3_pair(rng, (M, N))
+    mat = synth.deal_relu3_material(rng, M * N)
+    md, rd, rtd = mpc.material_to_device(mat), dev3(mpc, r), dev3(mpc, rt)
+    buf = {k: dev3(mpc, deals[0][k]) for k in "xyabc"}
+    z = tuple(torch.empty_like(buf["c"][0]) for _ in range(3))
+    y = tuple(torch.empty_like(buf["c"][0]) for _ in range(3))
+
+    def layer():
+        lane.beaver_matmul3(buf["x"], buf["y"], buf["a"], buf["b"], buf["c"], out=z)
+        lane.truncate3(z, rd, rtd)
+        lane.relu3(z, md, out=y)
+    layer(); lane.sync()
+    with lane.capture() as cap:
+        layer()
+    for d in deals:
+        for k in buf:
+            for i in range(3):
+                buf[k][i].copy_(mpc.to_device(d[k][i]))
+        torch.cuda.synchronize()
+        cap.graph.launch(lane)
+        want = oracle.relu3(oracle.truncate3(oracle.beaver_matmul3(*[d[k] for k in "xyabc"]), r, rt), mat).y
+        assert_shares_equal(host3(mpc, lane, y), want, "graph replay, three parties")
+        other = lane.relu3(dev3(mpc, d["c"]), md)                       # eager work on the same workspace
+        assert_shares_equal(host3(mpc, lane, other), oracle.relu3(d["c"], mat).y, "eager between replays")
+    cap.graph.close(); lane.close()
