@@ -47,9 +47,11 @@ _lib = None
 
 
 def lib():
+    """The compiled oracle.  MPC_ORACLE_LIB names another build of mpc_oracle.c to load instead: the
+    mutation test points it at copies with a planted mistake, to show that the pins notice."""
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        _lib = ctypes.CDLL(os.environ.get("MPC_ORACLE_LIB") or build())
     return _lib
 
 
