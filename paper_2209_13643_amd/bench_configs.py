@@ -504,10 +504,38 @@ def bench_pipeline3(n_mb: int = 4, micro_batch: int = 32, reps: int = 3):
     return res
 
 
+def bench_hbm_copy(reps: int = 20):
+    """Attainable streaming rate of this device: a plain device-to-device copy (torch's copy kernel) at
+    footprints inside and far beyond the 256 MB last-level cache.  Context for the HBM fractions of the
+    ReLU chains, which are quoted against the nominal 8 TB/s."""
+    dev = torch.device("cuda", 0)
+    rows = []
+    for mib in (32, 128, 512, 2048):
+        n = mib * (1 << 20) // 8
+        src = torch.ones(n, dtype=torch.int64, device=dev); dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            dst.copy_(src)
+        e1.record(); torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        rows.append((mib, ms, 2 * n * 8 / (ms * 1e-3) / 1e12))
+        del src, dst
+    return rows
+
+
 def main(argv):
     if argv and argv[0] == "sweep":
         print("== tile-count sweep, secure ReLU on 2097152 elements")
         sweep_tiles()
+        return
+    if argv and argv[0] == "hbm":
+        print("== device-to-device copy (read + write counted), repeated on the same buffers")
+        for mib, ms, tbs in bench_hbm_copy():
+            print(f"  {mib:5d} MiB source + {mib:5d} MiB destination: {ms * 1e3:8.1f} us  {tbs:5.2f} TB/s = {100 * tbs / 8.0:4.1f}% of 8 TB/s", flush=True)
         return
     if argv and argv[0] == "parties3":
         r = bench_three_parties()
