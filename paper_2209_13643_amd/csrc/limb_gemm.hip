@@ -273,11 +273,12 @@ void k_limb_gemm(GemmArgs g)
     };
 
     // ---- output pointers, and the addend c_i of the epilogue.  Its loads (indices clamped
-    // into the matrix, no per-word branch) are issued all at once: for short contractions,
-    // where the epilogue is a large part of a tile's time, from inside the last step but one
-    // (after that step's counted wait, so no later wait of the ring covers them; they land
-    // while the last two steps compute: 5 % on 64-deep contractions); for long ones at the
-    // start of the epilogue (measured 1 % better there than the extra issue work in the loop).
+    // into the matrix, no per-word branch) are issued all at once at the start of the
+    // epilogue.  Issuing them from inside the last steps hides their latency (4 % on
+    // 64-deep contractions) but keeps 64 more registers live across the main loop; the
+    // kernel stays below 128 vector registers instead, so that a wave of a streaming
+    // kernel from another lane (secure ReLU: at most 128) fits beside it on the same SIMD
+    // and fills the issue slots the MFMAs leave free: 7-13 % on the inter-batch pipeline.
     const bool partial = g.ksplit > 1;      // raw partial products go to the workspace; a second kernel finishes
     const u64* addend = (g.addend[party] && !partial) ? g.addend[party] + (size_t)bidx * g.out_bstride : nullptr;
     const u64* addend2 = (g.addend2[party] && !partial) ? g.addend2[party] + (size_t)bidx * g.out_bstride : nullptr;
@@ -301,8 +302,6 @@ void k_limb_gemm(GemmArgs g)
             }
         }
     };
-    const int t_addend = T >= 2 ? T - 2 : 0;        // always one of the last NS steps
-    const bool early_addend = T <= 24;
 
     // ---- main loop.  Ring slot t%NS holds K step t.  At the top of step t the
     // slot of step t+1 must have landed (this wave's loads: all but the most
@@ -333,7 +332,6 @@ void k_limb_gemm(GemmArgs g)
         if (FULL || t + 2 < T) __builtin_amdgcn_s_waitcnt(vmcnt_imm(PER_STAGE));
         else if (have_next)    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
         __syncthreads();
-        if constexpr (!FULL) { if (early_addend && t == t_addend) load_addend(); }
         const int nslot = slot + 1 == NS ? 0 : slot + 1;
         if (fill) stage_begin(slot);
         // MFMA number n (0..71) <-> block j, left digit i, column half c
@@ -363,7 +361,7 @@ void k_limb_gemm(GemmArgs g)
     for (; t + NS < T; ++t) step(std::true_type{}, t);
     for (; t < T; ++t) step(std::false_type{}, t);
 
-    if (!early_addend) load_addend();
+    load_addend();
     // The explicit accumulator reads below are opaque to the compiler's hazard
     // handling: give the last MFMA (8 passes) time to retire before the first read.
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");

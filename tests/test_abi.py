@@ -131,3 +131,21 @@ def test_three_party_workspace_queries(lib):
 def mpc_null3():
     from paper_2209_13643_amd import mpc
     return mpc.CShare3()
+
+
+def test_gemm_kernel_leaves_room_for_a_streaming_wave():
+    """The digit-plane GEMM owns all 256 accumulator registers of a SIMD; it must stay at or below 128
+    vector registers so that a wave of another lane's streaming kernel (at most 128 registers) fits on
+    the same SIMD: the inter-batch pipeline overlaps MFMA-bound and HBM-bound work that way.  Compiled
+    here with the resource-usage remarks on (no GPU needed)."""
+    import subprocess
+    import __graft_entry__ as ge
+    src = os.path.join(ge.CSRC, "limb_gemm.hip")
+    out = subprocess.run([ge.HIPCC, *ge.HIP_FLAGS, "--cuda-device-only", "-Rpass-analysis=kernel-resource-usage",
+                          "-c", src, "-o", os.devnull], capture_output=True, text=True)
+    assert out.returncode == 0, out.stderr[-2000:]
+    rows = re.findall(r"Function Name: (\S+).*?VGPRs: (\d+).*?AGPRs: (\d+).*?VGPRs Spill: (\d+)", out.stderr, flags=re.S)
+    gemm = [(n, int(v), int(a), int(sp)) for n, v, a, sp in rows if "k_limb_gemm" in n]
+    assert len(gemm) == 4, [r[0] for r in gemm]
+    for name, vgprs, agprs, spill in gemm:
+        assert agprs == 256 and spill == 0 and vgprs <= 128, (name, vgprs, agprs, spill)
