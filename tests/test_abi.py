@@ -134,10 +134,11 @@ def mpc_null3():
 
 
 def test_gemm_kernel_leaves_room_for_a_streaming_wave():
-    """The digit-plane GEMM owns all 256 accumulator registers of a SIMD; it must stay at or below 128
-    vector registers so that a wave of another lane's streaming kernel (at most 128 registers) fits on
-    the same SIMD: the inter-batch pipeline overlaps MFMA-bound and HBM-bound work that way.  Compiled
-    here with the resource-usage remarks on (no GPU needed)."""
+    """The digit-plane GEMM owns all 256 accumulator registers of a SIMD; it must stay at or below 120
+    vector registers, so that 136 of the SIMD's 512 remain and a wave of another lane's streaming
+    kernel (the secure-ReLU stages use up to 134) fits beside it: the inter-batch pipeline overlaps
+    MFMA-bound and HBM-bound work that way.  Compiled here with the resource-usage remarks on (no GPU
+    needed)."""
     import subprocess
     import __graft_entry__ as ge
     src = os.path.join(ge.CSRC, "limb_gemm.hip")
@@ -148,4 +149,18 @@ def test_gemm_kernel_leaves_room_for_a_streaming_wave():
     gemm = [(n, int(v), int(a), int(sp)) for n, v, a, sp in rows if "k_limb_gemm" in n]
     assert len(gemm) == 4, [r[0] for r in gemm]
     for name, vgprs, agprs, spill in gemm:
-        assert agprs == 256 and spill == 0 and vgprs <= 128, (name, vgprs, agprs, spill)
+        assert agprs == 256 and spill == 0 and vgprs <= 120, (name, vgprs, agprs, spill)
+
+
+def test_relu_stage_kernels_fit_beside_the_gemm():
+    """... and the other half of that budget: every secure-ReLU stage kernel stays within 136 vector registers."""
+    import subprocess
+    import __graft_entry__ as ge
+    out = subprocess.run([ge.HIPCC, *ge.HIP_FLAGS, "--cuda-device-only", "-Rpass-analysis=kernel-resource-usage",
+                          "-c", os.path.join(ge.CSRC, "relu.hip"), "-o", os.devnull], capture_output=True, text=True)
+    assert out.returncode == 0, out.stderr[-2000:]
+    rows = re.findall(r"Function Name: (\S+).*?VGPRs: (\d+).*?AGPRs: (\d+)", out.stderr, flags=re.S)
+    stages = [(n, int(v) + int(a)) for n, v, a in rows if "k_relu_stage" in n or "k_relu_msb_stage" in n]
+    assert len(stages) > 50
+    worst = max(stages, key=lambda r: r[1])
+    assert worst[1] <= 136, worst
