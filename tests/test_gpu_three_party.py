@@ -242,3 +242,41 @@ def test_three_party_layer_as_a_recorded_graph(mpc):
         other = lane.relu3(dev3(mpc, d["c"]), md)                       # eager work on the same workspace
         assert_shares_equal(host3(mpc, lane, other), oracle.relu3(d["c"], mat).y, "eager between replays")
     cap.graph.close(); lane.close()
+
+
+def test_word_aligned_but_not_16_byte_aligned_buffers(mpc, lane):
+    """Shares that start one word into an allocation (8-byte, not 16-byte aligned): every kernel has to
+    fall back from its 16-byte accesses.  Two- and three-party layer against the oracle."""
+    import torch
+    from helpers import deal_matmul, oracle_matmul
+
+    def shifted(arr):
+        flat = mpc.to_device(np.ascontiguousarray(arr).ravel())
+        buf = torch.empty(flat.numel() + 1, dtype=flat.dtype, device=flat.device)
+        view = buf[1:]
+        view.copy_(flat)
+        assert view.data_ptr() % 16 == 8 or flat.dtype == torch.uint8
+        return view.view(np.shape(arr))
+
+    rng = np.random.default_rng(395)
+    M, K, N = 34, 70, 18
+    d = deal_matmul(rng, M, K, N, x_std=1.0, w_std=0.1)
+    mat = synth.deal_relu_material(rng, M * N)
+    sh2 = lambda pair: tuple(shifted(v) for v in pair)
+    z = lane.beaver_matmul(*[sh2(d[k]) for k in "xyabc"], out=sh2((np.zeros((M, N), dtype=U64),) * 2))
+    y = lane.relu(z, {k: sh2(v) for k, v in mat.items()}, out=sh2((np.zeros((M, N), dtype=U64),) * 2))
+    lane.sync()
+    want_t = oracle_matmul(d)
+    want_y = oracle.relu(want_t, mat).y
+    for i in range(2):
+        assert np.array_equal(mpc.to_host(z[i]), want_t[i]) and np.array_equal(mpc.to_host(y[i]), want_y[i].reshape(M, N))
+    # three parties
+    d3 = deal_matmul3(rng, (M, K), (K, N), 1.0, 0.1, oracle.ring_matmul)
+    r, rt = synth.deal_trunc3_pair(rng, (M, N))
+    mat3 = synth.deal_relu3_material(rng, M * N)
+    sh3 = lambda tri: tuple(shifted(v) for v in tri)
+    z3 = lane.beaver_matmul3(*[sh3(d3[k]) for k in "xyabc"], out=sh3((np.zeros((M, N), dtype=U64),) * 3))
+    lane.truncate3(z3, sh3(r), sh3(rt))
+    y3 = lane.relu3(z3, {k: sh3(v) for k, v in mat3.items()}, out=sh3((np.zeros((M, N), dtype=U64),) * 3))
+    want3 = oracle.relu3(oracle.truncate3(oracle.beaver_matmul3(*[d3[k] for k in "xyabc"]), r, rt), mat3).y
+    assert_shares_equal(host3(mpc, lane, y3), want3, "three parties, shifted buffers")
