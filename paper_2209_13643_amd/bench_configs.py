@@ -532,6 +532,13 @@ def main(argv):
         print("== tile-count sweep, secure ReLU on 2097152 elements")
         sweep_tiles()
         return
+    if argv and argv[0] == "pipeline":
+        # config 4's inter-batch pipeline alone (sign-only packed ReLU, prepared planes): the run a kernel trace is taken of
+        p = bench_pipeline(packed_relu=True, prepared=True)
+        print(f"  inter-batch pipeline, batch 128 = 4 x 32, sign-only packed ReLU, prepared planes: "
+              f"serial {p['serial']['ms']:.2f} ms ({p['serial']['images_per_s']:.0f} img/s), "
+              f"pipelined {p['pipelined']['ms']:.2f} ms ({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)
+        return
     if argv and argv[0] == "hbm":
         print("== device-to-device copy (read + write counted), repeated on the same buffers")
         for mib, ms, tbs in bench_hbm_copy():

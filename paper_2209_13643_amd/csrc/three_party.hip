@@ -64,7 +64,7 @@ struct Relu3Party {
     u64* recv[2];                        // [4][n] the same from party+1 / party+2
     u8* vsend; u8* vrecv[2];             // B2A round (one byte per element)
 };
-struct Relu3Args { Relu3Party p[3]; size_t n; };
+struct Relu3Args { Relu3Party p[3]; size_t n; size_t tn; };   // n: elements of this call or chunk; tn: row stride of the [13][tn] triples
 
 // Words are processed one per thread, or two per thread with 16-byte accesses
 // when the element count is even and every array is 16-byte aligned.
@@ -102,9 +102,11 @@ __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
     const size_t n = q.n;                                    // words per row
     const size_t units = n / (sizeof(T) / sizeof(u64));
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    // row r of a [rows][n] word array, as units
+    // row r of a [rows][n] workspace array / of a [13][tn] triple array, as units
+    const size_t tn = q.tn;
     auto in = [n](const u64* base, int r) { return reinterpret_cast<const T*>(base + (size_t)r * n); };
     auto out = [n](u64* base, int r) { return reinterpret_cast<T*>(base + (size_t)r * n); };
+    auto tr = [tn](const u64* base, int r) { return reinterpret_cast<const T*>(base + (size_t)r * tn); };
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < units; i += stride) {
         // masked words of the previous round, opened
         T o[4] = {};
@@ -120,37 +122,37 @@ __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
             const T V = party == 1 ? own : party == 2 ? w2 : w1;
             const T W = party == 2 ? own : party == 0 ? w2 : w1;
             out(p.S, 0)[i] = U ^ V ^ W; out(p.Wd, 0)[i] = W;
-            out(p.send, 0)[i] = (U ^ W) ^ in(p.ta, 0)[i];
-            out(p.send, 1)[i] = (V ^ W) ^ in(p.tb, 0)[i];
+            out(p.send, 0)[i] = (U ^ W) ^ tr(p.ta, 0)[i];
+            out(p.send, 1)[i] = (V ^ W) ^ tr(p.tb, 0)[i];
         } else if constexpr (STAGE == 1) {
-            const T Tm = and_finish<T>(party, o[0], o[1], in(p.ta, 0)[i], in(p.tb, 0)[i], in(p.tc, 0)[i]);
+            const T Tm = and_finish<T>(party, o[0], o[1], tr(p.ta, 0)[i], tr(p.tb, 0)[i], tr(p.tc, 0)[i]);
             const T S = in(p.S, 0)[i];
             const T K = (Tm ^ in(p.Wd, 0)[i]) << 1;
             const T P = S ^ K;
             out(p.P, 0)[i] = P; reinterpret_cast<B*>(p.p63)[i] = to_bytes(P >> 63);
-            out(p.send, 0)[i] = S ^ in(p.ta, 1)[i];
-            out(p.send, 1)[i] = K ^ in(p.tb, 1)[i];
+            out(p.send, 0)[i] = S ^ tr(p.ta, 1)[i];
+            out(p.send, 1)[i] = K ^ tr(p.tb, 1)[i];
         } else if constexpr (STAGE == 2) {
-            const T G = and_finish<T>(party, o[0], o[1], in(p.ta, 1)[i], in(p.tb, 1)[i], in(p.tc, 1)[i]);
+            const T G = and_finish<T>(party, o[0], o[1], tr(p.ta, 1)[i], tr(p.tb, 1)[i], tr(p.tc, 1)[i]);
             const T P = in(p.P, 0)[i];
             out(p.G, 0)[i] = G;
-            out(p.send, 0)[i] = P ^ in(p.ta, 2)[i];  out(p.send, 1)[i] = (G << 1) ^ in(p.tb, 2)[i];
-            out(p.send, 2)[i] = P ^ in(p.ta, 3)[i];  out(p.send, 3)[i] = (P << 1) ^ in(p.tb, 3)[i];
+            out(p.send, 0)[i] = P ^ tr(p.ta, 2)[i];  out(p.send, 1)[i] = (G << 1) ^ tr(p.tb, 2)[i];
+            out(p.send, 2)[i] = P ^ tr(p.ta, 3)[i];  out(p.send, 3)[i] = (P << 1) ^ tr(p.tb, 3)[i];
         } else if constexpr (STAGE >= 3 && STAGE <= 7) {
             constexpr int L = STAGE - 3;                 // level being finished
             constexpr int tg = 2 + 2 * L, tp = 3 + 2 * L;
-            const T T1 = and_finish<T>(party, o[0], o[1], in(p.ta, tg)[i], in(p.tb, tg)[i], in(p.tc, tg)[i]);
-            const T P = and_finish<T>(party, o[2], o[3], in(p.ta, tp)[i], in(p.tb, tp)[i], in(p.tc, tp)[i]);
+            const T T1 = and_finish<T>(party, o[0], o[1], tr(p.ta, tg)[i], tr(p.tb, tg)[i], tr(p.tc, tg)[i]);
+            const T P = and_finish<T>(party, o[2], o[3], tr(p.ta, tp)[i], tr(p.tb, tp)[i], tr(p.tc, tp)[i]);
             const T G = in(p.G, 0)[i] ^ T1;
             out(p.G, 0)[i] = G;
             constexpr int d = 2 << L;                    // shift of level L + 1
             constexpr int ng = tg + 2, np = tp + 2;
-            out(p.send, 0)[i] = P ^ in(p.ta, ng)[i];  out(p.send, 1)[i] = (G << d) ^ in(p.tb, ng)[i];
+            out(p.send, 0)[i] = P ^ tr(p.ta, ng)[i];  out(p.send, 1)[i] = (G << d) ^ tr(p.tb, ng)[i];
             if constexpr (L + 1 < 5) {                   // the last level needs no P update
-                out(p.send, 2)[i] = P ^ in(p.ta, np)[i];  out(p.send, 3)[i] = (P << d) ^ in(p.tb, np)[i];
+                out(p.send, 2)[i] = P ^ tr(p.ta, np)[i];  out(p.send, 3)[i] = (P << d) ^ tr(p.tb, np)[i];
             }
         } else if constexpr (STAGE == 8) {
-            const T T1 = and_finish<T>(party, o[0], o[1], in(p.ta, 12)[i], in(p.tb, 12)[i], in(p.tc, 12)[i]);
+            const T T1 = and_finish<T>(party, o[0], o[1], tr(p.ta, 12)[i], tr(p.tb, 12)[i], tr(p.tc, 12)[i]);
             const T G = in(p.G, 0)[i] ^ T1;
             const B s = reinterpret_cast<const B*>(p.p63)[i] ^ to_bytes((G >> 62) & 1);
             if (p.s_bit) reinterpret_cast<B*>(p.s_bit)[i] = s;
@@ -180,7 +182,7 @@ __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
 // 16-byte accesses need an even element count (rows of the [k][n] arrays stay aligned) and aligned arrays
 bool relu3_vectorisable(const Relu3Args& q)
 {
-    if (q.n & 1) return false;
+    if ((q.n | q.tn) & 1) return false;
     uintptr_t w = 0, b = 0;
     for (int i = 0; i < 3; ++i) {
         const Relu3Party& p = q.p[i];
@@ -248,11 +250,11 @@ void fill3(Relu3Args& q, const u64* const x[3], const mpc_relu3_material* m, u64
         p.y = y[i];
         p.s_bit = s_bit ? s_bit[i] : nullptr; p.s_arith = s_arith ? s_arith[i] : nullptr;
     }
-    q.n = n;
+    q.n = n; q.tn = n;
 }
 
-// The whole chain on one stream: A2B distribution, 11 stage kernels, 10 word exchanges, one byte exchange.
-int relu3_run(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
+// The whole chain for one chunk on one stream: A2B distribution, 11 stage kernels, 10 word exchanges, one byte exchange.
+int relu3_chunk(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
 {
     const size_t n = q.n;
     const bool vec = relu3_vectorisable(q);
@@ -284,6 +286,39 @@ int relu3_run(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
     }
     MPC_TRY(launch_stage<9>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
     MPC_TRY(launch_stage<10>(c, st, q, vec));
+    return MPC_OK;
+}
+
+// Chunks of about 2^19 elements: the exchanged words and the carried state of a chunk (about 0.35 GB
+// for the three parties) then stay close to the last-level cache from stage to stage, and only the
+// offline material streams from DRAM.  Chunk boundaries are even, so 16-byte accesses stay possible.
+constexpr size_t kChunk3 = (size_t)1 << 19;
+inline int relu3_chunks(size_t n) { return n <= kChunk3 + kChunk3 / 2 ? 1 : (int)((n + kChunk3 - 1) / kChunk3); }
+inline size_t relu3_chunk_cap(size_t n)          // largest chunk of relu3_run's split
+{
+    const int k = relu3_chunks(n);
+    return k == 1 ? n : ((n + k - 1) / k + 1) & ~(size_t)1;
+}
+
+// q: caller arrays of the whole call (q.n = q.tn = n), workspace carved for relu3_chunk_cap(n) elements.
+int relu3_run(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
+{
+    const size_t n = q.n;
+    const int k = relu3_chunks(n);
+    if (k == 1) return relu3_chunk(c, st, q);
+    const size_t cap = relu3_chunk_cap(n);
+    for (size_t lo = 0; lo < n; lo += cap) {
+        Relu3Args ch = q;
+        ch.n = n - lo < cap ? n - lo : cap;
+        for (int i = 0; i < 3; ++i) {
+            Relu3Party& p = ch.p[i];
+            p.x += lo; p.r0 += lo; p.r1 += lo; p.ta += lo; p.tb += lo; p.tc += lo;
+            p.rb += lo; p.ra += lo; p.ma += lo; p.mb += lo; p.mc += lo; p.y += lo;
+            if (p.s_bit) p.s_bit += lo;
+            if (p.s_arith) p.s_arith += lo;
+        }
+        MPC_TRY(relu3_chunk(c, st, ch));
+    }
     return MPC_OK;
 }
 
@@ -378,7 +413,7 @@ size_t mpc_relu3_workspace_bytes(size_t n)
 {
     if (n == 0) return 0;
     Relu3Args q{};
-    return relu3_ws(nullptr, 0, n, &q, nullptr);
+    return relu3_ws(nullptr, 0, relu3_chunk_cap(n), &q, nullptr);
 }
 
 int mpc_relu3(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* m, mpc_share3 y, size_t n,
@@ -390,7 +425,7 @@ int mpc_relu3(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* m, mpc_share3
     for (int i = 0; i < 3; ++i) if (!x.p[i] || !y.p[i]) return MPC_EINVAL;
     Relu3Args q{};
     bool ok = false;
-    relu3_ws(c->ws, c->ws_bytes, n, &q, &ok);
+    relu3_ws(c->ws, c->ws_bytes, relu3_chunk_cap(n), &q, &ok);
     if (!ok) return MPC_ENOMEM;
     fill3(q, x.p, m, y.p, s_bit, s_arith, n);
     hipStream_t st = c->s[0];
@@ -429,8 +464,8 @@ int mpc_maxpool3(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* mat1, cons
     if (!wa.ok) return MPC_ENOMEM;
     Relu3Args q1{}, q2{};
     bool ok1 = false, ok2 = false;
-    relu3_ws(c->ws + wa.off, c->ws_bytes - wa.off, 2 * n_out, &q1, &ok1);
-    relu3_ws(c->ws + wa.off, c->ws_bytes - wa.off, n_out, &q2, &ok2);      // the second conversion reuses the scratch
+    relu3_ws(c->ws + wa.off, c->ws_bytes - wa.off, relu3_chunk_cap(2 * n_out), &q1, &ok1);
+    relu3_ws(c->ws + wa.off, c->ws_bytes - wa.off, relu3_chunk_cap(n_out), &q2, &ok2);      // the second conversion reuses the scratch
     if (!ok1 || !ok2) return MPC_ENOMEM;
     fill3(q1, pq.d1, mat1, r1, nullptr, nullptr, 2 * n_out);
     fill3(q2, pq.d2, mat2, y.p, nullptr, nullptr, n_out);
