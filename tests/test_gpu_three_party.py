@@ -144,6 +144,22 @@ def test_relu3(mpc, lane, n):
     assert np.array_equal(rec3(host3(mpc, lane, y)).view(np.int64), np.maximum(X.view(np.int64), 0))
 
 
+@pytest.mark.parametrize("n", [786434, 786435, 1100000])
+def test_relu3_in_several_chunks(mpc, n):
+    """Above about 3/4 M elements the chain runs chunk by chunk: even and odd totals, ragged last chunk."""
+    lane = mpc.Lane(0); lane.use_single_queue()
+    rng = np.random.default_rng(n)
+    X = synth.normal_fixed(rng, n, 4.0)
+    x = synth.share_additive3(rng, X)
+    mat = synth.deal_relu3_material(rng, n)
+    want = oracle.relu3(x, mat)
+    y, sb, sa = lane.relu3(dev3(mpc, x), mpc.material_to_device(mat), want_sign=True)
+    assert_shares_equal(host3(mpc, lane, y), want.y, "relu3 y")
+    assert_shares_equal(host3(mpc, lane, sb), want.s_bit, "relu3 s_bit")
+    assert_shares_equal(host3(mpc, lane, sa), want.s_arith, "relu3 s_arith")
+    lane.close()
+
+
 def test_relu3_uniform_words_and_carry_patterns(mpc, lane):
     """Uniform 64-bit values and inputs whose sum ripples a carry through every level."""
     rng = np.random.default_rng(360)
