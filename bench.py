@@ -42,6 +42,7 @@ RELU_MSB_BYTES_PER_ELEMENT = (31.71875 + 71.25 + 41.5625) * 8 + 16
 
 
 RELU3_BYTES_PER_ELEMENT = 966 * 8 + 33      # three parties: 141 W + 3 B, 606 W + 21 B, 219 W + 9 B (same three classes)
+RELU3_MSB_BYTES_PER_ELEMENT = 2961          # three parties, sign-only chain: 59.6 W + 3 B, 226.0 W + 21 B, 80.3 W + 9 B
 
 
 def three_party_leg(lane, L, steps, warmup):
@@ -87,12 +88,27 @@ def three_party_leg(lane, L, steps, warmup):
                                      (d["W"].double() / 65536).permute(3, 2, 0, 1), padding=L.pad, stride=L.stride)
     err = (rt[:2].double() / 65536 - ref.permute(0, 2, 3, 1)).abs().max().item()
     assert err <= 2.0 ** -12, f"three-party decoded conv output off by {err}"
+    # the same ReLU on the sign's carry chain only (packed material)
+    del mat
+    matp = dealer.relu3_material(g, n, dev, packed=True)
+    y2 = tuple(torch.empty_like(v) for v in y)
+    for _ in range(warmup):
+        lane.relu3(z, matp, out=y2, packed=True)
+    lane.sync(); lane.set_profiling(True); lane.profile_reset()
+    for _ in range(steps):
+        lane.relu3(z, matp, out=y2, packed=True)
+    lane.sync(); lane.set_profiling(False)
+    msb = statistics.median(lane.profile_samples(mpc.PROF_RELU))
+    assert torch.equal(y2[0] + y2[1] + y2[2], ry), "three-party sign-only ReLU reconstructs differently"
     macs = M * K * N
     return {"parties": 3, "ms_beaver_conv_call": lin, "value": macs / (lin * 1e-3), "unit": "secure MACs/s",
             "ms_gemm_kernels": gemm, "gemm_frac_of_int8_peak": 432 * macs / (gemm * 1e-3) / 1e12 / INT8_PEAK_TOPS,
             "ms_relu_call": relu, "relu_value": n / (relu * 1e-3),
             "relu_bytes_per_element": RELU3_BYTES_PER_ELEMENT,
             "relu_frac_of_hbm_peak": RELU3_BYTES_PER_ELEMENT * n / (relu * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "ms_relu_msb_call": msb, "relu_msb_value": n / (msb * 1e-3),
+            "relu_msb_bytes_per_element": RELU3_MSB_BYTES_PER_ELEMENT,
+            "relu_msb_frac_of_hbm_peak": RELU3_MSB_BYTES_PER_ELEMENT * n / (msb * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "max_abs_err_vs_float64": err}
 
 

@@ -489,6 +489,31 @@ int mpc_maxpool3(mpc_ctx* ctx, mpc_cshare3 x, const mpc_relu3_material* mat1,
                  const mpc_relu3_material* mat2, mpc_share3 y,
                  int B, int H, int W, int C);
 
+/* The three-party ReLU on the sign's carry chain only (Sec. 4.2), as
+ * mpc_relu_msb is to mpc_relu: the carry-save step and G = S & K stay on whole
+ * words, the six prefix levels keep the positions bit 63 depends on, packed
+ * 2^(l+1) elements to a word at level l (the layout mpc_relu_msb documents).
+ * Every output (y, s_bit, s_arith) is the same word as mpc_relu3 returns for
+ * the same material.  and_a / and_b / and_c of the material each point to
+ * mpc_relu3_packed_words(n) words, 16-byte aligned:
+ *   triples 0 and 1: n plain words each, padded to a multiple of 4;
+ *   triple t = 2..12 (level l = (t-2)/2): ceil64(n) / 2^(l+1) packed words,
+ *   padded to a multiple of 4; segments follow one another in triple order.
+ * mpc_relu3_pack_triples converts one [13][n] array per party into this
+ * layout on the device (offline helper, no workspace).  One pass, no chunks.
+ * Errors: MPC_EINVAL for null or misaligned packed arrays, MPC_ENOMEM for a
+ * workspace below mpc_relu3_msb_workspace_bytes(n). */
+size_t mpc_relu3_packed_words(size_t n);
+int mpc_relu3_pack_triples(mpc_ctx* ctx, mpc_cshare3 words, mpc_share3 packed, size_t n);
+size_t mpc_relu3_msb_workspace_bytes(size_t n);
+int mpc_relu3_msb(mpc_ctx* ctx, mpc_cshare3 x, const mpc_relu3_material* mat, mpc_share3 y,
+                  size_t n, uint8_t* const s_bit[3], uint64_t* const s_arith[3]);
+/* mpc_maxpool3 with both conversions on the packed chain (packed material). */
+size_t mpc_maxpool3_msb_workspace_bytes(int B, int H, int W, int C);
+int mpc_maxpool3_msb(mpc_ctx* ctx, mpc_cshare3 x, const mpc_relu3_material* mat1,
+                     const mpc_relu3_material* mat2, mpc_share3 y,
+                     int B, int H, int W, int C);
+
 /* -------------------------------------------------- dealer helper (offline) */
 
 /* Plain ring product Z = L*R mod 2^64 on public device arrays, computed with

@@ -233,11 +233,12 @@ def bench_training(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_r
     return res
 
 
-def bench_graph(reps: int = 50):
+def bench_graph(reps: int = 50, pool_first: bool = False, exchange: str = "copy"):
     """Eager issue vs replay of a captured HIP graph: the tiny secure layer (configs[0]) and one
-    VGG16-CIFAR micro-batch forward (sign-only packed ReLU, prepared planes)."""
+    VGG16-CIFAR micro-batch forward (sign-only packed ReLU, prepared planes).
+    pool_first: pooled layers run as ReLU(maxpool(z)) (same function, fewer conversions)."""
     res = {}
-    lane = mpc.Lane(0); lane.use_single_queue()
+    lane = mpc.Lane(0); lane.use_single_queue(); lane.set_exchange(exchange)
     dev = lane.device
     g = dealer.gen(synth.BASE_SEED + 90, dev)
     L = synth.config_tiny().layers[0]
@@ -265,7 +266,7 @@ def bench_graph(reps: int = 50):
 
     wl = synth.config_vgg16_pipeline(32)
     weights = pipeline.deal_weights(g, wl.layers, dev)
-    states = pipeline.deal_microbatch(lane, g, wl.layers, weights, packed_relu=True)
+    states = pipeline.deal_microbatch(lane, g, wl.layers, weights, packed_relu=True, pool_first=pool_first)
     pipeline.prepare_layers(lane, wl.layers, states)
     x = dealer.share(g, dealer.normal_fixed(g, (32, 32, 32, 3), 1.0, dev))
     torch.cuda.synchronize()
@@ -283,8 +284,8 @@ def bench_graph(reps: int = 50):
     lanes = [lane] + [mpc.Lane(0) for _ in range(3)]
     graphs, pins = [cap2.graph], [kept]
     for ln in lanes[1:]:
-        ln.use_single_queue()
-        st = pipeline.deal_microbatch(ln, g, wl.layers, weights, packed_relu=True)
+        ln.use_single_queue(); ln.set_exchange(exchange)
+        st = pipeline.deal_microbatch(ln, g, wl.layers, weights, packed_relu=True, pool_first=pool_first)
         pipeline.prepare_layers(ln, wl.layers, st)
         xm = dealer.share(g, dealer.normal_fixed(g, (32, 32, 32, 3), 1.0, dev))
         torch.cuda.synchronize()
@@ -311,19 +312,20 @@ def bench_graph(reps: int = 50):
     return res
 
 
-def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = False, prepared: bool = False):
+def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = False, prepared: bool = False,
+                   pool_first: bool = False, exchange: str = "copy"):
     """Config 4: serial (one lane, micro-batches one after the other) vs pipelined (one lane each)."""
     wl = synth.config_vgg16_pipeline(micro_batch)
     layers = wl.layers
     lanes = [mpc.Lane(0) for _ in range(n_mb)]
     for ln in lanes:
-        ln.use_single_queue()
+        ln.use_single_queue(); ln.set_exchange(exchange)
     dev = lanes[0].device
     g = dealer.gen(synth.BASE_SEED + wl.index, dev)
     weights = pipeline.deal_weights(g, layers, dev)
     states, xs = [], []
     for m in range(n_mb):
-        states.append(pipeline.deal_microbatch(lanes[m], g, layers, weights, packed_relu=packed_relu))
+        states.append(pipeline.deal_microbatch(lanes[m], g, layers, weights, packed_relu=packed_relu, pool_first=pool_first))
         X = dealer.normal_fixed(g, (micro_batch, 32, 32, 3), 1.0, dev)
         xs.append(dealer.share(g, X))
         torch.cuda.synchronize()
@@ -417,7 +419,13 @@ def bench_three_parties(reps: int = 20):
     141 W + 3 B; openings: 28 words per party broadcast (written once, then per peer copied = read + write,
     and read: 7 traversals) and 2 A2B masks per party to one peer each (3 traversals) = 3 * 202 = 606 W + 21 B;
     carried state per party S, W, P written and read (6), G (12), own masked words read again (28), a and b
-    of every triple read again (26), x again (1) = 3 * 73 = 219 W + 9 B  =>  966 W + 33 B = 7761 B."""
+    of every triple read again (26), x again (1) = 3 * 73 = 219 W + 9 B  =>  966 W + 33 B = 7761 B.
+
+    Sign-only chain (mpc_relu3_msb), same rules.  Per party a triple component is 2 + 2 * 31/32 + 1/64 =
+    3.953 words and the broadcast words are 2 + 2 + 4 * 31/32 + 2/64 + 2 = 9.906: material and I/O
+    8 + 3 * 3.953 = 19.86 W + 1 B; openings 7 * 9.906 + 6 = 75.34 W + 7 B; carried state S, W, P (6), kept G
+    bits (2 * 63/64), own masked words again (9.906), a and b again (7.906), x again (1) = 26.78 W + 3 B
+    =>  3 * 121.98 W + 33 B = 2961 B."""
     wl = synth.CONFIGS[1](); L = wl.layers[0]
     lane = mpc.Lane(0); lane.use_single_queue()
     dev = lane.device
@@ -445,6 +453,14 @@ def bench_three_parties(reps: int = 20):
 
     conv_med, conv_min, gemm_ms = timed(conv, mpc.PROF_LINEAR)
     relu_med, relu_min, _ = timed(lambda: lane.relu3(z, mat, out=y), mpc.PROF_RELU)
+    y_whole = tuple(v.clone() for v in y)
+    del mat
+    matp = dealer.relu3_material(g, n, dev, packed=True)
+    msb_med, msb_min, _ = timed(lambda: lane.relu3(z, matp, out=y, packed=True), mpc.PROF_RELU)
+    lane.sync()
+    # other material, same function: the reconstructed outputs agree
+    assert torch.equal(y[0] + y[1] + y[2], y_whole[0] + y_whole[1] + y_whole[2]), "sign-only chain reconstructs differently"
+    del matp
     # the rescale has no region of its own: wall clock around back-to-back calls
     t = tuple(v.clone() for v in z)
     for _ in range(5):
@@ -456,14 +472,17 @@ def bench_three_parties(reps: int = 20):
     lane.close()
     macs = M * K * N
     relu_bytes = 966 * 8 + 33
+    msb_bytes = 2961
     return dict(gemm=f"{M}x{K}x{N}", conv_ms=conv_med, conv_min_ms=conv_min, gemm_kernels_ms=gemm_ms,
                 secure_macs_per_s=macs / conv_med * 1e3, mfma_frac=432 * macs / (gemm_ms * 1e-3) / 5.0e15,
                 trunc_ms=trunc_ms, relu_n=n, relu_ms=relu_med, relu_min_ms=relu_min,
                 relu_elems_per_s=n / relu_med * 1e3, relu_bytes_per_element=relu_bytes,
-                relu_hbm_frac=relu_bytes * n / (relu_med * 1e-3) / 8.0e12)
+                relu_hbm_frac=relu_bytes * n / (relu_med * 1e-3) / 8.0e12,
+                msb_ms=msb_med, msb_min_ms=msb_min, msb_elems_per_s=n / msb_med * 1e3, msb_bytes_per_element=msb_bytes,
+                msb_hbm_frac=msb_bytes * n / (msb_med * 1e-3) / 8.0e12)
 
 
-def bench_pipeline3(n_mb: int = 4, micro_batch: int = 32, reps: int = 3):
+def bench_pipeline3(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = False):
     """Config 4's network with three parties: serial on one lane vs one lane per micro-batch."""
     wl = synth.config_vgg16_pipeline(micro_batch)
     layers = wl.layers
@@ -475,7 +494,7 @@ def bench_pipeline3(n_mb: int = 4, micro_batch: int = 32, reps: int = 3):
     weights = pipeline.deal_weights3(g, layers, dev)
     states, xs = [], []
     for m in range(n_mb):
-        states.append(pipeline.deal_microbatch3(lanes[m], g, layers, weights))
+        states.append(pipeline.deal_microbatch3(lanes[m], g, layers, weights, packed_relu=packed_relu))
         xs.append(dealer.share3(g, dealer.normal_fixed(g, (micro_batch, 32, 32, 3), 1.0, dev)))
         torch.cuda.synchronize()
         pipeline.preopen_weights3(lanes[m], states[m])
@@ -552,10 +571,13 @@ def main(argv):
         print(f"  masked rescale of {r['relu_n']} words: {r['trunc_ms']:.3f} ms (host clock around back-to-back calls)")
         print(f"  secure ReLU, {r['relu_n']} elements: {r['relu_ms']:.3f} ms (min {r['relu_min_ms']:.3f}), {r['relu_elems_per_s'] / 1e9:.2f} G elems/s; "
               f"{r['relu_bytes_per_element']} B per element -> {100 * r['relu_hbm_frac']:.1f}% of 8 TB/s", flush=True)
-        p = bench_pipeline3()
-        print(f"  VGG16-CIFAR forward with three parties, batch 128 = 4 x 32 (whole-word ReLU, weight masks opened ahead): "
-              f"serial {p['serial']['ms']:.2f} ms ({p['serial']['images_per_s']:.0f} img/s), "
-              f"one lane per micro-batch {p['pipelined']['ms']:.2f} ms ({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)
+        print(f"  the same ReLU on the sign's carry chain only: {r['msb_ms']:.3f} ms (min {r['msb_min_ms']:.3f}), {r['msb_elems_per_s'] / 1e9:.2f} G elems/s; "
+              f"{r['msb_bytes_per_element']} B per element -> {100 * r['msb_hbm_frac']:.1f}% of 8 TB/s", flush=True)
+        for packed in (False, True):
+            p = bench_pipeline3(packed_relu=packed)
+            print(f"  VGG16-CIFAR forward with three parties, batch 128 = 4 x 32 ({'sign-only packed' if packed else 'whole-word'} ReLU, weight masks opened ahead): "
+                  f"serial {p['serial']['ms']:.2f} ms ({p['serial']['images_per_s']:.0f} img/s), "
+                  f"one lane per micro-batch {p['pipelined']['ms']:.2f} ms ({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)
         return
     if argv and argv[0] == "backward":
         for idx in ([int(a) for a in argv[1:]] or [1, 2, 3]):
@@ -593,6 +615,15 @@ def main(argv):
         print(f"  VGG16-CIFAR forward, 32 images (packed ReLU, prepared planes): eager {r['vgg16_eager_ms']:.3f} ms, "
               f"graph replay {r['vgg16_graph_ms']:.3f} ms; batch 128 = 4 x 32 as four recorded graphs on four lanes: "
               f"{r['vgg16_4lanes_graph_ms']:.2f} ms ({128 / r['vgg16_4lanes_graph_ms'] * 1e3:.0f} img/s)", flush=True)
+        for pf, ex in ((False, "put"), (True, "put")):
+            r = bench_graph(pool_first=pf, exchange=ex)
+            print(f"  exchange by remote store{', pooled layers as ReLU(maxpool(z))' if pf else ''}: eager {r['vgg16_eager_ms']:.3f} ms, "
+                  f"graph replay {r['vgg16_graph_ms']:.3f} ms; four recorded graphs on four lanes: "
+                  f"{r['vgg16_4lanes_graph_ms']:.2f} ms ({128 / r['vgg16_4lanes_graph_ms'] * 1e3:.0f} img/s)", flush=True)
+        r = bench_graph(pool_first=True)
+        print(f"  the same with pooled layers as ReLU(maxpool(z)): eager {r['vgg16_eager_ms']:.3f} ms, "
+              f"graph replay {r['vgg16_graph_ms']:.3f} ms; four recorded graphs on four lanes: "
+              f"{r['vgg16_4lanes_graph_ms']:.2f} ms ({128 / r['vgg16_4lanes_graph_ms'] * 1e3:.0f} img/s)", flush=True)
         return
     if argv and argv[0] == "train":
         for packed in (False, True):
@@ -622,10 +653,12 @@ def main(argv):
             print(line, flush=True)
         print(f"  totals: linear calls {tot['lin']:.3f} ms ({tot['prep']:.3f} ms on prepared planes), ReLU {tot['relu']:.3f} ms whole-word / {tot['msb']:.3f} ms sign-only", flush=True)
         if idx == 4:
-            for packed, prepared in ((False, False), (True, False), (True, True)):
-                p = bench_pipeline(packed_relu=packed, prepared=prepared)
+            for packed, prepared, pool_first, ex in ((False, False, False, "copy"), (True, False, False, "copy"), (True, True, False, "copy"),
+                                                     (True, True, True, "copy"), (True, True, True, "put")):
+                p = bench_pipeline(packed_relu=packed, prepared=prepared, pool_first=pool_first, exchange=ex)
                 print(f"  inter-batch pipeline, batch 128 = 4 x 32, {'sign-only packed' if packed else 'whole-word'} ReLU"
-                      f"{', prepared planes' if prepared else ''}: "
+                      f"{', prepared planes' if prepared else ''}{', pooled layers as ReLU(maxpool(z))' if pool_first else ''}"
+                      f"{', exchange by remote store' if ex == 'put' else ''}: "
                       f"serial {p['serial']['ms']:.2f} ms ({p['serial']['images_per_s']:.0f} img/s), "
                       f"pipelined {p['pipelined']['ms']:.2f} ms ({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)
         print(json.dumps({"config": idx, "layers": rows}), file=sys.stderr)

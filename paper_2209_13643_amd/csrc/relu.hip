@@ -24,6 +24,7 @@
 // The triples of the levels arrive packed the same way, and every exchange
 // after G = U & V shrinks by the same factor.  Bit for bit the same shares.
 #include "common.h"
+#include "msb_pack.h"
 
 namespace {
 
@@ -299,38 +300,7 @@ __device__ __forceinline__ void b_select(const ReluParty& p, size_t lo, size_t h
     }
 }
 
-// ---- MSB-only carry chain on packed words -------------------------------------
-// Level l (shift d = 2^l, group s = 2d) needs G', P' only at the positions
-// S_l = { p : p = s-2 (mod s), p <= 62 }.  pack_l puts s consecutive elements in
-// one word: element k contributes rotl(word & mask_l, k).  A level reads its
-// operands from two words of pack_(l-1) (elements 0..d-1 and d..2d-1 of the
-// group; pack_(-1) is the plain word) where S_(l-1) splits into the positions
-// p (kept: sel_mask) and p - d (shifted in: low_mask).
-constexpr u64 rotl_c(u64 x, int k) { k &= 63; return k ? (x << k) | (x >> (64 - k)) : x; }
-constexpr u64 msb_mask(int level)
-{
-    const int s = 2 << level; u64 m = 0;
-    for (int p = s - 2; p < 63; p += s) m |= (u64)1 << p;
-    return m;
-}
-constexpr u64 sel_mask(int level)
-{
-    u64 a = 0;
-    for (int k = 0; k < (1 << level); ++k) a |= rotl_c(msb_mask(level), k);
-    return a;
-}
-constexpr u64 low_mask(int level)
-{
-    u64 b = 0;
-    for (int k = 0; k < (1 << level); ++k) b |= rotl_c(msb_mask(level) >> (1 << level), k);
-    return b;
-}
-template <int K> __device__ __forceinline__ u64 rotl(u64 x)
-{
-    constexpr int k = K & 63;
-    if constexpr (k == 0) return x; else return (x << k) | (x >> (64 - k));
-}
-
+// ---- MSB-only carry chain on packed words (bit geometry: msb_pack.h) -----------
 // Word counts and offsets of the packed arrays for n elements.
 struct MsbGeom {
     size_t n;
@@ -345,10 +315,9 @@ MsbGeom msb_geom(size_t n)
 {
     MsbGeom g{};
     g.n = n;
-    const size_t n64 = (n + 63) / 64 * 64;
     size_t lo = 0, go = 0;
     for (int l = 0; l < 6; ++l) {
-        g.pw[l] = ((n64 >> (l + 1)) + 3) / 4 * 4;
+        g.pw[l] = msb_level_words(n, l);
         g.loff[l] = lo; lo += 4 * g.pw[l];
         g.goff[l] = go; go += g.pw[l];
     }

@@ -5,6 +5,7 @@
 // launches go to the lane's first stream, one launch per step for all three
 // parties (blockIdx.y = party), and every exchange is a copy kernel.
 #include "common.h"
+#include "msb_pack.h"
 
 namespace {
 
@@ -63,6 +64,8 @@ struct Relu3Party {
     u64* send;                           // [4][n] masked words of the current round
     u64* recv[2];                        // [4][n] the same from party+1 / party+2
     u8* vsend; u8* vrecv[2];             // B2A round (one byte per element)
+    // sign-only chain: per level a [4][pw] block of masked packed words, and the G bits a level keeps
+    u64* sendL; u64* recvL[2]; u64* gsel;
 };
 struct Relu3Args { Relu3Party p[3]; size_t n; size_t tn; };   // n: elements of this call or chunk; tn: row stride of the [13][tn] triples
 
@@ -195,6 +198,178 @@ bool relu3_vectorisable(const Relu3Args& q)
     return (w & 15) == 0 && (b & 1) == 0;
 }
 
+// ---- the sign-only chain (mpc_relu3_msb) ---------------------------------------------
+// Stages 0 and 1 (carry-save step, P and the operands of G = S & K) run on whole words as
+// above.  From there the Kogge-Stone levels keep only the positions bit 63 depends on
+// (msb_pack.h): level l works on n / 2^(l+1) packed words, its triples arrive packed the
+// same way, and the exchanges shrink by the same factor.  Triple layout of one party's
+// and_a / and_b / and_c: rows 0 and 1 (majority, G) whole words, padded to a multiple of
+// four; then triples 2 .. 12 packed for their level.
+struct Msb3Geom {
+    size_t n;
+    size_t pw[6];       // words of level l's packed arrays
+    size_t toff[13];    // offset of triple t inside a packed and_a / and_b / and_c buffer
+    size_t loff[6];     // offset of level l's [4][pw] block inside sendL / recvL
+    size_t goff[6];     // offset of level l's words inside gsel
+    size_t words_triples, words_blocks, words_gsel;
+};
+
+Msb3Geom msb3_geom(size_t n)
+{
+    Msb3Geom g{};
+    g.n = n;
+    size_t lo = 0, go = 0;
+    for (int l = 0; l < 6; ++l) {
+        g.pw[l] = msb_level_words(n, l);
+        g.loff[l] = lo; lo += 4 * g.pw[l];
+        g.goff[l] = go; go += g.pw[l];
+    }
+    const size_t n4 = (n + 3) / 4 * 4;
+    g.toff[0] = 0; g.toff[1] = n4;
+    size_t to = 2 * n4;
+    for (int t = 2; t < 13; ++t) { g.toff[t] = to; to += g.pw[(t - 2) / 2]; }
+    g.words_triples = to; g.words_blocks = lo; g.words_gsel = go;
+    return g;
+}
+
+struct W4 { u64 v[4]; };
+// four consecutive words: two 16-byte loads when `vec`, else one by one with words past `n` read as zero
+__device__ __forceinline__ W4 ld4(const u64* p, size_t i, size_t n, bool vec)
+{
+    W4 r;
+    if (vec) {
+        const u64v2 a = *reinterpret_cast<const u64v2*>(p + i), b = *reinterpret_cast<const u64v2*>(p + i + 2);
+        r.v[0] = a.x; r.v[1] = a.y; r.v[2] = b.x; r.v[3] = b.y;
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) r.v[k] = i + k < n ? p[i + k] : 0;
+    }
+    return r;
+}
+__device__ __forceinline__ W4 xor3(const W4& a, const W4& b, const W4& c)
+{
+    W4 r;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r.v[k] = a.v[k] ^ b.v[k] ^ c.v[k];
+    return r;
+}
+__device__ __forceinline__ void st2(u64* p, size_t j, u64 a, u64 b)
+{
+    u64v2 t; t.x = a; t.y = b;
+    *reinterpret_cast<u64v2*>(p + j) = t;        // packed arrays are 16-byte aligned and padded to four words
+}
+
+// Packed level LEVEL: finish the ANDs of the round before (G = S & K on whole words for
+// LEVEL 0, else level LEVEL - 1 on packed words) for the four input words behind two
+// output words, regroup, and mask this level's operands.  `vec0`: the whole-word arrays
+// of LEVEL 0 allow 16-byte loads (n a multiple of four, aligned bases).
+template <int LEVEL>
+__global__ __launch_bounds__(kT) void k3_plevel(Relu3Args q, Msb3Geom g, bool vec0)
+{
+    const int party = blockIdx.y;
+    const Relu3Party& p = q.p[party];
+    constexpr int d = 1 << LEVEL, s = 2 * d;
+    constexpr u64 A = sel_mask(LEVEL), Bm = low_mask(LEVEL);
+    const size_t n = q.n;
+    const size_t whi = (n + s - 1) >> (LEVEL + 1);                   // output words that hold an element
+    const size_t stride = (size_t)gridDim.x * blockDim.x * 2;
+    for (size_t j = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 2; j < whi; j += stride) {
+        W4 G, P;
+        if constexpr (LEVEL == 0) {
+            const size_t e = 2 * j;
+            const bool v = vec0 && e + 3 < n;
+            const W4 od = xor3(ld4(p.send, e, n, v), ld4(p.recv[0], e, n, v), ld4(p.recv[1], e, n, v));
+            const W4 og = xor3(ld4(p.send + n, e, n, v), ld4(p.recv[0] + n, e, n, v), ld4(p.recv[1] + n, e, n, v));
+            const W4 a = ld4(p.ta + g.toff[1], e, n, v), b = ld4(p.tb + g.toff[1], e, n, v), c = ld4(p.tc + g.toff[1], e, n, v);
+            P = ld4(p.P, e, n, v);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) G.v[k] = and_finish<u64>(party, od.v[k], og.v[k], a.v[k], b.v[k], c.v[k]);
+        } else {
+            constexpr int lq = LEVEL - 1, tg = 2 + 2 * lq, tp = 3 + 2 * lq;
+            const size_t w = 2 * j, pq = g.pw[lq];
+            const u64* sp = p.sendL + g.loff[lq];
+            const u64* r0 = p.recvL[0] + g.loff[lq]; const u64* r1 = p.recvL[1] + g.loff[lq];
+            const W4 gs = ld4(p.gsel + g.goff[lq], w, pq, true);
+            const W4 d1 = xor3(ld4(sp, w, pq, true), ld4(r0, w, pq, true), ld4(r1, w, pq, true));
+            const W4 g1 = xor3(ld4(sp + pq, w, pq, true), ld4(r0 + pq, w, pq, true), ld4(r1 + pq, w, pq, true));
+            const W4 d2 = xor3(ld4(sp + 2 * pq, w, pq, true), ld4(r0 + 2 * pq, w, pq, true), ld4(r1 + 2 * pq, w, pq, true));
+            const W4 g2 = xor3(ld4(sp + 3 * pq, w, pq, true), ld4(r0 + 3 * pq, w, pq, true), ld4(r1 + 3 * pq, w, pq, true));
+            const W4 a1 = ld4(p.ta + g.toff[tg], w, pq, true), b1 = ld4(p.tb + g.toff[tg], w, pq, true), c1 = ld4(p.tc + g.toff[tg], w, pq, true);
+            const W4 a2 = ld4(p.ta + g.toff[tp], w, pq, true), b2 = ld4(p.tb + g.toff[tp], w, pq, true), c2 = ld4(p.tc + g.toff[tp], w, pq, true);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                G.v[k] = gs.v[k] ^ and_finish<u64>(party, d1.v[k], g1.v[k], a1.v[k], b1.v[k], c1.v[k]);
+                P.v[k] = and_finish<u64>(party, d2.v[k], g2.v[k], a2.v[k], b2.v[k], c2.v[k]);
+            }
+        }
+        u64 X[2], Gk[2], Y1[2], Y2[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const u64 Glo = G.v[2 * k], Ghi = G.v[2 * k + 1], Plo = P.v[2 * k], Phi = P.v[2 * k + 1];
+            X[k] = (Plo & A) | rotl<d>(Phi & A);                 // P[p]
+            Gk[k] = (Glo & A) | rotl<d>(Ghi & A);                // G[p]
+            Y1[k] = rotl<d>(Glo & Bm) | rotl<2 * d>(Ghi & Bm);   // G[p - d] moved to p
+            Y2[k] = rotl<d>(Plo & Bm) | rotl<2 * d>(Phi & Bm);   // P[p - d] moved to p
+        }
+        constexpr int ng = 2 + 2 * LEVEL, np = 3 + 2 * LEVEL;
+        const size_t pl = g.pw[LEVEL];
+        u64* so = p.sendL + g.loff[LEVEL];
+        const u64v2 na1 = *reinterpret_cast<const u64v2*>(p.ta + g.toff[ng] + j), nb1 = *reinterpret_cast<const u64v2*>(p.tb + g.toff[ng] + j);
+        st2(so, j, X[0] ^ na1.x, X[1] ^ na1.y);
+        st2(so + pl, j, Y1[0] ^ nb1.x, Y1[1] ^ nb1.y);
+        if constexpr (LEVEL < 5) {                               // the last level needs no P update
+            const u64v2 na2 = *reinterpret_cast<const u64v2*>(p.ta + g.toff[np] + j), nb2 = *reinterpret_cast<const u64v2*>(p.tb + g.toff[np] + j);
+            st2(so + 2 * pl, j, X[0] ^ na2.x, X[1] ^ na2.y);
+            st2(so + 3 * pl, j, Y2[0] ^ nb2.x, Y2[1] ^ nb2.y);
+        }
+        st2(p.gsel + g.goff[LEVEL], j, Gk[0], Gk[1]);
+    }
+}
+
+// Packed sign stage: finish level 5; element i's carry into bit 63 sits at bit
+// (62 + i) mod 64 of word i / 64.  Then the B2A mask as in stage 8 of the whole-word chain.
+__global__ __launch_bounds__(kT) void k3_psign(Relu3Args q, Msb3Geom g)
+{
+    const int party = blockIdx.y;
+    const Relu3Party& p = q.p[party];
+    const size_t p5 = g.pw[5];
+    const u64* sp = p.sendL + g.loff[5];
+    const u64* r0 = p.recvL[0] + g.loff[5]; const u64* r1 = p.recvL[1] + g.loff[5];
+    const u64* gs = p.gsel + g.goff[5];
+    const u64 *a = p.ta + g.toff[12], *b = p.tb + g.toff[12], *c = p.tc + g.toff[12];
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < q.n; i += stride) {
+        const size_t w = i >> 6;
+        const u64 Gw = gs[w] ^ and_finish<u64>(party, sp[w] ^ r0[w] ^ r1[w], sp[p5 + w] ^ r0[p5 + w] ^ r1[p5 + w], a[w], b[w], c[w]);
+        const u8 sb = (u8)(p.p63[i] ^ (u8)((Gw >> ((62 + i) & 63)) & 1));
+        if (p.s_bit) p.s_bit[i] = sb;
+        p.vsend[i] = (u8)(sb ^ p.rb[i]);
+    }
+}
+
+// Offline helper: triple-major [13][n] words -> the packed layout (blockIdx.y = triple).
+__global__ __launch_bounds__(kT) void k3_pack_triples(const u64* __restrict__ in, u64* __restrict__ out, Msb3Geom g)
+{
+    const int t = blockIdx.y;
+    const size_t n = g.n, stride = (size_t)gridDim.x * blockDim.x;
+    const size_t first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < 2) {
+        const size_t n4 = g.toff[1];
+        for (size_t i = first; i < n4; i += stride) out[g.toff[t] + i] = i < n ? in[(size_t)t * n + i] : 0;
+        return;
+    }
+    const int l = (t - 2) / 2, s = 2 << l;
+    const u64 m = msb_mask(l);
+    for (size_t j = first; j < g.pw[l]; j += stride) {
+        u64 acc = 0;
+        for (int k = 0; k < s; ++k) {
+            const size_t e = j * s + k;
+            if (e < n) { const u64 v = in[(size_t)t * n + e] & m; acc |= k ? (v << k) | (v >> (64 - k)) : v; }
+        }
+        out[g.toff[t] + j] = acc;
+    }
+}
+
 template <int STAGE>
 int launch_stage(mpc_ctx* c, hipStream_t st, const Relu3Args& q, bool vec)
 {
@@ -322,6 +497,83 @@ int relu3_run(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
     return MPC_OK;
 }
 
+// ---- sign-only chain: workspace and the chain on one stream (no chunks: a call's packed
+// state is a third of the whole-word chain's, and its levels halve from round to round)
+size_t relu3_msb_ws(u8* base, size_t cap, size_t n, const Msb3Geom& g, Relu3Args* q, bool* ok)
+{
+    WsAlloc w(base, cap);
+    for (int i = 0; i < 3; ++i) {
+        Relu3Party& p = q->p[i];
+        p.wrecv[0] = w.take<u64>(n); p.wrecv[1] = w.take<u64>(n);
+        p.S = w.take<u64>(n); p.Wd = w.take<u64>(n); p.P = w.take<u64>(n); p.G = nullptr;
+        p.send = w.take<u64>(2 * n); p.recv[0] = w.take<u64>(2 * n); p.recv[1] = w.take<u64>(2 * n);
+        p.p63 = w.take<u8>(n); p.vsend = w.take<u8>(n); p.vrecv[0] = w.take<u8>(n); p.vrecv[1] = w.take<u8>(n);
+        p.sendL = w.take<u64>(g.words_blocks); p.recvL[0] = w.take<u64>(g.words_blocks); p.recvL[1] = w.take<u64>(g.words_blocks);
+        p.gsel = w.take<u64>(g.words_gsel);
+    }
+    if (ok) *ok = w.ok;
+    return w.off;
+}
+
+template <int LEVEL>
+int launch_plevel(mpc_ctx* c, hipStream_t st, const Relu3Args& q, const Msb3Geom& g, bool vec0)
+{
+    const size_t words = (q.n + ((size_t)2 << LEVEL) - 1) >> (LEVEL + 1);
+    hipLaunchKernelGGL(k3_plevel<LEVEL>, dim3(grid3((words + 1) / 2), 3), dim3(kT), 0, st, q, g, vec0);
+    MPC_HIP(c, hipGetLastError());
+    // this level's masked packed words go to both peers
+    const size_t len = (size_t)(LEVEL < 5 ? 4 : 2) * g.pw[LEVEL] * sizeof(u64);
+    CopySeg cp[6]; int k = 0;
+    for (int i = 0; i < 3; ++i)
+        for (int s = 0; s < 2; ++s)
+            cp[k++] = CopySeg{ (const u8*)(q.p[(i + 1 + s) % 3].sendL + g.loff[LEVEL]), (u8*)(q.p[i].recvL[s] + g.loff[LEVEL]), len, 0 };
+    return launch_copy_multi(c, st, cp, 6);
+}
+
+// q: caller arrays (q.n = n, q.tn = the packed buffers' whole-word row stride), workspace from relu3_msb_ws
+int relu3_msb_run(mpc_ctx* c, hipStream_t st, const Relu3Args& q, const Msb3Geom& g)
+{
+    const size_t n = q.n;
+    const bool vec = relu3_vectorisable(q);
+    const bool vec0 = vec && n % 4 == 0;
+    {
+        CopySeg cp[6];
+        for (int i = 0; i < 3; ++i) {
+            cp[2 * i] = CopySeg{ (const u8*)q.p[(i + 1) % 3].r1, (u8*)q.p[i].wrecv[0], n * sizeof(u64), 0 };
+            cp[2 * i + 1] = CopySeg{ (const u8*)q.p[(i + 2) % 3].r0, (u8*)q.p[i].wrecv[1], n * sizeof(u64), 0 };
+        }
+        MPC_TRY(launch_copy_multi(c, st, cp, 6));
+    }
+    MPC_TRY(launch_stage<0>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
+    MPC_TRY(launch_stage<1>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
+    MPC_TRY(launch_plevel<0>(c, st, q, g, vec0));
+    MPC_TRY(launch_plevel<1>(c, st, q, g, vec0));
+    MPC_TRY(launch_plevel<2>(c, st, q, g, vec0));
+    MPC_TRY(launch_plevel<3>(c, st, q, g, vec0));
+    MPC_TRY(launch_plevel<4>(c, st, q, g, vec0));
+    MPC_TRY(launch_plevel<5>(c, st, q, g, vec0));
+    hipLaunchKernelGGL(k3_psign, dim3(grid3(n), 3), dim3(kT), 0, st, q, g);
+    MPC_HIP(c, hipGetLastError());
+    {
+        CopySeg cp[6]; int k = 0;
+        for (int i = 0; i < 3; ++i)
+            for (int s = 0; s < 2; ++s)
+                cp[k++] = CopySeg{ q.p[(i + 1 + s) % 3].vsend, q.p[i].vrecv[s], n, 0 };
+        MPC_TRY(launch_copy_multi(c, st, cp, 6));
+    }
+    MPC_TRY(launch_stage<9>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
+    MPC_TRY(launch_stage<10>(c, st, q, vec));
+    return MPC_OK;
+}
+
+// the packed buffers must allow 16-byte accesses
+int check_packed3(const mpc_relu3_material* m)
+{
+    for (int i = 0; i < 3; ++i)
+        if (((uintptr_t)m->and_a.p[i] | (uintptr_t)m->and_b.p[i] | (uintptr_t)m->and_c.p[i]) & 15) return MPC_EINVAL;
+    return MPC_OK;
+}
+
 // ---- 2x2 max-pool by max(p, q) = q + ReLU(p - q): the local steps (blockIdx.y = party)
 struct Pool3Args { const u64* x[3]; u64* d1[3]; const u64* r1[3]; u64* v[3]; u64* d2[3]; u64* y[3]; int B, H, W, C; };
 
@@ -436,20 +688,72 @@ int mpc_relu3(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* m, mpc_share3
     return lane_fanout(c);
 }
 
-size_t mpc_maxpool3_workspace_bytes(int B, int H, int W, int C)
+size_t mpc_relu3_packed_words(size_t n) { return n ? msb3_geom(n).words_triples : 0; }
+
+size_t mpc_relu3_msb_workspace_bytes(size_t n)
+{
+    if (n == 0) return 0;
+    Relu3Args q{};
+    return relu3_msb_ws(nullptr, 0, n, msb3_geom(n), &q, nullptr);
+}
+
+int mpc_relu3_pack_triples(mpc_ctx* c, mpc_cshare3 words, mpc_share3 packed, size_t n)
+{
+    if (!c || n == 0) return MPC_EINVAL;
+    if (n > ((size_t)1 << 40)) return MPC_ERANGE;
+    for (int i = 0; i < 3; ++i) if (!words.p[i] || !packed.p[i]) return MPC_EINVAL;
+    const Msb3Geom g = msb3_geom(n);
+    hipStream_t st = c->s[0];
+    MPC_TRY(lane_join(c));
+    for (int i = 0; i < 3; ++i) {
+        hipLaunchKernelGGL(k3_pack_triples, dim3(grid3(n), 13), dim3(kT), 0, st, words.p[i], packed.p[i], g);
+        MPC_HIP(c, hipGetLastError());
+    }
+    return lane_fanout(c);
+}
+
+int mpc_relu3_msb(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* m, mpc_share3 y, size_t n,
+                  uint8_t* const s_bit[3], uint64_t* const s_arith[3])
+{
+    if (!c || n == 0) return MPC_EINVAL;
+    if (n > ((size_t)1 << 40)) return MPC_ERANGE;
+    MPC_TRY(check_material3(m));
+    MPC_TRY(check_packed3(m));
+    for (int i = 0; i < 3; ++i) if (!x.p[i] || !y.p[i]) return MPC_EINVAL;
+    const Msb3Geom g = msb3_geom(n);
+    Relu3Args q{};
+    bool ok = false;
+    relu3_msb_ws(c->ws, c->ws_bytes, n, g, &q, &ok);
+    if (!ok) return MPC_ENOMEM;
+    fill3(q, x.p, m, y.p, s_bit, s_arith, n);
+    q.tn = g.toff[1];
+    hipStream_t st = c->s[0];
+    MPC_TRY(lane_join(c));
+    const int pi = prof_begin(c, MPC_PROF_RELU, st);
+    MPC_TRY(relu3_msb_run(c, st, q, g));
+    prof_end(c, MPC_PROF_RELU, pi, st);
+    return lane_fanout(c);
+}
+
+static size_t maxpool3_ws(int B, int H, int W, int C, bool packed)
 {
     if (B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1)) return 0;
     const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
     // per party: d1 (2 n_out), r1 (2 n_out), v (n_out), d2 (n_out); then the larger conversion's scratch
-    return 3 * (2 * align_up(2 * n_out * 8) + 2 * align_up(n_out * 8)) + mpc_relu3_workspace_bytes(2 * n_out);
+    return 3 * (2 * align_up(2 * n_out * 8) + 2 * align_up(n_out * 8)) +
+           (packed ? mpc_relu3_msb_workspace_bytes(2 * n_out) : mpc_relu3_workspace_bytes(2 * n_out));
 }
 
-int mpc_maxpool3(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* mat1, const mpc_relu3_material* mat2,
-                 mpc_share3 y, int B, int H, int W, int C)
+size_t mpc_maxpool3_workspace_bytes(int B, int H, int W, int C) { return maxpool3_ws(B, H, W, C, false); }
+size_t mpc_maxpool3_msb_workspace_bytes(int B, int H, int W, int C) { return maxpool3_ws(B, H, W, C, true); }
+
+static int maxpool3_entry(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* mat1, const mpc_relu3_material* mat2,
+                          mpc_share3 y, int B, int H, int W, int C, bool packed)
 {
     if (!c || B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1)) return MPC_EINVAL;
     MPC_TRY(check_material3(mat1));
     MPC_TRY(check_material3(mat2));
+    if (packed) { MPC_TRY(check_packed3(mat1)); MPC_TRY(check_packed3(mat2)); }
     for (int i = 0; i < 3; ++i) if (!x.p[i] || !y.p[i]) return MPC_EINVAL;
     const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
     WsAlloc wa(c->ws, c->ws_bytes);
@@ -464,19 +768,40 @@ int mpc_maxpool3(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* mat1, cons
     if (!wa.ok) return MPC_ENOMEM;
     Relu3Args q1{}, q2{};
     bool ok1 = false, ok2 = false;
-    relu3_ws(c->ws + wa.off, c->ws_bytes - wa.off, relu3_chunk_cap(2 * n_out), &q1, &ok1);
-    relu3_ws(c->ws + wa.off, c->ws_bytes - wa.off, relu3_chunk_cap(n_out), &q2, &ok2);      // the second conversion reuses the scratch
+    const Msb3Geom g1 = msb3_geom(2 * n_out), g2 = msb3_geom(n_out);
+    u8* rest = c->ws ? c->ws + wa.off : nullptr;
+    const size_t room = c->ws_bytes - wa.off;
+    if (packed) {
+        relu3_msb_ws(rest, room, 2 * n_out, g1, &q1, &ok1);
+        relu3_msb_ws(rest, room, n_out, g2, &q2, &ok2);                        // the second conversion reuses the scratch
+    } else {
+        relu3_ws(rest, room, relu3_chunk_cap(2 * n_out), &q1, &ok1);
+        relu3_ws(rest, room, relu3_chunk_cap(n_out), &q2, &ok2);
+    }
     if (!ok1 || !ok2) return MPC_ENOMEM;
     fill3(q1, pq.d1, mat1, r1, nullptr, nullptr, 2 * n_out);
     fill3(q2, pq.d2, mat2, y.p, nullptr, nullptr, n_out);
+    if (packed) { q1.tn = g1.toff[1]; q2.tn = g2.toff[1]; }
     hipStream_t st = c->s[0];
     MPC_TRY(lane_join(c));
     MPC_TRY(launch_pool<0>(c, st, pq, n_out));       // first tournament level: max(p00, p01), max(p10, p11)
-    MPC_TRY(relu3_run(c, st, q1));
+    MPC_TRY(packed ? relu3_msb_run(c, st, q1, g1) : relu3_run(c, st, q1));
     MPC_TRY(launch_pool<1>(c, st, pq, n_out));       // second level: the two winners
-    MPC_TRY(relu3_run(c, st, q2));
+    MPC_TRY(packed ? relu3_msb_run(c, st, q2, g2) : relu3_run(c, st, q2));
     MPC_TRY(launch_pool<2>(c, st, pq, n_out));       // out = v + ReLU(u - v)
     return lane_fanout(c);
+}
+
+int mpc_maxpool3(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* mat1, const mpc_relu3_material* mat2,
+                 mpc_share3 y, int B, int H, int W, int C)
+{
+    return maxpool3_entry(c, x, mat1, mat2, y, B, H, W, C, false);
+}
+
+int mpc_maxpool3_msb(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* mat1, const mpc_relu3_material* mat2,
+                     mpc_share3 y, int B, int H, int W, int C)
+{
+    return maxpool3_entry(c, x, mat1, mat2, y, B, H, W, C, true);
 }
 
 }  // extern "C"

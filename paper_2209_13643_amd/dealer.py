@@ -174,11 +174,14 @@ def conv_layer3(lane: "mpc.Lane", g, B, H, W, Cin, Cout, KH, KW, pad, stride, x_
     return d
 
 
-def relu3_material(g, n: int, device) -> dict:
-    """Three-party secure-ReLU material for n elements (13 AND triples, two A2B masks per party)."""
+def relu3_material(g, n: int, device, packed: bool = False) -> dict:
+    """Three-party secure-ReLU material for n elements (13 AND triples, two A2B masks per party).
+    packed=True draws the AND triples directly in the packed layout of mpc_relu3_msb (uniform
+    words satisfy the bit-wise triple relation in any layout)."""
     w = lambda shape: rand_words(g, shape, device)
     m = {"r0": tuple(w((n,)) for _ in range(3)), "r1": tuple(w((n,)) for _ in range(3))}
-    A, Bm = w((mpc.N_AND_TRIPLES3, n)), w((mpc.N_AND_TRIPLES3, n))
+    tshape = (mpc.lib().mpc_relu3_packed_words(n),) if packed else (mpc.N_AND_TRIPLES3, n)
+    A, Bm = w(tshape), w(tshape)
     m["and_a"], m["and_b"], m["and_c"] = share_xor3(g, A), share_xor3(g, Bm), share_xor3(g, A & Bm)
     bits = [torch.randint(0, 2, (n,), generator=g, device=device, dtype=torch.uint8) for _ in range(3)]
     m["rb"] = tuple(bits)

@@ -67,6 +67,8 @@ EXPORTS = [
     "mpc_open3", "mpc_matmul3_workspace_bytes", "mpc_beaver_matmul3", "mpc_conv2d3_workspace_bytes", "mpc_conv2d3",
     "mpc_truncate3_workspace_bytes", "mpc_truncate3", "mpc_relu3_workspace_bytes", "mpc_relu3",
     "mpc_maxpool3_workspace_bytes", "mpc_maxpool3",
+    "mpc_relu3_packed_words", "mpc_relu3_pack_triples", "mpc_relu3_msb_workspace_bytes", "mpc_relu3_msb",
+    "mpc_maxpool3_msb_workspace_bytes", "mpc_maxpool3_msb",
 ]
 
 _lib = None
@@ -153,6 +155,12 @@ def lib():
                             POINTER(_P8 * 3), POINTER(_P64 * 3)]
     L.mpc_maxpool3_workspace_bytes.argtypes = [c_int] * 4; L.mpc_maxpool3_workspace_bytes.restype = c_size_t
     L.mpc_maxpool3.argtypes = [c_void_p, CShare3, POINTER(Relu3Material), POINTER(Relu3Material), CShare3] + [c_int] * 4
+    L.mpc_relu3_packed_words.argtypes = [c_size_t]; L.mpc_relu3_packed_words.restype = c_size_t
+    L.mpc_relu3_pack_triples.argtypes = [c_void_p, CShare3, CShare3, c_size_t]
+    L.mpc_relu3_msb_workspace_bytes.argtypes = [c_size_t]; L.mpc_relu3_msb_workspace_bytes.restype = c_size_t
+    L.mpc_relu3_msb.argtypes = L.mpc_relu3.argtypes
+    L.mpc_maxpool3_msb_workspace_bytes.argtypes = [c_int] * 4; L.mpc_maxpool3_msb_workspace_bytes.restype = c_size_t
+    L.mpc_maxpool3_msb.argtypes = L.mpc_maxpool3.argtypes
     _lib = L
     return L
 
@@ -194,15 +202,16 @@ def _share3(tri):
     return s
 
 
-def _material3(mat: dict, n: int) -> Relu3Material:
+def _material3(mat: dict, n: int, packed: bool = False) -> Relu3Material:
     m = Relu3Material()
+    tw = lib().mpc_relu3_packed_words(n) if packed else N_AND_TRIPLES3 * n
     for key in ("r0", "r1", "ra", "ma", "mb", "mc"):
         if any(t.numel() != n for t in mat[key]):
             raise ValueError(f"material '{key}': {n} words per party expected")
         setattr(m, key, _share3(mat[key]))
     for key in ("and_a", "and_b", "and_c"):
-        if any(t.numel() != N_AND_TRIPLES3 * n for t in mat[key]):
-            raise ValueError(f"material '{key}': [13][{n}] words per party expected")
+        if any(t.numel() != tw for t in mat[key]):
+            raise ValueError(f"material '{key}': {tw} words per party expected ({'packed' if packed else '[13][n]'} layout)")
         setattr(m, key, _share3(mat[key]))
     if any(t.numel() != n for t in mat["rb"]):
         raise ValueError("material 'rb': one byte per element and party expected")
@@ -567,27 +576,43 @@ class Lane:
         self._check(lib().mpc_truncate3(self._h, _share3(z), _share3(r), _share3(rt), n, bits))
         return z
 
-    def relu3(self, x, mat, want_sign=False, out=None):
+    def pack_material3(self, mat: dict) -> dict:
+        """Offline helper: three-party material with and_a/b/c in the packed layout of relu3(packed=True)."""
+        n = mat["r0"][0].numel()
+        words = lib().mpc_relu3_packed_words(n)
+        out = dict(mat)
+        for key in ("and_a", "and_b", "and_c"):
+            pk = tuple(torch.empty(words, dtype=torch.int64, device=self.device) for _ in range(3))
+            self._check(lib().mpc_relu3_pack_triples(self._h, _share3(mat[key]), _share3(pk), n))
+            out[key] = pk
+        self.sync()
+        return out
+
+    def relu3(self, x, mat, want_sign=False, out=None, packed=False):
+        """Three-party secure ReLU; packed=True runs the sign-only carry chain on packed material (mpc_relu3_msb)."""
         n = x[0].numel()
-        self.reserve(lib().mpc_relu3_workspace_bytes(n))
+        fn = lib().mpc_relu3_msb if packed else lib().mpc_relu3
+        self.reserve(lib().mpc_relu3_msb_workspace_bytes(n) if packed else lib().mpc_relu3_workspace_bytes(n))
         y = out if out is not None else self._empty3(x[0])
-        m = _material3(mat, n)
+        m = _material3(mat, n, packed)
         if want_sign:
             sb = tuple(torch.empty(n, dtype=torch.uint8, device=self.device) for _ in range(3))
             sa = tuple(torch.empty(n, dtype=torch.int64, device=self.device) for _ in range(3))
             sbp = (_P8 * 3)(*[_p8(t) for t in sb]); sap = (_P64 * 3)(*[_p64(t) for t in sa])
-            self._check(lib().mpc_relu3(self._h, _share3(x), byref(m), _share3(y), n, byref(sbp), byref(sap)))
+            self._check(fn(self._h, _share3(x), byref(m), _share3(y), n, byref(sbp), byref(sap)))
             return y, sb, sa
-        self._check(lib().mpc_relu3(self._h, _share3(x), byref(m), _share3(y), n, None, None))
+        self._check(fn(self._h, _share3(x), byref(m), _share3(y), n, None, None))
         return y
 
-    def maxpool3(self, x, mat1, mat2):
+    def maxpool3(self, x, mat1, mat2, packed=False):
         B, H, W, C = x[0].shape
         n_out = B * (H // 2) * (W // 2) * C
-        self.reserve(lib().mpc_maxpool3_workspace_bytes(B, H, W, C))
+        ws = lib().mpc_maxpool3_msb_workspace_bytes if packed else lib().mpc_maxpool3_workspace_bytes
+        self.reserve(ws(B, H, W, C))
         y = tuple(torch.empty((B, H // 2, W // 2, C), dtype=torch.int64, device=self.device) for _ in range(3))
-        m1, m2 = _material3(mat1, 2 * n_out), _material3(mat2, n_out)
-        self._check(lib().mpc_maxpool3(self._h, _share3(x), byref(m1), byref(m2), _share3(y), B, H, W, C))
+        m1, m2 = _material3(mat1, 2 * n_out, packed), _material3(mat2, n_out, packed)
+        fn = lib().mpc_maxpool3_msb if packed else lib().mpc_maxpool3
+        self._check(fn(self._h, _share3(x), byref(m1), byref(m2), _share3(y), B, H, W, C))
         return y
 
     def truncate(self, z, bits=16):

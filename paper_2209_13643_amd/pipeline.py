@@ -32,6 +32,7 @@ class LayerState:
     packed: bool = False          # ReLU / pool material in the packed layout of mpc_relu_msb
     right: torch.Tensor | None = None   # prepared digit planes of f, b_0 + f, b_1 (prepare_layers)
     left: torch.Tensor | None = None    # prepared digit planes of a_0, a_1
+    pool_first: bool = False      # pooled layer evaluated as ReLU(maxpool(z)): the ReLU material covers the pooled size
 
 
 def with_batch(layers, batch: int):
@@ -56,9 +57,11 @@ def deal_weights(g, layers, device):
     return ws
 
 
-def deal_microbatch(lane: mpc.Lane, g, layers, weights, packed_relu: bool = False) -> list:
+def deal_microbatch(lane: mpc.Lane, g, layers, weights, packed_relu: bool = False, pool_first: bool = False) -> list:
     """Triples and ReLU / pool material for one micro-batch (offline phase stand-in).
-    packed_relu: material for the sign-only carry chain (mpc_relu_msb / mpc_maxpool2x2_msb)."""
+    packed_relu: material for the sign-only carry chain (mpc_relu_msb / mpc_maxpool2x2_msb).
+    pool_first: layers with ReLU and max-pool are evaluated as ReLU(maxpool(z)) - the same function, since
+    max and ReLU commute, on a quarter of the ReLU elements; their ReLU material is dealt for the pooled size."""
     dev = lane.device
     states = []
     for L, (W, wsh) in zip(layers, weights):
@@ -74,9 +77,12 @@ def deal_microbatch(lane: mpc.Lane, g, layers, weights, packed_relu: bool = Fals
             n_out = L.M * L.N
         lane.sync()
         st = LayerState(w=wsh, a=dealer.share(g, A), b=dealer.share(g, Bm), c=dealer.share(g, C), packed=packed_relu)
+        pooled = isinstance(L, synth.Conv) and L.pool
+        st.pool_first = pool_first and pooled and L.relu
         if L.relu:
-            st.relu = dealer.relu_material(g, n_out, dev, packed=packed_relu)
-        if isinstance(L, synth.Conv) and L.pool:
+            n_relu = L.B * (L.Ho // 2) * (L.Wo // 2) * L.Cout if st.pool_first else n_out
+            st.relu = dealer.relu_material(g, n_relu, dev, packed=packed_relu)
+        if pooled:
             n_pool = L.B * (L.Ho // 2) * (L.Wo // 2) * L.Cout
             st.pool1 = dealer.relu_material(g, 2 * n_pool, dev, packed=packed_relu)
             st.pool2 = dealer.relu_material(g, n_pool, dev, packed=packed_relu)
@@ -128,6 +134,11 @@ def run_layer(lane: mpc.Lane, L, st: LayerState, x, keep: list, n_chunks=1, relu
         else:
             z = lane.beaver_matmul(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public, n_chunks=n_chunks, flags=flags)
     outs = [z]
+    if st.pool_first:
+        z = lane.maxpool2x2(z, st.pool1, st.pool2, n_chunks=relu_chunks, packed=st.packed); outs.append(z)
+        z = lane.relu(z, st.relu, n_chunks=relu_chunks, packed=st.packed); outs.append(z)
+        keep.extend(outs)
+        return z
     if st.relu is not None:
         z = lane.relu(z, st.relu, n_chunks=relu_chunks, packed=st.packed); outs.append(z)
     if st.pool1 is not None:
@@ -186,6 +197,7 @@ class LayerState3:
     relu: dict | None = None
     pool1: dict | None = None
     pool2: dict | None = None
+    packed: bool = False          # ReLU / pool material in the packed layout: sign-only chain (mpc_relu3_msb)
 
 
 def deal_weights3(g, layers, device):
@@ -197,8 +209,9 @@ def deal_weights3(g, layers, device):
     return ws
 
 
-def deal_microbatch3(lane: mpc.Lane, g, layers, weights) -> list:
-    """Triples, rescale pairs and ReLU / pool material of one micro-batch for three parties."""
+def deal_microbatch3(lane: mpc.Lane, g, layers, weights, packed_relu: bool = False) -> list:
+    """Triples, rescale pairs and ReLU / pool material of one micro-batch for three parties.
+    packed_relu: material for the sign-only carry chain (mpc_relu3_msb / mpc_maxpool3_msb)."""
     dev = lane.device
     states = []
     for L, (W, wsh) in zip(layers, weights):
@@ -215,13 +228,13 @@ def deal_microbatch3(lane: mpc.Lane, g, layers, weights) -> list:
         lane.sync()
         r = dealer.rand_words(g, C.shape, dev) & ((1 << 63) - 1)
         st = LayerState3(w=wsh, a=dealer.share3(g, A), b=dealer.share3(g, Bm), c=dealer.share3(g, C),
-                         r=dealer.share3(g, r), rt=dealer.share3(g, r >> dealer.FRAC_BITS))
+                         r=dealer.share3(g, r), rt=dealer.share3(g, r >> dealer.FRAC_BITS), packed=packed_relu)
         if L.relu:
-            st.relu = dealer.relu3_material(g, n_out, dev)
+            st.relu = dealer.relu3_material(g, n_out, dev, packed=packed_relu)
         if isinstance(L, synth.Conv) and L.pool:
             n_pool = L.B * (L.Ho // 2) * (L.Wo // 2) * L.Cout
-            st.pool1 = dealer.relu3_material(g, 2 * n_pool, dev)
-            st.pool2 = dealer.relu3_material(g, n_pool, dev)
+            st.pool1 = dealer.relu3_material(g, 2 * n_pool, dev, packed=packed_relu)
+            st.pool2 = dealer.relu3_material(g, n_pool, dev, packed=packed_relu)
         states.append(st)
     torch.cuda.synchronize(dev)
     return states
@@ -246,9 +259,9 @@ def run_layer3(lane: mpc.Lane, L, st: LayerState3, x, keep: list):
     lane.truncate3(z, st.r, st.rt)
     outs = [z]
     if st.relu is not None:
-        z = lane.relu3(z, st.relu); outs.append(z)
+        z = lane.relu3(z, st.relu, packed=st.packed); outs.append(z)
     if st.pool1 is not None:
-        z = lane.maxpool3(z, st.pool1, st.pool2); outs.append(z)
+        z = lane.maxpool3(z, st.pool1, st.pool2, packed=st.packed); outs.append(z)
     keep.extend(outs)
     return z
 

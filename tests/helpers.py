@@ -58,9 +58,10 @@ def oracle_conv(d, truncate_bits=16):
 
 
 # ----------------------------------------------------------- whole networks (host)
-def deal_network_host(rng, layers, weights=None):
+def deal_network_host(rng, layers, weights=None, pool_first=False):
     """Per-layer shares / triples / material as numpy arrays for one micro-batch.
-    `weights`: list of (W, (w0, w1)) to reuse across micro-batches, or None to draw them."""
+    `weights`: list of (W, (w0, w1)) to reuse across micro-batches, or None to draw them.
+    `pool_first`: layers with ReLU and max-pool get their ReLU material at the pooled size."""
     states, wout = [], []
     for li, L in enumerate(layers):
         conv = isinstance(L, synth.Conv)
@@ -78,8 +79,9 @@ def deal_network_host(rng, layers, weights=None):
             a, b, c = synth.deal_product_triple(rng, (L.M, L.K), wshape, oracle.ring_matmul)
             n_out = L.M * L.N
         st = dict(W=W, w=wsh, a=a, b=b, c=c, relu=None, pool1=None, pool2=None)
+        st["pool_first"] = bool(pool_first and conv and L.pool and L.relu)
         if L.relu:
-            st["relu"] = synth.deal_relu_material(rng, n_out)
+            st["relu"] = synth.deal_relu_material(rng, n_out // 4 if st["pool_first"] else n_out)
         if conv and L.pool:
             n_pool = L.B * (L.Ho // 2) * (L.Wo // 2) * L.Cout
             st["pool1"] = synth.deal_relu_material(rng, 2 * n_pool)
@@ -98,10 +100,15 @@ def oracle_forward(layers, states, x):
         else:
             xs = (x[0].reshape(L.M, L.K), x[1].reshape(L.M, L.K))
             z = oracle.truncate(oracle.beaver_matmul(xs, st["w"], st["a"], st["b"], st["c"]), 16)
-        if st["relu"] is not None:
-            z = oracle.relu(z, st["relu"]).y
-        if st["pool1"] is not None:
+        if st.get("pool_first"):
             z = oracle.maxpool2x2(z, st["pool1"], st["pool2"])
+            z = oracle.relu((z[0].reshape(-1), z[1].reshape(-1)), st["relu"]).y
+            z = (z[0].reshape(L.B, L.Ho // 2, L.Wo // 2, L.Cout), z[1].reshape(L.B, L.Ho // 2, L.Wo // 2, L.Cout))
+        else:
+            if st["relu"] is not None:
+                z = oracle.relu(z, st["relu"]).y
+            if st["pool1"] is not None:
+                z = oracle.maxpool2x2(z, st["pool1"], st["pool2"])
         outs.append(z)
         x = z
     return outs

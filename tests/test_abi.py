@@ -124,6 +124,18 @@ def test_three_party_workspace_queries(lib):
     assert lib.mpc_relu3_workspace_bytes(0) == 0
     assert lib.mpc_maxpool3_workspace_bytes(1, 4, 4, 2) > lib.mpc_relu3_workspace_bytes(16)
     assert lib.mpc_maxpool3_workspace_bytes(1, 3, 4, 2) == 0               # odd height
+    # sign-only chain: two whole-word triples, then eleven packed ones (64, 64, 32, 32, ... words at n = 128,
+    # each padded to four: 64+64+32+32+16+16+8+8+4+4+4 = 252)
+    assert lib.mpc_relu3_packed_words(128) == 2 * 128 + 252
+    assert lib.mpc_relu3_packed_words(1) == 2 * 4 + 32 + 32 + 16 + 16 + 8 + 8 + 4 + 4 + 4 + 4 + 4
+    assert lib.mpc_relu3_packed_words(0) == 0
+    big = 1 << 20
+    assert lib.mpc_relu3_packed_words(big) < 13 * big // 3                 # against 13 n words unpacked
+    # one pass over the whole call: the whole-word words of the first two rounds and a block per level
+    assert 3 * 11 * 8 * big < lib.mpc_relu3_msb_workspace_bytes(big) < 3 * 26 * 8 * big
+    assert lib.mpc_relu3_msb_workspace_bytes(0) == 0
+    assert lib.mpc_maxpool3_msb_workspace_bytes(1, 4, 4, 2) > lib.mpc_relu3_msb_workspace_bytes(16)
+    assert lib.mpc_maxpool3_msb_workspace_bytes(1, 3, 4, 2) == 0
     # null arguments are rejected before any device work
     assert lib.mpc_open3(None, mpc_null3(), None, 4) == -1
 

@@ -319,3 +319,9 @@ def test_config1_with_three_parties(mods, lane):
     for i in range(3):
         assert np.array_equal(take(y[i]), res.y[i]), f"relu3 sample, party {i}"
         assert np.array_equal(take(sa[i]), res.s_arith[i]), f"relu3 sign share sample, party {i}"
+    # the sign-only chain on the same material, packed on the device: the same words everywhere
+    # (whole-word run), and the sampled oracle recomputation again
+    yp, sbp, sap = lane.relu3(t, lane.pack_material3(mat), want_sign=True, packed=True); lane.sync()
+    for i in range(3):
+        assert torch.equal(yp[i], y[i]) and torch.equal(sbp[i], sb[i]) and torch.equal(sap[i], sa[i]), f"relu3 packed, party {i}"
+        assert np.array_equal(take(yp[i]), res.y[i]), f"relu3 packed sample, party {i}"

@@ -47,7 +47,7 @@ def to_state(mpc, pipeline, st, pack_lane=None):
         return pack_lane.pack_material(md) if pack_lane is not None else md
     return pipeline.LayerState(w=dv(st["w"]), a=dv(st["a"]), b=dv(st["b"]), c=dv(st["c"]),
                                relu=mat(st["relu"]), pool1=mat(st["pool1"]), pool2=mat(st["pool2"]),
-                               packed=pack_lane is not None)
+                               packed=pack_lane is not None, pool_first=st.get("pool_first", False))
 
 
 def check(mpc, got_pair, want_pair, what):
@@ -73,6 +73,38 @@ def test_vgg16_every_layer_matches_oracle(mods, dealt, packed_relu):
     # decoded logits close to a float64 run of the same quantised network
     logits = oracle.decode(rec((mpc.to_host(x[0]), mpc.to_host(x[1]))))
     assert logits.shape == (2, 10) and np.isfinite(logits).all()
+    lane.close()
+
+
+@pytest.mark.parametrize("packed_relu", [False, True], ids=["whole-word-relu", "sign-only-packed-relu"])
+def test_pooled_layers_as_relu_of_maxpool(mods, dealt, packed_relu):
+    """max and ReLU commute, so a layer with both may pool first and convert a quarter of the elements.
+    The oracle run in that order reconstructs to the very values of the usual order at every layer
+    (both are exact on the truncated product), and the device run matches it share for share."""
+    mpc, pipeline = mods
+    layers, mbs = dealt
+    print(f"vgg16 with pooled layers as ReLU(maxpool(z)), packed_relu={packed_relu}", flush=True)
+    mb = mbs[0]
+    rng = synth.rng_for(4, 12)
+    weights = [(st["W"], st["w"]) for st in mb["states"]]
+    host, _ = deal_network_host(rng, layers, weights, pool_first=True)
+    assert sum(st["pool_first"] for st in host) == 5
+    want = oracle_forward(layers, host, mb["x"])
+    # truncation noise differs with the triples (one unit in the last place per product), so the two
+    # orders are compared on one layer's own input: same z, then both orders of the nonlinear part
+    L, st, st0 = layers[1], host[1], mb["states"][1]
+    z = want[0]
+    zc = oracle.truncate(oracle.beaver_conv2d(z, st["w"], st["a"], st["b"], st["c"], L.pad, L.stride), 16)
+    usual = oracle.maxpool2x2(oracle.relu(zc, st0["relu"]).y, st0["pool1"], st0["pool2"])
+    assert np.array_equal(rec(usual), rec(want[1]))
+    lane = mpc.Lane(0); lane.use_single_queue()
+    states = [to_state(mpc, pipeline, s, lane if packed_relu else None) for s in host]
+    x = (mpc.to_device(mb["x"][0]), mpc.to_device(mb["x"][1]))
+    keep = []
+    for li, (L, s) in enumerate(zip(layers, states)):
+        x = pipeline.run_layer(lane, L, s, x, keep)
+        lane.sync()
+        check(mpc, x, want[li], f"layer {li} ({L.name}), pool first")
     lane.close()
 
 
@@ -240,11 +272,13 @@ def test_strided_network_training_step(mods):
     lane.close()
 
 
-def test_vgg16_with_three_parties(mods):
+@pytest.mark.parametrize("packed_relu", [False, True], ids=["whole-word-relu", "sign-only-packed-relu"])
+def test_vgg16_with_three_parties(mods, packed_relu):
     """The whole VGG16-CIFAR layer list with three simulated parties (Sec. 5.6): every layer's three
     output shares against the oracle, then two micro-batches on two lanes in layer-major order and with
     the weight masks opened ahead of time: not a bit may change."""
     mpc, pipeline = mods
+    packer = mpc.Lane(0)
     base = synth.config_vgg16_pipeline(micro_batch=2)
     layers = base.layers
     rng = synth.rng_for(base.index, 13)
@@ -255,9 +289,14 @@ def test_vgg16_with_three_parties(mods):
         xs = synth.share_additive3(rng, X)
         mbs.append(dict(states=states, X=X, x=xs, want=oracle_forward3(layers, states, xs)))
     d3 = lambda t: tuple(mpc.to_device(v) for v in t)
-    m3 = lambda m: None if m is None else mpc.material_to_device(m)
+    def m3(m):
+        if m is None:
+            return None
+        md = mpc.material_to_device(m)
+        return packer.pack_material3(md) if packed_relu else md
     up = lambda st: pipeline.LayerState3(w=d3(st["w"]), a=d3(st["a"]), b=d3(st["b"]), c=d3(st["c"]), r=d3(st["r"]),
-                                         rt=d3(st["rt"]), relu=m3(st["relu"]), pool1=m3(st["pool1"]), pool2=m3(st["pool2"]))
+                                         rt=d3(st["rt"]), relu=m3(st["relu"]), pool1=m3(st["pool1"]), pool2=m3(st["pool2"]),
+                                         packed=packed_relu)
 
     def check3(got, want, what):
         for i in range(3):
@@ -288,5 +327,5 @@ def test_vgg16_with_three_parties(mods):
         ln.sync()
     for m in range(2):
         check3(outs[m], mbs[m]["want"][-1], f"pipelined micro-batch {m}")
-    for ln in lanes:
+    for ln in lanes + [packer]:
         ln.close()

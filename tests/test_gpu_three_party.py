@@ -130,37 +130,50 @@ def test_small_output_long_contraction_is_split(mpc, lane):
     assert_shares_equal(host3(mpc, lane, z), want, "split-K")
 
 
-@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 1000, 4097, 100003])
-def test_relu3(mpc, lane, n):
+PACKED = pytest.mark.parametrize("packed", [False, True], ids=["whole-word", "sign-only-packed"])
+
+
+def material3(mpc, lane, mat, packed):
+    """Upload the [13][n] material; for the sign-only chain pack its triples on the device (the oracle keeps the words)."""
+    md = mpc.material_to_device(mat)
+    return lane.pack_material3(md) if packed else md
+
+
+@PACKED
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 63, 64, 65, 127, 128, 129, 1000, 4097, 4100, 100003])
+def test_relu3(mpc, lane, n, packed):
     rng = np.random.default_rng(350 + n)
     X = synth.normal_fixed(rng, n, 4.0)
     x = synth.share_additive3(rng, X)
     mat = synth.deal_relu3_material(rng, n)
     want = oracle.relu3(x, mat)
-    y, sb, sa = lane.relu3(dev3(mpc, x), mpc.material_to_device(mat), want_sign=True)
+    y, sb, sa = lane.relu3(dev3(mpc, x), material3(mpc, lane, mat, packed), want_sign=True, packed=packed)
     assert_shares_equal(host3(mpc, lane, y), want.y, "relu3 y")
     assert_shares_equal(host3(mpc, lane, sb), want.s_bit, "relu3 s_bit")
     assert_shares_equal(host3(mpc, lane, sa), want.s_arith, "relu3 s_arith")
     assert np.array_equal(rec3(host3(mpc, lane, y)).view(np.int64), np.maximum(X.view(np.int64), 0))
 
 
+@PACKED
 @pytest.mark.parametrize("n", [786434, 786435, 1100000])
-def test_relu3_in_several_chunks(mpc, n):
-    """Above about 3/4 M elements the chain runs chunk by chunk: even and odd totals, ragged last chunk."""
+def test_relu3_in_several_chunks(mpc, n, packed):
+    """Above about 3/4 M elements the whole-word chain runs chunk by chunk: even and odd totals, ragged
+    last chunk.  The sign-only chain takes the same sizes in one pass (several grid strides per thread)."""
     lane = mpc.Lane(0); lane.use_single_queue()
     rng = np.random.default_rng(n)
     X = synth.normal_fixed(rng, n, 4.0)
     x = synth.share_additive3(rng, X)
     mat = synth.deal_relu3_material(rng, n)
     want = oracle.relu3(x, mat)
-    y, sb, sa = lane.relu3(dev3(mpc, x), mpc.material_to_device(mat), want_sign=True)
+    y, sb, sa = lane.relu3(dev3(mpc, x), material3(mpc, lane, mat, packed), want_sign=True, packed=packed)
     assert_shares_equal(host3(mpc, lane, y), want.y, "relu3 y")
     assert_shares_equal(host3(mpc, lane, sb), want.s_bit, "relu3 s_bit")
     assert_shares_equal(host3(mpc, lane, sa), want.s_arith, "relu3 s_arith")
     lane.close()
 
 
-def test_relu3_uniform_words_and_carry_patterns(mpc, lane):
+@PACKED
+def test_relu3_uniform_words_and_carry_patterns(mpc, lane, packed):
     """Uniform 64-bit values and inputs whose sum ripples a carry through every level."""
     rng = np.random.default_rng(360)
     X = np.concatenate([synth.rand_words(rng, 5000),
@@ -171,14 +184,15 @@ def test_relu3_uniform_words_and_carry_patterns(mpc, lane):
                    (np.full(n, (1 << 64) - 1, dtype=U64), np.ones(n, dtype=U64), X),       # shares that sum with a full ripple
                    (np.full(n, 1 << 63, dtype=U64), np.full(n, 1 << 63, dtype=U64), X)):
         want = oracle.relu3(shares, mat)
-        y = lane.relu3(dev3(mpc, shares), mpc.material_to_device(mat))
+        y = lane.relu3(dev3(mpc, shares), material3(mpc, lane, mat, packed), packed=packed)
         got = host3(mpc, lane, y)
         assert_shares_equal(got, want.y, "relu3")
         assert np.array_equal(rec3(got).view(np.int64), np.maximum(X.view(np.int64), 0))
 
 
+@PACKED
 @pytest.mark.parametrize("shape", [(1, 2, 2, 1), (2, 8, 6, 5), (3, 16, 16, 64)])
-def test_maxpool3(mpc, lane, shape):
+def test_maxpool3(mpc, lane, shape, packed):
     B, H, W, C = shape
     rng = np.random.default_rng(380 + C)
     X = synth.normal_fixed(rng, shape, 2.0)
@@ -186,7 +200,7 @@ def test_maxpool3(mpc, lane, shape):
     n_out = B * (H // 2) * (W // 2) * C
     mat1, mat2 = synth.deal_relu3_material(rng, 2 * n_out), synth.deal_relu3_material(rng, n_out)
     want = oracle.maxpool2x2_3(x, mat1, mat2)
-    y = lane.maxpool3(dev3(mpc, x), mpc.material_to_device(mat1), mpc.material_to_device(mat2))
+    y = lane.maxpool3(dev3(mpc, x), material3(mpc, lane, mat1, packed), material3(mpc, lane, mat2, packed), packed=packed)
     got = host3(mpc, lane, y)
     assert_shares_equal(got, want, f"maxpool3 {shape}")
     assert np.array_equal(rec3(got).view(np.int64), X.view(np.int64).reshape(B, H // 2, 2, W // 2, 2, C).max(axis=(2, 4)))
@@ -222,6 +236,18 @@ def test_three_party_argument_errors(mpc, lane):
     r, rt = synth.deal_trunc3_pair(rng, (8, 8))
     with pytest.raises(mpc.MpcError):
         lane.truncate3(z, dev3(mpc, r), dev3(mpc, rt), bits=63)
+    # the sign-only chain wants the packed triple layout, 16-byte aligned
+    n = 64
+    x = dev3(mpc, synth.share_additive3(rng, synth.normal_fixed(rng, n, 1.0)))
+    md = mpc.material_to_device(synth.deal_relu3_material(rng, n))
+    with pytest.raises(ValueError):
+        lane.relu3(x, md, packed=True)
+    pk = lane.pack_material3(md)
+    import torch
+    shifted = dict(pk)
+    shifted["and_b"] = tuple(torch.cat([t.new_zeros(1), t])[1:] for t in pk["and_b"])     # same words, 8 bytes off
+    with pytest.raises(mpc.MpcError):
+        lane.relu3(x, shifted, packed=True)
     lane.sync()
 
 

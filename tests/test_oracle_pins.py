@@ -529,6 +529,25 @@ def test_maxpool_by_composition():
     assert np.array_equal(oracle.to_signed(rec(out)), want)
 
 
+def test_relu_and_maxpool_commute():
+    """ReLU is monotone, so ReLU(max window) = max window of ReLU: a runner may pool first and
+    convert a quarter of the elements.  Both orders are exact, so the reconstructions are equal."""
+    rng = np.random.default_rng(22)
+    B, H, W, C = 2, 4, 6, 3
+    X = rng.integers(-(1 << 30), 1 << 30, size=(B, H, W, C)).astype(np.int64)
+    X[0, :2, :2, 0] = -5                     # an all-negative window: both orders give 0
+    xs = synth.share_additive(rng, X.view(U64))
+    n, n_out = X.size, X.size // 4
+    deal = lambda k: synth.deal_relu_material(rng, k)
+    relu_then_pool = oracle.maxpool2x2(oracle.relu(xs, deal(n)).y, deal(2 * n_out), deal(n_out))
+    pooled = oracle.maxpool2x2(xs, deal(2 * n_out), deal(n_out))
+    pool_then_relu = oracle.relu(pooled, deal(n_out)).y
+    want = np.maximum(X.reshape(B, H // 2, 2, W // 2, 2, C).max(axis=(2, 4)), 0)
+    assert np.array_equal(oracle.to_signed(rec(relu_then_pool)), want)
+    assert np.array_equal(oracle.to_signed(rec(pool_then_relu)).reshape(want.shape), want)
+    assert want[0, 0, 0, 0] == 0
+
+
 # ------------------------------------------------------- fixed point vs float64
 def test_tiny_layer_float64_agreement():
     """Config 0 end to end on the oracle: decoded output within 2^-12 of the
