@@ -73,12 +73,18 @@ struct Relu3Args { Relu3Party p[3]; size_t n; size_t tn; };   // n: elements of 
 // when the element count is even and every array is 16-byte aligned.
 typedef u64 u64v2 __attribute__((ext_vector_type(2)));
 typedef u8 u8v2 __attribute__((ext_vector_type(2)));
+// four words per thread: two 16-byte accesses each (the type asks for no more than 16-byte alignment)
+typedef u64 u64v4 __attribute__((ext_vector_type(4), aligned(16)));
+typedef u8 u8v4 __attribute__((ext_vector_type(4)));
 template <typename T> struct ByteOf { typedef u8 type; };
 template <> struct ByteOf<u64v2> { typedef u8v2 type; };
+template <> struct ByteOf<u64v4> { typedef u8v4 type; };
 __device__ __forceinline__ u8 to_bytes(u64 v) { return (u8)v; }
 __device__ __forceinline__ u8v2 to_bytes(u64v2 v) { return __builtin_convertvector(v, u8v2); }
+__device__ __forceinline__ u8v4 to_bytes(u64v4 v) { return __builtin_convertvector(v, u8v4); }
 __device__ __forceinline__ u64 to_words(u8 v) { return v; }
 __device__ __forceinline__ u64v2 to_words(u8v2 v) { return __builtin_convertvector(v, u64v2); }
+__device__ __forceinline__ u64v4 to_words(u8v4 v) { return __builtin_convertvector(v, u64v4); }
 
 // One Beaver AND gate finished: own and received masked operands -> this party's share.
 template <typename T>
@@ -182,10 +188,11 @@ __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
     }
 }
 
-// 16-byte accesses need an even element count (rows of the [k][n] arrays stay aligned) and aligned arrays
-bool relu3_vectorisable(const Relu3Args& q)
+// Words per thread: 16-byte accesses need an even element count (rows of the [k][n] arrays stay aligned)
+// and aligned arrays; four words per thread a multiple of four and 4-byte aligned byte arrays.
+int relu3_vectorisable(const Relu3Args& q)
 {
-    if ((q.n | q.tn) & 1) return false;
+    if ((q.n | q.tn) & 1) return 1;
     uintptr_t w = 0, b = 0;
     for (int i = 0; i < 3; ++i) {
         const Relu3Party& p = q.p[i];
@@ -195,7 +202,8 @@ bool relu3_vectorisable(const Relu3Args& q)
             w |= (uintptr_t)ptr;
         b |= (uintptr_t)p.rb | (uintptr_t)p.s_bit;
     }
-    return (w & 15) == 0 && (b & 1) == 0;
+    if ((w & 15) != 0 || (b & 1) != 0) return 1;
+    return ((q.n | q.tn) & 3) == 0 && (b & 3) == 0 ? 4 : 2;
 }
 
 // ---- the sign-only chain (mpc_relu3_msb) ---------------------------------------------
@@ -328,6 +336,7 @@ __global__ __launch_bounds__(kT) void k3_plevel(Relu3Args q, Msb3Geom g, bool ve
 
 // Packed sign stage: finish level 5; element i's carry into bit 63 sits at bit
 // (62 + i) mod 64 of word i / 64.  Then the B2A mask as in stage 8 of the whole-word chain.
+template <int V>
 __global__ __launch_bounds__(kT) void k3_psign(Relu3Args q, Msb3Geom g)
 {
     const int party = blockIdx.y;
@@ -337,13 +346,24 @@ __global__ __launch_bounds__(kT) void k3_psign(Relu3Args q, Msb3Geom g)
     const u64* r0 = p.recvL[0] + g.loff[5]; const u64* r1 = p.recvL[1] + g.loff[5];
     const u64* gs = p.gsel + g.goff[5];
     const u64 *a = p.ta + g.toff[12], *b = p.tb + g.toff[12], *c = p.tc + g.toff[12];
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < q.n; i += stride) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x * V;
+    // V consecutive elements (V = 4: n is a multiple of four, so they share word i / 64 and one 4-byte access each)
+    for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * V; i < q.n; i += stride) {
         const size_t w = i >> 6;
         const u64 Gw = gs[w] ^ and_finish<u64>(party, sp[w] ^ r0[w] ^ r1[w], sp[p5 + w] ^ r0[p5 + w] ^ r1[p5 + w], a[w], b[w], c[w]);
-        const u8 sb = (u8)(p.p63[i] ^ (u8)((Gw >> ((62 + i) & 63)) & 1));
-        if (p.s_bit) p.s_bit[i] = sb;
-        p.vsend[i] = (u8)(sb ^ p.rb[i]);
+        if constexpr (V == 4) {
+            const uint32_t top = *reinterpret_cast<const uint32_t*>(p.p63 + i), rb = *reinterpret_cast<const uint32_t*>(p.rb + i);
+            uint32_t carry = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) carry |= (uint32_t)((Gw >> ((62 + i + k) & 63)) & 1) << (8 * k);
+            const uint32_t sb = top ^ carry;
+            if (p.s_bit) *reinterpret_cast<uint32_t*>(p.s_bit + i) = sb;
+            *reinterpret_cast<uint32_t*>(p.vsend + i) = sb ^ rb;
+        } else {
+            const u8 sb = (u8)(p.p63[i] ^ (u8)((Gw >> ((62 + i) & 63)) & 1));
+            if (p.s_bit) p.s_bit[i] = sb;
+            p.vsend[i] = (u8)(sb ^ p.rb[i]);
+        }
     }
 }
 
@@ -371,10 +391,11 @@ __global__ __launch_bounds__(kT) void k3_pack_triples(const u64* __restrict__ in
 }
 
 template <int STAGE>
-int launch_stage(mpc_ctx* c, hipStream_t st, const Relu3Args& q, bool vec)
+int launch_stage(mpc_ctx* c, hipStream_t st, const Relu3Args& q, int vec)
 {
-    if (vec) hipLaunchKernelGGL((k3_relu<STAGE, u64v2>), dim3(grid3(q.n / 2), 3), dim3(kT), 0, st, q);
-    else     hipLaunchKernelGGL((k3_relu<STAGE, u64>), dim3(grid3(q.n), 3), dim3(kT), 0, st, q);
+    if (vec == 4)      hipLaunchKernelGGL((k3_relu<STAGE, u64v4>), dim3(grid3(q.n / 4), 3), dim3(kT), 0, st, q);
+    else if (vec == 2) hipLaunchKernelGGL((k3_relu<STAGE, u64v2>), dim3(grid3(q.n / 2), 3), dim3(kT), 0, st, q);
+    else               hipLaunchKernelGGL((k3_relu<STAGE, u64>), dim3(grid3(q.n), 3), dim3(kT), 0, st, q);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
 }
@@ -432,7 +453,7 @@ void fill3(Relu3Args& q, const u64* const x[3], const mpc_relu3_material* m, u64
 int relu3_chunk(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
 {
     const size_t n = q.n;
-    const bool vec = relu3_vectorisable(q);
+    const int vec = relu3_vectorisable(q);
     // Alg. 2: party j sends the mask r1_j to party j+2 and r0_j to party j+1, i.e. party i
     // receives its share of word i+1 (that party's r1) and of word i+2 (that party's r0)
     {
@@ -466,13 +487,13 @@ int relu3_chunk(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
 
 // Chunks of about 2^19 elements: the exchanged words and the carried state of a chunk (about 0.35 GB
 // for the three parties) then stay close to the last-level cache from stage to stage, and only the
-// offline material streams from DRAM.  Chunk boundaries are even, so 16-byte accesses stay possible.
+// offline material streams from DRAM.  Chunk boundaries are multiples of four, so wide accesses stay possible.
 constexpr size_t kChunk3 = (size_t)1 << 19;
 inline int relu3_chunks(size_t n) { return n <= kChunk3 + kChunk3 / 2 ? 1 : (int)((n + kChunk3 - 1) / kChunk3); }
 inline size_t relu3_chunk_cap(size_t n)          // largest chunk of relu3_run's split
 {
     const int k = relu3_chunks(n);
-    return k == 1 ? n : ((n + k - 1) / k + 1) & ~(size_t)1;
+    return k == 1 ? n : ((n + k - 1) / k + 3) & ~(size_t)3;
 }
 
 // q: caller arrays of the whole call (q.n = q.tn = n), workspace carved for relu3_chunk_cap(n) elements.
@@ -534,8 +555,8 @@ int launch_plevel(mpc_ctx* c, hipStream_t st, const Relu3Args& q, const Msb3Geom
 int relu3_msb_run(mpc_ctx* c, hipStream_t st, const Relu3Args& q, const Msb3Geom& g)
 {
     const size_t n = q.n;
-    const bool vec = relu3_vectorisable(q);
-    const bool vec0 = vec && n % 4 == 0;
+    const int vec = relu3_vectorisable(q);
+    const bool vec0 = vec >= 2 && n % 4 == 0;
     {
         CopySeg cp[6];
         for (int i = 0; i < 3; ++i) {
@@ -552,7 +573,8 @@ int relu3_msb_run(mpc_ctx* c, hipStream_t st, const Relu3Args& q, const Msb3Geom
     MPC_TRY(launch_plevel<3>(c, st, q, g, vec0));
     MPC_TRY(launch_plevel<4>(c, st, q, g, vec0));
     MPC_TRY(launch_plevel<5>(c, st, q, g, vec0));
-    hipLaunchKernelGGL(k3_psign, dim3(grid3(n), 3), dim3(kT), 0, st, q, g);
+    if (vec == 4) hipLaunchKernelGGL(k3_psign<4>, dim3(grid3(n / 4), 3), dim3(kT), 0, st, q, g);
+    else          hipLaunchKernelGGL(k3_psign<1>, dim3(grid3(n), 3), dim3(kT), 0, st, q, g);
     MPC_HIP(c, hipGetLastError());
     {
         CopySeg cp[6]; int k = 0;
