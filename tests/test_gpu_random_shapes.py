@@ -121,3 +121,59 @@ def test_random_relu_sizes_both_chains(mpc, lane):
         same(mpc, lane, y, want.y, f"relu n={n}"); same(mpc, lane, sa, want.s_arith, "sign shares")
         y, sb, sa = lane.relu(dev(mpc, xs), lane.pack_material(md), n_chunks=chunks, want_sign=True, packed=True)
         same(mpc, lane, y, want.y, f"packed relu n={n}"); same(mpc, lane, sb, want.s_bit, "packed sign bits")
+
+
+# ------------------------------------------------------------------ three parties
+def dev3(mpc, tri):
+    return tuple(mpc.to_device(v) for v in tri)
+
+
+def same3(mpc, lane, got, want, what):
+    lane.sync()
+    for i in range(3):
+        g = mpc.to_host(got[i]).reshape(np.shape(want[i]))
+        assert np.array_equal(g, want[i]), f"{what}: party {i} differs in {(g != want[i]).sum()} of {g.size} words"
+
+
+def test_random_three_party_products_and_rescale(mpc, lane):
+    rng = np.random.default_rng(2031)
+    for it in range(16):
+        if rng.integers(0, 2):
+            M, K, N = (int(rng.integers(1, 160)), int(rng.integers(1, 300)), int(rng.integers(1, 160)))
+            print(f"random matmul3 {it}: {M}x{K}x{N}", flush=True)
+            X = synth.normal_fixed(rng, (M, K), 1.0); Y = synth.normal_fixed(rng, (K, N), 0.1)
+            x, y = synth.share_additive3(rng, X), synth.share_additive3(rng, Y)
+            a, b, c = synth.deal_product_triple3(rng, X.shape, Y.shape, oracle.ring_matmul)
+            want = oracle.beaver_matmul3(x, y, a, b, c)
+            z = lane.beaver_matmul3(dev3(mpc, x), dev3(mpc, y), dev3(mpc, a), dev3(mpc, b), dev3(mpc, c))
+        else:
+            B, H, W = int(rng.integers(1, 4)), int(rng.integers(3, 12)), int(rng.integers(3, 12))
+            Cin, Cout = int(rng.integers(1, 40)), int(rng.integers(1, 70))
+            KH = int(rng.choice([1, 3])); pad = int(rng.integers(0, KH // 2 + 1)); stride = int(rng.integers(1, 3))
+            print(f"random conv2d3 {it}: B{B} {H}x{W} {Cin}->{Cout} k{KH} pad {pad} stride {stride}", flush=True)
+            conv = lambda A, Bm: oracle.ring_conv2d(A, Bm, pad, stride)
+            X = synth.normal_fixed(rng, (B, H, W, Cin), 1.0); Y = synth.normal_fixed(rng, (KH, KH, Cin, Cout), 0.1)
+            x, y = synth.share_additive3(rng, X), synth.share_additive3(rng, Y)
+            a, b, c = synth.deal_product_triple3(rng, X.shape, Y.shape, conv)
+            want = oracle.beaver_conv2d3(x, y, a, b, c, pad, stride)
+            z = lane.conv2d3(dev3(mpc, x), dev3(mpc, y), dev3(mpc, a), dev3(mpc, b), dev3(mpc, c), pad, stride)
+        same3(mpc, lane, z, want, "three-party product")
+        r, rt = synth.deal_trunc3_pair(rng, np.shape(want[0]))
+        t = lane.truncate3(z, dev3(mpc, r), dev3(mpc, rt))
+        same3(mpc, lane, t, oracle.truncate3(want, r, rt), "three-party rescale")
+
+
+def test_random_three_party_relu_sizes_both_chains(mpc, lane):
+    rng = np.random.default_rng(2032)
+    for it in range(12):
+        n = int(rng.integers(1, 3000))
+        print(f"random relu3 {it}: n={n}", flush=True)
+        xs = tuple(synth.rand_words(rng, n) for _ in range(3))
+        mat = synth.deal_relu3_material(rng, n)
+        want = oracle.relu3(xs, mat)
+        md = mpc.material_to_device(mat)
+        y, sb, sa = lane.relu3(dev3(mpc, xs), md, want_sign=True)
+        same3(mpc, lane, y, want.y, f"relu3 n={n}"); same3(mpc, lane, sa, want.s_arith, "sign shares")
+        y, sb, sa = lane.relu3(dev3(mpc, xs), lane.pack_material3(md), want_sign=True, packed=True)
+        same3(mpc, lane, y, want.y, f"packed relu3 n={n}"); same3(mpc, lane, sb, want.s_bit, "packed sign bits")
+        same3(mpc, lane, sa, want.s_arith, "packed sign shares")
