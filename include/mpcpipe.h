@@ -514,6 +514,55 @@ int mpc_maxpool3_msb(mpc_ctx* ctx, mpc_cshare3 x, const mpc_relu3_material* mat1
                      const mpc_relu3_material* mat2, mpc_share3 y,
                      int B, int H, int W, int C);
 
+/* Backward pass with three parties (Sec. 4.1 and Sec. 5.3 for N = 3): the
+ * gradient products are Alg. 1 with another bilinear map, as for two parties.
+ * Dense layers: mpc_beaver_matmul3 with MPC_TRANS_X / MPC_TRANS_Y.
+ * mpc_conv2d3_grad_x: g, a [B][Ho][Wo][Cout]; w, b the forward filter layout
+ * [KH][KW][Cin][Cout]; c and gx [B][H][W][Cin]; square filters, pad <= KH-1;
+ * f_public: the opened w - b of the forward pass, or NULL.
+ * mpc_conv2d3_grad_w: x, a [B][H][W][Cin]; g, b [B][Ho][Wo][Cout]; c and gw
+ * [KH][KW][Cin][Cout].  No rescale inside (mpc_truncate3 follows).
+ * Errors as for mpc_conv2d3. */
+size_t mpc_conv2d3_grad_x_workspace_bytes(int B, int H, int W, int Cin, int Cout,
+                                          int KH, int KW, int pad, int stride);
+size_t mpc_conv2d3_grad_w_workspace_bytes(int B, int H, int W, int Cin, int Cout,
+                                          int KH, int KW, int pad, int stride);
+int mpc_conv2d3_grad_x(mpc_ctx* ctx, mpc_cshare3 g, mpc_cshare3 w,
+                       mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 c, mpc_share3 gx,
+                       int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                       int pad, int stride, const uint64_t* f_public);
+int mpc_conv2d3_grad_w(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 g,
+                       mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 c, mpc_share3 gw,
+                       int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                       int pad, int stride);
+
+/* Element-wise Alg. 1 on n words with three parties: z = x * y with the
+ * triple (a, b, c), c = a * b element by element, no rescale.
+ * mpc_relu3_backward: output gradient times the input mask 1 - s; s_arith are
+ * the additive sign shares mpc_relu3 / mpc_relu3_msb returned, the mask
+ * shares are [1 - s]_0 = 1 - [s]_0, [1 - s]_i = -[s]_i.
+ * mpc_maxpool3_signs: mpc_maxpool3 (packed = 0) or mpc_maxpool3_msb that also
+ * returns the sign shares of its two conversions (s1[i]: 2*n_out words, pairs
+ * interleaved as in mat1; s2[i]: n_out words).  mpc_maxpool3_backward routes
+ * the output gradient to the window maxima exactly as
+ * mpc_maxpool2x2_backward does (triples a2, b2, c2 on n_out words, a1, b1, c1
+ * on 2*n_out words).  Workspace: the matching *_workspace_bytes query. */
+size_t mpc_mul3_workspace_bytes(size_t n);
+int mpc_mul3(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 y,
+             mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 c, mpc_share3 z, size_t n);
+int mpc_relu3_backward(mpc_ctx* ctx, mpc_cshare3 g, mpc_cshare3 s_arith,
+                       mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 c, mpc_share3 gx,
+                       size_t n);
+int mpc_maxpool3_signs(mpc_ctx* ctx, mpc_cshare3 x, const mpc_relu3_material* mat1,
+                       const mpc_relu3_material* mat2, mpc_share3 y,
+                       uint64_t* const s1[3], uint64_t* const s2[3],
+                       int B, int H, int W, int C, int packed);
+size_t mpc_maxpool3_backward_workspace_bytes(int B, int H, int W, int C);
+int mpc_maxpool3_backward(mpc_ctx* ctx, mpc_cshare3 g, mpc_cshare3 s1, mpc_cshare3 s2,
+                          mpc_cshare3 a1, mpc_cshare3 b1, mpc_cshare3 c1,
+                          mpc_cshare3 a2, mpc_cshare3 b2, mpc_cshare3 c2,
+                          mpc_share3 gx, int B, int H, int W, int C);
+
 /* -------------------------------------------------- dealer helper (offline) */
 
 /* Plain ring product Z = L*R mod 2^64 on public device arrays, computed with

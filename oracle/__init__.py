@@ -464,15 +464,54 @@ def relu3(x, mat) -> ReluResult:
                       tuple(v.reshape(shp) for v in sa))
 
 
-def maxpool2x2_3(x, mat1, mat2):
+def maxpool2x2_3(x, mat1, mat2, want_signs=False):
     """Three-party 2x2 max-pool by max(p,q) = q + ReLU(p-q): the local gathers of
-    maxpool2x2 on every party's share, the two conversions by relu3."""
+    maxpool2x2 on every party's share, the two conversions by relu3.  With
+    want_signs also the additive sign shares of the two conversions."""
     B, H, W, C = np.shape(x[0])
-    r1 = relu3(tuple(pool_level1(x[p]) for p in range(3)), mat1).y
+    c1 = relu3(tuple(pool_level1(x[p]) for p in range(3)), mat1); r1 = c1.y
     lv2 = [pool_level2(x[p], r1[p]) for p in range(3)]
-    r2 = relu3(tuple(q[1] for q in lv2), mat2).y
+    c2 = relu3(tuple(q[1] for q in lv2), mat2); r2 = c2.y
     shp = (B, H // 2, W // 2, C)
-    return tuple((lv2[p][0] + r2[p]).reshape(shp) for p in range(3))
+    y = tuple((lv2[p][0] + r2[p]).reshape(shp) for p in range(3))
+    return (y, c1.s_arith, c2.s_arith) if want_signs else y
+
+
+def beaver_bilinear3(product, p, q, a, b, c):
+    """beaver_bilinear with three parties (Alg. 1 for N = 3): e = p - a and f = q - b
+    opened from three shares; party 0 adds product(e, f)."""
+    u = lambda v: np.asarray(v, U64)
+    e = open3(tuple(u(p[i]) - u(a[i]) for i in range(3)))
+    f = open3(tuple(u(q[i]) - u(b[i]) for i in range(3)))
+    z = [u(c[i]) + product(e, b[i]) + product(a[i], f) for i in range(3)]
+    z[0] = z[0] + product(e, f)
+    return tuple(z)
+
+
+def relu_backward3(g, s_arith, a, b, c):
+    """relu_backward with three parties: mask shares [1 - s]_0 = 1 - [s]_0, [1 - s]_i = -[s]_i."""
+    m = tuple(U64(1 if i == 0 else 0) - np.asarray(s_arith[i], U64) for i in range(3))
+    return beaver_mul3(g, m, a, b, c)
+
+
+def maxpool2x2_backward3(g, s1, s2, t1, t2, x_shape):
+    """maxpool2x2_backward with three parties: the same two element-wise products
+    (Sec. 5.3) and local sums, on triples of shares."""
+    B, H, W, C = x_shape
+    gs = tuple(np.asarray(v, U64).reshape(-1) for v in g)
+    gu = relu_backward3(gs, s2, *t2)
+    gv = tuple(gs[i] - gu[i] for i in range(3))
+    G1 = tuple(np.stack([gu[i], gv[i]], axis=1).reshape(-1) for i in range(3))
+    P = relu_backward3(G1, s1, *t1)
+    out = []
+    for i in range(3):
+        Pi = P[i].reshape(B, H // 2, W // 2, C, 2)
+        gui = gu[i].reshape(B, H // 2, W // 2, C); gvi = gv[i].reshape(B, H // 2, W // 2, C)
+        gx = np.empty((B, H // 2, 2, W // 2, 2, C), dtype=U64)
+        gx[:, :, 0, :, 0, :] = Pi[..., 0];       gx[:, :, 0, :, 1, :] = gui - Pi[..., 0]
+        gx[:, :, 1, :, 0, :] = Pi[..., 1];       gx[:, :, 1, :, 1, :] = gvi - Pi[..., 1]
+        out.append(gx.reshape(B, H, W, C))
+    return tuple(out)
 
 
 # --------------------------------------------- checkers on reconstructed values

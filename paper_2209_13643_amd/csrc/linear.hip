@@ -441,7 +441,7 @@ LinearWs3 carve3(u8* base, size_t cap, const LinearShape& s)
 // contraction [e | a_i] x [b_i (+ f for party 0) ; f] for parties 0 and 1 in
 // one launch and for party 2 in a second one.
 int beaver_linear3(mpc_ctx* c, const LinearShape& s, mpc_cshare3 x, mpc_cshare3 y,
-                   mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 cc, mpc_share3 z, const u64* f_public)
+                   mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 cc, mpc_share3 z, const u64* f_public, size_t ws_off = 0)
 {
     if (!c) return MPC_EINVAL;
     MPC_TRY(check_shape(s));
@@ -449,7 +449,8 @@ int beaver_linear3(mpc_ctx* c, const LinearShape& s, mpc_cshare3 x, mpc_cshare3 
         if (!x.p[i] || !a.p[i] || !b.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
         if (!f_public && !y.p[i]) return MPC_EINVAL;
     }
-    LinearWs3 w = carve3(c->ws, c->ws_bytes, s);
+    if (ws_off > c->ws_bytes) return MPC_ENOMEM;
+    LinearWs3 w = carve3(c->ws ? c->ws + ws_off : nullptr, c->ws_bytes - ws_off, s);
     if (!w.ok) return MPC_ENOMEM;
     hipStream_t st = c->s[0];
     MPC_TRY(lane_join(c));
@@ -795,6 +796,61 @@ int mpc_conv2d3(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 w, mpc_cshare3 a, mpc_c
     if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
         return MPC_EINVAL;
     return beaver_linear3(ctx, shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride), x, w, a, b, c, z, f_public);
+}
+
+size_t mpc_conv2d3_grad_x_workspace_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (stride <= 0 || KH != KW || KH <= 0 || pad < 0 || pad > KH - 1 || H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return 0;
+    LinearShape s = shape_conv_grad_x(B, H, W, Cin, Cout, KH, KW, pad);
+    if (check_shape(s) != MPC_OK) return 0;
+    // a strided layer first scatters g_i and its mask a_i (three parties) into the dilated grid
+    const size_t extra = stride > 1 ? 6 * align_up(dilated_geom(B, H, W, Cout, KH, KW, pad, stride).words * sizeof(u64)) : 0;
+    return extra + carve3(nullptr, 0, s).bytes;
+}
+
+size_t mpc_conv2d3_grad_w_workspace_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (stride <= 0 || KH <= 0 || KW <= 0 || pad < 0 || H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return 0;
+    LinearShape s = shape_conv_grad_w(B, H, W, Cin, Cout, KH, KW, pad, stride);
+    if (check_shape(s) != MPC_OK) return 0;
+    return carve3(nullptr, 0, s).bytes;
+}
+
+int mpc_conv2d3_grad_x(mpc_ctx* ctx, mpc_cshare3 g, mpc_cshare3 w, mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 c,
+                       mpc_share3 gx, int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride,
+                       const uint64_t* f_public)
+{
+    if (!ctx || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0 || stride <= 0) return MPC_EINVAL;
+    if (KH != KW || pad > KH - 1 || H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return MPC_EINVAL;
+    const LinearShape s = shape_conv_grad_x(B, H, W, Cin, Cout, KH, KW, pad);
+    if (stride == 1) return beaver_linear3(ctx, s, g, w, a, b, c, gx, f_public);
+    for (int i = 0; i < 3; ++i) if (!g.p[i] || !a.p[i]) return MPC_EINVAL;
+    const DilatedGeom d = dilated_geom(B, H, W, Cout, KH, KW, pad, stride);
+    WsAlloc wa(ctx->ws, ctx->ws_bytes);
+    u64* gd[3]; u64* ad[3];
+    for (int i = 0; i < 3; ++i) { gd[i] = wa.take<u64>(d.words); ad[i] = wa.take<u64>(d.words); }
+    if (!wa.ok) return MPC_ENOMEM;
+    MPC_TRY(lane_join(ctx));
+    // the scatter kernel takes four tensors per launch: parties 0 and 1, then party 2
+    for (int first = 0; first < 3; first += 2) {
+        DilateArgs q{};
+        for (int i = first, k = 0; i < 3 && k < 2; ++i, ++k) {
+            q.src[2 * k] = g.p[i]; q.dst[2 * k] = gd[i]; q.src[2 * k + 1] = a.p[i]; q.dst[2 * k + 1] = ad[i];
+        }
+        q.B = B; q.Ho = d.Ho; q.Wo = d.Wo; q.Hd = d.Hd; q.Wd = d.Wd; q.C = Cout; q.stride = stride;
+        MPC_TRY(launch_dilate(ctx, ctx->s[0], q));
+    }
+    const mpc_cshare3 gs = { { gd[0], gd[1], gd[2] } }, as = { { ad[0], ad[1], ad[2] } };
+    return beaver_linear3(ctx, s, gs, w, as, b, c, gx, f_public, wa.off);
+}
+
+int mpc_conv2d3_grad_w(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 g, mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 c,
+                       mpc_share3 gw, int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
+        return MPC_EINVAL;
+    if (H + 2 * pad - KH < 0 || W + 2 * pad - KW < 0) return MPC_EINVAL;
+    return beaver_linear3(ctx, shape_conv_grad_w(B, H, W, Cin, Cout, KH, KW, pad, stride), x, g, a, b, c, gw, nullptr);
 }
 
 }  // extern "C"

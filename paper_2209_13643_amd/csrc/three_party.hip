@@ -627,6 +627,104 @@ __global__ __launch_bounds__(kT) void k3_pool(Pool3Args q)
     }
 }
 
+// ---- element-wise Alg. 1 with three parties, and the backward steps built on it ------
+struct Mul3Args {
+    const u64 *x[3], *y[3], *a[3], *b[3], *c[3];
+    u64 *se[3], *sf[3];                       // own masked words
+    const u64 *re[3][2], *rf[3][2];           // the masked words of party+1 / party+2
+    u64* z[3];
+    size_t n; int mask_from_sign;             // mask_from_sign: y holds sign shares s, the factor is 1 - s
+};
+
+__global__ __launch_bounds__(kT) void k3_mul_mask(Mul3Args q)
+{
+    const int i = blockIdx.y;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < q.n; k += stride) {
+        u64 y = q.y[i][k];
+        if (q.mask_from_sign) y = (i == 0 ? (u64)1 : (u64)0) - y;
+        q.se[i][k] = q.x[i][k] - q.a[i][k];
+        q.sf[i][k] = y - q.b[i][k];
+    }
+}
+
+__global__ __launch_bounds__(kT) void k3_mul_finish(Mul3Args q)
+{
+    const int i = blockIdx.y;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < q.n; k += stride) {
+        const u64 e = q.se[i][k] + q.re[i][0][k] + q.re[i][1][k], f = q.sf[i][k] + q.rf[i][0][k] + q.rf[i][1][k];
+        u64 z = q.c[i][k] + e * q.b[i][k] + q.a[i][k] * f;
+        if (i == 0) z += e * f;
+        q.z[i][k] = z;
+    }
+}
+
+size_t mul3_ws_bytes(size_t n) { return 18 * align_up(n * sizeof(u64)); }
+
+// z = x * y element by element (no rescale); ws_off: bytes of the workspace the caller keeps for itself
+int mul3_run(mpc_ctx* c, hipStream_t st, const u64* const x[3], const u64* const y[3], const u64* const a[3],
+             const u64* const b[3], const u64* const cc[3], u64* const z[3], size_t n, int mask_from_sign, size_t ws_off)
+{
+    if (ws_off > c->ws_bytes) return MPC_ENOMEM;
+    WsAlloc ws(c->ws ? c->ws + ws_off : nullptr, c->ws_bytes - ws_off);
+    Mul3Args q{};
+    u64 *re[3][2], *rf[3][2];
+    for (int i = 0; i < 3; ++i) {
+        q.se[i] = ws.take<u64>(n); q.sf[i] = ws.take<u64>(n);
+        for (int k = 0; k < 2; ++k) { re[i][k] = ws.take<u64>(n); rf[i][k] = ws.take<u64>(n); q.re[i][k] = re[i][k]; q.rf[i][k] = rf[i][k]; }
+    }
+    if (!ws.ok) return MPC_ENOMEM;
+    for (int i = 0; i < 3; ++i) { q.x[i] = x[i]; q.y[i] = y[i]; q.a[i] = a[i]; q.b[i] = b[i]; q.c[i] = cc[i]; q.z[i] = z[i]; }
+    q.n = n; q.mask_from_sign = mask_from_sign;
+    hipLaunchKernelGGL(k3_mul_mask, dim3(grid3(n), 3), dim3(kT), 0, st, q);
+    MPC_HIP(c, hipGetLastError());
+    // both masked words of every party go to both peers: two launches of six copies
+    for (int what = 0; what < 2; ++what) {
+        CopySeg cp[6]; int k = 0;
+        for (int i = 0; i < 3; ++i)
+            for (int sdx = 0; sdx < 2; ++sdx) {
+                const int from = (i + 1 + sdx) % 3;
+                cp[k++] = CopySeg{ (const u8*)(what ? q.sf[from] : q.se[from]), (u8*)(what ? rf[i][sdx] : re[i][sdx]), n * sizeof(u64), 0 };
+            }
+        MPC_TRY(launch_copy_multi(c, st, cp, 6));
+    }
+    hipLaunchKernelGGL(k3_mul_finish, dim3(grid3(n), 3), dim3(kT), 0, st, q);
+    MPC_HIP(c, hipGetLastError());
+    return MPC_OK;
+}
+
+// max-pool backward: the local steps around its two element-wise products (blockIdx.y = party)
+struct PoolBwd3Args { const u64* g[3]; const u64* gu[3]; u64* pairs[3]; const u64* prod[3]; u64* gx[3]; size_t n_out; int B, H, W, C; };
+
+// STEP 0: grad_v = g - grad_u, the pair (grad_u, grad_v) interleaved as the first tournament level stored its pairs
+// STEP 1: after P = pairs * mask1 the four window positions receive P[2o], grad_u - P[2o], P[2o+1], grad_v - P[2o+1]
+template <int STEP>
+__global__ __launch_bounds__(kT) void k3_poolbwd(PoolBwd3Args q)
+{
+    const int i = blockIdx.y;
+    const int Ho = q.H / 2, Wo = q.W / 2;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < q.n_out; o += stride) {
+        if constexpr (STEP == 0) {
+            const u64 gu = q.gu[i][o];
+            q.pairs[i][2 * o] = gu;
+            q.pairs[i][2 * o + 1] = q.g[i][o] - gu;
+        } else {
+            const int ch = (int)(o % q.C); size_t t = o / q.C;
+            const int wo = (int)(t % Wo); t /= Wo;
+            const int ho = (int)(t % Ho); const int b = (int)(t / Ho);
+            const size_t base = (((size_t)b * q.H + 2 * ho) * q.W + 2 * wo) * q.C + ch;
+            const size_t dw = q.C, dh = (size_t)q.W * q.C;
+            const u64 p0 = q.prod[i][2 * o], p1 = q.prod[i][2 * o + 1];
+            const u64 gu = q.pairs[i][2 * o], gv = q.pairs[i][2 * o + 1];
+            u64* gx = q.gx[i];
+            gx[base] = p0;            gx[base + dw] = gu - p0;
+            gx[base + dh] = p1;       gx[base + dh + dw] = gv - p1;
+        }
+    }
+}
+
 template <int STEP>
 int launch_pool(mpc_ctx* c, hipStream_t st, const Pool3Args& q, size_t n_out)
 {
@@ -770,7 +868,8 @@ size_t mpc_maxpool3_workspace_bytes(int B, int H, int W, int C) { return maxpool
 size_t mpc_maxpool3_msb_workspace_bytes(int B, int H, int W, int C) { return maxpool3_ws(B, H, W, C, true); }
 
 static int maxpool3_entry(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* mat1, const mpc_relu3_material* mat2,
-                          mpc_share3 y, int B, int H, int W, int C, bool packed)
+                          mpc_share3 y, int B, int H, int W, int C, bool packed,
+                          uint64_t* const s1[3] = nullptr, uint64_t* const s2[3] = nullptr)
 {
     if (!c || B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1)) return MPC_EINVAL;
     MPC_TRY(check_material3(mat1));
@@ -801,8 +900,8 @@ static int maxpool3_entry(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* m
         relu3_ws(rest, room, relu3_chunk_cap(n_out), &q2, &ok2);
     }
     if (!ok1 || !ok2) return MPC_ENOMEM;
-    fill3(q1, pq.d1, mat1, r1, nullptr, nullptr, 2 * n_out);
-    fill3(q2, pq.d2, mat2, y.p, nullptr, nullptr, n_out);
+    fill3(q1, pq.d1, mat1, r1, nullptr, s1, 2 * n_out);
+    fill3(q2, pq.d2, mat2, y.p, nullptr, s2, n_out);
     if (packed) { q1.tn = g1.toff[1]; q2.tn = g2.toff[1]; }
     hipStream_t st = c->s[0];
     MPC_TRY(lane_join(c));
@@ -824,6 +923,77 @@ int mpc_maxpool3_msb(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* mat1, 
                      mpc_share3 y, int B, int H, int W, int C)
 {
     return maxpool3_entry(c, x, mat1, mat2, y, B, H, W, C, true);
+}
+
+int mpc_maxpool3_signs(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* mat1, const mpc_relu3_material* mat2,
+                       mpc_share3 y, uint64_t* const s1[3], uint64_t* const s2[3],
+                       int B, int H, int W, int C, int packed)
+{
+    if (!s1 || !s2) return MPC_EINVAL;
+    for (int i = 0; i < 3; ++i) if (!s1[i] || !s2[i]) return MPC_EINVAL;
+    return maxpool3_entry(c, x, mat1, mat2, y, B, H, W, C, packed != 0, s1, s2);
+}
+
+size_t mpc_mul3_workspace_bytes(size_t n) { return n ? mul3_ws_bytes(n) : 0; }
+
+int mpc_mul3(mpc_ctx* c, mpc_cshare3 x, mpc_cshare3 y, mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 cc, mpc_share3 z, size_t n)
+{
+    if (!c || n == 0) return MPC_EINVAL;
+    for (int i = 0; i < 3; ++i) if (!x.p[i] || !y.p[i] || !a.p[i] || !b.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
+    hipStream_t st = c->s[0];
+    MPC_TRY(lane_join(c));
+    MPC_TRY(mul3_run(c, st, x.p, y.p, a.p, b.p, cc.p, z.p, n, 0, 0));
+    return lane_fanout(c);
+}
+
+int mpc_relu3_backward(mpc_ctx* c, mpc_cshare3 g, mpc_cshare3 s_arith, mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 cc,
+                       mpc_share3 gx, size_t n)
+{
+    if (!c || n == 0) return MPC_EINVAL;
+    for (int i = 0; i < 3; ++i) if (!g.p[i] || !s_arith.p[i] || !a.p[i] || !b.p[i] || !cc.p[i] || !gx.p[i]) return MPC_EINVAL;
+    hipStream_t st = c->s[0];
+    MPC_TRY(lane_join(c));
+    MPC_TRY(mul3_run(c, st, g.p, s_arith.p, a.p, b.p, cc.p, gx.p, n, 1, 0));
+    return lane_fanout(c);
+}
+
+size_t mpc_maxpool3_backward_workspace_bytes(int B, int H, int W, int C)
+{
+    if (B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1)) return 0;
+    const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
+    // per party grad_u (n_out), pairs and their product (2 n_out each); then the larger product's scratch
+    return 3 * (align_up(n_out * 8) + 2 * align_up(2 * n_out * 8)) + mul3_ws_bytes(2 * n_out);
+}
+
+int mpc_maxpool3_backward(mpc_ctx* c, mpc_cshare3 g, mpc_cshare3 s1, mpc_cshare3 s2,
+                          mpc_cshare3 a1, mpc_cshare3 b1, mpc_cshare3 c1,
+                          mpc_cshare3 a2, mpc_cshare3 b2, mpc_cshare3 c2,
+                          mpc_share3 gx, int B, int H, int W, int C)
+{
+    if (!c || B <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1)) return MPC_EINVAL;
+    for (int i = 0; i < 3; ++i)
+        if (!g.p[i] || !s1.p[i] || !s2.p[i] || !gx.p[i] || !a1.p[i] || !b1.p[i] || !c1.p[i] || !a2.p[i] || !b2.p[i] || !c2.p[i])
+            return MPC_EINVAL;
+    const size_t n_out = (size_t)B * (H / 2) * (W / 2) * C;
+    WsAlloc ws(c->ws, c->ws_bytes);
+    u64 *gu[3], *pairs[3], *prod[3];
+    for (int i = 0; i < 3; ++i) { gu[i] = ws.take<u64>(n_out); pairs[i] = ws.take<u64>(2 * n_out); prod[i] = ws.take<u64>(2 * n_out); }
+    if (!ws.ok) return MPC_ENOMEM;
+    const size_t off = ws.off;
+    hipStream_t st = c->s[0];
+    MPC_TRY(lane_join(c));
+    // grad_u = g * (1 - s2)
+    MPC_TRY(mul3_run(c, st, g.p, s2.p, a2.p, b2.p, c2.p, gu, n_out, 1, off));
+    PoolBwd3Args q{};
+    for (int i = 0; i < 3; ++i) { q.g[i] = g.p[i]; q.gu[i] = gu[i]; q.pairs[i] = pairs[i]; q.prod[i] = prod[i]; q.gx[i] = gx.p[i]; }
+    q.n_out = n_out; q.B = B; q.H = H; q.W = W; q.C = C;
+    hipLaunchKernelGGL(k3_poolbwd<0>, dim3(grid3(n_out), 3), dim3(kT), 0, st, q);
+    MPC_HIP(c, hipGetLastError());
+    // (grad_p00, grad_p10) = (grad_u, grad_v) * (1 - s1)
+    MPC_TRY(mul3_run(c, st, pairs, s1.p, a1.p, b1.p, c1.p, prod, 2 * n_out, 1, off));
+    hipLaunchKernelGGL(k3_poolbwd<1>, dim3(grid3(n_out), 3), dim3(kT), 0, st, q);
+    MPC_HIP(c, hipGetLastError());
+    return lane_fanout(c);
 }
 
 }  // extern "C"

@@ -69,6 +69,9 @@ EXPORTS = [
     "mpc_maxpool3_workspace_bytes", "mpc_maxpool3",
     "mpc_relu3_packed_words", "mpc_relu3_pack_triples", "mpc_relu3_msb_workspace_bytes", "mpc_relu3_msb",
     "mpc_maxpool3_msb_workspace_bytes", "mpc_maxpool3_msb",
+    "mpc_conv2d3_grad_x_workspace_bytes", "mpc_conv2d3_grad_w_workspace_bytes", "mpc_conv2d3_grad_x", "mpc_conv2d3_grad_w",
+    "mpc_mul3_workspace_bytes", "mpc_mul3", "mpc_relu3_backward", "mpc_maxpool3_signs",
+    "mpc_maxpool3_backward_workspace_bytes", "mpc_maxpool3_backward",
 ]
 
 _lib = None
@@ -161,6 +164,17 @@ def lib():
     L.mpc_relu3_msb.argtypes = L.mpc_relu3.argtypes
     L.mpc_maxpool3_msb_workspace_bytes.argtypes = [c_int] * 4; L.mpc_maxpool3_msb_workspace_bytes.restype = c_size_t
     L.mpc_maxpool3_msb.argtypes = L.mpc_maxpool3.argtypes
+    for fn in (L.mpc_conv2d3_grad_x_workspace_bytes, L.mpc_conv2d3_grad_w_workspace_bytes):
+        fn.argtypes = [c_int] * 9; fn.restype = c_size_t
+    L.mpc_conv2d3_grad_x.argtypes = [c_void_p] + [CShare3] * 6 + [c_int] * 9 + [_P64]
+    L.mpc_conv2d3_grad_w.argtypes = [c_void_p] + [CShare3] * 6 + [c_int] * 9
+    L.mpc_mul3_workspace_bytes.argtypes = [c_size_t]; L.mpc_mul3_workspace_bytes.restype = c_size_t
+    L.mpc_mul3.argtypes = [c_void_p] + [CShare3] * 6 + [c_size_t]
+    L.mpc_relu3_backward.argtypes = [c_void_p] + [CShare3] * 6 + [c_size_t]
+    L.mpc_maxpool3_signs.argtypes = [c_void_p, CShare3, POINTER(Relu3Material), POINTER(Relu3Material), CShare3,
+                                     POINTER(_P64 * 3), POINTER(_P64 * 3)] + [c_int] * 5
+    L.mpc_maxpool3_backward_workspace_bytes.argtypes = [c_int] * 4; L.mpc_maxpool3_backward_workspace_bytes.restype = c_size_t
+    L.mpc_maxpool3_backward.argtypes = [c_void_p] + [CShare3] * 10 + [c_int] * 4
     _lib = L
     return L
 
@@ -604,16 +618,75 @@ class Lane:
         self._check(fn(self._h, _share3(x), byref(m), _share3(y), n, None, None))
         return y
 
-    def maxpool3(self, x, mat1, mat2, packed=False):
+    def maxpool3(self, x, mat1, mat2, packed=False, want_signs=False):
+        """Three-party 2x2 max-pool; want_signs=True also returns the sign shares (s1, s2) the backward pass needs."""
         B, H, W, C = x[0].shape
         n_out = B * (H // 2) * (W // 2) * C
         ws = lib().mpc_maxpool3_msb_workspace_bytes if packed else lib().mpc_maxpool3_workspace_bytes
         self.reserve(ws(B, H, W, C))
         y = tuple(torch.empty((B, H // 2, W // 2, C), dtype=torch.int64, device=self.device) for _ in range(3))
         m1, m2 = _material3(mat1, 2 * n_out, packed), _material3(mat2, n_out, packed)
+        if want_signs:
+            s1 = tuple(torch.empty(2 * n_out, dtype=torch.int64, device=self.device) for _ in range(3))
+            s2 = tuple(torch.empty(n_out, dtype=torch.int64, device=self.device) for _ in range(3))
+            p1 = (_P64 * 3)(*[_p64(t) for t in s1]); p2 = (_P64 * 3)(*[_p64(t) for t in s2])
+            self._check(lib().mpc_maxpool3_signs(self._h, _share3(x), byref(m1), byref(m2), _share3(y), byref(p1), byref(p2),
+                                                 B, H, W, C, 1 if packed else 0))
+            return y, s1, s2
         fn = lib().mpc_maxpool3_msb if packed else lib().mpc_maxpool3
         self._check(fn(self._h, _share3(x), byref(m1), byref(m2), _share3(y), B, H, W, C))
         return y
+
+    def conv2d3_grad_x(self, g, w, a, b, c, pad, stride=1, f_public=None, out=None):
+        """Input gradient of conv2d3 (no rescale): g, a [B,Ho,Wo,Cout]; w, b [KH,KW,Cin,Cout]; c and result [B,H,W,Cin]."""
+        B, H, W, Cin = c[0].shape
+        KH, KW, Cin2, Cout = b[0].shape
+        if Cin != Cin2 or a[0].shape[-1] != Cout:
+            raise ValueError("operand shapes do not match")
+        self.reserve(lib().mpc_conv2d3_grad_x_workspace_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride))
+        gx = out if out is not None else self._empty3(c[0])
+        self._check(lib().mpc_conv2d3_grad_x(self._h, _share3(g), _share3(w), _share3(a), _share3(b), _share3(c), _share3(gx),
+                                             B, H, W, Cin, Cout, KH, KW, pad, stride, _p64(f_public)))
+        return gx
+
+    def conv2d3_grad_w(self, x, g, a, b, c, pad, stride, out=None):
+        """Filter gradient of conv2d3 (no rescale): x, a [B,H,W,Cin]; g, b [B,Ho,Wo,Cout]; c and result [KH,KW,Cin,Cout]."""
+        B, H, W, Cin = a[0].shape
+        KH, KW, Cin2, Cout = c[0].shape
+        if Cin != Cin2 or b[0].shape[-1] != Cout:
+            raise ValueError("operand shapes do not match")
+        self.reserve(lib().mpc_conv2d3_grad_w_workspace_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride))
+        gw = out if out is not None else self._empty3(c[0])
+        self._check(lib().mpc_conv2d3_grad_w(self._h, _share3(x), _share3(g), _share3(a), _share3(b), _share3(c), _share3(gw),
+                                             B, H, W, Cin, Cout, KH, KW, pad, stride))
+        return gw
+
+    def mul3(self, x, y, a, b, c, out=None):
+        """Element-wise Alg. 1 with three parties (no rescale)."""
+        n = x[0].numel()
+        self.reserve(lib().mpc_mul3_workspace_bytes(n))
+        z = out if out is not None else self._empty3(x[0])
+        self._check(lib().mpc_mul3(self._h, _share3(x), _share3(y), _share3(a), _share3(b), _share3(c), _share3(z), n))
+        return z
+
+    def relu3_backward(self, g, s_arith, a, b, c, out=None):
+        """Output gradient times the ReLU input mask 1 - s (s_arith from the forward relu3)."""
+        n = g[0].numel()
+        self.reserve(lib().mpc_mul3_workspace_bytes(n))
+        gx = out if out is not None else self._empty3(g[0])
+        self._check(lib().mpc_relu3_backward(self._h, _share3(g), _share3(s_arith), _share3(a), _share3(b), _share3(c),
+                                             _share3(gx), n))
+        return gx
+
+    def maxpool3_backward(self, g, s1, s2, t1, t2, x_shape):
+        """Gradient of maxpool3 w.r.t. its input; t1 / t2: element-wise triples (a, b, c) on 2*n_out / n_out words."""
+        B, H, W, C = x_shape
+        self.reserve(lib().mpc_maxpool3_backward_workspace_bytes(B, H, W, C))
+        gx = tuple(torch.empty(tuple(x_shape), dtype=torch.int64, device=self.device) for _ in range(3))
+        self._check(lib().mpc_maxpool3_backward(self._h, _share3(g), _share3(s1), _share3(s2),
+                                                _share3(t1[0]), _share3(t1[1]), _share3(t1[2]),
+                                                _share3(t2[0]), _share3(t2[1]), _share3(t2[2]), _share3(gx), B, H, W, C))
+        return gx
 
     def truncate(self, z, bits=16):
         self._check(lib().mpc_truncate(self._h, _share(z), z[0].numel(), bits))

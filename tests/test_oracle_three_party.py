@@ -292,3 +292,64 @@ def test_maxpool3_is_the_window_maximum():
                             synth.deal_relu3_material(rng, n_out))
     want = X.view(np.int64).reshape(B, H // 2, 2, W // 2, 2, C).max(axis=(2, 4))
     assert np.array_equal(rec3(y).view(np.int64), want)
+
+
+# --------------------------------------------------------------- backward pass
+def test_beaver_bilinear3_reconstructs_the_gradient_products():
+    """Alg. 1 with the two gradient maps of a convolution in place of the product: the three
+    shares reconstruct to the plain ring gradient, whatever the triple and the sharing."""
+    rng = np.random.default_rng(501)
+    B, H, W, Cin, Cout, KH, pad, stride = 2, 6, 5, 3, 4, 3, 1, 2
+    X = synth.rand_words(rng, (B, H, W, Cin)); Wt = synth.rand_words(rng, (KH, KH, Cin, Cout))
+    Ho, Wo = oracle.conv_out_hw(H, W, KH, KH, pad, stride)
+    G = synth.rand_words(rng, (B, Ho, Wo, Cout))
+    gx_map = lambda g, w: oracle.ring_conv2d_grad_x(g, w, X.shape, pad, stride)
+    gw_map = lambda x, g: oracle.ring_conv2d_grad_w(x, g, KH, KH, pad, stride)
+    for trial in range(2):
+        gs, ws, xs = (synth.share_additive3(rng, v) for v in (G, Wt, X))
+        a, b, c = synth.deal_product_triple3(rng, G.shape, Wt.shape, gx_map)
+        assert np.array_equal(rec3(oracle.beaver_bilinear3(gx_map, gs, ws, a, b, c)), gx_map(G, Wt))
+        a, b, c = synth.deal_product_triple3(rng, X.shape, G.shape, gw_map)
+        assert np.array_equal(rec3(oracle.beaver_bilinear3(gw_map, xs, gs, a, b, c)), gw_map(X, G))
+    # with an empty third party it is the two-party composition word for word
+    z2 = lambda n: np.zeros(n, dtype=U64)
+    g2, w2 = synth.share_additive(rng, G), synth.share_additive(rng, Wt)
+    a2, b2, c2 = synth.deal_product_triple(rng, G.shape, Wt.shape, gx_map)
+    want = oracle.beaver_bilinear(gx_map, g2, w2, a2, b2, c2)
+    pad3 = lambda pair: (pair[0], pair[1], z2(np.shape(pair[0])))
+    got = oracle.beaver_bilinear3(gx_map, pad3(g2), pad3(w2), pad3(a2), pad3(b2), pad3(c2))
+    assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]) and not got[2].any()
+
+
+def test_relu_backward3_is_gradient_times_the_input_mask():
+    rng = np.random.default_rng(502)
+    n = 300
+    X = rng.integers(-(1 << 20), 1 << 20, size=n).astype(np.int64); X[:3] = (0, -1, 1)
+    G = rng.integers(-(1 << 30), 1 << 30, size=n).astype(np.int64)
+    fwd = oracle.relu3(synth.share_additive3(rng, X.view(U64)), synth.deal_relu3_material(rng, n))
+    t = synth.deal_product_triple3(rng, (n,), (n,), lambda p, q: p * q)
+    gx = oracle.relu_backward3(synth.share_additive3(rng, G.view(U64)), fwd.s_arith, *t)
+    assert np.array_equal(oracle.to_signed(rec3(gx)), np.where(X >= 0, G, 0))
+
+
+def test_maxpool_backward3_routes_gradient_to_the_window_maximum():
+    """Against autograd of torch's max_pool2d on integers with a unique maximum per window."""
+    import torch
+    rng = np.random.default_rng(503)
+    B, H, W, C = 2, 4, 6, 3
+    Xi = rng.permutation(B * H * W * C).reshape(B, H, W, C).astype(np.int64) - 70
+    Gi = rng.integers(-1000, 1000, size=(B, H // 2, W // 2, C)).astype(np.int64)
+    xs = synth.share_additive3(rng, Xi.view(U64)); gs = synth.share_additive3(rng, Gi.view(U64))
+    n_out = Gi.size
+    y, s1, s2 = oracle.maxpool2x2_3(xs, synth.deal_relu3_material(rng, 2 * n_out), synth.deal_relu3_material(rng, n_out),
+                                    want_signs=True)
+    mul = lambda p, q: p * q
+    t1 = synth.deal_product_triple3(rng, (2 * n_out,), (2 * n_out,), mul)
+    t2 = synth.deal_product_triple3(rng, (n_out,), (n_out,), mul)
+    gx = oracle.maxpool2x2_backward3(gs, s1, s2, t1, t2, Xi.shape)
+    xt = torch.from_numpy(Xi).double().permute(0, 3, 1, 2).requires_grad_()
+    torch.nn.functional.max_pool2d(xt, 2).backward(torch.from_numpy(Gi).double().permute(0, 3, 1, 2))
+    assert np.array_equal(oracle.to_signed(rec3(gx)), xt.grad.permute(0, 2, 3, 1).numpy().astype(np.int64))
+    assert np.array_equal(oracle.to_signed(rec3(y)), Xi.reshape(B, H // 2, 2, W // 2, 2, C).max(axis=(2, 4)))
+    # the sign shares reconstruct to 0 / 1
+    assert set(np.unique(rec3(s1))) <= {0, 1} and set(np.unique(rec3(s2))) <= {0, 1}
