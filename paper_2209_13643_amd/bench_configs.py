@@ -233,6 +233,45 @@ def bench_training(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_r
     return res
 
 
+def bench_training3(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = True):
+    """bench_training's step (forward with tape + backward, no update) with three simulated parties."""
+    wl = synth.config_vgg16_pipeline(micro_batch)
+    layers = wl.layers
+    lanes = [mpc.Lane(0) for _ in range(n_mb)]
+    for ln in lanes:
+        ln.use_single_queue()
+    dev = lanes[0].device
+    g = dealer.gen(synth.BASE_SEED + 71, dev)
+    weights = pipeline.deal_weights3(g, layers, dev)
+    states, bstates, xs, gouts = [], [], [], []
+    for m in range(n_mb):
+        states.append(pipeline.deal_microbatch3(lanes[m], g, layers, weights, packed_relu=packed_relu))
+        bstates.append(pipeline.deal_backward3(lanes[m], g, layers, states[m]))
+        xs.append(dealer.share3(g, dealer.normal_fixed(g, (micro_batch, 32, 32, 3), 1.0, dev)))
+        gouts.append(dealer.share3(g, dealer.normal_fixed(g, (micro_batch, 10), 0.1, dev)))
+        torch.cuda.synchronize()
+        pipeline.preopen_weights3(lanes[m], states[m])
+    res = {}
+    for mode in ("serial", "pipelined"):
+        best = None
+        for _ in range(reps + 1):
+            keep = []
+            torch.cuda.synchronize(); t0 = time.perf_counter()
+            for m in range(n_mb):
+                ln = lanes[0] if mode == "serial" else lanes[m]
+                out, tape = pipeline.forward_train3(ln, layers, states[m], xs[m], keep)
+                pipeline.backward3(ln, layers, states[m], bstates[m], tape, gouts[m], keep)
+            for ln in lanes:
+                ln.sync()
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+            del keep
+        res[mode] = dict(ms=best * 1e3, images_per_s=n_mb * micro_batch / best)
+    for ln in lanes:
+        ln.close()
+    return res
+
+
 def bench_graph(reps: int = 50, pool_first: bool = False, exchange: str = "copy"):
     """Eager issue vs replay of a captured HIP graph: the tiny secure layer (configs[0]) and one
     VGG16-CIFAR micro-batch forward (sign-only packed ReLU, prepared planes).
@@ -580,6 +619,11 @@ def main(argv):
             p = bench_pipeline3(packed_relu=packed)
             print(f"  VGG16-CIFAR forward with three parties, batch 128 = 4 x 32 ({'sign-only packed' if packed else 'whole-word'} ReLU, weight masks opened ahead): "
                   f"serial {p['serial']['ms']:.2f} ms ({p['serial']['images_per_s']:.0f} img/s), "
+                  f"one lane per micro-batch {p['pipelined']['ms']:.2f} ms ({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)
+        for packed in (False, True):
+            p = bench_training3(packed_relu=packed)
+            print(f"  VGG16-CIFAR training step (forward + backward) with three parties, batch 128 = 4 x 32 "
+                  f"({'sign-only packed' if packed else 'whole-word'} ReLU): serial {p['serial']['ms']:.2f} ms ({p['serial']['images_per_s']:.0f} img/s), "
                   f"one lane per micro-batch {p['pipelined']['ms']:.2f} ms ({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)
         return
     if argv and argv[0] == "backward":

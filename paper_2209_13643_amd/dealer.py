@@ -192,5 +192,19 @@ def relu3_material(g, n: int, device, packed: bool = False) -> dict:
     return m
 
 
+def mul_triple3(g, n: int, device):
+    """Element-wise multiplication triple on n words, three parties."""
+    a = rand_words(g, (n,), device); b = rand_words(g, (n,), device)
+    t = (share3(g, a), share3(g, b), share3(g, a * b))
+    torch.cuda.synchronize(device)
+    return t
+
+
+def trunc3_pair(g, shape, device, bits: int = FRAC_BITS):
+    """Offline pair of the three-party rescale: shares of r in [0, 2^63) and of r >> bits."""
+    r = rand_words(g, shape, device) & ((1 << 63) - 1)
+    return share3(g, r), share3(g, r >> bits)
+
+
 def he_std(fan_in: int) -> float:
     return math.sqrt(2.0 / fan_in)

@@ -283,6 +283,118 @@ def forward_pipelined3(lanes, layers, states_per_mb, xs, keep: list):
 
 # ------------------------------------------------------------------ training step
 @dataclass
+class BackwardState3:
+    """Gradient triples and rescale pairs of one layer for one micro-batch, three parties."""
+    gx: dict | None               # input gradient: a (mask of g), b (= forward weight mask), c, r, rt
+    gw: dict                      # weight gradient: a (= forward activation mask), b (mask of g), c, r, rt
+    relu_t: tuple | None = None
+    pool_t1: tuple | None = None
+    pool_t2: tuple | None = None
+
+
+def deal_backward3(lane: mpc.Lane, g, layers, states) -> list:
+    """deal_backward for three parties: the forward masks are reused, every gradient product
+    gets a rescale pair of its own."""
+    dev = lane.device
+    out = []
+    for li, (L, st) in enumerate(zip(layers, states)):
+        A = st.a[0] + st.a[1] + st.a[2]; Bm = st.b[0] + st.b[1] + st.b[2]
+        conv = isinstance(L, synth.Conv)
+        gshape = (L.B, L.Ho, L.Wo, L.Cout) if conv else (L.M, L.N)
+        n_out = A.new_empty(gshape).numel()
+        Ag = dealer.rand_words(g, gshape, dev); Bg = dealer.rand_words(g, gshape, dev)
+        lane.wait_torch()
+        if conv:
+            Cw = lane.ring_conv2d_grad_w(A, Bg, L.KH, L.KW, L.pad, L.stride)
+            Cx = lane.ring_conv2d_grad_x(Ag, Bm, A.shape, L.pad, L.stride) if li > 0 else None
+        else:
+            AT = A.transpose(0, 1).contiguous(); BT = Bm.transpose(0, 1).contiguous()
+            lane.wait_torch()
+            Cw = lane.ring_matmul(AT, Bg)
+            Cx = lane.ring_matmul(Ag, BT) if li > 0 else None
+        lane.sync()
+        rw, rtw = dealer.trunc3_pair(g, Cw.shape, dev)
+        gx = None
+        if Cx is not None:
+            rx, rtx = dealer.trunc3_pair(g, Cx.shape, dev)
+            gx = dict(a=dealer.share3(g, Ag), b=st.b, c=dealer.share3(g, Cx), r=rx, rt=rtx)
+        bs = BackwardState3(gx=gx, gw=dict(a=st.a, b=dealer.share3(g, Bg), c=dealer.share3(g, Cw), r=rw, rt=rtw))
+        if st.relu is not None:
+            bs.relu_t = dealer.mul_triple3(g, n_out, dev)
+        if st.pool1 is not None:
+            n_pool = n_out // 4
+            bs.pool_t1 = dealer.mul_triple3(g, 2 * n_pool, dev); bs.pool_t2 = dealer.mul_triple3(g, n_pool, dev)
+        out.append(bs)
+    torch.cuda.synchronize(dev)
+    return out
+
+
+def forward_train3(lane: mpc.Lane, layers, states, x, keep: list):
+    """forward3 that keeps every layer's input shares and the sign shares of its conversions (the tape)."""
+    tape = []
+    for L, st in zip(layers, states):
+        rec = dict(x=x)
+        y_arg = None if st.f_public is not None else st.w
+        if isinstance(L, synth.Conv):
+            xs = tuple(v.view(L.B, L.H, L.W, L.Cin) for v in x)
+            z = lane.conv2d3(xs, y_arg, st.a, st.b, st.c, L.pad, L.stride, f_public=st.f_public)
+        else:
+            xs = tuple(v.view(L.M, L.K) for v in x)
+            z = lane.beaver_matmul3(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public)
+        lane.truncate3(z, st.r, st.rt)
+        keep.append(z)
+        if st.relu is not None:
+            z, sb, sa = lane.relu3(z, st.relu, want_sign=True, packed=st.packed)
+            rec["relu_sign"] = sa; keep.extend([z, sb, sa])
+        if st.pool1 is not None:
+            rec["pool_in_shape"] = tuple(z[0].shape)
+            z, s1, s2 = lane.maxpool3(z, st.pool1, st.pool2, packed=st.packed, want_signs=True)
+            rec["pool_signs"] = (s1, s2); keep.extend([z, s1, s2])
+        tape.append(rec)
+        x = z
+    return x, tape
+
+
+def backward3(lane: mpc.Lane, layers, states, bstates, tape, gout, keep: list):
+    """backward for three parties: max-pool backward, ReLU backward, then the two gradient
+    products of the layer, each followed by its masked rescale.  Returns the weight-gradient shares."""
+    g = gout
+    grads = [None] * len(layers)
+    for li in range(len(layers) - 1, -1, -1):
+        L, st, bs, rec = layers[li], states[li], bstates[li], tape[li]
+        if st.pool1 is not None:
+            B, H, W, C = rec["pool_in_shape"]
+            gp = tuple(v.view(B, H // 2, W // 2, C) for v in g)
+            g = lane.maxpool3_backward(gp, rec["pool_signs"][0], rec["pool_signs"][1], bs.pool_t1, bs.pool_t2, (B, H, W, C))
+            keep.append(g)
+        if st.relu is not None:
+            g = lane.relu3_backward(tuple(v.reshape(-1) for v in g), rec["relu_sign"], *bs.relu_t)
+            keep.append(g)
+        x = rec["x"]
+        w_arg = None if st.f_public is not None else st.w
+        gx = None
+        if isinstance(L, synth.Conv):
+            gs = tuple(v.view(L.B, L.Ho, L.Wo, L.Cout) for v in g)
+            xs = tuple(v.view(L.B, L.H, L.W, L.Cin) for v in x)
+            gw = lane.conv2d3_grad_w(xs, gs, bs.gw["a"], bs.gw["b"], bs.gw["c"], L.pad, L.stride)
+            if bs.gx is not None:
+                gx = lane.conv2d3_grad_x(gs, w_arg, bs.gx["a"], bs.gx["b"], bs.gx["c"], L.pad, L.stride, f_public=st.f_public)
+        else:
+            gs = tuple(v.view(L.M, L.N) for v in g)
+            xs = tuple(v.view(L.M, L.K) for v in x)
+            gw = lane.beaver_matmul3(xs, gs, bs.gw["a"], bs.gw["b"], bs.gw["c"], flags=mpc.MPC_TRANS_X)
+            if bs.gx is not None:
+                gx = lane.beaver_matmul3(gs, w_arg, bs.gx["a"], bs.gx["b"], bs.gx["c"], f_public=st.f_public, flags=mpc.MPC_TRANS_Y)
+        lane.truncate3(gw, bs.gw["r"], bs.gw["rt"])
+        if gx is not None:
+            lane.truncate3(gx, bs.gx["r"], bs.gx["rt"])
+        grads[li] = gw
+        keep.extend([gw, gx])
+        g = gx
+    return grads
+
+
+@dataclass
 class BackwardState:
     """Gradient triples of one layer for one micro-batch (offline material)."""
     gx: dict | None               # input gradient: a (mask of g), b (= forward weight mask), c

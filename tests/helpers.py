@@ -242,3 +242,86 @@ def oracle_train_step(layers, states, bstates, x, gout):
         grads[li] = gw
         g = gx
     return out, grads
+
+
+def deal_backward_host3(rng, layers, states):
+    """deal_backward_host for three parties; every gradient product also gets a rescale pair."""
+    mul = lambda p, q: p * q
+    rec3 = lambda t: np.asarray(t[0], U64) + np.asarray(t[1], U64) + np.asarray(t[2], U64)
+    out = []
+    for li, (L, st) in enumerate(zip(layers, states)):
+        conv = isinstance(L, synth.Conv)
+        A = rec3(st["a"]); Bm = rec3(st["b"])
+        gshape = (L.B, L.Ho, L.Wo, L.Cout) if conv else (L.M, L.N)
+        n_out = int(np.prod(gshape))
+        Ag = synth.rand_words(rng, gshape); Bg = synth.rand_words(rng, gshape)
+        if conv:
+            Cw = oracle.ring_conv2d_grad_w(A, Bg, L.KH, L.KW, L.pad, L.stride)
+            Cx = oracle.ring_conv2d_grad_x(Ag, Bm, A.shape, L.pad, L.stride) if li > 0 else None
+        else:
+            Cw = oracle.ring_matmul(np.ascontiguousarray(A.T), Bg)
+            Cx = oracle.ring_matmul(Ag, np.ascontiguousarray(Bm.T)) if li > 0 else None
+        rw, rtw = synth.deal_trunc3_pair(rng, Cw.shape)
+        bs = dict(gw=dict(a=st["a"], b=synth.share_additive3(rng, Bg), c=synth.share_additive3(rng, Cw), r=rw, rt=rtw),
+                  gx=None, relu_t=None, pool_t1=None, pool_t2=None)
+        if Cx is not None:
+            rx, rtx = synth.deal_trunc3_pair(rng, Cx.shape)
+            bs["gx"] = dict(a=synth.share_additive3(rng, Ag), b=st["b"], c=synth.share_additive3(rng, Cx), r=rx, rt=rtx)
+        if st["relu"] is not None:
+            bs["relu_t"] = synth.deal_product_triple3(rng, (n_out,), (n_out,), mul)
+        if st["pool1"] is not None:
+            n_pool = n_out // 4
+            bs["pool_t1"] = synth.deal_product_triple3(rng, (2 * n_pool,), (2 * n_pool,), mul)
+            bs["pool_t2"] = synth.deal_product_triple3(rng, (n_pool,), (n_pool,), mul)
+        out.append(bs)
+    return out
+
+
+def oracle_train_step3(layers, states, bstates, x, gout):
+    """oracle_train_step for three parties: forward with the tape, backward with a masked
+    rescale after every gradient product."""
+    tape = []
+    for L, st in zip(layers, states):
+        t = dict(x=x)
+        if isinstance(L, synth.Conv):
+            xs = tuple(v.reshape(L.B, L.H, L.W, L.Cin) for v in x)
+            z = oracle.beaver_conv2d3(xs, st["w"], st["a"], st["b"], st["c"], L.pad, L.stride)
+        else:
+            xs = tuple(v.reshape(L.M, L.K) for v in x)
+            z = oracle.beaver_matmul3(xs, st["w"], st["a"], st["b"], st["c"])
+        z = oracle.truncate3(z, st["r"], st["rt"], 16)
+        if st["relu"] is not None:
+            r = oracle.relu3(z, st["relu"]); z = r.y; t["relu_sign"] = r.s_arith
+        if st["pool1"] is not None:
+            t["pool_in_shape"] = z[0].shape
+            z, s1, s2 = oracle.maxpool2x2_3(z, st["pool1"], st["pool2"], want_signs=True); t["pool_signs"] = (s1, s2)
+        tape.append(t); x = z
+    out = x
+    g = gout
+    grads = [None] * len(layers)
+    for li in range(len(layers) - 1, -1, -1):
+        L, st, bs, t = layers[li], states[li], bstates[li], tape[li]
+        if st["pool1"] is not None:
+            g = oracle.maxpool2x2_backward3(g, t["pool_signs"][0], t["pool_signs"][1], bs["pool_t1"], bs["pool_t2"], t["pool_in_shape"])
+        if st["relu"] is not None:
+            g = oracle.relu_backward3(tuple(v.reshape(-1) for v in g), t["relu_sign"], *bs["relu_t"])
+        xin = t["x"]
+        if isinstance(L, synth.Conv):
+            gs = tuple(v.reshape(L.B, L.Ho, L.Wo, L.Cout) for v in g)
+            xs = tuple(v.reshape(L.B, L.H, L.W, L.Cin) for v in xin)
+            fw = lambda p, q, L=L: oracle.ring_conv2d_grad_w(p, q, L.KH, L.KW, L.pad, L.stride)
+            fx = lambda p, q, L=L: oracle.ring_conv2d_grad_x(p, q, (L.B, L.H, L.W, L.Cin), L.pad, L.stride)
+        else:
+            gs = tuple(v.reshape(L.M, L.N) for v in g)
+            xs = tuple(v.reshape(L.M, L.K) for v in xin)
+            fw = lambda p, q: oracle.ring_matmul(np.ascontiguousarray(p.T), q)
+            fx = lambda p, q: oracle.ring_matmul(p, np.ascontiguousarray(q.T))
+        gw = oracle.truncate3(oracle.beaver_bilinear3(fw, xs, gs, bs["gw"]["a"], bs["gw"]["b"], bs["gw"]["c"]),
+                              bs["gw"]["r"], bs["gw"]["rt"], 16)
+        gx = None
+        if bs["gx"] is not None:
+            gx = oracle.truncate3(oracle.beaver_bilinear3(fx, gs, st["w"], bs["gx"]["a"], bs["gx"]["b"], bs["gx"]["c"]),
+                                  bs["gx"]["r"], bs["gx"]["rt"], 16)
+        grads[li] = gw
+        g = gx
+    return out, grads

@@ -7,8 +7,8 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import (deal_backward_host, deal_network_host, deal_network_host3, oracle_forward, oracle_forward3,
-                     oracle_train_step, rec)
+from helpers import (deal_backward_host, deal_backward_host3, deal_network_host, deal_network_host3, oracle_forward,
+                     oracle_forward3, oracle_train_step, oracle_train_step3, rec)
 from paper_2209_13643_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -329,3 +329,51 @@ def test_vgg16_with_three_parties(mods, packed_relu):
         check3(outs[m], mbs[m]["want"][-1], f"pipelined micro-batch {m}")
     for ln in lanes + [packer]:
         ln.close()
+
+
+@pytest.mark.parametrize("packed_relu", [False, True], ids=["whole-word-relu", "sign-only-packed-relu"])
+def test_vgg16_training_step_with_three_parties(mods, packed_relu):
+    """Forward with the tape and backward through max-pool, ReLU, conv and dense layers with three
+    simulated parties: logits and every layer's weight-gradient shares against the oracle (Sec. 5.3, Sec. 5.6)."""
+    mpc, pipeline = mods
+    base = synth.config_vgg16_pipeline(micro_batch=2)
+    layers = base.layers
+    rng = synth.rng_for(base.index, 14)
+    host, _ = deal_network_host3(rng, layers)
+    xs = synth.share_additive3(rng, synth.normal_fixed(rng, (2, 32, 32, 3), 1.0))
+    bhost = deal_backward_host3(rng, layers, host)
+    gout = synth.share_additive3(rng, synth.normal_fixed(rng, (2, 10), 0.5))
+    print(f"three parties, training step, packed_relu={packed_relu}: oracle", flush=True)
+    want_out, want_grads = oracle_train_step3(layers, host, bhost, xs, gout)
+    lane = mpc.Lane(0); lane.use_single_queue()
+    d3 = lambda t: tuple(mpc.to_device(v) for v in t)
+    def m3(m):
+        if m is None:
+            return None
+        md = mpc.material_to_device(m)
+        return lane.pack_material3(md) if packed_relu else md
+    states = [pipeline.LayerState3(w=d3(st["w"]), a=d3(st["a"]), b=d3(st["b"]), c=d3(st["c"]), r=d3(st["r"]), rt=d3(st["rt"]),
+                                   relu=m3(st["relu"]), pool1=m3(st["pool1"]), pool2=m3(st["pool2"]), packed=packed_relu)
+              for st in host]
+    trip = lambda t: None if t is None else tuple(d3(q) for q in t)
+    bstates = []
+    for st, bs in zip(states, bhost):
+        gx = None if bs["gx"] is None else dict(a=d3(bs["gx"]["a"]), b=st.b, c=d3(bs["gx"]["c"]), r=d3(bs["gx"]["r"]), rt=d3(bs["gx"]["rt"]))
+        bstates.append(pipeline.BackwardState3(
+            gx=gx, gw=dict(a=st.a, b=d3(bs["gw"]["b"]), c=d3(bs["gw"]["c"]), r=d3(bs["gw"]["r"]), rt=d3(bs["gw"]["rt"])),
+            relu_t=trip(bs["relu_t"]), pool_t1=trip(bs["pool_t1"]), pool_t2=trip(bs["pool_t2"])))
+    print("device run", flush=True)
+    keep = []
+    out, tape = pipeline.forward_train3(lane, layers, states, d3(xs), keep)
+    grads = pipeline.backward3(lane, layers, states, bstates, tape, d3(gout), keep)
+    lane.sync()
+
+    def check3(got, want, what):
+        for i in range(3):
+            g = mpc.to_host(got[i]).reshape(want[i].shape)
+            assert np.array_equal(g, want[i]), f"{what}: party {i} differs in {(g != want[i]).sum()} elements"
+
+    check3(out, want_out, "logits")
+    for li, L in enumerate(layers):
+        check3(grads[li], want_grads[li], f"weight gradient of layer {li} ({L.name})")
+    lane.close()
