@@ -547,6 +547,10 @@ int mpc_conv2d3_grad_w(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 g,
  * the output gradient to the window maxima exactly as
  * mpc_maxpool2x2_backward does (triples a2, b2, c2 on n_out words, a1, b1, c1
  * on 2*n_out words).  Workspace: the matching *_workspace_bytes query. */
+/* Local linear steps on three shares (Sec. 3.1: additions need no
+ * communication): out_i = x_i + y_i / x_i - y_i; out may alias x or y. */
+int mpc_add3(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 y, mpc_share3 out, size_t n);
+int mpc_sub3(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 y, mpc_share3 out, size_t n);
 size_t mpc_mul3_workspace_bytes(size_t n);
 int mpc_mul3(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 y,
              mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 c, mpc_share3 z, size_t n);

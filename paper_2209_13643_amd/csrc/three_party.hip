@@ -934,6 +934,21 @@ int mpc_maxpool3_signs(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* mat1
     return maxpool3_entry(c, x, mat1, mat2, y, B, H, W, C, packed != 0, s1, s2);
 }
 
+// local linear steps on three shares: out_i = x_i +/- y_i
+static int linear3(mpc_ctx* c, mpc_cshare3 x, mpc_cshare3 y, mpc_share3 out, size_t n, bool subtract)
+{
+    if (!c || n == 0) return MPC_EINVAL;
+    for (int i = 0; i < 3; ++i) if (!x.p[i] || !y.p[i] || !out.p[i]) return MPC_EINVAL;
+    hipStream_t st = c->s[0];
+    MPC_TRY(lane_join(c));
+    for (int i = 0; i < 3; ++i)
+        MPC_TRY(subtract ? launch_sub(c, st, x.p[i], y.p[i], out.p[i], n) : launch_add(c, st, x.p[i], y.p[i], out.p[i], n));
+    return lane_fanout(c);
+}
+
+int mpc_add3(mpc_ctx* c, mpc_cshare3 x, mpc_cshare3 y, mpc_share3 out, size_t n) { return linear3(c, x, y, out, n, false); }
+int mpc_sub3(mpc_ctx* c, mpc_cshare3 x, mpc_cshare3 y, mpc_share3 out, size_t n) { return linear3(c, x, y, out, n, true); }
+
 size_t mpc_mul3_workspace_bytes(size_t n) { return n ? mul3_ws_bytes(n) : 0; }
 
 int mpc_mul3(mpc_ctx* c, mpc_cshare3 x, mpc_cshare3 y, mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 cc, mpc_share3 z, size_t n)

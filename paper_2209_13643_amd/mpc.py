@@ -70,7 +70,7 @@ EXPORTS = [
     "mpc_relu3_packed_words", "mpc_relu3_pack_triples", "mpc_relu3_msb_workspace_bytes", "mpc_relu3_msb",
     "mpc_maxpool3_msb_workspace_bytes", "mpc_maxpool3_msb",
     "mpc_conv2d3_grad_x_workspace_bytes", "mpc_conv2d3_grad_w_workspace_bytes", "mpc_conv2d3_grad_x", "mpc_conv2d3_grad_w",
-    "mpc_mul3_workspace_bytes", "mpc_mul3", "mpc_relu3_backward", "mpc_maxpool3_signs",
+    "mpc_add3", "mpc_sub3", "mpc_mul3_workspace_bytes", "mpc_mul3", "mpc_relu3_backward", "mpc_maxpool3_signs",
     "mpc_maxpool3_backward_workspace_bytes", "mpc_maxpool3_backward",
 ]
 
@@ -168,6 +168,8 @@ def lib():
         fn.argtypes = [c_int] * 9; fn.restype = c_size_t
     L.mpc_conv2d3_grad_x.argtypes = [c_void_p] + [CShare3] * 6 + [c_int] * 9 + [_P64]
     L.mpc_conv2d3_grad_w.argtypes = [c_void_p] + [CShare3] * 6 + [c_int] * 9
+    L.mpc_add3.argtypes = [c_void_p, CShare3, CShare3, CShare3, c_size_t]
+    L.mpc_sub3.argtypes = [c_void_p, CShare3, CShare3, CShare3, c_size_t]
     L.mpc_mul3_workspace_bytes.argtypes = [c_size_t]; L.mpc_mul3_workspace_bytes.restype = c_size_t
     L.mpc_mul3.argtypes = [c_void_p] + [CShare3] * 6 + [c_size_t]
     L.mpc_relu3_backward.argtypes = [c_void_p] + [CShare3] * 6 + [c_size_t]
@@ -660,6 +662,16 @@ class Lane:
         self._check(lib().mpc_conv2d3_grad_w(self._h, _share3(x), _share3(g), _share3(a), _share3(b), _share3(c), _share3(gw),
                                              B, H, W, Cin, Cout, KH, KW, pad, stride))
         return gw
+
+    def add3(self, x, y, out=None):
+        z = out if out is not None else self._empty3(x[0])
+        self._check(lib().mpc_add3(self._h, _share3(x), _share3(y), _share3(z), x[0].numel()))
+        return z
+
+    def sub3(self, x, y, out=None):
+        z = out if out is not None else self._empty3(x[0])
+        self._check(lib().mpc_sub3(self._h, _share3(x), _share3(y), _share3(z), x[0].numel()))
+        return z
 
     def mul3(self, x, y, a, b, c, out=None):
         """Element-wise Alg. 1 with three parties (no rescale)."""

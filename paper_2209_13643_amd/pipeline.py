@@ -243,7 +243,7 @@ def deal_microbatch3(lane: mpc.Lane, g, layers, weights, packed_relu: bool = Fal
 def preopen_weights3(lane: mpc.Lane, states):
     """Alg. 3's early broadcast of the weight masks with three parties."""
     for st in states:
-        st.f_public = lane.open3(tuple(w - b for w, b in zip(st.w, st.b)))
+        st.f_public = lane.open3(lane.sub3(st.w, st.b))
     lane.sync()
 
 
@@ -392,6 +392,17 @@ def backward3(lane: mpc.Lane, layers, states, bstates, tape, gout, keep: list):
         keep.extend([gw, gx])
         g = gx
     return grads
+
+
+def sgd_step3(lane: mpc.Lane, states, grads, lr_pairs, lr_shift: int):
+    """w <- w - 2^-lr_shift * grad_w with three parties: one more masked rescale of the gradient
+    (in place; lr_pairs[l] = the offline pair (r, r >> lr_shift) of layer l) and a local
+    subtraction.  Weight masks opened ahead of time are opened again."""
+    for st, gw, (r, rt) in zip(states, grads, lr_pairs):
+        lane.truncate3(gw, r, rt, bits=lr_shift)
+        lane.sub3(st.w, tuple(v.view(st.w[0].shape) for v in gw), out=st.w)
+        if st.f_public is not None:
+            st.f_public = lane.open3(lane.sub3(st.w, st.b))
 
 
 @dataclass

@@ -109,7 +109,7 @@ def test_pooled_layers_as_relu_of_maxpool(mods, dealt, packed_relu):
 
 
 @pytest.mark.parametrize("mode", ["serial-3stream", "pipelined", "pipelined-preopened", "pipelined-two-phase-chunked",
-                                  "pipelined-packed-relu", "pipelined-prepared-planes"])
+                                  "pipelined-packed-relu", "pipelined-prepared-planes", "pipelined-packed-relu-remote-store"])
 def test_pipeline_invariance(mods, dealt, mode):
     mpc, pipeline = mods
     layers, mbs = dealt
@@ -118,7 +118,10 @@ def test_pipeline_invariance(mods, dealt, mode):
     if mode != "serial-3stream":
         for ln in lanes:
             ln.use_single_queue()
-    pk = lanes[0] if mode == "pipelined-packed-relu" else None
+    pk = lanes[0] if mode.startswith("pipelined-packed-relu") else None
+    if mode.endswith("remote-store"):
+        for ln in lanes:
+            ln.set_exchange("put")
     states = [[to_state(mpc, pipeline, st, pk) for st in mb["states"]] for mb in mbs]
     xs = [(mpc.to_device(mb["x"][0]), mpc.to_device(mb["x"][1])) for mb in mbs]
     kw = {}
@@ -376,4 +379,12 @@ def test_vgg16_training_step_with_three_parties(mods, packed_relu):
     check3(out, want_out, "logits")
     for li, L in enumerate(layers):
         check3(grads[li], want_grads[li], f"weight gradient of layer {li} ({L.name})")
+    # SGD step with learning rate 2^-6: one more masked rescale, then a local subtraction
+    pairs = [synth.deal_trunc3_pair(rng, want_grads[li][0].shape, bits=6) for li in range(len(layers))]
+    pipeline.sgd_step3(lane, states, grads, [(d3(r), d3(rt)) for r, rt in pairs], 6)
+    lane.sync()
+    for li, (L, st) in enumerate(zip(layers, host)):
+        step = oracle.truncate3(want_grads[li], pairs[li][0], pairs[li][1], 6)
+        want_w = tuple(st["w"][i] - step[i].reshape(st["w"][i].shape) for i in range(3))
+        check3(states[li].w, want_w, f"updated weights of layer {li} ({L.name})")
     lane.close()
