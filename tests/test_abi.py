@@ -176,3 +176,11 @@ def test_relu_stage_kernels_fit_beside_the_gemm():
     assert len(stages) > 50
     worst = max(stages, key=lambda r: r[1])
     assert worst[1] <= 136, worst
+    # the three-party kernels: the same budget, and nothing spilled
+    out = subprocess.run([ge.HIPCC, *ge.HIP_FLAGS, "--cuda-device-only", "-Rpass-analysis=kernel-resource-usage",
+                          "-c", os.path.join(ge.CSRC, "three_party.hip"), "-o", os.devnull], capture_output=True, text=True)
+    assert out.returncode == 0, out.stderr[-2000:]
+    rows = re.findall(r"Function Name: (\S+).*?VGPRs: (\d+).*?AGPRs: (\d+).*?ScratchSize \[bytes/lane\]: (\d+)", out.stderr, flags=re.S)
+    assert len(rows) > 40
+    for name, v, a, scratch in rows:
+        assert int(v) + int(a) <= 136 and int(scratch) == 0, (name, v, a, scratch)
