@@ -2,12 +2,12 @@
 the benchmark times (single-queue lane, automatic ReLU chunking).
 
 Linear layers: inputs and triples are dealt on the host (triple products by the
-oracle) and every output share is compared bit for bit.  Secure ReLU at sizes
-whose offline material does not fit a host array comfortably: material is drawn
-on the device by the seeded dealer (a random-number source, not the code under
-test), the oracle recomputes a random sample of elements from the downloaded
-material slices, and the whole output is checked through the property
-rec(y) == max(rec(x), 0)."""
+oracle) and every output share is compared bit for bit.  Secure ReLU at the
+large sizes: material is drawn on the device by the seeded dealer (a
+random-number source, not the code under test), downloaded slab by slab, and
+the oracle recomputes every element: all output words (y, sign bits, sign
+shares) of both parties are compared; the whole output is also checked through
+the property rec(y) == max(rec(x), 0)."""
 import numpy as np
 import pytest
 import torch
@@ -46,8 +46,10 @@ def assert_equal_shares(mpc, got, want, what):
         assert np.array_equal(g, want[i]), f"{what}: party {i}: {(g != want[i]).sum()} of {g.size} words differ"
 
 
-def relu_sampled_check(mpc, dealer, lane, z, seed, n_sample=200_000):
-    """Full-size secure ReLU on device shares z: sampled oracle parity + exact property."""
+def relu_sampled_check(mpc, dealer, lane, z, seed, slab=4 << 20):
+    """Full-size secure ReLU on device shares z: every output word of both parties against the oracle
+    (elements are independent, so the oracle runs slab by slab on the downloaded material), plus the
+    reconstruction property on the device."""
     n = z[0].numel()
     g = dealer.gen(seed, lane.device)
     mat = dealer.relu_material(g, n, lane.device)
@@ -57,15 +59,19 @@ def relu_sampled_check(mpc, dealer, lane, z, seed, n_sample=200_000):
     assert torch.equal(ry, torch.clamp(rz, min=0)), "rec(y) != max(rec(x), 0)"
     assert torch.equal((sb[0] ^ sb[1]).view(-1).bool(), rz < 0)
     assert torch.equal((sa[0] + sa[1]).view(-1), (rz < 0).to(torch.int64))
-    idx = torch.randperm(n, device=lane.device, generator=g)[:n_sample].sort().values
-    take = lambda t: mpc.to_host(t.view(-1)[idx])
-    take12 = lambda t: mpc.to_host(t.view(12, n)[:, idx])
-    sub = {k: (take(mat[k][0]), take(mat[k][1])) for k in ("r", "rb", "ra", "ma", "mb", "mc")}
-    for k in ("and_a", "and_b", "and_c"):
-        sub[k] = (take12(mat[k][0]), take12(mat[k][1]))
-    want = oracle.relu((take(z[0]), take(z[1])), sub)
-    assert_equal_shares(mpc, (y[0].view(-1)[idx], y[1].view(-1)[idx]), want.y, "relu sample")
-    assert_equal_shares(mpc, (sa[0].view(-1)[idx], sa[1].view(-1)[idx]), want.s_arith, "sign share sample")
+    for lo in range(0, n, slab):
+        hi = min(n, lo + slab)
+        take = lambda t: mpc.to_host(t.view(-1)[lo:hi])
+        take12 = lambda t: mpc.to_host(t.view(12, n)[:, lo:hi].contiguous())
+        sub = {k: (take(mat[k][0]), take(mat[k][1])) for k in ("r", "rb", "ra", "ma", "mb", "mc")}
+        for k in ("and_a", "and_b", "and_c"):
+            sub[k] = (take12(mat[k][0]), take12(mat[k][1]))
+        want = oracle.relu((take(z[0]), take(z[1])), sub)
+        for i in range(2):
+            assert np.array_equal(take(y[i]), want.y[i]), f"relu y, party {i}, elements {lo}..{hi}"
+            assert np.array_equal(take(sb[i]), want.s_bit[i]), f"relu sign bits, party {i}, elements {lo}..{hi}"
+            assert np.array_equal(take(sa[i]), want.s_arith[i]), f"relu sign shares, party {i}, elements {lo}..{hi}"
+        del sub, want
     # the sign-only packed chain on the same material, packed on the device: every word of
     # every output equals the whole-word protocol's, which was just checked
     packed = lane.pack_material(mat)
@@ -269,6 +275,39 @@ def test_config4_vgg16_pipeline_full(mods, packed_relu):
             x = p
     for ln in lanes:
         ln.close()
+
+
+def test_config4_one_micro_batch_every_share_against_oracle(mods, lane):
+    """One micro-batch of config 4 at its full size (32 images) with inputs, triples and material
+    dealt on the host: every layer's output shares, both parties, against the oracle word for word;
+    the sign-only packed chain on the same material gives the same words."""
+    from helpers import deal_network_host, oracle_forward
+    mpc, dealer, pipeline = mods
+    wl = synth.config_vgg16_pipeline(32)
+    layers = wl.layers
+    rng = synth.rng_for(wl.index, 21)
+    print("config 4, 32 images: dealing on the host", flush=True)
+    host, _ = deal_network_host(rng, layers)
+    xs = synth.share_additive(rng, synth.normal_fixed(rng, (32, 32, 32, 3), 1.0))
+    print("oracle forward", flush=True)
+    want = oracle_forward(layers, host, xs)
+    for packed in (False, True):
+        print(f"device forward, packed={packed}", flush=True)
+        x = dev(mpc, xs)
+        keep = []
+        for li, (L, st) in enumerate(zip(layers, host)):
+            def mat(m):
+                if m is None:
+                    return None
+                md = mpc.material_to_device(m)
+                return lane.pack_material(md) if packed else md
+            state = pipeline.LayerState(w=dev(mpc, st["w"]), a=dev(mpc, st["a"]), b=dev(mpc, st["b"]), c=dev(mpc, st["c"]),
+                                        relu=mat(st["relu"]), pool1=mat(st["pool1"]), pool2=mat(st["pool2"]), packed=packed)
+            x = pipeline.run_layer(lane, L, state, x, keep)
+            lane.sync()
+            assert_equal_shares(mpc, x, want[li], f"layer {li} ({L.name}), packed={packed}")
+            keep.clear(); del state
+            torch.cuda.empty_cache()
 
 
 def test_config1_with_three_parties(mods, lane):
