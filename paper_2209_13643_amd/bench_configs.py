@@ -605,6 +605,26 @@ def main(argv):
         for mib, ms, tbs in bench_hbm_copy():
             print(f"  {mib:5d} MiB source + {mib:5d} MiB destination: {ms * 1e3:8.1f} us  {tbs:5.2f} TB/s = {100 * tbs / 8.0:4.1f}% of 8 TB/s", flush=True)
         return
+    if argv and argv[0] == "relu3":
+        # the three-party ReLU alone, both chains (the command the per-kernel profile is taken with)
+        n = int(argv[1]) if len(argv) > 1 else 2097152
+        lane = mpc.Lane(0); lane.use_single_queue()
+        g = dealer.gen(synth.BASE_SEED + 33, lane.device)
+        x = dealer.share3(g, dealer.normal_fixed(g, (n,), 1.0, lane.device))
+        y = tuple(torch.empty_like(v) for v in x)
+        for packed in (False, True):
+            mat = dealer.relu3_material(g, n, lane.device, packed=packed)
+            for _ in range(3):
+                lane.relu3(x, mat, out=y, packed=packed)
+            lane.sync(); t0 = time.perf_counter()
+            for _ in range(20):
+                lane.relu3(x, mat, out=y, packed=packed)
+            lane.sync(); ms = (time.perf_counter() - t0) / 20 * 1e3
+            print(f"  three-party ReLU, {n} elements, {'sign-only packed' if packed else 'whole-word'} chain: {ms:.3f} ms "
+                  f"({n / ms / 1e6:.2f} G elems/s)", flush=True)
+            del mat
+        lane.close()
+        return
     if argv and argv[0] == "parties3":
         r = bench_three_parties()
         print("== configs[1] with three simulated parties (432 int8 ops per secure MAC: 3 parties x 2 ring products x 36 x 2)")
