@@ -1,9 +1,11 @@
 // Three simulated parties (Alg. 1 and Alg. 2 are stated for N parties; Sec. 3.3,
-// Sec. 5.6): opening, the masked rescale, and the secure ReLU whose A2B step
-// adds three binary-shared words (carry-save step, then the Kogge-Stone
-// network).  Everything here streams whole words and is bound by HBM; all
-// launches go to the lane's first stream, one launch per step for all three
-// parties (blockIdx.y = party), and every exchange is a copy kernel.
+// Sec. 5.6): opening, the masked rescale, the secure ReLU whose A2B step adds
+// three binary-shared words (carry-save step, then the Kogge-Stone network) on
+// whole words or on the sign's carry chain only, 2x2 max-pool by composition,
+// and the element-wise steps of the backward pass (Sec. 5.3).  Everything here
+// is bound by HBM; all launches go to the lane's first stream, one launch per
+// step for all three parties (blockIdx.y = party), and every exchange is a copy
+// kernel.  The linear layers with three parties live in linear.hip.
 #include "common.h"
 #include "msb_pack.h"
 
