@@ -524,7 +524,7 @@ def bench_three_parties(reps: int = 20):
                 msb_hbm_frac=msb_bytes * n / (msb_med * 1e-3) / 8.0e12)
 
 
-def bench_pipeline3(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = False):
+def bench_pipeline3(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = False, pool_first: bool = False):
     """Config 4's network with three parties: serial on one lane vs one lane per micro-batch."""
     wl = synth.config_vgg16_pipeline(micro_batch)
     layers = wl.layers
@@ -536,7 +536,7 @@ def bench_pipeline3(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_
     weights = pipeline.deal_weights3(g, layers, dev)
     states, xs = [], []
     for m in range(n_mb):
-        states.append(pipeline.deal_microbatch3(lanes[m], g, layers, weights, packed_relu=packed_relu))
+        states.append(pipeline.deal_microbatch3(lanes[m], g, layers, weights, packed_relu=packed_relu, pool_first=pool_first))
         xs.append(dealer.share3(g, dealer.normal_fixed(g, (micro_batch, 32, 32, 3), 1.0, dev)))
         torch.cuda.synchronize()
         pipeline.preopen_weights3(lanes[m], states[m])
@@ -635,9 +635,10 @@ def main(argv):
               f"{r['relu_bytes_per_element']} B per element -> {100 * r['relu_hbm_frac']:.1f}% of 8 TB/s", flush=True)
         print(f"  the same ReLU on the sign's carry chain only: {r['msb_ms']:.3f} ms (min {r['msb_min_ms']:.3f}), {r['msb_elems_per_s'] / 1e9:.2f} G elems/s; "
               f"{r['msb_bytes_per_element']} B per element -> {100 * r['msb_hbm_frac']:.1f}% of 8 TB/s", flush=True)
-        for packed in (False, True):
-            p = bench_pipeline3(packed_relu=packed)
-            print(f"  VGG16-CIFAR forward with three parties, batch 128 = 4 x 32 ({'sign-only packed' if packed else 'whole-word'} ReLU, weight masks opened ahead): "
+        for packed, pf in ((False, False), (True, False), (True, True)):
+            p = bench_pipeline3(packed_relu=packed, pool_first=pf)
+            print(f"  VGG16-CIFAR forward with three parties, batch 128 = 4 x 32 ({'sign-only packed' if packed else 'whole-word'} ReLU"
+                  f"{', pooled layers as ReLU(maxpool(z))' if pf else ''}, weight masks opened ahead): "
                   f"serial {p['serial']['ms']:.2f} ms ({p['serial']['images_per_s']:.0f} img/s), "
                   f"one lane per micro-batch {p['pipelined']['ms']:.2f} ms ({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)
         for packed in (False, True):

@@ -198,6 +198,7 @@ class LayerState3:
     pool1: dict | None = None
     pool2: dict | None = None
     packed: bool = False          # ReLU / pool material in the packed layout: sign-only chain (mpc_relu3_msb)
+    pool_first: bool = False      # pooled layer evaluated as ReLU(maxpool(z)): the ReLU material covers the pooled size
 
 
 def deal_weights3(g, layers, device):
@@ -209,9 +210,10 @@ def deal_weights3(g, layers, device):
     return ws
 
 
-def deal_microbatch3(lane: mpc.Lane, g, layers, weights, packed_relu: bool = False) -> list:
+def deal_microbatch3(lane: mpc.Lane, g, layers, weights, packed_relu: bool = False, pool_first: bool = False) -> list:
     """Triples, rescale pairs and ReLU / pool material of one micro-batch for three parties.
-    packed_relu: material for the sign-only carry chain (mpc_relu3_msb / mpc_maxpool3_msb)."""
+    packed_relu: material for the sign-only carry chain (mpc_relu3_msb / mpc_maxpool3_msb).
+    pool_first: as in deal_microbatch (pooled layers run as ReLU(maxpool(z)))."""
     dev = lane.device
     states = []
     for L, (W, wsh) in zip(layers, weights):
@@ -229,8 +231,9 @@ def deal_microbatch3(lane: mpc.Lane, g, layers, weights, packed_relu: bool = Fal
         r = dealer.rand_words(g, C.shape, dev) & ((1 << 63) - 1)
         st = LayerState3(w=wsh, a=dealer.share3(g, A), b=dealer.share3(g, Bm), c=dealer.share3(g, C),
                          r=dealer.share3(g, r), rt=dealer.share3(g, r >> dealer.FRAC_BITS), packed=packed_relu)
+        st.pool_first = pool_first and isinstance(L, synth.Conv) and L.pool and L.relu
         if L.relu:
-            st.relu = dealer.relu3_material(g, n_out, dev, packed=packed_relu)
+            st.relu = dealer.relu3_material(g, n_out // 4 if st.pool_first else n_out, dev, packed=packed_relu)
         if isinstance(L, synth.Conv) and L.pool:
             n_pool = L.B * (L.Ho // 2) * (L.Wo // 2) * L.Cout
             st.pool1 = dealer.relu3_material(g, 2 * n_pool, dev, packed=packed_relu)
@@ -258,6 +261,11 @@ def run_layer3(lane: mpc.Lane, L, st: LayerState3, x, keep: list):
         z = lane.beaver_matmul3(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public)
     lane.truncate3(z, st.r, st.rt)
     outs = [z]
+    if st.pool_first:
+        z = lane.maxpool3(z, st.pool1, st.pool2, packed=st.packed); outs.append(z)
+        z = lane.relu3(z, st.relu, packed=st.packed); outs.append(z)
+        keep.extend(outs)
+        return z
     if st.relu is not None:
         z = lane.relu3(z, st.relu, packed=st.packed); outs.append(z)
     if st.pool1 is not None:

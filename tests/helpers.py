@@ -115,7 +115,7 @@ def oracle_forward(layers, states, x):
 
 
 # ------------------------------------------------ whole networks, three parties
-def deal_network_host3(rng, layers, weights=None):
+def deal_network_host3(rng, layers, weights=None, pool_first=False):
     """deal_network_host for three parties: every share a triple, plus the rescale pair of every layer."""
     states, wout = [], []
     for li, L in enumerate(layers):
@@ -135,8 +135,9 @@ def deal_network_host3(rng, layers, weights=None):
             n_out = L.M * L.N
         r, rt = synth.deal_trunc3_pair(rng, c[0].shape)
         st = dict(W=W, w=wsh, a=a, b=b, c=c, r=r, rt=rt, relu=None, pool1=None, pool2=None)
+        st["pool_first"] = bool(pool_first and conv and L.pool and L.relu)
         if L.relu:
-            st["relu"] = synth.deal_relu3_material(rng, n_out)
+            st["relu"] = synth.deal_relu3_material(rng, n_out // 4 if st["pool_first"] else n_out)
         if conv and L.pool:
             n_pool = L.B * (L.Ho // 2) * (L.Wo // 2) * L.Cout
             st["pool1"] = synth.deal_relu3_material(rng, 2 * n_pool)
@@ -155,10 +156,14 @@ def oracle_forward3(layers, states, x):
             xs = tuple(v.reshape(L.M, L.K) for v in x)
             z = oracle.beaver_matmul3(xs, st["w"], st["a"], st["b"], st["c"])
         z = oracle.truncate3(z, st["r"], st["rt"], 16)
-        if st["relu"] is not None:
-            z = oracle.relu3(z, st["relu"]).y
-        if st["pool1"] is not None:
+        if st.get("pool_first"):
             z = oracle.maxpool2x2_3(z, st["pool1"], st["pool2"])
+            z = oracle.relu3(z, st["relu"]).y
+        else:
+            if st["relu"] is not None:
+                z = oracle.relu3(z, st["relu"]).y
+            if st["pool1"] is not None:
+                z = oracle.maxpool2x2_3(z, st["pool1"], st["pool2"])
         outs.append(z)
         x = z
     return outs

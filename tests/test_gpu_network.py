@@ -334,6 +334,33 @@ def test_vgg16_with_three_parties(mods, packed_relu):
         ln.close()
 
 
+def test_three_party_pooled_layers_as_relu_of_maxpool(mods):
+    """The reordered network (pool first, then ReLU on a quarter of the elements) with three parties,
+    sign-only chain: every layer's shares against the oracle run in the same order."""
+    mpc, pipeline = mods
+    base = synth.config_vgg16_pipeline(micro_batch=2)
+    layers = base.layers
+    rng = synth.rng_for(base.index, 15)
+    host, _ = deal_network_host3(rng, layers, pool_first=True)
+    assert sum(st["pool_first"] for st in host) == 5
+    xs = synth.share_additive3(rng, synth.normal_fixed(rng, (2, 32, 32, 3), 1.0))
+    want = oracle_forward3(layers, host, xs)
+    lane = mpc.Lane(0); lane.use_single_queue()
+    d3 = lambda t: tuple(mpc.to_device(v) for v in t)
+    m3 = lambda m: None if m is None else lane.pack_material3(mpc.material_to_device(m))
+    x = d3(xs); keep = []
+    for li, (L, st) in enumerate(zip(layers, host)):
+        state = pipeline.LayerState3(w=d3(st["w"]), a=d3(st["a"]), b=d3(st["b"]), c=d3(st["c"]), r=d3(st["r"]), rt=d3(st["rt"]),
+                                     relu=m3(st["relu"]), pool1=m3(st["pool1"]), pool2=m3(st["pool2"]), packed=True,
+                                     pool_first=st["pool_first"])
+        x = pipeline.run_layer3(lane, L, state, x, keep)
+        lane.sync()
+        for i in range(3):
+            g = mpc.to_host(x[i]).reshape(want[li][i].shape)
+            assert np.array_equal(g, want[li][i]), f"layer {li} ({L.name}), party {i}"
+    lane.close()
+
+
 @pytest.mark.parametrize("packed_relu", [False, True], ids=["whole-word-relu", "sign-only-packed-relu"])
 def test_vgg16_training_step_with_three_parties(mods, packed_relu):
     """Forward with the tape and backward through max-pool, ReLU, conv and dense layers with three
