@@ -144,7 +144,9 @@ int mpc_graph_destroy(mpc_graph* graph);
  *   two devices); the next round starts when that kernel has ended.  One launch
  *   per round instead of two and one traversal less per exchanged word.  Takes
  *   effect on lanes whose three streams are one queue; elsewhere the copy
- *   kernels are used.  Results are identical. */
+ *   kernels are used.  Results are identical.  The three-party ReLU and
+ *   max-pool calls honour it on every lane (they use one stream): each stage
+ *   kernel stores its masked words into both peers' receive buffers. */
 enum { MPC_EXCHANGE_COPY = 0, MPC_EXCHANGE_PUT = 1 };
 int mpc_ctx_set_exchange(mpc_ctx* ctx, int mode);
 

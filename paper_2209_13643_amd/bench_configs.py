@@ -614,14 +614,16 @@ def main(argv):
         y = tuple(torch.empty_like(v) for v in x)
         for packed in (False, True):
             mat = dealer.relu3_material(g, n, lane.device, packed=packed)
-            for _ in range(3):
-                lane.relu3(x, mat, out=y, packed=packed)
-            lane.sync(); t0 = time.perf_counter()
-            for _ in range(20):
-                lane.relu3(x, mat, out=y, packed=packed)
-            lane.sync(); ms = (time.perf_counter() - t0) / 20 * 1e3
-            print(f"  three-party ReLU, {n} elements, {'sign-only packed' if packed else 'whole-word'} chain: {ms:.3f} ms "
-                  f"({n / ms / 1e6:.2f} G elems/s)", flush=True)
+            for ex in ("copy", "put"):
+                lane.set_exchange(ex)
+                for _ in range(3):
+                    lane.relu3(x, mat, out=y, packed=packed)
+                lane.sync(); t0 = time.perf_counter()
+                for _ in range(20):
+                    lane.relu3(x, mat, out=y, packed=packed)
+                lane.sync(); ms = (time.perf_counter() - t0) / 20 * 1e3
+                print(f"  three-party ReLU, {n} elements, {'sign-only packed' if packed else 'whole-word'} chain"
+                      f"{', exchange by remote store' if ex == 'put' else ''}: {ms:.3f} ms ({n / ms / 1e6:.2f} G elems/s)", flush=True)
             del mat
         lane.close()
         return

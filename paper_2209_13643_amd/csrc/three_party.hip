@@ -66,6 +66,10 @@ struct Relu3Party {
     u64* send;                           // [4][n] masked words of the current round
     u64* recv[2];                        // [4][n] the same from party+1 / party+2
     u8* vsend; u8* vrecv[2];             // B2A round (one byte per element)
+    // exchange by remote store: the stage kernel also writes its masked words where the two peers
+    // read them (put[s]: the receive buffer recv[s] of party (me + 2 - s) mod 3); recv_alt is the second
+    // set of receive buffers, alternating with recv from stage to stage in that mode
+    u64* put[2]; u64* putL[2]; u8* vput[2]; u64* recv_alt[2];
     // sign-only chain: per level a [4][pw] block of masked packed words, and the G bits a level keeps
     u64* sendL; u64* recvL[2]; u64* gsel;
 };
@@ -104,7 +108,7 @@ __device__ __forceinline__ T and_finish(int party, T d, T g, T a, T b, T c)
 //       8      : level 5 finished -> sign share, B2A masked
 //       9      : B2A finished -> m = 1 - s, select masked
 //       10     : select finished -> y
-template <int STAGE, typename T>
+template <int STAGE, typename T, bool PUT>
 __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
 {
     typedef typename ByteOf<T>::type B;
@@ -119,6 +123,11 @@ __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
     auto out = [n](u64* base, int r) { return reinterpret_cast<T*>(base + (size_t)r * n); };
     auto tr = [tn](const u64* base, int r) { return reinterpret_cast<const T*>(base + (size_t)r * tn); };
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < units; i += stride) {
+        // row k of this round's masked words: into the own send buffer and, by remote store, to both peers
+        auto send = [&](int k, T v) {
+            out(p.send, k)[i] = v;
+            if constexpr (PUT) { out(p.put[0], k)[i] = v; out(p.put[1], k)[i] = v; }
+        };
         // masked words of the previous round, opened
         T o[4] = {};
         constexpr int kOpen = (STAGE == 0 || STAGE >= 9) ? 0 : (STAGE >= 3 && STAGE <= 7) ? 4 : 2;
@@ -133,22 +142,22 @@ __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
             const T V = party == 1 ? own : party == 2 ? w2 : w1;
             const T W = party == 2 ? own : party == 0 ? w2 : w1;
             out(p.S, 0)[i] = U ^ V ^ W; out(p.Wd, 0)[i] = W;
-            out(p.send, 0)[i] = (U ^ W) ^ tr(p.ta, 0)[i];
-            out(p.send, 1)[i] = (V ^ W) ^ tr(p.tb, 0)[i];
+            send(0, (U ^ W) ^ tr(p.ta, 0)[i]);
+            send(1, (V ^ W) ^ tr(p.tb, 0)[i]);
         } else if constexpr (STAGE == 1) {
             const T Tm = and_finish<T>(party, o[0], o[1], tr(p.ta, 0)[i], tr(p.tb, 0)[i], tr(p.tc, 0)[i]);
             const T S = in(p.S, 0)[i];
             const T K = (Tm ^ in(p.Wd, 0)[i]) << 1;
             const T P = S ^ K;
             out(p.P, 0)[i] = P; reinterpret_cast<B*>(p.p63)[i] = to_bytes(P >> 63);
-            out(p.send, 0)[i] = S ^ tr(p.ta, 1)[i];
-            out(p.send, 1)[i] = K ^ tr(p.tb, 1)[i];
+            send(0, S ^ tr(p.ta, 1)[i]);
+            send(1, K ^ tr(p.tb, 1)[i]);
         } else if constexpr (STAGE == 2) {
             const T G = and_finish<T>(party, o[0], o[1], tr(p.ta, 1)[i], tr(p.tb, 1)[i], tr(p.tc, 1)[i]);
             const T P = in(p.P, 0)[i];
             out(p.G, 0)[i] = G;
-            out(p.send, 0)[i] = P ^ tr(p.ta, 2)[i];  out(p.send, 1)[i] = (G << 1) ^ tr(p.tb, 2)[i];
-            out(p.send, 2)[i] = P ^ tr(p.ta, 3)[i];  out(p.send, 3)[i] = (P << 1) ^ tr(p.tb, 3)[i];
+            send(0, P ^ tr(p.ta, 2)[i]);  send(1, (G << 1) ^ tr(p.tb, 2)[i]);
+            send(2, P ^ tr(p.ta, 3)[i]);  send(3, (P << 1) ^ tr(p.tb, 3)[i]);
         } else if constexpr (STAGE >= 3 && STAGE <= 7) {
             constexpr int L = STAGE - 3;                 // level being finished
             constexpr int tg = 2 + 2 * L, tp = 3 + 2 * L;
@@ -158,16 +167,18 @@ __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
             out(p.G, 0)[i] = G;
             constexpr int d = 2 << L;                    // shift of level L + 1
             constexpr int ng = tg + 2, np = tp + 2;
-            out(p.send, 0)[i] = P ^ tr(p.ta, ng)[i];  out(p.send, 1)[i] = (G << d) ^ tr(p.tb, ng)[i];
+            send(0, P ^ tr(p.ta, ng)[i]);  send(1, (G << d) ^ tr(p.tb, ng)[i]);
             if constexpr (L + 1 < 5) {                   // the last level needs no P update
-                out(p.send, 2)[i] = P ^ tr(p.ta, np)[i];  out(p.send, 3)[i] = (P << d) ^ tr(p.tb, np)[i];
+                send(2, P ^ tr(p.ta, np)[i]);  send(3, (P << d) ^ tr(p.tb, np)[i]);
             }
         } else if constexpr (STAGE == 8) {
             const T T1 = and_finish<T>(party, o[0], o[1], tr(p.ta, 12)[i], tr(p.tb, 12)[i], tr(p.tc, 12)[i]);
             const T G = in(p.G, 0)[i] ^ T1;
             const B s = reinterpret_cast<const B*>(p.p63)[i] ^ to_bytes((G >> 62) & 1);
             if (p.s_bit) reinterpret_cast<B*>(p.s_bit)[i] = s;
-            reinterpret_cast<B*>(p.vsend)[i] = s ^ reinterpret_cast<const B*>(p.rb)[i];
+            const B masked = s ^ reinterpret_cast<const B*>(p.rb)[i];
+            reinterpret_cast<B*>(p.vsend)[i] = masked;
+            if constexpr (PUT) { reinterpret_cast<B*>(p.vput[0])[i] = masked; reinterpret_cast<B*>(p.vput[1])[i] = masked; }
         } else if constexpr (STAGE == 9) {
             const T v = to_words(reinterpret_cast<const B*>(p.vsend)[i] ^ reinterpret_cast<const B*>(p.vrecv[0])[i] ^
                                  reinterpret_cast<const B*>(p.vrecv[1])[i]);
@@ -176,8 +187,8 @@ __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
             if (party == 0) sa += v;
             if (p.s_arith) out(p.s_arith, 0)[i] = sa;
             const T m = (party == 0 ? (u64)1 : (u64)0) - sa;
-            out(p.send, 0)[i] = in(p.x, 0)[i] - in(p.ma, 0)[i];
-            out(p.send, 1)[i] = m - in(p.mb, 0)[i];
+            send(0, in(p.x, 0)[i] - in(p.ma, 0)[i]);
+            send(1, m - in(p.mb, 0)[i]);
         } else {
             // additive opening of the select product's masked operands
             const T e = in(p.send, 0)[i] + in(p.recv[0], 0)[i] + in(p.recv[1], 0)[i];
@@ -273,7 +284,7 @@ __device__ __forceinline__ void st2(u64* p, size_t j, u64 a, u64 b)
 // LEVEL 0, else level LEVEL - 1 on packed words) for the four input words behind two
 // output words, regroup, and mask this level's operands.  `vec0`: the whole-word arrays
 // of LEVEL 0 allow 16-byte loads (n a multiple of four, aligned bases).
-template <int LEVEL>
+template <int LEVEL, bool PUT>
 __global__ __launch_bounds__(kT) void k3_plevel(Relu3Args q, Msb3Geom g, bool vec0)
 {
     const int party = blockIdx.y;
@@ -325,12 +336,20 @@ __global__ __launch_bounds__(kT) void k3_plevel(Relu3Args q, Msb3Geom g, bool ve
         const size_t pl = g.pw[LEVEL];
         u64* so = p.sendL + g.loff[LEVEL];
         const u64v2 na1 = *reinterpret_cast<const u64v2*>(p.ta + g.toff[ng] + j), nb1 = *reinterpret_cast<const u64v2*>(p.tb + g.toff[ng] + j);
-        st2(so, j, X[0] ^ na1.x, X[1] ^ na1.y);
-        st2(so + pl, j, Y1[0] ^ nb1.x, Y1[1] ^ nb1.y);
+        // row r of this level's block: own send buffer and, by remote store, both peers' receive blocks
+        auto send2 = [&](int r, u64 a, u64 b) {
+            st2(so + (size_t)r * pl, j, a, b);
+            if constexpr (PUT) {
+                st2(p.putL[0] + g.loff[LEVEL] + (size_t)r * pl, j, a, b);
+                st2(p.putL[1] + g.loff[LEVEL] + (size_t)r * pl, j, a, b);
+            }
+        };
+        send2(0, X[0] ^ na1.x, X[1] ^ na1.y);
+        send2(1, Y1[0] ^ nb1.x, Y1[1] ^ nb1.y);
         if constexpr (LEVEL < 5) {                               // the last level needs no P update
             const u64v2 na2 = *reinterpret_cast<const u64v2*>(p.ta + g.toff[np] + j), nb2 = *reinterpret_cast<const u64v2*>(p.tb + g.toff[np] + j);
-            st2(so + 2 * pl, j, X[0] ^ na2.x, X[1] ^ na2.y);
-            st2(so + 3 * pl, j, Y2[0] ^ nb2.x, Y2[1] ^ nb2.y);
+            send2(2, X[0] ^ na2.x, X[1] ^ na2.y);
+            send2(3, Y2[0] ^ nb2.x, Y2[1] ^ nb2.y);
         }
         st2(p.gsel + g.goff[LEVEL], j, Gk[0], Gk[1]);
     }
@@ -338,7 +357,7 @@ __global__ __launch_bounds__(kT) void k3_plevel(Relu3Args q, Msb3Geom g, bool ve
 
 // Packed sign stage: finish level 5; element i's carry into bit 63 sits at bit
 // (62 + i) mod 64 of word i / 64.  Then the B2A mask as in stage 8 of the whole-word chain.
-template <int V>
+template <int V, bool PUT>
 __global__ __launch_bounds__(kT) void k3_psign(Relu3Args q, Msb3Geom g)
 {
     const int party = blockIdx.y;
@@ -361,10 +380,13 @@ __global__ __launch_bounds__(kT) void k3_psign(Relu3Args q, Msb3Geom g)
             const uint32_t sb = top ^ carry;
             if (p.s_bit) *reinterpret_cast<uint32_t*>(p.s_bit + i) = sb;
             *reinterpret_cast<uint32_t*>(p.vsend + i) = sb ^ rb;
+            if constexpr (PUT) { *reinterpret_cast<uint32_t*>(p.vput[0] + i) = sb ^ rb; *reinterpret_cast<uint32_t*>(p.vput[1] + i) = sb ^ rb; }
         } else {
             const u8 sb = (u8)(p.p63[i] ^ (u8)((Gw >> ((62 + i) & 63)) & 1));
             if (p.s_bit) p.s_bit[i] = sb;
-            p.vsend[i] = (u8)(sb ^ p.rb[i]);
+            const u8 masked = (u8)(sb ^ p.rb[i]);
+            p.vsend[i] = masked;
+            if constexpr (PUT) { p.vput[0][i] = masked; p.vput[1][i] = masked; }
         }
     }
 }
@@ -392,14 +414,48 @@ __global__ __launch_bounds__(kT) void k3_pack_triples(const u64* __restrict__ in
     }
 }
 
-template <int STAGE>
-int launch_stage(mpc_ctx* c, hipStream_t st, const Relu3Args& q, int vec)
+// Arguments of one stage launch when the exchange is by remote store: the launch with index k
+// reads the receive-buffer set (k - 1) & 1 and stores into the peers' set k & 1, so that no party
+// stores where a peer's same launch still reads.  Party i's words land in recv[s] of party
+// (i + 2 - s) mod 3, the buffer that party reads for its peer number s.
+Relu3Args put_args(const Relu3Args& q, int k)
 {
-    if (vec == 4)      hipLaunchKernelGGL((k3_relu<STAGE, u64v4>), dim3(grid3(q.n / 4), 3), dim3(kT), 0, st, q);
-    else if (vec == 2) hipLaunchKernelGGL((k3_relu<STAGE, u64v2>), dim3(grid3(q.n / 2), 3), dim3(kT), 0, st, q);
-    else               hipLaunchKernelGGL((k3_relu<STAGE, u64>), dim3(grid3(q.n), 3), dim3(kT), 0, st, q);
+    Relu3Args a = q;
+    for (int i = 0; i < 3; ++i)
+        for (int s = 0; s < 2; ++s) {
+            const int peer = (i + 2 - s) % 3;
+            u64* const rd[2] = { q.p[i].recv[s], q.p[i].recv_alt[s] };
+            u64* const wr[2] = { q.p[peer].recv[s], q.p[peer].recv_alt[s] };
+            a.p[i].recv[s] = rd[(k + 1) & 1];
+            a.p[i].put[s] = wr[k & 1];
+            a.p[i].putL[s] = q.p[peer].recvL[s];
+            a.p[i].vput[s] = q.p[peer].vrecv[s];
+        }
+    return a;
+}
+
+template <int STAGE, bool PUT>
+int launch_stage_t(mpc_ctx* c, hipStream_t st, const Relu3Args& q, int vec)
+{
+    if (vec == 4)      hipLaunchKernelGGL((k3_relu<STAGE, u64v4, PUT>), dim3(grid3(q.n / 4), 3), dim3(kT), 0, st, q);
+    else if (vec == 2) hipLaunchKernelGGL((k3_relu<STAGE, u64v2, PUT>), dim3(grid3(q.n / 2), 3), dim3(kT), 0, st, q);
+    else               hipLaunchKernelGGL((k3_relu<STAGE, u64, PUT>), dim3(grid3(q.n), 3), dim3(kT), 0, st, q);
     MPC_HIP(c, hipGetLastError());
     return MPC_OK;
+}
+
+int exchange_words(mpc_ctx* c, hipStream_t st, const Relu3Args& q, int words);
+int exchange_bytes(mpc_ctx* c, hipStream_t st, const Relu3Args& q);
+
+// Stage STAGE for all three parties, then the exchange of what it sends: `rows` word rows,
+// bytes for rows < 0, nothing for rows == 0.  By remote store the kernel itself delivers.
+template <int STAGE>
+int launch_stage(mpc_ctx* c, hipStream_t st, const Relu3Args& q, int vec, int rows)
+{
+    if (c->exchange_put && rows != 0) return launch_stage_t<STAGE, true>(c, st, put_args(q, STAGE), vec);
+    MPC_TRY((launch_stage_t<STAGE, false>(c, st, c->exchange_put ? put_args(q, STAGE) : q, vec)));
+    if (c->exchange_put || rows == 0) return MPC_OK;
+    return rows > 0 ? exchange_words(c, st, q, rows) : exchange_bytes(c, st, q);
 }
 
 // every party's first `words` rows of its send buffer go to both peers
@@ -413,6 +469,16 @@ int exchange_words(mpc_ctx* c, hipStream_t st, const Relu3Args& q, int words)
     return launch_copy_multi(c, st, cp, 6);
 }
 
+// the masked sign bytes of every party go to both peers
+int exchange_bytes(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
+{
+    CopySeg cp[6]; int k = 0;
+    for (int i = 0; i < 3; ++i)
+        for (int s = 0; s < 2; ++s)
+            cp[k++] = CopySeg{ q.p[(i + 1 + s) % 3].vsend, q.p[i].vrecv[s], q.n, 0 };
+    return launch_copy_multi(c, st, cp, 6);
+}
+
 size_t relu3_ws(u8* base, size_t cap, size_t n, Relu3Args* q, bool* ok)
 {
     WsAlloc w(base, cap);
@@ -423,6 +489,8 @@ size_t relu3_ws(u8* base, size_t cap, size_t n, Relu3Args* q, bool* ok)
         p.send = w.take<u64>(4 * n); p.recv[0] = w.take<u64>(4 * n); p.recv[1] = w.take<u64>(4 * n);
         p.p63 = w.take<u8>(n); p.vsend = w.take<u8>(n); p.vrecv[0] = w.take<u8>(n); p.vrecv[1] = w.take<u8>(n);
     }
+    for (int i = 0; i < 3; ++i)      // only touched by the remote-store exchange
+        for (int s = 0; s < 2; ++s) q->p[i].recv_alt[s] = w.take<u64>(4 * n);
     if (ok) *ok = w.ok;
     return w.off;
 }
@@ -466,24 +534,17 @@ int relu3_chunk(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
         }
         MPC_TRY(launch_copy_multi(c, st, cp, 6));
     }
-    MPC_TRY(launch_stage<0>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<1>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<2>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<3>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<4>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<5>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<6>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 4));
-    MPC_TRY(launch_stage<7>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<8>(c, st, q, vec));
-    {
-        CopySeg cp[6]; int k = 0;
-        for (int i = 0; i < 3; ++i)
-            for (int s = 0; s < 2; ++s)
-                cp[k++] = CopySeg{ q.p[(i + 1 + s) % 3].vsend, q.p[i].vrecv[s], n, 0 };
-        MPC_TRY(launch_copy_multi(c, st, cp, 6));
-    }
-    MPC_TRY(launch_stage<9>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<10>(c, st, q, vec));
+    MPC_TRY(launch_stage<0>(c, st, q, vec, 2));
+    MPC_TRY(launch_stage<1>(c, st, q, vec, 2));
+    MPC_TRY(launch_stage<2>(c, st, q, vec, 4));
+    MPC_TRY(launch_stage<3>(c, st, q, vec, 4));
+    MPC_TRY(launch_stage<4>(c, st, q, vec, 4));
+    MPC_TRY(launch_stage<5>(c, st, q, vec, 4));
+    MPC_TRY(launch_stage<6>(c, st, q, vec, 4));
+    MPC_TRY(launch_stage<7>(c, st, q, vec, 2));
+    MPC_TRY(launch_stage<8>(c, st, q, vec, -1));
+    MPC_TRY(launch_stage<9>(c, st, q, vec, 2));
+    MPC_TRY(launch_stage<10>(c, st, q, vec, 0));
     return MPC_OK;
 }
 
@@ -534,6 +595,8 @@ size_t relu3_msb_ws(u8* base, size_t cap, size_t n, const Msb3Geom& g, Relu3Args
         p.sendL = w.take<u64>(g.words_blocks); p.recvL[0] = w.take<u64>(g.words_blocks); p.recvL[1] = w.take<u64>(g.words_blocks);
         p.gsel = w.take<u64>(g.words_gsel);
     }
+    for (int i = 0; i < 3; ++i)      // only touched by the remote-store exchange
+        for (int s = 0; s < 2; ++s) q->p[i].recv_alt[s] = w.take<u64>(2 * n);
     if (ok) *ok = w.ok;
     return w.off;
 }
@@ -542,7 +605,14 @@ template <int LEVEL>
 int launch_plevel(mpc_ctx* c, hipStream_t st, const Relu3Args& q, const Msb3Geom& g, bool vec0)
 {
     const size_t words = (q.n + ((size_t)2 << LEVEL) - 1) >> (LEVEL + 1);
-    hipLaunchKernelGGL(k3_plevel<LEVEL>, dim3(grid3((words + 1) / 2), 3), dim3(kT), 0, st, q, g, vec0);
+    const dim3 grid(grid3((words + 1) / 2), 3), block(kT);
+    if (c->exchange_put) {
+        // level 0 reads the whole words stage 1 delivered (launch index 2); the levels' own blocks do not alternate
+        hipLaunchKernelGGL((k3_plevel<LEVEL, true>), grid, block, 0, st, put_args(q, 2), g, vec0);
+        MPC_HIP(c, hipGetLastError());
+        return MPC_OK;
+    }
+    hipLaunchKernelGGL((k3_plevel<LEVEL, false>), grid, block, 0, st, q, g, vec0);
     MPC_HIP(c, hipGetLastError());
     // this level's masked packed words go to both peers
     const size_t len = (size_t)(LEVEL < 5 ? 4 : 2) * g.pw[LEVEL] * sizeof(u64);
@@ -567,26 +637,28 @@ int relu3_msb_run(mpc_ctx* c, hipStream_t st, const Relu3Args& q, const Msb3Geom
         }
         MPC_TRY(launch_copy_multi(c, st, cp, 6));
     }
-    MPC_TRY(launch_stage<0>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<1>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
+    MPC_TRY(launch_stage<0>(c, st, q, vec, 2));
+    MPC_TRY(launch_stage<1>(c, st, q, vec, 2));
     MPC_TRY(launch_plevel<0>(c, st, q, g, vec0));
     MPC_TRY(launch_plevel<1>(c, st, q, g, vec0));
     MPC_TRY(launch_plevel<2>(c, st, q, g, vec0));
     MPC_TRY(launch_plevel<3>(c, st, q, g, vec0));
     MPC_TRY(launch_plevel<4>(c, st, q, g, vec0));
     MPC_TRY(launch_plevel<5>(c, st, q, g, vec0));
-    if (vec == 4) hipLaunchKernelGGL(k3_psign<4>, dim3(grid3(n / 4), 3), dim3(kT), 0, st, q, g);
-    else          hipLaunchKernelGGL(k3_psign<1>, dim3(grid3(n), 3), dim3(kT), 0, st, q, g);
-    MPC_HIP(c, hipGetLastError());
-    {
-        CopySeg cp[6]; int k = 0;
-        for (int i = 0; i < 3; ++i)
-            for (int s = 0; s < 2; ++s)
-                cp[k++] = CopySeg{ q.p[(i + 1 + s) % 3].vsend, q.p[i].vrecv[s], n, 0 };
-        MPC_TRY(launch_copy_multi(c, st, cp, 6));
+    const dim3 sgrid(vec == 4 ? grid3(n / 4) : grid3(n), 3), block(kT);
+    if (c->exchange_put) {
+        const Relu3Args a = put_args(q, 8);
+        if (vec == 4) hipLaunchKernelGGL((k3_psign<4, true>), sgrid, block, 0, st, a, g);
+        else          hipLaunchKernelGGL((k3_psign<1, true>), sgrid, block, 0, st, a, g);
+        MPC_HIP(c, hipGetLastError());
+    } else {
+        if (vec == 4) hipLaunchKernelGGL((k3_psign<4, false>), sgrid, block, 0, st, q, g);
+        else          hipLaunchKernelGGL((k3_psign<1, false>), sgrid, block, 0, st, q, g);
+        MPC_HIP(c, hipGetLastError());
+        MPC_TRY(exchange_bytes(c, st, q));
     }
-    MPC_TRY(launch_stage<9>(c, st, q, vec));  MPC_TRY(exchange_words(c, st, q, 2));
-    MPC_TRY(launch_stage<10>(c, st, q, vec));
+    MPC_TRY(launch_stage<9>(c, st, q, vec, 2));
+    MPC_TRY(launch_stage<10>(c, st, q, vec, 0));
     return MPC_OK;
 }
 

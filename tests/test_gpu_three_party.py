@@ -17,11 +17,13 @@ def mpc():
     return m
 
 
-@pytest.fixture(params=["three-streams", "single-queue"])
+@pytest.fixture(params=["three-streams", "single-queue", "single-queue-put"])
 def lane(mpc, request):
     ln = mpc.Lane(0)
-    if request.param == "single-queue":
+    if request.param != "three-streams":
         ln.use_single_queue()
+    if request.param == "single-queue-put":
+        ln.set_exchange("put")
     yield ln
     ln.sync()
     ln.close()
@@ -155,11 +157,12 @@ def test_relu3(mpc, lane, n, packed):
 
 
 @PACKED
+@pytest.mark.parametrize("exchange", ["copy", "put"])
 @pytest.mark.parametrize("n", [786434, 786435, 1100000])
-def test_relu3_in_several_chunks(mpc, n, packed):
+def test_relu3_in_several_chunks(mpc, n, packed, exchange):
     """Above about 3/4 M elements the whole-word chain runs chunk by chunk: even and odd totals, ragged
     last chunk.  The sign-only chain takes the same sizes in one pass (several grid strides per thread)."""
-    lane = mpc.Lane(0); lane.use_single_queue()
+    lane = mpc.Lane(0); lane.use_single_queue(); lane.set_exchange(exchange)
     rng = np.random.default_rng(n)
     X = synth.normal_fixed(rng, n, 4.0)
     x = synth.share_additive3(rng, X)

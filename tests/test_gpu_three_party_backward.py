@@ -17,11 +17,13 @@ def mpc():
     return m
 
 
-@pytest.fixture(params=["three-streams", "single-queue"])
+@pytest.fixture(params=["three-streams", "single-queue", "single-queue-put"])
 def lane(mpc, request):
     ln = mpc.Lane(0)
-    if request.param == "single-queue":
+    if request.param != "three-streams":
         ln.use_single_queue()
+    if request.param == "single-queue-put":
+        ln.set_exchange("put")
     yield ln
     ln.sync()
     ln.close()
