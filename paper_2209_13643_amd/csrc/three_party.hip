@@ -5,7 +5,8 @@
 // and the element-wise steps of the backward pass (Sec. 5.3).  Everything here
 // is bound by HBM; all launches go to the lane's first stream, one launch per
 // step for all three parties (blockIdx.y = party), and every exchange is a copy
-// kernel.  The linear layers with three parties live in linear.hip.
+// kernel or, on request, a remote store by the stage kernel itself.  The linear
+// layers with three parties live in linear.hip.
 #include "common.h"
 #include "msb_pack.h"
 
