@@ -516,6 +516,30 @@ int mpc_maxpool3_msb(mpc_ctx* ctx, mpc_cshare3 x, const mpc_relu3_material* mat1
                      const mpc_relu3_material* mat2, mpc_share3 y,
                      int B, int H, int W, int C);
 
+/* Prepared layers with three parties, as mpc_*_prepared for two: right_planes
+ * holds the planes of f, b_0 + f, b_1, b_2 (needs b and the opened f_public),
+ * left_planes those of a_0, a_1, a_2; sizes from mpc_*3_prepared_bytes, buffers
+ * caller-owned and 16-byte aligned, either may be NULL in the prepare call;
+ * the online calls need right_planes, left_planes may be NULL.  Same words as
+ * mpc_beaver_matmul3 / mpc_conv2d3 with f_public; no rescale inside. */
+int mpc_matmul3_prepared_bytes(int M, int K, int N, int batch, size_t* right, size_t* left);
+int mpc_conv2d3_prepared_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                               int pad, int stride, size_t* right, size_t* left);
+int mpc_matmul3_prepare(mpc_ctx* ctx, mpc_cshare3 a, mpc_cshare3 b, const uint64_t* f_public,
+                        void* right_planes, void* left_planes,
+                        int M, int K, int N, int batch, int flags);
+int mpc_conv2d3_prepare(mpc_ctx* ctx, mpc_cshare3 a, mpc_cshare3 b, const uint64_t* f_public,
+                        void* right_planes, void* left_planes,
+                        int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                        int pad, int stride);
+int mpc_beaver_matmul3_prepared(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 a, mpc_cshare3 c, mpc_share3 z,
+                                const void* right_planes, const void* left_planes,
+                                int M, int K, int N, int batch, int flags);
+int mpc_conv2d3_prepared(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 a, mpc_cshare3 c, mpc_share3 z,
+                         const void* right_planes, const void* left_planes,
+                         int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                         int pad, int stride);
+
 /* Backward pass with three parties (Sec. 4.1 and Sec. 5.3 for N = 3): the
  * gradient products are Alg. 1 with another bilinear map, as for two parties.
  * Dense layers: mpc_beaver_matmul3 with MPC_TRANS_X / MPC_TRANS_Y.

@@ -524,7 +524,8 @@ def bench_three_parties(reps: int = 20):
                 msb_hbm_frac=msb_bytes * n / (msb_med * 1e-3) / 8.0e12)
 
 
-def bench_pipeline3(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = False, pool_first: bool = False):
+def bench_pipeline3(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_relu: bool = False, pool_first: bool = False,
+                    prepared: bool = False, exchange: str = "copy"):
     """Config 4's network with three parties: serial on one lane vs one lane per micro-batch."""
     wl = synth.config_vgg16_pipeline(micro_batch)
     layers = wl.layers
@@ -539,7 +540,10 @@ def bench_pipeline3(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_
         states.append(pipeline.deal_microbatch3(lanes[m], g, layers, weights, packed_relu=packed_relu, pool_first=pool_first))
         xs.append(dealer.share3(g, dealer.normal_fixed(g, (micro_batch, 32, 32, 3), 1.0, dev)))
         torch.cuda.synchronize()
+        lanes[m].set_exchange(exchange)
         pipeline.preopen_weights3(lanes[m], states[m])
+        if prepared:
+            pipeline.prepare_layers3(lanes[m], layers, states[m])
     res = {}
     for mode in ("serial", "pipelined"):
         best = None
@@ -637,10 +641,12 @@ def main(argv):
               f"{r['relu_bytes_per_element']} B per element -> {100 * r['relu_hbm_frac']:.1f}% of 8 TB/s", flush=True)
         print(f"  the same ReLU on the sign's carry chain only: {r['msb_ms']:.3f} ms (min {r['msb_min_ms']:.3f}), {r['msb_elems_per_s'] / 1e9:.2f} G elems/s; "
               f"{r['msb_bytes_per_element']} B per element -> {100 * r['msb_hbm_frac']:.1f}% of 8 TB/s", flush=True)
-        for packed, pf in ((False, False), (True, False), (True, True)):
-            p = bench_pipeline3(packed_relu=packed, pool_first=pf)
+        for packed, pf, prep, ex in ((False, False, False, "copy"), (True, False, False, "copy"), (True, True, False, "copy"),
+                                     (True, True, True, "put")):
+            p = bench_pipeline3(packed_relu=packed, pool_first=pf, prepared=prep, exchange=ex)
             print(f"  VGG16-CIFAR forward with three parties, batch 128 = 4 x 32 ({'sign-only packed' if packed else 'whole-word'} ReLU"
-                  f"{', pooled layers as ReLU(maxpool(z))' if pf else ''}, weight masks opened ahead): "
+                  f"{', pooled layers as ReLU(maxpool(z))' if pf else ''}{', prepared planes' if prep else ''}"
+                  f"{', ReLU exchange by remote store' if ex == 'put' else ''}, weight masks opened ahead): "
                   f"serial {p['serial']['ms']:.2f} ms ({p['serial']['images_per_s']:.0f} img/s), "
                   f"one lane per micro-batch {p['pipelined']['ms']:.2f} ms ({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)
         for packed in (False, True):

@@ -441,17 +441,32 @@ LinearWs3 carve3(u8* base, size_t cap, const LinearShape& s)
 // contraction [e | a_i] x [b_i (+ f for party 0) ; f] for parties 0 and 1 in
 // one launch and for party 2 in a second one.
 int beaver_linear3(mpc_ctx* c, const LinearShape& s, mpc_cshare3 x, mpc_cshare3 y,
-                   mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 cc, mpc_share3 z, const u64* f_public, size_t ws_off = 0)
+                   mpc_cshare3 a, mpc_cshare3 b, mpc_cshare3 cc, mpc_share3 z, const u64* f_public, size_t ws_off = 0,
+                   const u8* prep_right = nullptr, const u8* prep_left = nullptr)
 {
     if (!c) return MPC_EINVAL;
     MPC_TRY(check_shape(s));
+    // prepared planes: digit planes of the input-independent operands, recoded ahead of time
+    const bool skip_right = prep_right != nullptr, skip_left = prep_left != nullptr;
     for (int i = 0; i < 3; ++i) {
-        if (!x.p[i] || !a.p[i] || !b.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
-        if (!f_public && !y.p[i]) return MPC_EINVAL;
+        if (!x.p[i] || !a.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
+        if (!skip_right && !b.p[i]) return MPC_EINVAL;
+        if (!skip_right && !f_public && !y.p[i]) return MPC_EINVAL;
     }
+    if ((skip_right && ((uintptr_t)prep_right & 15)) || (skip_left && ((uintptr_t)prep_left & 15))) return MPC_EINVAL;
     if (ws_off > c->ws_bytes) return MPC_ENOMEM;
     LinearWs3 w = carve3(c->ws ? c->ws + ws_off : nullptr, c->ws_bytes - ws_off, s);
     if (!w.ok) return MPC_ENOMEM;
+    if (skip_right) {
+        const size_t rp = align_up(8 * s.R_plane * s.batch);
+        w.pr_f = const_cast<u8*>(prep_right);
+        for (int i = 0; i < 3; ++i) w.pr_b[i] = w.pr_f + (size_t)(i + 1) * rp;
+    }
+    if (skip_left) {
+        const size_t lp = align_up(8 * s.L_plane * s.batch);
+        for (int i = 0; i < 3; ++i) w.pl_a[i] = const_cast<u8*>(prep_left) + (size_t)i * lp;
+    }
+    const bool have_f = f_public != nullptr || skip_right;
     hipStream_t st = c->s[0];
     MPC_TRY(lane_join(c));
     const int pi = prof_begin(c, MPC_PROF_LINEAR, st);
@@ -459,7 +474,7 @@ int beaver_linear3(mpc_ctx* c, const LinearShape& s, mpc_cshare3 x, mpc_cshare3 
     // Alg. 1: every party masks its shares ...
     SubSeg sub[6]; int ns = 0;
     for (int i = 0; i < 3; ++i) sub[ns++] = SubSeg{ x.p[i], a.p[i], w.se[i], s.nx, 0, nullptr };
-    for (int i = 0; i < 3 && !f_public; ++i) sub[ns++] = SubSeg{ y.p[i], b.p[i], w.sf[i], s.nw, 0, nullptr };
+    for (int i = 0; i < 3 && !have_f; ++i) sub[ns++] = SubSeg{ y.p[i], b.p[i], w.sf[i], s.nw, 0, nullptr };
     MPC_TRY(launch_sub_multi(c, st, sub, ns));
     // ... and broadcasts them: party i receives from party i+1 and party i+2
     CopySeg cp[6];
@@ -467,7 +482,7 @@ int beaver_linear3(mpc_ctx* c, const LinearShape& s, mpc_cshare3 x, mpc_cshare3 
         for (int k = 0; k < 2; ++k)
             cp[2 * i + k] = CopySeg{ (const u8*)w.se[(i + 1 + k) % 3], (u8*)w.re[i][k], s.nx * sizeof(u64), 0 };
     MPC_TRY(launch_copy_multi(c, st, cp, 6));
-    if (!f_public) {
+    if (!have_f) {
         for (int i = 0; i < 3; ++i)
             for (int k = 0; k < 2; ++k)
                 cp[2 * i + k] = CopySeg{ (const u8*)w.sf[(i + 1 + k) % 3], (u8*)w.rf[i][k], s.nw * sizeof(u64), 0 };
@@ -476,21 +491,25 @@ int beaver_linear3(mpc_ctx* c, const LinearShape& s, mpc_cshare3 x, mpc_cshare3 
     // Delta and epsilon (all parties hold the same three words; formed once, from party 0's buffers)
     MPC_TRY(launch_sum3(c, st, w.se[0], w.re[0][0], w.re[0][1], w.e_pub, s.nx));
     const u64* f = f_public;
-    if (!f) { MPC_TRY(launch_sum3(c, st, w.sf[0], w.rf[0][0], w.rf[0][1], w.f_pub, s.nw)); f = w.f_pub; }
+    if (!have_f) { MPC_TRY(launch_sum3(c, st, w.sf[0], w.rf[0][0], w.rf[0][1], w.f_pub, s.nw)); f = w.f_pub; }
 
     // digit planes
     {
-        const u64* src[3] = { a.p[0], a.p[1], a.p[2] };
-        const u64* none[3] = { nullptr, nullptr, nullptr };
-        u8* dst[3] = { w.pl_a[0], w.pl_a[1], w.pl_a[2] };
-        MPC_TRY(launch_left(c, st, s, 3, src, none, dst));
+        if (!skip_left) {
+            const u64* src[3] = { a.p[0], a.p[1], a.p[2] };
+            const u64* none[3] = { nullptr, nullptr, nullptr };
+            u8* dst[3] = { w.pl_a[0], w.pl_a[1], w.pl_a[2] };
+            MPC_TRY(launch_left(c, st, s, 3, src, none, dst));
+        }
         MPC_TRY(launch_left1(c, st, s, w.e_pub, nullptr, w.pl_e));
-        RecodeArgs rr[4];
-        rr[0] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
-        rr[1] = recode_right(s, b.p[2], nullptr, nullptr, w.pr_b[2]);
-        rr[2] = recode_right(s, f, nullptr, nullptr, w.pr_f);
-        rr[3] = recode_right(s, b.p[0], f, nullptr, w.pr_b[0]);
-        MPC_TRY(launch_recode_multi(c, st, rr, 4));
+        if (!skip_right) {
+            RecodeArgs rr[4];
+            rr[0] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
+            rr[1] = recode_right(s, b.p[2], nullptr, nullptr, w.pr_b[2]);
+            rr[2] = recode_right(s, f, nullptr, nullptr, w.pr_f);
+            rr[3] = recode_right(s, b.p[0], f, nullptr, w.pr_b[0]);
+            MPC_TRY(launch_recode_multi(c, st, rr, 4));
+        }
     }
 
     GemmArgs g{};
@@ -567,6 +586,40 @@ int ring_product(mpc_ctx* c, const LinearShape& s, const u64* L, const u64* R, u
     MPC_TRY(launch_limb_gemm(c, P0, g));
     MPC_TRY(chain(c, P0, c->s[1]));
     return MPC_OK;
+}
+
+// Three parties: right = [f | b_0 + f | b_1 | b_2], left = [a_0 | a_1 | a_2].
+void prepared_sizes3(const LinearShape& s, size_t* right, size_t* left)
+{
+    if (right) *right = 4 * align_up(8 * s.R_plane * s.batch);
+    if (left) *left = 3 * align_up(8 * s.L_plane * s.batch);
+}
+
+int prepare_planes3(mpc_ctx* c, const LinearShape& s, mpc_cshare3 a, mpc_cshare3 b, const u64* f_public,
+                    u8* right, u8* left)
+{
+    if (!c || (!right && !left)) return MPC_EINVAL;
+    MPC_TRY(check_shape(s));
+    if (right && (!f_public || !b.p[0] || !b.p[1] || !b.p[2] || ((uintptr_t)right & 15))) return MPC_EINVAL;
+    if (left && (!a.p[0] || !a.p[1] || !a.p[2] || ((uintptr_t)left & 15))) return MPC_EINVAL;
+    hipStream_t st = c->s[0];
+    MPC_TRY(lane_join(c));
+    if (left) {
+        const size_t lp = align_up(8 * s.L_plane * s.batch);
+        const u64* src[3] = { a.p[0], a.p[1], a.p[2] }; const u64* none[3] = { nullptr, nullptr, nullptr };
+        u8* dst[3] = { left, left + lp, left + 2 * lp };
+        MPC_TRY(launch_left(c, st, s, 3, src, none, dst));
+    }
+    if (right) {
+        const size_t rp = align_up(8 * s.R_plane * s.batch);
+        RecodeArgs rr[4];
+        rr[0] = recode_right(s, f_public, nullptr, nullptr, right);
+        rr[1] = recode_right(s, b.p[0], f_public, nullptr, right + rp);
+        rr[2] = recode_right(s, b.p[1], nullptr, nullptr, right + 2 * rp);
+        rr[3] = recode_right(s, b.p[2], nullptr, nullptr, right + 3 * rp);
+        MPC_TRY(launch_recode_multi(c, st, rr, 4));
+    }
+    return lane_fanout(c);
 }
 
 }  // namespace
@@ -796,6 +849,64 @@ int mpc_conv2d3(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 w, mpc_cshare3 a, mpc_c
     if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
         return MPC_EINVAL;
     return beaver_linear3(ctx, shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride), x, w, a, b, c, z, f_public);
+}
+
+int mpc_matmul3_prepared_bytes(int M, int K, int N, int batch, size_t* right, size_t* left)
+{
+    if (M <= 0 || K <= 0 || N <= 0 || batch <= 0) return MPC_EINVAL;
+    LinearShape s = shape_matmul(M, K, N, batch);
+    MPC_TRY(check_shape(s));
+    prepared_sizes3(s, right, left);
+    return MPC_OK;
+}
+
+int mpc_conv2d3_prepared_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride,
+                               size_t* right, size_t* left)
+{
+    if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
+        return MPC_EINVAL;
+    LinearShape s = shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride);
+    MPC_TRY(check_shape(s));
+    prepared_sizes3(s, right, left);
+    return MPC_OK;
+}
+
+int mpc_matmul3_prepare(mpc_ctx* ctx, mpc_cshare3 a, mpc_cshare3 b, const uint64_t* f_public,
+                        void* right_planes, void* left_planes, int M, int K, int N, int batch, int flags)
+{
+    if (M <= 0 || K <= 0 || N <= 0 || batch <= 0 || (flags & ~(MPC_TRANS_X | MPC_TRANS_Y))) return MPC_EINVAL;
+    return prepare_planes3(ctx, shape_matmul(M, K, N, batch, flags), a, b, f_public, (u8*)right_planes, (u8*)left_planes);
+}
+
+int mpc_conv2d3_prepare(mpc_ctx* ctx, mpc_cshare3 a, mpc_cshare3 b, const uint64_t* f_public,
+                        void* right_planes, void* left_planes,
+                        int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
+        return MPC_EINVAL;
+    return prepare_planes3(ctx, shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride), a, b, f_public,
+                           (u8*)right_planes, (u8*)left_planes);
+}
+
+int mpc_beaver_matmul3_prepared(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 a, mpc_cshare3 c, mpc_share3 z,
+                                const void* right_planes, const void* left_planes,
+                                int M, int K, int N, int batch, int flags)
+{
+    if (M <= 0 || K <= 0 || N <= 0 || batch <= 0 || !right_planes || (flags & ~(MPC_TRANS_X | MPC_TRANS_Y))) return MPC_EINVAL;
+    const mpc_cshare3 none = { { nullptr, nullptr, nullptr } };
+    return beaver_linear3(ctx, shape_matmul(M, K, N, batch, flags), x, none, a, none, c, z, nullptr, 0,
+                          (const u8*)right_planes, (const u8*)left_planes);
+}
+
+int mpc_conv2d3_prepared(mpc_ctx* ctx, mpc_cshare3 x, mpc_cshare3 a, mpc_cshare3 c, mpc_share3 z,
+                         const void* right_planes, const void* left_planes,
+                         int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0 || !right_planes)
+        return MPC_EINVAL;
+    const mpc_cshare3 none = { { nullptr, nullptr, nullptr } };
+    return beaver_linear3(ctx, shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride), x, none, a, none, c, z, nullptr, 0,
+                          (const u8*)right_planes, (const u8*)left_planes);
 }
 
 size_t mpc_conv2d3_grad_x_workspace_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)

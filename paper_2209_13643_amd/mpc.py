@@ -69,6 +69,8 @@ EXPORTS = [
     "mpc_maxpool3_workspace_bytes", "mpc_maxpool3",
     "mpc_relu3_packed_words", "mpc_relu3_pack_triples", "mpc_relu3_msb_workspace_bytes", "mpc_relu3_msb",
     "mpc_maxpool3_msb_workspace_bytes", "mpc_maxpool3_msb",
+    "mpc_matmul3_prepared_bytes", "mpc_conv2d3_prepared_bytes", "mpc_matmul3_prepare", "mpc_conv2d3_prepare",
+    "mpc_beaver_matmul3_prepared", "mpc_conv2d3_prepared",
     "mpc_conv2d3_grad_x_workspace_bytes", "mpc_conv2d3_grad_w_workspace_bytes", "mpc_conv2d3_grad_x", "mpc_conv2d3_grad_w",
     "mpc_add3", "mpc_sub3", "mpc_mul3_workspace_bytes", "mpc_mul3", "mpc_relu3_backward", "mpc_maxpool3_signs",
     "mpc_maxpool3_backward_workspace_bytes", "mpc_maxpool3_backward",
@@ -164,6 +166,12 @@ def lib():
     L.mpc_relu3_msb.argtypes = L.mpc_relu3.argtypes
     L.mpc_maxpool3_msb_workspace_bytes.argtypes = [c_int] * 4; L.mpc_maxpool3_msb_workspace_bytes.restype = c_size_t
     L.mpc_maxpool3_msb.argtypes = L.mpc_maxpool3.argtypes
+    L.mpc_matmul3_prepared_bytes.argtypes = [c_int] * 4 + [POINTER(c_size_t)] * 2
+    L.mpc_conv2d3_prepared_bytes.argtypes = [c_int] * 9 + [POINTER(c_size_t)] * 2
+    L.mpc_matmul3_prepare.argtypes = [c_void_p, CShare3, CShare3, _P64, c_void_p, c_void_p] + [c_int] * 5
+    L.mpc_conv2d3_prepare.argtypes = [c_void_p, CShare3, CShare3, _P64, c_void_p, c_void_p] + [c_int] * 9
+    L.mpc_beaver_matmul3_prepared.argtypes = [c_void_p, CShare3, CShare3, CShare3, CShare3, c_void_p, c_void_p] + [c_int] * 5
+    L.mpc_conv2d3_prepared.argtypes = [c_void_p, CShare3, CShare3, CShare3, CShare3, c_void_p, c_void_p] + [c_int] * 9
     for fn in (L.mpc_conv2d3_grad_x_workspace_bytes, L.mpc_conv2d3_grad_w_workspace_bytes):
         fn.argtypes = [c_int] * 9; fn.restype = c_size_t
     L.mpc_conv2d3_grad_x.argtypes = [c_void_p] + [CShare3] * 6 + [c_int] * 9 + [_P64]
@@ -583,6 +591,46 @@ class Lane:
         z = out if out is not None else self._empty3(c[0])
         self._check(lib().mpc_conv2d3(self._h, _share3(x), _share3(w), _share3(a), _share3(b), _share3(c), _share3(z),
                                       B, H, W, Cin, Cout, KH, KW, pad, stride, _p64(f_public)))
+        return z
+
+    def prepare_matmul3(self, a, b, f_public, left=True):
+        """Returns (right_planes, left_planes or None) for beaver_matmul3_prepared."""
+        shp = a[0].shape
+        batch = 1 if len(shp) == 2 else shp[0]
+        M, K = shp[-2], shp[-1]; N = b[0].shape[-1]
+        r, l = c_size_t(), c_size_t()
+        self._check(lib().mpc_matmul3_prepared_bytes(M, K, N, batch, byref(r), byref(l)))
+        right = self._planes(r.value); lp = self._planes(l.value) if left else None
+        self._check(lib().mpc_matmul3_prepare(self._h, _share3(a), _share3(b), _p64(f_public), right.data_ptr(),
+                                              lp.data_ptr() if left else None, M, K, N, batch, 0))
+        return right, lp
+
+    def beaver_matmul3_prepared(self, x, a, c, right, left=None, out=None):
+        shp = a[0].shape
+        batch = 1 if len(shp) == 2 else shp[0]
+        M, K = shp[-2], shp[-1]; N = c[0].shape[-1]
+        self.reserve(lib().mpc_matmul3_workspace_bytes(M, K, N, batch))
+        z = out if out is not None else self._empty3(c[0])
+        self._check(lib().mpc_beaver_matmul3_prepared(self._h, _share3(x), _share3(a), _share3(c), _share3(z), right.data_ptr(),
+                                                      left.data_ptr() if left is not None else None, M, K, N, batch, 0))
+        return z
+
+    def prepare_conv2d3(self, a, b, f_public, pad, stride, left=True):
+        B, H, W, Cin = a[0].shape; KH, KW, _, Cout = b[0].shape
+        r, l = c_size_t(), c_size_t()
+        self._check(lib().mpc_conv2d3_prepared_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride, byref(r), byref(l)))
+        right = self._planes(r.value); lp = self._planes(l.value) if left else None
+        self._check(lib().mpc_conv2d3_prepare(self._h, _share3(a), _share3(b), _p64(f_public), right.data_ptr(),
+                                              lp.data_ptr() if left else None, B, H, W, Cin, Cout, KH, KW, pad, stride))
+        return right, lp
+
+    def conv2d3_prepared(self, x, a, c, right, left, KH, KW, pad, stride, out=None):
+        B, H, W, Cin = a[0].shape; Cout = c[0].shape[-1]
+        self.reserve(lib().mpc_conv2d3_workspace_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride))
+        z = out if out is not None else self._empty3(c[0])
+        self._check(lib().mpc_conv2d3_prepared(self._h, _share3(x), _share3(a), _share3(c), _share3(z), right.data_ptr(),
+                                               left.data_ptr() if left is not None else None,
+                                               B, H, W, Cin, Cout, KH, KW, pad, stride))
         return z
 
     def truncate3(self, z, r, rt, bits=16):

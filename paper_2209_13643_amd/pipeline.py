@@ -199,6 +199,8 @@ class LayerState3:
     pool2: dict | None = None
     packed: bool = False          # ReLU / pool material in the packed layout: sign-only chain (mpc_relu3_msb)
     pool_first: bool = False      # pooled layer evaluated as ReLU(maxpool(z)): the ReLU material covers the pooled size
+    right: torch.Tensor | None = None   # prepared digit planes of f, b_0 + f, b_1, b_2 (prepare_layers3)
+    left: torch.Tensor | None = None    # prepared digit planes of a_0, a_1, a_2
 
 
 def deal_weights3(g, layers, device):
@@ -250,15 +252,33 @@ def preopen_weights3(lane: mpc.Lane, states):
     lane.sync()
 
 
+def prepare_layers3(lane: mpc.Lane, layers, states):
+    """prepare_layers for three parties: the planes of every layer's input-independent operands, recoded once."""
+    if any(st.f_public is None for st in states):
+        preopen_weights3(lane, states)
+    for L, st in zip(layers, states):
+        if isinstance(L, synth.Conv):
+            st.right, st.left = lane.prepare_conv2d3(st.a, st.b, st.f_public, L.pad, L.stride)
+        else:
+            st.right, st.left = lane.prepare_matmul3(st.a, st.b, st.f_public)
+    lane.sync()
+
+
 def run_layer3(lane: mpc.Lane, L, st: LayerState3, x, keep: list):
     """One secure layer with three parties: linear, masked rescale (+ ReLU) (+ 2x2 max-pool)."""
     y_arg = None if st.f_public is not None else st.w
     if isinstance(L, synth.Conv):
         xs = tuple(v.view(L.B, L.H, L.W, L.Cin) for v in x)
-        z = lane.conv2d3(xs, y_arg, st.a, st.b, st.c, L.pad, L.stride, f_public=st.f_public)
+        if st.right is not None:
+            z = lane.conv2d3_prepared(xs, st.a, st.c, st.right, st.left, L.KH, L.KW, L.pad, L.stride)
+        else:
+            z = lane.conv2d3(xs, y_arg, st.a, st.b, st.c, L.pad, L.stride, f_public=st.f_public)
     else:
         xs = tuple(v.view(L.M, L.K) for v in x)
-        z = lane.beaver_matmul3(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public)
+        if st.right is not None:
+            z = lane.beaver_matmul3_prepared(xs, st.a, st.c, st.right, st.left)
+        else:
+            z = lane.beaver_matmul3(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public)
     lane.truncate3(z, st.r, st.rt)
     outs = [z]
     if st.pool_first:

@@ -330,6 +330,14 @@ def test_vgg16_with_three_parties(mods, packed_relu):
         ln.sync()
     for m in range(2):
         check3(outs[m], mbs[m]["want"][-1], f"pipelined micro-batch {m}")
+    # the same on prepared planes
+    for ln, st in zip(lanes, sts):
+        pipeline.prepare_layers3(ln, layers, st)
+    outs = pipeline.forward_pipelined3(lanes, layers, sts, [d3(mb["x"]) for mb in mbs], keep)
+    for ln in lanes:
+        ln.sync()
+    for m in range(2):
+        check3(outs[m], mbs[m]["want"][-1], f"pipelined micro-batch {m}, prepared planes")
     for ln in lanes + [packer]:
         ln.close()
 

@@ -123,6 +123,38 @@ def test_conv2d3(mpc, lane, case):
     assert np.array_equal(rec3(want), conv(d["X"], d["Y"]))
 
 
+@pytest.mark.parametrize("shape", [(5, 7, 3), (64, 256, 128), (130, 70, 200), (8, 6000, 8)])
+@pytest.mark.parametrize("left", [True, False])
+def test_beaver_matmul3_prepared_planes(mpc, lane, shape, left):
+    """Planes of a_0..a_2, f, b_0 + f, b_1, b_2 recoded ahead of time: the same shares as the plain call."""
+    M, K, N = shape
+    rng = np.random.default_rng(M * K + N + 3)
+    d = deal_matmul3(rng, (M, K), (K, N), 1.0, 0.1, oracle.ring_matmul)
+    want = oracle.beaver_matmul3(d["x"], d["y"], d["a"], d["b"], d["c"])
+    f_public = mpc.to_device(sum((d["y"][i] - d["b"][i] for i in range(1, 3)), d["y"][0] - d["b"][0]))
+    a, b, c = dev3(mpc, d["a"]), dev3(mpc, d["b"]), dev3(mpc, d["c"])
+    right, lp = lane.prepare_matmul3(a, b, f_public, left=left)
+    for _ in range(2):                                   # the planes are reusable
+        z = lane.beaver_matmul3_prepared(dev3(mpc, d["x"]), a, c, right, lp)
+        assert_shares_equal(host3(mpc, lane, z), want, "prepared matmul3")
+
+
+@pytest.mark.parametrize("case", [(2, 8, 8, 3, 16, 3, 3, 1, 1), (1, 9, 7, 20, 70, 3, 3, 1, 2), (3, 6, 6, 33, 40, 1, 1, 0, 1)])
+def test_conv2d3_prepared_planes(mpc, lane, case):
+    B, H, W, Cin, Cout, KH, KW, pad, stride = case
+    rng = np.random.default_rng(sum(case) + 9)
+    conv = lambda A, Bm: oracle.ring_conv2d(A, Bm, pad, stride)
+    d = deal_matmul3(rng, (B, H, W, Cin), (KH, KW, Cin, Cout), 1.0, 0.1, conv)
+    want = oracle.beaver_conv2d3(d["x"], d["y"], d["a"], d["b"], d["c"], pad, stride)
+    f_public = mpc.to_device(sum((d["y"][i] - d["b"][i] for i in range(1, 3)), d["y"][0] - d["b"][0]))
+    a, b, c = dev3(mpc, d["a"]), dev3(mpc, d["b"]), dev3(mpc, d["c"])
+    right, lp = lane.prepare_conv2d3(a, b, f_public, pad, stride)
+    z = lane.conv2d3_prepared(dev3(mpc, d["x"]), a, c, right, lp, KH, KW, pad, stride)
+    assert_shares_equal(host3(mpc, lane, z), want, "prepared conv2d3")
+    z = lane.conv2d3_prepared(dev3(mpc, d["x"]), a, c, right, None, KH, KW, pad, stride)
+    assert_shares_equal(host3(mpc, lane, z), want, "prepared conv2d3, left planes recoded in the call")
+
+
 def test_small_output_long_contraction_is_split(mpc, lane):
     """Few output tiles and a long contraction: the split-contraction path, both GEMM launches."""
     rng = np.random.default_rng(340)
