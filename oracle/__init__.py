@@ -530,43 +530,3 @@ def truncation_wraps(z_rec, t_rec, bits=16):
     want = to_signed(z_rec) >> bits
     got = to_signed(t_rec)
     return np.abs(got - want) > 1
-
-
-# ----------------------------- the divide-and-conquer adder of Sec. 4.2's listing
-def spk_constants():
-    """Public per-level constants for a 64-bit prefix tree in which level i
-    joins blocks of 2^i bits into blocks of 2^(i+1): the top bit of each lower
-    half is selected (in_mask), spread over the upper half by an integer
-    multiply (mult), and combined under P restricted to the upper half
-    (out_mask).  The paper does not print the values; these follow from that
-    description."""
-    in_masks, out_masks, mults = [], [], []
-    for i in range(6):
-        half, blk = 1 << i, 1 << (i + 1)
-        im = om = 0
-        for base in range(0, 64, blk):
-            im |= 1 << (base + half - 1)
-            om |= ((1 << half) - 1) << (base + half)
-        in_masks.append(im); out_masks.append(om)
-        mults.append(sum(1 << k for k in range(1, half + 1)))
-    return in_masks, out_masks, mults
-
-
-def spk_tree_carries(U, V, and_fn):
-    """Carry word (bit j = carry out of [0..j]) for python ints U, V < 2^64 in
-    the clear, looping as the listing does: per level one AND of the stacked
-    (S, P) selection against P on the upper halves.  ``and_fn(x, y)`` is the
-    AND gate (tests pass either plain & or a Beaver AND on shares)."""
-    M64 = (1 << 64) - 1
-    in_masks, out_masks, mults = spk_constants()
-    S, P = and_fn(U, V), U ^ V
-    for i in range(6):
-        im, om, mu = in_masks[i], out_masks[i], mults[i]
-        P0 = P & om
-        S1 = ((S & im) * mu) & M64
-        P1 = ((P & im) * mu) & M64
-        upd_S = and_fn(P0, S1)
-        upd_P = and_fn(P0, P1)
-        P = (P & (om ^ M64)) ^ upd_P
-        S = S ^ upd_S
-    return S

@@ -199,6 +199,8 @@ int check_shape(const LinearShape& s)
         if (s.B <= 0 || s.H <= 0 || s.W <= 0 || s.Cin <= 0 || s.Cout <= 0 || s.KH <= 0 || s.KW <= 0 ||
             s.pad < 0 || s.stride <= 0 || s.Ho <= 0 || s.Wo <= 0 || s.KH * s.KW > 64)
             return MPC_EINVAL;
+        // the filter window must fit the padded image (C division would round a negative extent up to one output)
+        if (s.H + 2 * s.pad < s.KH || s.W + 2 * s.pad < s.KW) return MPC_EINVAL;
         if ((long long)s.KH * s.KW * s.CB * 16 > MPC_MAX_K_TOTAL) return MPC_ERANGE;
     } else if (s.K > MPC_MAX_K_TOTAL) return MPC_ERANGE;
     if ((long long)s.M * s.N * s.batch > (1ll << 40)) return MPC_ERANGE;
@@ -251,24 +253,28 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         fill_geom(s, w, g);
         g.nparty = 2;
         if ((size_t)n_chunks > s.nx) n_chunks = (int)s.nx;
+        bool f_pending = !have_f;                            // the weight mask rides with the first launch issued
         for (int ch = 0; ch < n_chunks; ++ch) {
             size_t lo = (s.nx * ch / n_chunks) & ~(size_t)1, hi = (s.nx * (ch + 1) / n_chunks) & ~(size_t)1;
             if (ch == n_chunks - 1) hi = s.nx;
-            if (hi <= lo) continue;
+            const bool last = ch == n_chunks - 1;
             SubSeg sub[4]; CopySeg cp[4]; int ns = 0;
-            for (int i = 0; i < 2 && !x_public; ++i) {
+            for (int i = 0; i < 2 && !x_public && hi > lo; ++i) {
                 sub[ns] = SubSeg{ x.p[i] + lo, a.p[i] + lo, w.se[i] + lo, hi - lo, 0,
                                   c->exchange_put ? w.re[1 - i] + lo : nullptr };
                 cp[ns] = CopySeg{ (const u8*)(w.se[i] + lo), (u8*)(w.re[1 - i] + lo), (hi - lo) * sizeof(u64), 0 };
                 ++ns;
             }
-            if (!have_f && ch == 0)
+            // an empty chunk (fewer than two words per chunk) issues nothing; the weight mask must not depend on it
+            if (f_pending && (ns > 0 || last)) {
                 for (int i = 0; i < 2; ++i) {
                     sub[ns] = SubSeg{ y.p[i], b.p[i], w.sf[i], s.nw, 0, c->exchange_put ? w.rf[1 - i] : nullptr };
                     cp[ns] = CopySeg{ (const u8*)w.sf[i], (u8*)w.rf[1 - i], s.nw * sizeof(u64), 0 };
                     ++ns;
                 }
-            if (ns == 0) continue;                           // both operands were opened ahead of time
+                f_pending = false;
+            }
+            if (ns == 0) continue;                           // empty chunk, or both operands were opened ahead of time
             MPC_TRY(launch_sub_multi(c, P0, sub, ns));       // Alg. 1: mask (and, by remote store, send)
             if (!c->exchange_put) MPC_TRY(launch_copy_multi(c, P0, cp, ns));       // Alg. 1: exchange
         }

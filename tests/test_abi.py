@@ -100,6 +100,17 @@ def test_prepared_plane_sizes(lib):
     assert lib.mpc_conv2d_prepared_bytes(2, 8, 8, 16, 32, 3, 3, 1, 0, ctypes.byref(r), ctypes.byref(l)) == -1
 
 
+def test_filter_window_larger_than_the_padded_image_is_rejected(lib):
+    """H + 2 pad < KH (or the same in W): no output pixel exists; every query and prepare-size call says so,
+    whatever the stride (integer division would otherwise round the negative extent up to one pixel)."""
+    r, l = ctypes.c_size_t(), ctypes.c_size_t()
+    for (H, W, KH, KW, pad, stride) in [(2, 8, 3, 3, 0, 2), (8, 2, 3, 3, 0, 2), (1, 1, 5, 5, 1, 3), (2, 2, 3, 3, 0, 1)]:
+        assert lib.mpc_conv2d_workspace_bytes(1, H, W, 4, 4, KH, KW, pad, stride) == 0, (H, W, KH, KW, pad, stride)
+        assert lib.mpc_conv2d3_workspace_bytes(1, H, W, 4, 4, KH, KW, pad, stride) == 0
+        assert lib.mpc_conv2d_prepared_bytes(1, H, W, 4, 4, KH, KW, pad, stride, ctypes.byref(r), ctypes.byref(l)) == -1
+    assert lib.mpc_conv2d_workspace_bytes(1, 3, 3, 4, 4, 3, 3, 0, 2) > 0          # the window just fits
+
+
 def test_gradient_and_elementwise_workspace_queries(lib):
     assert lib.mpc_conv2d_grad_x_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 1) > 0
     assert lib.mpc_conv2d_grad_x_workspace_bytes(2, 8, 8, 3, 16, 3, 3, 1, 2) > 0       # strided: plus the dilated gradient

@@ -167,6 +167,19 @@ def test_beaver_matmul_schedule_invariance(mpc, lane, n_chunks, mode):
     assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "schedule")
 
 
+@pytest.mark.parametrize("shape", [(1, 1, 1), (1, 3, 2), (5, 1, 4), (1, 7, 3), (2, 3, 5)])
+@pytest.mark.parametrize("n_chunks", [2, 3, 4, 8])
+def test_beaver_matmul_more_chunks_than_word_pairs(mpc, lane, shape, n_chunks):
+    """Fewer than two words of x per chunk: leading chunks are empty, and the weight mask
+    (opened in the same call) must still be formed and exchanged."""
+    M, K, N = shape
+    print(f"tiny chunked matmul {shape} chunks={n_chunks}", flush=True)
+    d = deal_matmul(np.random.default_rng(1000 + M * K + n_chunks), M, K, N)
+    z = lane.beaver_matmul(dev(mpc, d["x"]), dev(mpc, d["y"]), dev(mpc, d["a"]), dev(mpc, d["b"]),
+                           dev(mpc, d["c"]), n_chunks=n_chunks, flags=mpc.MPC_TRUNCATE)
+    assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "tiny chunked")
+
+
 # ---------------------------------------------------------------------- conv (Eq. 3)
 CONV_CASES = [  # B,H,W,Cin,Cout,KH,KW,pad,stride
     (1, 3, 3, 1, 1, 3, 3, 1, 1), (2, 8, 8, 3, 16, 3, 3, 1, 1), (2, 9, 7, 20, 24, 3, 3, 1, 1),

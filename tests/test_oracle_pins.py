@@ -364,66 +364,105 @@ def test_adder_random_and_carry_corners(w):
         assert (S[0] ^ S[1]) == (U + V) & wm, (hex(U), hex(V))
 
 
-def test_kogge_stone_agrees_with_listing_tree():
-    """The divide-and-conquer tree of the Sec. 4.2 listing (six levels, one
-    stacked AND each) yields the same carries, hence the same sum."""
+def _carry_outs(U, V):
+    """Bit j = carry out of positions [0..j] of U + V, from plain integer addition of the low j + 1 bits."""
+    g = 0
+    for j in range(64):
+        m = (1 << (j + 1)) - 1
+        g |= (((U & m) + (V & m)) >> (j + 1)) << j
+    return g
+
+
+def _tree_carries_rec(rng, U, V):
+    """Reconstructed carry word of the oracle's share-level prefix tree, random sharing and triples."""
+    a, b, c = _adder_triples(rng, 64)
+    u0, v0 = int(rng.integers(0, 1 << 64, dtype=U64)), int(rng.integers(0, 1 << 64, dtype=U64))
+    G = oracle.tree_carries((u0, U ^ u0), (v0, V ^ v0), a, b, c)
+    return G[0] ^ G[1]
+
+
+def test_listing_tree_carries_are_the_integer_carries_exhaustive_bytes():
+    """Every pair of 8-bit operands, placed at bit offsets that exercise every level of the tree
+    (0: levels 0-2 only; 28 and 29: straddling the 32-bit join; 56: top byte), with the surrounding
+    bits all-propagate or zero: the tree's carries are those of integer addition, position by position."""
     rng = np.random.default_rng(15)
     M64 = MOD - 1
-    cases = [(M64, 1), (M64 >> 1, 1), (0, 0), (M64, M64)] + \
-            [(int(q), int(p)) for q, p in zip(synth.rand_words(rng, 200), synth.rand_words(rng, 200))]
-    for U, V in cases:
-        carries = oracle.spk_tree_carries(U, V, lambda p, q: p & q)
-        assert (U ^ V ^ ((carries << 1) & M64)) == (U + V) & M64
-        a, b, c = _adder_triples(rng, 64)
-        u0, v0 = int(rng.integers(0, 1 << 64, dtype=U64)), int(rng.integers(0, 1 << 64, dtype=U64))
-        S = oracle.ks_add((u0, U ^ u0), (v0, V ^ v0), 64, a, b, c)
-        assert (S[0] ^ S[1]) == (U ^ V ^ ((carries << 1) & M64))
+    for off, fill in ((0, 0), (28, 0), (29, M64), (56, M64)):
+        keep = M64 ^ (0xFF << off)
+        for u in range(256):
+            for v in range(0, 256, 1 if off == 0 else 5):
+                U = ((u << off) | (fill & keep)) & M64
+                V = (v << off) & M64
+                assert _tree_carries_rec(rng, U, V) == _carry_outs(U, V), (off, u, v)
 
 
-def test_listing_tree_on_shares_with_beaver_and():
-    """Same tree evaluated on XOR shares, every gate a Beaver AND from the oracle."""
+def test_listing_tree_carries_sixteen_bit_sweep_and_64_bit_corners():
     rng = np.random.default_rng(16)
-    for _ in range(20):
-        U, V = int(rng.integers(0, 1 << 64, dtype=U64)), int(rng.integers(0, 1 << 64, dtype=U64))
-        # run the tree twice, once per party view, by carrying share pairs through and_fn
-        def and_fn(p, q):
-            t = [int(v) for v in synth.rand_words(rng, 5)]
-            c1 = ((t[0] ^ t[1]) & (t[2] ^ t[3])) ^ t[4]
-            p0, q0 = int(rng.integers(0, 1 << 64, dtype=U64)), int(rng.integers(0, 1 << 64, dtype=U64))
-            o = oracle.beaver_and((p0, p ^ p0), (q0, q ^ q0), t[0:2], t[2:4], (t[4], c1))
-            return o[0] ^ o[1]
-        carries = oracle.spk_tree_carries(U, V, and_fn)
-        assert (U ^ V ^ ((carries << 1) & (MOD - 1))) == (U + V) % MOD
-
-
-def test_tree_adder_on_shares_equals_the_listing_transcription():
-    """The share-level tree of the oracle's ReLU against the independent python
-    transcription of the listing, gate by gate with the same triples: identical
-    carry shares for both parties."""
-    rng = np.random.default_rng(17)
     M64 = MOD - 1
-    for _ in range(50):
+    # a 16-bit sweep: all u in steps that hit every low pattern, v from a coprime stride, at two offsets
+    for off in (0, 40):
+        for u in range(0, 1 << 16, 97):
+            v = (u * 40503 + 12345) & 0xFFFF
+            U, V = (u << off) & M64, (v << off) & M64
+            assert _tree_carries_rec(rng, U, V) == _carry_outs(U, V)
+    corners = [(M64, 1), (M64 >> 1, 1), (0, 0), (M64, M64), (1 << 63, 1 << 63), (M64, 0),
+               (0xAAAAAAAAAAAAAAAA, 0x5555555555555555), (0xAAAAAAAAAAAAAAAA, 0xAAAAAAAAAAAAAAAA),
+               (0x5555555555555555, 0x5555555555555555), ((1 << 32) - 1, 1), ((1 << 31), (1 << 31)),
+               (0x00000000FFFFFFFF, 0xFFFFFFFF00000001)] + \
+              [((1 << k) - 1, 1) for k in range(1, 65)] + [(M64 ^ (1 << k), 1) for k in range(64)]
+    rand = [(int(q), int(p)) for q, p in zip(synth.rand_words(rng, 500), synth.rand_words(rng, 500))]
+    for U, V in corners + rand:
+        U &= M64; V &= M64
+        got = _tree_carries_rec(rng, U, V)
+        assert got == _carry_outs(U, V), (hex(U), hex(V))
+        # and hence the Kogge-Stone network's sum
+        a, b, c = _adder_triples(rng, 64)
+        S = oracle.ks_add((5, U ^ 5), (9, V ^ 9), 64, a, b, c)
+        assert (S[0] ^ S[1]) == (U ^ V ^ ((got << 1) & M64))
+
+
+def test_tree_adder_gate_wiring_bit_by_bit():
+    """Which gate reads which bit and which triple bit: a prefix tree written on bit lists with index
+    arithmetic only (position j of an upper half-block at level i combines with position
+    (j >> i << i) - 1, the top of the lower half; all other positions enter the gate as zeros), every
+    gate a one-bit Beaver AND that takes bit j of triple word 1 + 2i (carry update) / 2 + 2i (propagate
+    update).  Carry shares must agree with the
+    oracle's word-level tree for both parties."""
+    rng = np.random.default_rng(17)
+
+    def and1(p, q, a, b, c, t, j):
+        """One-bit Beaver AND at bit j of triple t, on share pairs of bits."""
+        bit = lambda w: (int(w) >> j) & 1
+        o = oracle.beaver_and(p, q, (bit(a[0][t]), bit(a[1][t])), (bit(b[0][t]), bit(b[1][t])), (bit(c[0][t]), bit(c[1][t])))
+        return (int(o[0]) & 1, int(o[1]) & 1)
+
+    for _ in range(40):
         U, V = int(rng.integers(0, 1 << 64, dtype=U64)), int(rng.integers(0, 1 << 64, dtype=U64))
         u0, v0 = int(rng.integers(0, 1 << 64, dtype=U64)), int(rng.integers(0, 1 << 64, dtype=U64))
         a, b, c = _adder_triples(rng, 64)
-        got = oracle.tree_carries((u0, U ^ u0), (v0, V ^ v0), a, b, c)
-        # the transcription runs on pairs of shares; its gates take the triples in order 0, 1, 2, ...
-        # but it evaluates the dead P update of the last level too: give that gate a throw-away triple
-        order = iter(list(range(12)) + [None])
-        def and_fn(p, q):
-            t = next(order)
-            if t is None:
-                return (0, 0)
-            o = oracle.beaver_and(p, q, (a[0][t], a[1][t]), (b[0][t], b[1][t]), (c[0][t], c[1][t]))
-            return (int(o[0]), int(o[1]))
-
-        class Pair(tuple):        # share pairs under the public-constant operations the tree uses
-            def __and__(self, m): return Pair((self[0] & m, self[1] & m))
-            def __xor__(self, o): return Pair((self[0] ^ o[0], self[1] ^ o[1])) if isinstance(o, tuple) else Pair((self[0] ^ o, self[1]))
-            def __mul__(self, m): return Pair(((self[0] * m) & M64, (self[1] * m) & M64))
-        want = oracle.spk_tree_carries(Pair((u0, U ^ u0)), Pair((v0, V ^ v0)), lambda p, q: Pair(and_fn(p, q)))
-        assert got == (want[0], want[1])
-        assert ((got[0] ^ got[1]) << 1) & M64 == (U ^ V) ^ ((U + V) & M64)
+        Us, Vs = (u0, U ^ u0), (v0, V ^ v0)
+        got = oracle.tree_carries(Us, Vs, a, b, c)
+        ub = [((Us[0] >> j) & 1, (Us[1] >> j) & 1) for j in range(64)]
+        vb = [((Vs[0] >> j) & 1, (Vs[1] >> j) & 1) for j in range(64)]
+        P = [(ub[j][0] ^ vb[j][0], ub[j][1] ^ vb[j][1]) for j in range(64)]
+        G = [and1(ub[j], vb[j], a, b, c, 0, j) for j in range(64)]
+        for i in range(6):
+            Gn, Pn = list(G), list(P)
+            for j in range(64):
+                # the AND is a word operation: positions outside the upper halves enter it as shared zeros
+                # (their gate output is a sharing of zero that still re-randomises the share bits)
+                upper = (j >> i) & 1
+                src = ((j >> i) << i) - 1
+                x = P[j] if upper else (0, 0)
+                t = and1(x, G[src] if upper else (0, 0), a, b, c, 1 + 2 * i, j)
+                Gn[j] = (G[j][0] ^ t[0], G[j][1] ^ t[1])
+                if i < 5:
+                    q = and1(x, P[src] if upper else (0, 0), a, b, c, 2 + 2 * i, j)
+                    Pn[j] = q if upper else (P[j][0] ^ q[0], P[j][1] ^ q[1])
+            G, P = Gn, Pn
+        want = tuple(sum(G[j][k] << j for j in range(64)) for k in range(2))
+        assert got == want
+        assert (got[0] ^ got[1]) == _carry_outs(U, V)
 
 
 def test_relu_with_the_listing_tree():
