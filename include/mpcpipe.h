@@ -45,7 +45,8 @@ enum {
     MPC_EINVAL = -1,   /* null pointer, non-positive size, unsupported shape   */
     MPC_ENOMEM = -2,   /* workspace missing or smaller than mpc_*_workspace()  */
     MPC_EHIP = -3,     /* a HIP call failed; mpc_last_hip_error() has the code */
-    MPC_ERANGE = -4    /* contraction too long for exact int32 digit sums      */
+    MPC_ERANGE = -4    /* contraction too long for exact int32 digit sums, or
+                          n beyond a fixed-size entry point's maximum          */
 };
 
 /* flags for mpc_beaver_matmul / mpc_conv2d and the gradient products */
@@ -341,6 +342,25 @@ typedef struct {
 int mpc_relu(mpc_ctx* ctx, mpc_cshare x, const mpc_relu_material* mat, mpc_share y,
              size_t n, int n_chunks,
              uint8_t* const s_bit[2], uint64_t* const s_arith[2]);
+
+/* mpc_relu for callers that cannot allocate device memory or own a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): same arguments, same shares, but the rounds' exchange buffers
+ * and carried state live in a fixed array inside the library's code object
+ * instead of the context's workspace.  The call performs no device or pinned
+ * allocation and opens no timing region (mpc_ctx_profile never counts it).
+ *   n <= mpc_relu_static_max_n() (65536), else MPC_ERANGE; the array takes
+ *   about 14.4 MiB on every device the library runs on, until the process ends.
+ *   The context must come from mpc_ctx_create (which resolves the array's
+ *   device address for the context's device), else MPC_EINVAL.
+ *   All calls on one device share the array, which keeps the previous call's
+ *   contents (every word read is first written by the same call, so nothing
+ *   needs clearing): calls that overlap on a device, on any lane, race.
+ *   Calls on one lane are ordered as usual. */
+size_t mpc_relu_static_max_n(void);
+int mpc_relu_static(mpc_ctx* ctx, mpc_cshare x, const mpc_relu_material* mat, mpc_share y,
+                    size_t n, int n_chunks,
+                    uint8_t* const s_bit[2], uint64_t* const s_arith[2]);
 
 /* 2x2 / stride-2 max-pool on NHWC shares by max(p, q) = q + ReLU(p - q): two
  * tournament levels, i.e. two conversions per window (Sec. 4.2).  mat1 holds

@@ -129,6 +129,10 @@ struct WsAlloc {
     }
 };
 
+// resolves, once per device, the address of the fixed scratch array of mpc_relu_static (relu.hip);
+// called by mpc_ctx_create with the context's device current
+int relu_static_setup(mpc_ctx* c);
+
 // ---- element-wise launchers (elementwise.hip) --------------------------------
 int launch_sub(mpc_ctx* c, hipStream_t st, const u64* x, const u64* a, u64* out, size_t n);
 int launch_add(mpc_ctx* c, hipStream_t st, const u64* x, const u64* y, u64* out, size_t n);

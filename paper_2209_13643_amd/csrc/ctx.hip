@@ -25,6 +25,7 @@ int mpc_ctx_create(mpc_ctx** out, int device, int frac_bits)
         (void)mpc_ctx_destroy(c);       // releases whatever was created; the HIP code is lost with the context
         return MPC_EHIP;
     }
+    if (relu_static_setup(c) != MPC_OK) { (void)mpc_ctx_destroy(c); return MPC_EHIP; }
     *out = c;
     return MPC_OK;
 }
@@ -207,7 +208,7 @@ const char* mpc_strerror(int code)
     case MPC_EINVAL: return "invalid argument (null pointer, non-positive size or unsupported shape)";
     case MPC_ENOMEM: return "workspace missing or too small for this call";
     case MPC_EHIP: return "a HIP runtime call failed (see mpc_last_hip_error)";
-    case MPC_ERANGE: return "contraction length exceeds the exact int32 digit-sum bound";
+    case MPC_ERANGE: return "size out of range: contraction beyond the exact int32 digit-sum bound, or more elements than a fixed-size entry point holds";
     default: return "unknown mpcpipe error code";
     }
 }

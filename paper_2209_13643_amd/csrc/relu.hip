@@ -24,6 +24,8 @@
 // The triples of the levels arrive packed the same way, and every exchange
 // after G = U & V shrinks by the same factor.  Bit for bit the same shares.
 #include "common.h"
+
+#include <atomic>
 #include "msb_pack.h"
 
 namespace {
@@ -890,7 +892,8 @@ __global__ __launch_bounds__(kThreads) void k_pool_l2(const u64* __restrict__ x,
 
 // Shared body of the two entry points; `packed` selects the MSB-only chain.
 int relu_entry(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat, mpc_share y, size_t n, int n_chunks,
-               uint8_t* const s_bit[2], uint64_t* const s_arith[2], bool packed)
+               uint8_t* const s_bit[2], uint64_t* const s_arith[2], bool packed,
+               u8* ws, size_t ws_bytes, bool timed = true)
 {
     if (!c || n == 0 || n_chunks < 0 || !x.p[0] || !x.p[1] || !y.p[0] || !y.p[1]) return MPC_EINVAL;
     MPC_TRY(check_material(mat));
@@ -900,13 +903,13 @@ int relu_entry(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat, mpc_share
         for (int i = 0; i < 2; ++i)
             if (((uintptr_t)mat->and_a.p[i] | (uintptr_t)mat->and_b.p[i] | (uintptr_t)mat->and_c.p[i]) & 15) return MPC_EINVAL;
         g = msb_geom(n);
-        w = carve_relu_msb(c->ws, c->ws_bytes, n, g);
+        w = carve_relu_msb(ws, ws_bytes, n, g);
     } else {
-        w = carve_relu(c->ws, c->ws_bytes, n);
+        w = carve_relu(ws, ws_bytes, n);
     }
     if (!w.ok) return MPC_ENOMEM;
     MPC_TRY(lane_join(c));
-    const int pi = prof_begin(c, MPC_PROF_RELU, c->s[0]);
+    const int pi = timed ? prof_begin(c, MPC_PROF_RELU, c->s[0]) : -1;
     ReluParty pp[2];
     for (int i = 0; i < 2; ++i)
         fill_party(pp[i], i, x.p[i], mat, w, y.p[i], s_bit ? s_bit[i] : nullptr, s_arith ? s_arith[i] : nullptr, n);
@@ -979,9 +982,50 @@ int maxpool_entry(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat1, const
     return MPC_OK;
 }
 
+// ---- the entry point that allocates nothing ------------------------------------
+// Its rounds exchange and carry state through a fixed array in the code object
+// instead of the caller's workspace.  Layout and size are those carve_relu gives
+// for kStaticMaxN elements: per party 2 x [4][n] words (sent / received), 2 x n
+// bytes, G, P (n words each), n bytes; then the two alternate receive buffers.
+constexpr size_t kStaticMaxN = 65536;
+constexpr size_t static_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+constexpr size_t kStaticBytes =
+    2 * (2 * static_up(32 * kStaticMaxN) + 2 * static_up(kStaticMaxN) + 2 * static_up(8 * kStaticMaxN) + static_up(kStaticMaxN)) +
+    2 * static_up(32 * kStaticMaxN);
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+// Device address of `scratch` per device (every device holds its own copy of the
+// array); resolved once per device by relu_static_setup, with that device current.
+constexpr int kMaxDevices = 16;
+std::atomic<u8*> g_scratch_ptr[kMaxDevices];
+
 }  // namespace
 
+int relu_static_setup(mpc_ctx* c)
+{
+    if (c->device < 0 || c->device >= kMaxDevices) return MPC_OK;     // mpc_relu_static reports it
+    if (g_scratch_ptr[c->device].load(std::memory_order_acquire)) return MPC_OK;
+    void* p = nullptr;
+    MPC_HIP(c, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || ((uintptr_t)p % kAlign) != 0) return MPC_EHIP;
+    g_scratch_ptr[c->device].store((u8*)p, std::memory_order_release);
+    return MPC_OK;
+}
+
 extern "C" {
+
+size_t mpc_relu_static_max_n(void) { return kStaticMaxN; }
+
+int mpc_relu_static(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat, mpc_share y, size_t n, int n_chunks,
+                    uint8_t* const s_bit[2], uint64_t* const s_arith[2])
+{
+    if (!c || c->device < 0 || c->device >= kMaxDevices) return MPC_EINVAL;
+    if (n > kStaticMaxN) return MPC_ERANGE;
+    u8* ws = g_scratch_ptr[c->device].load(std::memory_order_acquire);
+    if (!ws) return MPC_EINVAL;          // the context was not created on this device by mpc_ctx_create
+    // no timing region: its events would be created here
+    return relu_entry(c, x, mat, y, n, n_chunks, s_bit, s_arith, false, ws, kStaticBytes, false);
+}
 
 size_t mpc_relu_workspace_bytes(size_t n)
 {
@@ -1003,13 +1047,15 @@ size_t mpc_maxpool_msb_workspace_bytes(int B, int H, int W, int C) { return maxp
 int mpc_relu(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat, mpc_share y, size_t n, int n_chunks,
              uint8_t* const s_bit[2], uint64_t* const s_arith[2])
 {
-    return relu_entry(c, x, mat, y, n, n_chunks, s_bit, s_arith, false);
+    if (!c) return MPC_EINVAL;
+    return relu_entry(c, x, mat, y, n, n_chunks, s_bit, s_arith, false, c->ws, c->ws_bytes);
 }
 
 int mpc_relu_msb(mpc_ctx* c, mpc_cshare x, const mpc_relu_material* mat, mpc_share y, size_t n, int n_chunks,
                  uint8_t* const s_bit[2], uint64_t* const s_arith[2])
 {
-    return relu_entry(c, x, mat, y, n, n_chunks, s_bit, s_arith, true);
+    if (!c) return MPC_EINVAL;
+    return relu_entry(c, x, mat, y, n, n_chunks, s_bit, s_arith, true, c->ws, c->ws_bytes);
 }
 
 int mpc_relu_pack_triples(mpc_ctx* c, mpc_cshare words, mpc_share packed, size_t n)

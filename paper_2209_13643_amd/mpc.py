@@ -53,7 +53,7 @@ EXPORTS = [
     "mpc_ctx_set_profiling", "mpc_ctx_profile", "mpc_ctx_profile_reset",
     "mpc_matmul_workspace_bytes", "mpc_conv2d_workspace_bytes", "mpc_relu_workspace_bytes",
     "mpc_maxpool_workspace_bytes", "mpc_open", "mpc_sub", "mpc_beaver_matmul", "mpc_conv2d", "mpc_truncate",
-    "mpc_relu", "mpc_maxpool2x2", "mpc_ring_matmul", "mpc_ring_conv2d",
+    "mpc_relu", "mpc_maxpool2x2", "mpc_ring_matmul", "mpc_ring_conv2d", "mpc_relu_static", "mpc_relu_static_max_n",
     "mpc_relu_msb_workspace_bytes", "mpc_maxpool_msb_workspace_bytes", "mpc_relu_packed_words",
     "mpc_relu_pack_triples", "mpc_relu_msb", "mpc_maxpool2x2_msb",
     "mpc_conv2d_grad_x_workspace_bytes", "mpc_conv2d_grad_w_workspace_bytes", "mpc_conv2d_grad_x",
@@ -140,6 +140,8 @@ def lib():
     L.mpc_maxpool2x2.argtypes = [c_void_p, CShare, POINTER(ReluMaterial), POINTER(ReluMaterial), CShare,
                                  c_int, c_int, c_int, c_int, c_int]
     L.mpc_relu_msb.argtypes = L.mpc_relu.argtypes
+    L.mpc_relu_static.argtypes = L.mpc_relu.argtypes
+    L.mpc_relu_static_max_n.argtypes = []; L.mpc_relu_static_max_n.restype = c_size_t
     L.mpc_maxpool2x2_signs.argtypes = [c_void_p, CShare, POINTER(ReluMaterial), POINTER(ReluMaterial), CShare,
                                        POINTER(_P64 * 2), POINTER(_P64 * 2)] + [c_int] * 6
     L.mpc_maxpool_backward_workspace_bytes.argtypes = [c_int] * 4
@@ -780,13 +782,23 @@ class Lane:
         self._check(fn(self._h, _share(x), byref(m), _share(y), n, n_chunks, None, None))
         return y
 
-    def maxpool2x2(self, x, mat1, mat2, n_chunks=0, packed=False, want_signs=False):
+    def relu_static(self, x, mat, y, n_chunks=0, s_bit=None, s_arith=None):
+        """mpc_relu_static: secure ReLU on the library's fixed scratch array; every buffer is the caller's."""
+        n = x[0].numel()
+        m = _material(mat, n, False)
+        sbp = byref((_P8 * 2)(_p8(s_bit[0]), _p8(s_bit[1]))) if s_bit is not None else None
+        sap = byref((_P64 * 2)(_p64(s_arith[0]), _p64(s_arith[1]))) if s_arith is not None else None
+        self._check(lib().mpc_relu_static(self._h, _share(x), byref(m), _share(y), n, n_chunks, sbp, sap))
+        return y
+
+    def maxpool2x2(self, x, mat1, mat2, n_chunks=0, packed=False, want_signs=False, out=None):
         """2x2 max-pool; want_signs=True also returns the sign shares (s1, s2) the backward pass needs."""
         B, H, W, C = x[0].shape
         n_out = B * (H // 2) * (W // 2) * C
         ws = lib().mpc_maxpool_msb_workspace_bytes if packed else lib().mpc_maxpool_workspace_bytes
         self.reserve(ws(B, H, W, C))
-        y = tuple(torch.empty((B, H // 2, W // 2, C), dtype=torch.int64, device=self.device) for _ in range(2))
+        y = out if out is not None else \
+            tuple(torch.empty((B, H // 2, W // 2, C), dtype=torch.int64, device=self.device) for _ in range(2))
         m1, m2 = _material(mat1, 2 * n_out, packed), _material(mat2, n_out, packed)
         if want_signs:
             s1 = tuple(torch.empty(2 * n_out, dtype=torch.int64, device=self.device) for _ in range(2))
