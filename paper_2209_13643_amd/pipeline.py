@@ -113,47 +113,74 @@ def prepare_layers(lane: mpc.Lane, layers, states):
     lane.sync()
 
 
-def run_layer(lane: mpc.Lane, L, st: LayerState, x, keep: list, n_chunks=1, relu_chunks=0, flags=mpc.MPC_TRUNCATE):
+def alloc_outputs(lane: mpc.Lane, layers, states):
+    """Output tensors of every call of one forward pass on `lane`, allocated once: a pass that is given
+    them (run_layer's `out`) allocates nothing, so a serving loop can reuse them step after step (a lane
+    executes its calls in order: step k+1 overwrites a tensor only after step k's readers have run)."""
+    dev = lane.device
+    pair = lambda shape: tuple(torch.empty(shape, dtype=torch.int64, device=dev) for _ in range(2))
+    bufs = []
+    for L, st in zip(layers, states):
+        if isinstance(L, synth.Conv):
+            full, pooled = (L.B, L.Ho, L.Wo, L.Cout), (L.B, L.Ho // 2, L.Wo // 2, L.Cout)
+        else:
+            full, pooled = (L.M, L.N), None
+        b = dict(z=pair(full))
+        if st.pool1 is not None:
+            b["p"] = pair(pooled)
+        if st.relu is not None:
+            b["y"] = pair(pooled if st.pool_first else full)
+        bufs.append(b)
+    return bufs
+
+
+def run_layer(lane: mpc.Lane, L, st: LayerState, x, keep: list, n_chunks=1, relu_chunks=0, flags=mpc.MPC_TRUNCATE,
+              out: dict | None = None):
     """One secure layer on one lane: linear (+ ReLU) (+ 2x2 max-pool).  Returns output shares.
     Every tensor the layer produces is appended to `keep`: the calls only enqueue work and torch's
     allocator knows nothing about the lane's queue, so nothing may be freed (and handed out again)
-    before the caller has synchronised the lane."""
+    before the caller has synchronised the lane.  With `out` (one entry of alloc_outputs) the calls
+    write into those tensors instead and nothing is allocated."""
+    o = out or {}
     y_arg = None if st.f_public is not None else st.w
     if isinstance(L, synth.Conv):
         xs = (x[0].view(L.B, L.H, L.W, L.Cin), x[1].view(L.B, L.H, L.W, L.Cin))
         if st.right is not None:
             z = lane.conv2d_prepared(xs, st.a, st.c, st.right, st.left, L.KH, L.KW, L.pad, L.stride,
-                                     n_chunks=n_chunks, flags=flags)
+                                     n_chunks=n_chunks, flags=flags, out=o.get("z"))
         else:
             z = lane.conv2d(xs, y_arg, st.a, st.b, st.c, L.pad, L.stride, f_public=st.f_public,
-                            n_chunks=n_chunks, flags=flags)
+                            n_chunks=n_chunks, flags=flags, out=o.get("z"))
     else:
         xs = (x[0].view(L.M, L.K), x[1].view(L.M, L.K))
         if st.right is not None:
-            z = lane.beaver_matmul_prepared(xs, st.a, st.c, st.right, st.left, n_chunks=n_chunks, flags=flags)
+            z = lane.beaver_matmul_prepared(xs, st.a, st.c, st.right, st.left, n_chunks=n_chunks, flags=flags, out=o.get("z"))
         else:
-            z = lane.beaver_matmul(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public, n_chunks=n_chunks, flags=flags)
+            z = lane.beaver_matmul(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public, n_chunks=n_chunks, flags=flags,
+                                   out=o.get("z"))
     outs = [z]
     if st.pool_first:
-        z = lane.maxpool2x2(z, st.pool1, st.pool2, n_chunks=relu_chunks, packed=st.packed); outs.append(z)
-        z = lane.relu(z, st.relu, n_chunks=relu_chunks, packed=st.packed); outs.append(z)
-        keep.extend(outs)
+        z = lane.maxpool2x2(z, st.pool1, st.pool2, n_chunks=relu_chunks, packed=st.packed, out=o.get("p")); outs.append(z)
+        z = lane.relu(z, st.relu, n_chunks=relu_chunks, packed=st.packed, out=o.get("y")); outs.append(z)
+        if out is None:
+            keep.extend(outs)
         return z
     if st.relu is not None:
-        z = lane.relu(z, st.relu, n_chunks=relu_chunks, packed=st.packed); outs.append(z)
+        z = lane.relu(z, st.relu, n_chunks=relu_chunks, packed=st.packed, out=o.get("y")); outs.append(z)
     if st.pool1 is not None:
-        z = lane.maxpool2x2(z, st.pool1, st.pool2, n_chunks=relu_chunks, packed=st.packed); outs.append(z)
-    keep.extend(outs)
+        z = lane.maxpool2x2(z, st.pool1, st.pool2, n_chunks=relu_chunks, packed=st.packed, out=o.get("p")); outs.append(z)
+    if out is None:
+        keep.extend(outs)
     return z
 
 
-def forward(lane: mpc.Lane, layers, states, x, keep: list, **kw):
+def forward(lane: mpc.Lane, layers, states, x, keep: list, outs=None, **kw):
     """All layers on one lane.  Every intermediate tensor is appended to `keep`:
     the calls only enqueue work, and torch's allocator knows nothing about the
     lane's queue, so nothing may be freed (and handed out again) until the
-    caller has synchronised the lane."""
-    for L, st in zip(layers, states):
-        x = run_layer(lane, L, st, x, keep, **kw)
+    caller has synchronised the lane.  `outs` (alloc_outputs): preallocated tensors instead."""
+    for li, (L, st) in enumerate(zip(layers, states)):
+        x = run_layer(lane, L, st, x, keep, out=outs[li] if outs is not None else None, **kw)
     return x
 
 
@@ -174,12 +201,13 @@ def forward_interlinear(lane: mpc.Lane, wlane: mpc.Lane, layers, states, x, keep
     return x
 
 
-def forward_pipelined(lanes, layers, states_per_mb, xs, keep: list, **kw):
+def forward_pipelined(lanes, layers, states_per_mb, xs, keep: list, outs_per_mb=None, **kw):
     """Inter-batch pipeline: micro-batch m on lanes[m]; layer-major issue order."""
     cur = list(xs)
     for li, L in enumerate(layers):
         for m, lane in enumerate(lanes):
-            cur[m] = run_layer(lane, L, states_per_mb[m][li], cur[m], keep, **kw)
+            cur[m] = run_layer(lane, L, states_per_mb[m][li], cur[m], keep,
+                               out=outs_per_mb[m][li] if outs_per_mb is not None else None, **kw)
     return cur
 
 
