@@ -54,7 +54,8 @@ enum {
     MPC_TRUNCATE = 1,     /* rescale the product by 2^-frac_bits (local truncation)       */
     MPC_TWO_PHASE = 2,    /* Alg. 3 ordering: [a_i]*f first, while e is still "in flight" */
     MPC_TRANS_X = 4,      /* mpc_beaver_matmul: x, a are stored [K][M] (left operand = their transpose)  */
-    MPC_TRANS_Y = 8       /* mpc_beaver_matmul: y, b, f_public are stored [N][K]                          */
+    MPC_TRANS_Y = 8,      /* mpc_beaver_matmul: y, b, f_public are stored [N][K]                          */
+    MPC_FOLDED = 16       /* mpc_*_prepared: c.p[0] is the folded addend c_0 - a_0*b_0 of mpc_*_fold      */
 };
 
 #define MPC_N_AND_TRIPLES 12
@@ -233,7 +234,20 @@ int mpc_conv2d(mpc_ctx* ctx, mpc_cshare x, mpc_cshare w,
  *     flags: MPC_TRANS_X / MPC_TRANS_Y as for mpc_beaver_matmul (storage of a / of b, f).
  *   mpc_beaver_matmul_prepared / mpc_conv2d_prepared: the online call.
  *     right_planes is required; left_planes may be NULL (then [a_i] is recoded
- *     in the call).  Other arguments, workspace and errors as for the plain calls. */
+ *     in the call).  Other arguments, workspace and errors as for the plain calls.
+ *   Folded triple (flag MPC_FOLDED on the online call; needs both plane buffers).  Alg. 1's
+ *     z_0 = c_0 + e*b_0 + a_0*f + e*f equals (c_0 - a_0*b_0) + (a_0 + e)*(b_0 + f) in the ring, and
+ *     a_0 + e = x_0 + e_1, party 0's own share plus the masked word it receives.  With the
+ *     input-independent local product folded into the addend ahead of time (mpc_*_fold:
+ *     c0_folded = c_0 - a_0*b_0, M x N words, all pointers party 0's), party 0 contracts one product
+ *     online instead of two (party 1 keeps [e | a_1] x [b_1 ; f]): three ring products per call, the
+ *     same output words.  The online call then takes c.p[0] = c0_folded; a.p[0] is still needed for
+ *     the mask x_0 - a_0, a_0's planes in left_planes are not read.  Not with MPC_TWO_PHASE. */
+int mpc_matmul_fold(mpc_ctx* ctx, const uint64_t* a0, const uint64_t* b0, const uint64_t* c0,
+                    uint64_t* c0_folded, int M, int K, int N, int batch, int flags);
+int mpc_conv2d_fold(mpc_ctx* ctx, const uint64_t* a0, const uint64_t* b0, const uint64_t* c0,
+                    uint64_t* c0_folded, int B, int H, int W, int Cin, int Cout, int KH, int KW,
+                    int pad, int stride);
 int mpc_matmul_prepared_bytes(int M, int K, int N, int batch, size_t* right, size_t* left);
 int mpc_conv2d_prepared_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW,
                               int pad, int stride, size_t* right, size_t* left);

@@ -238,10 +238,17 @@ struct GemmArgs {
     int trunc_bits;                   // 0: none
     int rows_L;                       // rows of the left planes (plain: M)
     ConvGeom conv;
-    int ksplit;                       // > 1: split the contraction over this many workgroups per tile
+    int ksplit;                       // > 1: split the (longest party's) contraction over this many workgroups per tile
     int steps_per_split;              // filled by the launcher
-    int tiles_m, tiles_n, tiles_total;   // filled by the launcher: output tiles per matrix, all tiles (x batch x ksplit)
+    int tiles_m, tiles_n;             // filled by the launcher: output tiles per matrix
+    int ksplit_p[2];                  // filled by the launcher: slices of each party's contraction (equal unless the
+                                      // parties contract different lengths: a party's second segment may have KB = 0)
+    int tiles_party[2];               // filled by the launcher: tiles x batch x ksplit_p
+    int heavy_first;                  // filled by the launcher: 1 = all workgroups of party 1 (the longer contraction)
+                                      // come before party 0's in the grid, so the long ones start first
     u64* partial;                     // [ksplit][nparty][batch][M][N] partial products (ksplit > 1)
 };
 int gemm_ksplit(int M, int N, int batch, int nparty, int total_steps);
+// the same choice when party 0 contracts steps0 and party 1 steps1 K steps (slices of the longer one)
+int gemm_ksplit2(int M, int N, int batch, int steps0, int steps1);
 int launch_limb_gemm(mpc_ctx* c, hipStream_t st, const GemmArgs& g);

@@ -103,17 +103,30 @@ void k_limb_gemm(GemmArgs g)
     //  - plain matrices: party 0's tiles, then party 1's, in index order (no halo to share).
     const unsigned id = blockIdx.x;
     int party; unsigned tile;
-    if (CONV) {
+    if (g.heavy_first) {
+        // the parties contract different lengths: party 1's workgroups (the long ones) fill the chip
+        // first, party 0's follow as units free up; inside a party's block the order is as below
+        const unsigned blk1 = (unsigned)((g.tiles_party[1] + 7) / 8 * 8);
+        party = id < blk1 ? 1 : 0;
+        const unsigned local = party ? id : id - blk1;
+        if (CONV) {
+            const unsigned per_xcd = (unsigned)((g.tiles_party[party] + 7) / 8);
+            const unsigned q = local >> 3;
+            tile = q < per_xcd ? (local & 7) * per_xcd + q : 0xffffffffu;
+        } else {
+            tile = local;
+        }
+    } else if (CONV) {
         const unsigned r8 = id & 7, sl = id >> 3;
-        const unsigned per_xcd = (unsigned)((g.tiles_total + 7) / 8);
+        const unsigned per_xcd = (unsigned)((g.tiles_party[0] + 7) / 8);
         const unsigned q = sl / (unsigned)g.nparty;
         party = (int)(sl % (unsigned)g.nparty);
         tile = q < per_xcd ? r8 * per_xcd + q : 0xffffffffu;
     } else {
-        const unsigned per = (unsigned)((g.tiles_total + 7) / 8 * 8);
+        const unsigned per = (unsigned)((g.tiles_party[0] + 7) / 8 * 8);
         party = (int)(id / per); tile = id % per;
     }
-    if (tile >= (unsigned)g.tiles_total) return;             // padding of the last group of eight
+    if (tile >= (unsigned)g.tiles_party[party]) return;      // padding of the last group of eight
     const int mt = (int)(tile % (unsigned)g.tiles_m);
     const unsigned t1 = tile / (unsigned)g.tiles_m;
     const int nt = (int)(t1 % (unsigned)g.tiles_n);
@@ -125,12 +138,12 @@ void k_limb_gemm(GemmArgs g)
     // ---- per-party operands as scalars
     const GemmSeg& sg0 = party ? g.seg[1][0] : g.seg[0][0];
     const GemmSeg& sg1 = party ? g.seg[1][1] : g.seg[0][1];
-    const int KB0 = sg0.KB, KB1 = g.nseg > 1 ? sg1.KB : 0;
+    const int KB0 = sg0.KB, KB1 = g.nseg > 1 ? sg1.KB : 0;        // a party's second segment may be empty
     // K steps of this workgroup: all of them, or one slice when the contraction is split
     const int T_all = (KB0 + KB1) / KS;
     const int st0 = split * g.steps_per_split;
     const int T = T_all - st0 < g.steps_per_split ? T_all - st0 : g.steps_per_split;
-    if (T <= 0) return;             // cannot happen with the launcher's slicing
+    if (T <= 0) return;             // cannot happen: the launcher gives each party ceil(steps / steps_per_split) slices
     const long long krowL = (long long)g.rows_L * 16;      // bytes between k blocks of a left plane
     const long long krowR = (long long)g.N * 16;
 
@@ -428,7 +441,7 @@ __global__ __launch_bounds__(256) void k_splitk_finish(GemmArgs g)
         const int party = (int)(i / per);
         const size_t w = i - (size_t)party * per;
         u64 z = 0;
-        for (int sp = 0; sp < g.ksplit; ++sp) z += g.partial[((size_t)sp * g.nparty + party) * per + w];
+        for (int sp = 0; sp < g.ksplit_p[party]; ++sp) z += g.partial[((size_t)sp * g.nparty + party) * per + w];
         if (g.addend[party]) z += g.addend[party][w];
         if (g.addend2[party]) z += g.addend2[party][w];
         if (g.trunc_bits) z = party == 0 ? (z >> g.trunc_bits) : (u64)0 - (((u64)0 - z) >> g.trunc_bits);
@@ -451,17 +464,23 @@ int launch_cfg(mpc_ctx* c, hipStream_t st, const GemmArgs& g)
     }
     GemmArgs ga = g;
     ga.tiles_m = (g.M + C::TM - 1) / C::TM; ga.tiles_n = (g.N + C::TN - 1) / C::TN;
-    const long long tiles = (long long)ga.tiles_m * ga.tiles_n * g.batch * g.ksplit;
-    const long long wgs = (tiles + 7) / 8 * 8 * g.nparty;
+    long long wgs = 0;
+    for (int p = 0; p < 2; ++p) {
+        const long long tiles = p < g.nparty ? (long long)ga.tiles_m * ga.tiles_n * g.batch * g.ksplit_p[p] : 0;
+        if (tiles >= (1ll << 30)) return MPC_EINVAL;
+        ga.tiles_party[p] = (int)tiles;
+        wgs += (tiles + 7) / 8 * 8;
+    }
+    // equal slice counts: the interleaved / party-major orders of the kernel assume equal blocks
+    if (!ga.heavy_first && g.nparty == 2 && ga.tiles_party[0] != ga.tiles_party[1]) return MPC_EINVAL;
     if (wgs >= (1ll << 31)) return MPC_EINVAL;
-    ga.tiles_total = (int)tiles;
     dim3 grid((unsigned)wgs, 1, 1);
     const int pi = prof_begin(c, MPC_PROF_GEMM_KERNEL, st);
     hipLaunchKernelGGL(kern, grid, dim3(C::NT), C::LDS_BYTES, st, ga);
     if (g.ksplit > 1) {
         const size_t total = (size_t)g.batch * g.out_bstride * g.nparty;
         size_t blocks = (total + 255) / 256; if (blocks > 4096) blocks = 4096;
-        hipLaunchKernelGGL(k_splitk_finish, dim3((unsigned)blocks), dim3(256), 0, st, g);
+        hipLaunchKernelGGL(k_splitk_finish, dim3((unsigned)blocks), dim3(256), 0, st, ga);
     }
     prof_end(c, MPC_PROF_GEMM_KERNEL, pi, st);
     MPC_HIP(c, hipGetLastError());
@@ -476,46 +495,75 @@ int launch_cfg(mpc_ctx* c, hipStream_t st, const GemmArgs& g)
 // matter beyond their low 32 bits hold at most four pairs, so 4 * 2^14 * k < 2^31.
 constexpr int kMaxStepsExact = 1023;
 
-int gemm_ksplit(int M, int N, int batch, int nparty, int total_steps)
+// steps[p]: K steps party p contracts (steps[1] = 0 for a one-party launch).  Returns the number of slices
+// of the longer contraction; a party with fewer steps gets ceil(its steps / slice length) slices.
+static int ksplit_for(int M, int N, int batch, const int steps[2])
 {
     const bool narrow = ((N - 1) % 128) < 64 && (N <= 64 || M >= 4096);
-    const long long tiles = (long long)((M + (narrow ? 127 : 63)) / (narrow ? 128 : 64)) *
-                            ((N + (narrow ? 63 : 127)) / (narrow ? 64 : 128)) * batch * nparty;
+    const long long tiles_pp = (long long)((M + (narrow ? 127 : 63)) / (narrow ? 128 : 64)) *
+                               ((N + (narrow ? 63 : 127)) / (narrow ? 64 : 128)) * batch;      // per party
+    const int nparty = steps[1] > 0 ? 2 : 1;
+    const int longest = steps[0] > steps[1] ? steps[0] : steps[1];
     // the int32 digit sums of one workgroup stay exact for at most kMaxStepsExact steps
-    const int s_exact = (total_steps + kMaxStepsExact - 1) / kMaxStepsExact;
+    const int s_exact = (longest + kMaxStepsExact - 1) / kMaxStepsExact;
     int s = s_exact;
-    if (tiles < 160 && total_steps >= 8) {
+    if (tiles_pp * nparty < 160 && longest >= 8) {
         // One workgroup per compute unit at a time: pick the slice count that minimises
         // (rounds of workgroups over the 256 units) x (steps per slice + fixed cost per
         // workgroup: pipeline fill, epilogue, its share of the finishing pass).
         long long best = -1;
-        const int s_max = total_steps / 4 < 32 ? total_steps / 4 : 32;
+        const int s_max = longest / 4 < 32 ? longest / 4 : 32;
         for (int q = s_exact < 1 ? 1 : s_exact; q <= s_max; ++q) {
-            const long long rounds = (tiles * q + 255) / 256;
-            const long long cost = rounds * ((total_steps + q - 1) / q + 6);
+            const int per = (longest + q - 1) / q;
+            long long wgs = 0;
+            for (int p = 0; p < nparty; ++p) wgs += tiles_pp * ((steps[p] + per - 1) / per);
+            const long long rounds = (wgs + 255) / 256;
+            const long long cost = rounds * (per + 6);
             if (best < 0 || cost < best) { best = cost; s = q; }
         }
     }
     if (s <= 1) return 1;
-    const int per = (total_steps + s - 1) / s;
-    return (total_steps + per - 1) / per;          // no empty slice
+    const int per = (longest + s - 1) / s;
+    return (longest + per - 1) / per;          // no empty slice
+}
+
+int gemm_ksplit(int M, int N, int batch, int nparty, int total_steps)
+{
+    const int steps[2] = { total_steps, nparty > 1 ? total_steps : 0 };
+    return ksplit_for(M, N, batch, steps);
+}
+
+int gemm_ksplit2(int M, int N, int batch, int steps0, int steps1)
+{
+    const int steps[2] = { steps0, steps1 };
+    return ksplit_for(M, N, batch, steps);
 }
 
 int launch_limb_gemm(mpc_ctx* c, hipStream_t st, const GemmArgs& g_in)
 {
     GemmArgs g = g_in;
+    if (g.nparty < 1 || g.nparty > 2 || g.nseg < 1 || g.nseg > 2) return MPC_EINVAL;
     {
-        int total_steps = 0;
-        for (int s = 0; s < g.nseg; ++s) total_steps += g.seg[0][s].KB / KS;
+        int steps[2] = { 0, 0 };
+        for (int p = 0; p < g.nparty; ++p)
+            for (int s = 0; s < g.nseg; ++s) steps[p] += g.seg[p][s].KB / KS;
+        const int longest = steps[0] > steps[1] ? steps[0] : steps[1];
         if (g.ksplit < 1 || !g.partial) g.ksplit = 1;
-        g.steps_per_split = (total_steps + g.ksplit - 1) / g.ksplit;
-        g.ksplit = (total_steps + g.steps_per_split - 1) / g.steps_per_split;      // no empty slice
-        if (g.steps_per_split > kMaxStepsExact) return MPC_ERANGE;
+        g.steps_per_split = (longest + g.ksplit - 1) / g.ksplit;
+        if (g.steps_per_split < 1 || g.steps_per_split > kMaxStepsExact) return MPC_ERANGE;
+        g.ksplit = 1;
+        for (int p = 0; p < 2; ++p) {
+            g.ksplit_p[p] = p < g.nparty ? (steps[p] + g.steps_per_split - 1) / g.steps_per_split : 0;      // no empty slice
+            if (g.ksplit_p[p] > g.ksplit) g.ksplit = g.ksplit_p[p];
+        }
+        // the longer contraction first (party 1's by construction of the callers)
+        g.heavy_first = g.nparty == 2 && steps[1] > steps[0];
+        if (g.nparty == 2 && steps[1] < steps[0]) return MPC_EINVAL;
     }
     if (g.M <= 0 || g.N <= 0 || g.batch <= 0 || g.nseg < 1 || g.nseg > 2) return MPC_EINVAL;
     for (int p = 0; p < g.nparty; ++p)
         for (int s = 0; s < g.nseg; ++s)
-            if (g.seg[p][s].KB <= 0 || g.seg[p][s].KB % KS) return MPC_EINVAL;
+            if (g.seg[p][s].KB < (s == 0 ? 1 : 0) || g.seg[p][s].KB % KS) return MPC_EINVAL;     // a second segment may be empty
     // per-lane byte offsets inside one k block of a plane are 32-bit
     if ((long long)g.rows_L * 16 >= (1ll << 32) || (long long)g.N * 16 >= (1ll << 32)) return MPC_EINVAL;
     // 64x128 workgroup tiles, or 128x64 when a second 64-column half would be empty

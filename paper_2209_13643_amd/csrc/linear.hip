@@ -95,7 +95,7 @@ struct LinearWs {
     size_t bytes; bool ok;
 };
 
-LinearWs carve(u8* base, size_t cap, const LinearShape& s)
+LinearWs carve(u8* base, size_t cap, const LinearShape& s, bool folded = false)
 {
     WsAlloc w(base, cap);
     LinearWs r{};
@@ -104,8 +104,9 @@ LinearWs carve(u8* base, size_t cap, const LinearShape& s)
     const size_t lp = 8 * s.L_plane * s.batch, rp = 8 * s.R_plane * s.batch;
     r.pl_e = w.take<u8>(lp); r.pl_a[0] = w.take<u8>(lp); r.pl_a[1] = w.take<u8>(lp);
     r.pr_f = w.take<u8>(rp); r.pr_b[0] = w.take<u8>(rp); r.pr_b[1] = w.take<u8>(rp);
-    // the two-segment, two-party launch is the one that decides the split
-    r.ksplit = gemm_ksplit(s.M, s.N, s.batch, 2, 2 * s.KB / 2);
+    // the two-segment, two-party launch is the one that decides the split (folded: party 0 contracts one segment)
+    r.ksplit = folded ? gemm_ksplit2(s.M, s.N, s.batch, s.KB / 2, 2 * s.KB / 2)
+                      : gemm_ksplit(s.M, s.N, s.batch, 2, 2 * s.KB / 2);
     r.partial = r.ksplit > 1 ? w.take<u64>((size_t)r.ksplit * 2 * s.batch * s.M * s.N) : nullptr;
     r.bytes = w.off; r.ok = w.ok;
     return r;
@@ -219,6 +220,9 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
     if (n_chunks < 1) return MPC_EINVAL;
     // prepared planes: digit planes of the input-independent operands, recoded ahead of time
     const bool skip_right = prep_right != nullptr, skip_left = prep_left != nullptr;
+    // folded triple: cc.p[0] holds c_0 - a_0 * b_0, and party 0 contracts (x_0 + e_1) against b_0 + f alone
+    const bool folded = (flags & MPC_FOLDED) != 0;
+    if (folded && (!skip_right || !skip_left || x_public || (flags & MPC_TWO_PHASE))) return MPC_EINVAL;
     for (int i = 0; i < 2; ++i) {
         if (!a.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
         if (!skip_right && !b.p[i]) return MPC_EINVAL;
@@ -227,7 +231,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
     }
     if ((skip_right && ((uintptr_t)prep_right & 15)) || (skip_left && ((uintptr_t)prep_left & 15))) return MPC_EINVAL;
     if (ws_off > c->ws_bytes) return MPC_ENOMEM;
-    LinearWs w = carve(c->ws ? c->ws + ws_off : nullptr, c->ws_bytes - ws_off, s);
+    LinearWs w = carve(c->ws ? c->ws + ws_off : nullptr, c->ws_bytes - ws_off, s, folded);
     if (!w.ok) return MPC_ENOMEM;
     if (skip_right) {
         const size_t rp = align_up(8 * s.R_plane * s.batch);
@@ -235,7 +239,9 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
     }
     if (skip_left) {
         const size_t lp = align_up(8 * s.L_plane * s.batch);
-        w.pl_a[0] = const_cast<u8*>(prep_left); w.pl_a[1] = w.pl_a[0] + lp;
+        // folded: the workspace slot of a_0's planes receives the planes of x_0 + e_1 instead
+        if (!folded) w.pl_a[0] = const_cast<u8*>(prep_left);
+        w.pl_a[1] = const_cast<u8*>(prep_left) + lp;
     }
     const bool have_f = f_public != nullptr || skip_right;     // the weight mask needs no exchange in this call
 
@@ -284,9 +290,14 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         const u64* lsrc[3] = { a.p[0], a.p[1], x_public ? x_public : w.se[0] };
         const u64* lsrc2[3] = { nullptr, nullptr, x_public ? nullptr : w.re[0] };
         u8* ldst[3] = { w.pl_a[0], w.pl_a[1], w.pl_e };
+        if (folded) {
+            // party 0: a_0 + e = x_0 + e_1 (own share + received word); party 1: e from its own and the received word
+            lsrc[1] = x.p[0]; lsrc2[1] = w.re[0]; ldst[1] = w.pl_a[0];
+            lsrc[2] = w.se[1]; lsrc2[2] = w.re[1];
+        }
         // all digit planes of the call in one launch (the transposed-im2col recoder is a kernel of its own)
         int nr = 0;
-        const int l0 = skip_left ? 2 : 0;
+        const int l0 = folded ? 1 : skip_left ? 2 : 0;
         if (s.im2colT) {
             MPC_TRY(launch_left(c, P0, s, 3 - l0, lsrc + l0, lsrc2 + l0, ldst + l0));
         } else {
@@ -318,6 +329,11 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
                 g.seg[i][0] = make_seg(s, w.pl_e, w.pr_b[i]);
                 g.seg[i][1] = make_seg(s, w.pl_a[i], w.pr_f);
                 g.addend[i] = cc.p[i]; g.addend2[i] = nullptr; g.out[i] = z.p[i];
+            }
+            if (folded) {
+                // z_0 = (c_0 - a_0 b_0) + (a_0 + e)(b_0 + f): one product; party 1 as ever
+                g.seg[0][0] = make_seg(s, w.pl_a[0], w.pr_b[0]);
+                g.seg[0][1] = GemmSeg{};
             }
             g.trunc_bits = trunc;
             MPC_TRY(launch_limb_gemm(c, P0, g));
@@ -351,6 +367,27 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
     }
     const u64* e_src = x_public ? x_public : w.se[0];
     const u64* e_src2 = x_public ? nullptr : w.re[0];
+
+    if (folded) {
+        // after the exchange each party recodes what it contracts: party 0 the planes of x_0 + e_1,
+        // party 1 those of e; then the joint launch, party 0 with one segment
+        MPC_TRY(chain(c, Wr, P0));
+        MPC_TRY(chain(c, Wr, P1));
+        MPC_TRY(launch_left1(c, P0, s, x.p[0], w.re[0], w.pl_a[0]));
+        MPC_TRY(launch_left1(c, P1, s, w.se[1], w.re[1], w.pl_e));
+        MPC_TRY(chain(c, P1, P0));
+        GemmArgs g{};
+        fill_geom(s, w, g);
+        g.nparty = 2; g.nseg = 2;
+        g.seg[0][0] = make_seg(s, w.pl_a[0], w.pr_b[0]); g.seg[0][1] = GemmSeg{};
+        g.seg[1][0] = make_seg(s, w.pl_e, w.pr_b[1]);    g.seg[1][1] = make_seg(s, w.pl_a[1], w.pr_f);
+        for (int i = 0; i < 2; ++i) { g.addend[i] = cc.p[i]; g.addend2[i] = nullptr; g.out[i] = z.p[i]; }
+        g.trunc_bits = trunc;
+        MPC_TRY(launch_limb_gemm(c, P0, g));
+        prof_end(c, MPC_PROF_LINEAR, pi, P0);
+        MPC_TRY(chain(c, P0, P1));
+        return MPC_OK;
+    }
 
     // -- digit planes that do not depend on the exchange: [a_i] (and b_1)
     for (int i = 0; i < 2 && !skip_left; ++i)
@@ -594,6 +631,15 @@ int ring_product(mpc_ctx* c, const LinearShape& s, const u64* L, const u64* R, u
     return MPC_OK;
 }
 
+// Party 0's folded addend of a prepared layer: out = c_0 - a_0 * b_0 (a local, input-independent product).
+int fold_addend(mpc_ctx* c, const LinearShape& s, const u64* a0, const u64* b0, const u64* c0, u64* out)
+{
+    if (!c || !a0 || !b0 || !c0 || !out) return MPC_EINVAL;
+    MPC_TRY(ring_product(c, s, a0, b0, out));
+    MPC_TRY(launch_sub(c, c->s[0], c0, out, out, s.nz));    // element-wise, in place: out = c_0 - out
+    return chain(c, c->s[0], c->s[1]);
+}
+
 // Three parties: right = [f | b_0 + f | b_1 | b_2], left = [a_0 | a_1 | a_2].
 void prepared_sizes3(const LinearShape& s, size_t* right, size_t* left)
 {
@@ -636,7 +682,9 @@ size_t mpc_matmul_workspace_bytes(int M, int K, int N, int batch)
 {
     LinearShape s = shape_matmul(M, K, N, batch);
     if (check_shape(s) != MPC_OK) return 0;
-    return carve(nullptr, 0, s).bytes;
+    // the folded prepared call may slice its contraction differently: the query covers both
+    const size_t plain = carve(nullptr, 0, s).bytes, folded = carve(nullptr, 0, s, true).bytes;
+    return plain > folded ? plain : folded;
 }
 
 size_t mpc_conv2d_workspace_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
@@ -644,7 +692,8 @@ size_t mpc_conv2d_workspace_bytes(int B, int H, int W, int Cin, int Cout, int KH
     if (stride <= 0) return 0;
     LinearShape s = shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride);
     if (check_shape(s) != MPC_OK) return 0;
-    return carve(nullptr, 0, s).bytes;
+    const size_t plain = carve(nullptr, 0, s).bytes, folded = carve(nullptr, 0, s, true).bytes;
+    return plain > folded ? plain : folded;
 }
 
 int mpc_beaver_matmul(mpc_ctx* ctx, mpc_cshare x, mpc_cshare y, mpc_cshare a, mpc_cshare b, mpc_cshare c,
@@ -713,6 +762,21 @@ int mpc_conv2d_prepared(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_cshare c, 
     const mpc_cshare none = { { nullptr, nullptr } };
     return beaver_linear(ctx, shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride), x, none, a, none, c, z,
                          nullptr, n_chunks, flags, nullptr, (const u8*)right_planes, (const u8*)left_planes);
+}
+
+int mpc_matmul_fold(mpc_ctx* ctx, const uint64_t* a0, const uint64_t* b0, const uint64_t* c0, uint64_t* c0_folded,
+                    int M, int K, int N, int batch, int flags)
+{
+    if (M <= 0 || K <= 0 || N <= 0 || batch <= 0 || (flags & ~(MPC_TRANS_X | MPC_TRANS_Y))) return MPC_EINVAL;
+    return fold_addend(ctx, shape_matmul(M, K, N, batch, flags), a0, b0, c0, c0_folded);
+}
+
+int mpc_conv2d_fold(mpc_ctx* ctx, const uint64_t* a0, const uint64_t* b0, const uint64_t* c0, uint64_t* c0_folded,
+                    int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)
+{
+    if (stride <= 0 || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || pad < 0)
+        return MPC_EINVAL;
+    return fold_addend(ctx, shape_conv(B, H, W, Cin, Cout, KH, KW, pad, stride), a0, b0, c0, c0_folded);
 }
 
 size_t mpc_conv2d_grad_x_workspace_bytes(int B, int H, int W, int Cin, int Cout, int KH, int KW, int pad, int stride)

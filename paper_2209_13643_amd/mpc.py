@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libmpcpipe.so")
 MPC_TRUNCATE = 1
 MPC_TRANS_X = 4
 MPC_TRANS_Y = 8
+MPC_FOLDED = 16
 MPC_TWO_PHASE = 2
 PROF_GEMM_KERNEL, PROF_LINEAR, PROF_RELU = 0, 1, 2
 N_AND_TRIPLES = 12
@@ -62,7 +63,7 @@ EXPORTS = [
     "mpc_maxpool2x2_signs", "mpc_maxpool_backward_workspace_bytes", "mpc_maxpool2x2_backward",
     "mpc_ctx_set_adder", "mpc_ctx_set_exchange", "mpc_ctx_profile_samples", "mpc_add",
     "mpc_matmul_prepared_bytes", "mpc_conv2d_prepared_bytes", "mpc_matmul_prepare", "mpc_conv2d_prepare",
-    "mpc_beaver_matmul_prepared", "mpc_conv2d_prepared",
+    "mpc_beaver_matmul_prepared", "mpc_conv2d_prepared", "mpc_matmul_fold", "mpc_conv2d_fold",
     "mpc_ctx_capture_begin", "mpc_ctx_capture_end", "mpc_graph_launch", "mpc_graph_destroy",
     "mpc_open3", "mpc_matmul3_workspace_bytes", "mpc_beaver_matmul3", "mpc_conv2d3_workspace_bytes", "mpc_conv2d3",
     "mpc_truncate3_workspace_bytes", "mpc_truncate3", "mpc_relu3_workspace_bytes", "mpc_relu3",
@@ -101,6 +102,8 @@ def lib():
     L.mpc_conv2d_prepare.argtypes = [c_void_p, CShare, CShare, _P64, c_void_p, c_void_p] + [c_int] * 9
     L.mpc_beaver_matmul_prepared.argtypes = [c_void_p, CShare, CShare, CShare, CShare, c_void_p, c_void_p] + [c_int] * 6
     L.mpc_conv2d_prepared.argtypes = [c_void_p, CShare, CShare, CShare, CShare, c_void_p, c_void_p] + [c_int] * 11
+    L.mpc_matmul_fold.argtypes = [c_void_p, _P64, _P64, _P64, _P64] + [c_int] * 5
+    L.mpc_conv2d_fold.argtypes = [c_void_p, _P64, _P64, _P64, _P64] + [c_int] * 9
     L.mpc_ctx_profile_samples.argtypes = [c_void_p, c_int, POINTER(ctypes.c_double), c_int, POINTER(c_int)]
     L.mpc_ctx_set_exchange.argtypes = [c_void_p, c_int]
     L.mpc_ctx_set_streams.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
@@ -492,6 +495,26 @@ class Lane:
                                                      left.data_ptr() if left is not None else None,
                                                      M, K, N, batch, n_chunks, flags))
         return z
+
+    def fold_matmul(self, a, b, c, flags=0):
+        """Party 0's folded addend c_0 - a_0 b_0 for beaver_matmul_prepared(..., flags | MPC_FOLDED)."""
+        shp = a[0].shape
+        batch = 1 if len(shp) == 2 else shp[0]
+        M, K = (shp[-1], shp[-2]) if flags & MPC_TRANS_X else (shp[-2], shp[-1])
+        N = c[0].shape[-1]
+        self.reserve(lib().mpc_matmul_workspace_bytes(M, K, N, batch))
+        out = torch.empty_like(c[0])
+        self._check(lib().mpc_matmul_fold(self._h, _p64(a[0]), _p64(b[0]), _p64(c[0]), _p64(out), M, K, N, batch, flags))
+        return out
+
+    def fold_conv2d(self, a, b, c, pad, stride):
+        """Party 0's folded addend c_0 - conv(a_0, b_0) for conv2d_prepared(..., flags | MPC_FOLDED)."""
+        B, H, W, Cin = a[0].shape; KH, KW, _, Cout = b[0].shape
+        self.reserve(lib().mpc_conv2d_workspace_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride))
+        out = torch.empty_like(c[0])
+        self._check(lib().mpc_conv2d_fold(self._h, _p64(a[0]), _p64(b[0]), _p64(c[0]), _p64(out),
+                                          B, H, W, Cin, Cout, KH, KW, pad, stride))
+        return out
 
     def prepare_conv2d(self, a, b, f_public, pad, stride, left=True):
         B, H, W, Cin = a[0].shape; KH, KW, _, Cout = b[0].shape

@@ -33,6 +33,7 @@ class LayerState:
     right: torch.Tensor | None = None   # prepared digit planes of f, b_0 + f, b_1 (prepare_layers)
     left: torch.Tensor | None = None    # prepared digit planes of a_0, a_1
     pool_first: bool = False      # pooled layer evaluated as ReLU(maxpool(z)): the ReLU material covers the pooled size
+    c_fold: tuple | None = None   # (c_0 - a_0 b_0, c_1): addends of the folded prepared call (prepare_layers(fold=True))
 
 
 def with_batch(layers, batch: int):
@@ -99,17 +100,23 @@ def preopen_weights(lane: mpc.Lane, states):
     lane.sync()
 
 
-def prepare_layers(lane: mpc.Lane, layers, states):
+def prepare_layers(lane: mpc.Lane, layers, states, fold: bool = False):
     """Recode the input-independent operands of every layer once (the triples' [a_i] and, from the
     opened weight mask, f, b_0 + f, b_1) and keep their digit planes resident: run_layer then only
-    masks, exchanges and recodes the activation.  Opens the weight masks first if that was not done."""
+    masks, exchanges and recodes the activation.  Opens the weight masks first if that was not done.
+    fold: also form party 0's folded addend c_0 - a_0 b_0, so that the online call contracts three
+    ring products instead of four (MPC_FOLDED)."""
     if any(st.f_public is None for st in states):
         preopen_weights(lane, states)
     for L, st in zip(layers, states):
         if isinstance(L, synth.Conv):
             st.right, st.left = lane.prepare_conv2d(st.a, st.b, st.f_public, L.pad, L.stride)
+            if fold:
+                st.c_fold = (lane.fold_conv2d(st.a, st.b, st.c, L.pad, L.stride), st.c[1])
         else:
             st.right, st.left = lane.prepare_matmul(st.a, st.b, st.f_public)
+            if fold:
+                st.c_fold = (lane.fold_matmul(st.a, st.b, st.c), st.c[1])
     lane.sync()
 
 
@@ -145,7 +152,10 @@ def run_layer(lane: mpc.Lane, L, st: LayerState, x, keep: list, n_chunks=1, relu
     y_arg = None if st.f_public is not None else st.w
     if isinstance(L, synth.Conv):
         xs = (x[0].view(L.B, L.H, L.W, L.Cin), x[1].view(L.B, L.H, L.W, L.Cin))
-        if st.right is not None:
+        if st.right is not None and st.c_fold is not None:
+            z = lane.conv2d_prepared(xs, st.a, st.c_fold, st.right, st.left, L.KH, L.KW, L.pad, L.stride,
+                                     n_chunks=n_chunks, flags=flags | mpc.MPC_FOLDED, out=o.get("z"))
+        elif st.right is not None:
             z = lane.conv2d_prepared(xs, st.a, st.c, st.right, st.left, L.KH, L.KW, L.pad, L.stride,
                                      n_chunks=n_chunks, flags=flags, out=o.get("z"))
         else:
@@ -153,7 +163,10 @@ def run_layer(lane: mpc.Lane, L, st: LayerState, x, keep: list, n_chunks=1, relu
                             n_chunks=n_chunks, flags=flags, out=o.get("z"))
     else:
         xs = (x[0].view(L.M, L.K), x[1].view(L.M, L.K))
-        if st.right is not None:
+        if st.right is not None and st.c_fold is not None:
+            z = lane.beaver_matmul_prepared(xs, st.a, st.c_fold, st.right, st.left, n_chunks=n_chunks,
+                                            flags=flags | mpc.MPC_FOLDED, out=o.get("z"))
+        elif st.right is not None:
             z = lane.beaver_matmul_prepared(xs, st.a, st.c, st.right, st.left, n_chunks=n_chunks, flags=flags, out=o.get("z"))
         else:
             z = lane.beaver_matmul(xs, y_arg, st.a, st.b, st.c, f_public=st.f_public, n_chunks=n_chunks, flags=flags,

@@ -109,7 +109,8 @@ def test_pooled_layers_as_relu_of_maxpool(mods, dealt, packed_relu):
 
 
 @pytest.mark.parametrize("mode", ["serial-3stream", "pipelined", "pipelined-preopened", "pipelined-two-phase-chunked",
-                                  "pipelined-packed-relu", "pipelined-prepared-planes", "pipelined-packed-relu-remote-store"])
+                                  "pipelined-packed-relu", "pipelined-prepared-planes", "pipelined-folded-preallocated",
+                                  "pipelined-packed-relu-remote-store"])
 def test_pipeline_invariance(mods, dealt, mode):
     mpc, pipeline = mods
     layers, mbs = dealt
@@ -131,6 +132,13 @@ def test_pipeline_invariance(mods, dealt, mode):
     if mode == "pipelined-prepared-planes":
         for ln, sts in zip(lanes, states):
             pipeline.prepare_layers(ln, layers, sts)
+    outs_pre = None
+    if mode == "pipelined-folded-preallocated":
+        # prepared planes with party 0's addend folded, every output tensor allocated ahead of the pass
+        for ln, sts in zip(lanes, states):
+            pipeline.prepare_layers(ln, layers, sts, fold=True)
+        outs_pre = [pipeline.alloc_outputs(ln, layers, sts) for ln, sts in zip(lanes, states)]
+        kw = dict(outs_per_mb=outs_pre)
     if mode == "pipelined-two-phase-chunked":
         kw = dict(n_chunks=3, relu_chunks=3, flags=mpc.MPC_TRUNCATE | mpc.MPC_TWO_PHASE)
     keep = []

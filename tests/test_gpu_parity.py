@@ -372,6 +372,64 @@ def test_conv2d_prepared_planes(mpc, lane, case):
     assert_shares_equal(host(mpc, lane, z), oracle_conv(d), "prepared conv, two-phase, chunked")
 
 
+FOLDED_MATMUL = [(1, 1, 1), (5, 7, 3), (64, 256, 128), (130, 70, 200), (300, 1100, 150), (32, 512, 10), (128, 4608, 512),
+                 (700, 64, 300)]
+
+
+@pytest.mark.parametrize("shape", FOLDED_MATMUL)
+@pytest.mark.parametrize("n_chunks", [1, 3])
+def test_beaver_matmul_folded(mpc, lane, shape, n_chunks):
+    """Party 0's addend folded ahead of time (c_0 - a_0 b_0): party 0 contracts one product, party 1 two,
+    and every output word is Alg. 1's.  Shapes cover one-tile outputs whose contraction is sliced (the two
+    parties then get different slice counts), many tiles, ragged edges, and a rescale-free call."""
+    M, K, N = shape
+    print(f"folded matmul {shape} chunks={n_chunks}", flush=True)
+    d = deal_matmul(np.random.default_rng(M * K + N + 9), M, K, N)
+    f_public = mpc.to_device((d["y"][0] - d["b"][0]) + (d["y"][1] - d["b"][1]))
+    a, b, c = dev(mpc, d["a"]), dev(mpc, d["b"]), dev(mpc, d["c"])
+    right, lp = lane.prepare_matmul(a, b, f_public)
+    c0f = lane.fold_matmul(a, b, c)
+    lane.sync()
+    assert np.array_equal(mpc.to_host(c0f), d["c"][0] - oracle.ring_matmul(d["a"][0], d["b"][0]))
+    for trunc in (True, False):
+        z = lane.beaver_matmul_prepared(dev(mpc, d["x"]), a, (c0f, c[1]), right, lp, n_chunks=n_chunks,
+                                        flags=(mpc.MPC_TRUNCATE if trunc else 0) | mpc.MPC_FOLDED)
+        assert_shares_equal(host(mpc, lane, z), oracle_matmul(d, 16 if trunc else 0), "folded matmul")
+
+
+def test_beaver_matmul_folded_batched(mpc, lane):
+    print("folded matmul batched", flush=True)
+    d = deal_matmul(np.random.default_rng(78), 48, 64, 40, batch=6)
+    f_public = mpc.to_device((d["y"][0] - d["b"][0]) + (d["y"][1] - d["b"][1]))
+    a, b, c = dev(mpc, d["a"]), dev(mpc, d["b"]), dev(mpc, d["c"])
+    right, lp = lane.prepare_matmul(a, b, f_public)
+    c0f = lane.fold_matmul(a, b, c)
+    z = lane.beaver_matmul_prepared(dev(mpc, d["x"]), a, (c0f, c[1]), right, lp, flags=mpc.MPC_TRUNCATE | mpc.MPC_FOLDED)
+    assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "folded batched")
+
+
+@pytest.mark.parametrize("case", CONV_CASES + [(2, 4, 4, 512, 96, 3, 3, 1, 1), (3, 16, 16, 3, 64, 3, 3, 1, 1)])
+def test_conv2d_folded(mpc, lane, case):
+    B, H, W, Cin, Cout, KH, KW, pad, stride = case
+    print(f"folded conv {case}", flush=True)
+    d = deal_conv(np.random.default_rng(sum(case) + 4), B, H, W, Cin, Cout, KH, KW, pad, stride)
+    f_public = mpc.to_device((d["y"][0] - d["b"][0]) + (d["y"][1] - d["b"][1]))
+    a, b, c = dev(mpc, d["a"]), dev(mpc, d["b"]), dev(mpc, d["c"])
+    right, lp = lane.prepare_conv2d(a, b, f_public, pad, stride)
+    c0f = lane.fold_conv2d(a, b, c, pad, stride)
+    for _ in range(2):
+        z = lane.conv2d_prepared(dev(mpc, d["x"]), a, (c0f, c[1]), right, lp, KH, KW, pad, stride,
+                                 flags=mpc.MPC_TRUNCATE | mpc.MPC_FOLDED)
+        assert_shares_equal(host(mpc, lane, z), oracle_conv(d), "folded conv")
+    # what the folded call cannot be combined with is refused before anything is enqueued
+    with pytest.raises(mpc.MpcError):
+        lane.conv2d_prepared(dev(mpc, d["x"]), a, (c0f, c[1]), right, None, KH, KW, pad, stride,
+                             flags=mpc.MPC_TRUNCATE | mpc.MPC_FOLDED)
+    with pytest.raises(mpc.MpcError):
+        lane.conv2d_prepared(dev(mpc, d["x"]), a, (c0f, c[1]), right, lp, KH, KW, pad, stride,
+                             flags=mpc.MPC_TRUNCATE | mpc.MPC_FOLDED | mpc.MPC_TWO_PHASE)
+
+
 def test_graph_capture_replays(mpc):
     """A secure layer (Beaver matmul + ReLU) recorded once and replayed on fresh inputs in the same
     buffers, with eager work and synchronisation between the replays: every replay equals the oracle."""
