@@ -51,9 +51,14 @@ INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_OPS_PER_SECURE_MAC = 288          # 2 parties x 2 ring GEMMs x 36 digit products x 2 ops
 RELU_BYTES_PER_ELEMENT = 86 * 8 + 2 + 216 * 8 + 137 * 8   # compulsory + openings + carried state, both parties
+# the same chain with the exchange by remote store (no copy kernels; a level stage recomputes its own masked words from
+# the carried state and stores them to the peer only), per party in words: A2B copy 2, first 10, level-0 stage 18,
+# levels 1..4 22 each, level 5 18, sign 7, B2A 8, select 8 = 159 W, plus 7 bytes (sign bit, random bit, masked bit)
+RELU_PUT_BYTES_PER_ELEMENT = 2 * (159 * 8 + 7)
 RELU_COMPULSORY_BYTES = 86 * 8 + 2                        # x, y, r, 12 AND triples, B2A pair, select triple: DRAM-compulsory
 # the sign-only packed chain (mpc_relu_msb), same three classes: 31.72 W + 2 B, 71.25 W + 8 B, 41.56 W + 6 B
 RELU_MSB_BYTES_PER_ELEMENT = (31.71875 + 71.25 + 41.5625) * 8 + 16
+RELU_MSB_PUT_BYTES_PER_ELEMENT = RELU_MSB_BYTES_PER_ELEMENT - 71.25 * 8 / 4      # one of the four traversals of every opened word less
 RELU_MSB_COMPULSORY_BYTES = 31.71875 * 8 + 2
 RELU3_BYTES_PER_ELEMENT = 966 * 8 + 33      # three parties: 141 W + 3 B, 606 W + 21 B, 219 W + 9 B (same three classes)
 RELU3_MSB_BYTES_PER_ELEMENT = 2961          # three parties, sign-only chain: 59.6 W + 3 B, 226.0 W + 21 B, 80.3 W + 9 B
@@ -98,7 +103,7 @@ def read_pmc_summary(path):
 class Net:
     """configs[4] on four lanes in one mode: lanes, material, inputs and preallocated outputs."""
 
-    def __init__(self, seed, packed_relu=False, prepared=False, pool_first=False, exchange="copy"):
+    def __init__(self, seed, packed_relu=False, prepared=False, fold=False, pool_first=False, exchange="copy"):
         import torch
         from paper_2209_13643_amd import dealer, mpc, pipeline, synth
         self.pipeline, self.torch = pipeline, torch
@@ -118,7 +123,7 @@ class Net:
             torch.cuda.synchronize()
             pipeline.preopen_weights(self.lanes[m], st)          # Alg. 3: weight masks travel ahead of the inputs
             if prepared:
-                pipeline.prepare_layers(self.lanes[m], self.layers, st)
+                pipeline.prepare_layers(self.lanes[m], self.layers, st, fold=fold)
             self.outs.append(pipeline.alloc_outputs(self.lanes[m], self.layers, st))
         # serial runs put every micro-batch on lane 0: its outputs are reused from step to step as well
         torch.cuda.synchronize()
@@ -186,73 +191,78 @@ def check_network(net, torch):
     return worst
 
 
+def run_mode(seed, args, torch, with_kinds=False, **mode):
+    """configs[4] in one mode: four lanes eager (the timed step when `with_kinds`), serial on one lane, and one
+    recorded graph per lane; optionally the serial pass split by kind of call (HIP-event regions)."""
+    from paper_2209_13643_amd import mpc
+    net = Net(seed, **mode)
+    ms_pipe = net.timed(net.step_pipelined, args.steps, args.warmup)
+    err = check_network(net, torch)
+    ms_serial = net.timed(net.step_serial, max(2, args.steps // 2), 2)
+    res = {"serial_ms": ms_serial, "four_lanes_ms": ms_pipe, "max_abs_err_logits": err}
+    if with_kinds:
+        lane = net.lanes[0]
+        lane.set_profiling(True); lane.profile_reset()
+        reps = 3
+        for _ in range(reps):
+            net.step_serial()
+        net.sync(); lane.set_profiling(False)
+        res["kinds"] = tuple(sum(lane.profile_samples(w)) / reps for w in (mpc.PROF_LINEAR, mpc.PROF_GEMM_KERNEL, mpc.PROF_RELU))
+        lane.profile_reset()
+    gs = net.graphs()
+    ms_graphs = net.timed(lambda: [g.launch(ln) for g, ln in zip(gs, net.lanes)], args.steps, 3)
+    del gs
+    net.close(); del net
+    torch.cuda.empty_cache()
+    res.update(four_lanes_recorded_graphs_ms=ms_graphs, speedup_four_lanes=ms_serial / ms_pipe,
+               speedup_recorded_graphs=ms_serial / ms_graphs,
+               images_per_s_serial=N_MB * MICRO_BATCH / ms_serial * 1e3,
+               images_per_s_four_lanes=N_MB * MICRO_BATCH / ms_pipe * 1e3,
+               images_per_s_recorded_graphs=N_MB * MICRO_BATCH / ms_graphs * 1e3)
+    return res
+
+
 def pipeline_legs(args, torch):
-    """The timed steps (default mode), the serial pass and its per-kind split, and the best mode."""
-    from paper_2209_13643_amd import bench_configs, mpc, synth
+    """The timed steps (the step's mode), its serial pass split by kind, and the other modes beside it."""
+    from paper_2209_13643_amd import bench_configs, synth
     seed = synth.BASE_SEED + 4
-    net = Net(seed)
-    layers = net.layers
+    layers = synth.config_vgg16_pipeline(MICRO_BATCH).layers
     macs = sum(bench_configs.layer_macs(L) for L in layers) * N_MB
     relu_el = pool_cmp = 0
     for L in layers:
         n_out = (L.B * L.Ho * L.Wo * L.Cout) if isinstance(L, synth.Conv) else L.M * L.N
         if L.relu: relu_el += n_out * N_MB
         if isinstance(L, synth.Conv) and L.pool: pool_cmp += 3 * (n_out // 4) * N_MB
-    # ---- the timed region: exactly `steps` pipelined steps between two synchronisations
-    ms_step = net.timed(net.step_pipelined, args.steps, args.warmup)
-    err = check_network(net, torch)
-    ms_serial = net.timed(net.step_serial, max(2, args.steps // 2), 2)
-    # ---- serial pass with timing regions: which kind of call takes the time
-    lane = net.lanes[0]
-    lane.set_profiling(True); lane.profile_reset()
-    reps = 3
-    for _ in range(reps):
-        net.step_serial()
-    net.sync(); lane.set_profiling(False)
-    lin = sum(lane.profile_samples(mpc.PROF_LINEAR)) / reps
-    gem = sum(lane.profile_samples(mpc.PROF_GEMM_KERNEL)) / reps
-    rel = sum(lane.profile_samples(mpc.PROF_RELU)) / reps
-    lane.profile_reset()
-    gs = net.graphs()
-    ms_graphs = net.timed(lambda: [g.launch(ln) for g, ln in zip(gs, net.lanes)], args.steps, 3)
-    del gs
-    net.close(); del net
-    torch.cuda.empty_cache()
+    # ---- the timed region: exactly `steps` four-lane steps between two synchronisations
+    step = run_mode(seed, args, torch, with_kinds=True, prepared=True, fold=True, exchange="put")
+    lin, gem, rel = step.pop("kinds")
+    ms_step, ms_serial = step["four_lanes_ms"], step["serial_ms"]
+    step = {"relu": "whole words (mpc_relu: the full 64-bit adder of Sec. 4.2)", "exchange": "remote store into the peer's receive buffer",
+            "planes": "prepared: weight masks opened ahead (Alg. 3), triples' digit planes and party 0's folded addend formed offline",
+            "network": "as written (ReLU, then max-pool)", **step}
     out = {
-        "ms_per_step": ms_step, "macs": macs, "relu_elements": relu_el, "pool_comparisons": pool_cmp, "err": err,
-        "pipeline": {"default_mode": {"relu": "whole-word (mpc_relu)", "exchange": "copy kernels", "planes": "recoded in the call",
-                                      "serial_ms": ms_serial, "four_lanes_ms": ms_step,
-                                      "four_lanes_recorded_graphs_ms": ms_graphs,
-                                      "speedup_four_lanes": ms_serial / ms_step,
-                                      "speedup_recorded_graphs": ms_serial / ms_graphs,
-                                      "images_per_s_serial": N_MB * MICRO_BATCH / ms_serial * 1e3,
-                                      "images_per_s_four_lanes": N_MB * MICRO_BATCH / ms_step * 1e3,
-                                      "images_per_s_recorded_graphs": N_MB * MICRO_BATCH / ms_graphs * 1e3}},
-        "per_kind": {"source": "serial pass, HIP-event regions of the library, batch 128",
+        "ms_per_step": ms_step, "macs": macs, "relu_elements": relu_el, "pool_comparisons": pool_cmp, "err": step["max_abs_err_logits"],
+        "pipeline": {"step_mode": step},
+        "per_kind": {"source": "serial pass of the step's mode, HIP-event regions of the library, batch 128",
                      "ms_beaver_calls": lin, "ms_gemm_kernels": gem, "ms_relu_calls": rel,
                      "ms_maxpool_and_gaps": ms_serial - lin - rel,
                      "beaver_macs_per_s": macs / (lin * 1e-3), "relu_elems_per_s": relu_el / (rel * 1e-3),
                      "beaver_call_frac_of_int8_peak": INT8_OPS_PER_SECURE_MAC * macs / (lin * 1e-3) / 1e12 / INT8_PEAK_TOPS,
                      "gemm_kernel_frac_of_int8_peak": INT8_OPS_PER_SECURE_MAC * macs / (gem * 1e-3) / 1e12 / INT8_PEAK_TOPS,
-                     "relu_frac_of_hbm_peak": RELU_BYTES_PER_ELEMENT * relu_el / (rel * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                     "relu_frac_of_hbm_peak": RELU_PUT_BYTES_PER_ELEMENT * relu_el / (rel * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "relu_bytes_per_element": RELU_PUT_BYTES_PER_ELEMENT,
+                     "note": "the four-lane pipeline hides MFMA-bound GEMM time behind the HBM-bound ReLU, pooling and recoding "
+                             "of other micro-batches: its floor is the larger of the two sums, here the HBM-bound one"},
     }
-    if not args.no_best_mode:
-        net = Net(seed, packed_relu=True, prepared=True, pool_first=True, exchange="put")
-        b_pipe = net.timed(net.step_pipelined, args.steps, 3)
-        err_b = check_network(net, torch)
-        b_serial = net.timed(net.step_serial, max(2, args.steps // 2), 2)
-        gs = net.graphs()
-        b_graphs = net.timed(lambda: [g.launch(ln) for g, ln in zip(gs, net.lanes)], args.steps, 3)
-        del gs
-        net.close(); del net
-        torch.cuda.empty_cache()
+    if not args.no_other_modes:
+        r = run_mode(seed, args, torch)
+        out["pipeline"]["copy_exchange_planes_in_call"] = {
+            "relu": "whole words (mpc_relu)", "exchange": "copy kernels on the wire queue", "planes": "recoded inside every call (mpc_conv2d with f_public)",
+            "network": "as written", **r}
+        r = run_mode(seed, args, torch, packed_relu=True, prepared=True, fold=True, pool_first=True, exchange="put")
         out["pipeline"]["best_mode"] = {
-            "relu": "sign-only packed chain (mpc_relu_msb), pooled layers as ReLU(maxpool(z))",
-            "exchange": "remote store", "planes": "prepared (input-independent operands recoded ahead of time)",
-            "serial_ms": b_serial, "four_lanes_ms": b_pipe, "four_lanes_recorded_graphs_ms": b_graphs,
-            "speedup_four_lanes": b_serial / b_pipe, "speedup_recorded_graphs": b_serial / b_graphs,
-            "images_per_s_four_lanes": N_MB * MICRO_BATCH / b_pipe * 1e3,
-            "images_per_s_recorded_graphs": N_MB * MICRO_BATCH / b_graphs * 1e3, "max_abs_err_logits": err_b}
+            "relu": "sign-only packed chain (mpc_relu_msb: the adder evaluated where bit 63 depends on it)",
+            "exchange": "remote store", "planes": "prepared and folded", "network": "pooled layers as ReLU(maxpool(z))", **r}
     return out
 
 
@@ -263,19 +273,30 @@ def per_config_table(args):
     for idx in range(len(synth.CONFIGS)):
         name, rows = bench_configs.bench_layers(idx, reps=10)
         macs = sum(bench_configs.layer_macs(L) for L in synth.CONFIGS[idx]().layers)
-        call = sum(r["call_ms"] for r in rows); kern = sum(r["kernel_ms"] for r in rows); prep = sum(r["prepared_call_ms"] for r in rows)
-        e = {"config": idx, "name": name, "secure_macs": macs, "ms_beaver_calls": call, "ms_beaver_calls_prepared_planes": prep,
-             "ms_gemm_kernels": kern, "secure_macs_per_s": macs / (call * 1e-3),
-             "call_frac_of_int8_peak": INT8_OPS_PER_SECURE_MAC * macs / (call * 1e-3) / 1e12 / INT8_PEAK_TOPS,
-             "prepared_call_frac_of_int8_peak": INT8_OPS_PER_SECURE_MAC * macs / (prep * 1e-3) / 1e12 / INT8_PEAK_TOPS,
-             "kernel_frac_of_int8_peak": INT8_OPS_PER_SECURE_MAC * macs / (kern * 1e-3) / 1e12 / INT8_PEAK_TOPS}
+        call = sum(r["call_ms"] for r in rows); kern = sum(r["kernel_ms"] for r in rows)
+        fold = sum(r["folded_call_ms"] for r in rows); fkern = sum(r["folded_kernel_ms"] for r in rows)
+        f = lambda ms: INT8_OPS_PER_SECURE_MAC * macs / (ms * 1e-3) / 1e12 / INT8_PEAK_TOPS
+        e = {"config": idx, "name": name, "secure_macs": macs,
+             "folded_prepared_calls": {"ms_beaver_calls": fold, "ms_gemm_kernels": fkern, "secure_macs_per_s": macs / (fold * 1e-3),
+                                       "call_frac_of_int8_peak": f(fold), "kernel_frac_of_int8_peak": f(fkern),
+                                       "executed_int8_ops_per_secure_mac": 216},
+             "plain_calls": {"ms_beaver_calls": call, "ms_gemm_kernels": kern, "secure_macs_per_s": macs / (call * 1e-3),
+                             "call_frac_of_int8_peak": f(call), "kernel_frac_of_int8_peak": f(kern),
+                             "executed_int8_ops_per_secure_mac": 288}}
         rl = [r for r in rows if "relu_ms" in r]
         if rl:
-            n = sum(r["relu_n"] for r in rl); t = sum(r["relu_ms"] for r in rl); tm = sum(r["msb_ms"] for r in rl)
-            e.update(relu_elements=n, ms_relu_calls=t, relu_elems_per_s=n / (t * 1e-3),
-                     relu_frac_of_hbm_peak=RELU_BYTES_PER_ELEMENT * n / (t * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     ms_relu_msb_calls=tm, relu_msb_elems_per_s=n / (tm * 1e-3),
-                     relu_msb_frac_of_hbm_peak=RELU_MSB_BYTES_PER_ELEMENT * n / (tm * 1e-3) / 1e9 / HBM_PEAK_GBS)
+            n = sum(r["relu_n"] for r in rl)
+            t = {k: sum(r[k] for r in rl) for k in ("relu_ms", "relu_put_ms", "msb_ms", "msb_put_ms")}
+            h = lambda bpe, ms: bpe * n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+            e["relu"] = {"elements": n,
+                         "whole_words_remote_store": {"ms": t["relu_put_ms"], "elems_per_s": n / (t["relu_put_ms"] * 1e-3),
+                                                      "frac_of_hbm_peak": h(RELU_PUT_BYTES_PER_ELEMENT, t["relu_put_ms"])},
+                         "whole_words_copy": {"ms": t["relu_ms"], "elems_per_s": n / (t["relu_ms"] * 1e-3),
+                                              "frac_of_hbm_peak": h(RELU_BYTES_PER_ELEMENT, t["relu_ms"])},
+                         "sign_only_remote_store": {"ms": t["msb_put_ms"], "elems_per_s": n / (t["msb_put_ms"] * 1e-3),
+                                                    "frac_of_hbm_peak": h(RELU_MSB_PUT_BYTES_PER_ELEMENT, t["msb_put_ms"])},
+                         "sign_only_copy": {"ms": t["msb_ms"], "elems_per_s": n / (t["msb_ms"] * 1e-3),
+                                            "frac_of_hbm_peak": h(RELU_MSB_BYTES_PER_ELEMENT, t["msb_ms"])}}
         if args.layers:
             e["layers"] = [{k: (round(v, 6) if isinstance(v, float) else v) for k, v in r.items()} for r in rows]
         table.append(e)
@@ -285,7 +306,12 @@ def per_config_table(args):
 def config1_leg(steps, warmup, pmc_summary):
     """configs[1] alone (VGG16-style conv block: Beaver conv [16384x1152]x[1152x128] + truncation, secure ReLU on its
     2 097 152 outputs): the step whose kernels the committed rocprofv3 summaries cover (`bench.py --only-config1`).
-    Returns the three roofline objects and the leg's times."""
+    Three sequences, each conv call followed by its ReLU as in a network (the chip is power-limited: a GEMM
+    that follows a memory-bound phase runs at a higher clock than one in a back-to-back series of GEMMs):
+      step mode   folded prepared conv call + whole-word ReLU with the remote-store exchange;
+      plain       mpc_conv2d (planes recoded in the call, four ring products) + ReLU with the copy exchange;
+      sign-only   the folded call + mpc_relu_msb.
+    Returns the roofline objects and the leg's times."""
     import torch
     from paper_2209_13643_amd import bench_configs, dealer, mpc, synth
 
@@ -299,15 +325,28 @@ def config1_leg(steps, warmup, pmc_summary):
     g = dealer.gen(synth.BASE_SEED + wl.index, dev)
     d = dealer.conv_layer(lane, g, L.B, L.H, L.W, L.Cin, L.Cout, L.KH, L.KW, L.pad, L.stride, L.x_std, L.w_std)
     mat = dealer.relu_material(g, n, dev)
+    mat_p = dealer.relu_material(g, n, dev, packed=True)
     z = tuple(torch.empty((L.B, L.Ho, L.Wo, L.Cout), dtype=torch.int64, device=dev) for _ in range(2))
+    zf = tuple(torch.empty_like(z[0]) for _ in range(2))
     y = tuple(torch.empty_like(z[0]) for _ in range(2))
-    torch.cuda.synchronize()
+    y2 = tuple(torch.empty_like(z[0]) for _ in range(2))
+    # offline: planes of the triple and of the opened weight mask, party 0's folded addend
+    right, left = lane.prepare_conv2d(d["a"], d["b"], d["f_public"], L.pad, L.stride)
+    cf = (lane.fold_conv2d(d["a"], d["b"], d["c"], L.pad, L.stride), d["c"][1])
+    lane.sync(); torch.cuda.synchronize()
 
-    def step():
-        lane.conv2d(d["x"], d["w"], d["a"], d["b"], d["c"], L.pad, L.stride, out=z)      # Alg. 1 / Eq. 3 + truncation
-        lane.relu(z, mat, out=y)                                                            # Alg. 2 + Sec. 4.2
+    def conv_folded():
+        lane.conv2d_prepared(d["x"], d["a"], cf, right, left, L.KH, L.KW, L.pad, L.stride, out=zf,
+                             flags=mpc.MPC_TRUNCATE | mpc.MPC_FOLDED)                    # Alg. 1 / Eq. 3 + truncation
 
-    def timed(fn):
+    def conv_prepared():
+        lane.conv2d_prepared(d["x"], d["a"], d["c"], right, left, L.KH, L.KW, L.pad, L.stride, out=zf)
+
+    def conv_plain():
+        lane.conv2d(d["x"], d["w"], d["a"], d["b"], d["c"], L.pad, L.stride, out=z)
+
+    def timed(fn, exchange):
+        lane.set_exchange(exchange)
         for _ in range(warmup):
             fn()
         lane.sync(); torch.cuda.synchronize()
@@ -318,39 +357,36 @@ def config1_leg(steps, warmup, pmc_summary):
         lane.sync(); torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) * 1e3 / steps
         lane.set_profiling(False)
-        reg = {}
+        reg = {"ms_step": ms}
         for key, which in (("gemm_kernel", mpc.PROF_GEMM_KERNEL), ("beaver_conv_call", mpc.PROF_LINEAR), ("relu_call", mpc.PROF_RELU)):
             smp = lane.profile_samples(which)
             if smp:
                 reg[key] = {"mean_ms": sum(smp) / len(smp), "median_ms": statistics.median(smp), "min_ms": min(smp),
                             "max_ms": max(smp), "n": len(smp)}
-        return ms, reg
+        return reg
 
-    ms_step, reg = timed(step)
-    gemm_ms, lin_ms, relu_ms = (reg[k]["mean_ms"] for k in ("gemm_kernel", "beaver_conv_call", "relu_call"))
-    # sanity on the result of the last step: ReLU of the reconstructed conv output, exactly
-    rec_z = (z[0] + z[1]); rec_y = (y[0] + y[1])
-    assert torch.equal(rec_y, torch.clamp(rec_z, min=0)), "secure ReLU output does not reconstruct to max(z, 0)"
+    seq = {
+        "step_mode": timed(lambda: (conv_folded(), lane.relu(zf, mat, out=y)), "put"),
+        "plain_call_copy_exchange": timed(lambda: (conv_plain(), lane.relu(z, mat, out=y2)), "copy"),
+        "prepared_call_unfolded": timed(lambda: (conv_prepared(), lane.relu(zf, mat, out=y2)), "put"),
+        "sign_only_relu": timed(lambda: (conv_folded(), lane.relu(zf, mat_p, out=y2, packed=True)), "put"),
+        "sign_only_relu_copy_exchange": timed(lambda: (conv_folded(), lane.relu(zf, mat_p, out=y2, packed=True)), "copy"),
+    }
+    # sanity on the results of the last steps: same shares from all three conv calls, ReLU of the reconstructed output exactly
+    assert torch.equal(z[0], zf[0]) and torch.equal(z[1], zf[1]), "folded / prepared convolution differs from the plain call"
+    rec_z = z[0] + z[1]
+    assert torch.equal(y[0] + y[1], torch.clamp(rec_z, min=0)), "secure ReLU output does not reconstruct to max(z, 0)"
+    assert torch.equal(y2[0] + y2[1], torch.clamp(rec_z, min=0)), "mpc_relu_msb output does not reconstruct to max(z, 0)"
     ref = torch.nn.functional.conv2d((d["X"].double() / 65536).permute(0, 3, 1, 2)[:2],
                                      (d["W"].double() / 65536).permute(3, 2, 0, 1), padding=L.pad).permute(0, 2, 3, 1)
     err = (rec_z[:2].double() / 65536 - ref).abs().max().item()
     assert err <= 2.0 ** -12, f"decoded conv output off by {err}"
-
-    # the sign-only packed chain on the same conv output, timed on its own
-    mat_p = dealer.relu_material(g, n, dev, packed=True)
-    y2 = tuple(torch.empty_like(z[0]) for _ in range(2))
-    _, r2 = timed(lambda: lane.relu(z, mat_p, out=y2, packed=True))
-    msb_ms = r2["relu_call"]["mean_ms"]; reg["relu_msb_call"] = r2["relu_call"]
-    assert torch.equal(y2[0] + y2[1], torch.clamp(rec_z, min=0)), "mpc_relu_msb output does not reconstruct to max(z, 0)"
-    # the Beaver convolution with the input-independent operands' digit planes recoded ahead of time
-    right, left = lane.prepare_conv2d(d["a"], d["b"], d["f_public"], L.pad, L.stride)
-    _, r3 = timed(lambda: lane.conv2d_prepared(d["x"], d["a"], d["c"], right, left, L.KH, L.KW, L.pad, L.stride, out=y2))
-    prep_ms = r3["beaver_conv_call"]["mean_ms"]; reg["beaver_conv_call_prepared_planes"] = r3["beaver_conv_call"]
-    assert torch.equal(y2[0], z[0]) and torch.equal(y2[1], z[1]), "prepared-plane convolution differs from the plain call"
     lane.close()
 
     macs = M * K * N
     tops = lambda ms: INT8_OPS_PER_SECURE_MAC * macs / (ms * 1e-3) / 1e12
+    lvl = lambda r: {"achieved": tops(r["mean_ms"]), "frac": tops(r["mean_ms"]) / INT8_PEAK_TOPS, "ms": r["mean_ms"]}
+    sm, pl, pu = seq["step_mode"], seq["plain_call_copy_exchange"], seq["prepared_call_unfolded"]
     pmc = read_pmc_summary(pmc_summary)
     traffic = relu_traffic = msb_traffic = None
     if pmc is not None:
@@ -359,44 +395,70 @@ def config1_leg(steps, warmup, pmc_summary):
                    "algorithmic_bytes": bench_configs.gemm_algorithmic_bytes(L), **src}
         if "relu_bytes_per_element" in pmc: relu_traffic = {"bytes_per_element": pmc["relu_bytes_per_element"], **src}
         if "relu_msb_bytes_per_element" in pmc: msb_traffic = {"bytes_per_element": pmc["relu_msb_bytes_per_element"], **src}
-    relu_gbs = RELU_BYTES_PER_ELEMENT * n / (relu_ms * 1e-3) / 1e9
-    msb_gbs = RELU_MSB_BYTES_PER_ELEMENT * n / (msb_ms * 1e-3) / 1e9
+    gbs = lambda bpe, ms: bpe * n / (ms * 1e-3) / 1e9
+    relu_ms, relu_copy_ms = sm["relu_call"]["mean_ms"], pl["relu_call"]["mean_ms"]
+    msb_ms, msb_copy_ms = seq["sign_only_relu"]["relu_call"]["mean_ms"], seq["sign_only_relu_copy_exchange"]["relu_call"]["mean_ms"]
+    call = lvl(sm["beaver_conv_call"])
     return {
         "times": {"workload": "configs[1] vgg16-cifar-conv-block: batch 64, 128x16x16, conv3x3 128->128 pad 1 = Beaver GEMM "
                               f"[{M}x{K}]x[{K}x{N}] + truncation + secure ReLU on {n} elements",
-                  "ms_step": ms_step, "ms_beaver_conv_call": lin_ms, "ms_gemm_kernel": gemm_ms, "ms_relu_call": relu_ms,
-                  "ms_relu_msb_call": msb_ms, "ms_beaver_conv_call_prepared_planes": prep_ms,
-                  "secure_macs_per_s": macs / (lin_ms * 1e-3), "secure_macs_per_s_prepared_planes": macs / (prep_ms * 1e-3),
-                  "relu_elems_per_s": n / (relu_ms * 1e-3), "relu_msb_elems_per_s": n / (msb_ms * 1e-3),
-                  "region_times": reg, "max_abs_err_vs_float64": err},
+                  "ms_step": sm["ms_step"], "ms_beaver_conv_call": sm["beaver_conv_call"]["mean_ms"],
+                  "ms_gemm_kernel": sm["gemm_kernel"]["mean_ms"], "ms_relu_call": relu_ms,
+                  "secure_macs_per_s": macs / (sm["beaver_conv_call"]["mean_ms"] * 1e-3), "relu_elems_per_s": n / (relu_ms * 1e-3),
+                  "plain_call_copy_exchange": {"ms_step": pl["ms_step"], "ms_beaver_conv_call": pl["beaver_conv_call"]["mean_ms"],
+                                               "ms_gemm_kernel": pl["gemm_kernel"]["mean_ms"], "ms_relu_call": relu_copy_ms,
+                                               "secure_macs_per_s": macs / (pl["beaver_conv_call"]["mean_ms"] * 1e-3),
+                                               "relu_elems_per_s": n / (relu_copy_ms * 1e-3)},
+                  "ms_relu_msb_call": msb_ms, "relu_msb_elems_per_s": n / (msb_ms * 1e-3),
+                  "ms_relu_msb_call_copy_exchange": msb_copy_ms,
+                  "region_times": seq, "max_abs_err_vs_float64": err},
         "roofline": {
-            "kernel": "secure GEMM: k_limb_gemm<2,2,true> (both parties, [e|a_i] x [b_i';f], fused add-c + truncation) inside the "
-                      "Beaver conv call (mask, exchange, digit recoding, GEMM)",
+            "kernel": "secure GEMM: k_limb_gemm<2,2,true> (party 0: [x_0 + e_1] x [b_0 + f]; party 1: [e | a_1] x [b_1 ; f]; fused "
+                      "addend + truncation) inside the folded prepared Beaver conv call (mask + remote-store exchange, digit recoding, GEMM)",
             "workload": f"configs[1] conv3x3 as [{M}x{K}]x[{K}x{N}]",
-            "bound": "mfma", "achieved": tops(lin_ms), "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": tops(lin_ms) / INT8_PEAK_TOPS,
-            "level": "call: 288 int8 ops per secure MAC over the whole Beaver conv call (HIP events around the call's launches)",
-            "kernel_only": {"achieved": tops(gemm_ms), "frac": tops(gemm_ms) / INT8_PEAK_TOPS, "ms": gemm_ms,
+            "bound": "mfma", "achieved": call["achieved"], "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": call["frac"],
+            "level": "call: 288 useful int8 ops per secure MAC (2 parties x 2 ring products x 36 digit products x 2, the frozen "
+                     "accounting) over the whole Beaver conv call, HIP events around the call's launches",
+            "executed_int8_ops_per_secure_mac": 216,
+            "frac_executed_ops": call["frac"] * 0.75,
+            "executed_note": "the folded call contracts three ring products online instead of four (party 0's a_0*b_0 moved to the "
+                             "offline phase): `frac` counts the useful 288 ops, `frac_executed_ops` the 216 the matrix cores execute",
+            "ms_call": call["ms"],
+            "kernel_only": {**lvl(sm["gemm_kernel"]), "frac_executed_ops": lvl(sm["gemm_kernel"])["frac"] * 0.75,
                             "level": "HIP events around the GEMM launch alone"},
-            "prepared_planes_call": {"achieved": tops(prep_ms), "frac": tops(prep_ms) / INT8_PEAK_TOPS, "ms": prep_ms},
-            "ms_call": lin_ms, "traffic": traffic,
+            "prepared_call_unfolded": {"call": lvl(pu["beaver_conv_call"]), "kernel_only": lvl(pu["gemm_kernel"]),
+                                       "note": "prepared planes, four ring products (executed = useful ops)"},
+            "plain_call": {"call": lvl(pl["beaver_conv_call"]), "kernel_only": lvl(pl["gemm_kernel"]),
+                           "note": "mpc_conv2d: every digit plane recoded inside the call, copy exchange, four ring products"},
+            "traffic": traffic,
             "note": "power-limited attainable rate with random int8 operands measured on this chip with a back-to-back "
                     "MFMA loop is about 3070 TOP/s"},
         "roofline_relu": {
-            "kernel": "secure ReLU chain: k_relu_stage<0..9> (both parties per launch) + k_wire_words / k_wire_bytes",
-            "workload": f"configs[1], {n} elements", "bound": "hbm", "achieved": relu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": relu_gbs / HBM_PEAK_GBS, "bytes_per_element": RELU_BYTES_PER_ELEMENT, "ms_call": relu_ms,
+            "kernel": "secure ReLU chain on whole words, exchange by remote store: k_relu_stage<0..9, put> (both parties per launch) "
+                      "+ k_wire_words<1> for the A2B masks",
+            "workload": f"configs[1], {n} elements", "bound": "hbm", "achieved": gbs(RELU_PUT_BYTES_PER_ELEMENT, relu_ms),
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs(RELU_PUT_BYTES_PER_ELEMENT, relu_ms) / HBM_PEAK_GBS,
+            "bytes_per_element": RELU_PUT_BYTES_PER_ELEMENT, "ms_call": relu_ms, "elems_per_s": n / (relu_ms * 1e-3),
+            "copy_exchange": {"kernel": "k_relu_stage<0..9> + k_wire_words / k_wire_bytes", "bytes_per_element": RELU_BYTES_PER_ELEMENT,
+                              "ms_call": relu_copy_ms, "elems_per_s": n / (relu_copy_ms * 1e-3),
+                              "achieved": gbs(RELU_BYTES_PER_ELEMENT, relu_copy_ms),
+                              "frac": gbs(RELU_BYTES_PER_ELEMENT, relu_copy_ms) / HBM_PEAK_GBS, "traffic": relu_traffic},
             "dram_compulsory": {"bytes_per_element": RELU_COMPULSORY_BYTES,
-                                "frac": RELU_COMPULSORY_BYTES * n / (relu_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                "frac": gbs(RELU_COMPULSORY_BYTES, relu_ms) / HBM_PEAK_GBS,
                                 "note": "inputs, outputs and offline material only: the exchanged words and the state carried from "
                                         "round to round are served by the 256 MB last-level cache when a chunk fits it"},
-            "traffic": relu_traffic},
+            "traffic": None},
         "roofline_relu_msb": {
-            "kernel": "sign-only packed ReLU chain: k_relu_msb_stage<0..9> + k_wire_words / k_wire_bytes",
-            "workload": f"configs[1], {n} elements", "bound": "hbm", "achieved": msb_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": msb_gbs / HBM_PEAK_GBS, "bytes_per_element": RELU_MSB_BYTES_PER_ELEMENT, "ms_call": msb_ms,
+            "kernel": "sign-only packed ReLU chain, exchange by remote store: k_relu_msb_stage<0..9, put>",
+            "workload": f"configs[1], {n} elements", "bound": "hbm", "achieved": gbs(RELU_MSB_PUT_BYTES_PER_ELEMENT, msb_ms),
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs(RELU_MSB_PUT_BYTES_PER_ELEMENT, msb_ms) / HBM_PEAK_GBS,
+            "bytes_per_element": RELU_MSB_PUT_BYTES_PER_ELEMENT, "ms_call": msb_ms, "elems_per_s": n / (msb_ms * 1e-3),
+            "copy_exchange": {"bytes_per_element": RELU_MSB_BYTES_PER_ELEMENT, "ms_call": msb_copy_ms,
+                              "elems_per_s": n / (msb_copy_ms * 1e-3), "achieved": gbs(RELU_MSB_BYTES_PER_ELEMENT, msb_copy_ms),
+                              "frac": gbs(RELU_MSB_BYTES_PER_ELEMENT, msb_copy_ms) / HBM_PEAK_GBS, "traffic": msb_traffic},
             "dram_compulsory": {"bytes_per_element": RELU_MSB_COMPULSORY_BYTES,
-                                "frac": RELU_MSB_COMPULSORY_BYTES * n / (msb_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
-            "traffic": msb_traffic},
+                                "frac": gbs(RELU_MSB_COMPULSORY_BYTES, msb_ms) / HBM_PEAK_GBS},
+            "traffic": None},
     }
 
 
@@ -588,7 +650,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-three-party", action="store_true", help="skip the three-party leg (configs[1], N = 3)")
     ap.add_argument("--no-per-config", action="store_true", help="skip the table of all five workloads (and the rooflines taken from it)")
-    ap.add_argument("--no-best-mode", action="store_true", help="skip the best-mode pipeline leg")
+    ap.add_argument("--no-other-modes", action="store_true", help="skip the pipeline legs beside the step's own mode")
     ap.add_argument("--layers", action="store_true", help="per-layer rows inside `configs`")
     ap.add_argument("--only-config1", action="store_true",
                     help="run only the configs[1] leg (conv block + ReLU) and print its rooflines: the command the rocprofv3 summaries are taken with")
@@ -629,6 +691,7 @@ def main():
                                "2x2 max-pooling, FC 512-512-10, batch 128 = 4 micro-batches of 32 on four lanes; per layer Beaver "
                                "conv / matmul + truncation, whole-word secure ReLU, max-pool by two conversions",
                    "parties": 2, "frac_bits": 16, "lanes": N_MB, "lane": "single in-order queue each", "relu_chunks": "auto (about 2^20 elements each)",
+                   "mode": legs["pipeline"]["step_mode"]["relu"] + "; exchange: " + legs["pipeline"]["step_mode"]["exchange"] + "; planes: " + legs["pipeline"]["step_mode"]["planes"],
                    "secure_macs_per_step": legs["macs"], "relu_elements_per_step": legs["relu_elements"],
                    "maxpool_comparisons_per_step": legs["pool_comparisons"], "images_per_s": N_MB * MICRO_BATCH / ms_step * 1e3,
                    "max_abs_err_logits_vs_plain_fixed_point": legs["err"]},

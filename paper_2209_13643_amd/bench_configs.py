@@ -20,6 +20,8 @@ INT8_PEAK = 5.0e15
 HBM_PEAK = 8.0e12
 RELU_BYTES = 3514
 RELU_MSB_BYTES = 1172.25      # the sign-only packed chain
+RELU_PUT_BYTES = 2 * (159 * 8 + 7)            # whole words, exchange by remote store (bench.py derives it)
+RELU_MSB_PUT_BYTES = RELU_MSB_BYTES - 71.25 * 8 / 4
 
 
 def layer_macs(L):
@@ -59,18 +61,24 @@ def bench_layers(idx: int, reps: int = 20, workload=None):
             n_out = L.M * L.N * max(L.batch, 1)
             z = (torch.empty_like(d["c"][0]), torch.empty_like(d["c"][1]))
             shape = f"{L.M}x{L.K}x{L.N}" + (f" x{L.batch}" if L.batch > 1 else "")
-        # the same call on prepared planes (input-independent operands recoded ahead of time)
+        # the same layer as a folded prepared call: input-independent operands recoded ahead of time, party 0's
+        # addend c_0 - a_0 b_0 formed offline (three ring products online instead of four)
         if isinstance(L, synth.Conv):
             right, left = lane.prepare_conv2d(d["a"], d["b"], d["f_public"], L.pad, L.stride)
-            run_prep = lambda: lane.conv2d_prepared(d["x"], d["a"], d["c"], right, left, L.KH, L.KW, L.pad, L.stride, out=z)
+            cf = (lane.fold_conv2d(d["a"], d["b"], d["c"], L.pad, L.stride), d["c"][1])
+            run_prep = lambda: lane.conv2d_prepared(d["x"], d["a"], cf, right, left, L.KH, L.KW, L.pad, L.stride, out=z,
+                                                    flags=mpc.MPC_TRUNCATE | mpc.MPC_FOLDED)
         else:
             right, left = lane.prepare_matmul(d["a"], d["b"], d["f_public"])
-            run_prep = lambda: lane.beaver_matmul_prepared(d["x"], d["a"], d["c"], right, left, out=z)
+            cf = (lane.fold_matmul(d["a"], d["b"], d["c"]), d["c"][1])
+            run_prep = lambda: lane.beaver_matmul_prepared(d["x"], d["a"], cf, right, left, out=z,
+                                                           flags=mpc.MPC_TRUNCATE | mpc.MPC_FOLDED)
         mat = dealer.relu_material(g, n_out, dev) if L.relu else None
         y = (torch.empty_like(z[0]), torch.empty_like(z[1])) if L.relu else None
         # both variants are timed in the same sequence (linear call, then the layer's ReLU): the chip is
         # power-limited, and a GEMM that follows a memory-bound phase runs at a higher clock than one in a
         # back-to-back series of GEMMs
+        lane.set_exchange("put")
         for _ in range(5):
             run_prep()
             if mat: lane.relu(z, mat, out=y)
@@ -79,9 +87,13 @@ def bench_layers(idx: int, reps: int = 20, workload=None):
             run_prep()
             if mat: lane.relu(z, mat, out=y)
         lane.sync(); lane.set_profiling(False)
-        prep_ms, prep_n = lane.profile(mpc.PROF_LINEAR)
-        prep_ms /= prep_n
-        del right, left
+        prep_ms, prep_n = lane.profile(mpc.PROF_LINEAR); fk, fkn = lane.profile(mpc.PROF_GEMM_KERNEL)
+        prep_ms /= prep_n; fk /= fkn
+        put_ms = None
+        if mat:
+            rl, rn = lane.profile(mpc.PROF_RELU); put_ms = rl / rn
+        del right, left, cf
+        lane.set_exchange("copy")
         for _ in range(5):
             run()
             if mat: lane.relu(z, mat, out=y)
@@ -92,26 +104,34 @@ def bench_layers(idx: int, reps: int = 20, workload=None):
         lane.sync(); lane.set_profiling(False)
         gk, gn = lane.profile(mpc.PROF_GEMM_KERNEL); lin, ln = lane.profile(mpc.PROF_LINEAR)
         macs = layer_macs(L)
-        row = dict(layer=L.name, gemm=shape, repeat=L.repeat, call_ms=lin / ln, prepared_call_ms=prep_ms, kernel_ms=gk / gn,
+        row = dict(layer=L.name, gemm=shape, repeat=L.repeat, call_ms=lin / ln, kernel_ms=gk / gn,
                    kernel_min_ms=min(lane.profile_samples(mpc.PROF_GEMM_KERNEL)),
-                   secure_macs_per_s=macs / (lin / ln * 1e-3), mfma_frac=288 * macs / (gk / gn * 1e-3) / INT8_PEAK,
+                   folded_call_ms=prep_ms, folded_kernel_ms=fk,
+                   secure_macs_per_s=macs / (lin / ln * 1e-3), folded_secure_macs_per_s=macs / (prep_ms * 1e-3),
+                   mfma_frac=288 * macs / (gk / gn * 1e-3) / INT8_PEAK, folded_mfma_frac=288 * macs / (fk * 1e-3) / INT8_PEAK,
                    gemm_hbm_frac=gemm_algorithmic_bytes(L) / (gk / gn * 1e-3) / HBM_PEAK)
         if mat:
             rl, rn = lane.profile(mpc.PROF_RELU)
             row.update(relu_n=n_out, relu_ms=rl / rn, relu_elems_per_s=n_out / (rl / rn * 1e-3),
-                       hbm_frac=RELU_BYTES * n_out / (rl / rn * 1e-3) / HBM_PEAK)
+                       hbm_frac=RELU_BYTES * n_out / (rl / rn * 1e-3) / HBM_PEAK,
+                       relu_put_ms=put_ms, relu_put_elems_per_s=n_out / (put_ms * 1e-3),
+                       put_hbm_frac=RELU_PUT_BYTES * n_out / (put_ms * 1e-3) / HBM_PEAK)
             # the same ReLU on the sign's carry chain only, packed material
             del mat
             mat = dealer.relu_material(g, n_out, dev, packed=True)
-            for _ in range(5):
-                lane.relu(z, mat, out=y, packed=True)
-            lane.sync(); lane.set_profiling(True); lane.profile_reset()
-            for _ in range(reps):
-                lane.relu(z, mat, out=y, packed=True)
-            lane.sync(); lane.set_profiling(False)
-            rl, rn = lane.profile(mpc.PROF_RELU)
-            row.update(msb_ms=rl / rn, msb_elems_per_s=n_out / (rl / rn * 1e-3),
-                       msb_hbm_frac=RELU_MSB_BYTES * n_out / (rl / rn * 1e-3) / HBM_PEAK)
+            for ex, key in (("copy", "msb"), ("put", "msb_put")):
+                lane.set_exchange(ex)
+                for _ in range(5):
+                    lane.relu(z, mat, out=y, packed=True)
+                lane.sync(); lane.set_profiling(True); lane.profile_reset()
+                for _ in range(reps):
+                    lane.relu(z, mat, out=y, packed=True)
+                lane.sync(); lane.set_profiling(False)
+                rl, rn = lane.profile(mpc.PROF_RELU)
+                bpe = RELU_MSB_BYTES if ex == "copy" else RELU_MSB_PUT_BYTES
+                row.update({f"{key}_ms": rl / rn, f"{key}_elems_per_s": n_out / (rl / rn * 1e-3),
+                            f"{key}_hbm_frac": bpe * n_out / (rl / rn * 1e-3) / HBM_PEAK})
+            lane.set_exchange("copy")
         rows.append(row)
         del d, mat, z, y
         torch.cuda.empty_cache()
@@ -306,7 +326,7 @@ def bench_graph(reps: int = 50, pool_first: bool = False, exchange: str = "copy"
     wl = synth.config_vgg16_pipeline(32)
     weights = pipeline.deal_weights(g, wl.layers, dev)
     states = pipeline.deal_microbatch(lane, g, wl.layers, weights, packed_relu=True, pool_first=pool_first)
-    pipeline.prepare_layers(lane, wl.layers, states)
+    pipeline.prepare_layers(lane, wl.layers, states, fold=True)
     x = dealer.share(g, dealer.normal_fixed(g, (32, 32, 32, 3), 1.0, dev))
     torch.cuda.synchronize()
     keep = []
@@ -328,7 +348,7 @@ def bench_graph(reps: int = 50, pool_first: bool = False, exchange: str = "copy"
     for ln in lanes[1:]:
         ln.use_single_queue(); ln.set_exchange(exchange)
         st = pipeline.deal_microbatch(ln, g, wl.layers, weights, packed_relu=True, pool_first=pool_first)
-        pipeline.prepare_layers(ln, wl.layers, st)
+        pipeline.prepare_layers(ln, wl.layers, st, fold=True)
         xm = dealer.share(g, dealer.normal_fixed(g, (32, 32, 32, 3), 1.0, dev))
         torch.cuda.synchronize()
         warm = []; pipeline.forward(ln, wl.layers, st, xm, warm); ln.sync(); del warm
@@ -373,7 +393,7 @@ def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_r
         torch.cuda.synchronize()
         pipeline.preopen_weights(lanes[m], states[m])
         if prepared:
-            pipeline.prepare_layers(lanes[m], layers, states[m])
+            pipeline.prepare_layers(lanes[m], layers, states[m], fold=True)
     res = {}
     for mode in ("serial", "pipelined"):
         best = None
@@ -675,14 +695,14 @@ def main(argv):
             tot_lin = tot_relu = tot_msb = tot_prep = 0.0
             for r in rows:
                 line = (f"  {r['layer']:16s} x{r['repeat']:<2d} {r['gemm']:22s} call {r['call_ms']:8.3f} ms "
-                        f"{r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s  prepared {r['prepared_call_ms']:7.3f} ms  mfma {100 * r['mfma_frac']:5.1f}%")
-                tot_lin += r['call_ms'] * r['repeat']; tot_prep += r['prepared_call_ms'] * r['repeat']
+                        f"{r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s  folded {r['folded_call_ms']:7.3f} ms  mfma {100 * r['mfma_frac']:5.1f}%")
+                tot_lin += r['call_ms'] * r['repeat']; tot_prep += r['folded_call_ms'] * r['repeat']
                 if "relu_ms" in r:
                     line += (f"  | relu {r['relu_n']:9d} el {r['relu_ms']:7.3f} ms hbm {100 * r['hbm_frac']:5.1f}%"
                              f"  | sign-only {r['msb_ms']:7.3f} ms hbm {100 * r['msb_hbm_frac']:5.1f}%")
                     tot_relu += r['relu_ms'] * r['repeat']; tot_msb += r['msb_ms'] * r['repeat']
                 print(line, flush=True)
-            print(f"  sum over layers (x multiplicity): linear {tot_lin:.2f} ms ({tot_prep:.2f} ms on prepared planes), ReLU {tot_relu:.2f} ms whole-word / "
+            print(f"  sum over layers (x multiplicity): linear {tot_lin:.2f} ms ({tot_prep:.2f} ms as folded prepared calls), ReLU {tot_relu:.2f} ms whole-word / "
                   f"{tot_msb:.2f} ms sign-only", flush=True)
         return
     if argv and argv[0] == "graph":
@@ -719,21 +739,25 @@ def main(argv):
             # both roofs of the GEMM kernel; '*' marks the one that binds (the larger fraction)
             mf, hf = 100 * r['mfma_frac'], 100 * r['gemm_hbm_frac']
             line = (f"  {r['layer']:10s} {r['gemm']:22s} call {r['call_ms']:8.3f} ms  {r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s"
-                    f"  prepared {r['prepared_call_ms']:7.3f} ms"
-                    f"  kernel {r['kernel_ms']:8.3f} ms (min {r['kernel_min_ms']:.3f})  mfma {mf:5.1f}%{'*' if mf >= hf else ' '} hbm {hf:5.1f}%{'*' if hf > mf else ' '}")
-            tot['lin'] += r['call_ms']; tot['prep'] = tot.get('prep', 0.0) + r['prepared_call_ms']
+                    f"  kernel {r['kernel_ms']:7.3f} ms  mfma {mf:5.1f}%{'*' if mf >= hf else ' '} hbm {hf:5.1f}%{'*' if hf > mf else ' '}"
+                    f"  | folded call {r['folded_call_ms']:7.3f} ms {r['folded_secure_macs_per_s'] / 1e12:6.2f} T MAC/s kernel {r['folded_kernel_ms']:7.3f} ms {100 * r['folded_mfma_frac']:5.1f}%")
+            tot['lin'] += r['call_ms']; tot['prep'] = tot.get('prep', 0.0) + r['folded_call_ms']
             if "relu_ms" in r:
                 tot['relu'] += r['relu_ms']; tot['msb'] += r['msb_ms']
-                line += f"  | relu {r['relu_n']:9d} el {r['relu_ms']:7.3f} ms {r['relu_elems_per_s'] / 1e9:5.2f} G/s hbm {100 * r['hbm_frac']:5.1f}%"
-                line += f"  | sign-only {r['msb_ms']:7.3f} ms {r['msb_elems_per_s'] / 1e9:5.2f} G/s hbm {100 * r['msb_hbm_frac']:5.1f}%"
+                tot['put'] = tot.get('put', 0.0) + r['relu_put_ms']; tot['msb_put'] = tot.get('msb_put', 0.0) + r['msb_put_ms']
+                line += (f"  | relu {r['relu_n']:9d} el copy {r['relu_ms']:7.3f} ms {r['relu_elems_per_s'] / 1e9:5.2f} G/s {100 * r['hbm_frac']:5.1f}%"
+                         f" put {r['relu_put_ms']:7.3f} ms {r['relu_put_elems_per_s'] / 1e9:5.2f} G/s {100 * r['put_hbm_frac']:5.1f}%")
+                line += (f"  | sign-only copy {r['msb_ms']:7.3f} ms {r['msb_elems_per_s'] / 1e9:5.2f} G/s {100 * r['msb_hbm_frac']:5.1f}%"
+                         f" put {r['msb_put_ms']:7.3f} ms {r['msb_put_elems_per_s'] / 1e9:5.2f} G/s {100 * r['msb_put_hbm_frac']:5.1f}%")
             print(line, flush=True)
-        print(f"  totals: linear calls {tot['lin']:.3f} ms ({tot['prep']:.3f} ms on prepared planes), ReLU {tot['relu']:.3f} ms whole-word / {tot['msb']:.3f} ms sign-only", flush=True)
+        print(f"  totals: linear calls {tot['lin']:.3f} ms ({tot['prep']:.3f} ms as folded prepared calls), ReLU whole-word {tot['relu']:.3f} ms copy / "
+              f"{tot.get('put', 0.0):.3f} ms put, sign-only {tot['msb']:.3f} ms copy / {tot.get('msb_put', 0.0):.3f} ms put", flush=True)
         if idx == 4:
             for packed, prepared, pool_first, ex in ((False, False, False, "copy"), (True, False, False, "copy"), (True, True, False, "copy"),
                                                      (True, True, True, "copy"), (True, True, True, "put")):
                 p = bench_pipeline(packed_relu=packed, prepared=prepared, pool_first=pool_first, exchange=ex)
                 print(f"  inter-batch pipeline, batch 128 = 4 x 32, {'sign-only packed' if packed else 'whole-word'} ReLU"
-                      f"{', prepared planes' if prepared else ''}{', pooled layers as ReLU(maxpool(z))' if pool_first else ''}"
+                      f"{', folded prepared planes' if prepared else ''}{', pooled layers as ReLU(maxpool(z))' if pool_first else ''}"
                       f"{', exchange by remote store' if ex == 'put' else ''}: "
                       f"serial {p['serial']['ms']:.2f} ms ({p['serial']['images_per_s']:.0f} img/s), "
                       f"pipelined {p['pipelined']['ms']:.2f} ms ({p['pipelined']['images_per_s']:.0f} img/s)", flush=True)

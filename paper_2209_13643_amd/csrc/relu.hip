@@ -213,15 +213,17 @@ __device__ __forceinline__ void b_level(const ReluParty& p, size_t lo, size_t hi
         Pack<V> d1, g1;
 #pragma unroll
         for (int k = 0; k < V; ++k) { d1.v[k] = op_x<TOPO, LEVEL>(P.v[k]) ^ na1.v[k]; g1.v[k] = op_y<TOPO, LEVEL>(G.v[k]) ^ nb1.v[k]; }
-        d1.st(p.send, i); g1.st(p.send + n, i);
+        // The next stage recomputes this party's own masked words from the carried (G, P), so with the
+        // exchange by remote store they go to the peer only; the copy exchange needs them in the send buffer.
         if constexpr (PUT) { d1.st(p.put, i); g1.st(p.put + n, i); }
+        else               { d1.st(p.send, i); g1.st(p.send + n, i); }
         if constexpr (LEVEL < 5) {
             const Pack<V> na2 = Pack<V>::ld(p.ta + u2 * n, i), nb2 = Pack<V>::ld(p.tb + u2 * n, i);
             Pack<V> d2, g2;
 #pragma unroll
             for (int k = 0; k < V; ++k) { d2.v[k] = op_x<TOPO, LEVEL>(P.v[k]) ^ na2.v[k]; g2.v[k] = op_y<TOPO, LEVEL>(P.v[k]) ^ nb2.v[k]; }
-            d2.st(p.send + 2 * n, i); g2.st(p.send + 3 * n, i);
             if constexpr (PUT) { d2.st(p.put + 2 * n, i); g2.st(p.put + 3 * n, i); }
+            else               { d2.st(p.send + 2 * n, i); g2.st(p.send + 3 * n, i); }
         }
         G.st(p.G, i); P.st(p.P, i);
     }
