@@ -277,6 +277,67 @@ def test_config4_vgg16_pipeline_full(mods, packed_relu):
         ln.close()
 
 
+def test_config4_four_lanes_device_dealt_every_micro_batch_against_oracle(mods):
+    """The benchmark's step as it is launched (batch 128 = 4 micro-batches of 32 on four lanes, folded prepared
+    calls, remote-store exchange, outputs allocated ahead of the pass) on material dealt on the device: every
+    micro-batch's shares, triples and ReLU / pool material are downloaded, the oracle runs the whole network on
+    them, and every layer's output shares of all four micro-batches are compared word for word.  The device
+    dealer forms C = A * B with the library's own ring product: for the first and the last convolution and the
+    last dense layer the oracle recomputes C from the downloaded A and B."""
+    from helpers import oracle_forward
+    mpc, dealer, pipeline = mods
+    wl = synth.config_vgg16_pipeline(32)
+    layers = wl.layers
+    n_mb = 4
+    print("config 4, four lanes, device-dealt: dealing", flush=True)
+    lanes = [mpc.Lane(0) for _ in range(n_mb)]
+    for ln in lanes:
+        ln.use_single_queue(); ln.set_exchange("put")
+    g = dealer.gen(synth.BASE_SEED + wl.index + 500, lanes[0].device)
+    weights = pipeline.deal_weights(g, layers, lanes[0].device)
+    states, xs, outs = [], [], []
+    for m in range(n_mb):
+        st = pipeline.deal_microbatch(lanes[m], g, layers, weights)
+        xs.append(dealer.share(g, dealer.normal_fixed(g, (32, 32, 32, 3), 1.0, lanes[0].device)))
+        torch.cuda.synchronize()
+        pipeline.prepare_layers(lanes[m], layers, st, fold=True)
+        states.append(st); outs.append(pipeline.alloc_outputs(lanes[m], layers, st))
+    for _ in range(2):                        # the second pass overwrites the first one's outputs in place
+        pipeline.forward_pipelined(lanes, layers, states, xs, [], outs_per_mb=outs)
+    for ln in lanes:
+        ln.sync()
+    h = lambda t: mpc.to_host(t)
+    pair = lambda p: (h(p[0]), h(p[1]))
+
+    def host_material(mat):
+        if mat is None:
+            return None
+        n = mat["r"][0].numel()
+        out = {k: pair(mat[k]) for k in ("r", "rb", "ra", "ma", "mb", "mc")}
+        for k in ("and_a", "and_b", "and_c"):
+            out[k] = tuple(h(mat[k][i].view(12, n)) for i in range(2))
+        return out
+
+    last_conv = max(i for i, L in enumerate(layers) if isinstance(L, synth.Conv))
+    for m in range(n_mb):
+        print(f"micro-batch {m}: download, oracle forward, compare", flush=True)
+        host = []
+        for li, (L, st) in enumerate(zip(layers, states[m])):
+            host.append(dict(w=pair(st.w), a=pair(st.a), b=pair(st.b), c=pair(st.c), relu=host_material(st.relu),
+                             pool1=host_material(st.pool1), pool2=host_material(st.pool2), pool_first=False))
+            if li in (0, last_conv, len(layers) - 1):
+                A, Bm = host[-1]["a"][0] + host[-1]["a"][1], host[-1]["b"][0] + host[-1]["b"][1]
+                C = oracle.ring_conv2d(A, Bm, L.pad, L.stride) if isinstance(L, synth.Conv) else oracle.ring_matmul(A, Bm)
+                assert np.array_equal(host[-1]["c"][0] + host[-1]["c"][1], C), f"micro-batch {m}, {L.name}: dealt C != A * B"
+        want = oracle_forward(layers, host, pair(xs[m]))
+        for li, (L, o) in enumerate(zip(layers, outs[m])):
+            got = o["p"] if "p" in o else o["y"] if "y" in o else o["z"]
+            assert_equal_shares(mpc, got, want[li], f"micro-batch {m}, layer {li} ({L.name})")
+        del host, want
+    for ln in lanes:
+        ln.close()
+
+
 def test_config4_one_micro_batch_every_share_against_oracle(mods, lane):
     """One micro-batch of config 4 at its full size (32 images) with inputs, triples and material
     dealt on the host: every layer's output shares, both parties, against the oracle word for word;
