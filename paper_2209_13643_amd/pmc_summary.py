@@ -29,6 +29,10 @@ def sources_digest() -> str:
     return h.hexdigest()[:16]
 
 
+def clean(name):
+    return name.replace("(anonymous namespace)::", "").replace("void ", "").split("(")[0]
+
+
 def dispatches(path, counter):
     """[(dispatch id, kernel, grid, KiB)] in dispatch order; library kernels of torch are left out."""
     rows = []
@@ -39,8 +43,7 @@ def dispatches(path, counter):
             name = r["Kernel_Name"]
             if "at::native" in name or name.startswith("Cijk") or "rocclr" in name:
                 continue
-            name = name.split("(")[0].replace("void ", "").replace("(anonymous namespace)::", "")
-            rows.append((int(r["Dispatch_Id"]), name, int(r["Grid_Size"]), float(r["Counter_Value"])))
+            rows.append((int(r["Dispatch_Id"]), clean(name), int(r["Grid_Size"]), float(r["Counter_Value"])))
     rows.sort()
     return rows
 
@@ -53,21 +56,44 @@ def per_kernel(rows):
     return collections.OrderedDict((k, sum(v) / len(v)) for k, v in groups.items())
 
 
-def relu_call_kib(rows, n, auto_chunk=1 << 20):
-    """KiB per secure-ReLU call, whole-word chain and sign-only chain: every stage and wire dispatch of the chain's
-    leg summed, divided by the number of calls (dispatches of the chain's last stage / chunks per call).  The legs
-    run one after the other, so a wire copy belongs to the chain whose stage kernels surround it."""
-    chunks = max(1, (n + auto_chunk // 2) // auto_chunk)
-    first_msb = next((i for i, r in enumerate(rows) if "k_relu_msb_stage" in r[1]), len(rows))
-    if first_msb < len(rows) and first_msb > 0 and "k_wire" in rows[first_msb - 1][1]:
-        first_msb -= 1                                   # the A2B mask copy that opens the first sign-only call
-    out = {}
-    for chain, lo, hi, stage in (("relu", 0, first_msb, "k_relu_stage<9"), ("relu_msb", first_msb, len(rows), "k_relu_msb_stage<9")):
-        part = [r for r in rows[lo:hi] if "k_relu" in r[1] or "k_wire" in r[1]]
-        calls = sum(1 for r in part if r[1].startswith(stage)) / chunks
-        if calls > 0:
-            out[chain] = sum(r[3] for r in part) / calls
-    return out
+def is_relu(name):
+    return name.startswith(("k_relu_stage", "k_relu_msb_stage", "k_wire_words", "k_wire_bytes"))
+
+
+def relu_calls(rows):
+    """KiB per secure-ReLU call by chain and exchange: a call is a maximal run of stage and wire dispatches (the
+    conv call's kernels separate the runs; the chunks of a call follow each other), the chain shows in the stage
+    kernels' name, the exchange in their last template argument."""
+    out = collections.defaultdict(list)
+    run = []
+    for r in list(rows) + [(0, "end", 0, 0.0)]:
+        if is_relu(r[1]):
+            run.append(r)
+            continue
+        if run:
+            stages = [q[1] for q in run if "stage<" in q[1]]
+            if stages:
+                chain = "sign-only" if any("msb" in q for q in stages) else "whole words"
+                put = any(q.rstrip(">").endswith("true") for q in stages)
+                out[(chain, "remote store" if put else "copy")].append(sum(q[3] for q in run))
+            run = []
+    return {k: sum(v) / len(v) for k, v in out.items()}
+
+
+def gemm_calls(rows):
+    """KiB per two-party GEMM launch by the form of the Beaver call, read off the recoding launch before it:
+    plain call (six plane sets recoded), prepared call (e only), folded prepared call (x_0 + e_1 and e)."""
+    biggest = max((r[2] for r in rows if r[1].startswith("k_limb_gemm")), default=0)
+    by_grid = collections.defaultdict(list)
+    last_recode = None
+    for r in rows:
+        if r[1].startswith("k_recode_mixed"):
+            last_recode = r[2]
+        elif r[1].startswith("k_limb_gemm") and r[2] == biggest and last_recode is not None:
+            by_grid[last_recode].append(r[3])
+    grids = sorted(by_grid)            # recoding grids grow with the number of plane sets
+    names = ["prepared call (four products)", "folded prepared call (three products)", "plain call (four products)"]
+    return {names[i]: sum(by_grid[g]) / len(by_grid[g]) for i, g in enumerate(grids[:3])} if len(grids) == 3 else {}
 
 
 def main(argv):
@@ -82,7 +108,7 @@ def main(argv):
     if not ck:
         print("no k_copy_multi dispatch in the counter file: cannot calibrate", file=sys.stderr)
         return 1
-    ck = max(ck, key=lambda k: fetch[k])                 # the Beaver conv's exchange (the largest copy)
+    ck = max(ck, key=lambda k: fetch[k])                 # the plain Beaver conv's exchange (the largest copy)
     fscale, wscale = copy_kib / fetch[ck], copy_kib / write[ck]
     print("# HBM traffic counters: configs[1] leg of bench.py\n")
     print(f"sources sha256/16: {sources_digest()}\n")
@@ -90,20 +116,26 @@ def main(argv):
     print("    rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/pmc_fetch -o f -- python3 bench.py --only-config1 --steps 3 --warmup 1")
     print("    rocprofv3 --pmc WRITE_SIZE --output-format csv -d gpurun_out/pmc_write -o w -- python3 bench.py --only-config1 --steps 3 --warmup 1")
     print("    python3 -m paper_2209_13643_amd.pmc_summary <f_counter_collection.csv> <w_counter_collection.csv>\n")
-    print(f"Calibration on the plain copy kernel {ck[0]} (the wire copy of the masked operands: {copy_kib:.0f} KiB in, the same out, "
-          f"per launch): FETCH_SIZE reads {fetch[ck]:.1f} KiB -> scale x{fscale:.3f}; WRITE_SIZE reads {write[ck]:.1f} KiB -> scale x{wscale:.3f}.\n")
-    print("Per launch, after scaling (MiB):\n")
+    print(f"Calibration on the plain copy kernel {ck[0]} (the wire copy of the plain call's masked operands: {copy_kib:.0f} KiB in, the same "
+          f"out, per launch): FETCH_SIZE reads {fetch[ck]:.1f} KiB -> scale x{fscale:.3f}; WRITE_SIZE reads {write[ck]:.1f} KiB -> scale x{wscale:.3f}.\n")
+    print("Per launch, after scaling (MiB; mean over the launches of that kernel and grid in the run):\n")
     print("| kernel | grid | fetch MiB | write MiB |\n|---|---:|---:|---:|")
     for k in fetch:
         print(f"| {k[0]} | {k[1]} | {fetch[k] * fscale / 1024:.1f} | {write.get(k, 0.0) * wscale / 1024:.1f} |")
+    gf, gw = gemm_calls(frows), gemm_calls(wrows)
+    if gf:
+        print("\nThe two-party GEMM launch by the form of the Beaver call (MiB per launch):\n")
+        print("| call | fetch MiB | write MiB |\n|---|---:|---:|")
+        for name in gf:
+            print(f"| k_limb_gemm in the {name} | {gf[name] * fscale / 1024:.1f} | {gw.get(name, 0.0) * wscale / 1024:.1f} |")
     n = L.B * L.Ho * L.Wo * L.Cout
-    fr, wr = relu_call_kib(frows, n), relu_call_kib(wrows, n)
+    fr, wr = relu_calls(frows), relu_calls(wrows)
     print()
-    for chain, label in (("relu", "Secure ReLU on whole words (mpc_relu)"), ("relu_msb", "Sign-only packed chain (mpc_relu_msb)")):
-        if chain in fr and chain in wr:
-            fb, wb = fr[chain] * fscale * 1024, wr[chain] * wscale * 1024
-            print(f"{label}, all kernels of one call (both parties + wire), {n} elements: fetch {fb / 1e6:.0f} MB + write {wb / 1e6:.0f} MB "
-                  f"= {(fb + wb) / n:.0f} bytes per element.\n")
+    for key in sorted(fr):
+        if key in wr:
+            fb, wb = fr[key] * fscale * 1024, wr[key] * wscale * 1024
+            print(f"Secure ReLU, {key[0]}, exchange by {key[1]}, all kernels of one call (both parties + wire), {n} elements: "
+                  f"fetch {fb / 1e6:.0f} MB + write {wb / 1e6:.0f} MB = {(fb + wb) / n:.0f} bytes per element.\n")
     return 0
 
 
