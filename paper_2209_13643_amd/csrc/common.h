@@ -152,6 +152,8 @@ struct RecodeArgs {
     const u64* src;       // element (row r, k) at src[r*row_stride + k*k_stride (+ tap*tap_stride)]
     const u64* src2;      // optional addends with the same indexing (nullptr: none)
     const u64* src3;
+    const u64* sub;       // optional: subtracted from src first (v = src - sub), same indexing
+    u64* side;            // optional: v is also stored here, same indexing (a mask kernel's output, formed on the way)
     u8* dst;              // plane base
     long long row_stride, k_stride, tap_stride;
     int plane_rows;       // rows of the plane tensor (>= rows); rows beyond `rows` are zero-filled

@@ -91,6 +91,8 @@ __device__ __forceinline__ void recode_body(const RecodeArgs& a, int tap /* == n
     const u64* src = a.src + (size_t)b * a.src_batch_stride;
     const u64* src2 = a.src2 ? a.src2 + (size_t)b * a.src_batch_stride : nullptr;
     const u64* src3 = a.src3 ? a.src3 + (size_t)b * a.src_batch_stride : nullptr;
+    const u64* sub = a.sub ? a.sub + (size_t)b * a.src_batch_stride : nullptr;
+    u64* side = a.side ? a.side + (size_t)b * a.src_batch_stride : nullptr;
     u8* dst = a.dst + (size_t)b * a.dst_batch_stride;
     const bool padtap = tap >= a.ntaps;
     const int kb_count = padtap ? a.KB_total - a.ntaps * a.KB_tap : a.KB_tap;
@@ -109,6 +111,7 @@ __device__ __forceinline__ void recode_body(const RecodeArgs& a, int tap /* == n
                 // tap_stride may be negative (filters read in reverse tap order)
                 const long long idx = (long long)row * a.row_stride + (long long)k * a.k_stride + (long long)tap * a.tap_stride;
                 v = src[idx];
+                if (sub) { v -= sub[idx]; if (side) side[idx] = v; }
                 if (src2) v += src2[idx];
                 if (src3) v += src3[idx];
             }
@@ -148,9 +151,12 @@ __device__ __forceinline__ void recode_rows_body(const RecodeArgs& a, int b, uns
     const u64* src = a.src + (size_t)b * a.src_batch_stride;
     const u64* src2 = a.src2 ? a.src2 + (size_t)b * a.src_batch_stride : nullptr;
     const u64* src3 = a.src3 ? a.src3 + (size_t)b * a.src_batch_stride : nullptr;
+    const u64* sub = a.sub ? a.sub + (size_t)b * a.src_batch_stride : nullptr;
+    u64* side = a.side ? a.side + (size_t)b * a.src_batch_stride : nullptr;
     u8* dst = a.dst + (size_t)b * a.dst_batch_stride;
     const bool vec_ok = (a.row_stride % 2 == 0) && (((uintptr_t)src & 15) == 0) &&
-                        (!src2 || ((uintptr_t)src2 & 15) == 0) && (!src3 || ((uintptr_t)src3 & 15) == 0);
+                        (!src2 || ((uintptr_t)src2 & 15) == 0) && (!src3 || ((uintptr_t)src3 & 15) == 0) &&
+                        (!sub || ((uintptr_t)sub & 15) == 0) && (!side || ((uintptr_t)side & 15) == 0);
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const int seg = threadIdx.x + 256 * p;
@@ -162,6 +168,14 @@ __device__ __forceinline__ void recode_rows_body(const RecodeArgs& a, int b, uns
             if (vec_ok && k + 3 < a.K) {
                 const u64x2 p0 = *reinterpret_cast<const u64x2*>(src + idx), p1 = *reinterpret_cast<const u64x2*>(src + idx + 2);
                 v[0] = p0.a; v[1] = p0.b; v[2] = p1.a; v[3] = p1.b;
+                if (sub) {
+                    const u64x2 q0 = *reinterpret_cast<const u64x2*>(sub + idx), q1 = *reinterpret_cast<const u64x2*>(sub + idx + 2);
+                    v[0] -= q0.a; v[1] -= q0.b; v[2] -= q1.a; v[3] -= q1.b;
+                    if (side) {
+                        u64x2 s0, s1; s0.a = v[0]; s0.b = v[1]; s1.a = v[2]; s1.b = v[3];
+                        *reinterpret_cast<u64x2*>(side + idx) = s0; *reinterpret_cast<u64x2*>(side + idx + 2) = s1;
+                    }
+                }
                 if (src2) { const u64x2 q0 = *reinterpret_cast<const u64x2*>(src2 + idx), q1 = *reinterpret_cast<const u64x2*>(src2 + idx + 2);
                             v[0] += q0.a; v[1] += q0.b; v[2] += q1.a; v[3] += q1.b; }
                 if (src3) { const u64x2 q0 = *reinterpret_cast<const u64x2*>(src3 + idx), q1 = *reinterpret_cast<const u64x2*>(src3 + idx + 2);
@@ -171,6 +185,7 @@ __device__ __forceinline__ void recode_rows_body(const RecodeArgs& a, int b, uns
                 for (int t = 0; t < 4; ++t)
                     if (k + t < a.K) {
                         v[t] = src[idx + t];
+                        if (sub) { v[t] -= sub[idx + t]; if (side) side[idx + t] = v[t]; }
                         if (src2) v[t] += src2[idx + t];
                         if (src3) v[t] += src3[idx + t];
                     }

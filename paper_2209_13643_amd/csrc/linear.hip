@@ -258,6 +258,28 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         GemmArgs g{};
         fill_geom(s, w, g);
         g.nparty = 2;
+        if (folded && c->exchange_put && !s.im2colT) {
+            // Folded call with the exchange by remote store: three passes over the activation, each word touched once.
+            //   party 0 masks and sends:           e_0 = x_0 - a_0                  -> party 1's receive buffer
+            //   party 1 masks, sends and recodes:  e_1 = x_1 - a_1 -> party 0's receive buffer; planes of e = e_1 + e_0
+            //   party 0 recodes:                   planes of a_0 + e = x_0 + e_1
+            // (party 1's word leaves after party 0's has arrived: on a network the two directions of this exchange
+            // would follow each other; with the copy exchange they stay simultaneous.)
+            SubSeg sub0{ x.p[0], a.p[0], w.re[1], s.nx, 0, nullptr };
+            MPC_TRY(launch_sub_multi(c, P0, &sub0, 1));
+            RecodeArgs r1 = recode_left(s, x.p[1], w.re[1], w.pl_e);
+            r1.sub = a.p[1]; r1.side = w.re[0];
+            MPC_TRY(launch_recode(c, P0, r1));
+            MPC_TRY(launch_recode(c, P0, recode_left(s, x.p[0], w.re[0], w.pl_a[0])));
+            g.nseg = 2;
+            g.seg[0][0] = make_seg(s, w.pl_a[0], w.pr_b[0]); g.seg[0][1] = GemmSeg{};
+            g.seg[1][0] = make_seg(s, w.pl_e, w.pr_b[1]);    g.seg[1][1] = make_seg(s, w.pl_a[1], w.pr_f);
+            for (int i = 0; i < 2; ++i) { g.addend[i] = cc.p[i]; g.addend2[i] = nullptr; g.out[i] = z.p[i]; }
+            g.trunc_bits = trunc;
+            MPC_TRY(launch_limb_gemm(c, P0, g));
+            prof_end(c, MPC_PROF_LINEAR, pi, P0);
+            return MPC_OK;
+        }
         if ((size_t)n_chunks > s.nx) n_chunks = (int)s.nx;
         bool f_pending = !have_f;                            // the weight mask rides with the first launch issued
         for (int ch = 0; ch < n_chunks; ++ch) {
