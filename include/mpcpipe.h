@@ -220,6 +220,14 @@ int mpc_conv2d(mpc_ctx* ctx, mpc_cshare x, mpc_cshare w,
                int pad, int stride,
                const uint64_t* f_public, int n_chunks, int flags);
 
+/* Tuning of the ring GEMM's tile choice, process-wide; results never depend on it.  A launch whose longest
+ * contraction has at most max_steps K steps (32 terms each; default 16) and whose output has at least min_tiles
+ * tiles of 64 x 64 (default 512) runs with 64 x 64 workgroup tiles of four half-width waves, two workgroups per
+ * compute unit: short contractions spend most of a workgroup's life in pipeline fill and epilogue, which a second
+ * resident wave per SIMD hides.  max_steps = 0 switches the small tile off.  MPC_EINVAL for max_steps < 0 or
+ * min_tiles < 1. */
+int mpc_set_gemm_small_tile(int max_steps, int min_tiles);
+
 /* Prepared layers.  The GEMM consumes digit planes; those of the operands that
  * do not depend on the input - the triple's [a_i] on the left, and on the right
  * the opened weight mask f = w - b (Alg. 3 sends it ahead of time), b_0 + f and

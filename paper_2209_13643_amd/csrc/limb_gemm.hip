@@ -39,11 +39,15 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int KS = 2;   // 16-wide k blocks per pipeline stage = one MFMA K step
-constexpr int NS = 3;   // LDS ring depth
+// LDS ring depth: three slots for the one-workgroup-per-unit tiles; two for the small tile of short
+// contractions, which then fits twice on a compute unit
 
-template <int WGM, int WGN>
+// NH: 32-column halves of a wave's output tile (2: 32 x 64, all 256 accumulator registers, one wave per SIMD;
+// 1: 32 x 32, 128 accumulator registers, two waves per SIMD).
+template <int WGM, int WGN, int NS, int NH>
 struct Cfg {
-    static constexpr int TM = 32 * WGM, TN = 64 * WGN, NW = WGM * WGN, NT = 64 * NW;
+    static constexpr int WN = 32 * NH;
+    static constexpr int TM = 32 * WGM, TN = WN * WGN, NW = WGM * WGN, NT = 64 * NW;
     static constexpr int L_UNITS = 8 * KS * TM, R_UNITS = 8 * KS * TN;   // 16-byte units per stage
     static constexpr int STAGE_UNITS = L_UNITS + R_UNITS;
     static constexpr size_t LDS_BYTES = (size_t)NS * STAGE_UNITS * 16;
@@ -54,7 +58,7 @@ struct Cfg {
     static constexpr int RCM = TM / 64, RCN = TN / 64;
     static constexpr int DPW = 8 / NW;
     static constexpr int LPW = DPW * KS * RCM, RPW = DPW * KS * RCN;     // loads per wave per stage
-    static_assert(TM % 64 == 0, "left tile is a whole number of 64-row chunks");
+    static_assert(TM % 64 == 0 && TN % 64 == 0, "tiles are whole numbers of 64-row chunks");
     static_assert(8 % NW == 0, "digits divide evenly over waves");
 };
 
@@ -82,11 +86,11 @@ __device__ __forceinline__ void load_lds16(const u8* base, unsigned voff, unsign
                  :: "s"(lds_slot), "n"(LDS_OFF), "v"(voff), "s"(base) : "memory", "scc");
 }
 
-template <int WGM, int WGN, bool CONV>
-__global__ __launch_bounds__(64 * WGM * WGN, 1)
+template <int WGM, int WGN, bool CONV, int NS, int NH>
+__global__ __launch_bounds__(64 * WGM * WGN, NH == 1 ? 2 : 1)
 void k_limb_gemm(GemmArgs g)
 {
-    using C = Cfg<WGM, WGN>;
+    using C = Cfg<WGM, WGN, NS, NH>;
     extern __shared__ uint4 lds[];
     const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
 
@@ -264,23 +268,23 @@ void k_limb_gemm(GemmArgs g)
         static_for<PER_STAGE>([&](auto q) { issue_one(q); });
     };
 
-    v16i acc[2][8];
+    v16i acc[NH][8];
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int c = 0; c < NH; ++c)
 #pragma unroll
         for (int s = 0; s < 8; ++s)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[c][s][v] = 0;
 
-    v4i A[8], B[2][8];
+    v4i A[8], B[NH][8];
     auto read_A = [&](int slot, int d) {
         const uint4 a = lds[(size_t)slot * C::STAGE_UNITS + (d * KS + g2) * C::TM + wm * 32 + i32];
         A[d] = v4i{ (int)a.x, (int)a.y, (int)a.z, (int)a.w };
     };
     auto read_B = [&](int slot, int d) {
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const uint4 b = lds[(size_t)slot * C::STAGE_UNITS + C::L_UNITS + (d * KS + g2) * C::TN + wn * 64 + c * 32 + i32];
+        for (int c = 0; c < NH; ++c) {
+            const uint4 b = lds[(size_t)slot * C::STAGE_UNITS + C::L_UNITS + (d * KS + g2) * C::TN + wn * C::WN + c * 32 + i32];
             B[c][d] = v4i{ (int)b.x, (int)b.y, (int)b.z, (int)b.w };
         }
     };
@@ -301,11 +305,11 @@ void k_limb_gemm(GemmArgs g)
     const int shift = partial ? 0 : g.trunc_bits;
     const u64 neg = (party != 0 && shift != 0) ? ~(u64)0 : 0;       // two's-complement negation as (z ^ neg) - neg
     const bool interior = m0 + C::TM <= g.M && n0 + C::TN <= g.N;   // uniform: no per-word bounds checks
-    u64 addw[2][16];
+    u64 addw[NH][16];
     auto load_addend = [&]() {
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const int col = n0 + wn * 64 + c * 32 + i32;
+        for (int c = 0; c < NH; ++c) {
+            const int col = n0 + wn * C::WN + c * 32 + i32;
             const int colc = col < g.N ? col : g.N - 1;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -329,10 +333,13 @@ void k_limb_gemm(GemmArgs g)
     // has to sit in the seven free issue slots an 8-pass MFMA leaves behind.
     issue_all(0);
     if (1 < T) issue_all(1);
-    if (2 < T) issue_all(2);
-    if (T > 2)      __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * PER_STAGE));
-    else if (T > 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(1 * PER_STAGE));
-    else            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    if (NS > 2 && 2 < T) issue_all(2);
+    // slot 0 must have landed: everything but the stages issued after it
+    static_assert(NS == 2 || NS == 3, "ring depth");
+    static_assert((NS - 1) * PER_STAGE <= 63, "vmcnt is a six-bit counter");
+    if (NS > 2 && T > 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * PER_STAGE));
+    else if (T > 1)      __builtin_amdgcn_s_waitcnt(vmcnt_imm(1 * PER_STAGE));
+    else                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
 #pragma unroll
     for (int d = 0; d < 8; ++d) { read_A(0, d); read_B(0, d); }
@@ -342,8 +349,9 @@ void k_limb_gemm(GemmArgs g)
     auto step = [&](auto full_tag, int t) {
         constexpr bool FULL = decltype(full_tag)::value;
         const bool have_next = FULL || t + 1 < T, fill = FULL || t + NS < T;
-        if (FULL || t + 2 < T) __builtin_amdgcn_s_waitcnt(vmcnt_imm(PER_STAGE));
-        else if (have_next)    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        // slot t+1 must have landed; with three slots the loads of step t+2 may still be in flight
+        if (NS > 2 && (FULL || t + 2 < T)) __builtin_amdgcn_s_waitcnt(vmcnt_imm(PER_STAGE));
+        else if (have_next)               __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
         __syncthreads();
         const int nslot = slot + 1 == NS ? 0 : slot + 1;
         if (fill) stage_begin(slot);
@@ -352,10 +360,10 @@ void k_limb_gemm(GemmArgs g)
             constexpr int j = decltype(jt)::value;
             static_for<8 - j>([&](auto it) {
                 constexpr int i = 7 - j - decltype(it)::value;
-                static_for<2>([&](auto ct) {
+                static_for<NH>([&](auto ct) {
                     constexpr int c = decltype(ct)::value;
-                    // MFMAs before this block: sum_{j'<j} 2*(8-j') = j*(17-j)
-                    constexpr int n = j * (17 - j) + 2 * (7 - j - i) + c;
+                    // MFMAs before this block: sum_{j'<j} NH*(8-j') = NH*j*(17-j)/2
+                    constexpr int n = NH * (j * (17 - j) / 2 + (7 - j - i)) + c;
                     acc[c][i + j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[i], B[c][j], acc[c][i + j], 0, 0, 0);
                     if constexpr (n % 4 == 1 && n / 4 < PER_STAGE) {
                         if (fill) issue_one(std::integral_constant<int, n / 4>{});
@@ -380,9 +388,9 @@ void k_limb_gemm(GemmArgs g)
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
     // ---- epilogue: recombine, add, truncate, store.
-    static_for<2>([&](auto ct) {
+    static_for<NH>([&](auto ct) {
         constexpr int c = decltype(ct)::value;
-        const int col = n0 + wn * 64 + c * 32 + i32;
+        const int col = n0 + wn * C::WN + c * 32 + i32;
         u64 (&add)[16] = addw[c];
         if (addend2) {                  // partial sums of a two-phase call: loaded here, all 16 at once
             const int colc = col < g.N ? col : g.N - 1;
@@ -449,13 +457,13 @@ __global__ __launch_bounds__(256) void k_splitk_finish(GemmArgs g)
     }
 }
 
-template <int WGM, int WGN, bool CONV>
+template <int WGM, int WGN, bool CONV, int NS = 3, int NH = 2>
 int launch_cfg(mpc_ctx* c, hipStream_t st, const GemmArgs& g)
 {
-    using C = Cfg<WGM, WGN>;
+    using C = Cfg<WGM, WGN, NS, NH>;
     // once per device and kernel: allow the large dynamic LDS allocation (lanes may live on several host threads)
     static std::atomic<bool> attr_set[16];
-    auto kern = k_limb_gemm<WGM, WGN, CONV>;
+    auto kern = k_limb_gemm<WGM, WGN, CONV, NS, NH>;
     if (c->device < 0 || c->device >= 16) return MPC_EINVAL;
     if (!attr_set[c->device].load(std::memory_order_acquire)) {
         MPC_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -495,15 +503,29 @@ int launch_cfg(mpc_ctx* c, hipStream_t st, const GemmArgs& g)
 // matter beyond their low 32 bits hold at most four pairs, so 4 * 2^14 * k < 2^31.
 constexpr int kMaxStepsExact = 1023;
 
+// Output tile of a workgroup: 0 = 64 x 128 (2 x 2 waves), 1 = 128 x 64 (4 x 1 waves) when a second 64-column half
+// would be empty, 2 = 64 x 64 (2 x 2 waves of 32 x 32 with half the accumulator registers, two-slot ring: two
+// workgroups per compute unit, two waves per SIMD) for short contractions, where a workgroup's life is mostly
+// pipeline fill and epilogue and a second resident wave hides them.
+// Tile 2 is chosen when the longest contraction of the launch has at most g_small_max_steps K steps (32 terms each)
+// and the output has at least g_small_min_tiles tiles of 64 x 64 (mpc_set_gemm_small_tile changes both).
+static std::atomic<int> g_small_max_steps{ 16 }, g_small_min_tiles{ 512 };
+static int tile_kind(int M, int N, int batch, int longest_steps)
+{
+    if (longest_steps <= g_small_max_steps.load(std::memory_order_relaxed) &&
+        (long long)((M + 63) / 64) * ((N + 63) / 64) * batch >= g_small_min_tiles.load(std::memory_order_relaxed)) return 2;
+    return (((N - 1) % 128) < 64 && (N <= 64 || M >= 4096)) ? 1 : 0;
+}
+
 // steps[p]: K steps party p contracts (steps[1] = 0 for a one-party launch).  Returns the number of slices
 // of the longer contraction; a party with fewer steps gets ceil(its steps / slice length) slices.
 static int ksplit_for(int M, int N, int batch, const int steps[2])
 {
-    const bool narrow = ((N - 1) % 128) < 64 && (N <= 64 || M >= 4096);
-    const long long tiles_pp = (long long)((M + (narrow ? 127 : 63)) / (narrow ? 128 : 64)) *
-                               ((N + (narrow ? 63 : 127)) / (narrow ? 64 : 128)) * batch;      // per party
     const int nparty = steps[1] > 0 ? 2 : 1;
     const int longest = steps[0] > steps[1] ? steps[0] : steps[1];
+    const int kind = tile_kind(M, N, batch, longest);
+    const int tm = kind == 1 ? 128 : 64, tn = kind == 0 ? 128 : 64;
+    const long long tiles_pp = (long long)((M + tm - 1) / tm) * ((N + tn - 1) / tn) * batch;      // per party
     // the int32 digit sums of one workgroup stay exact for at most kMaxStepsExact steps
     const int s_exact = (longest + kMaxStepsExact - 1) / kMaxStepsExact;
     int s = s_exact;
@@ -539,15 +561,25 @@ int gemm_ksplit2(int M, int N, int batch, int steps0, int steps1)
     return ksplit_for(M, N, batch, steps);
 }
 
+extern "C" int mpc_set_gemm_small_tile(int max_steps, int min_tiles)
+{
+    if (max_steps < 0 || min_tiles < 1) return MPC_EINVAL;
+    g_small_max_steps.store(max_steps, std::memory_order_relaxed);
+    g_small_min_tiles.store(min_tiles, std::memory_order_relaxed);
+    return MPC_OK;
+}
+
 int launch_limb_gemm(mpc_ctx* c, hipStream_t st, const GemmArgs& g_in)
 {
     GemmArgs g = g_in;
     if (g.nparty < 1 || g.nparty > 2 || g.nseg < 1 || g.nseg > 2) return MPC_EINVAL;
+    int longest_steps = 0;
     {
         int steps[2] = { 0, 0 };
         for (int p = 0; p < g.nparty; ++p)
             for (int s = 0; s < g.nseg; ++s) steps[p] += g.seg[p][s].KB / KS;
         const int longest = steps[0] > steps[1] ? steps[0] : steps[1];
+        longest_steps = longest;
         if (g.ksplit < 1 || !g.partial) g.ksplit = 1;
         g.steps_per_split = (longest + g.ksplit - 1) / g.ksplit;
         if (g.steps_per_split < 1 || g.steps_per_split > kMaxStepsExact) return MPC_ERANGE;
@@ -567,7 +599,8 @@ int launch_limb_gemm(mpc_ctx* c, hipStream_t st, const GemmArgs& g_in)
     // per-lane byte offsets inside one k block of a plane are 32-bit
     if ((long long)g.rows_L * 16 >= (1ll << 32) || (long long)g.N * 16 >= (1ll << 32)) return MPC_EINVAL;
     // 64x128 workgroup tiles, or 128x64 when a second 64-column half would be empty
-    const bool narrow = ((g.N - 1) % 128) < 64 && (g.N <= 64 || g.M >= 4096);
-    if (g.conv.enabled) return narrow ? launch_cfg<4, 1, true>(c, st, g) : launch_cfg<2, 2, true>(c, st, g);
-    return narrow ? launch_cfg<4, 1, false>(c, st, g) : launch_cfg<2, 2, false>(c, st, g);
+    const int kind = g.ksplit > 1 ? tile_kind(g.M, g.N, g.batch, 1 << 30) : tile_kind(g.M, g.N, g.batch, longest_steps);
+    if (g.conv.enabled)
+        return kind == 2 ? launch_cfg<2, 2, true, 2, 1>(c, st, g) : kind == 1 ? launch_cfg<4, 1, true>(c, st, g) : launch_cfg<2, 2, true>(c, st, g);
+    return kind == 2 ? launch_cfg<2, 2, false, 2, 1>(c, st, g) : kind == 1 ? launch_cfg<4, 1, false>(c, st, g) : launch_cfg<2, 2, false>(c, st, g);
 }

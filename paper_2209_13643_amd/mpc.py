@@ -63,7 +63,7 @@ EXPORTS = [
     "mpc_maxpool2x2_signs", "mpc_maxpool_backward_workspace_bytes", "mpc_maxpool2x2_backward",
     "mpc_ctx_set_adder", "mpc_ctx_set_exchange", "mpc_ctx_profile_samples", "mpc_add",
     "mpc_matmul_prepared_bytes", "mpc_conv2d_prepared_bytes", "mpc_matmul_prepare", "mpc_conv2d_prepare",
-    "mpc_beaver_matmul_prepared", "mpc_conv2d_prepared", "mpc_matmul_fold", "mpc_conv2d_fold",
+    "mpc_beaver_matmul_prepared", "mpc_conv2d_prepared", "mpc_matmul_fold", "mpc_conv2d_fold", "mpc_set_gemm_small_tile",
     "mpc_ctx_capture_begin", "mpc_ctx_capture_end", "mpc_graph_launch", "mpc_graph_destroy",
     "mpc_open3", "mpc_matmul3_workspace_bytes", "mpc_beaver_matmul3", "mpc_conv2d3_workspace_bytes", "mpc_conv2d3",
     "mpc_truncate3_workspace_bytes", "mpc_truncate3", "mpc_relu3_workspace_bytes", "mpc_relu3",
@@ -102,6 +102,7 @@ def lib():
     L.mpc_conv2d_prepare.argtypes = [c_void_p, CShare, CShare, _P64, c_void_p, c_void_p] + [c_int] * 9
     L.mpc_beaver_matmul_prepared.argtypes = [c_void_p, CShare, CShare, CShare, CShare, c_void_p, c_void_p] + [c_int] * 6
     L.mpc_conv2d_prepared.argtypes = [c_void_p, CShare, CShare, CShare, CShare, c_void_p, c_void_p] + [c_int] * 11
+    L.mpc_set_gemm_small_tile.argtypes = [c_int, c_int]
     L.mpc_matmul_fold.argtypes = [c_void_p, _P64, _P64, _P64, _P64] + [c_int] * 5
     L.mpc_conv2d_fold.argtypes = [c_void_p, _P64, _P64, _P64, _P64] + [c_int] * 9
     L.mpc_ctx_profile_samples.argtypes = [c_void_p, c_int, POINTER(ctypes.c_double), c_int, POINTER(c_int)]
@@ -321,6 +322,13 @@ class _Capture:
             self.lane._check(rc)
             self.graph = Graph(h, [self.lane._ws])
         return False
+
+
+def set_gemm_small_tile(max_steps: int = 16, min_tiles: int = 512):
+    """Process-wide tuning of the GEMM's tile choice (mpc_set_gemm_small_tile); the defaults restore the library's."""
+    rc = lib().mpc_set_gemm_small_tile(max_steps, min_tiles)
+    if rc != 0:
+        raise MpcError(f"mpcpipe error {rc}: {lib().mpc_strerror(rc).decode()}")
 
 
 class Lane:

@@ -430,6 +430,55 @@ def test_conv2d_folded(mpc, lane, case):
                              flags=mpc.MPC_TRUNCATE | mpc.MPC_FOLDED | mpc.MPC_TWO_PHASE)
 
 
+@pytest.fixture()
+def small_tile_everywhere(mpc):
+    """Every unsliced GEMM launch on 64 x 64 workgroup tiles of half-width waves, whatever its size."""
+    mpc.set_gemm_small_tile(1 << 20, 1)
+    yield
+    mpc.set_gemm_small_tile()
+
+
+@pytest.mark.parametrize("shape", RING_SHAPES + [(640, 96, 700)])
+def test_ring_matmul_on_small_tiles(mpc, lane, small_tile_everywhere, shape):
+    M, K, N = shape
+    print(f"ring_matmul, small tiles {shape}", flush=True)
+    rng = np.random.default_rng(M * 11 + K)
+    L, R = synth.rand_words(rng, (M, K)), synth.rand_words(rng, (K, N))
+    Z = lane.ring_matmul(mpc.to_device(L), mpc.to_device(R))
+    lane.sync()
+    assert np.array_equal(mpc.to_host(Z), oracle.ring_matmul(L, R))
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv2d_plain_and_folded_on_small_tiles(mpc, lane, small_tile_everywhere, case):
+    B, H, W, Cin, Cout, KH, KW, pad, stride = case
+    print(f"conv, small tiles {case}", flush=True)
+    d = deal_conv(np.random.default_rng(sum(case) + 5), B, H, W, Cin, Cout, KH, KW, pad, stride)
+    x, y, a, b, c = (dev(mpc, d[k]) for k in ("x", "y", "a", "b", "c"))
+    z = lane.conv2d(x, y, a, b, c, pad, stride)
+    assert_shares_equal(host(mpc, lane, z), oracle_conv(d), "conv on small tiles")
+    f_public = mpc.to_device((d["y"][0] - d["b"][0]) + (d["y"][1] - d["b"][1]))
+    right, lp = lane.prepare_conv2d(a, b, f_public, pad, stride)
+    c0f = lane.fold_conv2d(a, b, c, pad, stride)
+    z = lane.conv2d_prepared(x, a, (c0f, c[1]), right, lp, KH, KW, pad, stride, flags=mpc.MPC_TRUNCATE | mpc.MPC_FOLDED)
+    assert_shares_equal(host(mpc, lane, z), oracle_conv(d), "folded conv on small tiles")
+
+
+def test_beaver_matmul_batched_and_extreme_digits_on_small_tiles(mpc, lane, small_tile_everywhere):
+    print("batched matmul and extreme digits, small tiles", flush=True)
+    d = deal_matmul(np.random.default_rng(79), 48, 64, 40, batch=6)
+    z = lane.beaver_matmul(dev(mpc, d["x"]), dev(mpc, d["y"]), dev(mpc, d["a"]), dev(mpc, d["b"]), dev(mpc, d["c"]))
+    assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "batched on small tiles")
+    M, K, N = 200, 4608, 200                 # 200 tiles: enough workgroups that the contraction stays unsliced
+    pats = np.array([0x8080808080808080, 0x7F7F7F7F7F7F7F7F], dtype=U64)
+    rng = np.random.default_rng(8)
+    L = pats[rng.integers(0, 2, size=(M, K))]; R = pats[rng.integers(0, 2, size=(K, N))]
+    L[::3] = pats[0]; R[:, ::2] = pats[0]
+    Z = lane.ring_matmul(mpc.to_device(L), mpc.to_device(R))
+    lane.sync()
+    assert np.array_equal(mpc.to_host(Z), oracle.ring_matmul(L, R))
+
+
 def test_graph_capture_replays(mpc):
     """A secure layer (Beaver matmul + ReLU) recorded once and replayed on fresh inputs in the same
     buffers, with eager work and synchronisation between the replays: every replay equals the oracle."""
