@@ -87,13 +87,16 @@ def read_pmc_summary(path):
     except OSError:
         return None
     m = re.search(r"sources sha256/16: ([0-9a-f]{16})", text)
-    rows = re.findall(r"k_limb_gemm[^|\n]*\|\s*(\d+)\s*\|\s*([0-9.]+)\s*\|\s*([0-9.]+)\s*\|", text)
-    if not m or not rows or m.group(1) != sources_digest():
+    forms = dict((k, (float(f), float(w))) for k, f, w in
+                 re.findall(r"k_limb_gemm in the ([a-z ]+call) \([a-z ]+\)\s*\|\s*([0-9.]+)\s*\|\s*([0-9.]+)\s*\|", text))
+    if not m or "folded prepared call" not in forms or m.group(1) != sources_digest():
         return None
-    grid, fetch, write = max(rows, key=lambda r: int(r[0]))       # the two-party launch of the Beaver call
-    out = {"fetch_bytes": float(fetch) * 2 ** 20, "write_bytes": float(write) * 2 ** 20,
+    out = {"fetch_bytes": forms["folded prepared call"][0] * 2 ** 20, "write_bytes": forms["folded prepared call"][1] * 2 ** 20,
            "source": os.path.relpath(path, ROOT), "measured_in_this_run": False}
-    for key, label in (("relu_bytes_per_element", "Secure ReLU on whole words"), ("relu_msb_bytes_per_element", "Sign-only packed chain")):
+    if "plain call" in forms:
+        out["four_product_launch"] = {"fetch_bytes": forms["plain call"][0] * 2 ** 20, "write_bytes": forms["plain call"][1] * 2 ** 20}
+    for key, label in (("relu_bytes_per_element", "whole words, exchange by copy"), ("relu_put_bytes_per_element", "whole words, exchange by remote store"),
+                       ("relu_msb_bytes_per_element", "sign-only, exchange by copy"), ("relu_msb_put_bytes_per_element", "sign-only, exchange by remote store")):
         r = re.search(re.escape(label) + r"[^\n]*= (\d+) bytes per element", text)
         if r:
             out[key] = int(r.group(1))
@@ -394,13 +397,19 @@ def config1_leg(steps, warmup, pmc_summary):
     lvl = lambda r: {"achieved": tops(r["mean_ms"]), "frac": tops(r["mean_ms"]) / INT8_PEAK_TOPS, "ms": r["mean_ms"]}
     sm, pl, pu = seq["step_mode"], seq["plain_call_copy_exchange"], seq["prepared_call_unfolded"]
     pmc = read_pmc_summary(pmc_summary)
-    traffic = relu_traffic = msb_traffic = None
+    traffic = traffic4 = None
+    rt = {}
     if pmc is not None:
         src = {"source": pmc["source"], "measured_in_this_run": False}
-        traffic = {"fetch_bytes": pmc["fetch_bytes"], "write_bytes": pmc["write_bytes"],
-                   "algorithmic_bytes": bench_configs.gemm_algorithmic_bytes(L), **src}
-        if "relu_bytes_per_element" in pmc: relu_traffic = {"bytes_per_element": pmc["relu_bytes_per_element"], **src}
-        if "relu_msb_bytes_per_element" in pmc: msb_traffic = {"bytes_per_element": pmc["relu_msb_bytes_per_element"], **src}
+        # algorithmic bytes of the folded launch: party 0 reads one left and one right plane set instead of two each
+        alg4 = bench_configs.gemm_algorithmic_bytes(L)
+        act, wts = L.B * L.H * L.W * L.Cin, L.KH * L.KW * L.Cin * L.Cout
+        traffic = {"fetch_bytes": pmc["fetch_bytes"], "write_bytes": pmc["write_bytes"], "algorithmic_bytes": alg4 - 8 * (act + wts), **src}
+        if "four_product_launch" in pmc:
+            traffic4 = {**pmc["four_product_launch"], "algorithmic_bytes": alg4, **src}
+        for key in ("relu_bytes_per_element", "relu_put_bytes_per_element", "relu_msb_bytes_per_element", "relu_msb_put_bytes_per_element"):
+            if key in pmc:
+                rt[key] = {"bytes_per_element": pmc[key], **src}
     gbs = lambda bpe, ms: bpe * n / (ms * 1e-3) / 1e9
     relu_ms, relu_copy_ms = sm["relu_call"]["mean_ms"], pl["relu_call"]["mean_ms"]
     msb_ms, msb_copy_ms = seq["sign_only_relu"]["relu_call"]["mean_ms"], seq["sign_only_relu_copy_exchange"]["relu_call"]["mean_ms"]
@@ -435,7 +444,8 @@ def config1_leg(steps, warmup, pmc_summary):
             "prepared_call_unfolded": {"call": lvl(pu["beaver_conv_call"]), "kernel_only": lvl(pu["gemm_kernel"]),
                                        "note": "prepared planes, four ring products (executed = useful ops)"},
             "plain_call": {"call": lvl(pl["beaver_conv_call"]), "kernel_only": lvl(pl["gemm_kernel"]),
-                           "note": "mpc_conv2d: every digit plane recoded inside the call, copy exchange, four ring products"},
+                           "note": "mpc_conv2d: every digit plane recoded inside the call, copy exchange, four ring products",
+                           "traffic": traffic4},
             "traffic": traffic,
             "note": "power-limited attainable rate with random int8 operands measured on this chip with a back-to-back "
                     "MFMA loop is about 3070 TOP/s"},
@@ -448,12 +458,12 @@ def config1_leg(steps, warmup, pmc_summary):
             "copy_exchange": {"kernel": "k_relu_stage<0..9> + k_wire_words / k_wire_bytes", "bytes_per_element": RELU_BYTES_PER_ELEMENT,
                               "ms_call": relu_copy_ms, "elems_per_s": n / (relu_copy_ms * 1e-3),
                               "achieved": gbs(RELU_BYTES_PER_ELEMENT, relu_copy_ms),
-                              "frac": gbs(RELU_BYTES_PER_ELEMENT, relu_copy_ms) / HBM_PEAK_GBS, "traffic": relu_traffic},
+                              "frac": gbs(RELU_BYTES_PER_ELEMENT, relu_copy_ms) / HBM_PEAK_GBS, "traffic": rt.get("relu_bytes_per_element")},
             "dram_compulsory": {"bytes_per_element": RELU_COMPULSORY_BYTES,
                                 "frac": gbs(RELU_COMPULSORY_BYTES, relu_ms) / HBM_PEAK_GBS,
                                 "note": "inputs, outputs and offline material only: the exchanged words and the state carried from "
                                         "round to round are served by the 256 MB last-level cache when a chunk fits it"},
-            "traffic": None},
+            "traffic": rt.get("relu_put_bytes_per_element")},
         "roofline_relu_msb": {
             "kernel": "sign-only packed ReLU chain, exchange by remote store: k_relu_msb_stage<0..9, put>",
             "workload": f"configs[1], {n} elements", "bound": "hbm", "achieved": gbs(RELU_MSB_PUT_BYTES_PER_ELEMENT, msb_ms),
@@ -461,10 +471,10 @@ def config1_leg(steps, warmup, pmc_summary):
             "bytes_per_element": RELU_MSB_PUT_BYTES_PER_ELEMENT, "ms_call": msb_ms, "elems_per_s": n / (msb_ms * 1e-3),
             "copy_exchange": {"bytes_per_element": RELU_MSB_BYTES_PER_ELEMENT, "ms_call": msb_copy_ms,
                               "elems_per_s": n / (msb_copy_ms * 1e-3), "achieved": gbs(RELU_MSB_BYTES_PER_ELEMENT, msb_copy_ms),
-                              "frac": gbs(RELU_MSB_BYTES_PER_ELEMENT, msb_copy_ms) / HBM_PEAK_GBS, "traffic": msb_traffic},
+                              "frac": gbs(RELU_MSB_BYTES_PER_ELEMENT, msb_copy_ms) / HBM_PEAK_GBS, "traffic": rt.get("relu_msb_bytes_per_element")},
             "dram_compulsory": {"bytes_per_element": RELU_MSB_COMPULSORY_BYTES,
                                 "frac": gbs(RELU_MSB_COMPULSORY_BYTES, msb_ms) / HBM_PEAK_GBS},
-            "traffic": None},
+            "traffic": rt.get("relu_msb_put_bytes_per_element")},
     }
 
 
@@ -536,7 +546,7 @@ def three_party_leg(steps, warmup):
             "max_abs_err_vs_float64": err}
 
 
-def cpu_baseline(budget_s=15.0, images=2):
+def cpu_baseline(budget_s=15.0, images=8):
     """The oracle as it stands, on the host cores: the same network, layer by layer (Alg. 1 with five direct
     ring convolutions, truncation, ReLU, max-pool), on a few images per repetition."""
     import oracle
@@ -707,6 +717,11 @@ def main():
         out["configs"] = per_config_table(args)
     c1 = config1_leg(args.steps, args.warmup, args.pmc_summary)
     out["config1_step"] = c1["times"]
+    out["value_definition"] = {
+        "value": "whole job: all secure MACs of the configs[4] batch over the wall time of the step (ReLU and pooling included)",
+        "earlier_lines": "quoted the Beaver conv call of configs[1] alone (its secure MACs over the call's own time, plain call)",
+        "that_quantity_now": {"plain_call": c1["times"]["plain_call_copy_exchange"]["secure_macs_per_s"],
+                              "folded_prepared_call": c1["times"]["secure_macs_per_s"], "unit": "secure MACs/s"}}
     for k in ("roofline", "roofline_relu", "roofline_relu_msb"):
         out[k] = c1[k]
     if not args.no_three_party:
