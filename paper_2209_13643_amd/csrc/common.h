@@ -154,6 +154,7 @@ struct RecodeArgs {
     const u64* src3;
     const u64* sub;       // optional: subtracted from src first (v = src - sub), same indexing
     u64* side;            // optional: v is also stored here, same indexing (a mask kernel's output, formed on the way)
+    const u64* minuend;   // optional, with side and without sub: side = minuend - src instead (src itself is recoded)
     u8* dst;              // plane base
     long long row_stride, k_stride, tap_stride;
     int plane_rows;       // rows of the plane tensor (>= rows); rows beyond `rows` are zero-filled

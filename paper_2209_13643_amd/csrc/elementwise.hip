@@ -93,6 +93,7 @@ __device__ __forceinline__ void recode_body(const RecodeArgs& a, int tap /* == n
     const u64* src3 = a.src3 ? a.src3 + (size_t)b * a.src_batch_stride : nullptr;
     const u64* sub = a.sub ? a.sub + (size_t)b * a.src_batch_stride : nullptr;
     u64* side = a.side ? a.side + (size_t)b * a.src_batch_stride : nullptr;
+    const u64* minuend = (a.minuend && a.side && !a.sub) ? a.minuend + (size_t)b * a.src_batch_stride : nullptr;
     u8* dst = a.dst + (size_t)b * a.dst_batch_stride;
     const bool padtap = tap >= a.ntaps;
     const int kb_count = padtap ? a.KB_total - a.ntaps * a.KB_tap : a.KB_tap;
@@ -112,6 +113,7 @@ __device__ __forceinline__ void recode_body(const RecodeArgs& a, int tap /* == n
                 const long long idx = (long long)row * a.row_stride + (long long)k * a.k_stride + (long long)tap * a.tap_stride;
                 v = src[idx];
                 if (sub) { v -= sub[idx]; if (side) side[idx] = v; }
+                else if (minuend) side[idx] = minuend[idx] - v;
                 if (src2) v += src2[idx];
                 if (src3) v += src3[idx];
             }
@@ -153,10 +155,12 @@ __device__ __forceinline__ void recode_rows_body(const RecodeArgs& a, int b, uns
     const u64* src3 = a.src3 ? a.src3 + (size_t)b * a.src_batch_stride : nullptr;
     const u64* sub = a.sub ? a.sub + (size_t)b * a.src_batch_stride : nullptr;
     u64* side = a.side ? a.side + (size_t)b * a.src_batch_stride : nullptr;
+    const u64* minuend = (a.minuend && a.side && !a.sub) ? a.minuend + (size_t)b * a.src_batch_stride : nullptr;
     u8* dst = a.dst + (size_t)b * a.dst_batch_stride;
     const bool vec_ok = (a.row_stride % 2 == 0) && (((uintptr_t)src & 15) == 0) &&
                         (!src2 || ((uintptr_t)src2 & 15) == 0) && (!src3 || ((uintptr_t)src3 & 15) == 0) &&
-                        (!sub || ((uintptr_t)sub & 15) == 0) && (!side || ((uintptr_t)side & 15) == 0);
+                        (!sub || ((uintptr_t)sub & 15) == 0) && (!side || ((uintptr_t)side & 15) == 0) &&
+                        (!minuend || ((uintptr_t)minuend & 15) == 0);
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const int seg = threadIdx.x + 256 * p;
@@ -176,6 +180,11 @@ __device__ __forceinline__ void recode_rows_body(const RecodeArgs& a, int b, uns
                         *reinterpret_cast<u64x2*>(side + idx) = s0; *reinterpret_cast<u64x2*>(side + idx + 2) = s1;
                     }
                 }
+                if (minuend) {
+                    const u64x2 q0 = *reinterpret_cast<const u64x2*>(minuend + idx), q1 = *reinterpret_cast<const u64x2*>(minuend + idx + 2);
+                    u64x2 s0, s1; s0.a = q0.a - v[0]; s0.b = q0.b - v[1]; s1.a = q1.a - v[2]; s1.b = q1.b - v[3];
+                    *reinterpret_cast<u64x2*>(side + idx) = s0; *reinterpret_cast<u64x2*>(side + idx + 2) = s1;
+                }
                 if (src2) { const u64x2 q0 = *reinterpret_cast<const u64x2*>(src2 + idx), q1 = *reinterpret_cast<const u64x2*>(src2 + idx + 2);
                             v[0] += q0.a; v[1] += q0.b; v[2] += q1.a; v[3] += q1.b; }
                 if (src3) { const u64x2 q0 = *reinterpret_cast<const u64x2*>(src3 + idx), q1 = *reinterpret_cast<const u64x2*>(src3 + idx + 2);
@@ -186,6 +195,7 @@ __device__ __forceinline__ void recode_rows_body(const RecodeArgs& a, int b, uns
                     if (k + t < a.K) {
                         v[t] = src[idx + t];
                         if (sub) { v[t] -= sub[idx + t]; if (side) side[idx + t] = v[t]; }
+                        else if (minuend) side[idx + t] = minuend[idx + t] - v[t];
                         if (src2) v[t] += src2[idx + t];
                         if (src3) v[t] += src3[idx + t];
                     }

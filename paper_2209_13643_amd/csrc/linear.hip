@@ -280,6 +280,45 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
             prof_end(c, MPC_PROF_LINEAR, pi, P0);
             return MPC_OK;
         }
+        if (c->exchange_put && !folded && !skip_left && !x_public && !s.im2colT && !(two_phase && have_f)) {
+            // Plain call with the exchange by remote store: the pass that recodes the triple's [a_i] forms the masked
+            // shares on the way (e_i = x_i - a_i, stored into the peer's receive buffer), and the opened e is recoded
+            // from party 0's own shares and the word it received: every activation word is read once per use.
+            if (!have_f) {
+                SubSeg sub[2];
+                for (int i = 0; i < 2; ++i) sub[i] = SubSeg{ y.p[i], b.p[i], w.sf[i], s.nw, 0, w.rf[1 - i] };
+                MPC_TRY(launch_sub_multi(c, P0, sub, 2));
+            }
+            RecodeArgs k1[3]; int n1 = 0;
+            for (int i = 0; i < 2; ++i) {
+                k1[n1] = recode_left(s, a.p[i], nullptr, w.pl_a[i]);
+                k1[n1].minuend = x.p[i]; k1[n1].side = w.re[1 - i];
+                ++n1;
+            }
+            if (!skip_right) k1[n1++] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
+            MPC_TRY(launch_recode_any(c, P0, k1, n1));
+            RecodeArgs k2[3]; int n2 = 0;
+            k2[n2] = recode_left(s, x.p[0], w.re[0], w.pl_e);
+            k2[n2].sub = a.p[0];
+            ++n2;
+            if (!skip_right) {
+                const u64* f0 = f_public ? f_public : w.sf[0];
+                const u64* f1 = f_public ? nullptr : w.rf[0];
+                k2[n2++] = recode_right(s, f0, f1, nullptr, w.pr_f);
+                k2[n2++] = recode_right(s, b.p[0], f0, f1, w.pr_b[0]);
+            }
+            MPC_TRY(launch_recode_any(c, P0, k2, n2));
+            g.nseg = 2;
+            for (int i = 0; i < 2; ++i) {
+                g.seg[i][0] = make_seg(s, w.pl_e, w.pr_b[i]);
+                g.seg[i][1] = make_seg(s, w.pl_a[i], w.pr_f);
+                g.addend[i] = cc.p[i]; g.addend2[i] = nullptr; g.out[i] = z.p[i];
+            }
+            g.trunc_bits = trunc;
+            MPC_TRY(launch_limb_gemm(c, P0, g));
+            prof_end(c, MPC_PROF_LINEAR, pi, P0);
+            return MPC_OK;
+        }
         if ((size_t)n_chunks > s.nx) n_chunks = (int)s.nx;
         bool f_pending = !have_f;                            // the weight mask rides with the first launch issued
         for (int ch = 0; ch < n_chunks; ++ch) {

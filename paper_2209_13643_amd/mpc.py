@@ -8,6 +8,7 @@ library is missing or the device is absent, calls raise.
 from __future__ import annotations
 
 import ctypes
+import threading
 import os
 from ctypes import POINTER, byref, c_int, c_size_t, c_uint8, c_uint64, c_void_p
 
@@ -199,10 +200,31 @@ class MpcError(RuntimeError):
     pass
 
 
+# Argument lifetime.  The calls only enqueue work, and torch's allocator knows nothing about a lane's queues: a
+# tensor passed as a temporary would go back to the allocator when the call returns and could be handed out (and
+# overwritten) while the enqueued kernels still read it.  Every tensor whose pointer is marshalled is therefore
+# noted here and kept by the lane (Lane._check) until the lane is next synchronised.
+_marshalled = threading.local()
+
+
+def _note(t):
+    lst = getattr(_marshalled, "tensors", None)
+    if lst is None:
+        lst = _marshalled.tensors = []
+    lst.append(t)
+
+
+def _take_noted():
+    lst = getattr(_marshalled, "tensors", None)
+    _marshalled.tensors = []
+    return lst or []
+
+
 def _p64(t):
     if t is None:
         return ctypes.cast(None, _P64)
     assert t.is_cuda and t.is_contiguous() and t.dtype == torch.int64, "int64 contiguous device tensor expected"
+    _note(t)
     return ctypes.cast(t.data_ptr(), _P64)
 
 
@@ -210,6 +232,7 @@ def _p8(t):
     if t is None:
         return ctypes.cast(None, _P8)
     assert t.is_cuda and t.is_contiguous() and t.dtype == torch.uint8
+    _note(t)
     return ctypes.cast(t.data_ptr(), _P8)
 
 
@@ -339,12 +362,16 @@ class Lane:
             raise RuntimeError("mpcpipe needs a GPU: no HIP device is visible")
         self.device = torch.device("cuda", device)
         self._h = c_void_p()
+        self._pending = []           # tensors the enqueued calls still use (see _note); released by sync()
         self._check(lib().mpc_ctx_create(byref(self._h), device, frac_bits))
         self._ws = None
         self._ws_bytes = 0
 
     # -- plumbing
     def _check(self, rc: int):
+        self._pending.extend(_take_noted())
+        if len(self._pending) > (1 << 17):       # a queue this deep without a sync: let the oldest half go
+            del self._pending[: 1 << 16]
         if rc != 0:
             msg = lib().mpc_strerror(rc).decode()
             hip = lib().mpc_last_hip_error(self._h) if self._h else 0
@@ -364,6 +391,7 @@ class Lane:
 
     def sync(self):
         self._check(lib().mpc_ctx_sync(self._h))
+        self._pending.clear()
 
     def set_profiling(self, on: bool):
         self._check(lib().mpc_ctx_set_profiling(self._h, 1 if on else 0))

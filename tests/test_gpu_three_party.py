@@ -332,6 +332,7 @@ def test_word_aligned_but_not_16_byte_aligned_buffers(mpc, lane):
         buf = torch.empty(flat.numel() + 1, dtype=flat.dtype, device=flat.device)
         view = buf[1:]
         view.copy_(flat)
+        torch.cuda.synchronize()        # the copy ran on torch's stream; the lane's queues do not wait for that one
         assert view.data_ptr() % 16 == 8 or flat.dtype == torch.uint8
         return view.view(np.shape(arr))
 
@@ -340,8 +341,11 @@ def test_word_aligned_but_not_16_byte_aligned_buffers(mpc, lane):
     d = deal_matmul(rng, M, K, N, x_std=1.0, w_std=0.1)
     mat = synth.deal_relu_material(rng, M * N)
     sh2 = lambda pair: tuple(shifted(v) for v in pair)
-    z = lane.beaver_matmul(*[sh2(d[k]) for k in "xyabc"], out=sh2((np.zeros((M, N), dtype=U64),) * 2))
-    y = lane.relu(z, {k: sh2(v) for k, v in mat.items()}, out=sh2((np.zeros((M, N), dtype=U64),) * 2))
+    # the calls only enqueue work: their inputs must stay alive (and out of torch's allocator) until the lane is synchronised
+    ins = [sh2(d[k]) for k in "xyabc"]
+    z = lane.beaver_matmul(*ins, out=sh2((np.zeros((M, N), dtype=U64),) * 2))
+    mat_dev = {k: sh2(v) for k, v in mat.items()}
+    y = lane.relu(z, mat_dev, out=sh2((np.zeros((M, N), dtype=U64),) * 2))
     lane.sync()
     want_t = oracle_matmul(d)
     want_y = oracle.relu(want_t, mat).y
@@ -352,8 +356,11 @@ def test_word_aligned_but_not_16_byte_aligned_buffers(mpc, lane):
     r, rt = synth.deal_trunc3_pair(rng, (M, N))
     mat3 = synth.deal_relu3_material(rng, M * N)
     sh3 = lambda tri: tuple(shifted(v) for v in tri)
-    z3 = lane.beaver_matmul3(*[sh3(d3[k]) for k in "xyabc"], out=sh3((np.zeros((M, N), dtype=U64),) * 3))
-    lane.truncate3(z3, sh3(r), sh3(rt))
-    y3 = lane.relu3(z3, {k: sh3(v) for k, v in mat3.items()}, out=sh3((np.zeros((M, N), dtype=U64),) * 3))
+    ins3 = [sh3(d3[k]) for k in "xyabc"]
+    z3 = lane.beaver_matmul3(*ins3, out=sh3((np.zeros((M, N), dtype=U64),) * 3))
+    r_dev, rt_dev = sh3(r), sh3(rt)
+    lane.truncate3(z3, r_dev, rt_dev)
+    mat3_dev = {k: sh3(v) for k, v in mat3.items()}
+    y3 = lane.relu3(z3, mat3_dev, out=sh3((np.zeros((M, N), dtype=U64),) * 3))
     want3 = oracle.relu3(oracle.truncate3(oracle.beaver_matmul3(*[d3[k] for k in "xyabc"]), r, rt), mat3).y
     assert_shares_equal(host3(mpc, lane, y3), want3, "three parties, shifted buffers")
