@@ -709,8 +709,10 @@ def main(argv):
             tot_lin = tot_relu = tot_msb = tot_prep = 0.0
             for r in rows:
                 line = (f"  {r['layer']:16s} x{r['repeat']:<2d} {r['gemm']:22s} call {r['call_ms']:8.3f} ms "
-                        f"{r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s  folded {r['folded_call_ms']:7.3f} ms  mfma {100 * r['mfma_frac']:5.1f}%")
-                tot_lin += r['call_ms'] * r['repeat']; tot_prep += r['folded_call_ms'] * r['repeat']
+                        f"{r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s  "
+                        + (f"plain, remote store {r['call_put_ms']:7.3f} ms" if r['activation_product'] else f"folded {r['folded_call_ms']:7.3f} ms")
+                        + f"  mfma {100 * r['mfma_frac']:5.1f}%")
+                tot_lin += r['call_ms'] * r['repeat']; tot_prep += (r['call_put_ms'] if r['activation_product'] else r['folded_call_ms']) * r['repeat']
                 if "relu_ms" in r:
                     line += (f"  | relu {r['relu_n']:9d} el {r['relu_ms']:7.3f} ms hbm {100 * r['hbm_frac']:5.1f}%"
                              f"  | sign-only {r['msb_ms']:7.3f} ms hbm {100 * r['msb_hbm_frac']:5.1f}%")
