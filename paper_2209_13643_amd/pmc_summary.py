@@ -80,20 +80,39 @@ def relu_calls(rows):
     return {k: sum(v) / len(v) for k, v in out.items()}
 
 
-def gemm_calls(rows):
-    """KiB per two-party GEMM launch by the form of the Beaver call, read off the recoding launch before it:
-    plain call (six plane sets recoded), prepared call (e only), folded prepared call (x_0 + e_1 and e)."""
+def gemm_launches(rows):
+    """{form of the Beaver call: [value per two-party GEMM launch]} for rows of (id, kernel, grid, value) in dispatch
+    order.  The form is read off the call's own kernels before the launch: the remote-store folded call recodes with
+    k_recode_rows alone; the other forms use one k_recode_mixed launch whose grid grows with the number of plane
+    sets (prepared call: e; folded call with the copy exchange: x_0 + e_1 and e; plain call: six sets)."""
     biggest = max((r[2] for r in rows if r[1].startswith("k_limb_gemm")), default=0)
-    by_grid = collections.defaultdict(list)
-    last_recode = None
+    groups = collections.OrderedDict()
+    prologue = []
     for r in rows:
-        if r[1].startswith("k_recode_mixed"):
-            last_recode = r[2]
-        elif r[1].startswith("k_limb_gemm") and r[2] == biggest and last_recode is not None:
-            by_grid[last_recode].append(r[3])
-    grids = sorted(by_grid)            # recoding grids grow with the number of plane sets
-    names = ["prepared call (four products)", "folded prepared call (three products)", "plain call (four products)"]
-    return {names[i]: sum(by_grid[g]) / len(by_grid[g]) for i, g in enumerate(grids[:3])} if len(grids) == 3 else {}
+        if is_relu(r[1]):
+            prologue = []
+        elif r[1].startswith("k_limb_gemm"):
+            if r[2] == biggest and prologue:
+                mixed = [g for n, g in prologue if n.startswith("k_recode_mixed")]
+                rows_only = not mixed and any(n.startswith("k_recode_rows") for n, _ in prologue)
+                if mixed or rows_only:
+                    groups.setdefault(("rows", 0) if rows_only else ("mixed", mixed[-1]), []).append(r[3])
+            prologue = []
+        else:
+            prologue.append((r[1], r[2]))
+    out = collections.OrderedDict()
+    if ("rows", 0) in groups:
+        out["folded prepared call (three products)"] = groups[("rows", 0)]
+    mixed = sorted(k for k in groups if k[0] == "mixed")
+    names = ["prepared call (four products)", "folded prepared call with the copy exchange (three products)", "plain call (four products)"]
+    for i, k in enumerate(mixed):
+        out[names[i] if len(mixed) == 3 else f"call whose recoding launch has grid {k[1]}"] = groups[k]
+    return out
+
+
+def gemm_calls(rows):
+    """Mean KiB per two-party GEMM launch by the form of the Beaver call."""
+    return collections.OrderedDict((k, sum(v) / len(v)) for k, v in gemm_launches(rows).items())
 
 
 def main(argv):

@@ -30,20 +30,22 @@ def _run(scale):
     A = "(anonymous namespace)::"
     gemm = f"void {A}k_limb_gemm<2, 2, true>(GemmArgs)"
     rec = f"{A}k_recode_mixed({A}RecodeMixed)"
+    rows = f"{A}k_recode_rows({A}RecodeArgs)"
     st = lambda s, put: f"void {A}k_relu_stage<{s}, 4, 0, {'true' if put else 'false'}>({A}ReluParty, {A}ReluParty, int, unsigned long, unsigned long)"
     wire = f"void {A}k_wire_words<4>(unsigned long const*, unsigned long*)"
-    rows = [("void at::native::something<int>(int)", 512, 999.0),                    # torch: ignored
+    out = [("void at::native::something<int>(int)", 512, 999.0),                    # torch: ignored
             (f"void {A}k_sub_multi<false>(SubBatch)", 4194304, 70144.0 * scale),
             (f"{A}k_copy_multi(CopyBatch)", 4194304, 35072.0 * scale),               # the calibration kernel
             (rec, 422400, 100.0), (gemm, 131072, 135.0 * 1024 * scale),              # plain call
             (rec, 131584, 100.0), (gemm, 131072, 135.0 * 1024 * scale),              # prepared call
-            (rec, 263168, 100.0), (gemm, 131072, 108.0 * 1024 * scale),              # folded call
+            (rec, 263168, 100.0), (gemm, 131072, 110.0 * 1024 * scale),              # folded call, copy exchange
+            (rows, 65792, 50.0), (rows, 65792, 50.0), (gemm, 131072, 108.0 * 1024 * scale),      # folded call, remote store
             (gemm, 65536, 25.0 * 1024 * scale)]                                      # a dealer launch (smaller grid)
     relu_copy = [(wire, 1048576, 1000.0 * scale)] + [(st(s, False), 524288, 2000.0 * scale) for s in range(10)]
     relu_put = [(st(s, s < 9), 524288, 1500.0 * scale) for s in range(10)]
     # two chunks per call, calls separated by a conv-call kernel
-    rows += relu_copy + relu_copy + [(rec, 263168, 100.0)] + relu_put + relu_put + [(rec, 263168, 100.0)]
-    return rows
+    out += relu_copy + relu_copy + [(rec, 263168, 100.0)] + relu_put + relu_put + [(rec, 263168, 100.0)]
+    return out
 
 
 def test_pmc_summary_and_bench_quote(tmp_path, monkeypatch):
@@ -60,6 +62,7 @@ def test_pmc_summary_and_bench_quote(tmp_path, monkeypatch):
     assert f"sources sha256/16: {pmc_summary.sources_digest()}" in text
     assert "| k_limb_gemm in the folded prepared call (three products) | 108.0 | 108.0 |" in text
     assert "| k_limb_gemm in the plain call (four products) | 135.0 | 135.0 |" in text
+    assert "| k_limb_gemm in the folded prepared call with the copy exchange (three products) | 110.0 | 110.0 |" in text
     n = 64 * 16 * 16 * 128
     per_call_copy = 2 * (1000.0 + 10 * 2000.0) * 1024 * 2            # two chunks, fetch + write after scaling
     assert f"whole words, exchange by copy, all kernels of one call (both parties + wire), {n} elements" in text
