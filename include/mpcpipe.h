@@ -237,7 +237,8 @@ int mpc_set_gemm_small_tile(int max_steps, int min_tiles);
  * mpc_beaver_matmul / mpc_conv2d with f_public.
  *   mpc_*_prepared_bytes: sizes of the two caller-owned device buffers
  *     (right: three plane tensors; left: two); either pointer may be NULL.
- *   mpc_*_prepare: fill them.  right_planes needs b and f_public, left_planes
+ *   mpc_*_prepare: fill them.  right_planes needs b and f_public (with f_public = NULL only the
+ *     slot of b_1 is filled: see the folded product of two activations below), left_planes
  *     needs a; pass NULL for the one not wanted.  Buffers 16-byte aligned.
  *     flags: MPC_TRANS_X / MPC_TRANS_Y as for mpc_beaver_matmul (storage of a / of b, f).
  *   mpc_beaver_matmul_prepared / mpc_conv2d_prepared: the online call.
@@ -250,7 +251,16 @@ int mpc_set_gemm_small_tile(int max_steps, int min_tiles);
  *     c0_folded = c_0 - a_0*b_0, M x N words, all pointers party 0's), party 0 contracts one product
  *     online instead of two (party 1 keeps [e | a_1] x [b_1 ; f]): three ring products per call, the
  *     same output words.  The online call then takes c.p[0] = c0_folded; a.p[0] is still needed for
- *     the mask x_0 - a_0, a_0's planes in left_planes are not read.  Not with MPC_TWO_PHASE. */
+ *     the mask x_0 - a_0, a_0's planes in left_planes are not read.  Not with MPC_TWO_PHASE.
+ *   Folded product of two activations (mpc_beaver_matmul_folded; Sec. 5.3's attention products Q*K^T and
+ *     A*V, where y is a share like x and f = y - b opens in the call).  The triple is still input-independent:
+ *     c.p[0] = c0_folded from mpc_matmul_fold, left_planes from mpc_matmul_prepare (a_1's planes are read),
+ *     right_planes from mpc_matmul_prepare with f_public = NULL, which fills only the slot of b_1 (the two
+ *     others are workspace-side in this call and are not read).  Online, party 0 contracts
+ *     (x_0 + e_1) * (y_0 + f_1), since b_0 + f = y_0 + f_1, and party 1 [e | a_1] x [b_1 ; f]: three ring
+ *     products, the same output words as mpc_beaver_matmul.  x, y, a, b: both parties' shares (all four
+ *     needed for the masks); flags: MPC_TRUNCATE, MPC_TRANS_X, MPC_TRANS_Y (MPC_FOLDED is implied);
+ *     MPC_EINVAL for a NULL plane buffer or share. */
 int mpc_matmul_fold(mpc_ctx* ctx, const uint64_t* a0, const uint64_t* b0, const uint64_t* c0,
                     uint64_t* c0_folded, int M, int K, int N, int batch, int flags);
 int mpc_conv2d_fold(mpc_ctx* ctx, const uint64_t* a0, const uint64_t* b0, const uint64_t* c0,
@@ -273,6 +283,9 @@ int mpc_conv2d_prepared(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_cshare c, 
                         const void* right_planes, const void* left_planes,
                         int B, int H, int W, int Cin, int Cout, int KH, int KW,
                         int pad, int stride, int n_chunks, int flags);
+int mpc_beaver_matmul_folded(mpc_ctx* ctx, mpc_cshare x, mpc_cshare y, mpc_cshare a, mpc_cshare b, mpc_cshare c,
+                             mpc_share z, const void* right_planes, const void* left_planes,
+                             int M, int K, int N, int batch, int n_chunks, int flags);
 
 /* Backward pass of mpc_conv2d (Sec. 4.1 "Application to the backward pass",
  * Sec. 5.3): both gradients are Alg. 1 / Eq. 3 with another bilinear product

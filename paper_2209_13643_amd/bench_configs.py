@@ -68,6 +68,12 @@ def bench_layers(idx: int, reps: int = 20, workload=None):
             cf = (lane.fold_conv2d(d["a"], d["b"], d["c"], L.pad, L.stride), d["c"][1])
             run_prep = lambda: lane.conv2d_prepared(d["x"], d["a"], cf, right, left, L.KH, L.KW, L.pad, L.stride, out=z,
                                                     flags=mpc.MPC_TRUNCATE | mpc.MPC_FOLDED)
+        elif L.batch > 1:
+            # per-head attention products multiply two activations: f opens in the call, a_1's and b_1's planes and
+            # the folded addend still come from the offline phase
+            right, left = lane.prepare_matmul(d["a"], d["b"], None)
+            cf = (lane.fold_matmul(d["a"], d["b"], d["c"]), d["c"][1])
+            run_prep = lambda: lane.beaver_matmul_folded(d["x"], d["w"], d["a"], d["b"], cf, right, left, out=z)
         else:
             right, left = lane.prepare_matmul(d["a"], d["b"], d["f_public"])
             cf = (lane.fold_matmul(d["a"], d["b"], d["c"]), d["c"][1])
@@ -115,8 +121,7 @@ def bench_layers(idx: int, reps: int = 20, workload=None):
         lane.sync(); lane.set_profiling(False)
         gk, gn = lane.profile(mpc.PROF_GEMM_KERNEL); lin, ln = lane.profile(mpc.PROF_LINEAR)
         macs = layer_macs(L)
-        # per-head attention products multiply two activations: neither mask can be opened ahead of the input, so
-        # only the plain call applies to them (the folded figures are kept in the row, the sums must not use them)
+        # activation_product: both operands are shares (per-head attention); its folded call opens f online
         row = dict(layer=L.name, gemm=shape, repeat=L.repeat, activation_product=(not isinstance(L, synth.Conv)) and L.batch > 1,
                    call_ms=lin / ln, kernel_ms=gk / gn,
                    kernel_min_ms=min(lane.profile_samples(mpc.PROF_GEMM_KERNEL)),
@@ -709,10 +714,8 @@ def main(argv):
             tot_lin = tot_relu = tot_msb = tot_prep = 0.0
             for r in rows:
                 line = (f"  {r['layer']:16s} x{r['repeat']:<2d} {r['gemm']:22s} call {r['call_ms']:8.3f} ms "
-                        f"{r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s  "
-                        + (f"plain, remote store {r['call_put_ms']:7.3f} ms" if r['activation_product'] else f"folded {r['folded_call_ms']:7.3f} ms")
-                        + f"  mfma {100 * r['mfma_frac']:5.1f}%")
-                tot_lin += r['call_ms'] * r['repeat']; tot_prep += (r['call_put_ms'] if r['activation_product'] else r['folded_call_ms']) * r['repeat']
+                        f"{r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s  folded {r['folded_call_ms']:7.3f} ms  mfma {100 * r['mfma_frac']:5.1f}%")
+                tot_lin += r['call_ms'] * r['repeat']; tot_prep += r['folded_call_ms'] * r['repeat']
                 if "relu_ms" in r:
                     line += (f"  | relu {r['relu_n']:9d} el {r['relu_ms']:7.3f} ms hbm {100 * r['hbm_frac']:5.1f}%"
                              f"  | sign-only {r['msb_ms']:7.3f} ms hbm {100 * r['msb_hbm_frac']:5.1f}%")
@@ -757,9 +760,9 @@ def main(argv):
             line = (f"  {r['layer']:10s} {r['gemm']:22s} call {r['call_ms']:8.3f} ms  {r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s"
                     f"  kernel {r['kernel_ms']:7.3f} ms  mfma {mf:5.1f}%{'*' if mf >= hf else ' '} hbm {hf:5.1f}%{'*' if hf > mf else ' '}"
                     f"  | folded call {r['folded_call_ms']:7.3f} ms {r['folded_secure_macs_per_s'] / 1e12:6.2f} T MAC/s kernel {r['folded_kernel_ms']:7.3f} ms {100 * r['folded_mfma_frac']:5.1f}%")
-            tot['lin'] += r['call_ms']; tot['prep'] = tot.get('prep', 0.0) + (r['call_put_ms'] if r['activation_product'] else r['folded_call_ms'])
+            tot['lin'] += r['call_ms']; tot['prep'] = tot.get('prep', 0.0) + r['folded_call_ms']
             if r['activation_product']:
-                line += f"  (activation x activation: plain call only, {r['call_put_ms']:.3f} ms with the remote-store exchange)"
+                line += f"  (both operands shared: f opens in the call; plain call with the remote-store exchange {r['call_put_ms']:.3f} ms)"
             if "relu_ms" in r:
                 tot['relu'] += r['relu_ms']; tot['msb'] += r['msb_ms']
                 tot['put'] = tot.get('put', 0.0) + r['relu_put_ms']; tot['msb_put'] = tot.get('msb_put', 0.0) + r['msb_put_ms']
@@ -768,7 +771,7 @@ def main(argv):
                 line += (f"  | sign-only copy {r['msb_ms']:7.3f} ms {r['msb_elems_per_s'] / 1e9:5.2f} G/s {100 * r['msb_hbm_frac']:5.1f}%"
                          f" put {r['msb_put_ms']:7.3f} ms {r['msb_put_elems_per_s'] / 1e9:5.2f} G/s {100 * r['msb_put_hbm_frac']:5.1f}%")
             print(line, flush=True)
-        print(f"  totals: linear calls {tot['lin']:.3f} ms ({tot['prep']:.3f} ms with folded prepared calls where the right operand is a weight), ReLU whole-word {tot['relu']:.3f} ms copy / "
+        print(f"  totals: linear calls {tot['lin']:.3f} ms ({tot['prep']:.3f} ms as folded calls), ReLU whole-word {tot['relu']:.3f} ms copy / "
               f"{tot.get('put', 0.0):.3f} ms put, sign-only {tot['msb']:.3f} ms copy / {tot.get('msb_put', 0.0):.3f} ms put", flush=True)
         if idx == 4:
             for packed, prepared, pool_first, ex in ((False, False, False, "copy"), (True, False, False, "copy"), (True, True, False, "copy"),

@@ -219,17 +219,21 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
     MPC_TRY(check_shape(s));
     if (n_chunks < 1) return MPC_EINVAL;
     // prepared planes: digit planes of the input-independent operands, recoded ahead of time
-    const bool skip_right = prep_right != nullptr, skip_left = prep_left != nullptr;
     // folded triple: cc.p[0] holds c_0 - a_0 * b_0, and party 0 contracts (x_0 + e_1) against b_0 + f alone
     const bool folded = (flags & MPC_FOLDED) != 0;
-    if (folded && (!skip_right || !skip_left || x_public || (flags & MPC_TWO_PHASE))) return MPC_EINVAL;
+    // folded product of two activations: y arrives as shares and f opens in this call, so of the right planes only
+    // party 1's [b_1] can be prepared; those of f and of b_0 + f = y_0 + f_1 are recoded here
+    const bool right_online = folded && prep_right != nullptr && y.p[0] != nullptr && y.p[1] != nullptr;
+    const bool skip_right = prep_right != nullptr && !right_online, skip_left = prep_left != nullptr;
+    if (folded && (!(skip_right || right_online) || !skip_left || x_public || (flags & MPC_TWO_PHASE))) return MPC_EINVAL;
+    if (right_online && f_public) return MPC_EINVAL;
     for (int i = 0; i < 2; ++i) {
         if (!a.p[i] || !cc.p[i] || !z.p[i]) return MPC_EINVAL;
         if (!skip_right && !b.p[i]) return MPC_EINVAL;
         if (!x_public && !x.p[i]) return MPC_EINVAL;
         if (!skip_right && !f_public && !y.p[i]) return MPC_EINVAL;
     }
-    if ((skip_right && ((uintptr_t)prep_right & 15)) || (skip_left && ((uintptr_t)prep_left & 15))) return MPC_EINVAL;
+    if ((prep_right && ((uintptr_t)prep_right & 15)) || (skip_left && ((uintptr_t)prep_left & 15))) return MPC_EINVAL;
     if (ws_off > c->ws_bytes) return MPC_ENOMEM;
     LinearWs w = carve(c->ws ? c->ws + ws_off : nullptr, c->ws_bytes - ws_off, s, folded);
     if (!w.ok) return MPC_ENOMEM;
@@ -237,6 +241,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         const size_t rp = align_up(8 * s.R_plane * s.batch);
         w.pr_f = const_cast<u8*>(prep_right); w.pr_b[0] = w.pr_f + rp; w.pr_b[1] = w.pr_f + 2 * rp;
     }
+    if (right_online) w.pr_b[1] = const_cast<u8*>(prep_right) + 2 * align_up(8 * s.R_plane * s.batch);
     if (skip_left) {
         const size_t lp = align_up(8 * s.L_plane * s.batch);
         // folded: the workspace slot of a_0's planes receives the planes of x_0 + e_1 instead
@@ -265,12 +270,24 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
             //   party 0 recodes:                   planes of a_0 + e = x_0 + e_1
             // (party 1's word leaves after party 0's has arrived: on a network the two directions of this exchange
             // would follow each other; with the copy exchange they stay simultaneous.)
-            SubSeg sub0{ x.p[0], a.p[0], w.re[1], s.nx, 0, nullptr };
-            MPC_TRY(launch_sub_multi(c, P0, &sub0, 1));
-            RecodeArgs r1 = recode_left(s, x.p[1], w.re[1], w.pl_e);
-            r1.sub = a.p[1]; r1.side = w.re[0];
-            MPC_TRY(launch_recode(c, P0, r1));
-            MPC_TRY(launch_recode(c, P0, recode_left(s, x.p[0], w.re[0], w.pl_a[0])));
+            // A product of two activations opens f the same way, in the same three launches:
+            //   f_0 = y_0 - b_0 -> party 1;  f_1 = y_1 - b_1 -> party 0 and planes of f;  planes of b_0 + f = y_0 + f_1.
+            SubSeg sub0[2] = { SubSeg{ x.p[0], a.p[0], w.re[1], s.nx, 0, nullptr },
+                               SubSeg{ y.p[0], b.p[0], w.rf[1], s.nw, 0, nullptr } };
+            MPC_TRY(launch_sub_multi(c, P0, sub0, right_online ? 2 : 1));
+            RecodeArgs r1[2] = { recode_left(s, x.p[1], w.re[1], w.pl_e), RecodeArgs{} };
+            r1[0].sub = a.p[1]; r1[0].side = w.re[0];
+            RecodeArgs r0[2] = { recode_left(s, x.p[0], w.re[0], w.pl_a[0]), RecodeArgs{} };
+            if (right_online) {
+                r1[1] = recode_right(s, y.p[1], w.rf[1], nullptr, w.pr_f);
+                r1[1].sub = b.p[1]; r1[1].side = w.rf[0];
+                r0[1] = recode_right(s, y.p[0], w.rf[0], nullptr, w.pr_b[0]);
+                MPC_TRY(launch_recode_any(c, P0, r1, 2));
+                MPC_TRY(launch_recode_any(c, P0, r0, 2));
+            } else {
+                MPC_TRY(launch_recode(c, P0, r1[0]));
+                MPC_TRY(launch_recode(c, P0, r0[0]));
+            }
             g.nseg = 2;
             g.seg[0][0] = make_seg(s, w.pl_a[0], w.pr_b[0]); g.seg[0][1] = GemmSeg{};
             g.seg[1][0] = make_seg(s, w.pl_e, w.pr_b[1]);    g.seg[1][1] = make_seg(s, w.pl_a[1], w.pr_f);
@@ -365,7 +382,7 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
             for (int i = l0; i < 3; ++i) rr[nr++] = recode_left(s, lsrc[i], lsrc2[i], ldst[i]);
         }
         if (!skip_right) {
-            rr[nr++] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
+            if (!right_online) rr[nr++] = recode_right(s, b.p[1], nullptr, nullptr, w.pr_b[1]);
             rr[nr++] = recode_right(s, f0, f1, nullptr, w.pr_f);
             rr[nr++] = recode_right(s, b.p[0], f0, f1, w.pr_b[0]);
         }
@@ -436,6 +453,11 @@ int beaver_linear(mpc_ctx* c, const LinearShape& s, mpc_cshare x, mpc_cshare y,
         MPC_TRY(chain(c, Wr, P1));
         MPC_TRY(launch_left1(c, P0, s, x.p[0], w.re[0], w.pl_a[0]));
         MPC_TRY(launch_left1(c, P1, s, w.se[1], w.re[1], w.pl_e));
+        if (right_online) {
+            // f opened in this call: party 0 recodes b_0 + f, party 1 f, each from its own and the received word
+            MPC_TRY(launch_recode(c, P0, recode_right(s, b.p[0], w.sf[0], w.rf[0], w.pr_b[0])));
+            MPC_TRY(launch_recode(c, P1, recode_right(s, w.sf[1], w.rf[1], nullptr, w.pr_f)));
+        }
         MPC_TRY(chain(c, P1, P0));
         GemmArgs g{};
         fill_geom(s, w, g);
@@ -649,7 +671,8 @@ int prepare_planes(mpc_ctx* c, const LinearShape& s, mpc_cshare a, mpc_cshare b,
 {
     if (!c || (!right && !left)) return MPC_EINVAL;
     MPC_TRY(check_shape(s));
-    if (right && (!f_public || !b.p[0] || !b.p[1] || ((uintptr_t)right & 15))) return MPC_EINVAL;
+    // without f (a product of two activations, whose f opens online) only [b_1] can be recoded ahead of time
+    if (right && (!b.p[1] || (f_public && !b.p[0]) || ((uintptr_t)right & 15))) return MPC_EINVAL;
     if (left && (!a.p[0] || !a.p[1] || ((uintptr_t)left & 15))) return MPC_EINVAL;
     hipStream_t P0 = c->s[0];
     MPC_TRY(lane_join(c));
@@ -661,11 +684,15 @@ int prepare_planes(mpc_ctx* c, const LinearShape& s, mpc_cshare a, mpc_cshare b,
     }
     if (right) {
         const size_t rp = align_up(8 * s.R_plane * s.batch);
-        RecodeArgs rr[3];
-        rr[0] = recode_right(s, f_public, nullptr, nullptr, right);
-        rr[1] = recode_right(s, b.p[0], f_public, nullptr, right + rp);
-        rr[2] = recode_right(s, b.p[1], nullptr, nullptr, right + 2 * rp);
-        MPC_TRY(launch_recode_multi(c, P0, rr, 3));
+        if (f_public) {
+            RecodeArgs rr[3];
+            rr[0] = recode_right(s, f_public, nullptr, nullptr, right);
+            rr[1] = recode_right(s, b.p[0], f_public, nullptr, right + rp);
+            rr[2] = recode_right(s, b.p[1], nullptr, nullptr, right + 2 * rp);
+            MPC_TRY(launch_recode_multi(c, P0, rr, 3));
+        } else {
+            MPC_TRY(launch_recode(c, P0, recode_right(s, b.p[1], nullptr, nullptr, right + 2 * rp)));
+        }
     }
     MPC_TRY(chain(c, P0, c->s[1]));
     return MPC_OK;
@@ -810,6 +837,17 @@ int mpc_beaver_matmul_prepared(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_csh
     const mpc_cshare none = { { nullptr, nullptr } };
     return beaver_linear(ctx, shape_matmul(M, K, N, batch, flags), x, none, a, none, c, z, nullptr, n_chunks, flags,
                          nullptr, (const u8*)right_planes, (const u8*)left_planes);
+}
+
+int mpc_beaver_matmul_folded(mpc_ctx* ctx, mpc_cshare x, mpc_cshare y, mpc_cshare a, mpc_cshare b, mpc_cshare c,
+                             mpc_share z, const void* right_planes, const void* left_planes,
+                             int M, int K, int N, int batch, int n_chunks, int flags)
+{
+    if (M <= 0 || K <= 0 || N <= 0 || batch <= 0 || !right_planes || !left_planes || !y.p[0] || !y.p[1] ||
+        !b.p[0] || !b.p[1])
+        return MPC_EINVAL;
+    return beaver_linear(ctx, shape_matmul(M, K, N, batch, flags), x, y, a, b, c, z, nullptr, n_chunks,
+                         flags | MPC_FOLDED, nullptr, (const u8*)right_planes, (const u8*)left_planes);
 }
 
 int mpc_conv2d_prepared(mpc_ctx* ctx, mpc_cshare x, mpc_cshare a, mpc_cshare c, mpc_share z,

@@ -64,7 +64,7 @@ EXPORTS = [
     "mpc_maxpool2x2_signs", "mpc_maxpool_backward_workspace_bytes", "mpc_maxpool2x2_backward",
     "mpc_ctx_set_adder", "mpc_ctx_set_exchange", "mpc_ctx_profile_samples", "mpc_add",
     "mpc_matmul_prepared_bytes", "mpc_conv2d_prepared_bytes", "mpc_matmul_prepare", "mpc_conv2d_prepare",
-    "mpc_beaver_matmul_prepared", "mpc_conv2d_prepared", "mpc_matmul_fold", "mpc_conv2d_fold", "mpc_set_gemm_small_tile",
+    "mpc_beaver_matmul_prepared", "mpc_conv2d_prepared", "mpc_beaver_matmul_folded", "mpc_matmul_fold", "mpc_conv2d_fold", "mpc_set_gemm_small_tile",
     "mpc_ctx_capture_begin", "mpc_ctx_capture_end", "mpc_graph_launch", "mpc_graph_destroy",
     "mpc_open3", "mpc_matmul3_workspace_bytes", "mpc_beaver_matmul3", "mpc_conv2d3_workspace_bytes", "mpc_conv2d3",
     "mpc_truncate3_workspace_bytes", "mpc_truncate3", "mpc_relu3_workspace_bytes", "mpc_relu3",
@@ -103,6 +103,7 @@ def lib():
     L.mpc_conv2d_prepare.argtypes = [c_void_p, CShare, CShare, _P64, c_void_p, c_void_p] + [c_int] * 9
     L.mpc_beaver_matmul_prepared.argtypes = [c_void_p, CShare, CShare, CShare, CShare, c_void_p, c_void_p] + [c_int] * 6
     L.mpc_conv2d_prepared.argtypes = [c_void_p, CShare, CShare, CShare, CShare, c_void_p, c_void_p] + [c_int] * 11
+    L.mpc_beaver_matmul_folded.argtypes = [c_void_p] + [CShare] * 6 + [c_void_p, c_void_p] + [c_int] * 6
     L.mpc_set_gemm_small_tile.argtypes = [c_int, c_int]
     L.mpc_matmul_fold.argtypes = [c_void_p, _P64, _P64, _P64, _P64] + [c_int] * 5
     L.mpc_conv2d_fold.argtypes = [c_void_p, _P64, _P64, _P64, _P64] + [c_int] * 9
@@ -530,6 +531,19 @@ class Lane:
         self._check(lib().mpc_beaver_matmul_prepared(self._h, _share(x), _share(a), _share(c), _share(z), right.data_ptr(),
                                                      left.data_ptr() if left is not None else None,
                                                      M, K, N, batch, n_chunks, flags))
+        return z
+
+    def beaver_matmul_folded(self, x, y, a, b, c, right, left, n_chunks=1, flags=MPC_TRUNCATE, out=None):
+        """Folded product of two shared operands: c = (fold_matmul(a, b, c), c_1); right, left from
+        prepare_matmul(a, b, None)."""
+        shp = a[0].shape
+        batch = 1 if len(shp) == 2 else shp[0]
+        M, K = (shp[-1], shp[-2]) if flags & MPC_TRANS_X else (shp[-2], shp[-1])
+        N = c[0].shape[-1]
+        self.reserve(lib().mpc_matmul_workspace_bytes(M, K, N, batch))
+        z = out if out is not None else (torch.empty_like(c[0]), torch.empty_like(c[1]))
+        self._check(lib().mpc_beaver_matmul_folded(self._h, _share(x), _share(y), _share(a), _share(b), _share(c), _share(z),
+                                                   right.data_ptr(), left.data_ptr(), M, K, N, batch, n_chunks, flags))
         return z
 
     def fold_matmul(self, a, b, c, flags=0):

@@ -408,6 +408,56 @@ def test_beaver_matmul_folded_batched(mpc, lane):
     assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "folded batched")
 
 
+@pytest.mark.parametrize("shape", [(1, 1, 1), (5, 7, 3), (64, 256, 128), (130, 70, 200), (300, 1100, 150), (700, 64, 300)])
+def test_beaver_matmul_folded_two_shared_operands(mpc, lane, shape):
+    """The folded call on a product of two shared operands (f opens in the call, only a_1's and b_1's planes and
+    the folded addend come from the offline phase): every output word is Alg. 1's."""
+    M, K, N = shape
+    print(f"folded matmul, y shared {shape}", flush=True)
+    d = deal_matmul(np.random.default_rng(M * K + N + 21), M, K, N)
+    x, y, a, b, c = (dev(mpc, d[k]) for k in ("x", "y", "a", "b", "c"))
+    right, lp = lane.prepare_matmul(a, b, None)
+    c0f = lane.fold_matmul(a, b, c)
+    for trunc in (True, False):
+        z = lane.beaver_matmul_folded(x, y, a, b, (c0f, c[1]), right, lp, flags=mpc.MPC_TRUNCATE if trunc else 0)
+        assert_shares_equal(host(mpc, lane, z), oracle_matmul(d, 16 if trunc else 0), "folded matmul, y shared")
+    # chunked masking gives the same words
+    z = lane.beaver_matmul_folded(x, y, a, b, (c0f, c[1]), right, lp, n_chunks=3)
+    assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "folded matmul, y shared, chunked")
+    lib = mpc.lib()
+    none = mpc._share(None)
+    z2 = (z[0].clone(), z[1].clone())
+    args = (lane._h, mpc._share(x), none, mpc._share(a), mpc._share(b), mpc._share((c0f, c[1])), mpc._share(z2),
+            right.data_ptr(), lp.data_ptr(), M, K, N, 1, 1, 0)
+    assert lib.mpc_beaver_matmul_folded(*args) == -1          # MPC_EINVAL: y missing
+    args = args[:7] + (None,) + args[8:]
+    assert lib.mpc_beaver_matmul_folded(*args) == -1          # MPC_EINVAL: no prepared planes
+    lane.sync()
+
+
+def test_beaver_matmul_folded_attention_heads(mpc, lane):
+    """Per-head Q * K^T (right operand stored [N][K]) and A * V as batched folded calls."""
+    print("folded attention products", flush=True)
+    rng = np.random.default_rng(91)
+    heads, S, dh = 6, 80, 64
+    # Q * K^T: K is stored [S][dh] = [N][K]
+    d = deal_matmul(rng, S, dh, S, batch=heads)
+    tr = lambda pair: (np.ascontiguousarray(pair[0].transpose(0, 2, 1)), np.ascontiguousarray(pair[1].transpose(0, 2, 1)))
+    x, a, c = dev(mpc, d["x"]), dev(mpc, d["a"]), dev(mpc, d["c"])
+    yT, bT = dev(mpc, tr(d["y"])), dev(mpc, tr(d["b"]))
+    right, lp = lane.prepare_matmul(a, bT, None, flags=mpc.MPC_TRANS_Y)
+    c0f = lane.fold_matmul(a, bT, c, flags=mpc.MPC_TRANS_Y)
+    z = lane.beaver_matmul_folded(x, yT, a, bT, (c0f, c[1]), right, lp, flags=mpc.MPC_TRUNCATE | mpc.MPC_TRANS_Y)
+    assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "folded Q K^T")
+    # A * V
+    d = deal_matmul(rng, S, S, dh, batch=heads)
+    x, y, a, b, c = (dev(mpc, d[k]) for k in ("x", "y", "a", "b", "c"))
+    right, lp = lane.prepare_matmul(a, b, None)
+    c0f = lane.fold_matmul(a, b, c)
+    z = lane.beaver_matmul_folded(x, y, a, b, (c0f, c[1]), right, lp)
+    assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "folded A V")
+
+
 @pytest.mark.parametrize("case", CONV_CASES + [(2, 4, 4, 512, 96, 3, 3, 1, 1), (3, 16, 16, 3, 64, 3, 3, 1, 1)])
 def test_conv2d_folded(mpc, lane, case):
     B, H, W, Cin, Cout, KH, KW, pad, stride = case
