@@ -284,6 +284,7 @@ def per_config_table(args):
         e = {"config": idx, "name": name, "secure_macs": macs,
              "folded_prepared_calls": {"ms_beaver_calls": fold, "ms_gemm_kernels": fkern, "secure_macs_per_s": macs / (fold * 1e-3),
                                        "call_frac_of_int8_peak": f(fold), "kernel_frac_of_int8_peak": f(fkern),
+                                       "call_frac_of_hbm_peak": sum(r["folded_call_bytes"] for r in rows) / (fold * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                        "executed_int8_ops_per_secure_mac": 216,
                                        "note": "three ring products per call, party 0's addend c_0 - a_0 b_0 and the planes of the "
                                                "triple's a, b from the offline phase; layers whose right operand is a weight also "

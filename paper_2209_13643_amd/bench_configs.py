@@ -42,6 +42,20 @@ def gemm_algorithmic_bytes(L) -> int:
     return 2 * 8 * (2 * act + 2 * wts + 2 * out)
 
 
+def folded_call_algorithmic_bytes(L) -> int:
+    """The folded call with the remote-store exchange, every word counted once per pass that has to touch it.  Activation
+    (8-byte words): mask and send e_0 (read x_0, a_0; write e_0), party 1's recode (read x_1, a_1, e_0; write e_1 and the
+    planes of e), party 0's recode (read x_0, e_1; write the planes of x_0 + e_1) = 11 passes, and the same 11 over the
+    right operand when it is a share too (per-head attention).  GEMM launch: the planes of x_0 + e_1, e, a_1 (3 x
+    activation) and of b_0 + f, b_1, f (3 x right operand), the addends c_i and the outputs z_i."""
+    if isinstance(L, synth.Conv):
+        act, wts, out, shared_right = L.B * L.H * L.W * L.Cin, L.KH * L.KW * L.Cin * L.Cout, L.B * L.Ho * L.Wo * L.Cout, False
+    else:
+        b = max(L.batch, 1)
+        act, wts, out, shared_right = b * L.M * L.K, b * L.K * L.N, b * L.M * L.N, L.batch > 1
+    return 8 * (14 * act + (14 if shared_right else 3) * wts + 4 * out)
+
+
 def bench_layers(idx: int, reps: int = 20, workload=None):
     wl = workload if workload is not None else synth.CONFIGS[idx]()
     lane = mpc.Lane(0); lane.use_single_queue()
@@ -128,7 +142,9 @@ def bench_layers(idx: int, reps: int = 20, workload=None):
                    folded_call_ms=prep_ms, folded_kernel_ms=fk, call_put_ms=pp_ms, kernel_put_ms=pk,
                    secure_macs_per_s=macs / (lin / ln * 1e-3), folded_secure_macs_per_s=macs / (prep_ms * 1e-3),
                    mfma_frac=288 * macs / (gk / gn * 1e-3) / INT8_PEAK, folded_mfma_frac=288 * macs / (fk * 1e-3) / INT8_PEAK,
-                   gemm_hbm_frac=gemm_algorithmic_bytes(L) / (gk / gn * 1e-3) / HBM_PEAK)
+                   gemm_hbm_frac=gemm_algorithmic_bytes(L) / (gk / gn * 1e-3) / HBM_PEAK,
+                   folded_call_bytes=folded_call_algorithmic_bytes(L),
+                   folded_call_hbm_frac=folded_call_algorithmic_bytes(L) / (prep_ms * 1e-3) / HBM_PEAK)
         if mat:
             rl, rn = lane.profile(mpc.PROF_RELU)
             row.update(relu_n=n_out, relu_ms=rl / rn, relu_elems_per_s=n_out / (rl / rn * 1e-3),
@@ -759,7 +775,8 @@ def main(argv):
             mf, hf = 100 * r['mfma_frac'], 100 * r['gemm_hbm_frac']
             line = (f"  {r['layer']:10s} {r['gemm']:22s} call {r['call_ms']:8.3f} ms  {r['secure_macs_per_s'] / 1e12:6.2f} T MAC/s"
                     f"  kernel {r['kernel_ms']:7.3f} ms  mfma {mf:5.1f}%{'*' if mf >= hf else ' '} hbm {hf:5.1f}%{'*' if hf > mf else ' '}"
-                    f"  | folded call {r['folded_call_ms']:7.3f} ms {r['folded_secure_macs_per_s'] / 1e12:6.2f} T MAC/s kernel {r['folded_kernel_ms']:7.3f} ms {100 * r['folded_mfma_frac']:5.1f}%")
+                    f"  | folded call {r['folded_call_ms']:7.3f} ms {r['folded_secure_macs_per_s'] / 1e12:6.2f} T MAC/s kernel {r['folded_kernel_ms']:7.3f} ms {100 * r['folded_mfma_frac']:5.1f}%"
+                    f" call: mfma {100 * 288 * r['folded_secure_macs_per_s'] / INT8_PEAK:5.1f}% hbm {100 * r['folded_call_hbm_frac']:5.1f}%")
             tot['lin'] += r['call_ms']; tot['prep'] = tot.get('prep', 0.0) + r['folded_call_ms']
             if r['activation_product']:
                 line += f"  (both operands shared: f opens in the call; plain call with the remote-store exchange {r['call_put_ms']:.3f} ms)"
