@@ -111,9 +111,9 @@ class Net:
         from paper_2209_13643_amd import dealer, mpc, pipeline, synth
         self.pipeline, self.torch = pipeline, torch
         self.layers = synth.config_vgg16_pipeline(MICRO_BATCH).layers
-        self.lanes = [mpc.Lane(0) for _ in range(N_MB)]
+        self.lanes = [mpc.Lane(0, single_queue=True) for _ in range(N_MB)]
         for ln in self.lanes:
-            ln.use_single_queue(); ln.set_exchange(exchange)
+            ln.set_exchange(exchange)
         dev = self.lanes[0].device
         g = dealer.gen(seed, dev)
         self.weights = pipeline.deal_weights(g, self.layers, dev)
@@ -334,8 +334,7 @@ def config1_leg(steps, warmup, pmc_summary):
     L = wl.layers[0]
     M, K, N = L.gemm_mkn
     n = M * N
-    lane = mpc.Lane(0)
-    lane.use_single_queue()      # one in-order queue per lane: no cross-stream event latency inside a call
+    lane = mpc.Lane(0, single_queue=True)      # one in-order queue per lane: no cross-stream event latency inside a call
     dev = lane.device
     g = dealer.gen(synth.BASE_SEED + wl.index, dev)
     d = dealer.conv_layer(lane, g, L.B, L.H, L.W, L.Cin, L.Cout, L.KH, L.KW, L.pad, L.stride, L.x_std, L.w_std)
@@ -387,6 +386,39 @@ def config1_leg(steps, warmup, pmc_summary):
         "sign_only_relu": timed(lambda: (conv_folded(), lane.relu(zf, mat_p, out=y2, packed=True)), "put"),
         "sign_only_relu_copy_exchange": timed(lambda: (conv_folded(), lane.relu(zf, mat_p, out=y2, packed=True)), "copy"),
     }
+    # Alg. 3's overlap inside the layer: the batch cut into two image chunks, each a complete folded call, on two lanes
+    # (one chunk's HBM-bound mask / exchange / recoding under the other's MFMA-bound GEMM).  Wall clock of back-to-back
+    # layers without the ReLU between, the one-call layer timed the same way beside it.
+    from paper_2209_13643_amd import pipeline
+    lanes2 = [mpc.Lane(0, single_queue=True), mpc.Lane(0, single_queue=True)]
+    for ln in lanes2:
+        ln.set_exchange("put")
+    chunked = pipeline.ChunkedLinear(lanes2, L, pipeline.LayerState(w=d["w"], a=d["a"], b=d["b"], c=d["c"], f_public=d["f_public"]), n_chunks=2)
+    zc = tuple(torch.empty_like(z[0]) for _ in range(2))
+
+    def wall(fn, sync_lanes):
+        for _ in range(warmup):
+            fn()
+        for ln in sync_lanes:
+            ln.sync()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        for ln in sync_lanes:
+            ln.sync()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    lane.set_exchange("put")
+    one_ms = wall(conv_folded, [lane])
+    two_ms = wall(lambda: chunked(d["x"], zc), lanes2)
+    assert torch.equal(zc[0], zf[0]) and torch.equal(zc[1], zf[1]), "the layer as two image chunks differs from the one-call layer"
+    for ln in lanes2:
+        ln.close()
+    chunk_leg = {"what": "configs[1] conv layer as two image chunks (32 + 32) on two lanes, each chunk a folded prepared call; wall clock "
+                         "of back-to-back layers, no ReLU between; same output words as the one-call layer",
+                 "ms_one_call": one_ms, "ms_two_chunks_two_lanes": two_ms, "speedup": one_ms / two_ms,
+                 "call_frac_of_int8_peak_one_call": INT8_OPS_PER_SECURE_MAC * M * K * N / (one_ms * 1e-3) / 1e12 / INT8_PEAK_TOPS,
+                 "call_frac_of_int8_peak_two_chunks": INT8_OPS_PER_SECURE_MAC * M * K * N / (two_ms * 1e-3) / 1e12 / INT8_PEAK_TOPS}
     # sanity on the results of the last steps: same shares from all three conv calls, ReLU of the reconstructed output exactly
     assert torch.equal(z[0], zf[0]) and torch.equal(z[1], zf[1]), "folded / prepared convolution differs from the plain call"
     rec_z = z[0] + z[1]
@@ -432,6 +464,7 @@ def config1_leg(steps, warmup, pmc_summary):
                                                "relu_elems_per_s": n / (relu_copy_ms * 1e-3)},
                   "ms_relu_msb_call": msb_ms, "relu_msb_elems_per_s": n / (msb_ms * 1e-3),
                   "ms_relu_msb_call_copy_exchange": msb_copy_ms,
+                  "overlap_inside_the_layer": chunk_leg,
                   "region_times": seq, "max_abs_err_vs_float64": err},
         "roofline": {
             "kernel": "secure GEMM: k_limb_gemm<2,2,true> (party 0: [x_0 + e_1] x [b_0 + f]; party 1: [e | a_1] x [b_1 ; f]; fused "
@@ -490,7 +523,7 @@ def three_party_leg(steps, warmup):
     from paper_2209_13643_amd import dealer, mpc, synth
 
     L = synth.config_vgg_block().layers[0]
-    lane = mpc.Lane(0); lane.use_single_queue()
+    lane = mpc.Lane(0, single_queue=True)
     dev = lane.device
     g = dealer.gen(synth.BASE_SEED + 31, dev)
     d = dealer.conv_layer3(lane, g, L.B, L.H, L.W, L.Cin, L.Cout, L.KH, L.KW, L.pad, L.stride, L.x_std, L.w_std)

@@ -77,6 +77,12 @@ enum {
  * priority).  frac_bits in [0, 62] is the fixed-point scale used by
  * MPC_TRUNCATE.  Host-side allocation only. */
 int mpc_ctx_create(mpc_ctx** out, int device, int frac_bits);
+/* The same lane with one in-order stream for both parties and the wire from the start (what
+ * mpc_ctx_set_streams(s0, s0, s0) turns a lane into, without creating and destroying the two other streams).
+ * The runtime spreads streams over a small number of hardware queues (four by default) as they are
+ * created; lanes that are meant to overlap (Sec. 4.3: one lane per micro-batch; Alg. 3: chunks of a layer)
+ * should each hold exactly one stream so that they land on different hardware queues. */
+int mpc_ctx_create_single_queue(mpc_ctx** out, int device, int frac_bits);
 int mpc_ctx_destroy(mpc_ctx* ctx);
 
 /* Replace the lane's streams by caller-owned hipStream_t handles (e.g. from

@@ -58,7 +58,7 @@ def folded_call_algorithmic_bytes(L) -> int:
 
 def bench_layers(idx: int, reps: int = 20, workload=None):
     wl = workload if workload is not None else synth.CONFIGS[idx]()
-    lane = mpc.Lane(0); lane.use_single_queue()
+    lane = mpc.Lane(0, single_queue=True)
     dev = lane.device
     g = dealer.gen(synth.BASE_SEED + idx, dev)
     rows = []
@@ -178,7 +178,7 @@ def bench_backward(idx: int, reps: int = 5):
     """Per layer: the two gradient products (weight / activation masks opened in the forward
     pass reused) and the ReLU backward, timed with host clocks around a synchronised lane."""
     wl = synth.CONFIGS[idx]()
-    lane = mpc.Lane(0); lane.use_single_queue()
+    lane = mpc.Lane(0, single_queue=True)
     dev = lane.device
     g = dealer.gen(synth.BASE_SEED + 50 + idx, dev)
 
@@ -236,9 +236,7 @@ def bench_training(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_r
     serial on one lane vs one lane per micro-batch."""
     wl = synth.config_vgg16_pipeline(micro_batch)
     layers = wl.layers
-    lanes = [mpc.Lane(0) for _ in range(n_mb)]
-    for ln in lanes:
-        ln.use_single_queue()
+    lanes = [mpc.Lane(0, single_queue=True) for _ in range(n_mb)]
     dev = lanes[0].device
     g = dealer.gen(synth.BASE_SEED + 70, dev)
     weights = pipeline.deal_weights(g, layers, dev)
@@ -292,9 +290,7 @@ def bench_training3(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_
     """bench_training's step (forward with tape + backward, no update) with three simulated parties."""
     wl = synth.config_vgg16_pipeline(micro_batch)
     layers = wl.layers
-    lanes = [mpc.Lane(0) for _ in range(n_mb)]
-    for ln in lanes:
-        ln.use_single_queue()
+    lanes = [mpc.Lane(0, single_queue=True) for _ in range(n_mb)]
     dev = lanes[0].device
     g = dealer.gen(synth.BASE_SEED + 71, dev)
     weights = pipeline.deal_weights3(g, layers, dev)
@@ -332,7 +328,7 @@ def bench_graph(reps: int = 50, pool_first: bool = False, exchange: str = "copy"
     VGG16-CIFAR micro-batch forward (sign-only packed ReLU, prepared planes).
     pool_first: pooled layers run as ReLU(maxpool(z)) (same function, fewer conversions)."""
     res = {}
-    lane = mpc.Lane(0); lane.use_single_queue(); lane.set_exchange(exchange)
+    lane = mpc.Lane(0, single_queue=True); lane.set_exchange(exchange)
     dev = lane.device
     g = dealer.gen(synth.BASE_SEED + 90, dev)
     L = synth.config_tiny().layers[0]
@@ -378,10 +374,10 @@ def bench_graph(reps: int = 50, pool_first: bool = False, exchange: str = "copy"
     eager = pipeline.forward(lane, wl.layers, states, x, keep); lane.sync()
     assert torch.equal(eager[0], out[0]) and torch.equal(eager[1], out[1]), "graph replay differs from eager forward"
     # inter-batch pipeline with one recorded graph per micro-batch lane
-    lanes = [lane] + [mpc.Lane(0) for _ in range(3)]
+    lanes = [lane] + [mpc.Lane(0, single_queue=True) for _ in range(3)]
     graphs, pins = [cap2.graph], [kept]
     for ln in lanes[1:]:
-        ln.use_single_queue(); ln.set_exchange(exchange)
+        ln.set_exchange(exchange)
         st = pipeline.deal_microbatch(ln, g, wl.layers, weights, packed_relu=True, pool_first=pool_first)
         pipeline.prepare_layers(ln, wl.layers, st, fold=True)
         xm = dealer.share(g, dealer.normal_fixed(g, (32, 32, 32, 3), 1.0, dev))
@@ -414,9 +410,9 @@ def bench_pipeline(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_r
     """Config 4: serial (one lane, micro-batches one after the other) vs pipelined (one lane each)."""
     wl = synth.config_vgg16_pipeline(micro_batch)
     layers = wl.layers
-    lanes = [mpc.Lane(0) for _ in range(n_mb)]
+    lanes = [mpc.Lane(0, single_queue=True) for _ in range(n_mb)]
     for ln in lanes:
-        ln.use_single_queue(); ln.set_exchange(exchange)
+        ln.set_exchange(exchange)
     dev = lanes[0].device
     g = dealer.gen(synth.BASE_SEED + wl.index, dev)
     weights = pipeline.deal_weights(g, layers, dev)
@@ -484,7 +480,7 @@ def sweep_tiles(n: int = 2097152, reps: int = 10):
         for ns in (50176, 200704, 802816):
             line = f"  {'sign-only packed' if packed else 'whole-word':16s} n={ns:7d}:"
             for ex in ("copy", "put"):
-                lane = mpc.Lane(0); lane.use_single_queue(); lane.set_exchange(ex)
+                lane = mpc.Lane(0, single_queue=True); lane.set_exchange(ex)
                 xs = (x[0][:ns], x[1][:ns]); ys = (y[0][:ns], y[1][:ns])
                 ms = dealer.relu_material(g, ns, dev, packed=packed)
                 for _ in range(3):
@@ -497,7 +493,7 @@ def sweep_tiles(n: int = 2097152, reps: int = 10):
                 lane.close()
             print(line, flush=True)
     # the listing's prefix tree as the carry network (same rounds and bytes as Kogge-Stone)
-    lane = mpc.Lane(0); lane.use_single_queue(); lane.set_adder("tree")
+    lane = mpc.Lane(0, single_queue=True); lane.set_adder("tree")
     for _ in range(3):
         lane.relu(x, mats[False], n_chunks=2, out=y)
     lane.sync(); t0 = time.perf_counter()
@@ -524,7 +520,7 @@ def bench_three_parties(reps: int = 20):
     bits (2 * 63/64), own masked words again (9.906), a and b again (7.906), x again (1) = 26.78 W + 3 B
     =>  3 * 121.98 W + 33 B = 2961 B."""
     wl = synth.CONFIGS[1](); L = wl.layers[0]
-    lane = mpc.Lane(0); lane.use_single_queue()
+    lane = mpc.Lane(0, single_queue=True)
     dev = lane.device
     g = dealer.gen(synth.BASE_SEED + 31, dev)
     d = dealer.conv_layer3(lane, g, L.B, L.H, L.W, L.Cin, L.Cout, L.KH, L.KW, L.pad, L.stride, L.x_std, L.w_std)
@@ -584,9 +580,7 @@ def bench_pipeline3(n_mb: int = 4, micro_batch: int = 32, reps: int = 3, packed_
     """Config 4's network with three parties: serial on one lane vs one lane per micro-batch."""
     wl = synth.config_vgg16_pipeline(micro_batch)
     layers = wl.layers
-    lanes = [mpc.Lane(0) for _ in range(n_mb)]
-    for ln in lanes:
-        ln.use_single_queue()
+    lanes = [mpc.Lane(0, single_queue=True) for _ in range(n_mb)]
     dev = lanes[0].device
     g = dealer.gen(synth.BASE_SEED + 34, dev)
     weights = pipeline.deal_weights3(g, layers, dev)
@@ -647,7 +641,73 @@ def bench_hbm_copy(reps: int = 20):
     return rows
 
 
+def bench_chunks(L, n_chunks=2, n_lanes=2, reps=20, seed=78):
+    """One layer as a single folded prepared call and as row chunks on lanes (pipeline.ChunkedLinear): wall clock of
+    back-to-back layers, remote-store exchange; the outputs must be the same words."""
+    from . import pipeline
+    lanes = [mpc.Lane(0, single_queue=True) for _ in range(n_lanes)]
+    for ln in lanes:
+        ln.set_exchange("put")
+    l0 = lanes[0]
+    g = dealer.gen(seed, l0.device)
+    conv = isinstance(L, synth.Conv)
+    if conv:
+        d = dealer.conv_layer(l0, g, L.B, L.H, L.W, L.Cin, L.Cout, L.KH, L.KW, L.pad, L.stride, L.x_std, L.w_std)
+        right, left = l0.prepare_conv2d(d["a"], d["b"], d["f_public"], L.pad, L.stride)
+        cf = (l0.fold_conv2d(d["a"], d["b"], d["c"], L.pad, L.stride), d["c"][1])
+    else:
+        d = dealer.matmul_layer(l0, g, L.M, L.K, L.N, L.x_std, L.w_std)
+        right, left = l0.prepare_matmul(d["a"], d["b"], d["f_public"])
+        cf = (l0.fold_matmul(d["a"], d["b"], d["c"]), d["c"][1])
+    z = (torch.empty_like(d["c"][0]), torch.empty_like(d["c"][1]))
+    zc = (torch.empty_like(z[0]), torch.empty_like(z[1]))
+    F = mpc.MPC_TRUNCATE | mpc.MPC_FOLDED
+    one = (lambda: l0.conv2d_prepared(d["x"], d["a"], cf, right, left, L.KH, L.KW, L.pad, L.stride, out=z, flags=F)) if conv else \
+          (lambda: l0.beaver_matmul_prepared(d["x"], d["a"], cf, right, left, out=z, flags=F))
+    chunked = pipeline.ChunkedLinear(lanes, L, pipeline.LayerState(w=d["w"], a=d["a"], b=d["b"], c=d["c"], f_public=d["f_public"]),
+                                     n_chunks=n_chunks)
+
+    def wall(fn, sync):
+        for _ in range(5):
+            fn()
+        for ln in sync:
+            ln.sync()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        for ln in sync:
+            ln.sync()
+        return (time.perf_counter() - t0) * 1e3 / reps
+
+    one_ms = wall(one, [l0])
+    many_ms = wall(lambda: chunked(d["x"], zc), lanes)
+    same = torch.equal(z[0], zc[0]) and torch.equal(z[1], zc[1])
+    for ln in lanes:
+        ln.close()
+    return one_ms, many_ms, same
+
+
 def main(argv):
+    if argv and argv[0] == "chunks":
+        # Alg. 3's overlap inside a layer: row chunks as complete calls on two lanes
+        todo = [(1, None), (3, ("qkv", "out", "ffn1", "ffn2")), (4, ("conv2", "conv4", "conv6", "conv9"))]
+        for idx, names in todo:
+            wl = synth.CONFIGS[idx]()
+            print(f"== config {idx}: {wl.name}")
+            for L in wl.layers:
+                if names is not None and L.name not in names:
+                    continue
+                shape = "x".join(map(str, L.gemm_mkn)) if isinstance(L, synth.Conv) else f"{L.M}x{L.K}x{L.N}"
+                macs = layer_macs(L)
+                line = f"  {L.name:8s} {shape:20s}"
+                for nch, nl in ((2, 2), (4, 2), (4, 4)):
+                    one_ms, many_ms, same = bench_chunks(L, nch, nl)
+                    if nch == 2:
+                        line += f" one call {one_ms:7.3f} ms ({100 * 288 * macs / (one_ms * 1e-3) / INT8_PEAK:4.1f}%)"
+                    line += (f" | {nch} chunks on {nl} lanes {many_ms:7.3f} ms ({100 * 288 * macs / (many_ms * 1e-3) / INT8_PEAK:4.1f}%)"
+                             f"{'' if same else ' DIFFERENT WORDS'}")
+                print(line, flush=True)
+        return
     if argv and argv[0] == "sweep":
         print("== tile-count sweep, secure ReLU on 2097152 elements")
         sweep_tiles()
@@ -667,7 +727,7 @@ def main(argv):
     if argv and argv[0] == "relu3":
         # the three-party ReLU alone, both chains (the command the per-kernel profile is taken with)
         n = int(argv[1]) if len(argv) > 1 else 2097152
-        lane = mpc.Lane(0); lane.use_single_queue()
+        lane = mpc.Lane(0, single_queue=True)
         g = dealer.gen(synth.BASE_SEED + 33, lane.device)
         x = dealer.share3(g, dealer.normal_fixed(g, (n,), 1.0, lane.device))
         y = tuple(torch.empty_like(v) for v in x)

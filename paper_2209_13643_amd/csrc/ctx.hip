@@ -5,7 +5,7 @@
 
 extern "C" {
 
-int mpc_ctx_create(mpc_ctx** out, int device, int frac_bits)
+static int ctx_create(mpc_ctx** out, int device, int frac_bits, int n_streams)
 {
     if (!out || frac_bits < 0 || frac_bits > 62) return MPC_EINVAL;
     mpc_ctx* c = new (std::nothrow) mpc_ctx();
@@ -15,10 +15,11 @@ int mpc_ctx_create(mpc_ctx** out, int device, int frac_bits)
     for (int i = 0; i < 3; ++i) { c->s[i] = nullptr; c->own_stream[i] = false; }
     for (int i = 0; i < kEventPool; ++i) c->ev[i] = nullptr;
     hipError_t e = hipSetDevice(device);
-    for (int i = 0; i < 3 && e == hipSuccess; ++i) {
+    for (int i = 0; i < n_streams && e == hipSuccess; ++i) {
         e = hipStreamCreateWithFlags(&c->s[i], hipStreamNonBlocking);
         c->own_stream[i] = (e == hipSuccess);
     }
+    for (int i = n_streams; i < 3 && e == hipSuccess; ++i) c->s[i] = c->s[0];      // one in-order queue for everything
     for (int i = 0; i < kEventPool && e == hipSuccess; ++i)
         e = hipEventCreateWithFlags(&c->ev[i], hipEventDisableTiming);
     if (e != hipSuccess) {
@@ -29,6 +30,10 @@ int mpc_ctx_create(mpc_ctx** out, int device, int frac_bits)
     *out = c;
     return MPC_OK;
 }
+
+int mpc_ctx_create(mpc_ctx** out, int device, int frac_bits) { return ctx_create(out, device, frac_bits, 3); }
+
+int mpc_ctx_create_single_queue(mpc_ctx** out, int device, int frac_bits) { return ctx_create(out, device, frac_bits, 1); }
 
 int mpc_ctx_destroy(mpc_ctx* c)
 {

@@ -51,7 +51,7 @@ N_AND_TRIPLES3 = 13
 
 EXPORTS = [
     "mpc_ctx_create", "mpc_ctx_destroy", "mpc_ctx_set_streams", "mpc_ctx_stream", "mpc_ctx_set_workspace",
-    "mpc_ctx_sync", "mpc_ctx_wait", "mpc_last_hip_error", "mpc_strerror",
+    "mpc_ctx_create_single_queue", "mpc_ctx_sync", "mpc_ctx_wait", "mpc_last_hip_error", "mpc_strerror",
     "mpc_ctx_set_profiling", "mpc_ctx_profile", "mpc_ctx_profile_reset",
     "mpc_matmul_workspace_bytes", "mpc_conv2d_workspace_bytes", "mpc_relu_workspace_bytes",
     "mpc_maxpool_workspace_bytes", "mpc_open", "mpc_sub", "mpc_beaver_matmul", "mpc_conv2d", "mpc_truncate",
@@ -90,6 +90,7 @@ def lib():
         raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
     L = ctypes.CDLL(LIB_PATH)
     L.mpc_ctx_create.argtypes = [POINTER(c_void_p), c_int, c_int]
+    L.mpc_ctx_create_single_queue.argtypes = [POINTER(c_void_p), c_int, c_int]
     L.mpc_ctx_destroy.argtypes = [c_void_p]
     L.mpc_ctx_set_adder.argtypes = [c_void_p, c_int]
     L.mpc_add.argtypes = [c_void_p, CShare, CShare, CShare, c_size_t]
@@ -358,13 +359,14 @@ def set_gemm_small_tile(max_steps: int = 16, min_tiles: int = 512):
 class Lane:
     """One execution lane: a library context plus a grow-only workspace."""
 
-    def __init__(self, device: int = 0, frac_bits: int = 16):
+    def __init__(self, device: int = 0, frac_bits: int = 16, single_queue: bool = False):
         if not torch.cuda.is_available():
             raise RuntimeError("mpcpipe needs a GPU: no HIP device is visible")
         self.device = torch.device("cuda", device)
         self._h = c_void_p()
         self._pending = []           # tensors the enqueued calls still use (see _note); released by sync()
-        self._check(lib().mpc_ctx_create(byref(self._h), device, frac_bits))
+        create = lib().mpc_ctx_create_single_queue if single_queue else lib().mpc_ctx_create
+        self._check(create(byref(self._h), device, frac_bits))
         self._ws = None
         self._ws_bytes = 0
 
@@ -508,18 +510,18 @@ class Lane:
     def _planes(self, nbytes):
         return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=self.device)
 
-    def prepare_matmul(self, a, b, f_public, flags=0, left=True):
-        """Returns (right_planes, left_planes or None) for beaver_matmul_prepared."""
+    def prepare_matmul(self, a, b, f_public, flags=0, left=True, right=True):
+        """Returns (right_planes or None, left_planes or None) for beaver_matmul_prepared."""
         shp = a[0].shape
         batch = 1 if len(shp) == 2 else shp[0]
         M, K = (shp[-1], shp[-2]) if flags & MPC_TRANS_X else (shp[-2], shp[-1])
         N = b[0].shape[-2] if flags & MPC_TRANS_Y else b[0].shape[-1]
         r, l = c_size_t(), c_size_t()
         self._check(lib().mpc_matmul_prepared_bytes(M, K, N, batch, byref(r), byref(l)))
-        right = self._planes(r.value); lp = self._planes(l.value) if left else None
-        self._check(lib().mpc_matmul_prepare(self._h, _share(a), _share(b), _p64(f_public), right.data_ptr(),
+        rp = self._planes(r.value) if right else None; lp = self._planes(l.value) if left else None
+        self._check(lib().mpc_matmul_prepare(self._h, _share(a), _share(b), _p64(f_public), rp.data_ptr() if right else None,
                                              lp.data_ptr() if left else None, M, K, N, batch, flags))
-        return right, lp
+        return rp, lp
 
     def beaver_matmul_prepared(self, x, a, c, right, left=None, n_chunks=1, flags=MPC_TRUNCATE, out=None):
         shp = a[0].shape
@@ -566,14 +568,14 @@ class Lane:
                                           B, H, W, Cin, Cout, KH, KW, pad, stride))
         return out
 
-    def prepare_conv2d(self, a, b, f_public, pad, stride, left=True):
+    def prepare_conv2d(self, a, b, f_public, pad, stride, left=True, right=True):
         B, H, W, Cin = a[0].shape; KH, KW, _, Cout = b[0].shape
         r, l = c_size_t(), c_size_t()
         self._check(lib().mpc_conv2d_prepared_bytes(B, H, W, Cin, Cout, KH, KW, pad, stride, byref(r), byref(l)))
-        right = self._planes(r.value); lp = self._planes(l.value) if left else None
-        self._check(lib().mpc_conv2d_prepare(self._h, _share(a), _share(b), _p64(f_public), right.data_ptr(),
+        rp = self._planes(r.value) if right else None; lp = self._planes(l.value) if left else None
+        self._check(lib().mpc_conv2d_prepare(self._h, _share(a), _share(b), _p64(f_public), rp.data_ptr() if right else None,
                                              lp.data_ptr() if left else None, B, H, W, Cin, Cout, KH, KW, pad, stride))
-        return right, lp
+        return rp, lp
 
     def conv2d_prepared(self, x, a, c, right, left, KH, KW, pad, stride, n_chunks=1, flags=MPC_TRUNCATE, out=None):
         B, H, W, Cin = a[0].shape; Cout = c[0].shape[-1]

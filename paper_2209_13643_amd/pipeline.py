@@ -214,6 +214,70 @@ def forward_interlinear(lane: mpc.Lane, wlane: mpc.Lane, layers, states, x, keep
     return x
 
 
+class ChunkedLinear:
+    """One secure linear layer with real overlap inside the layer (Alg. 3, Sec. 4.1): the input's rows (images of a
+    convolution, rows of a dense layer) are cut into chunks, and chunk k runs as a folded prepared call on
+    lanes[k % len(lanes)].  A Beaver product is separable over the rows of its left operand, so every chunk is a
+    complete call on its slices of x, a and c (the right-operand planes are shared), and the output words are those
+    of the one-call layer; while one lane's call is in its MFMA-bound GEMM, the other lane's call masks, exchanges
+    and recodes its chunk, which is HBM-bound.  Slices along the leading dimension are contiguous: nothing is copied.
+
+    Offline (constructor): the right-operand planes once, and per chunk the planes of its a_1 rows; the folded addend
+    c_0 - a_0 b_0 is formed for the whole layer and sliced."""
+
+    def __init__(self, lanes, L, st: LayerState, n_chunks: int = 2):
+        self.lanes, self.L, self.conv = list(lanes), L, isinstance(L, synth.Conv)
+        rows = st.a[0].shape[0]
+        if not self.conv and st.a[0].dim() != 2:
+            raise ValueError("batched products are already many independent calls: run them on lanes as they are")
+        if n_chunks < 1 or n_chunks > rows:
+            raise ValueError("between one chunk and one chunk per row")
+        l0 = self.lanes[0]
+        if self.conv:
+            self.right, _ = l0.prepare_conv2d(st.a, st.b, st.f_public, L.pad, L.stride, left=False)
+            c0f = l0.fold_conv2d(st.a, st.b, st.c, L.pad, L.stride)
+        else:
+            self.right, _ = l0.prepare_matmul(st.a, st.b, st.f_public, left=False)
+            c0f = l0.fold_matmul(st.a, st.b, st.c)
+        self.c = (c0f, st.c[1])
+        self.bounds = [rows * k // n_chunks for k in range(n_chunks + 1)]
+        self.a, self.left = [], []
+        for k in range(n_chunks):
+            sl = slice(self.bounds[k], self.bounds[k + 1])
+            a = (st.a[0][sl], st.a[1][sl])
+            ln = self.lanes[k % len(self.lanes)]
+            if self.conv:
+                _, lp = ln.prepare_conv2d(a, st.b, None, L.pad, L.stride, right=False)
+            else:
+                _, lp = ln.prepare_matmul(a, st.b, None, right=False)
+            self.a.append(a); self.left.append(lp)
+        for ln in self.lanes:
+            ln.sync()
+
+    def __call__(self, x, out, after: mpc.Lane | None = None, flags=mpc.MPC_TRUNCATE):
+        """Issue all chunks; `out` = (z_0, z_1) of the whole layer's shape.  `after`: the lane that produced x (every
+        chunk lane waits for it on the device).  Call join() on the lane that consumes `out`."""
+        L = self.L
+        for ln in self.lanes if after is not None else ():
+            if ln is not after:
+                ln.wait_for(after)
+        for k, (a, lp) in enumerate(zip(self.a, self.left)):
+            sl = slice(self.bounds[k], self.bounds[k + 1])
+            ln = self.lanes[k % len(self.lanes)]
+            xs, cs, zs = (x[0][sl], x[1][sl]), (self.c[0][sl], self.c[1][sl]), (out[0][sl], out[1][sl])
+            if self.conv:
+                ln.conv2d_prepared(xs, a, cs, self.right, lp, L.KH, L.KW, L.pad, L.stride, flags=flags | mpc.MPC_FOLDED, out=zs)
+            else:
+                ln.beaver_matmul_prepared(xs, a, cs, self.right, lp, flags=flags | mpc.MPC_FOLDED, out=zs)
+        return out
+
+    def join(self, consumer: mpc.Lane):
+        """The consumer's next call waits (on the device) for every chunk lane."""
+        for ln in self.lanes:
+            if ln is not consumer:
+                consumer.wait_for(ln)
+
+
 def forward_pipelined(lanes, layers, states_per_mb, xs, keep: list, outs_per_mb=None, **kw):
     """Inter-batch pipeline: micro-batch m on lanes[m]; layer-major issue order."""
     cur = list(xs)

@@ -431,3 +431,45 @@ def test_vgg16_training_step_with_three_parties(mods, packed_relu):
         want_w = tuple(st["w"][i] - step[i].reshape(st["w"][i].shape) for i in range(3))
         check3(states[li].w, want_w, f"updated weights of layer {li} ({L.name})")
     lane.close()
+
+
+# ------------------------------------------------ one layer as row chunks on two lanes (Alg. 3 inside a layer)
+@pytest.mark.parametrize("kind,n_chunks,n_lanes", [("dense", 2, 2), ("dense", 3, 2), ("dense", 5, 1), ("conv", 2, 2), ("conv", 3, 3),
+                                                   ("conv-strided", 2, 2)])
+def test_layer_as_row_chunks_on_lanes(mods, kind, n_chunks, n_lanes):
+    """Every chunk is a complete folded call on its rows; the assembled output is the one-call layer's, word for word
+    against the oracle's Alg. 1 / Eq. 3 on the whole layer."""
+    from helpers import deal_conv, deal_matmul, oracle_conv, oracle_matmul
+    mpc, pipeline = mods
+    import torch
+    print(f"chunked layer {kind} chunks={n_chunks} lanes={n_lanes}", flush=True)
+    rng = np.random.default_rng(311 + n_chunks)
+    if kind == "dense":
+        L = synth.Gemm("fc", 203, 150, 77, 1.0, 0.1, 1, False)
+        d = deal_matmul(rng, L.M, L.K, L.N); want = oracle_matmul(d)
+    else:
+        stride = 2 if kind == "conv-strided" else 1
+        L = synth.Conv("conv", 5, 9, 8, 20, 33, 3, 3, 1, stride, 1.0, 0.1, False, False)
+        d = deal_conv(rng, L.B, L.H, L.W, L.Cin, L.Cout, L.KH, L.KW, L.pad, L.stride); want = oracle_conv(d)
+    up = lambda pair: (mpc.to_device(pair[0]), mpc.to_device(pair[1]))
+    st = pipeline.LayerState(w=up(d["y"]), a=up(d["a"]), b=up(d["b"]), c=up(d["c"]),
+                             f_public=mpc.to_device((d["y"][0] - d["b"][0]) + (d["y"][1] - d["b"][1])))
+    lanes = [mpc.Lane(0, single_queue=True) for _ in range(n_lanes)]
+    for ln in lanes:
+        ln.set_exchange("put")
+    consumer = mpc.Lane(0)
+    layer = pipeline.ChunkedLinear(lanes, L, st, n_chunks=n_chunks)
+    x = up(d["x"])
+    out = (torch.empty_like(st.c[0]), torch.empty_like(st.c[1]))
+    for rep in range(2):                      # the second pass reuses every buffer
+        layer(x, out)
+        layer.join(consumer)
+        got = consumer.open(out)              # issued on the consumer's queue: waits for the chunk lanes on the device
+        consumer.sync()
+        assert np.array_equal(mpc.to_host(got), want[0] + want[1])
+        for i in range(2):
+            assert np.array_equal(mpc.to_host(out[i]), want[i]), f"party {i}, pass {rep}"
+    with pytest.raises(ValueError):
+        pipeline.ChunkedLinear(lanes, L, st, n_chunks=0)
+    for ln in lanes + [consumer]:
+        ln.sync(); ln.close()
