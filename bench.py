@@ -423,6 +423,14 @@ def config1_leg(steps, warmup, pmc_summary):
                  "ms_one_call": one_ms, "ms_two_chunks_two_lanes": two_ms, "speedup": one_ms / two_ms,
                  "call_frac_of_int8_peak_one_call": INT8_OPS_PER_SECURE_MAC * M * K * N / (one_ms * 1e-3) / 1e12 / INT8_PEAK_TOPS,
                  "call_frac_of_int8_peak_two_chunks": INT8_OPS_PER_SECURE_MAC * M * K * N / (two_ms * 1e-3) / 1e12 / INT8_PEAK_TOPS}
+    # what the matrix cores sustain on register-resident operands in the GEMM's instruction order, measured now (the
+    # chip is power-limited: uniformly random digits, which is what shares are, hold a lower clock than constant operands)
+    zero_tops, rand_tops = lane.mfma_rate(False) / 1e12, lane.mfma_rate(True) / 1e12
+    kern_exec = INT8_OPS_PER_SECURE_MAC * 0.75 * M * K * N / (seq["step_mode"]["gemm_kernel"]["mean_ms"] * 1e-3) / 1e12
+    ceiling = {"what": "mpc_mfma_rate: 72 v_mfma_i32_32x32x32_i8 per K step on register operands, one wave per SIMD, no memory "
+                       "traffic, 10 launches of 2000 steps",
+               "zero_operands_tops": zero_tops, "random_operands_tops": rand_tops,
+               "gemm_launch_executed_tops": kern_exec, "gemm_launch_frac_of_random_operand_ceiling": kern_exec / rand_tops}
     # sanity on the results of the last steps: same shares from all three conv calls, ReLU of the reconstructed output exactly
     assert torch.equal(z[0], zf[0]) and torch.equal(z[1], zf[1]), "folded / prepared convolution differs from the plain call"
     rec_z = z[0] + z[1]
@@ -490,8 +498,7 @@ def config1_leg(steps, warmup, pmc_summary):
                            "note": "mpc_conv2d: every digit plane recoded inside the call, copy exchange, four ring products",
                            "traffic": traffic4},
             "traffic": traffic,
-            "note": "power-limited attainable rate with random int8 operands measured on this chip with a back-to-back "
-                    "MFMA loop is about 3070 TOP/s"},
+            "measured_ceiling": ceiling},
         "roofline_relu": {
             "kernel": "secure ReLU chain on whole words, exchange by remote store: k_relu_stage<0..9, put> (both parties per launch) "
                       "+ k_wire_words<1> for the A2B masks",

@@ -234,6 +234,16 @@ int mpc_conv2d(mpc_ctx* ctx, mpc_cshare x, mpc_cshare w,
  * min_tiles < 1. */
 int mpc_set_gemm_small_tile(int max_steps, int min_tiles);
 
+/* Measurement aid for the roofline of the ring GEMM (no step of the protocol): the int8 matrix-core rate the
+ * device sustains on register-resident operands, in the instruction order of the GEMM's K step, one workgroup of
+ * four waves per compute unit, no memory traffic.  random_operands = 0: all-zero operands; 1: every operand
+ * byte a uniform pseudo-random digit, which is what the digit planes of secret shares look like.  Runs
+ * `launches` launches of `iters` K steps (72 MFMA instructions each per wave) back to back on the lane's first
+ * stream, waits for them (the call blocks) and returns the rate in int8 operations per second (a
+ * multiply-accumulate counts as two).  Needs 4 bytes of workspace per thread launched (compute units x 256 x 4
+ * bytes; MPC_ENOMEM otherwise); MPC_EINVAL for iters outside [1, 2^20] or launches outside [1, 1024]. */
+int mpc_mfma_rate(mpc_ctx* ctx, int random_operands, int iters, int launches, double* int8_ops_per_s);
+
 /* Prepared layers.  The GEMM consumes digit planes; those of the operands that
  * do not depend on the input - the triple's [a_i] on the left, and on the right
  * the opened weight mask f = w - b (Alg. 3 sends it ahead of time), b_0 + f and

@@ -692,6 +692,17 @@ def bench_chunks(L, n_chunks=2, n_lanes=2, reps=20, seed=78):
 
 
 def main(argv):
+    if argv and argv[0] == "mfma":
+        # the matrix cores' sustained int8 rate on register-resident operands (mpc_mfma_rate)
+        lane = mpc.Lane(0, single_queue=True)
+        print("== int8 MFMA rate on register operands (72 x v_mfma_i32_32x32x32_i8 per step, one wave per SIMD, no memory traffic)")
+        for rnd in (False, True, False, True):
+            for iters, launches in ((2000, 10), (2000, 50)):
+                r = lane.mfma_rate(rnd, iters, launches)
+                print(f"  {'uniformly random digits' if rnd else 'all-zero operands      '}  {launches:3d} launches x {iters} steps: "
+                      f"{r / 1e15:.3f} POP/s = {100 * r / INT8_PEAK:.1f}% of 5.0 POP/s", flush=True)
+        lane.close()
+        return
     if argv and argv[0] == "chunks":
         # Alg. 3's overlap inside a layer: row chunks as complete calls on two lanes
         todo = [(1, None), (3, ("qkv", "out", "ffn1", "ffn2")), (4, ("conv2", "conv4", "conv6", "conv9"))]

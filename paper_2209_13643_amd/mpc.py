@@ -64,7 +64,7 @@ EXPORTS = [
     "mpc_maxpool2x2_signs", "mpc_maxpool_backward_workspace_bytes", "mpc_maxpool2x2_backward",
     "mpc_ctx_set_adder", "mpc_ctx_set_exchange", "mpc_ctx_profile_samples", "mpc_add",
     "mpc_matmul_prepared_bytes", "mpc_conv2d_prepared_bytes", "mpc_matmul_prepare", "mpc_conv2d_prepare",
-    "mpc_beaver_matmul_prepared", "mpc_conv2d_prepared", "mpc_beaver_matmul_folded", "mpc_matmul_fold", "mpc_conv2d_fold", "mpc_set_gemm_small_tile",
+    "mpc_beaver_matmul_prepared", "mpc_conv2d_prepared", "mpc_beaver_matmul_folded", "mpc_matmul_fold", "mpc_conv2d_fold", "mpc_set_gemm_small_tile", "mpc_mfma_rate",
     "mpc_ctx_capture_begin", "mpc_ctx_capture_end", "mpc_graph_launch", "mpc_graph_destroy",
     "mpc_open3", "mpc_matmul3_workspace_bytes", "mpc_beaver_matmul3", "mpc_conv2d3_workspace_bytes", "mpc_conv2d3",
     "mpc_truncate3_workspace_bytes", "mpc_truncate3", "mpc_relu3_workspace_bytes", "mpc_relu3",
@@ -106,6 +106,7 @@ def lib():
     L.mpc_conv2d_prepared.argtypes = [c_void_p, CShare, CShare, CShare, CShare, c_void_p, c_void_p] + [c_int] * 11
     L.mpc_beaver_matmul_folded.argtypes = [c_void_p] + [CShare] * 6 + [c_void_p, c_void_p] + [c_int] * 6
     L.mpc_set_gemm_small_tile.argtypes = [c_int, c_int]
+    L.mpc_mfma_rate.argtypes = [c_void_p, c_int, c_int, c_int, POINTER(ctypes.c_double)]
     L.mpc_matmul_fold.argtypes = [c_void_p, _P64, _P64, _P64, _P64] + [c_int] * 5
     L.mpc_conv2d_fold.argtypes = [c_void_p, _P64, _P64, _P64, _P64] + [c_int] * 9
     L.mpc_ctx_profile_samples.argtypes = [c_void_p, c_int, POINTER(ctypes.c_double), c_int, POINTER(c_int)]
@@ -558,6 +559,13 @@ class Lane:
         out = torch.empty_like(c[0])
         self._check(lib().mpc_matmul_fold(self._h, _p64(a[0]), _p64(b[0]), _p64(c[0]), _p64(out), M, K, N, batch, flags))
         return out
+
+    def mfma_rate(self, random_operands: bool, iters: int = 2000, launches: int = 10) -> float:
+        """int8 matrix-core operations per second on register-resident operands (mpc_mfma_rate); blocks."""
+        self.reserve(1 << 20)
+        r = ctypes.c_double()
+        self._check(lib().mpc_mfma_rate(self._h, 1 if random_operands else 0, iters, launches, byref(r)))
+        return r.value
 
     def fold_conv2d(self, a, b, c, pad, stride):
         """Party 0's folded addend c_0 - conv(a_0, b_0) for conv2d_prepared(..., flags | MPC_FOLDED)."""

@@ -606,3 +606,16 @@ def test_profiling_regions(mpc, lane):
     assert lane.profile_samples(mpc.PROF_LINEAR) == []
     assert lane.profile(mpc.PROF_LINEAR) == (0.0, 0)
     assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "result unaffected by profiling")
+
+
+def test_mfma_rate_measurement_aid(mpc):
+    """The roofline's measurement aid runs, ends, and reports a plausible rate: some POP/s, and not more for random
+    digits than for constant operands (the chip holds a lower clock when operand bits toggle)."""
+    print("mfma rate", flush=True)
+    lane = mpc.Lane(0, single_queue=True)
+    zero = lane.mfma_rate(False, iters=500, launches=4)
+    rand = lane.mfma_rate(True, iters=500, launches=4)
+    assert 0.5e15 < rand <= 1.05 * zero < 6e15, (zero, rand)
+    with pytest.raises(mpc.MpcError):
+        lane.mfma_rate(True, iters=0)
+    lane.close()
