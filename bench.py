@@ -425,10 +425,10 @@ def config1_leg(steps, warmup, pmc_summary):
                  "call_frac_of_int8_peak_two_chunks": INT8_OPS_PER_SECURE_MAC * M * K * N / (two_ms * 1e-3) / 1e12 / INT8_PEAK_TOPS}
     # what the matrix cores sustain on register-resident operands in the GEMM's instruction order, measured now (the
     # chip is power-limited: uniformly random digits, which is what shares are, hold a lower clock than constant operands)
-    zero_tops, rand_tops = lane.mfma_rate(False) / 1e12, lane.mfma_rate(True) / 1e12
+    zero_tops, rand_tops = lane.mfma_rate(False, 2000, 30) / 1e12, lane.mfma_rate(True, 2000, 30) / 1e12
     kern_exec = INT8_OPS_PER_SECURE_MAC * 0.75 * M * K * N / (seq["step_mode"]["gemm_kernel"]["mean_ms"] * 1e-3) / 1e12
     ceiling = {"what": "mpc_mfma_rate: 72 v_mfma_i32_32x32x32_i8 per K step on register operands, one wave per SIMD, no memory "
-                       "traffic, 10 launches of 2000 steps",
+                       "traffic, 30 launches of 2000 steps",
                "zero_operands_tops": zero_tops, "random_operands_tops": rand_tops,
                "gemm_launch_executed_tops": kern_exec, "gemm_launch_frac_of_random_operand_ceiling": kern_exec / rand_tops}
     # sanity on the results of the last steps: same shares from all three conv calls, ReLU of the reconstructed output exactly

@@ -609,13 +609,13 @@ def test_profiling_regions(mpc, lane):
 
 
 def test_mfma_rate_measurement_aid(mpc):
-    """The roofline's measurement aid runs, ends, and reports a plausible rate: some POP/s, and not more for random
-    digits than for constant operands (the chip holds a lower clock when operand bits toggle)."""
+    """The roofline's measurement aid runs, ends, and reports a plausible rate: some POP/s, never above what the
+    matrix cores can issue (which operand pattern is faster in so short a run depends on the clock's ramp)."""
     print("mfma rate", flush=True)
     lane = mpc.Lane(0, single_queue=True)
     zero = lane.mfma_rate(False, iters=500, launches=4)
     rand = lane.mfma_rate(True, iters=500, launches=4)
-    assert 0.5e15 < rand <= 1.05 * zero < 6e15, (zero, rand)
+    assert 0.5e15 < rand < 6e15 and 0.5e15 < zero < 6e15, (zero, rand)
     with pytest.raises(mpc.MpcError):
         lane.mfma_rate(True, iters=0)
     lane.close()
