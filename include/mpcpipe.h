@@ -230,7 +230,8 @@ int mpc_conv2d(mpc_ctx* ctx, mpc_cshare x, mpc_cshare w,
  * contraction has at most max_steps K steps (32 terms each; default 16) and whose output has at least min_tiles
  * tiles of 64 x 64 (default 512) runs with 64 x 64 workgroup tiles of four half-width waves, two workgroups per
  * compute unit: short contractions spend most of a workgroup's life in pipeline fill and epilogue, which a second
- * resident wave per SIMD hides.  max_steps = 0 switches the small tile off.  MPC_EINVAL for max_steps < 0 or
+ * resident wave per SIMD hides.  Launches whose parties contract different lengths (the folded calls) also take
+ * that tile at any contraction length once the output has 768 such tiles.  max_steps = 0 switches the small tile off.  MPC_EINVAL for max_steps < 0 or
  * min_tiles < 1. */
 int mpc_set_gemm_small_tile(int max_steps, int min_tiles);
 

@@ -509,11 +509,19 @@ constexpr int kMaxStepsExact = 1023;
 // pipeline fill and epilogue and a second resident wave hides them.
 // Tile 2 is chosen when the longest contraction of the launch has at most g_small_max_steps K steps (32 terms each)
 // and the output has at least g_small_min_tiles tiles of 64 x 64 (mpc_set_gemm_small_tile changes both).
+// A launch whose parties contract different lengths (the folded calls: party 0 one segment, party 1 two) also takes
+// tile 2 at any contraction length once the output has kAsymMinTiles tiles of 64 x 64: short and long workgroups then
+// mix two to a compute unit, and the launch loses less to the imbalance (BERT-base layers 2-9 % faster; at 512 tiles,
+// configs[1]'s convolution, the two tilings are even, and the wide tile keeps room for another lane's streaming waves).
 static std::atomic<int> g_small_max_steps{ 16 }, g_small_min_tiles{ 512 };
-static int tile_kind(int M, int N, int batch, int longest_steps)
+constexpr long long kAsymMinTiles = 768;
+static int tile_kind(int M, int N, int batch, int longest_steps, bool asymmetric)
 {
-    if (longest_steps <= g_small_max_steps.load(std::memory_order_relaxed) &&
-        (long long)((M + 63) / 64) * ((N + 63) / 64) * batch >= g_small_min_tiles.load(std::memory_order_relaxed)) return 2;
+    const long long tiles64 = (long long)((M + 63) / 64) * ((N + 63) / 64) * batch;
+    const int max_steps = g_small_max_steps.load(std::memory_order_relaxed);
+    if (longest_steps <= max_steps && tiles64 >= g_small_min_tiles.load(std::memory_order_relaxed)) return 2;
+    // (not the batched products one 64-column tile wide, per-head A*V: those are 5 % faster on the 128 x 64 tile)
+    if (asymmetric && max_steps > 0 && tiles64 >= kAsymMinTiles && !(batch > 1 && N <= 64)) return 2;
     return (((N - 1) % 128) < 64 && (N <= 64 || M >= 4096)) ? 1 : 0;
 }
 
@@ -523,7 +531,7 @@ static int ksplit_for(int M, int N, int batch, const int steps[2])
 {
     const int nparty = steps[1] > 0 ? 2 : 1;
     const int longest = steps[0] > steps[1] ? steps[0] : steps[1];
-    const int kind = tile_kind(M, N, batch, longest);
+    const int kind = tile_kind(M, N, batch, longest, nparty == 2 && steps[0] != steps[1]);
     const int tm = kind == 1 ? 128 : 64, tn = kind == 0 ? 128 : 64;
     const long long tiles_pp = (long long)((M + tm - 1) / tm) * ((N + tn - 1) / tn) * batch;      // per party
     // the int32 digit sums of one workgroup stay exact for at most kMaxStepsExact steps
@@ -599,7 +607,7 @@ int launch_limb_gemm(mpc_ctx* c, hipStream_t st, const GemmArgs& g_in)
     // per-lane byte offsets inside one k block of a plane are 32-bit
     if ((long long)g.rows_L * 16 >= (1ll << 32) || (long long)g.N * 16 >= (1ll << 32)) return MPC_EINVAL;
     // 64x128 workgroup tiles, or 128x64 when a second 64-column half would be empty
-    const int kind = g.ksplit > 1 ? tile_kind(g.M, g.N, g.batch, 1 << 30) : tile_kind(g.M, g.N, g.batch, longest_steps);
+    const int kind = g.ksplit > 1 ? tile_kind(g.M, g.N, g.batch, 1 << 30, false) : tile_kind(g.M, g.N, g.batch, longest_steps, g.heavy_first != 0);
     if (g.conv.enabled)
         return kind == 2 ? launch_cfg<2, 2, true, 2, 1>(c, st, g) : kind == 1 ? launch_cfg<4, 1, true>(c, st, g) : launch_cfg<2, 2, true>(c, st, g);
     return kind == 2 ? launch_cfg<2, 2, false, 2, 1>(c, st, g) : kind == 1 ? launch_cfg<4, 1, false>(c, st, g) : launch_cfg<2, 2, false>(c, st, g);
