@@ -303,7 +303,6 @@ void k_limb_gemm(GemmArgs g)
                        : g.out[party] + (size_t)bidx * g.out_bstride;
     const int rbase = m0 + wm * 32 + g2 * 4;
     const int shift = partial ? 0 : g.trunc_bits;
-    const u64 neg = (party != 0 && shift != 0) ? ~(u64)0 : 0;       // two's-complement negation as (z ^ neg) - neg
     const bool interior = m0 + C::TM <= g.M && n0 + C::TN <= g.N;   // uniform: no per-word bounds checks
     u64 addw[NH][16];
     auto load_addend = [&]() {
@@ -408,21 +407,30 @@ void k_limb_gemm(GemmArgs g)
         // 256 accumulator registers into vector registers at the loop exit, which leaves no
         // room for anything else to stay live across the main loop); the two column halves
         // are fenced from each other, inside a half the 16 words are independent chains.
-        // Local truncation without a branch: party 1 negates before and after the shift.
+        // Recombination sum_s acc_s 2^(8s) mod 2^64 in 32-bit pieces: the digit sums of weights 0..3 add up exactly
+        // as 64-bit terms built from two shifts each; of weights 4..7 only the low 32 bits reach the result, and
+        // those land in the high word.
         u64 z[16];
         static_for<16>([&](auto vt) {
             constexpr int v = decltype(vt)::value;
-            u64 acc64 = 0;
+            int d[8];
             static_for<8>([&](auto st) {
-                constexpr int sg = 7 - decltype(st)::value;
-                int d;
-                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(d) : "a"(acc[c][sg][v]));
-                acc64 = (acc64 << 8) + (u64)(long long)d;
+                constexpr int sg = decltype(st)::value;
+                int t;
+                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(acc[c][sg][v]));
+                d[sg] = t;
             });
+            u64 acc64 = (u64)(long long)d[0];
+#pragma unroll
+            for (int sg = 1; sg < 4; ++sg)
+                acc64 += (u64)((unsigned)d[sg] << (8 * sg)) | ((u64)(unsigned)(d[sg] >> (32 - 8 * sg)) << 32);
+            const unsigned high = (unsigned)d[4] + ((unsigned)d[5] << 8) + ((unsigned)d[6] << 16) + ((unsigned)d[7] << 24);
+            acc64 += (u64)high << 32;
             acc64 += add[v];
-            acc64 = (acc64 ^ neg) - neg;
-            acc64 >>= shift;
-            z[v] = (acc64 ^ neg) - neg;
+            // local truncation (party is uniform over the workgroup): party 0 shifts, party 1 negates around the shift
+            if (shift == 0)      z[v] = acc64;
+            else if (party == 0) z[v] = acc64 >> shift;
+            else                 z[v] = (u64)0 - (((u64)0 - acc64) >> shift);
         });
         if (interior) {
 #pragma unroll
