@@ -403,8 +403,9 @@ int mpc_relu(mpc_ctx* ctx, mpc_cshare x, const mpc_relu_material* mat, mpc_share
  * allocation and opens no timing region (mpc_ctx_profile never counts it).
  *   n <= mpc_relu_static_max_n() (65536), else MPC_ERANGE; the array takes
  *   about 14.4 MiB on every device the library runs on, until the process ends.
- *   The context must come from mpc_ctx_create (which resolves the array's
- *   device address for the context's device), else MPC_EINVAL.
+ *   The context must come from mpc_ctx_create or mpc_ctx_create_single_queue
+ *   (which resolve the array's device address for the context's device), else
+ *   MPC_EINVAL.
  *   All calls on one device share the array, which keeps the previous call's
  *   contents (every word read is first written by the same call, so nothing
  *   needs clearing): calls that overlap on a device, on any lane, race.
