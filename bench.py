@@ -298,6 +298,15 @@ def per_config_table(args):
              "plain_calls": {"ms_beaver_calls": call, "ms_gemm_kernels": kern, "secure_macs_per_s": macs / (call * 1e-3),
                              "call_frac_of_int8_peak": f(call), "kernel_frac_of_int8_peak": f(kern),
                              "executed_int8_ops_per_secure_mac": 288}}
+        if idx > 0:
+            # wall clock of back-to-back layers (no ReLU between): one call per layer, and the better of one call and two
+            # row chunks on two lanes (Alg. 3's overlap inside a layer; the runner picks per layer)
+            ov = bench_configs.bench_config_overlap(idx)
+            one = sum(r["one_call_ms"] for r in ov); best = sum(min(r["one_call_ms"], r["two_chunks_ms"]) for r in ov)
+            e["folded_calls_back_to_back_wall_clock"] = {
+                "ms_one_call_per_layer": one, "call_frac_of_int8_peak_one_call": f(one),
+                "ms_best_of_one_call_and_two_chunks_on_two_lanes": best, "call_frac_of_int8_peak_best": f(best),
+                "layers_faster_as_two_chunks": [r["layer"] for r in ov if r["two_chunks_ms"] < r["one_call_ms"]]}
         rl = [r for r in rows if "relu_ms" in r]
         if rl:
             n = sum(r["relu_n"] for r in rl)

@@ -641,7 +641,38 @@ def bench_hbm_copy(reps: int = 20):
     return rows
 
 
-def bench_chunks(L, n_chunks=2, n_lanes=2, reps=20, seed=78):
+def bench_config_overlap(idx, reps=10):
+    """Every linear layer of a workload as back-to-back folded calls, wall clock: one call per layer, and the better of
+    one call and two row chunks on two lanes (pipeline.ChunkedLinear).  Products of two shares (batched, per-head) are
+    already many independent products and run as one mpc_beaver_matmul_folded call in both columns."""
+    rows = []
+    for L in synth.CONFIGS[idx]().layers:
+        if not isinstance(L, synth.Conv) and L.batch > 1:
+            lane = mpc.Lane(0, single_queue=True); lane.set_exchange("put")
+            g = dealer.gen(synth.BASE_SEED + 90 + idx, lane.device)
+            d = dealer.matmul_layer(lane, g, L.M, L.K, L.N, L.x_std, L.w_std, batch=L.batch)
+            right, left = lane.prepare_matmul(d["a"], d["b"], None)
+            cf = (lane.fold_matmul(d["a"], d["b"], d["c"]), d["c"][1])
+            z = (torch.empty_like(d["c"][0]), torch.empty_like(d["c"][1]))
+            ts = []
+            for _ in range(3):
+                for _ in range(3):
+                    lane.beaver_matmul_folded(d["x"], d["w"], d["a"], d["b"], cf, right, left, out=z)
+                lane.sync(); t0 = time.perf_counter()
+                for _ in range(reps):
+                    lane.beaver_matmul_folded(d["x"], d["w"], d["a"], d["b"], cf, right, left, out=z)
+                lane.sync(); ts.append((time.perf_counter() - t0) * 1e3 / reps)
+            lane.close()
+            one_ms = two_ms = sorted(ts)[1]
+        else:
+            one_ms, two_ms, same = bench_chunks(L, 2, 2, reps=reps, rounds=3)
+            if not same:
+                raise RuntimeError(f"{L.name}: the layer as two chunks differs from the one-call layer")
+        rows.append(dict(layer=L.name, macs=layer_macs(L), one_call_ms=one_ms, two_chunks_ms=two_ms))
+    return rows
+
+
+def bench_chunks(L, n_chunks=2, n_lanes=2, reps=20, seed=78, rounds=5):
     """One layer as a single folded prepared call and as row chunks on lanes (pipeline.ChunkedLinear): wall clock of
     back-to-back layers, remote-store exchange; the outputs must be the same words."""
     from . import pipeline
@@ -681,10 +712,10 @@ def bench_chunks(L, n_chunks=2, n_lanes=2, reps=20, seed=78):
 
     # the chip's clock under a series of GEMMs depends on what ran just before: alternate the two forms, take medians
     ones, manys = [], []
-    for _ in range(5):
+    for _ in range(rounds):
         ones.append(wall(one, [l0]))
         manys.append(wall(lambda: chunked(d["x"], zc), lanes))
-    one_ms, many_ms = sorted(ones)[2], sorted(manys)[2]
+    one_ms, many_ms = sorted(ones)[rounds // 2], sorted(manys)[rounds // 2]
     same = torch.equal(z[0], zc[0]) and torch.equal(z[1], zc[1])
     for ln in lanes:
         ln.close()
