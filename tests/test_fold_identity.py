@@ -48,3 +48,19 @@ def test_fold_is_not_symmetric_for_free():
     folded1 = (d["c"][1] - oracle.ring_matmul(d["a"][1], d["b"][1])) + oracle.ring_matmul(d["a"][1] + E, d["b"][1] + F)
     assert np.array_equal(folded1 - oracle.ring_matmul(E, F), z[1])
     assert not np.array_equal(folded1, z[1])
+
+
+def test_beaver_product_is_separable_over_rows():
+    """What the row-chunked layer rests on: Alg. 1 / Eq. 3 on a slice of the left operand's rows (images), with the
+    same slices of a and c and the whole right operand, gives the same slice of every output share."""
+    d = deal_matmul(np.random.default_rng(41), 11, 7, 5)
+    z = oracle.beaver_matmul(d["x"], d["y"], d["a"], d["b"], d["c"])
+    for lo, hi in ((0, 4), (4, 11), (10, 11)):
+        cut = lambda k: (d[k][0][lo:hi], d[k][1][lo:hi])
+        zs = oracle.beaver_matmul(cut("x"), d["y"], cut("a"), d["b"], cut("c"))
+        assert np.array_equal(zs[0], z[0][lo:hi]) and np.array_equal(zs[1], z[1][lo:hi])
+    d = deal_conv(np.random.default_rng(42), 3, 5, 6, 2, 3, 3, 3, 1, 1)
+    z = oracle.beaver_conv2d(d["x"], d["y"], d["a"], d["b"], d["c"], d["pad"], d["stride"])
+    cut = lambda k: (d[k][0][1:3], d[k][1][1:3])
+    zs = oracle.beaver_conv2d(cut("x"), d["y"], cut("a"), d["b"], cut("c"), d["pad"], d["stride"])
+    assert np.array_equal(zs[0], z[0][1:3]) and np.array_equal(zs[1], z[1][1:3])
