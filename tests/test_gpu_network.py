@@ -434,9 +434,10 @@ def test_vgg16_training_step_with_three_parties(mods, packed_relu):
 
 
 # ------------------------------------------------ one layer as row chunks on two lanes (Alg. 3 inside a layer)
+@pytest.mark.parametrize("lane_kind", ["single-queue-put", "three-streams"])
 @pytest.mark.parametrize("kind,n_chunks,n_lanes", [("dense", 2, 2), ("dense", 3, 2), ("dense", 5, 1), ("conv", 2, 2), ("conv", 3, 3),
                                                    ("conv-strided", 2, 2)])
-def test_layer_as_row_chunks_on_lanes(mods, kind, n_chunks, n_lanes):
+def test_layer_as_row_chunks_on_lanes(mods, kind, n_chunks, n_lanes, lane_kind):
     """Every chunk is a complete folded call on its rows; the assembled output is the one-call layer's, word for word
     against the oracle's Alg. 1 / Eq. 3 on the whole layer."""
     from helpers import deal_conv, deal_matmul, oracle_conv, oracle_matmul
@@ -454,9 +455,12 @@ def test_layer_as_row_chunks_on_lanes(mods, kind, n_chunks, n_lanes):
     up = lambda pair: (mpc.to_device(pair[0]), mpc.to_device(pair[1]))
     st = pipeline.LayerState(w=up(d["y"]), a=up(d["a"]), b=up(d["b"]), c=up(d["c"]),
                              f_public=mpc.to_device((d["y"][0] - d["b"][0]) + (d["y"][1] - d["b"][1])))
-    lanes = [mpc.Lane(0, single_queue=True) for _ in range(n_lanes)]
-    for ln in lanes:
-        ln.set_exchange("put")
+    if lane_kind == "three-streams":
+        lanes = [mpc.Lane(0) for _ in range(n_lanes)]
+    else:
+        lanes = [mpc.Lane(0, single_queue=True) for _ in range(n_lanes)]
+        for ln in lanes:
+            ln.set_exchange("put")
     consumer = mpc.Lane(0)
     layer = pipeline.ChunkedLinear(lanes, L, st, n_chunks=n_chunks)
     x = up(d["x"])
