@@ -68,6 +68,10 @@ def test_null_context_is_rejected(lib):
     assert lib.mpc_ctx_create(None, 0, 16) == -1
     h = ctypes.c_void_p()
     assert lib.mpc_ctx_create(ctypes.byref(h), 0, 99) == -1              # frac_bits out of range
+    assert lib.mpc_ctx_create_single_queue(None, 0, 16) == -1
+    assert lib.mpc_ctx_create_single_queue(ctypes.byref(h), 0, -1) == -1
+    r = ctypes.c_double()
+    assert lib.mpc_mfma_rate(None, 1, 100, 1, ctypes.byref(r)) == -1
 
 
 def test_packed_triple_layout_size(lib):
