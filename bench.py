@@ -156,10 +156,12 @@ class Net:
     def graphs(self):
         """One recorded graph per lane (the whole micro-batch forward), replayed on its lane."""
         gs = []
+        self.pipeline.share_cache(self.lanes)           # the graphs run four at a time
         for m, ln in enumerate(self.lanes):
             with ln.capture() as cap:
                 self.pipeline.forward(ln, self.layers, self.states[m], self.xs[m], [], outs=self.outs[m])
             gs.append(cap.graph)
+        self.pipeline.share_cache(self.lanes, False)
         return gs
 
     def close(self):

@@ -395,6 +395,13 @@ int mpc_relu(mpc_ctx* ctx, mpc_cshare x, const mpc_relu_material* mat, mpc_share
              size_t n, int n_chunks,
              uint8_t* const s_bit[2], uint64_t* const s_arith[2]);
 
+/* Chunk size that n_chunks = 0 picks on this lane (results never depend on it): elements per chunk for mpc_relu /
+ * mpc_maxpool2x2 and for the packed chain of mpc_relu_msb; 0 = the library's default (2^20 / 2^22).  A chunk's
+ * exchanged words and carried state should still be in the last-level cache when the next round reads them; with
+ * several lanes converting at once (Sec. 4.3: one lane per micro-batch) each lane has a share of that cache only, and
+ * a runner gives its lanes the default divided by their number.  MPC_EINVAL below 1024 elements (other than 0). */
+int mpc_ctx_set_relu_chunk(mpc_ctx* ctx, size_t whole_word_elems, size_t packed_elems);
+
 /* mpc_relu for callers that cannot allocate device memory or own a workspace
  * (code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc): same arguments, same shares, but the rounds' exchange buffers

@@ -29,6 +29,7 @@ struct mpc_ctx {
     int last_hip;
     int adder;               // carry network of mpc_relu / mpc_maxpool2x2: MPC_ADDER_*
     bool exchange_put;       // secure ReLU on a single queue: exchange by remote store instead of copy kernels
+    size_t relu_chunk[2];    // elements per chunk when n_chunks = 0 (whole words, packed chain); 0: the library's default
     bool capturing;          // between mpc_ctx_capture_begin and mpc_ctx_capture_end
     bool profiling;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> prof[3];   // timing event pairs per region kind

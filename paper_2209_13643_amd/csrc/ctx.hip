@@ -12,6 +12,7 @@ static int ctx_create(mpc_ctx** out, int device, int frac_bits, int n_streams)
     if (!c) return MPC_ENOMEM;
     c->device = device; c->frac_bits = frac_bits; c->ev_next = 0;
     c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0; c->profiling = false;
+    c->relu_chunk[0] = c->relu_chunk[1] = 0;
     for (int i = 0; i < 3; ++i) { c->s[i] = nullptr; c->own_stream[i] = false; }
     for (int i = 0; i < kEventPool; ++i) c->ev[i] = nullptr;
     hipError_t e = hipSetDevice(device);

@@ -32,8 +32,9 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kMaxChunks = 64;
-constexpr size_t kAutoChunkElems = (size_t)1 << 20;   // chunk size picked when the caller passes n_chunks = 0
-constexpr size_t kAutoChunkElemsPacked = (size_t)1 << 22;   // the same on the packed path (a third of the bytes per element)
+// chunk size picked when the caller passes n_chunks = 0 and the lane sets none (mpc_ctx_set_relu_chunk)
+constexpr size_t kAutoChunkElems = (size_t)1 << 20;
+constexpr size_t kAutoChunkElemsPacked = (size_t)1 << 22;   // the packed path: a third of the bytes per element
 
 struct alignas(16) u64x2 { u64 a, b; };
 
@@ -701,7 +702,8 @@ int relu_run(mpc_ctx* c, ReluParty (&pp)[2], size_t n, int n_chunks, const MsbGe
     // chunk boundaries: multiples of four elements, and of 256 on the packed path
     // (four whole words of the deepest level)
     const size_t align = geom ? 256 : 4;
-    const size_t auto_elems = geom ? kAutoChunkElemsPacked : kAutoChunkElems;
+    const size_t lane_elems = c->relu_chunk[geom ? 1 : 0];
+    const size_t auto_elems = lane_elems ? lane_elems : geom ? kAutoChunkElemsPacked : kAutoChunkElems;
     if (n_chunks == 0)
         // automatic: about a million elements per chunk on a single queue (the chunk's
         // state then survives in the last-level cache from round to round), one chunk otherwise
@@ -1015,6 +1017,14 @@ int relu_static_setup(mpc_ctx* c)
 }
 
 extern "C" {
+
+int mpc_ctx_set_relu_chunk(mpc_ctx* c, size_t whole_word_elems, size_t packed_elems)
+{
+    if (!c || (whole_word_elems && whole_word_elems < 1024) || (packed_elems && packed_elems < 1024)) return MPC_EINVAL;
+    c->relu_chunk[0] = whole_word_elems; c->relu_chunk[1] = packed_elems;
+    return MPC_OK;
+}
+
 
 size_t mpc_relu_static_max_n(void) { return kStaticMaxN; }
 

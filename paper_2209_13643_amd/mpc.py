@@ -64,7 +64,7 @@ EXPORTS = [
     "mpc_maxpool2x2_signs", "mpc_maxpool_backward_workspace_bytes", "mpc_maxpool2x2_backward",
     "mpc_ctx_set_adder", "mpc_ctx_set_exchange", "mpc_ctx_profile_samples", "mpc_add",
     "mpc_matmul_prepared_bytes", "mpc_conv2d_prepared_bytes", "mpc_matmul_prepare", "mpc_conv2d_prepare",
-    "mpc_beaver_matmul_prepared", "mpc_conv2d_prepared", "mpc_beaver_matmul_folded", "mpc_matmul_fold", "mpc_conv2d_fold", "mpc_set_gemm_small_tile", "mpc_mfma_rate",
+    "mpc_beaver_matmul_prepared", "mpc_conv2d_prepared", "mpc_beaver_matmul_folded", "mpc_matmul_fold", "mpc_conv2d_fold", "mpc_set_gemm_small_tile", "mpc_mfma_rate", "mpc_ctx_set_relu_chunk",
     "mpc_ctx_capture_begin", "mpc_ctx_capture_end", "mpc_graph_launch", "mpc_graph_destroy",
     "mpc_open3", "mpc_matmul3_workspace_bytes", "mpc_beaver_matmul3", "mpc_conv2d3_workspace_bytes", "mpc_conv2d3",
     "mpc_truncate3_workspace_bytes", "mpc_truncate3", "mpc_relu3_workspace_bytes", "mpc_relu3",
@@ -106,6 +106,7 @@ def lib():
     L.mpc_conv2d_prepared.argtypes = [c_void_p, CShare, CShare, CShare, CShare, c_void_p, c_void_p] + [c_int] * 11
     L.mpc_beaver_matmul_folded.argtypes = [c_void_p] + [CShare] * 6 + [c_void_p, c_void_p] + [c_int] * 6
     L.mpc_set_gemm_small_tile.argtypes = [c_int, c_int]
+    L.mpc_ctx_set_relu_chunk.argtypes = [c_void_p, c_size_t, c_size_t]
     L.mpc_mfma_rate.argtypes = [c_void_p, c_int, c_int, c_int, POINTER(ctypes.c_double)]
     L.mpc_matmul_fold.argtypes = [c_void_p, _P64, _P64, _P64, _P64] + [c_int] * 5
     L.mpc_conv2d_fold.argtypes = [c_void_p, _P64, _P64, _P64, _P64] + [c_int] * 9
@@ -441,6 +442,10 @@ class Lane:
     def set_adder(self, name: str):
         """Carry network of relu / maxpool2x2: "kogge-stone" (default) or "tree" (the listing of Sec. 4.2)."""
         self._check(lib().mpc_ctx_set_adder(self._h, {"kogge-stone": 0, "tree": 1}[name]))
+
+    def set_relu_chunk(self, whole_word_elems: int = 0, packed_elems: int = 0):
+        """Elements per chunk of this lane's secure ReLU / max-pool when n_chunks = 0 (0: the library's default)."""
+        self._check(lib().mpc_ctx_set_relu_chunk(self._h, whole_word_elems, packed_elems))
 
     def use_single_queue(self):
         """Issue both parties and the wire on party 0's stream (one in-order queue)."""

@@ -278,13 +278,29 @@ class ChunkedLinear:
                 consumer.wait_for(ln)
 
 
+RELU_CHUNK_ELEMS = 1 << 20      # the library's default chunk of the whole-word conversions (one lane at a time)
+
+
+def share_cache(lanes, on: bool = True):
+    """Lanes that convert at the same time share the last-level cache: give each the default conversion chunk divided
+    by their number (so that a chunk's exchanged words and carried state still fit their share), or restore the
+    default.  Chunking never changes a result."""
+    n = len(lanes)
+    for ln in lanes:
+        ln.set_relu_chunk(max(1 << 16, RELU_CHUNK_ELEMS // n) if on and n > 1 else 0)
+
+
 def forward_pipelined(lanes, layers, states_per_mb, xs, keep: list, outs_per_mb=None, **kw):
     """Inter-batch pipeline: micro-batch m on lanes[m]; layer-major issue order."""
     cur = list(xs)
-    for li, L in enumerate(layers):
-        for m, lane in enumerate(lanes):
-            cur[m] = run_layer(lane, L, states_per_mb[m][li], cur[m], keep,
-                               out=outs_per_mb[m][li] if outs_per_mb is not None else None, **kw)
+    share_cache(lanes)
+    try:
+        for li, L in enumerate(layers):
+            for m, lane in enumerate(lanes):
+                cur[m] = run_layer(lane, L, states_per_mb[m][li], cur[m], keep,
+                                   out=outs_per_mb[m][li] if outs_per_mb is not None else None, **kw)
+    finally:
+        share_cache(lanes, False)           # chunk sizes are read when a call is issued: the lanes are back to the default
     return cur
 
 

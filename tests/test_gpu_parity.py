@@ -290,6 +290,24 @@ def test_relu_chunk_invariance(mpc, lane, n_chunks):
     assert_shares_equal(host(mpc, lane, y), oracle.relu(xs, mat).y, "relu chunks")
 
 
+def test_relu_lane_chunk_size_invariance(mpc, lane):
+    """The lane's automatic chunk size (what a runner shrinks when several lanes convert at once) changes no word."""
+    print("relu lane chunk size", flush=True)
+    rng = np.random.default_rng(322)
+    n = 50000
+    xs = (synth.rand_words(rng, n), synth.rand_words(rng, n))
+    mat = synth.deal_relu_material(rng, n)
+    want = oracle.relu(xs, mat).y
+    x, m = dev(mpc, xs), mpc.material_to_device(mat)
+    for elems in (4096, 1024, 0):
+        lane.set_relu_chunk(elems, elems)
+        assert_shares_equal(host(mpc, lane, lane.relu(x, m)), want, f"relu, {elems}-element chunks")
+        packed = lane.pack_material(m)
+        assert_shares_equal(host(mpc, lane, lane.relu(x, packed, packed=True)), want, f"packed relu, {elems}-element chunks")
+    with pytest.raises(mpc.MpcError):
+        lane.set_relu_chunk(100)
+
+
 @pytest.mark.parametrize("shape", [(1, 2, 2, 1), (2, 6, 4, 3), (3, 8, 8, 16)])
 def test_maxpool(mpc, lane, shape):
     print(f"maxpool {shape}", flush=True)
