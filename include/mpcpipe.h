@@ -77,11 +77,15 @@ enum {
  * priority).  frac_bits in [0, 62] is the fixed-point scale used by
  * MPC_TRUNCATE.  Host-side allocation only. */
 int mpc_ctx_create(mpc_ctx** out, int device, int frac_bits);
-/* The same lane with one in-order stream for both parties and the wire from the start (what
- * mpc_ctx_set_streams(s0, s0, s0) turns a lane into, without creating and destroying the two other streams).
- * The runtime spreads streams over a small number of hardware queues (four by default) as they are
- * created; lanes that are meant to overlap (Sec. 4.3: one lane per micro-batch; Alg. 3: chunks of a layer)
- * should each hold exactly one stream so that they land on different hardware queues. */
+/* The same lane with one in-order stream for both parties and the wire (what mpc_ctx_set_streams(s0, s0, s0)
+ * turns a lane into).  The stream comes from a fixed set of four per device that the library creates once and
+ * keeps until the process ends; a lane takes the least used of them and gives it back when it is destroyed.  The
+ * runtime multiplexes streams onto a small number of hardware queues (four by default), and lanes that are meant
+ * to overlap (Sec. 4.3: one lane per micro-batch; Alg. 3: chunks of a layer) were measured to lose half of their
+ * overlap once the process had used more streams than that: with the fixed set the overlap does not depend on
+ * what ran before.  A fifth concurrent single-queue lane shares a stream with another one: the two are then
+ * ordered with each other (never a wrong result), and a graph captured on one of them would record what the
+ * other issues during the capture, so lanes that share a stream must not issue work while one of them captures. */
 int mpc_ctx_create_single_queue(mpc_ctx** out, int device, int frac_bits);
 int mpc_ctx_destroy(mpc_ctx* ctx);
 

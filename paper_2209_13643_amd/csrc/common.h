@@ -22,6 +22,8 @@ struct mpc_ctx {
     int frac_bits;
     hipStream_t s[3];        // 0, 1: party streams; 2: wire
     bool own_stream[3];
+    bool pooled_stream;      // single-queue lane: `pooled` came from the device's fixed set of lane streams
+    hipStream_t pooled;
     hipEvent_t ev[kEventPool];
     int ev_next;
     u8* ws;                  // caller-owned workspace

@@ -1,7 +1,56 @@
 // Context (execution lane), opening and truncation entry points.
 #include "common.h"
 
+#include <mutex>
 #include <new>
+
+namespace {
+
+// Streams of the single-queue lanes.  The runtime multiplexes streams onto a small number of hardware queues (four
+// by default), and how well lanes overlap was found to depend on how many distinct streams the process has used
+// before: four lanes made after one other lane had run lost half of their overlap.  Single-queue lanes therefore
+// draw their stream from a fixed set of four per device, made once and kept until the process ends; a lane takes the
+// least used one, a fifth concurrent lane shares a stream with another (the two are then ordered with each other,
+// as two streams on one hardware queue would be).
+constexpr int kLaneStreams = 4, kPoolDevices = 16;
+struct LaneStreamPool {
+    std::mutex mu;
+    bool made[kPoolDevices] = {};
+    hipStream_t s[kPoolDevices][kLaneStreams] = {};
+    int users[kPoolDevices][kLaneStreams] = {};
+} g_lane_streams;
+
+hipError_t lane_stream_acquire(int device, hipStream_t* out)
+{
+    if (device < 0 || device >= kPoolDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_lane_streams.mu);
+    if (!g_lane_streams.made[device]) {
+        for (int i = 0; i < kLaneStreams; ++i) {
+            const hipError_t e = hipStreamCreateWithFlags(&g_lane_streams.s[device][i], hipStreamNonBlocking);
+            if (e != hipSuccess) {
+                for (int j = 0; j < i; ++j) { (void)hipStreamDestroy(g_lane_streams.s[device][j]); g_lane_streams.s[device][j] = nullptr; }
+                return e;
+            }
+        }
+        g_lane_streams.made[device] = true;
+    }
+    int best = 0;
+    for (int i = 1; i < kLaneStreams; ++i)
+        if (g_lane_streams.users[device][i] < g_lane_streams.users[device][best]) best = i;
+    ++g_lane_streams.users[device][best];
+    *out = g_lane_streams.s[device][best];
+    return hipSuccess;
+}
+
+void lane_stream_release(int device, hipStream_t st)
+{
+    if (device < 0 || device >= kPoolDevices) return;
+    std::lock_guard<std::mutex> lock(g_lane_streams.mu);
+    for (int i = 0; i < kLaneStreams; ++i)
+        if (g_lane_streams.s[device][i] == st && g_lane_streams.users[device][i] > 0) { --g_lane_streams.users[device][i]; return; }
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -16,11 +65,17 @@ static int ctx_create(mpc_ctx** out, int device, int frac_bits, int n_streams)
     for (int i = 0; i < 3; ++i) { c->s[i] = nullptr; c->own_stream[i] = false; }
     for (int i = 0; i < kEventPool; ++i) c->ev[i] = nullptr;
     hipError_t e = hipSetDevice(device);
-    for (int i = 0; i < n_streams && e == hipSuccess; ++i) {
-        e = hipStreamCreateWithFlags(&c->s[i], hipStreamNonBlocking);
-        c->own_stream[i] = (e == hipSuccess);
+    c->pooled_stream = false;
+    if (n_streams == 1) {
+        // one in-order queue for everything, drawn from the device's fixed set
+        if (e == hipSuccess) e = lane_stream_acquire(device, &c->s[0]);
+        if (e == hipSuccess) { c->pooled_stream = true; c->pooled = c->s[0]; c->s[1] = c->s[2] = c->s[0]; }
+    } else {
+        for (int i = 0; i < 3 && e == hipSuccess; ++i) {
+            e = hipStreamCreateWithFlags(&c->s[i], hipStreamNonBlocking);
+            c->own_stream[i] = (e == hipSuccess);
+        }
     }
-    for (int i = n_streams; i < 3 && e == hipSuccess; ++i) c->s[i] = c->s[0];      // one in-order queue for everything
     for (int i = 0; i < kEventPool && e == hipSuccess; ++i)
         e = hipEventCreateWithFlags(&c->ev[i], hipEventDisableTiming);
     if (e != hipSuccess) {
@@ -46,6 +101,7 @@ int mpc_ctx_destroy(mpc_ctx* c)
     (void)mpc_ctx_profile_reset(c);
     for (int i = 0; i < 3; ++i)
         if (c->own_stream[i] && c->s[i]) (void)hipStreamDestroy(c->s[i]);
+    if (c->pooled_stream) lane_stream_release(c->device, c->pooled);
     delete c;
     return MPC_OK;
 }
