@@ -552,11 +552,20 @@ int relu3_chunk(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
 // Chunks of about 2^19 elements: the exchanged words and the carried state of a chunk (about 0.35 GB
 // for the three parties) then stay close to the last-level cache from stage to stage, and only the
 // offline material streams from DRAM.  Chunk boundaries are multiples of four, so wide accesses stay possible.
+// A lane whose conversion chunk has been set (mpc_ctx_set_relu_chunk: lanes that convert at the same time share the
+// cache) takes half of that, a three-party element carrying about twice the exchanged words of a two-party one; a
+// smaller chunk never needs more workspace than the default one the workspace queries assume.
 constexpr size_t kChunk3 = (size_t)1 << 19;
-inline int relu3_chunks(size_t n) { return n <= kChunk3 + kChunk3 / 2 ? 1 : (int)((n + kChunk3 - 1) / kChunk3); }
-inline size_t relu3_chunk_cap(size_t n)          // largest chunk of relu3_run's split
+inline size_t relu3_chunk_of(const mpc_ctx* c)
 {
-    const int k = relu3_chunks(n);
+    if (!c || !c->relu_chunk[0]) return kChunk3;
+    const size_t half = c->relu_chunk[0] / 2;
+    return half < 4096 ? 4096 : half > kChunk3 ? kChunk3 : half;
+}
+inline int relu3_chunks(size_t n, size_t chunk = kChunk3) { return n <= chunk + chunk / 2 ? 1 : (int)((n + chunk - 1) / chunk); }
+inline size_t relu3_chunk_cap(size_t n, size_t chunk = kChunk3)          // largest chunk of relu3_run's split
+{
+    const int k = relu3_chunks(n, chunk);
     return k == 1 ? n : ((n + k - 1) / k + 3) & ~(size_t)3;
 }
 
@@ -564,9 +573,9 @@ inline size_t relu3_chunk_cap(size_t n)          // largest chunk of relu3_run's
 int relu3_run(mpc_ctx* c, hipStream_t st, const Relu3Args& q)
 {
     const size_t n = q.n;
-    const int k = relu3_chunks(n);
+    const int k = relu3_chunks(n, relu3_chunk_of(c));
     if (k == 1) return relu3_chunk(c, st, q);
-    const size_t cap = relu3_chunk_cap(n);
+    const size_t cap = relu3_chunk_cap(n, relu3_chunk_of(c));
     for (size_t lo = 0; lo < n; lo += cap) {
         Relu3Args ch = q;
         ch.n = n - lo < cap ? n - lo : cap;
@@ -872,7 +881,7 @@ int mpc_relu3(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* m, mpc_share3
     for (int i = 0; i < 3; ++i) if (!x.p[i] || !y.p[i]) return MPC_EINVAL;
     Relu3Args q{};
     bool ok = false;
-    relu3_ws(c->ws, c->ws_bytes, relu3_chunk_cap(n), &q, &ok);
+    relu3_ws(c->ws, c->ws_bytes, relu3_chunk_cap(n, relu3_chunk_of(c)), &q, &ok);
     if (!ok) return MPC_ENOMEM;
     fill3(q, x.p, m, y.p, s_bit, s_arith, n);
     hipStream_t st = c->s[0];
@@ -971,8 +980,8 @@ static int maxpool3_entry(mpc_ctx* c, mpc_cshare3 x, const mpc_relu3_material* m
         relu3_msb_ws(rest, room, 2 * n_out, g1, &q1, &ok1);
         relu3_msb_ws(rest, room, n_out, g2, &q2, &ok2);                        // the second conversion reuses the scratch
     } else {
-        relu3_ws(rest, room, relu3_chunk_cap(2 * n_out), &q1, &ok1);
-        relu3_ws(rest, room, relu3_chunk_cap(n_out), &q2, &ok2);
+        relu3_ws(rest, room, relu3_chunk_cap(2 * n_out, relu3_chunk_of(c)), &q1, &ok1);
+        relu3_ws(rest, room, relu3_chunk_cap(n_out, relu3_chunk_of(c)), &q2, &ok2);
     }
     if (!ok1 || !ok2) return MPC_ENOMEM;
     fill3(q1, pq.d1, mat1, r1, nullptr, s1, 2 * n_out);

@@ -424,9 +424,13 @@ def forward3(lane: mpc.Lane, layers, states, x, keep: list):
 def forward_pipelined3(lanes, layers, states_per_mb, xs, keep: list):
     """Inter-batch pipeline with three parties: micro-batch m on lanes[m], layer-major issue order."""
     cur = list(xs)
-    for li, L in enumerate(layers):
-        for m, lane in enumerate(lanes):
-            cur[m] = run_layer3(lane, L, states_per_mb[m][li], cur[m], keep)
+    share_cache(lanes)
+    try:
+        for li, L in enumerate(layers):
+            for m, lane in enumerate(lanes):
+                cur[m] = run_layer3(lane, L, states_per_mb[m][li], cur[m], keep)
+    finally:
+        share_cache(lanes, False)
     return cur
 
 
