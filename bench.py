@@ -767,7 +767,7 @@ def main():
         "config": {"workload": "configs[4] vgg16-cifar inter-batch pipeline: 32x32x3 input, 13 conv3x3 layers 64..512 channels with "
                                "2x2 max-pooling, FC 512-512-10, batch 128 = 4 micro-batches of 32 on four lanes; per layer Beaver "
                                "conv / matmul + truncation, whole-word secure ReLU, max-pool by two conversions",
-                   "parties": 2, "frac_bits": 16, "lanes": N_MB, "lane": "single in-order queue each", "relu_chunks": "auto (about 2^20 elements each)",
+                   "parties": 2, "frac_bits": 16, "lanes": N_MB, "lane": "single in-order queue each", "relu_chunks": "auto: 2^20 elements on one lane, 2^20 / lanes = 2^18 on the four concurrent lanes (their share of the last-level cache)",
                    "mode": legs["pipeline"]["step_mode"]["relu"] + "; exchange: " + legs["pipeline"]["step_mode"]["exchange"] + "; planes: " + legs["pipeline"]["step_mode"]["planes"],
                    "secure_macs_per_step": legs["macs"], "relu_elements_per_step": legs["relu_elements"],
                    "maxpool_comparisons_per_step": legs["pool_comparisons"], "images_per_s": N_MB * MICRO_BATCH / ms_step * 1e3,
