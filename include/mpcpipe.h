@@ -84,8 +84,8 @@ int mpc_ctx_create(mpc_ctx** out, int device, int frac_bits);
  * to overlap (Sec. 4.3: one lane per micro-batch; Alg. 3: chunks of a layer) were measured to lose half of their
  * overlap once the process had used more streams than that: with the fixed set the overlap does not depend on
  * what ran before.  A fifth concurrent single-queue lane shares a stream with another one: the two are then
- * ordered with each other (never a wrong result), and a graph captured on one of them would record what the
- * other issues during the capture, so lanes that share a stream must not issue work while one of them captures. */
+ * ordered with each other (never a wrong result); mpc_ctx_capture_begin refuses such a lane (MPC_EINVAL), since a
+ * graph recorded on a shared stream would also record what the other lane issues meanwhile. */
 int mpc_ctx_create_single_queue(mpc_ctx** out, int device, int frac_bits);
 int mpc_ctx_destroy(mpc_ctx* ctx);
 

@@ -42,6 +42,15 @@ hipError_t lane_stream_acquire(int device, hipStream_t* out)
     return hipSuccess;
 }
 
+int lane_stream_users(int device, hipStream_t st)
+{
+    if (device < 0 || device >= kPoolDevices) return 0;
+    std::lock_guard<std::mutex> lock(g_lane_streams.mu);
+    for (int i = 0; i < kLaneStreams; ++i)
+        if (g_lane_streams.s[device][i] == st) return g_lane_streams.users[device][i];
+    return 0;
+}
+
 void lane_stream_release(int device, hipStream_t st)
 {
     if (device < 0 || device >= kPoolDevices) return;
@@ -162,6 +171,8 @@ int mpc_ctx_capture_begin(mpc_ctx* c)
 {
     if (!c || c->capturing || c->profiling) return MPC_EINVAL;
     if (!(c->s[0] == c->s[1] && c->s[1] == c->s[2])) return MPC_EINVAL;      // events between streams are not recorded
+    // a stream shared with another lane (more than four single-queue lanes alive) would record that lane's calls too
+    if (c->pooled_stream && c->s[0] == c->pooled && lane_stream_users(c->device, c->pooled) > 1) return MPC_EINVAL;
     MPC_HIP(c, hipStreamBeginCapture(c->s[0], hipStreamCaptureModeRelaxed));
     c->capturing = true;
     return MPC_OK;

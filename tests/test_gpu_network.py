@@ -477,3 +477,29 @@ def test_layer_as_row_chunks_on_lanes(mods, kind, n_chunks, n_lanes, lane_kind):
         pipeline.ChunkedLinear(lanes, L, st, n_chunks=0)
     for ln in lanes + [consumer]:
         ln.sync(); ln.close()
+
+
+def test_fifth_single_queue_lane_shares_a_stream_and_cannot_record(mods):
+    """Single-queue lanes draw their stream from a fixed set of four: a fifth one shares a stream (its results are
+    still right), and recording a graph on a shared stream is refused."""
+    mpc, _ = mods
+    print("fifth single-queue lane", flush=True)
+    lanes = [mpc.Lane(0, single_queue=True) for _ in range(5)]
+    streams = [ln.stream(0) for ln in lanes]
+    assert len(set(streams[:4])) == 4 and streams[4] in streams[:4]
+    rng = np.random.default_rng(9)
+    s = (synth.rand_words(rng, 1000), synth.rand_words(rng, 1000))
+    outs = [ln.open((mpc.to_device(s[0]), mpc.to_device(s[1]))) for ln in lanes]
+    for ln, o in zip(lanes, outs):
+        ln.sync()
+        assert np.array_equal(mpc.to_host(o), s[0] + s[1])
+    shared = lanes[streams.index(streams[4])]
+    for ln in (lanes[4], shared):
+        with pytest.raises(mpc.MpcError):
+            with ln.capture():
+                pass
+    lanes[4].close()
+    with shared.capture():          # alone on its stream again
+        pass
+    for ln in lanes[:4]:
+        ln.close()
