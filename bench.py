@@ -52,13 +52,16 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_OPS_PER_SECURE_MAC = 288          # 2 parties x 2 ring GEMMs x 36 digit products x 2 ops
 RELU_BYTES_PER_ELEMENT = 86 * 8 + 2 + 216 * 8 + 137 * 8   # compulsory + openings + carried state, both parties
 # the same chain with the exchange by remote store (no copy kernels; a level stage recomputes its own masked words from
-# the carried state and stores them to the peer only), per party in words: A2B copy 2, first 10, level-0 stage 18,
-# levels 1..4 22 each, level 5 18, sign 7, B2A 8, select 8 = 159 W, plus 7 bytes (sign bit, random bit, masked bit)
-RELU_PUT_BYTES_PER_ELEMENT = 2 * (159 * 8 + 7)
+# the carried state and stores them to the peer only; so do the first and the B2A stage, whose own words the next stage
+# re-forms from x, r, P and from x, ra and the opened bit), per party in words: A2B copy 2, first 8, level-0 stage 18,
+# levels 1..4 22 each, level 5 18, sign 7, B2A 6, select 8 = 155 W, plus 9 bytes (sign bit, random bit, masked bits)
+RELU_PUT_BYTES_PER_ELEMENT = 2 * (155 * 8 + 9)
 RELU_COMPULSORY_BYTES = 86 * 8 + 2                        # x, y, r, 12 AND triples, B2A pair, select triple: DRAM-compulsory
 # the sign-only packed chain (mpc_relu_msb), same three classes: 31.72 W + 2 B, 71.25 W + 8 B, 41.56 W + 6 B
 RELU_MSB_BYTES_PER_ELEMENT = (31.71875 + 71.25 + 41.5625) * 8 + 16
-RELU_MSB_PUT_BYTES_PER_ELEMENT = RELU_MSB_BYTES_PER_ELEMENT - 71.25 * 8 / 4      # one of the four traversals of every opened word less
+# remote store: one of the four traversals of every opened word less, and the first and the B2A stage store their
+# masked words (2 W each per party) to the peer only (the select stage reads two bytes more instead)
+RELU_MSB_PUT_BYTES_PER_ELEMENT = RELU_MSB_BYTES_PER_ELEMENT - 71.25 * 8 / 4 - 2 * 4 * 8 + 2 * 2
 RELU_MSB_COMPULSORY_BYTES = 31.71875 * 8 + 2
 RELU3_BYTES_PER_ELEMENT = 966 * 8 + 33      # three parties: 141 W + 3 B, 606 W + 21 B, 219 W + 9 B (same three classes)
 RELU3_MSB_BYTES_PER_ELEMENT = 2961          # three parties, sign-only chain: 59.6 W + 3 B, 226.0 W + 21 B, 80.3 W + 9 B

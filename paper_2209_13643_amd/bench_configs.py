@@ -20,8 +20,8 @@ INT8_PEAK = 5.0e15
 HBM_PEAK = 8.0e12
 RELU_BYTES = 3514
 RELU_MSB_BYTES = 1172.25      # the sign-only packed chain
-RELU_PUT_BYTES = 2 * (159 * 8 + 7)            # whole words, exchange by remote store (bench.py derives it)
-RELU_MSB_PUT_BYTES = RELU_MSB_BYTES - 71.25 * 8 / 4
+RELU_PUT_BYTES = 2 * (155 * 8 + 9)            # whole words, exchange by remote store (bench.py derives it)
+RELU_MSB_PUT_BYTES = RELU_MSB_BYTES - 71.25 * 8 / 4 - 2 * 4 * 8 + 2 * 2
 
 
 def layer_macs(L):

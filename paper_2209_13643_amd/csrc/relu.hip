@@ -140,8 +140,11 @@ __device__ __forceinline__ void b_first(const ReluParty& p, size_t lo, size_t hi
             P.v[k] = U ^ Vv;
             top[k] = (u8)(P.v[k] >> 63);
         }
-        d.st(p.send, i); g.st(p.send + n, i); P.st(p.P, i);
+        // with the exchange by remote store the next stage re-forms this party's own masked words from x, r and P
+        // (U or V is the own x ^ r, the other one P ^ that), so they go to the peer only
         if constexpr (PUT) { d.st(p.put, i); g.st(p.put + n, i); }
+        else               { d.st(p.send, i); g.st(p.send + n, i); }
+        P.st(p.P, i);
         st_bytes<V>(p.p63, i, top);
     }
 }
@@ -180,10 +183,22 @@ __device__ __forceinline__ void b_level(const ReluParty& p, size_t lo, size_t hi
     FOR_ELEMS(V) {
         Pack<V> G, P;
         if constexpr (LEVEL == 0) {
-            const Pack<V> sd = Pack<V>::ld(p.send, i), sg = Pack<V>::ld(p.send + n, i);
             const Pack<V> rd = Pack<V>::ld(p.recv, i), rg = Pack<V>::ld(p.recv + n, i);
             const Pack<V> a = Pack<V>::ld(p.ta, i), b = Pack<V>::ld(p.tb, i), c = Pack<V>::ld(p.tc, i);
             P = Pack<V>::ld(p.P, i);
+            Pack<V> sd, sg;
+            if constexpr (PUT) {
+                // own masked words of G = U & V, re-formed: the own word of the pair (U, V) is x ^ r, the other P ^ it
+                const Pack<V> x = Pack<V>::ld(p.x, i), r = Pack<V>::ld(p.r, i);
+#pragma unroll
+                for (int k = 0; k < V; ++k) {
+                    const u64 own = x.v[k] ^ r.v[k], other = P.v[k] ^ own;
+                    sd.v[k] = (PARTY == 0 ? own : other) ^ a.v[k];
+                    sg.v[k] = (PARTY == 0 ? other : own) ^ b.v[k];
+                }
+            } else {
+                sd = Pack<V>::ld(p.send, i); sg = Pack<V>::ld(p.send + n, i);
+            }
 #pragma unroll
             for (int k = 0; k < V; ++k)
                 G.v[k] = and_finish<PARTY>(sd.v[k] ^ rd.v[k], sg.v[k] ^ rg.v[k], a.v[k], b.v[k], c.v[k]);
@@ -278,21 +293,37 @@ __device__ __forceinline__ void b_b2a(const ReluParty& p, size_t lo, size_t hi)
             e.v[k] = x.v[k] - ma.v[k];
             f.v[k] = m - mb.v[k];
         }
-        e.st(p.send, i); f.st(p.send + n, i);
+        // with the exchange by remote store the select stage re-forms this party's own masked words: peer only
         if constexpr (PUT) { e.st(p.put, i); f.st(p.put + n, i); }
+        else               { e.st(p.send, i); f.st(p.send + n, i); }
         if (p.s_arith) sa.st(p.s_arith, i);
     }
 }
 
 // ---- K_select -----------------------------------------------------------------
-template <int PARTY, int V>
+template <int PARTY, int V, bool PUT>
 __device__ __forceinline__ void b_select(const ReluParty& p, size_t lo, size_t hi)
 {
     const size_t n = p.n;
     FOR_ELEMS(V) {
-        const Pack<V> se = Pack<V>::ld(p.send, i), sf = Pack<V>::ld(p.send + n, i);
         const Pack<V> re = Pack<V>::ld(p.recv, i), rf = Pack<V>::ld(p.recv + n, i);
         const Pack<V> ma = Pack<V>::ld(p.ma, i), mb = Pack<V>::ld(p.mb, i), mc = Pack<V>::ld(p.mc, i);
+        Pack<V> se, sf;
+        if constexpr (PUT) {
+            // own masked words of the select product, re-formed as the B2A stage formed them
+            const Pack<V> x = Pack<V>::ld(p.x, i), ra = Pack<V>::ld(p.ra, i);
+            u8 own[V], got[V];
+            ld_bytes<V>(p.sendb, i, own); ld_bytes<V>(p.recvb, i, got);
+#pragma unroll
+            for (int k = 0; k < V; ++k) {
+                const u64 v = (u64)(own[k] ^ got[k]);
+                const u64 sa = ra.v[k] - 2 * v * ra.v[k] + (PARTY == 0 ? v : 0);
+                se.v[k] = x.v[k] - ma.v[k];
+                sf.v[k] = ((PARTY == 0 ? (u64)1 : (u64)0) - sa) - mb.v[k];
+            }
+        } else {
+            se = Pack<V>::ld(p.send, i); sf = Pack<V>::ld(p.send + n, i);
+        }
         Pack<V> y;
 #pragma unroll
         for (int k = 0; k < V; ++k) {
@@ -355,10 +386,22 @@ __device__ __forceinline__ void b_plevel(const ReluParty& p, const MsbGeom& g, s
         Pack<2 * W> G, P;
         if constexpr (LEVEL == 0) {
             const size_t n = p.n, e = 2 * j;
-            const Pack<2 * W> sd = ld_upto<2 * W>(p.send, e, n), sg = ld_upto<2 * W>(p.send + n, e, n);
             const Pack<2 * W> rd = ld_upto<2 * W>(p.recv, e, n), rg = ld_upto<2 * W>(p.recv + n, e, n);
             const Pack<2 * W> a = ld_upto<2 * W>(p.ta, e, n), b = ld_upto<2 * W>(p.tb, e, n), c = ld_upto<2 * W>(p.tc, e, n);
             P = ld_upto<2 * W>(p.P, e, n);
+            Pack<2 * W> sd, sg;
+            if constexpr (PUT) {
+                // own masked words of G = U & V, re-formed as in the whole-word level-0 stage
+                const Pack<2 * W> x = ld_upto<2 * W>(p.x, e, n), r = ld_upto<2 * W>(p.r, e, n);
+#pragma unroll
+                for (int k = 0; k < 2 * W; ++k) {
+                    const u64 own = x.v[k] ^ r.v[k], other = P.v[k] ^ own;
+                    sd.v[k] = (PARTY == 0 ? own : other) ^ a.v[k];
+                    sg.v[k] = (PARTY == 0 ? other : own) ^ b.v[k];
+                }
+            } else {
+                sd = ld_upto<2 * W>(p.send, e, n); sg = ld_upto<2 * W>(p.send + n, e, n);
+            }
 #pragma unroll
             for (int k = 0; k < 2 * W; ++k)
                 G.v[k] = and_finish<PARTY>(sd.v[k] ^ rd.v[k], sg.v[k] ^ rg.v[k], a.v[k], b.v[k], c.v[k]);
@@ -560,7 +603,7 @@ __device__ __forceinline__ void stage_body(const ReluParty& p, size_t lo, size_t
     else if constexpr (STAGE >= 1 && STAGE <= 6) b_level<PARTY, STAGE - 1, V, TOPO, PUT>(p, lo, hi);
     else if constexpr (STAGE == 7) b_sign<PARTY, V, TOPO, PUT>(p, lo, hi);
     else if constexpr (STAGE == 8) b_b2a<PARTY, V, PUT>(p, lo, hi);
-    else b_select<PARTY, V>(p, lo, hi);
+    else b_select<PARTY, V, PUT>(p, lo, hi);
 }
 
 template <int STAGE, int V, int TOPO, bool PUT>
@@ -575,9 +618,10 @@ template <int STAGE, int V>
 void launch_stage_t(hipStream_t st, const ReluParty& p0, const ReluParty& p1, int only, size_t lo, size_t hi, int topo)
 {
     const dim3 grid(grid_for((hi - lo + V - 1) / V), only >= 0 ? 1 : 2), block(kThreads);
-    // only the carry-network stages depend on the topology; the last stage sends nothing
+    // only the carry-network stages depend on the topology; the last stage sends nothing, but with the exchange
+    // by remote store it re-forms its own masked words instead of reading them back
     constexpr int T1 = (STAGE >= 1 && STAGE <= 7) ? 1 : 0;
-    constexpr bool P1 = STAGE <= 8;
+    constexpr bool P1 = true;
     const bool put = p0.put != nullptr && P1;
     if (topo && T1) {
         if (put) hipLaunchKernelGGL((k_relu_stage<STAGE, V, T1, P1>), grid, block, 0, st, p0, p1, only, lo, hi);
@@ -615,7 +659,7 @@ __device__ __forceinline__ void stage_body_msb(const ReluParty& p, const MsbGeom
     else if constexpr (STAGE >= 2 && STAGE <= 6) b_plevel<PARTY, STAGE - 1, 2, PUT>(p, g, lo, hi);
     else if constexpr (STAGE == 7) b_psign<PARTY, V, PUT>(p, g, lo, hi);
     else if constexpr (STAGE == 8) b_b2a<PARTY, V, PUT>(p, lo, hi);
-    else b_select<PARTY, V>(p, lo, hi);
+    else b_select<PARTY, V, PUT>(p, lo, hi);
 }
 
 template <int STAGE, int V, bool PUT>
@@ -640,7 +684,7 @@ void launch_msb_stage_t(hipStream_t st, const ReluParty& p0, const ReluParty& p1
         threads = (hi - lo + V - 1) / V;
     }
     const dim3 grid(grid_for(threads), only >= 0 ? 1 : 2), block(kThreads);
-    constexpr bool P1 = STAGE <= 8;
+    constexpr bool P1 = true;
     if (p0.put != nullptr && P1) hipLaunchKernelGGL((k_relu_msb_stage<STAGE, V, P1>), grid, block, 0, st, p0, p1, g, only, lo, hi);
     else                         hipLaunchKernelGGL((k_relu_msb_stage<STAGE, V, false>), grid, block, 0, st, p0, p1, g, only, lo, hi);
 }
