@@ -115,6 +115,26 @@ def test_ring_matmul_longest_exact_pass_worst_case(mpc):
     lane.close()
 
 
+@pytest.mark.parametrize("shape", [(130, 70, 650), (4100, 40, 680), (200, 33, 1100)])
+def test_ring_matmul_ragged_column_panels(mpc, lane, shape):
+    """Outputs whose column tiles do not fill the last panel of the tile order (6 tiles of 128 columns = panels of 4 + 2;
+    11 tiles of 64 columns on the 128 x 64 tile = 4 + 4 + 3; 9 tiles of 128 = 4 + 4 + 1), with ragged last tiles."""
+    M, K, N = shape
+    print(f"ring_matmul, ragged column panels {shape}", flush=True)
+    rng = np.random.default_rng(M + 3 * K + N)
+    L, R = synth.rand_words(rng, (M, K)), synth.rand_words(rng, (K, N))
+    Z = lane.ring_matmul(mpc.to_device(L), mpc.to_device(R))
+    lane.sync()
+    assert np.array_equal(mpc.to_host(Z), oracle.ring_matmul(L, R))
+
+
+def test_beaver_matmul_batched_ragged_column_panels(mpc, lane):
+    print("beaver_matmul batched, ragged column panels", flush=True)
+    d = deal_matmul(np.random.default_rng(83), 70, 40, 650, batch=3)
+    z = lane.beaver_matmul(dev(mpc, d["x"]), dev(mpc, d["y"]), dev(mpc, d["a"]), dev(mpc, d["b"]), dev(mpc, d["c"]))
+    assert_shares_equal(host(mpc, lane, z), oracle_matmul(d), "batched, ragged panels")
+
+
 def test_ring_matmul_batched(mpc, lane):
     print("ring_matmul batched", flush=True)
     rng = np.random.default_rng(6)
