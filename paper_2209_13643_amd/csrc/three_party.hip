@@ -124,16 +124,30 @@ __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
     auto out = [n](u64* base, int r) { return reinterpret_cast<T*>(base + (size_t)r * n); };
     auto tr = [tn](const u64* base, int r) { return reinterpret_cast<const T*>(base + (size_t)r * tn); };
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < units; i += stride) {
-        // row k of this round's masked words: into the own send buffer and, by remote store, to both peers
+        // row k of this round's masked words: into the own send buffer and, by remote store, to both peers.
+        // From stage 2 on a party that stores to its peers keeps no copy for itself: the stage that opens the
+        // words forms the party's own ones again from the state it carries and the triples it reads anyway
+        // (the level stages then also carry P).
+        constexpr bool kReform = PUT && STAGE >= 3;          // the round before left no own copy
         auto send = [&](int k, T v) {
-            out(p.send, k)[i] = v;
+            if constexpr (!(PUT && STAGE >= 2)) out(p.send, k)[i] = v;
             if constexpr (PUT) { out(p.put[0], k)[i] = v; out(p.put[1], k)[i] = v; }
         };
         // masked words of the previous round, opened
         T o[4] = {};
         constexpr int kOpen = (STAGE == 0 || STAGE >= 9) ? 0 : (STAGE >= 3 && STAGE <= 7) ? 4 : 2;
+        if constexpr (kReform && kOpen > 0) {
+            // stages 3..8 finish level L = STAGE - 3, masked by the stage before from its (P, G) with shift 2^L
+            constexpr int L = STAGE - 3, tg = 2 + 2 * L, tp = 3 + 2 * L;
+            const T Pp = in(p.P, 0)[i], Gp = in(p.G, 0)[i];
+            o[0] = Pp ^ tr(p.ta, tg)[i];  o[1] = (Gp << (1 << L)) ^ tr(p.tb, tg)[i];
+            if constexpr (kOpen == 4) { o[2] = Pp ^ tr(p.ta, tp)[i];  o[3] = (Pp << (1 << L)) ^ tr(p.tb, tp)[i]; }
 #pragma unroll
-        for (int k = 0; k < kOpen; ++k) o[k] = in(p.send, k)[i] ^ in(p.recv[0], k)[i] ^ in(p.recv[1], k)[i];
+            for (int k = 0; k < kOpen; ++k) o[k] ^= in(p.recv[0], k)[i] ^ in(p.recv[1], k)[i];
+        } else {
+#pragma unroll
+            for (int k = 0; k < kOpen; ++k) o[k] = in(p.send, k)[i] ^ in(p.recv[0], k)[i] ^ in(p.recv[1], k)[i];
+        }
 
         if constexpr (STAGE == 0) {
             const T own = in(p.x, 0)[i] ^ in(p.r0, 0)[i] ^ in(p.r1, 0)[i];
@@ -166,6 +180,7 @@ __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
             const T P = and_finish<T>(party, o[2], o[3], tr(p.ta, tp)[i], tr(p.tb, tp)[i], tr(p.tc, tp)[i]);
             const T G = in(p.G, 0)[i] ^ T1;
             out(p.G, 0)[i] = G;
+            if constexpr (PUT) out(p.P, 0)[i] = P;       // the next stage forms this party's masked words from (P, G)
             constexpr int d = 2 << L;                    // shift of level L + 1
             constexpr int ng = tg + 2, np = tp + 2;
             send(0, P ^ tr(p.ta, ng)[i]);  send(1, (G << d) ^ tr(p.tb, ng)[i]);
@@ -192,9 +207,21 @@ __global__ __launch_bounds__(kT) void k3_relu(Relu3Args q)
             send(1, m - in(p.mb, 0)[i]);
         } else {
             // additive opening of the select product's masked operands
-            const T e = in(p.send, 0)[i] + in(p.recv[0], 0)[i] + in(p.recv[1], 0)[i];
-            const T f = in(p.send, 1)[i] + in(p.recv[0], 1)[i] + in(p.recv[1], 1)[i];
             const T mb = in(p.mb, 0)[i], ma = in(p.ma, 0)[i];
+            T e_own, f_own;
+            if constexpr (PUT) {                         // formed again from x, ra and the opened sign byte
+                const T v = to_words(reinterpret_cast<const B*>(p.vsend)[i] ^ reinterpret_cast<const B*>(p.vrecv[0])[i] ^
+                                     reinterpret_cast<const B*>(p.vrecv[1])[i]);
+                const T ra = in(p.ra, 0)[i];
+                T sa = ra - 2 * v * ra;
+                if (party == 0) sa += v;
+                e_own = in(p.x, 0)[i] - ma;
+                f_own = ((party == 0 ? (u64)1 : (u64)0) - sa) - mb;
+            } else {
+                e_own = in(p.send, 0)[i]; f_own = in(p.send, 1)[i];
+            }
+            const T e = e_own + in(p.recv[0], 0)[i] + in(p.recv[1], 0)[i];
+            const T f = f_own + in(p.recv[0], 1)[i] + in(p.recv[1], 1)[i];
             T yv = in(p.mc, 0)[i] + e * mb + ma * f;
             if (party == 0) yv += e * f;
             out(p.y, 0)[i] = yv;
@@ -453,9 +480,9 @@ int exchange_bytes(mpc_ctx* c, hipStream_t st, const Relu3Args& q);
 template <int STAGE>
 int launch_stage(mpc_ctx* c, hipStream_t st, const Relu3Args& q, int vec, int rows)
 {
-    if (c->exchange_put && rows != 0) return launch_stage_t<STAGE, true>(c, st, put_args(q, STAGE), vec);
-    MPC_TRY((launch_stage_t<STAGE, false>(c, st, c->exchange_put ? put_args(q, STAGE) : q, vec)));
-    if (c->exchange_put || rows == 0) return MPC_OK;
+    if (c->exchange_put) return launch_stage_t<STAGE, true>(c, st, put_args(q, STAGE), vec);
+    MPC_TRY((launch_stage_t<STAGE, false>(c, st, q, vec)));
+    if (rows == 0) return MPC_OK;
     return rows > 0 ? exchange_words(c, st, q, rows) : exchange_bytes(c, st, q);
 }
 
