@@ -802,8 +802,8 @@ def main(argv):
               f"{r['relu_bytes_per_element']} B per element -> {100 * r['relu_hbm_frac']:.1f}% of 8 TB/s", flush=True)
         print(f"  the same ReLU on the sign's carry chain only: {r['msb_ms']:.3f} ms (min {r['msb_min_ms']:.3f}), {r['msb_elems_per_s'] / 1e9:.2f} G elems/s; "
               f"{r['msb_bytes_per_element']} B per element -> {100 * r['msb_hbm_frac']:.1f}% of 8 TB/s", flush=True)
-        for packed, pf, prep, ex in ((False, False, False, "copy"), (True, False, False, "copy"), (True, True, False, "copy"),
-                                     (True, True, True, "put")):
+        for packed, pf, prep, ex in ((False, False, False, "copy"), (False, False, True, "put"), (True, False, False, "copy"),
+                                     (True, True, False, "copy"), (True, True, True, "put")):
             p = bench_pipeline3(packed_relu=packed, pool_first=pf, prepared=prep, exchange=ex)
             print(f"  VGG16-CIFAR forward with three parties, batch 128 = 4 x 32 ({'sign-only packed' if packed else 'whole-word'} ReLU"
                   f"{', pooled layers as ReLU(maxpool(z))' if pf else ''}{', prepared planes' if prep else ''}"
